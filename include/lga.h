@@ -1,0 +1,167 @@
+/*
+ * lga.h - C ABI of the layered-gradient-accumulation layer-stack library (MI355X / gfx950).
+ *
+ * One GPU's share of a training step over n_mu micro-batches of a stack of identical pre-LN
+ * GPT decoder layers (paper section 5 "Model": attention module + two-layer feed-forward of
+ * width d_I; Table B.1 fixes the per-layer inventory at 12 d_m^2 + 13 d_m parameters, i.e.
+ * biases on all four linear maps and gain + bias on both layer norms).
+ *
+ * Conventions for every entry point
+ *  - Returns an lga_status code; nothing throws across this boundary.  A human-readable
+ *    message for the last failure on the calling thread is available from lga_last_error().
+ *  - All argument validation happens on the host before anything is launched.
+ *  - Pointers marked "dev" are device (HBM) addresses, "host" are host addresses.
+ *  - Work is enqueued on the HIP stream given in lga_config.stream (borrowed; NULL = the
+ *    default stream) and the call returns without synchronising; the caller synchronises.
+ *  - The caller owns x, y, dy, dx.  The library owns weights, Adam moments, gradient
+ *    buffer(s), the 16-bit parameter copies, the activation checkpoints and all scratch:
+ *    one arena, sized from the configuration and allocated once in lga_init_stack
+ *    (section 2.5: pre-allocated contiguous buffers, one fused tensor per layer).
+ *  - Pointers handed out by lga_grads / lga_params / lga_moments / lga_checkpoint are
+ *    borrowed: valid until the next call that overwrites that data or lga_destroy_stack.
+ *
+ * Canonical parameter layout of one layer (flat fp32 vector of length p_l; matrices are
+ * row-major [in, out] so that y = x W + b; W_qkv columns are [Q | K | V] and head h owns
+ * columns h*d_h .. (h+1)*d_h-1 inside each of the three):
+ *   ln1_g[d] ln1_b[d] W_qkv[d,3d] b_qkv[3d] W_o[d,d] b_o[d] ln2_g[d] ln2_b[d]
+ *   W_1[d,d_I] b_1[d_I] W_2[d_I,d] b_2[d]
+ * Gradients, moments and parameters are all exposed in this same layout.
+ *
+ * Activation tensors x, y, dy, dx are [n_micro, micro_batch, seq_len, d_model], contiguous,
+ * of the configured dtype (float, or bfloat16 stored as 16-bit).
+ */
+#ifndef LGA_H
+#define LGA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lga_stack lga_stack; /* opaque, library-owned */
+
+/* Activation / GEMM-input type.  Master weights, gradients and Adam moments are always fp32
+ * (section 2.2: bulk of the computation in 16 bits, weights stored and updated in fp32). */
+enum lga_dtype { LGA_FP32 = 0, LGA_BF16 = 1 };
+
+enum lga_status {
+    LGA_OK = 0,
+    LGA_ERR_ARG = -1,   /* NULL pointer, layer index out of range, bad enum value */
+    LGA_ERR_SHAPE = -2, /* configuration the kernels do not support (see lga_init_stack) */
+    LGA_ERR_OOM = -3,   /* device allocation failed */
+    LGA_ERR_STATE = -4, /* call sequence violated (backward before forward, ...) */
+    LGA_ERR_HIP = -5    /* HIP runtime error (no device, launch failure) */
+};
+
+/* Order in which (layer, micro-batch) pairs are visited. */
+enum lga_order { LGA_ORDER_LAYERED = 0, LGA_ORDER_MICROBATCH_MAJOR = 1 };
+
+typedef struct lga_config {
+    int32_t n_layers;     /* d_l  >= 1 */
+    int32_t d_model;      /* d_m */
+    int32_t n_heads;      /* d_a; d_h = d_model / n_heads */
+    int32_t d_ff;         /* d_I (4 * d_model in the paper's models) */
+    int32_t seq_len;      /* d_s */
+    int32_t micro_batch;  /* b_mu: sequences per micro-batch */
+    int32_t n_micro;      /* n_mu: micro-batches per step */
+    int32_t dtype;        /* enum lga_dtype */
+    int32_t group;        /* micro-batches handed to each kernel launch together (1..n_micro,
+                             must divide n_micro).  Only the layered order can use > 1: it
+                             contracts weight-gradient GEMMs over the concatenated tokens. */
+    int32_t retain_grads; /* 1: one fp32 gradient buffer per layer (needed by the micro-batch-major
+                             order and by unfused Adam when n_layers > 1); 0: a single layer-sized
+                             buffer, reused layer after layer (appendix C.3: gradient storage made
+                             negligible by updating a layer's weights at once) */
+    float ln_eps;         /* LayerNorm epsilon, inside the root (1e-5 in the benchmarks) */
+    void *stream;         /* hipStream_t, borrowed; NULL = default stream */
+} lga_config;
+
+/* Adam hyper-parameters (section 5 "Training": Adam assumed; Kingma-Ba form with bias
+ * correction, no weight decay, eps added to sqrt(v_hat)).  step is t >= 1. */
+typedef struct lga_adam {
+    float lr, beta1, beta2, eps;
+    int32_t step;
+} lga_adam;
+
+/* Create a stack.
+ *  cfg          host, copied.
+ *  host_params  host, n_layers * p_l floats, layer after layer in the canonical layout; copied.
+ *               NULL: weights are filled on the device by a counter-based generator
+ *               (matrices ~ N(0, 0.02^2), gains 1, biases 0), for throughput runs at sizes where a
+ *               host copy is impractical.
+ *  out          host, receives the handle.
+ * Adam moments start at zero.  The 16-bit parameter copy of every layer is produced here
+ * (section 2.5: parameters are converted to 16 bits before use) and refreshed by each Adam step.
+ * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in bf16 mode,
+ * d_h % 32 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  LGA_ERR_OOM if the arena does not fit. */
+int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **out);
+
+void lga_destroy_stack(lga_stack *stack);
+
+/* Layer-major forward (section 3): for each layer, every micro-batch group goes through it
+ * before the next layer starts; only layer-boundary activations (the checkpoints) are kept.
+ *  x  dev, in,  [n_micro, micro_batch, seq_len, d_model]
+ *  y  dev, out, same shape; may be NULL (the output stays readable through lga_checkpoint). */
+int lga_forward_layered(lga_stack *stack, const void *x, void *y);
+
+/* Layer-major backward (section 3; recompute inside the layer from its checkpoint, section 2.5).
+ * From the last layer down: every micro-batch group is recomputed and back-propagated through
+ * layer l, its weight gradients summed in fp32 into layer l's gradient buffer, and - if fused is
+ * not NULL - Adam is applied to layer l before layer l-1 starts (appendix C.3).
+ *  dy     dev, in,  gradient of the loss w.r.t. the stack output
+ *  dx     dev, out, gradient w.r.t. the stack input; may be NULL
+ *  fused  host, Adam hyper-parameters, or NULL to leave the gradients for lga_adam_step_layer.
+ * LGA_ERR_STATE if no forward pass precedes it, or if fused == NULL, retain_grads == 0 and
+ * n_layers > 1 (all but the last-computed gradient would be lost). */
+int lga_backward_layered(lga_stack *stack, const void *dy, void *dx, const lga_adam *fused);
+
+/* One Adam update of layer `layer` from its accumulated gradient; refreshes its 16-bit copy.
+ * LGA_ERR_STATE if that gradient is not (or no longer) available. */
+int lga_adam_step_layer(lga_stack *stack, int32_t layer, const lga_adam *adam);
+
+/* Borrow the accumulated fp32 gradient of a layer (canonical layout, *count = p_l).
+ * LGA_ERR_STATE if not available (never computed, or its buffer was reused by a later layer). */
+int lga_grads(lga_stack *stack, int32_t layer, const float **dev_ptr, size_t *count);
+
+/* Borrow the fp32 master parameters / Adam moments of a layer (canonical layout).
+ * The moment pointers are writable so that a caller can restore optimizer state. */
+int lga_params(lga_stack *stack, int32_t layer, const float **dev_master, size_t *count);
+int lga_moments(lga_stack *stack, int32_t layer, float **dev_m, float **dev_v, size_t *count);
+
+/* Borrow boundary activation `boundary` (0 = stack input ... n_layers = stack output) for all
+ * micro-batches: [n_micro, micro_batch, seq_len, d_model] of the configured dtype. */
+int lga_checkpoint(lga_stack *stack, int32_t boundary, const void **dev_ptr, size_t *bytes);
+
+/* The comparison order (section 2.5, standard gradient accumulation): each micro-batch goes
+ * through the whole stack forward and backward before the next; gradients accumulate in
+ * per-layer fp32 buffers with beta = 1; Adam (if adam != NULL) runs for all layers at the end.
+ * Same kernels as the layered calls.  Requires retain_grads == 1 and group == 1. */
+int lga_step_mbmajor(lga_stack *stack, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam);
+
+/* Host-only analytic model of one step (no device needed), for printing beside measured
+ * counters.  order is enum lga_order.
+ *  param_bytes  HBM bytes of parameter traffic: 16-bit weight reads by the forward, recompute and
+ *               input-gradient GEMM families per group, plus Adam's read of w, m, v and write of
+ *               w, m, v and the 16-bit copy.
+ *  grad_bytes   HBM bytes of fp32 gradient-buffer traffic: read-modify-write per group (write
+ *               only for a layer's first group) plus Adam's read.
+ *  flops        executed flops: GEMMs 2 flop per token per parameter for forward, recompute
+ *               (which skips the second feed-forward GEMM), input gradient and weight gradient
+ *               (appendix C.1), plus the causal attention products the paper neglects. */
+int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_bytes, uint64_t *grad_bytes,
+                      double *flops);
+
+/* Bytes of device memory lga_init_stack would allocate for cfg (host arithmetic only). */
+int lga_arena_bytes(const lga_config *cfg, uint64_t *bytes);
+
+/* p_l for cfg: 4 d^2 + 2 d d_I + 9 d + d_I (= 12 d^2 + 13 d when d_I = 4 d, Table B.1). */
+int lga_params_per_layer(const lga_config *cfg, uint64_t *count);
+
+const char *lga_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LGA_H */

@@ -1,0 +1,82 @@
+/*
+ * lga_ops.h - kernel-level entry points of the layer-stack library.
+ *
+ * Each call runs ONE of the kernels that lga_forward_layered / lga_backward_layered are built
+ * from, on caller-owned device buffers, so that every kernel can be checked on its own against the
+ * CPU oracle at small, ragged shapes.  Same conventions as lga.h: int status codes, validation on
+ * the host before any launch, `stream` is a borrowed hipStream_t (NULL = default), calls enqueue
+ * and return.  dtype is enum lga_dtype and selects the storage type of activation tensors
+ * (float or bfloat16); statistics, biases, gains and gradients of parameters are always float.
+ */
+#ifndef LGA_OPS_H
+#define LGA_OPS_H
+
+#include "lga.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Epilogues of lga_op_gemm.  All outputs are row-major [M, N] with leading dimension ldc. */
+enum lga_epilogue {
+    LGA_EPI_STORE = 0,      /* out = acc */
+    LGA_EPI_BIAS = 1,       /* out = acc + bias[n]                          (linear maps, section 5) */
+    LGA_EPI_BIAS_RESID = 2, /* out = acc + bias[n] + aux[m,n]               (residual add) */
+    LGA_EPI_BIAS_GELU = 3,  /* out2 = acc + bias[n]; out = gelu_tanh(out2)  (feed-forward non-linearity) */
+    LGA_EPI_MUL_DGELU = 4,  /* out = acc * gelu_tanh'(aux[m,n]) */
+    LGA_EPI_ACCUM_F32 = 5   /* outf = beta * outf + acc, fp32               (weight-gradient accumulation
+                               across micro-batches, section 2.5 / section 3) */
+};
+
+/* C[M,N] = sum_k A(m,k) B(k,n) followed by an epilogue (appendix C.1: the dense-layer products are
+ * the bulk of the computation).
+ *  a_kmajor != 0: A is stored [M][lda], k contiguous; else [K][lda], m contiguous.
+ *  b_kmajor != 0: B is stored [N][ldb], k contiguous; else [K][ldb], n contiguous.
+ * LGA_FP32: any shape.  LGA_BF16 (MFMA kernel): lda, ldb, ldc, N - and M when A is m-contiguous -
+ * must be multiples of 8, K a multiple of 8, all pointers 16-byte aligned, and the layout/epilogue
+ * pair must be one the layer uses: (k,n-major) with STORE/BIAS/BIAS_RESID/BIAS_GELU, (k,k-major)
+ * with STORE/MUL_DGELU, (m,n-major) with STORE/ACCUM_F32.  Otherwise LGA_ERR_SHAPE. */
+int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilogue, int32_t M, int32_t N, int32_t K,
+                const void *A, int32_t lda, const void *B, int32_t ldb, void *out, void *out2, float *outf,
+                int32_t ldc, const float *bias, const void *aux, float beta, void *stream);
+
+/* LayerNorm over rows of length d (biased variance, eps inside the root): y = (x-mean)*rstd*g + b.
+ * mean, rstd: [rows] float, written. */
+int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const float *b, void *y, float *mean,
+                         float *rstd, int32_t rows, int32_t d, float eps, void *stream);
+
+/* LayerNorm backward fused with the residual add:
+ *   dx = resid + rstd * (g*dy - mean_row(g*dy) - xhat * mean_row(g*dy*xhat))
+ *   dgamma = beta*dgamma + sum_rows dy*xhat ;  dbeta = beta*dbeta + sum_rows dy
+ * scratch: lga_op_colsum_scratch_floats(rows, d) floats of device memory. */
+int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const float *mean, const float *rstd,
+                         const float *g, const void *resid, void *dx, float *dgamma, float *dbeta, float beta,
+                         float *scratch, int32_t rows, int32_t d, void *stream);
+
+/* out[c] = beta*out[c] + sum_r a[r,c]  (bias gradients).  a: [rows][ld]. */
+int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int32_t ld, float beta, float *out,
+                  float *scratch, void *stream);
+uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols);
+
+/* Causal softmax attention per (sequence, head), scores scaled by 1/sqrt(d_h).
+ *  qkv  [n_seq*s, 3*heads*dh]: columns [Q | K | V], head h at columns h*dh inside each third
+ *  out  [n_seq*s, heads*dh]
+ *  lse  [n_seq, heads, s] float: log sum_j exp(scaled score_ij)
+ * kind 0: one-wavefront-per-position kernel (any dtype, any dh); kind 1: MFMA kernel with
+ * LDS-resident online softmax (LGA_BF16, dh in {32, 64, 96, 128, 160}). */
+int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out, float *lse, int32_t n_seq,
+                         int32_t s, int32_t heads, int32_t dh, void *stream);
+/* dqkv [n_seq*s, 3*heads*dh] written; delta [n_seq, heads, s] float scratch (written). */
+int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const void *out, const float *lse,
+                         const void *dout, void *dqkv, float *delta, int32_t n_seq, int32_t s, int32_t heads,
+                         int32_t dh, void *stream);
+
+/* One Adam update of n parameters in place (w, m, v fp32; g fp32 read-only); if w16 != NULL the new
+ * weights are also written as bfloat16 (section 2.5: 16-bit copy for the next use). */
+int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_t n, const lga_adam *adam,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LGA_OPS_H */

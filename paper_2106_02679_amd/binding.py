@@ -1,0 +1,206 @@
+"""ctypes binding of liblga.so: same names as include/lga.h and include/lga_ops.h.
+
+Argument marshalling only - every step of the path runs in the library's HIP kernels.
+PyTorch is used by callers for device memory and streams; tensors cross this boundary as raw
+device pointers (`tensor.data_ptr()`).  There is no CPU fallback: if the library has not been
+built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+# PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  Importing it first makes the
+# loader bind liblga.so to that same runtime, so the process holds ONE runtime and pointers from
+# torch allocations are known to the runtime that launches this library's kernels.
+import torch  # noqa: F401  (device memory and streams for the callers)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblga.so")
+
+LGA_FP32, LGA_BF16 = 0, 1
+LGA_OK, LGA_ERR_ARG, LGA_ERR_SHAPE, LGA_ERR_OOM, LGA_ERR_STATE, LGA_ERR_HIP = 0, -1, -2, -3, -4, -5
+LGA_ORDER_LAYERED, LGA_ORDER_MICROBATCH_MAJOR = 0, 1
+(LGA_EPI_STORE, LGA_EPI_BIAS, LGA_EPI_BIAS_RESID, LGA_EPI_BIAS_GELU, LGA_EPI_MUL_DGELU,
+ LGA_EPI_ACCUM_F32) = range(6)
+
+_STATUS_NAMES = {0: "LGA_OK", -1: "LGA_ERR_ARG", -2: "LGA_ERR_SHAPE", -3: "LGA_ERR_OOM", -4: "LGA_ERR_STATE",
+                 -5: "LGA_ERR_HIP"}
+
+
+class lga_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
+                ("seq_len", C.c_int32), ("micro_batch", C.c_int32), ("n_micro", C.c_int32), ("dtype", C.c_int32),
+                ("group", C.c_int32), ("retain_grads", C.c_int32), ("ln_eps", C.c_float), ("stream", C.c_void_p)]
+
+
+class lga_adam(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("step", C.c_int32)]
+
+
+class LgaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"{_STATUS_NAMES.get(code, code)}: {message}")
+        self.code = code
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2106_02679_amd.build` "
+                      "(there is no fallback path)")
+
+lib = C.CDLL(LIB_PATH)
+
+_vp, _i32, _u64, _f32 = C.c_void_p, C.c_int32, C.c_uint64, C.c_float
+_P = C.POINTER
+
+# name -> (restype, argtypes); every symbol include/*.h declares
+SIGNATURES = {
+    "lga_init_stack": (C.c_int, [_P(lga_config), _vp, _P(_vp)]),
+    "lga_destroy_stack": (None, [_vp]),
+    "lga_forward_layered": (C.c_int, [_vp, _vp, _vp]),
+    "lga_backward_layered": (C.c_int, [_vp, _vp, _vp, _P(lga_adam)]),
+    "lga_adam_step_layer": (C.c_int, [_vp, _i32, _P(lga_adam)]),
+    "lga_grads": (C.c_int, [_vp, _i32, _P(_vp), _P(C.c_size_t)]),
+    "lga_params": (C.c_int, [_vp, _i32, _P(_vp), _P(C.c_size_t)]),
+    "lga_moments": (C.c_int, [_vp, _i32, _P(_vp), _P(_vp), _P(C.c_size_t)]),
+    "lga_checkpoint": (C.c_int, [_vp, _i32, _P(_vp), _P(C.c_size_t)]),
+    "lga_step_mbmajor": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _P(lga_adam)]),
+    "lga_traffic_model": (C.c_int, [_P(lga_config), _i32, _P(_u64), _P(_u64), _P(C.c_double)]),
+    "lga_arena_bytes": (C.c_int, [_P(lga_config), _P(_u64)]),
+    "lga_params_per_layer": (C.c_int, [_P(lga_config), _P(_u64)]),
+    "lga_last_error": (C.c_char_p, []),
+    "lga_op_gemm": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _i32,
+                              _vp, _vp, _f32, _vp]),
+    "lga_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
+    "lga_op_layernorm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _i32,
+                                       _vp]),
+    "lga_op_colsum": (C.c_int, [_i32, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
+    "lga_op_colsum_scratch_floats": (_u64, [_i32, _i32]),
+    "lga_op_attention_fwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
+    "lga_op_attention_bwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
+    "lga_op_adam": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _u64, _P(lga_adam), _vp]),
+}
+for _name, (_res, _args) in SIGNATURES.items():
+    _fn = getattr(lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+_hip = C.CDLL("libamdhip64.so.7")      # already loaded (by torch); resolved by soname
+_hip.hipMemcpy.restype = C.c_int
+_hip.hipMemcpy.argtypes = [_vp, _vp, C.c_size_t, C.c_int]
+
+
+def read_device(ptr: int, count: int, dtype="float32"):
+    """Blocking copy of `count` elements at device address `ptr` into a new numpy array.
+    Synchronise the stream that produced the data first."""
+    import numpy as np
+    out = np.empty(count, dtype=dtype)
+    rc = _hip.hipMemcpy(out.ctypes.data_as(_vp), ptr, out.nbytes, 2)   # hipMemcpyDeviceToHost
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy device->host failed with HIP error {rc}")
+    return out
+
+
+def write_device(ptr: int, array) -> None:
+    """Blocking copy of a contiguous numpy array to device address `ptr`."""
+    import numpy as np
+    a = np.ascontiguousarray(array)
+    rc = _hip.hipMemcpy(ptr, a.ctypes.data_as(_vp), a.nbytes, 1)       # hipMemcpyHostToDevice
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy host->device failed with HIP error {rc}")
+
+
+def last_error() -> str:
+    return (lib.lga_last_error() or b"").decode()
+
+
+def check(code: int) -> None:
+    if code != LGA_OK:
+        raise LgaError(code, last_error())
+
+
+def make_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group=1, retain_grads=0,
+                ln_eps=1e-5, stream: Optional[int] = None) -> lga_config:
+    return lga_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group, retain_grads,
+                      ln_eps, stream)
+
+
+def params_per_layer(cfg: lga_config) -> int:
+    out = _u64()
+    check(lib.lga_params_per_layer(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def arena_bytes(cfg: lga_config) -> int:
+    out = _u64()
+    check(lib.lga_arena_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def traffic_model(cfg: lga_config, order: int):
+    pb, gb, fl = _u64(), _u64(), C.c_double()
+    check(lib.lga_traffic_model(C.byref(cfg), order, C.byref(pb), C.byref(gb), C.byref(fl)))
+    return pb.value, gb.value, fl.value
+
+
+class Stack:
+    """Owns an lga_stack handle.  Methods map one-to-one onto the C entry points."""
+
+    def __init__(self, cfg: lga_config, host_params=None):
+        self.cfg = cfg
+        self._h = _vp()
+        ptr = None
+        if host_params is not None:
+            import numpy as np
+            self._keep = np.ascontiguousarray(host_params, dtype=np.float32)
+            n = cfg.n_layers * params_per_layer(cfg)
+            if self._keep.size != n:
+                raise ValueError(f"host_params has {self._keep.size} floats, expected {n}")
+            ptr = self._keep.ctypes.data_as(_vp)
+        check(lib.lga_init_stack(C.byref(cfg), ptr, C.byref(self._h)))
+        self._keep = None
+
+    def close(self):
+        if self._h:
+            lib.lga_destroy_stack(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def forward_layered(self, x_ptr: int, y_ptr: Optional[int]):
+        check(lib.lga_forward_layered(self._h, x_ptr, y_ptr))
+
+    def backward_layered(self, dy_ptr: int, dx_ptr: Optional[int], adam: Optional[lga_adam]):
+        check(lib.lga_backward_layered(self._h, dy_ptr, dx_ptr, C.byref(adam) if adam is not None else None))
+
+    def step_mbmajor(self, x_ptr, dy_ptr, y_ptr, dx_ptr, adam: Optional[lga_adam]):
+        check(lib.lga_step_mbmajor(self._h, x_ptr, dy_ptr, y_ptr, dx_ptr, C.byref(adam) if adam is not None else None))
+
+    def adam_step_layer(self, layer: int, adam: lga_adam):
+        check(lib.lga_adam_step_layer(self._h, layer, C.byref(adam)))
+
+    def _borrow(self, fn, index):
+        p, n = _vp(), C.c_size_t()
+        check(fn(self._h, index, C.byref(p), C.byref(n)))
+        return p.value, n.value
+
+    def grads(self, layer: int):
+        return self._borrow(lib.lga_grads, layer)
+
+    def params(self, layer: int):
+        return self._borrow(lib.lga_params, layer)
+
+    def checkpoint(self, boundary: int):
+        return self._borrow(lib.lga_checkpoint, boundary)
+
+    def moments(self, layer: int):
+        m, v, n = _vp(), _vp(), C.c_size_t()
+        check(lib.lga_moments(self._h, layer, C.byref(m), C.byref(v), C.byref(n)))
+        return m.value, v.value, n.value

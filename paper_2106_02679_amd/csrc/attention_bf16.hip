@@ -1,0 +1,492 @@
+// Causal attention for gfx950 in bf16 with fp32 accumulation: forward with an LDS-resident
+// online softmax, and a deterministic two-kernel backward (no float atomics).
+//
+// All three kernels are built the same way.  A workgroup of 4 wavefronts owns 128 positions of
+// one (sequence, head); wavefront w owns 32 of them and lane l owns position l%32 of those, so
+// every softmax statistic, rescale factor and row sum is lane-local (only the two lane halves
+// of a position exchange a value, with one 32-lane swap).  That works because the score tile is
+// produced transposed - the tile that is streamed through LDS (keys in the forward and the dQ
+// kernel, queries in the dK/dV kernel) is the MFMA's first operand - and the v_mfma_f32_32x32x16
+// result layout (lane = column, 4 consecutive rows per register group) is, after conversion to
+// bf16, directly a valid second operand for the next MFMA: its K index is a permutation of the
+// streamed positions, and the first operand is read from a transposed LDS copy of the streamed
+// tile with the same permutation.  The transposed copies are made in registers (8x8 blocks of
+// 16-bit values) on the way from global memory to LDS.
+//
+//   forward      S^T = K Q^T ; P^T = softmax ; O^T += V^T P^T           streams K, V^T
+//   dQ kernel    S^T = K Q^T ; dP^T = V dO^T ; dS^T ; dQ^T += K^T dS^T   streams K, V, K^T
+//   dK/dV kernel S = Q K^T ; dP = dO V^T ; dV^T += dO^T P ; dK^T += Q^T dS   streams Q, dO, Q^T, dO^T
+#include "kernels.h"
+
+namespace lga {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// ---- LDS tile addressing -------------------------------------------------------------------
+// Natural tile [rows][DH] (DH contiguous), 16-byte chunks XOR-swizzled by row.
+template <int DH> __device__ __forceinline__ int sw_nat(int row) {
+    constexpr int NCH = DH / 8;
+    if constexpr ((NCH & (NCH - 1)) != 0) return (row >> 2) & 3;             // 96, 160: pitch = 16 banks mod 64
+    else if constexpr (DH == 32) return (row >> 2) & 3;
+    else if constexpr (DH == 64) return (row >> 1) & 7;
+    else return row & 15;                                                      // 128, 256
+}
+template <int DH> __device__ __forceinline__ int nat_off(int row, int chunk) {
+    return row * DH + ((chunk ^ sw_nat<DH>(row)) << 3);
+}
+// Transposed tile [DH][COLS] (streamed positions contiguous), COLS = 32 or 64.
+template <int COLS> __device__ __forceinline__ int sw_tr(int row) {
+    if constexpr (COLS == 64) return ((row >> 1) ^ (row >> 4)) & 7;
+    else return (row >> 2) & 3;
+}
+template <int COLS> __device__ __forceinline__ int tr_off(int row, int chunk) {
+    return row * COLS + ((chunk ^ sw_tr<COLS>(row)) << 3);
+}
+
+__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t x = in[2 * p][q], y = in[2 * p + 1][q];
+            out[2 * q][p] = (x & 0xFFFFu) | (y << 16);
+            out[2 * q + 1][p] = (x >> 16) | (y & 0xFFFF0000u);
+        }
+}
+
+// Cooperative (256 threads) copy of ROWS x DH bf16 from global (row pitch `pitch`) into a natural tile.
+// Rows at or beyond `nvalid` (counted from the tile's first row) are zero-filled.
+template <int ROWS, int DH>
+__device__ __forceinline__ void load_nat(bf16 *lds, const bf16 *__restrict__ src, size_t pitch, int nvalid) {
+    constexpr int NCH = DH / 8;
+    for (int idx = threadIdx.x; idx < ROWS * NCH; idx += 256) {
+        const int row = idx / NCH, c = idx % NCH;
+        u32x4 v = {0, 0, 0, 0};
+        if (row < nvalid) v = *reinterpret_cast<const u32x4 *>(src + (size_t)row * pitch + c * 8);
+        *reinterpret_cast<u32x4 *>(lds + nat_off<DH>(row, c)) = v;
+    }
+}
+// Same source tile, stored transposed: lds[dh][position].
+template <int COLS, int DH>
+__device__ __forceinline__ void load_tr(bf16 *lds, const bf16 *__restrict__ src, size_t pitch, int nvalid) {
+    constexpr int DB = DH / 8;
+    for (int blk = threadIdx.x; blk < DB * (COLS / 8); blk += 256) {
+        const int db = blk % DB, pb = blk / DB;
+        u32x4 in[8], out[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int row = pb * 8 + j;
+            in[j] = u32x4{0, 0, 0, 0};
+            if (row < nvalid) in[j] = *reinterpret_cast<const u32x4 *>(src + (size_t)row * pitch + db * 8);
+        }
+        transpose8x8(in, out);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(lds + tr_off<COLS>(db * 8 + c, pb)) = out[c];
+    }
+}
+
+// MFMA first operand from a natural tile: row `row`, k = 16*ks + 8*half + (0..7).
+template <int DH> __device__ __forceinline__ bf16x8 frag_nat(const bf16 *lds, int row, int ks, int half) {
+    return *reinterpret_cast<const bf16x8 *>(lds + nat_off<DH>(row, 2 * ks + half));
+}
+// MFMA first operand from a transposed tile: row `row` (a dh index), k element e <-> streamed position
+// 16*kk + 8*(e/4) + 4*half + e%4 - the permutation that matches a 32x32 MFMA result used as second operand.
+template <int COLS> __device__ __forceinline__ bf16x8 frag_tr(const bf16 *lds, int row, int kk, int half) {
+    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(lds + tr_off<COLS>(row, 2 * kk) + 4 * half);
+    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(lds + tr_off<COLS>(row, 2 * kk + 1) + 4 * half);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+// Second operand straight from global memory: 8 contiguous bf16 of one row (zero if the row is invalid).
+__device__ __forceinline__ bf16x8 frag_global(const bf16 *row_ptr, int ks, int half, bool valid) {
+    if (!valid) return bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    return *reinterpret_cast<const bf16x8 *>(row_ptr + 16 * ks + 8 * half);
+}
+// 32x32 fp32 result registers 8*kk .. 8*kk+7 -> bf16 second operand.
+__device__ __forceinline__ bf16x8 pack_bf16(const f32x16 &v, int kk) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16)v[8 * kk + e];
+    return o;
+}
+
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+// ============================================================================================
+// Forward.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ out,
+                                                       float *__restrict__ lse, AttnShape sh) {
+    constexpr int KT = 64;                 // keys per streamed tile
+    constexpr int NK = DH / 16, NC = DH / 32;
+    __shared__ __attribute__((aligned(16))) bf16 Ks[KT * DH];
+    __shared__ __attribute__((aligned(16))) bf16 Vt[DH * KT];
+
+    const int qblocks = (sh.s + 127) / 128;
+    const int qb = qblocks - 1 - blockIdx.x;
+    const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
+    const int d = sh.heads * DH;
+    const size_t pitch = 3 * (size_t)d;
+    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int qw0 = qb * 128 + wave * 32;          // first query of this wavefront
+    const int q = qw0 + lrow;
+    const bool qvalid = q < sh.s;
+
+    bf16x8 qf[NK];
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) qf[ks] = frag_global(seq + (size_t)q * pitch, ks, half, qvalid);
+
+    f32x16 oacc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c2 = rsqrtf((float)DH) * kLog2e;
+
+    const int kend = min(sh.s, qb * 128 + 128);     // keys needed by this block: [0, kend)
+    for (int k0 = 0; k0 < kend; k0 += KT) {
+        __syncthreads();
+        load_nat<KT, DH>(Ks, seq + (size_t)k0 * pitch + d, pitch, sh.s - k0);
+        load_tr<KT, DH>(Vt, seq + (size_t)k0 * pitch + 2 * d, pitch, sh.s - k0);
+        __syncthreads();
+        if (k0 > qw0 + 31) continue;               // whole tile is in this wavefront's future
+        f32x16 st[2];
+        const int nkb = (k0 + 32 > qw0 + 31) ? 1 : 2;   // second 32-key block may be entirely masked
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st[kb][r] = 0.f;
+            if (kb < nkb) {
+#pragma unroll
+                for (int ks = 0; ks < NK; ++ks)
+                    st[kb] = MFMA(frag_nat<DH>(Ks, kb * 32 + lrow, ks, half), qf[ks], st[kb]);
+            }
+        }
+        // scale into the log2 domain, mask, running max
+        float mx = m_run;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                const float v = (kb < nkb && key <= q) ? st[kb][r] * c2 : -INFINITY;
+                st[kb][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float alpha = exp2f(m_run - mx);       // 0 on the first tile (m_run = -inf, mx finite)
+        m_run = mx;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = exp2f(st[kb][r] - mx);
+                st[kb][r] = p;
+                psum += p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            if (kb < nkb) {
+#pragma unroll
+                for (int j2 = 0; j2 < 2; ++j2) {
+                    const bf16x8 pf = pack_bf16(st[kb], j2);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+                        oacc[c] = MFMA(frag_tr<KT>(Vt, c * 32 + lrow, 2 * kb + j2, half), pf, oacc[c]);
+                }
+            }
+        }
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (qvalid) {
+        const float inv = 1.0f / l_tot;
+        bf16 *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * DH;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[c][4 * g + i] * inv);
+                *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+            }
+        if (half == 0) lse[((size_t)b * sh.heads + h) * sh.s + q] = m_run * kLn2 + logf(l_tot);
+    }
+}
+
+// ============================================================================================
+// delta[b, h, q] = sum_c dO[q, h*DH + c] * O[q, h*DH + c].  One wavefront per (token, head).
+__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict__ out, const bf16 *__restrict__ dout,
+                                                         float *__restrict__ delta, AttnShape sh) {
+    const int lane = threadIdx.x & 63;
+    const size_t item = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);     // token * heads + head
+    const size_t total = (size_t)sh.n_seq * sh.s * sh.heads;
+    if (item >= total) return;
+    const int h = item % sh.heads;
+    const size_t tok = item / sh.heads;
+    const size_t off = tok * ((size_t)sh.heads * sh.dh) + (size_t)h * sh.dh;
+    float acc = 0.f;
+    for (int c = lane * 2; c < sh.dh; c += 128) {
+        acc += (float)out[off + c] * (float)dout[off + c] + (float)out[off + c + 1] * (float)dout[off + c + 1];
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) {
+        const size_t bb = tok / sh.s, qq = tok % sh.s;
+        delta[(bb * sh.heads + h) * sh.s + qq] = acc;
+    }
+}
+
+// ============================================================================================
+// dQ.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+                                                          const float *__restrict__ delta,
+                                                          const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
+                                                          AttnShape sh) {
+    constexpr int KT = 32;
+    constexpr int NK = DH / 16, NC = DH / 32;
+    __shared__ __attribute__((aligned(16))) bf16 Ks[KT * DH];
+    __shared__ __attribute__((aligned(16))) bf16 Vs[KT * DH];
+    __shared__ __attribute__((aligned(16))) bf16 Kt[DH * KT];
+
+    const int qblocks = (sh.s + 127) / 128;
+    const int qb = qblocks - 1 - blockIdx.x;
+    const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
+    const int d = sh.heads * DH;
+    const size_t pitch = 3 * (size_t)d;
+    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int qw0 = qb * 128 + wave * 32;
+    const int q = qw0 + lrow;
+    const bool qvalid = q < sh.s;
+
+    bf16x8 qf[NK], dof[NK];
+    const bf16 *dorow = dout + ((size_t)b * sh.s + q) * d + (size_t)h * DH;
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) {
+        qf[ks] = frag_global(seq + (size_t)q * pitch, ks, half, qvalid);
+        dof[ks] = frag_global(dorow, ks, half, qvalid);
+    }
+    const size_t stat = ((size_t)b * sh.heads + h) * sh.s + q;
+    const float lse2 = qvalid ? lse[stat] * kLog2e : 0.f;
+    const float dl = qvalid ? delta[stat] : 0.f;
+    const float scale = rsqrtf((float)DH);
+    const float c2 = scale * kLog2e;
+
+    f32x16 acc[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+
+    const int kend = min(sh.s, qb * 128 + 128);
+    for (int k0 = 0; k0 < kend; k0 += KT) {
+        __syncthreads();
+        load_nat<KT, DH>(Ks, seq + (size_t)k0 * pitch + d, pitch, sh.s - k0);
+        load_nat<KT, DH>(Vs, seq + (size_t)k0 * pitch + 2 * d, pitch, sh.s - k0);
+        load_tr<KT, DH>(Kt, seq + (size_t)k0 * pitch + d, pitch, sh.s - k0);
+        __syncthreads();
+        if (k0 > qw0 + 31) continue;
+        f32x16 st, dpt;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = dpt[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            st = MFMA(frag_nat<DH>(Ks, lrow, ks, half), qf[ks], st);
+            dpt = MFMA(frag_nat<DH>(Vs, lrow, ks, half), dof[ks], dpt);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = k0 + 8 * (r >> 2) + 4 * half + (r & 3);
+            const float p = (key <= q && qvalid) ? exp2f(st[r] * c2 - lse2) : 0.f;
+            st[r] = p * (dpt[r] - dl);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 dsf = pack_bf16(st, kk);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc[c] = MFMA(frag_tr<KT>(Kt, c * 32 + lrow, kk, half), dsf, acc[c]);
+        }
+    }
+    if (qvalid) {
+        bf16 *orow = dqkv + ((size_t)b * sh.s + q) * pitch + (size_t)h * DH;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = (bf16)(acc[c][4 * g + i] * scale);
+                *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+            }
+    }
+}
+
+// ============================================================================================
+// dK, dV.  grid.x = key blocks of 128 (smallest index first: it has the most queries), grid.y = n_seq * heads.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+                                                           const float *__restrict__ delta,
+                                                           const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
+                                                           AttnShape sh) {
+    constexpr int QT = 32;
+    constexpr int NK = DH / 16, NC = DH / 32;
+    __shared__ __attribute__((aligned(16))) bf16 Qs[QT * DH];
+    __shared__ __attribute__((aligned(16))) bf16 dOs[QT * DH];
+    __shared__ __attribute__((aligned(16))) bf16 Qt[DH * QT];
+    __shared__ __attribute__((aligned(16))) bf16 dOt[DH * QT];
+    __shared__ __attribute__((aligned(16))) float lse_s[QT];
+    __shared__ __attribute__((aligned(16))) float dl_s[QT];
+
+    const int kb128 = blockIdx.x;
+    const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
+    const int d = sh.heads * DH;
+    const size_t pitch = 3 * (size_t)d;
+    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
+    const bf16 *doseq = dout + (size_t)b * sh.s * d + (size_t)h * DH;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lrow = lane & 31, half = lane >> 5;
+    const int kw0 = kb128 * 128 + wave * 32;        // first key of this wavefront
+    const int key = kw0 + lrow;
+    const bool kvalid = key < sh.s;
+
+    bf16x8 kf[NK], vf[NK];
+#pragma unroll
+    for (int ks = 0; ks < NK; ++ks) {
+        kf[ks] = frag_global(seq + (size_t)key * pitch + d, ks, half, kvalid);
+        vf[ks] = frag_global(seq + (size_t)key * pitch + 2 * d, ks, half, kvalid);
+    }
+    const float scale = rsqrtf((float)DH);
+    const float c2 = scale * kLog2e;
+    const size_t stat0 = ((size_t)b * sh.heads + h) * sh.s;
+
+    f32x16 dk[NC], dv[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dk[c][r] = dv[c][r] = 0.f;
+
+    // queries that can see any key of this block: [kb128*128, s), walked in tiles of 32
+    for (int q0 = kb128 * 128; q0 < sh.s; q0 += QT) {
+        __syncthreads();
+        load_nat<QT, DH>(Qs, seq + (size_t)q0 * pitch, pitch, sh.s - q0);
+        load_nat<QT, DH>(dOs, doseq + (size_t)q0 * d, d, sh.s - q0);
+        load_tr<QT, DH>(Qt, seq + (size_t)q0 * pitch, pitch, sh.s - q0);
+        load_tr<QT, DH>(dOt, doseq + (size_t)q0 * d, d, sh.s - q0);
+        if (threadIdx.x < QT) {
+            const int qq = q0 + threadIdx.x;
+            lse_s[threadIdx.x] = qq < sh.s ? lse[stat0 + qq] * kLog2e : 0.f;
+            dl_s[threadIdx.x] = qq < sh.s ? delta[stat0 + qq] : 0.f;
+        }
+        __syncthreads();
+        if (q0 + QT - 1 < kw0) continue;            // every query of the tile precedes this wavefront's keys
+        f32x16 s_, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_[r] = dp[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            s_ = MFMA(frag_nat<DH>(Qs, lrow, ks, half), kf[ks], s_);
+            dp = MFMA(frag_nat<DH>(dOs, lrow, ks, half), vf[ks], dp);
+        }
+        f32x16 pr;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + 8 * g + 4 * half);
+            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dl_s + 8 * g + 4 * half);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = 4 * g + i;
+                const int qq = q0 + 8 * g + 4 * half + i;
+                const float p = (qq >= key && qq < sh.s && kvalid) ? exp2f(s_[r] * c2 - l4[i]) : 0.f;
+                pr[r] = p;
+                s_[r] = p * (dp[r] - d4[i]);
+            }
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 pf = pack_bf16(pr, kk);
+            const bf16x8 dsf = pack_bf16(s_, kk);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                dv[c] = MFMA(frag_tr<QT>(dOt, c * 32 + lrow, kk, half), pf, dv[c]);
+                dk[c] = MFMA(frag_tr<QT>(Qt, c * 32 + lrow, kk, half), dsf, dk[c]);
+            }
+        }
+    }
+    if (kvalid) {
+        bf16 *orow = dqkv + ((size_t)b * sh.s + key) * pitch + (size_t)h * DH;
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 ok, ov;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    ok[i] = (bf16)(dk[c][4 * g + i] * scale);
+                    ov[i] = (bf16)dv[c][4 * g + i];
+                }
+                *reinterpret_cast<bf16x4 *>(orow + d + c * 32 + 8 * g + 4 * half) = ok;
+                *reinterpret_cast<bf16x4 *>(orow + 2 * d + c * 32 + 8 * g + 4 * half) = ov;
+            }
+    }
+}
+
+template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
+    dim3 grid((sh.s + 127) / 128, sh.n_seq * sh.heads);
+    hipLaunchKernelGGL((attn_fwd_kernel<DH>), grid, dim3(256), 0, s, qkv, out, lse, sh);
+}
+template <int DH>
+void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *dout, bf16 *dqkv, AttnShape sh,
+            hipStream_t s) {
+    dim3 grid((sh.s + 127) / 128, sh.n_seq * sh.heads);
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+}
+
+}  // namespace
+
+bool attn_bf16_supports(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 160; }
+
+void launch_attn_fwd_bf16(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
+    if (sh.n_seq == 0 || sh.s == 0) return;
+    switch (sh.dh) {
+        case 32: fwd_dh<32>(qkv, out, lse, sh, s); break;
+        case 64: fwd_dh<64>(qkv, out, lse, sh, s); break;
+        case 96: fwd_dh<96>(qkv, out, lse, sh, s); break;
+        case 128: fwd_dh<128>(qkv, out, lse, sh, s); break;
+        case 160: fwd_dh<160>(qkv, out, lse, sh, s); break;
+        default: launch_attn_fwd_simple<bf16>(qkv, out, lse, sh, s); break;
+    }
+}
+
+void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, const bf16 *dout, bf16 *dqkv,
+                          float *delta, AttnShape sh, hipStream_t s) {
+    if (sh.n_seq == 0 || sh.s == 0) return;
+    if (!attn_bf16_supports(sh.dh)) {
+        launch_attn_bwd_simple<bf16>(qkv, out, lse, dout, dqkv, delta, sh, s);
+        return;
+    }
+    const size_t items = (size_t)sh.n_seq * sh.s * sh.heads;
+    hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, out, dout, delta, sh);
+    switch (sh.dh) {
+        case 32: bwd_dh<32>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 64: bwd_dh<64>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 96: bwd_dh<96>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 128: bwd_dh<128>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 160: bwd_dh<160>(qkv, lse, delta, dout, dqkv, sh, s); break;
+    }
+}
+
+}  // namespace lga

@@ -1,0 +1,96 @@
+// Shared device/host declarations for the layer-stack kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lga {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWave = 64;
+
+// ---- conversions -----------------------------------------------------------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); }
+template <class T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }
+
+// ---- wave / block reductions -------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Sum over a block of up to 1024 threads; every thread receives the total.
+// `scratch` must hold 16 floats of LDS and may be reused after the call returns.
+__device__ __forceinline__ float block_sum(float v, float *scratch) {
+    v = wave_sum(v);
+    const int w = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < nw; ++i) t += scratch[i];
+    return t;
+}
+
+// ---- GELU, tanh form ---------------------------------------------------------------------
+// 0.5 u (1 + tanh(c (u + a u^3))), c = sqrt(2/pi), a = 0.044715
+constexpr float kGeluC = 0.7978845608028654f;
+constexpr float kGeluA = 0.044715f;
+
+__device__ __forceinline__ float tanh_fast(float z) {
+    // tanh(z) = 1 - 2 / (exp(2z) + 1); saturates correctly for large |z|
+    const float e = __expf(2.0f * z);
+    return 1.0f - 2.0f / (e + 1.0f);
+}
+__device__ __forceinline__ float gelu_f(float u) {
+    const float z = kGeluC * (u + kGeluA * u * u * u);
+    return 0.5f * u * (1.0f + tanh_fast(z));
+}
+__device__ __forceinline__ float gelu_grad_f(float u) {
+    const float z = kGeluC * (u + kGeluA * u * u * u);
+    const float th = tanh_fast(z);
+    const float dz = kGeluC * (1.0f + 3.0f * kGeluA * u * u);
+    return 0.5f * (1.0f + th) + 0.5f * u * (1.0f - th * th) * dz;
+}
+
+// ---- GEMM epilogues ----------------------------------------------------------------------
+// C[m, n] = f(sum_k A(m,k) B(k,n)).  All outputs are row-major with leading dimension ldc.
+enum Epilogue : int {
+    EPI_STORE = 0,       // out = acc
+    EPI_BIAS = 1,        // out = acc + bias[n]
+    EPI_BIAS_RESID = 2,  // out = acc + bias[n] + aux[m, n]                 (aux: residual stream)
+    EPI_BIAS_GELU = 3,   // out2 = acc + bias[n]; out = gelu(out2)           (out2: pre-activation)
+    EPI_MUL_DGELU = 4,   // out = acc * gelu'(aux[m, n])                     (aux: pre-activation)
+    EPI_ACCUM_F32 = 5    // outf = beta * outf + acc (fp32 gradient buffer)
+};
+
+template <class T> struct GemmParams {
+    const T *A;      // see kernels for the storage convention selected by the transpose flags
+    const T *B;
+    int M, N, K;
+    int lda, ldb, ldc;
+    T *out;          // main output (activation type)
+    T *out2;         // second output (EPI_BIAS_GELU)
+    float *outf;     // fp32 output (EPI_ACCUM_F32)
+    const float *bias;
+    const T *aux;    // leading dimension ldc
+    float beta;
+};
+
+}  // namespace lga

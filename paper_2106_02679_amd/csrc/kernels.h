@@ -1,0 +1,67 @@
+// Host-side launchers of every HIP kernel of the layer-stack library.
+// Each launcher checks nothing: shapes are validated by the callers (stack.hip, ops_api.hip).
+#pragma once
+
+#include "common.h"
+
+namespace lga {
+
+// ---- element-wise / row kernels (rowops.hip) ---------------------------------------------
+// fp32 -> bf16 copy of a parameter vector ("restore": parameters converted to 16 bits before use).
+void launch_cast_f32_to_bf16(const float *src, bf16 *dst, size_t n, hipStream_t s);
+// Counter-based N(0, std^2) fill: element i gets a value that depends only on (seed, i).
+void launch_fill_normal(float *dst, size_t n, float std, uint64_t seed, hipStream_t s);
+void launch_fill_const(float *dst, size_t n, float value, hipStream_t s);
+
+// LayerNorm forward over rows of length d.  Writes y = xhat * g + b and the row statistics.
+template <class T>
+void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, float *mean, float *rstd,
+                          int rows, int d, float eps, hipStream_t s);
+// LayerNorm backward w.r.t. the input, fused with the residual add:
+//   dx = resid + rstd * (g dy - mean_row(g dy) - xhat * mean_row(g dy xhat))
+template <class T>
+void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const float *rstd, const float *g,
+                             const T *resid, T *dx, int rows, int d, hipStream_t s);
+
+// Column sums over rows, in two deterministic passes through `partial`:
+//   out0[c] = beta * out0[c] + sum_r a[r, c]
+//   out1[c] = beta * out1[c] + sum_r a[r, c] * (x[r, c] - mean[r]) * rstd[r]     (only if out1 != NULL)
+// a and x have leading dimension ld.  partial must hold colsum_partial_floats(rows, cols) floats.
+size_t colsum_partial_floats(int rows, int cols);
+template <class T>
+void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd, int rows, int cols, int ld,
+                   float beta, float *out0, float *out1, float *partial, hipStream_t s);
+
+// Adam update of n parameters in place; optionally also writes the bf16 copy of the new weights.
+void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t n, float lr, float beta1,
+                 float beta2, float eps, int step, hipStream_t s);
+
+// ---- GEMMs -------------------------------------------------------------------------------
+// C[M,N] = sum_k A(m,k) B(k,n), then the epilogue.
+//   a_kmajor: A is stored [M][lda] (k contiguous); otherwise [K][lda] (m contiguous).
+//   b_kmajor: B is stored [N][ldb] (k contiguous); otherwise [K][ldb] (n contiguous).
+// fp32 correctness-mode kernel (plain FMA, LDS tiles):
+void launch_gemm_f32(const GemmParams<float> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
+// bf16 MFMA kernel, fp32 accumulate.  Needs lda, ldb, ldc, N multiples of 8 and 16-byte aligned bases.
+void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
+
+// ---- causal attention --------------------------------------------------------------------
+// qkv: [tokens, 3 d] with columns [Q | K | V], head h at columns h*dh inside each third; tokens =
+// n_seq * s, each sequence attends only to itself.  out: [tokens, d].  lse: [n_seq, heads, s] holds
+// log(sum_j exp(score_ij)) of the scaled scores.  d = heads * dh.
+struct AttnShape {
+    int n_seq, s, heads, dh;
+};
+template <class T> void launch_attn_fwd_simple(const T *qkv, T *out, float *lse, AttnShape sh, hipStream_t s);
+// dqkv: [tokens, 3 d]; delta: scratch [n_seq, heads, s] (row sums of dout * out).
+template <class T>
+void launch_attn_bwd_simple(const T *qkv, const T *out, const float *lse, const T *dout, T *dqkv, float *delta,
+                            AttnShape sh, hipStream_t s);
+// MFMA kernels with LDS-resident online softmax (bf16).  Head sizes other than those
+// attn_bf16_supports() accepts are routed to the one-wavefront kernels above.
+bool attn_bf16_supports(int dh);
+void launch_attn_fwd_bf16(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s);
+void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, const bf16 *dout, bf16 *dqkv,
+                          float *delta, AttnShape sh, hipStream_t s);
+
+}  // namespace lga

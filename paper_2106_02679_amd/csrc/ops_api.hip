@@ -1,0 +1,176 @@
+// Kernel-level C ABI (include/lga_ops.h): one kernel per call on caller-owned device buffers.
+#include "../../include/lga_ops.h"
+
+#include <string>
+
+#include "kernels.h"
+
+using namespace lga;
+
+namespace lga {
+bool attn_bf16_supports(int dh);
+int set_last_error(int code, const char *msg);
+}  // namespace lga
+
+namespace {
+
+int err(int code, const char *msg) { return lga::set_last_error(code, msg); }
+
+bool a16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int done(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return err(LGA_ERR_HIP, (std::string(what) + ": " + hipGetErrorString(e)).c_str());
+    return LGA_OK;
+}
+
+bool dtype_ok(int32_t dt) { return dt == LGA_FP32 || dt == LGA_BF16; }
+
+}  // namespace
+
+extern "C" {
+
+int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilogue, int32_t M, int32_t N, int32_t K,
+                const void *A, int32_t lda, const void *B, int32_t ldb, void *out, void *out2, float *outf,
+                int32_t ldc, const float *bias, const void *aux, float beta, void *stream) {
+    if (!dtype_ok(dtype)) return err(LGA_ERR_ARG, "bad dtype");
+    if (epilogue < LGA_EPI_STORE || epilogue > LGA_EPI_ACCUM_F32) return err(LGA_ERR_ARG, "bad epilogue");
+    if (M < 0 || N < 0 || K < 0) return err(LGA_ERR_SHAPE, "negative size");
+    if ((M > 0 && N > 0) && (!A || !B) && K > 0) return err(LGA_ERR_ARG, "A or B is NULL");
+    const bool akm = a_kmajor != 0, bkm = b_kmajor != 0;
+    if (lda < (akm ? K : M) || ldb < (bkm ? K : N) || ldc < N) return err(LGA_ERR_SHAPE, "leading dimension too small");
+    const Epilogue e = static_cast<Epilogue>(epilogue);
+    if (e == EPI_ACCUM_F32 ? !outf : !out) return err(LGA_ERR_ARG, "output pointer is NULL");
+    if ((e == EPI_BIAS || e == EPI_BIAS_RESID || e == EPI_BIAS_GELU) && !bias) return err(LGA_ERR_ARG, "bias is NULL");
+    if ((e == EPI_BIAS_RESID || e == EPI_MUL_DGELU) && !aux) return err(LGA_ERR_ARG, "aux is NULL");
+    if (e == EPI_BIAS_GELU && !out2) return err(LGA_ERR_ARG, "out2 is NULL");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == LGA_FP32) {
+        GemmParams<float> p{};
+        p.A = static_cast<const float *>(A); p.B = static_cast<const float *>(B);
+        p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+        p.out = static_cast<float *>(out); p.out2 = static_cast<float *>(out2); p.outf = outf;
+        p.bias = bias; p.aux = static_cast<const float *>(aux); p.beta = beta;
+        launch_gemm_f32(p, akm, bkm, e, s);
+    } else {
+        if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || K % 8 || (!akm && M % 8))
+            return err(LGA_ERR_SHAPE, "bf16 GEMM needs lda, ldb, ldc, N, K (and M for m-contiguous A) to be multiples of 8");
+        if (!a16(A) || !a16(B) || !a16(out) || !a16(out2) || !a16(outf) || !a16(bias) || !a16(aux))
+            return err(LGA_ERR_SHAPE, "bf16 GEMM needs 16-byte aligned pointers");
+        bool ok = false;
+        if (akm && !bkm) ok = e == EPI_STORE || e == EPI_BIAS || e == EPI_BIAS_RESID || e == EPI_BIAS_GELU;
+        else if (akm && bkm) ok = e == EPI_STORE || e == EPI_MUL_DGELU;
+        else if (!akm && !bkm) ok = e == EPI_STORE || e == EPI_ACCUM_F32;
+        if (!ok) return err(LGA_ERR_SHAPE, "bf16 GEMM: this layout/epilogue pair is not built");
+        GemmParams<bf16> p{};
+        p.A = static_cast<const bf16 *>(A); p.B = static_cast<const bf16 *>(B);
+        p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+        p.out = static_cast<bf16 *>(out); p.out2 = static_cast<bf16 *>(out2); p.outf = outf;
+        p.bias = bias; p.aux = static_cast<const bf16 *>(aux); p.beta = beta;
+        launch_gemm_bf16(p, akm, bkm, e, s);
+    }
+    return done("lga_op_gemm");
+}
+
+int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const float *b, void *y, float *mean,
+                         float *rstd, int32_t rows, int32_t d, float eps, void *stream) {
+    if (!dtype_ok(dtype)) return err(LGA_ERR_ARG, "bad dtype");
+    if (rows < 0 || d < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if (!x || !g || !b || !y || !mean || !rstd) return err(LGA_ERR_ARG, "NULL argument");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == LGA_FP32)
+        launch_layernorm_fwd<float>(static_cast<const float *>(x), g, b, static_cast<float *>(y), mean, rstd, rows, d, eps, s);
+    else
+        launch_layernorm_fwd<bf16>(static_cast<const bf16 *>(x), g, b, static_cast<bf16 *>(y), mean, rstd, rows, d, eps, s);
+    return done("lga_op_layernorm_fwd");
+}
+
+int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const float *mean, const float *rstd,
+                         const float *g, const void *resid, void *dx, float *dgamma, float *dbeta, float beta,
+                         float *scratch, int32_t rows, int32_t d, void *stream) {
+    if (!dtype_ok(dtype)) return err(LGA_ERR_ARG, "bad dtype");
+    if (rows < 0 || d < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if (!dy || !x || !mean || !rstd || !g || !resid || !dx || !dgamma || !dbeta || !scratch)
+        return err(LGA_ERR_ARG, "NULL argument");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == LGA_FP32) {
+        launch_colsum<float>(static_cast<const float *>(dy), static_cast<const float *>(x), mean, rstd, rows, d, d, beta,
+                             dbeta, dgamma, scratch, s);
+        launch_layernorm_bwd_dx<float>(static_cast<const float *>(dy), static_cast<const float *>(x), mean, rstd, g,
+                                       static_cast<const float *>(resid), static_cast<float *>(dx), rows, d, s);
+    } else {
+        launch_colsum<bf16>(static_cast<const bf16 *>(dy), static_cast<const bf16 *>(x), mean, rstd, rows, d, d, beta,
+                            dbeta, dgamma, scratch, s);
+        launch_layernorm_bwd_dx<bf16>(static_cast<const bf16 *>(dy), static_cast<const bf16 *>(x), mean, rstd, g,
+                                      static_cast<const bf16 *>(resid), static_cast<bf16 *>(dx), rows, d, s);
+    }
+    return done("lga_op_layernorm_bwd");
+}
+
+uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols) {
+    if (rows < 0 || cols < 0) return 0;
+    return colsum_partial_floats(rows, cols);
+}
+
+int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int32_t ld, float beta, float *out,
+                  float *scratch, void *stream) {
+    if (!dtype_ok(dtype)) return err(LGA_ERR_ARG, "bad dtype");
+    if (rows < 0 || cols < 0 || ld < cols) return err(LGA_ERR_SHAPE, "bad shape");
+    if ((!a && rows > 0) || !out || !scratch) return err(LGA_ERR_ARG, "NULL argument");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (dtype == LGA_FP32)
+        launch_colsum<float>(static_cast<const float *>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr, scratch, s);
+    else
+        launch_colsum<bf16>(static_cast<const bf16 *>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr, scratch, s);
+    return done("lga_op_colsum");
+}
+
+int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out, float *lse, int32_t n_seq,
+                         int32_t s_len, int32_t heads, int32_t dh, void *stream) {
+    if (!dtype_ok(dtype) || (kind != 0 && kind != 1)) return err(LGA_ERR_ARG, "bad dtype or kind");
+    if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if (!qkv || !out || !lse) return err(LGA_ERR_ARG, "NULL argument");
+    if (kind == 1 && (dtype != LGA_BF16 || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out)))
+        return err(LGA_ERR_SHAPE, "MFMA attention needs bf16, 16-byte aligned tensors and d_h in {32,64,96,128,160}");
+    if ((size_t)(dh + s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
+    const AttnShape sh{n_seq, s_len, heads, dh};
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (kind == 1) launch_attn_fwd_bf16(static_cast<const bf16 *>(qkv), static_cast<bf16 *>(out), lse, sh, s);
+    else if (dtype == LGA_FP32) launch_attn_fwd_simple<float>(static_cast<const float *>(qkv), static_cast<float *>(out), lse, sh, s);
+    else launch_attn_fwd_simple<bf16>(static_cast<const bf16 *>(qkv), static_cast<bf16 *>(out), lse, sh, s);
+    return done("lga_op_attention_fwd");
+}
+
+int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const void *out, const float *lse,
+                         const void *dout, void *dqkv, float *delta, int32_t n_seq, int32_t s_len, int32_t heads,
+                         int32_t dh, void *stream) {
+    if (!dtype_ok(dtype) || (kind != 0 && kind != 1)) return err(LGA_ERR_ARG, "bad dtype or kind");
+    if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if (!qkv || !out || !lse || !dout || !dqkv || !delta) return err(LGA_ERR_ARG, "NULL argument");
+    if (kind == 1 && (dtype != LGA_BF16 || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out) || !a16(dout) || !a16(dqkv)))
+        return err(LGA_ERR_SHAPE, "MFMA attention needs bf16, 16-byte aligned tensors and d_h in {32,64,96,128,160}");
+    if ((size_t)(2 * dh + 2 * s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
+    const AttnShape sh{n_seq, s_len, heads, dh};
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (kind == 1)
+        launch_attn_bwd_bf16(static_cast<const bf16 *>(qkv), static_cast<const bf16 *>(out), lse,
+                             static_cast<const bf16 *>(dout), static_cast<bf16 *>(dqkv), delta, sh, s);
+    else if (dtype == LGA_FP32)
+        launch_attn_bwd_simple<float>(static_cast<const float *>(qkv), static_cast<const float *>(out), lse,
+                                      static_cast<const float *>(dout), static_cast<float *>(dqkv), delta, sh, s);
+    else
+        launch_attn_bwd_simple<bf16>(static_cast<const bf16 *>(qkv), static_cast<const bf16 *>(out), lse,
+                                     static_cast<const bf16 *>(dout), static_cast<bf16 *>(dqkv), delta, sh, s);
+    return done("lga_op_attention_bwd");
+}
+
+int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_t n, const lga_adam *adam,
+                void *stream) {
+    if (!w || !m || !v || !g || !adam) return err(LGA_ERR_ARG, "NULL argument");
+    if (adam->step < 1) return err(LGA_ERR_STATE, "Adam step t must be >= 1");
+    launch_adam(w, m, v, g, static_cast<bf16 *>(w16), n, adam->lr, adam->beta1, adam->beta2, adam->eps, adam->step,
+                reinterpret_cast<hipStream_t>(stream));
+    return done("lga_op_adam");
+}
+
+}  // extern "C"

@@ -1,0 +1,385 @@
+// HBM-bound kernels of the layer stack: parameter cast, LayerNorm forward / backward, column
+// sums (bias and LayerNorm-affine gradients), Adam, counter-based weight fill.
+// All arithmetic is fp32; T (float or bf16) is only the storage type of activations.
+#include "kernels.h"
+
+namespace lga {
+
+namespace {
+
+template <class T> struct VecOf;
+template <> struct VecOf<float> { static constexpr int N = 4; };
+template <> struct VecOf<bf16> { static constexpr int N = 8; };
+
+template <class T, int N> struct alignas(sizeof(T) * N) Pack { T v[N]; };
+
+template <class T, int N> __device__ __forceinline__ void load_pack(const T *p, float (&out)[N]) {
+    if constexpr (N == 1) {
+        out[0] = to_f32(p[0]);
+    } else {
+        const Pack<T, N> t = *reinterpret_cast<const Pack<T, N> *>(p);
+#pragma unroll
+        for (int i = 0; i < N; ++i) out[i] = to_f32(t.v[i]);
+    }
+}
+template <class T, int N> __device__ __forceinline__ void store_pack(T *p, const float (&in)[N]) {
+    if constexpr (N == 1) {
+        p[0] = from_f32<T>(in[0]);
+    } else {
+        Pack<T, N> t;
+#pragma unroll
+        for (int i = 0; i < N; ++i) t.v[i] = from_f32<T>(in[i]);
+        *reinterpret_cast<Pack<T, N> *>(p) = t;
+    }
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------------------------------------------
+__global__ void cast_kernel(const float *__restrict__ src, bf16 *__restrict__ dst, size_t n, size_t n4) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const f32x4 v = reinterpret_cast<const f32x4 *>(src)[i];
+        bf16x4 o;
+        o[0] = (bf16)v[0]; o[1] = (bf16)v[1]; o[2] = (bf16)v[2]; o[3] = (bf16)v[3];
+        reinterpret_cast<bf16x4 *>(dst)[i] = o;
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = (bf16)src[i];
+}
+
+__global__ void fill_const_kernel(float *dst, size_t n, float value) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = value;
+}
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Element i <- std * N(0,1) from a 64-bit mix of (seed, i) and Box-Muller.
+__global__ void fill_normal_kernel(float *dst, size_t n, float std, uint64_t seed) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const uint64_t h = mix64(seed * 0xD1342543DE82EF95ull + i);
+        const float u1 = ((float)(uint32_t)(h >> 40) + 1.0f) * (1.0f / 16777217.0f);   // (0, 1)
+        const float u2 = (float)(uint32_t)((h >> 8) & 0xFFFFFFu) * (1.0f / 16777216.0f);
+        dst[i] = std * sqrtf(-2.0f * __logf(u1)) * __cosf(6.283185307179586f * u2);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// LayerNorm forward: one block per row.
+template <class T, int V>
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T *__restrict__ x, const float *__restrict__ g,
+                                                            const float *__restrict__ b, T *__restrict__ y,
+                                                            float *__restrict__ mean_out, float *__restrict__ rstd_out,
+                                                            int d, float eps) {
+    __shared__ float red[16];
+    const size_t row = blockIdx.x;
+    const T *xr = x + row * (size_t)d;
+    T *yr = y + row * (size_t)d;
+    float s = 0.f;
+    for (int c = threadIdx.x * V; c < d; c += blockDim.x * V) {
+        float v[V];
+        load_pack<T, V>(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < V; ++i) s += v[i];
+    }
+    const float mean = block_sum(s, red) / (float)d;
+    float q = 0.f;
+    for (int c = threadIdx.x * V; c < d; c += blockDim.x * V) {
+        float v[V];
+        load_pack<T, V>(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < V; ++i) q += (v[i] - mean) * (v[i] - mean);
+    }
+    const float var = block_sum(q, red) / (float)d;
+    const float rstd = rsqrtf(var + eps);
+    if (threadIdx.x == 0) {
+        mean_out[row] = mean;
+        rstd_out[row] = rstd;
+    }
+    for (int c = threadIdx.x * V; c < d; c += blockDim.x * V) {
+        float v[V], o[V];
+        load_pack<T, V>(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = (v[i] - mean) * rstd * g[c + i] + b[c + i];
+        store_pack<T, V>(yr + c, o);
+    }
+}
+
+// LayerNorm backward w.r.t. the input, plus residual: one block per row.
+template <class T, int V>
+__global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const T *__restrict__ dy, const T *__restrict__ x,
+                                                               const float *__restrict__ mean,
+                                                               const float *__restrict__ rstd,
+                                                               const float *__restrict__ g, const T *resid,
+                                                               T *dx, int d) {
+    __shared__ float red[16];
+    const size_t row = blockIdx.x;
+    const T *dyr = dy + row * (size_t)d;
+    const T *xr = x + row * (size_t)d;
+    const T *rr = resid + row * (size_t)d;
+    T *dxr = dx + row * (size_t)d;
+    const float mu = mean[row], rs = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+    for (int c = threadIdx.x * V; c < d; c += blockDim.x * V) {
+        float a[V], v[V];
+        load_pack<T, V>(dyr + c, a);
+        load_pack<T, V>(xr + c, v);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float gd = a[i] * g[c + i];
+            s1 += gd;
+            s2 += gd * (v[i] - mu) * rs;
+        }
+    }
+    s1 = block_sum(s1, red) / (float)d;
+    s2 = block_sum(s2, red) / (float)d;
+    for (int c = threadIdx.x * V; c < d; c += blockDim.x * V) {
+        float a[V], v[V], r[V], o[V];
+        load_pack<T, V>(dyr + c, a);
+        load_pack<T, V>(xr + c, v);
+        load_pack<T, V>(rr + c, r);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const float xhat = (v[i] - mu) * rs;
+            o[i] = r[i] + rs * (a[i] * g[c + i] - s1 - xhat * s2);
+        }
+        store_pack<T, V>(dxr + c, o);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Column sums, pass 1: block (32 column-threads x 8 row-threads) reduces kColsumRows rows of a
+// strip of 32*V columns into partial[row_chunk][2][cols].
+constexpr int kColsumRows = 128;
+
+template <class T, int V, bool WITH_XHAT>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ a, const T *__restrict__ x,
+                                                             const float *__restrict__ mean,
+                                                             const float *__restrict__ rstd, int rows, int cols,
+                                                             int ld, float *__restrict__ partial) {
+    __shared__ float red[2][8][32 * V + 1];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int c0 = (blockIdx.x * 32 + tx) * V;
+    const int r0 = blockIdx.y * kColsumRows;
+    const int r1 = min(rows, r0 + kColsumRows);
+    float s0[V], s1[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) s0[i] = s1[i] = 0.f;
+    if (c0 < cols) {
+        for (int r = r0 + ty; r < r1; r += 8) {
+            float av[V];
+            load_pack<T, V>(a + (size_t)r * ld + c0, av);
+#pragma unroll
+            for (int i = 0; i < V; ++i) s0[i] += av[i];
+            if constexpr (WITH_XHAT) {
+                float xv[V];
+                load_pack<T, V>(x + (size_t)r * ld + c0, xv);
+                const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+                for (int i = 0; i < V; ++i) s1[i] += av[i] * (xv[i] - mu) * rs;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        red[0][ty][tx * V + i] = s0[i];
+        red[1][ty][tx * V + i] = s1[i];
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < 32 * V; j += 256) {
+        const int c = blockIdx.x * 32 * V + j;
+        if (c >= cols) continue;
+        float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            t0 += red[0][k][j];
+            t1 += red[1][k][j];
+        }
+        partial[((size_t)blockIdx.y * 2 + 0) * cols + c] = t0;
+        if constexpr (WITH_XHAT) partial[((size_t)blockIdx.y * 2 + 1) * cols + c] = t1;
+    }
+}
+
+__global__ void colsum_final_kernel(const float *__restrict__ partial, int chunks, int cols, float beta,
+                                    float *out0, float *out1) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= cols) return;
+    float t0 = 0.f, t1 = 0.f;
+    for (int k = 0; k < chunks; ++k) {
+        t0 += partial[((size_t)k * 2 + 0) * cols + c];
+        if (out1) t1 += partial[((size_t)k * 2 + 1) * cols + c];
+    }
+    out0[c] = (beta == 0.f ? 0.f : beta * out0[c]) + t0;
+    if (out1) out1[c] = (beta == 0.f ? 0.f : beta * out1[c]) + t1;
+}
+
+// ------------------------------------------------------------------------------------------
+// Adam: streams w, m, v, g once (16 B/param in, 12 B + 2 B out).
+struct AdamConsts {
+    float beta1, beta2, omb1, omb2, inv_bc1, inv_bc2, lr, eps;
+};
+
+__device__ __forceinline__ void adam_one(float &w, float &m, float &v, float g, const AdamConsts &c) {
+    m = c.beta1 * m + c.omb1 * g;
+    v = c.beta2 * v + c.omb2 * g * g;
+    const float mh = m * c.inv_bc1;
+    const float vh = v * c.inv_bc2;
+    w = w - c.lr * mh / (sqrtf(vh) + c.eps);
+}
+
+__global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float *__restrict__ m,
+                                                   float *__restrict__ v, const float *__restrict__ g,
+                                                   bf16 *__restrict__ w16, size_t n, size_t n4, AdamConsts c) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        f32x4 wv = reinterpret_cast<f32x4 *>(w)[i];
+        f32x4 mv = reinterpret_cast<f32x4 *>(m)[i];
+        f32x4 vv = reinterpret_cast<f32x4 *>(v)[i];
+        const f32x4 gv = reinterpret_cast<const f32x4 *>(g)[i];
+        float wa[4] = {wv[0], wv[1], wv[2], wv[3]}, ma[4] = {mv[0], mv[1], mv[2], mv[3]};
+        float va[4] = {vv[0], vv[1], vv[2], vv[3]};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) adam_one(wa[k], ma[k], va[k], gv[k], c);
+        wv = {wa[0], wa[1], wa[2], wa[3]};
+        mv = {ma[0], ma[1], ma[2], ma[3]};
+        vv = {va[0], va[1], va[2], va[3]};
+        reinterpret_cast<f32x4 *>(w)[i] = wv;
+        reinterpret_cast<f32x4 *>(m)[i] = mv;
+        reinterpret_cast<f32x4 *>(v)[i] = vv;
+        if (w16) {
+            bf16x4 o;
+            o[0] = (bf16)wa[0]; o[1] = (bf16)wa[1]; o[2] = (bf16)wa[2]; o[3] = (bf16)wa[3];
+            reinterpret_cast<bf16x4 *>(w16)[i] = o;
+        }
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float wa = w[i], ma = m[i], va = v[i];
+        adam_one(wa, ma, va, g[i], c);
+        w[i] = wa; m[i] = ma; v[i] = va;
+        if (w16) w16[i] = (bf16)wa;
+    }
+}
+
+inline int grid_for(size_t work_items, int block, int max_blocks = 256 * 16) {
+    size_t b = (work_items + block - 1) / block;
+    if (b < 1) b = 1;
+    if (b > (size_t)max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+}  // namespace
+
+// ==========================================================================================
+void launch_cast_f32_to_bf16(const float *src, bf16 *dst, size_t n, hipStream_t s) {
+    if (n == 0) return;
+    const size_t n4 = (aligned16(src) && (reinterpret_cast<uintptr_t>(dst) & 7u) == 0) ? n / 4 : 0;   // vector part
+    hipLaunchKernelGGL(cast_kernel, dim3(grid_for(n / 4 + 1, 256)), dim3(256), 0, s, src, dst, n, n4);
+}
+
+void launch_fill_normal(float *dst, size_t n, float std, uint64_t seed, hipStream_t s) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(fill_normal_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, dst, n, std, seed);
+}
+
+void launch_fill_const(float *dst, size_t n, float value, hipStream_t s) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(fill_const_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, dst, n, value);
+}
+
+template <class T>
+void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, float *mean, float *rstd, int rows,
+                          int d, float eps, hipStream_t s) {
+    if (rows == 0) return;
+    constexpr int V = VecOf<T>::N;
+    if (d % V == 0 && aligned16(x) && aligned16(y))
+        hipLaunchKernelGGL((layernorm_fwd_kernel<T, V>), dim3(rows), dim3(256), 0, s, x, g, b, y, mean, rstd, d, eps);
+    else
+        hipLaunchKernelGGL((layernorm_fwd_kernel<T, 1>), dim3(rows), dim3(256), 0, s, x, g, b, y, mean, rstd, d, eps);
+}
+template void launch_layernorm_fwd<float>(const float *, const float *, const float *, float *, float *, float *, int,
+                                          int, float, hipStream_t);
+template void launch_layernorm_fwd<bf16>(const bf16 *, const float *, const float *, bf16 *, float *, float *, int,
+                                         int, float, hipStream_t);
+
+template <class T>
+void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const float *rstd, const float *g,
+                             const T *resid, T *dx, int rows, int d, hipStream_t s) {
+    if (rows == 0) return;
+    constexpr int V = VecOf<T>::N;
+    if (d % V == 0 && aligned16(dy) && aligned16(x) && aligned16(resid) && aligned16(dx))
+        hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
+                           dx, d);
+    else
+        hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, 1>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
+                           dx, d);
+}
+template void launch_layernorm_bwd_dx<float>(const float *, const float *, const float *, const float *,
+                                             const float *, const float *, float *, int, int, hipStream_t);
+template void launch_layernorm_bwd_dx<bf16>(const bf16 *, const bf16 *, const float *, const float *, const float *,
+                                            const bf16 *, bf16 *, int, int, hipStream_t);
+
+size_t colsum_partial_floats(int rows, int cols) {
+    const size_t chunks = ((size_t)rows + kColsumRows - 1) / kColsumRows;
+    return (chunks > 0 ? chunks : 1) * 2 * (size_t)cols;
+}
+
+template <class T>
+void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd, int rows, int cols, int ld,
+                   float beta, float *out0, float *out1, float *partial, hipStream_t s) {
+    if (cols == 0) return;
+    constexpr int VMAX = VecOf<T>::N;
+    const int chunks = rows > 0 ? (rows + kColsumRows - 1) / kColsumRows : 0;
+    const bool vec = (cols % VMAX == 0) && (ld % VMAX == 0) && aligned16(a) && (x == nullptr || aligned16(x));
+    if (chunks > 0) {
+        if (vec) {
+            dim3 grid((cols + 32 * VMAX - 1) / (32 * VMAX), chunks);
+            if (out1)
+                hipLaunchKernelGGL((colsum_partial_kernel<T, VMAX, true>), grid, dim3(256), 0, s, a, x, mean, rstd,
+                                   rows, cols, ld, partial);
+            else
+                hipLaunchKernelGGL((colsum_partial_kernel<T, VMAX, false>), grid, dim3(256), 0, s, a, x, mean, rstd,
+                                   rows, cols, ld, partial);
+        } else {
+            dim3 grid((cols + 31) / 32, chunks);
+            if (out1)
+                hipLaunchKernelGGL((colsum_partial_kernel<T, 1, true>), grid, dim3(256), 0, s, a, x, mean, rstd, rows,
+                                   cols, ld, partial);
+            else
+                hipLaunchKernelGGL((colsum_partial_kernel<T, 1, false>), grid, dim3(256), 0, s, a, x, mean, rstd, rows,
+                                   cols, ld, partial);
+        }
+    }
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, partial, chunks, cols, beta,
+                       out0, out1);
+}
+template void launch_colsum<float>(const float *, const float *, const float *, const float *, int, int, int, float,
+                                   float *, float *, float *, hipStream_t);
+template void launch_colsum<bf16>(const bf16 *, const bf16 *, const float *, const float *, int, int, int, float,
+                                  float *, float *, float *, hipStream_t);
+
+void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t n, float lr, float beta1,
+                 float beta2, float eps, int step, hipStream_t s) {
+    if (n == 0) return;
+    AdamConsts c;
+    c.beta1 = beta1;
+    c.beta2 = beta2;
+    c.omb1 = (float)(1.0 - (double)beta1);
+    c.omb2 = (float)(1.0 - (double)beta2);
+    c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)beta1, (double)step)));
+    c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
+    c.lr = lr;
+    c.eps = eps;
+    const bool vec = aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
+                     (reinterpret_cast<uintptr_t>(w16) & 7u) == 0;
+    const size_t n4 = vec ? n / 4 : 0;
+    hipLaunchKernelGGL(adam_kernel, dim3(grid_for(n / 4 + 1, 256, 256 * 8)), dim3(256), 0, s, w, m, v, g, w16, n, n4,
+                       c);
+}
+
+}  // namespace lga

@@ -1,0 +1,556 @@
+// C ABI and layer-major scheduler of the layered-gradient-accumulation layer-stack library.
+// See include/lga.h for the contract of every entry point.
+#include "../../include/lga.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+#include <string>
+#include <type_traits>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace lga;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string &msg) {
+    g_last_error = msg;
+    return code;
+}
+
+}  // namespace
+
+namespace lga {
+int set_last_error(int code, const char *msg) { return fail(code, msg); }
+}  // namespace lga
+
+namespace {
+
+#define LGA_HIP(expr)                                                                                   \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess)                                                                           \
+            return fail(e_ == hipErrorOutOfMemory ? LGA_ERR_OOM : LGA_ERR_HIP,                          \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                             \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Offsets (in elements) of one layer's tensors inside its flat canonical vector.
+struct LayerLayout {
+    size_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_1, b_1, w_2, b_2, total, matrices;
+};
+
+LayerLayout make_layout(size_t d, size_t f) {
+    LayerLayout o{};
+    size_t p = 0;
+    o.ln1_g = p; p += d;
+    o.ln1_b = p; p += d;
+    o.w_qkv = p; p += d * 3 * d;
+    o.b_qkv = p; p += 3 * d;
+    o.w_o = p; p += d * d;
+    o.b_o = p; p += d;
+    o.ln2_g = p; p += d;
+    o.ln2_b = p; p += d;
+    o.w_1 = p; p += d * f;
+    o.b_1 = p; p += f;
+    o.w_2 = p; p += f * d;
+    o.b_2 = p; p += d;
+    o.total = p;
+    o.matrices = 4 * d * d + 2 * d * f;
+    return o;
+}
+
+int validate_config(const lga_config *c) {
+    if (!c) return fail(LGA_ERR_ARG, "config is NULL");
+    if (c->dtype != LGA_FP32 && c->dtype != LGA_BF16) return fail(LGA_ERR_ARG, "dtype must be LGA_FP32 or LGA_BF16");
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ff < 1 || c->seq_len < 1 || c->micro_batch < 1 ||
+        c->n_micro < 1)
+        return fail(LGA_ERR_SHAPE, "every size must be >= 1");
+    if (c->d_model % c->n_heads != 0) return fail(LGA_ERR_SHAPE, "d_model must be a multiple of n_heads");
+    if (c->group < 1 || c->group > c->n_micro || c->n_micro % c->group != 0)
+        return fail(LGA_ERR_SHAPE, "group must be in 1..n_micro and divide n_micro");
+    if (!(c->ln_eps >= 0.f)) return fail(LGA_ERR_ARG, "ln_eps must be >= 0");
+    if (c->dtype == LGA_FP32 && (2.0 * c->seq_len + 2.0 * c->d_model / c->n_heads) * 4 > 60000)
+        return fail(LGA_ERR_SHAPE, "fp32 mode: seq_len too long for the one-wavefront attention kernel's LDS rows");
+    if (c->dtype == LGA_BF16) {
+        const int dh = c->d_model / c->n_heads;
+        if (dh % 32 != 0) return fail(LGA_ERR_SHAPE, "bf16 mode needs head size d_h to be a multiple of 32");
+        if (c->d_model % 8 != 0 || c->d_ff % 8 != 0)
+            return fail(LGA_ERR_SHAPE, "bf16 mode needs d_model and d_ff to be multiples of 8");
+    }
+    // kernels index rows and columns with int and elements with size_t
+    const double tokens_group = (double)c->group * c->micro_batch * c->seq_len;
+    if (tokens_group > 1.0e9 || 3.0 * c->d_model > 2.0e9 || (double)c->n_heads * c->micro_batch * c->group > 2.0e9)
+        return fail(LGA_ERR_SHAPE, "sizes overflow the index range");
+    return LGA_OK;
+}
+
+// Arena plan: one allocation, every sub-buffer 256-byte aligned.
+struct Plan {
+    size_t w, m, v, grad, w16, ckpt, dact;
+    size_t h, qkv, a, x1, h2, u, gl, du, dh2, dx1, da, dqkv, dh;
+    size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
+    size_t total;
+};
+
+Plan make_plan(const lga_config &c) {
+    Plan p{};
+    const size_t d = c.d_model, f = c.d_ff, L = c.n_layers;
+    const size_t P = make_layout(d, f).total;
+    const size_t esz = c.dtype == LGA_BF16 ? 2 : 4;
+    const size_t T = (size_t)c.n_micro * c.micro_batch * c.seq_len;
+    const size_t t = (size_t)c.group * c.micro_batch * c.seq_len;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    p.w = take(L * P * 4);
+    p.m = take(L * P * 4);
+    p.v = take(L * P * 4);
+    p.grad = take((c.retain_grads ? L : 1) * P * 4);
+    p.w16 = take(c.dtype == LGA_BF16 ? L * P * 2 : 0);
+    p.ckpt = take((L + 1) * T * d * esz);
+    p.dact = take(T * d * esz);
+    p.h = take(t * d * esz);
+    p.qkv = take(t * 3 * d * esz);
+    p.a = take(t * d * esz);
+    p.x1 = take(t * d * esz);
+    p.h2 = take(t * d * esz);
+    p.u = take(t * f * esz);
+    p.gl = take(t * f * esz);
+    p.du = take(t * f * esz);
+    p.dh2 = take(t * d * esz);
+    p.dx1 = take(t * d * esz);
+    p.da = take(t * d * esz);
+    p.dqkv = take(t * 3 * d * esz);
+    p.dh = take(t * d * esz);
+    p.mean1 = take(t * 4);
+    p.rstd1 = take(t * 4);
+    p.mean2 = take(t * 4);
+    p.rstd2 = take(t * 4);
+    const size_t stats = (size_t)c.group * c.micro_batch * c.n_heads * c.seq_len;
+    p.lse = take(stats * 4);
+    p.delta = take(stats * 4);
+    const size_t widest = std::max<size_t>(3 * d, f);
+    p.partial = take(colsum_partial_floats((int)t, (int)widest) * 4);
+    p.total = off;
+    return p;
+}
+
+}  // namespace
+
+struct lga_stack {
+    lga_config cfg;
+    LayerLayout lay;
+    Plan plan;
+    hipStream_t stream;
+    char *arena;
+    size_t P, T, t;          // params per layer, tokens per step, tokens per group
+    bool have_forward;
+    std::vector<int> grad_owner;   // which layer's gradient each gradient buffer currently holds (-1: none)
+
+    template <class X> X *at(size_t off) const { return reinterpret_cast<X *>(arena + off); }
+    float *w(int l) const { return at<float>(plan.w) + (size_t)l * P; }
+    float *m(int l) const { return at<float>(plan.m) + (size_t)l * P; }
+    float *v(int l) const { return at<float>(plan.v) + (size_t)l * P; }
+    bf16 *w16(int l) const { return at<bf16>(plan.w16) + (size_t)l * P; }
+    int grad_slot(int l) const { return cfg.retain_grads ? l : 0; }
+    float *grad(int l) const { return at<float>(plan.grad) + (size_t)grad_slot(l) * P; }
+    size_t esz() const { return cfg.dtype == LGA_BF16 ? 2 : 4; }
+    char *ckpt(int boundary) const { return arena + plan.ckpt + (size_t)boundary * T * cfg.d_model * esz(); }
+};
+
+namespace {
+
+template <class T> void gemm(const GemmParams<T> &p, bool akm, bool bkm, Epilogue e, hipStream_t s) {
+    if constexpr (std::is_same<T, float>::value) launch_gemm_f32(p, akm, bkm, e, s);
+    else launch_gemm_bf16(p, akm, bkm, e, s);
+}
+
+// The weights the GEMMs read: fp32 masters in fp32 mode, the 16-bit copy in bf16 mode.
+template <class T> const T *gemm_weights(const lga_stack *st, int l) {
+    if constexpr (std::is_same<T, float>::value) return st->w(l);
+    else return st->w16(l);
+}
+
+// Forward of layer l on one micro-batch group (paper section 5 "Model"; pre-LN residual form).
+// x_in: [t, d] group slice of the layer's input checkpoint.  y_out: group slice of the next
+// checkpoint, or NULL when this is the backward pass's recompute (the second feed-forward GEMM's
+// output is not needed there, so it is not recomputed).
+template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_out) {
+    const lga_config &c = st->cfg;
+    const int d = c.d_model, f = c.d_ff, t = (int)st->t;
+    const LayerLayout &o = st->lay;
+    const float *pf = st->w(l);
+    const T *pw = gemm_weights<T>(st, l);
+    hipStream_t s = st->stream;
+    T *h = st->at<T>(st->plan.h), *qkv = st->at<T>(st->plan.qkv), *a = st->at<T>(st->plan.a);
+    T *x1 = st->at<T>(st->plan.x1), *h2 = st->at<T>(st->plan.h2), *u = st->at<T>(st->plan.u);
+    T *gl = st->at<T>(st->plan.gl);
+    float *lse = st->at<float>(st->plan.lse);
+    const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
+
+    launch_layernorm_fwd<T>(x_in, pf + o.ln1_g, pf + o.ln1_b, h, st->at<float>(st->plan.mean1),
+                            st->at<float>(st->plan.rstd1), t, d, c.ln_eps, s);
+    GemmParams<T> g{};
+    g.A = h; g.lda = d; g.B = pw + o.w_qkv; g.ldb = 3 * d; g.M = t; g.N = 3 * d; g.K = d;
+    g.out = qkv; g.ldc = 3 * d; g.bias = pf + o.b_qkv;
+    gemm<T>(g, true, false, EPI_BIAS, s);
+    if constexpr (std::is_same<T, float>::value) launch_attn_fwd_simple<float>(qkv, a, lse, ash, s);
+    else launch_attn_fwd_bf16(qkv, a, lse, ash, s);
+    g = GemmParams<T>{};
+    g.A = a; g.lda = d; g.B = pw + o.w_o; g.ldb = d; g.M = t; g.N = d; g.K = d;
+    g.out = x1; g.ldc = d; g.bias = pf + o.b_o; g.aux = x_in;
+    gemm<T>(g, true, false, EPI_BIAS_RESID, s);
+    launch_layernorm_fwd<T>(x1, pf + o.ln2_g, pf + o.ln2_b, h2, st->at<float>(st->plan.mean2),
+                            st->at<float>(st->plan.rstd2), t, d, c.ln_eps, s);
+    g = GemmParams<T>{};
+    g.A = h2; g.lda = d; g.B = pw + o.w_1; g.ldb = f; g.M = t; g.N = f; g.K = d;
+    g.out = gl; g.out2 = u; g.ldc = f; g.bias = pf + o.b_1;
+    gemm<T>(g, true, false, EPI_BIAS_GELU, s);
+    if (y_out) {
+        g = GemmParams<T>{};
+        g.A = gl; g.lda = f; g.B = pw + o.w_2; g.ldb = d; g.M = t; g.N = d; g.K = f;
+        g.out = y_out; g.ldc = d; g.bias = pf + o.b_2; g.aux = x1;
+        gemm<T>(g, true, false, EPI_BIAS_RESID, s);
+    }
+}
+
+// Backward of layer l on one group whose intermediates were just recomputed by layer_forward.
+// dy: [t, d] group slice of the running activation gradient, overwritten with dx.
+// gbuf: the layer's fp32 gradient buffer (canonical layout); beta = 0 for the layer's first group.
+template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *dy, float *gbuf, float beta) {
+    const lga_config &c = st->cfg;
+    const int d = c.d_model, f = c.d_ff, t = (int)st->t;
+    const LayerLayout &o = st->lay;
+    const float *pf = st->w(l);
+    const T *pw = gemm_weights<T>(st, l);
+    hipStream_t s = st->stream;
+    T *h = st->at<T>(st->plan.h), *qkv = st->at<T>(st->plan.qkv), *a = st->at<T>(st->plan.a);
+    T *x1 = st->at<T>(st->plan.x1), *h2 = st->at<T>(st->plan.h2), *u = st->at<T>(st->plan.u);
+    T *gl = st->at<T>(st->plan.gl), *du = st->at<T>(st->plan.du), *dh2 = st->at<T>(st->plan.dh2);
+    T *dx1 = st->at<T>(st->plan.dx1), *da = st->at<T>(st->plan.da), *dqkv = st->at<T>(st->plan.dqkv);
+    T *dh = st->at<T>(st->plan.dh);
+    float *mean1 = st->at<float>(st->plan.mean1), *rstd1 = st->at<float>(st->plan.rstd1);
+    float *mean2 = st->at<float>(st->plan.mean2), *rstd2 = st->at<float>(st->plan.rstd2);
+    float *lse = st->at<float>(st->plan.lse), *delta = st->at<float>(st->plan.delta);
+    float *partial = st->at<float>(st->plan.partial);
+    const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
+
+    auto wgrad = [&](const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off) {
+        GemmParams<T> g{};
+        g.A = X; g.lda = in; g.B = dY; g.ldb = out; g.M = in; g.N = out; g.K = t;
+        g.outf = gbuf + w_off; g.ldc = out; g.beta = beta;
+        gemm<T>(g, false, false, EPI_ACCUM_F32, s);
+        launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, out, beta, gbuf + b_off, nullptr, partial, s);
+    };
+    auto dgrad = [&](const T *dY, int out, size_t w_off, int in, T *dX, Epilogue e, const T *aux) {
+        GemmParams<T> g{};
+        g.A = dY; g.lda = out; g.B = pw + w_off; g.ldb = out; g.M = t; g.N = in; g.K = out;
+        g.out = dX; g.ldc = in; g.aux = aux;
+        gemm<T>(g, true, true, e, s);
+    };
+
+    // y = x1 + gelu(u) W2 + b2
+    wgrad(gl, f, dy, d, o.w_2, o.b_2);
+    dgrad(dy, d, o.w_2, f, du, EPI_MUL_DGELU, u);            // du = (dy W2^T) * gelu'(u)
+    // u = h2 W1 + b1
+    wgrad(h2, d, du, f, o.w_1, o.b_1);
+    dgrad(du, f, o.w_1, d, dh2, EPI_STORE, nullptr);
+    // h2 = LN2(x1); dx1 = dy + LN2'(dh2)
+    launch_colsum<T>(dh2, x1, mean2, rstd2, t, d, d, beta, gbuf + o.ln2_b, gbuf + o.ln2_g, partial, s);
+    launch_layernorm_bwd_dx<T>(dh2, x1, mean2, rstd2, pf + o.ln2_g, dy, dx1, t, d, s);
+    // x1 = x + a Wo + bo
+    wgrad(a, d, dx1, d, o.w_o, o.b_o);
+    dgrad(dx1, d, o.w_o, d, da, EPI_STORE, nullptr);
+    if constexpr (std::is_same<T, float>::value) launch_attn_bwd_simple<float>(qkv, a, lse, da, dqkv, delta, ash, s);
+    else launch_attn_bwd_bf16(qkv, a, lse, da, dqkv, delta, ash, s);
+    // qkv = h Wqkv + bqkv
+    wgrad(h, d, dqkv, 3 * d, o.w_qkv, o.b_qkv);
+    dgrad(dqkv, 3 * d, o.w_qkv, d, dh, EPI_STORE, nullptr);
+    // h = LN1(x); dx = dx1 + LN1'(dh)
+    launch_colsum<T>(dh, x_in, mean1, rstd1, t, d, d, beta, gbuf + o.ln1_b, gbuf + o.ln1_g, partial, s);
+    launch_layernorm_bwd_dx<T>(dh, x_in, mean1, rstd1, pf + o.ln1_g, dx1, dy, t, d, s);
+}
+
+void adam_layer(lga_stack *st, int l, const lga_adam &hp) {
+    launch_adam(st->w(l), st->m(l), st->v(l), st->grad(l), st->cfg.dtype == LGA_BF16 ? st->w16(l) : nullptr, st->P,
+                hp.lr, hp.beta1, hp.beta2, hp.eps, hp.step, st->stream);
+}
+
+int check_adam(const lga_adam *a) {
+    if (a->step < 1) return fail(LGA_ERR_STATE, "Adam step t must be >= 1");
+    if (!(a->beta1 >= 0.f && a->beta1 < 1.f && a->beta2 >= 0.f && a->beta2 < 1.f))
+        return fail(LGA_ERR_ARG, "Adam betas must lie in [0, 1)");
+    return LGA_OK;
+}
+
+int finish(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(LGA_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+    return LGA_OK;
+}
+
+template <class T> int forward_layered_t(lga_stack *st, const void *x, void *y) {
+    const lga_config &c = st->cfg;
+    const size_t act_bytes = st->T * c.d_model * sizeof(T);
+    LGA_HIP(hipMemcpyAsync(st->ckpt(0), x, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    const int groups = c.n_micro / c.group;
+    const size_t gstride = st->t * c.d_model;
+    for (int l = 0; l < c.n_layers; ++l) {                 // layers outside ...
+        const T *in = reinterpret_cast<const T *>(st->ckpt(l));
+        T *out = reinterpret_cast<T *>(st->ckpt(l + 1));
+        for (int gi = 0; gi < groups; ++gi)                 // ... micro-batches inside
+            layer_forward<T>(st, l, in + gi * gstride, out + gi * gstride);
+    }
+    if (y) LGA_HIP(hipMemcpyAsync(y, st->ckpt(c.n_layers), act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    return finish("lga_forward_layered");
+}
+
+template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *dx, const lga_adam *fused) {
+    const lga_config &c = st->cfg;
+    const size_t act_bytes = st->T * c.d_model * sizeof(T);
+    T *dact = st->at<T>(st->plan.dact);
+    LGA_HIP(hipMemcpyAsync(dact, dy, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    const int groups = c.n_micro / c.group;
+    const size_t gstride = st->t * c.d_model;
+    for (int l = c.n_layers - 1; l >= 0; --l) {
+        const T *in = reinterpret_cast<const T *>(st->ckpt(l));
+        float *gbuf = st->grad(l);
+        st->grad_owner[st->grad_slot(l)] = -1;
+        for (int gi = 0; gi < groups; ++gi) {
+            layer_forward<T>(st, l, in + gi * gstride, nullptr);                       // recompute
+            layer_backward<T>(st, l, in + gi * gstride, dact + gi * gstride, gbuf, gi == 0 ? 0.f : 1.f);
+        }
+        st->grad_owner[st->grad_slot(l)] = l;
+        if (fused) adam_layer(st, l, *fused);              // update as soon as the layer's gradient is complete
+    }
+    if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    if (fused) st->have_forward = false;                    // checkpoints no longer match the weights
+    return finish("lga_backward_layered");
+}
+
+template <class T>
+int step_mbmajor_t(lga_stack *st, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam) {
+    const lga_config &c = st->cfg;
+    const size_t act_bytes = st->T * c.d_model * sizeof(T);
+    T *dact = st->at<T>(st->plan.dact);
+    LGA_HIP(hipMemcpyAsync(st->ckpt(0), x, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    LGA_HIP(hipMemcpyAsync(dact, dy, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    const size_t gstride = st->t * c.d_model;               // group == 1: one micro-batch
+    for (int l = 0; l < c.n_layers; ++l) st->grad_owner[l] = -1;
+    for (int mu = 0; mu < c.n_micro; ++mu) {                // micro-batches outside ...
+        for (int l = 0; l < c.n_layers; ++l)                // ... layers inside
+            layer_forward<T>(st, l, reinterpret_cast<const T *>(st->ckpt(l)) + mu * gstride,
+                             reinterpret_cast<T *>(st->ckpt(l + 1)) + mu * gstride);
+        for (int l = c.n_layers - 1; l >= 0; --l) {
+            const T *in = reinterpret_cast<const T *>(st->ckpt(l)) + mu * gstride;
+            layer_forward<T>(st, l, in, nullptr);
+            layer_backward<T>(st, l, in, dact + mu * gstride, st->grad(l), mu == 0 ? 0.f : 1.f);
+        }
+    }
+    for (int l = 0; l < c.n_layers; ++l) st->grad_owner[l] = l;
+    if (y) LGA_HIP(hipMemcpyAsync(y, st->ckpt(c.n_layers), act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    if (adam)
+        for (int l = 0; l < c.n_layers; ++l) adam_layer(st, l, *adam);
+    st->have_forward = (adam == nullptr);
+    return finish("lga_step_mbmajor");
+}
+
+int check_layer(const lga_stack *st, int32_t layer) {
+    if (!st) return fail(LGA_ERR_ARG, "stack is NULL");
+    if (layer < 0 || layer >= st->cfg.n_layers) return fail(LGA_ERR_ARG, "layer index out of range");
+    return LGA_OK;
+}
+
+}  // namespace
+
+// ==============================================================================================
+extern "C" {
+
+const char *lga_last_error(void) { return g_last_error.c_str(); }
+
+int lga_params_per_layer(const lga_config *cfg, uint64_t *count) {
+    if (!cfg || !count) return fail(LGA_ERR_ARG, "NULL argument");
+    if (cfg->d_model < 1 || cfg->d_ff < 1) return fail(LGA_ERR_SHAPE, "d_model and d_ff must be >= 1");
+    *count = make_layout(cfg->d_model, cfg->d_ff).total;
+    return LGA_OK;
+}
+
+int lga_arena_bytes(const lga_config *cfg, uint64_t *bytes) {
+    if (!bytes) return fail(LGA_ERR_ARG, "NULL argument");
+    if (int rc = validate_config(cfg)) return rc;
+    *bytes = make_plan(*cfg).total;
+    return LGA_OK;
+}
+
+int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_bytes, uint64_t *grad_bytes,
+                      double *flops) {
+    if (int rc = validate_config(cfg)) return rc;
+    if (order != LGA_ORDER_LAYERED && order != LGA_ORDER_MICROBATCH_MAJOR) return fail(LGA_ERR_ARG, "bad order");
+    const LayerLayout lay = make_layout(cfg->d_model, cfg->d_ff);
+    const uint64_t P = lay.total, Pm = lay.matrices, df = (uint64_t)cfg->d_model * cfg->d_ff;
+    const uint64_t L = cfg->n_layers;
+    const uint64_t groups = order == LGA_ORDER_LAYERED ? cfg->n_micro / cfg->group : cfg->n_micro;
+    const uint64_t wsz = cfg->dtype == LGA_BF16 ? 2 : 4;
+    // Adam: read w, m, v (12 B), write w, m, v (12 B) and the 16-bit copy; per group the GEMM families
+    // read the matrices: forward all four, recompute all but W_2, input gradient all four.
+    const uint64_t adam_param = 24 * P + (cfg->dtype == LGA_BF16 ? 2 * P : 0);
+    const uint64_t per_group_param = wsz * (3 * Pm - df);
+    if (param_bytes) *param_bytes = L * (adam_param + groups * per_group_param);
+    // gradient buffer: first group writes (4 B), later groups read-modify-write (8 B); Adam reads (4 B)
+    if (grad_bytes) *grad_bytes = L * (4 * P + 4 * P + (groups - 1) * 8 * P);
+    if (flops) {
+        const double tokens = (double)cfg->n_micro * cfg->micro_batch * cfg->seq_len;
+        const double gemm = 2.0 * tokens * (double)L * (4.0 * Pm - df);                 // fwd, recompute - W_2, dX, dW
+        const double seqs = (double)cfg->n_micro * cfg->micro_batch;
+        // causal products executed: forward 2, recompute 2, dQ kernel 3, dK/dV kernel 4, each s^2 d_m flop
+        const double attn = 11.0 * seqs * (double)L * (double)cfg->seq_len * cfg->seq_len * cfg->d_model;
+        *flops = gemm + attn;
+    }
+    return LGA_OK;
+}
+
+int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **out) {
+    if (!out) return fail(LGA_ERR_ARG, "out is NULL");
+    *out = nullptr;
+    if (int rc = validate_config(cfg)) return rc;
+    lga_stack *st = new (std::nothrow) lga_stack();
+    if (!st) return fail(LGA_ERR_OOM, "host allocation failed");
+    st->cfg = *cfg;
+    st->lay = make_layout(cfg->d_model, cfg->d_ff);
+    st->plan = make_plan(*cfg);
+    st->stream = reinterpret_cast<hipStream_t>(cfg->stream);
+    st->P = st->lay.total;
+    st->T = (size_t)cfg->n_micro * cfg->micro_batch * cfg->seq_len;
+    st->t = (size_t)cfg->group * cfg->micro_batch * cfg->seq_len;
+    st->have_forward = false;
+    st->grad_owner.assign(cfg->retain_grads ? cfg->n_layers : 1, -1);
+    st->arena = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->arena), st->plan.total);
+    if (e != hipSuccess) {
+        std::string msg = std::string("hipMalloc of ") + std::to_string(st->plan.total) + " bytes: " + hipGetErrorString(e);
+        delete st;
+        (void)hipGetLastError();
+        return fail(e == hipErrorOutOfMemory ? LGA_ERR_OOM : LGA_ERR_HIP, msg);
+    }
+    auto bail = [&](hipError_t err, const char *what) {
+        std::string msg = std::string(what) + ": " + hipGetErrorString(err);
+        (void)hipFree(st->arena);
+        delete st;
+        return fail(LGA_ERR_HIP, msg);
+    };
+    const size_t LP = (size_t)cfg->n_layers * st->P;
+    if ((e = hipMemsetAsync(st->m(0), 0, LP * 4, st->stream)) != hipSuccess) return bail(e, "clear m");
+    if ((e = hipMemsetAsync(st->v(0), 0, LP * 4, st->stream)) != hipSuccess) return bail(e, "clear v");
+    if (host_params) {
+        if ((e = hipMemcpyAsync(st->w(0), host_params, LP * 4, hipMemcpyHostToDevice, st->stream)) != hipSuccess)
+            return bail(e, "copy parameters");
+    } else {
+        if ((e = hipMemsetAsync(st->w(0), 0, LP * 4, st->stream)) != hipSuccess) return bail(e, "clear w");
+        const size_t d = cfg->d_model, f = cfg->d_ff;
+        for (int l = 0; l < cfg->n_layers; ++l) {
+            float *w = st->w(l);
+            const uint64_t seed = 0x5EEDull + 16 * (uint64_t)l;
+            launch_fill_const(w + st->lay.ln1_g, d, 1.0f, st->stream);
+            launch_fill_const(w + st->lay.ln2_g, d, 1.0f, st->stream);
+            launch_fill_normal(w + st->lay.w_qkv, d * 3 * d, 0.02f, seed + 0, st->stream);
+            launch_fill_normal(w + st->lay.w_o, d * d, 0.02f, seed + 1, st->stream);
+            launch_fill_normal(w + st->lay.w_1, d * f, 0.02f, seed + 2, st->stream);
+            launch_fill_normal(w + st->lay.w_2, f * d, 0.02f, seed + 3, st->stream);
+        }
+    }
+    if (cfg->dtype == LGA_BF16) launch_cast_f32_to_bf16(st->w(0), st->w16(0), LP, st->stream);   // restore
+    if ((e = hipStreamSynchronize(st->stream)) != hipSuccess) return bail(e, "init sync");
+    if ((e = hipGetLastError()) != hipSuccess) return bail(e, "init kernels");
+    *out = st;
+    return LGA_OK;
+}
+
+void lga_destroy_stack(lga_stack *st) {
+    if (!st) return;
+    (void)hipStreamSynchronize(st->stream);
+    if (st->arena) (void)hipFree(st->arena);
+    delete st;
+}
+
+int lga_forward_layered(lga_stack *st, const void *x, void *y) {
+    if (!st || !x) return fail(LGA_ERR_ARG, "NULL argument");
+    int rc = st->cfg.dtype == LGA_BF16 ? forward_layered_t<bf16>(st, x, y) : forward_layered_t<float>(st, x, y);
+    if (rc == LGA_OK) st->have_forward = true;
+    return rc;
+}
+
+int lga_backward_layered(lga_stack *st, const void *dy, void *dx, const lga_adam *fused) {
+    if (!st || !dy) return fail(LGA_ERR_ARG, "NULL argument");
+    if (!st->have_forward) return fail(LGA_ERR_STATE, "lga_backward_layered needs a preceding forward pass");
+    if (!fused && !st->cfg.retain_grads && st->cfg.n_layers > 1)
+        return fail(LGA_ERR_STATE, "unfused backward with a single gradient buffer would lose all but one layer's gradient");
+    if (fused)
+        if (int rc = check_adam(fused)) return rc;
+    return st->cfg.dtype == LGA_BF16 ? backward_layered_t<bf16>(st, dy, dx, fused)
+                                     : backward_layered_t<float>(st, dy, dx, fused);
+}
+
+int lga_step_mbmajor(lga_stack *st, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam) {
+    if (!st || !x || !dy) return fail(LGA_ERR_ARG, "NULL argument");
+    if (!st->cfg.retain_grads) return fail(LGA_ERR_STATE, "micro-batch-major order needs retain_grads = 1");
+    if (st->cfg.group != 1) return fail(LGA_ERR_STATE, "micro-batch-major order needs group = 1");
+    if (adam)
+        if (int rc = check_adam(adam)) return rc;
+    return st->cfg.dtype == LGA_BF16 ? step_mbmajor_t<bf16>(st, x, dy, y, dx, adam)
+                                     : step_mbmajor_t<float>(st, x, dy, y, dx, adam);
+}
+
+int lga_adam_step_layer(lga_stack *st, int32_t layer, const lga_adam *adam) {
+    if (int rc = check_layer(st, layer)) return rc;
+    if (!adam) return fail(LGA_ERR_ARG, "adam is NULL");
+    if (int rc = check_adam(adam)) return rc;
+    if (st->grad_owner[st->grad_slot(layer)] != layer)
+        return fail(LGA_ERR_STATE, "no accumulated gradient is available for this layer");
+    adam_layer(st, layer, *adam);
+    st->have_forward = false;
+    return finish("lga_adam_step_layer");
+}
+
+int lga_grads(lga_stack *st, int32_t layer, const float **dev_ptr, size_t *count) {
+    if (int rc = check_layer(st, layer)) return rc;
+    if (!dev_ptr) return fail(LGA_ERR_ARG, "dev_ptr is NULL");
+    if (st->grad_owner[st->grad_slot(layer)] != layer)
+        return fail(LGA_ERR_STATE, "no accumulated gradient is available for this layer");
+    *dev_ptr = st->grad(layer);
+    if (count) *count = st->P;
+    return LGA_OK;
+}
+
+int lga_params(lga_stack *st, int32_t layer, const float **dev_master, size_t *count) {
+    if (int rc = check_layer(st, layer)) return rc;
+    if (!dev_master) return fail(LGA_ERR_ARG, "dev_master is NULL");
+    *dev_master = st->w(layer);
+    if (count) *count = st->P;
+    return LGA_OK;
+}
+
+int lga_moments(lga_stack *st, int32_t layer, float **dev_m, float **dev_v, size_t *count) {
+    if (int rc = check_layer(st, layer)) return rc;
+    if (dev_m) *dev_m = st->m(layer);
+    if (dev_v) *dev_v = st->v(layer);
+    if (count) *count = st->P;
+    return LGA_OK;
+}
+
+int lga_checkpoint(lga_stack *st, int32_t boundary, const void **dev_ptr, size_t *bytes) {
+    if (!st || !dev_ptr) return fail(LGA_ERR_ARG, "NULL argument");
+    if (boundary < 0 || boundary > st->cfg.n_layers) return fail(LGA_ERR_ARG, "boundary index out of range");
+    *dev_ptr = st->ckpt(boundary);
+    if (bytes) *bytes = st->T * st->cfg.d_model * st->esz();
+    return LGA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+"""Plumbing shared by the GPU parity tests: move seeded inputs to the device, run the C-ABI
+library through its binding, bring results back as float64 numpy arrays."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import synth_inputs as S
+from oracle import lga_oracle as O
+from paper_2106_02679_amd import binding as B
+
+
+def to_dev(a: np.ndarray, dtype: int) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype == B.LGA_BF16 else t
+
+
+def empty_dev(shape, dtype: int) -> torch.Tensor:
+    return torch.empty(shape, device="cuda", dtype=torch.bfloat16 if dtype == B.LGA_BF16 else torch.float32)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def rel_err(a: np.ndarray, ref: np.ndarray) -> float:
+    """Relative Frobenius error ||a - ref|| / ||ref|| (absolute norm if ref is all zero)."""
+    a = np.asarray(a, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    den = np.linalg.norm(ref.ravel())
+    num = np.linalg.norm((a - ref).ravel())
+    return float(num / den) if den > 0 else float(num)
+
+
+def dtype_code(w: S.Workload) -> int:
+    return B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
+
+
+def oracle_shape(w: S.Workload) -> O.StackShape:
+    return O.StackShape(d_l=w.n_layers, d_m=w.d_model, d_a=w.n_heads, d_I=w.d_ff, d_s=w.seq_len,
+                        b_mu=w.micro_batch, n_mu=w.n_micro)
+
+
+def adam_struct(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=1) -> B.lga_adam:
+    return B.lga_adam(lr, beta1, beta2, eps, step)
+
+
+def oracle_adam(a: B.lga_adam) -> O.AdamHyper:
+    """The oracle gets the hyper-parameters as they cross the ABI: rounded to float32."""
+    return O.AdamHyper(lr=float(np.float32(a.lr)), beta1=float(np.float32(a.beta1)), beta2=float(np.float32(a.beta2)),
+                       eps=float(np.float32(a.eps)), step=int(a.step))
+
+
+def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layered", adam=None, fused=True,
+                 want_ckpt=True):
+    """One training step through the C ABI.  Returns a dict of float64 numpy results."""
+    dt = dtype_code(w)
+    cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
+                        group=group, retain_grads=retain)
+    st = B.Stack(cfg, np.concatenate(params))
+    P = B.params_per_layer(cfg)
+    xd, Gd = to_dev(x, dt), to_dev(G, dt)
+    yd, dxd = empty_dev(x.shape, dt), empty_dev(x.shape, dt)
+    out = {"grads": [None] * w.n_layers}
+    np_dt = "float32"
+    try:
+        if order == "layered":
+            st.forward_layered(xd.data_ptr(), yd.data_ptr())
+            st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam if (adam is not None and fused) else None)
+        else:
+            st.step_mbmajor(xd.data_ptr(), Gd.data_ptr(), yd.data_ptr(), dxd.data_ptr(), adam)
+        torch.cuda.synchronize()
+        for l in range(w.n_layers):
+            try:
+                ptr, n = st.grads(l)
+                out["grads"][l] = B.read_device(ptr, n, np_dt).astype(np.float64)
+            except B.LgaError:
+                out["grads"][l] = None
+        if adam is not None and order == "layered" and not fused:
+            for l in range(w.n_layers):
+                st.adam_step_layer(l, adam)
+            torch.cuda.synchronize()
+        out["y"] = to_host(yd)
+        out["dx"] = to_host(dxd)
+        if want_ckpt:
+            n_act = int(np.prod(x.shape))
+            ck = []
+            for bnd in range(w.n_layers + 1):
+                ptr, nbytes = st.checkpoint(bnd)
+                if dt == B.LGA_BF16:
+                    bits = B.read_device(ptr, n_act, "uint16")
+                    ck.append(S.from_bf16_bits(bits).astype(np.float64).reshape(x.shape))
+                else:
+                    ck.append(B.read_device(ptr, n_act, "float32").astype(np.float64).reshape(x.shape))
+            out["boundaries"] = np.stack(ck)
+        out["params"], out["m"], out["v"] = [], [], []
+        for l in range(w.n_layers):
+            ptr, n = st.params(l)
+            out["params"].append(B.read_device(ptr, n).astype(np.float64))
+            mp, vp, n = st.moments(l)
+            out["m"].append(B.read_device(mp, n).astype(np.float64))
+            out["v"].append(B.read_device(vp, n).astype(np.float64))
+        assert n == P
+    finally:
+        st.close()
+    return out

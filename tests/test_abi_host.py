@@ -1,0 +1,126 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the headers declare,
+and its host-side logic (validation, sizing, traffic model) behaves.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2106_02679_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(lga_\w+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert {"lga_init_stack", "lga_forward_layered", "lga_backward_layered", "lga_adam_step_layer", "lga_grads"} <= names
+    for name in names:
+        assert hasattr(B.lib, name), name
+    assert names == set(B.SIGNATURES), names ^ set(B.SIGNATURES)
+
+
+def cfg(**kw):
+    base = dict(n_layers=2, d_model=64, n_heads=4, d_ff=256, seq_len=32, micro_batch=2, n_micro=4, dtype=B.LGA_FP32,
+                group=1, retain_grads=0)
+    base.update(kw)
+    return B.make_config(**base)
+
+
+def test_parameter_count_follows_table_b1_closed_form():
+    # Table B.1: p = 12 x^5 + 13 x^3 with d_m = x^2, d_l = x  =>  p_l = 12 d_m^2 + 13 d_m ; X_2 has 488
+    assert 2 * B.params_per_layer(cfg(d_model=4, n_heads=1, d_ff=16)) == 488
+    for d in (64, 768, 12288, 25600):
+        assert B.params_per_layer(cfg(d_model=d, n_heads=d // 64 if d > 64 else 4, d_ff=4 * d)) == 12 * d * d + 13 * d
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_layers=0), B.LGA_ERR_SHAPE), (dict(d_model=65), B.LGA_ERR_SHAPE), (dict(group=3), B.LGA_ERR_SHAPE),
+    (dict(group=0), B.LGA_ERR_SHAPE), (dict(group=8), B.LGA_ERR_SHAPE), (dict(dtype=7), B.LGA_ERR_ARG),
+    (dict(dtype=B.LGA_BF16), B.LGA_ERR_SHAPE),                      # d_h = 16 is not a multiple of 32
+    (dict(dtype=B.LGA_BF16, d_model=128, n_heads=4, d_ff=500), B.LGA_ERR_SHAPE),
+    (dict(seq_len=0), B.LGA_ERR_SHAPE),
+])
+def test_bad_configurations_are_refused_on_the_host(kw, code):
+    out = C.c_uint64()
+    assert B.lib.lga_arena_bytes(C.byref(cfg(**kw)), C.byref(out)) == code
+    assert B.last_error()
+    h = C.c_void_p()
+    assert B.lib.lga_init_stack(C.byref(cfg(**kw)), None, C.byref(h)) == code
+    assert not h.value
+
+
+def test_null_arguments():
+    h = C.c_void_p()
+    assert B.lib.lga_init_stack(None, None, C.byref(h)) == B.LGA_ERR_ARG
+    assert B.lib.lga_init_stack(C.byref(cfg()), None, None) == B.LGA_ERR_ARG
+    assert B.lib.lga_forward_layered(None, None, None) == B.LGA_ERR_ARG
+    assert B.lib.lga_grads(None, 0, None, None) == B.LGA_ERR_ARG
+    B.lib.lga_destroy_stack(None)      # must be a no-op
+
+
+def test_arena_holds_state_checkpoints_and_scratch():
+    c = cfg(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
+            dtype=B.LGA_BF16, group=2, retain_grads=0)
+    P = 12 * 12288 ** 2 + 13 * 12288
+    T = 32 * 2048
+    state = 12 * 4 * P                              # appendix C.3: 12 p bytes of fp32 parameters and moments
+    one_grad_buffer = 4 * P
+    copies16 = 2 * 4 * P
+    ckpts = 2 * 5 * T * 12288 + 2 * T * 12288       # L+1 boundaries and the running activation gradient
+    total = B.arena_bytes(c)
+    assert total > state + one_grad_buffer + copies16 + ckpts
+    assert total < 1.15 * (state + one_grad_buffer + copies16 + ckpts)      # scratch is a small addition
+    assert total < 288e9
+    # keeping every layer's gradient costs exactly (L-1) more buffers
+    c2 = cfg(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
+             dtype=B.LGA_BF16, group=2, retain_grads=1)
+    assert abs((B.arena_bytes(c2) - total) - 3 * 4 * P) < 4096
+
+
+def test_traffic_model_layered_is_independent_of_micro_batch_count_when_fully_grouped():
+    def model(n, g, order):
+        c = cfg(n_layers=1, d_model=1024, n_heads=8, d_ff=4096, seq_len=128, micro_batch=1, n_micro=n,
+                dtype=B.LGA_BF16, group=g, retain_grads=1)
+        return B.traffic_model(c, order)
+    p8, g8, f8 = model(8, 8, B.LGA_ORDER_LAYERED)
+    p32, g32, f32_ = model(32, 32, B.LGA_ORDER_LAYERED)
+    assert p8 == p32 and g8 == g32                    # bytes do not grow with n
+    assert abs(f32_ / f8 - 4.0) < 1e-12               # flops do
+    pm, gm, fm = model(32, 1, B.LGA_ORDER_MICROBATCH_MAJOR)
+    P = 12 * 1024 ** 2 + 13 * 1024
+    Pm = 12 * 1024 ** 2
+    assert gm == 8 * P + 31 * 8 * P                   # first write + Adam read, then read-modify-write per micro-batch
+    assert g32 == 8 * P
+    assert pm - p32 == 31 * 2 * (3 * Pm - 1024 * 4096)
+    assert fm == f32_
+
+
+def test_flop_model_against_the_papers_count():
+    # Appendix C.1: 8 flop per token per parameter with full recompute.  The library skips the second
+    # feed-forward GEMM in recompute (its output is not needed), i.e. executes 8 - 2 * (d d_I / p_matrices).
+    c = cfg(n_layers=3, d_model=1024, n_heads=8, d_ff=4096, seq_len=64, micro_batch=2, n_micro=4, dtype=B.LGA_BF16)
+    _, _, flops = B.traffic_model(c, B.LGA_ORDER_LAYERED)
+    tokens, Pm = 4 * 2 * 64, 12 * 1024 ** 2
+    gemm = 2.0 * tokens * 3 * (4 * Pm - 1024 * 4096)
+    attn = 11.0 * (4 * 2) * 3 * 64 * 64 * 1024
+    assert abs(flops - (gemm + attn)) / flops < 1e-12
+    assert abs(gemm / (8.0 * tokens * 3 * Pm) - (1 - 1 / 12)) < 1e-12
+
+
+def test_init_without_a_gpu_reports_a_hip_error_instead_of_crashing():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    h = C.c_void_p()
+    assert B.lib.lga_init_stack(C.byref(cfg()), None, C.byref(h)) == B.LGA_ERR_HIP
+    assert "hipMalloc" in B.last_error()

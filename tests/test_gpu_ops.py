@@ -1,0 +1,281 @@
+"""GPU parity, kernel by kernel: each HIP kernel is called through the C ABI (lga_ops.h) on small,
+ragged, multi-tile shapes and compared element-wise with the fp64 oracle's corresponding step.
+
+Tolerances (relative Frobenius norm of the error):
+  fp32 storage: 1e-5 (the gate the build is held to in fp32 mode).
+  bf16 storage: inputs are bf16-exact and shared with the oracle, products accumulate in fp32, so the
+  error is the rounding of the stored result, unit roundoff 2^-8 => about 2^-9/sqrt(3)*sqrt(2) ~ 1.6e-3
+  rms per element; 4e-3 leaves a factor 2.5.  Attention rounds P (and dS) to bf16 before its second
+  product, adding a similar term per product: 1e-2 forward, 2e-2 backward (the build's bf16 gate).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import lga_oracle as O
+import synth_inputs as S
+from paper_2106_02679_amd import binding as B
+from gpu_helpers import to_dev, empty_dev, to_host, rel_err
+
+F32, BF16 = B.LGA_FP32, B.LGA_BF16
+TOL_OUT = {F32: 1e-5, BF16: 4e-3}
+
+
+def rnd(rng, shape, dt, scale=1.0):
+    a = (scale * rng.standard_normal(shape)).astype(np.float32)
+    return S.round_to_bf16(a) if dt == BF16 else a
+
+
+def fvec(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def gemm_oracle(A, Bm, akm, bkm):
+    a = A if akm else A.T           # -> [M, K]
+    b = Bm.T if bkm else Bm         # -> [K, N]
+    return a.astype(np.float64) @ b.astype(np.float64)
+
+
+GEMM_CASES = [
+    # dtype, a_kmajor, b_kmajor, epilogue, M, N, K
+    (F32, 1, 0, B.LGA_EPI_BIAS, 70, 45, 33),
+    (F32, 1, 0, B.LGA_EPI_BIAS_RESID, 130, 64, 17),
+    (F32, 1, 0, B.LGA_EPI_BIAS_GELU, 65, 129, 64),
+    (F32, 1, 1, B.LGA_EPI_STORE, 67, 50, 40),
+    (F32, 1, 1, B.LGA_EPI_MUL_DGELU, 64, 64, 70),
+    (F32, 0, 0, B.LGA_EPI_ACCUM_F32, 45, 70, 100),
+    (BF16, 1, 0, B.LGA_EPI_BIAS, 300, 392, 200),
+    (BF16, 1, 0, B.LGA_EPI_STORE, 128, 128, 64),
+    (BF16, 1, 0, B.LGA_EPI_BIAS_RESID, 257, 136, 72),
+    (BF16, 1, 0, B.LGA_EPI_BIAS_GELU, 190, 264, 128),
+    (BF16, 1, 1, B.LGA_EPI_STORE, 300, 200, 392),
+    (BF16, 1, 1, B.LGA_EPI_MUL_DGELU, 131, 256, 136),
+    (BF16, 0, 0, B.LGA_EPI_ACCUM_F32, 200, 392, 300),
+    (BF16, 0, 0, B.LGA_EPI_STORE, 136, 72, 1000),
+    # >= 512 tiles of 256x256: the large-tile kernel, with ragged edges in m, n and k
+    (BF16, 1, 0, B.LGA_EPI_BIAS, 4100, 8200, 136),
+    (BF16, 1, 1, B.LGA_EPI_STORE, 4100, 8200, 72),
+    (BF16, 0, 0, B.LGA_EPI_ACCUM_F32, 4104, 8200, 200),
+]
+
+
+@pytest.mark.parametrize("case", GEMM_CASES, ids=lambda c: "-".join(map(str, c)))
+def test_gemm_against_oracle_matmul(case):
+    dt, akm, bkm, epi, M, N, K = case
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    pad = 8      # leading dimensions larger than the logical width: exercises pitches
+    lda = (K if akm else M) + pad
+    ldb = (K if bkm else N) + pad
+    ldc = N + pad
+    A = rnd(rng, (M if akm else K, lda), dt)
+    Bm = rnd(rng, (N if bkm else K, ldb), dt)
+    Al = A[:, :K] if akm else A[:, :M]
+    Bl = Bm[:, :K] if bkm else Bm[:, :N]
+    acc = gemm_oracle(Al, Bl, akm, bkm)
+    bias = rng.standard_normal(N).astype(np.float32)
+    aux = rnd(rng, (M, ldc), dt)
+    old = rng.standard_normal((M, ldc)).astype(np.float32)
+    beta = 1.0 if epi == B.LGA_EPI_ACCUM_F32 else 0.0
+    Ad, Bd, auxd, biasd = to_dev(A, dt), to_dev(Bm, dt), to_dev(aux, dt), fvec(bias)
+    out, out2 = empty_dev((M, ldc), dt), empty_dev((M, ldc), dt)
+    out.zero_(); out2.zero_()
+    outf = fvec(old)
+    B.check(B.lib.lga_op_gemm(dt, akm, bkm, epi, M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, out.data_ptr(),
+                              out2.data_ptr(), outf.data_ptr(), ldc, biasd.data_ptr(), auxd.data_ptr(), beta, None))
+    torch.cuda.synchronize()
+    a64 = aux[:, :N].astype(np.float64)
+    tol = TOL_OUT[dt]
+    if epi == B.LGA_EPI_STORE:
+        assert rel_err(to_host(out)[:, :N], acc) < tol
+    elif epi == B.LGA_EPI_BIAS:
+        assert rel_err(to_host(out)[:, :N], acc + bias) < tol
+    elif epi == B.LGA_EPI_BIAS_RESID:
+        assert rel_err(to_host(out)[:, :N], acc + bias + a64) < tol
+    elif epi == B.LGA_EPI_BIAS_GELU:
+        u = acc + bias
+        assert rel_err(to_host(out2)[:, :N], u) < tol
+        assert rel_err(to_host(out)[:, :N], O.gelu(u)) < tol
+    elif epi == B.LGA_EPI_MUL_DGELU:
+        assert rel_err(to_host(out)[:, :N], acc * O.gelu_grad(a64)) < tol
+    else:
+        got = outf.cpu().numpy().astype(np.float64)
+        assert rel_err(got[:, :N], old[:, :N].astype(np.float64) + acc) < 1e-5
+        assert np.array_equal(got[:, N:], old[:, N:].astype(np.float64))      # padding untouched
+        # beta = 0 must overwrite whatever was there (even NaN)
+        outf.fill_(float("nan"))
+        B.check(B.lib.lga_op_gemm(dt, akm, bkm, epi, M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, None, None,
+                                  outf.data_ptr(), ldc, None, None, 0.0, None))
+        torch.cuda.synchronize()
+        assert rel_err(outf.cpu().numpy().astype(np.float64)[:, :N], acc) < 1e-5
+    if epi != B.LGA_EPI_ACCUM_F32:
+        assert np.all(to_host(out)[:, N:] == 0)                                # padding untouched
+
+
+def test_gemm_empty_and_rejected_arguments():
+    t = torch.zeros(64, device="cuda")
+    # M = 0: nothing to do, no launch
+    B.check(B.lib.lga_op_gemm(F32, 1, 0, B.LGA_EPI_STORE, 0, 8, 8, t.data_ptr(), 8, t.data_ptr(), 8, t.data_ptr(), None,
+                              None, 8, None, None, 0.0, None))
+    # bf16 with N not a multiple of 8 is refused on the host
+    rc = B.lib.lga_op_gemm(BF16, 1, 0, B.LGA_EPI_STORE, 8, 12, 8, t.data_ptr(), 8, t.data_ptr(), 16, t.data_ptr(), None,
+                           None, 16, None, None, 0.0, None)
+    assert rc == B.LGA_ERR_SHAPE
+    rc = B.lib.lga_op_gemm(BF16, 0, 1, B.LGA_EPI_STORE, 8, 8, 8, t.data_ptr(), 8, t.data_ptr(), 8, t.data_ptr(), None,
+                           None, 8, None, None, 0.0, None)
+    assert rc == B.LGA_ERR_SHAPE                  # layout pair the layer never uses
+    rc = B.lib.lga_op_gemm(F32, 1, 0, B.LGA_EPI_BIAS, 8, 8, 8, t.data_ptr(), 8, t.data_ptr(), 8, t.data_ptr(), None,
+                           None, 8, None, None, 0.0, None)
+    assert rc == B.LGA_ERR_ARG                    # bias missing
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dt,rows,d", [(F32, 37, 70), (F32, 5, 1), (BF16, 130, 256), (BF16, 33, 1000), (BF16, 3, 12288)])
+def test_layernorm_forward_and_backward(dt, rows, d):
+    rng = np.random.default_rng(rows * 1000 + d)
+    x = rnd(rng, (rows, d), dt, 2.0) + (0.5 if dt == F32 else 0.0)
+    if dt == BF16:
+        x = S.round_to_bf16(x)
+    g = (1 + 0.3 * rng.standard_normal(d)).astype(np.float32)
+    b = (0.2 * rng.standard_normal(d)).astype(np.float32)
+    dy = rnd(rng, (rows, d), dt)
+    resid = rnd(rng, (rows, d), dt)
+    eps = 1e-5
+    y_ref, xhat, rstd = O.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), eps)
+    dx_ref, dg_ref, db_ref = O.layer_norm_backward(dy.astype(np.float64), xhat, rstd, g.astype(np.float64))
+    dx_ref = dx_ref + resid
+    xd, dyd, rd = to_dev(x, dt), to_dev(dy, dt), to_dev(resid, dt)
+    gd, bd = fvec(g), fvec(b)
+    y, dx = empty_dev((rows, d), dt), empty_dev((rows, d), dt)
+    mean, rs = torch.empty(rows, device="cuda"), torch.empty(rows, device="cuda")
+    B.check(B.lib.lga_op_layernorm_fwd(dt, xd.data_ptr(), gd.data_ptr(), bd.data_ptr(), y.data_ptr(), mean.data_ptr(),
+                                       rs.data_ptr(), rows, d, eps, None))
+    old_g = rng.standard_normal(d).astype(np.float32); old_b = rng.standard_normal(d).astype(np.float32)
+    dgd, dbd = fvec(old_g), fvec(old_b)
+    scratch = torch.empty(int(B.lib.lga_op_colsum_scratch_floats(rows, d)), device="cuda")
+    B.check(B.lib.lga_op_layernorm_bwd(dt, dyd.data_ptr(), xd.data_ptr(), mean.data_ptr(), rs.data_ptr(), gd.data_ptr(),
+                                       rd.data_ptr(), dx.data_ptr(), dgd.data_ptr(), dbd.data_ptr(), 1.0,
+                                       scratch.data_ptr(), rows, d, None))
+    torch.cuda.synchronize()
+    tol = TOL_OUT[dt]
+    assert rel_err(to_host(y), y_ref) < tol
+    assert np.abs(mean.cpu().numpy() - x.astype(np.float64).mean(-1)).max() < 1e-5
+    assert rel_err(rs.cpu().numpy(), rstd[:, 0]) < 1e-5
+    assert rel_err(to_host(dx), dx_ref) < tol
+    assert rel_err(dgd.cpu().numpy(), old_g + dg_ref) < 2e-5
+    assert rel_err(dbd.cpu().numpy(), old_b + db_ref) < 2e-5
+
+
+@pytest.mark.parametrize("dt,rows,cols,ld", [(F32, 300, 45, 50), (BF16, 1000, 264, 272), (BF16, 129, 8, 8), (F32, 0, 16, 16)])
+def test_column_sums(dt, rows, cols, ld):
+    rng = np.random.default_rng(rows + cols)
+    a = rnd(rng, (max(rows, 1), ld), dt)[:rows]
+    ad = to_dev(a if rows else np.zeros((1, ld), np.float32), dt)
+    old = rng.standard_normal(cols).astype(np.float32)
+    out = fvec(old)
+    scratch = torch.empty(max(1, int(B.lib.lga_op_colsum_scratch_floats(rows, cols))), device="cuda")
+    B.check(B.lib.lga_op_colsum(dt, ad.data_ptr(), rows, cols, ld, 1.0, out.data_ptr(), scratch.data_ptr(), None))
+    torch.cuda.synchronize()
+    ref = old.astype(np.float64) + a[:, :cols].astype(np.float64).sum(0)
+    assert rel_err(out.cpu().numpy(), ref) < 1e-5
+    B.check(B.lib.lga_op_colsum(dt, ad.data_ptr(), rows, cols, ld, 0.0, out.data_ptr(), scratch.data_ptr(), None))
+    torch.cuda.synchronize()
+    assert rel_err(out.cpu().numpy(), a[:, :cols].astype(np.float64).sum(0)) < 1e-5
+
+
+def attention_reference(qkv, dout, n_seq, s, heads, dh):
+    d = heads * dh
+    t = qkv.astype(np.float64).reshape(n_seq, s, 3, heads, dh)
+    q, k, v = (t[:, :, i].transpose(0, 2, 1, 3) for i in range(3))
+    out, prob = O.causal_attention(q, k, v)
+    scores = (q @ np.swapaxes(k, -1, -2)) / math.sqrt(dh)
+    mask = np.triu(np.ones((s, s), dtype=bool), 1)
+    scores = np.where(mask, -np.inf, scores)
+    mx = scores.max(-1, keepdims=True)
+    lse = (mx + np.log(np.exp(scores - mx).sum(-1, keepdims=True)))[..., 0]
+    do = dout.astype(np.float64).reshape(n_seq, s, heads, dh).transpose(0, 2, 1, 3)
+    dq, dk, dv = O.causal_attention_backward(do, q, k, v, prob)
+    merge = lambda z: z.transpose(0, 2, 1, 3).reshape(n_seq * s, d)
+    return merge(out), lse, np.concatenate([merge(dq), merge(dk), merge(dv)], axis=1)
+
+
+ATTN_CASES = [
+    # dtype, kind, n_seq, s, heads, dh
+    (F32, 0, 2, 37, 3, 16), (F32, 0, 1, 1, 1, 8), (BF16, 0, 2, 70, 2, 32),
+    (BF16, 1, 2, 200, 2, 32), (BF16, 1, 1, 333, 3, 64), (BF16, 1, 2, 256, 2, 128), (BF16, 1, 1, 130, 2, 160),
+    (BF16, 1, 1, 1, 1, 64), (BF16, 1, 3, 64, 1, 96),
+]
+
+
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "-".join(map(str, c)))
+def test_attention_forward_and_backward(case):
+    dt, kind, n_seq, s, heads, dh = case
+    d = heads * dh
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    qkv = rnd(rng, (n_seq * s, 3 * d), dt)
+    dout = rnd(rng, (n_seq * s, d), dt)
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh)
+    qd, dod = to_dev(qkv, dt), to_dev(dout, dt)
+    out, dqkv = empty_dev((n_seq * s, d), dt), empty_dev((n_seq * s, 3 * d), dt)
+    lse = torch.empty(n_seq * heads * s, device="cuda")
+    delta = torch.empty(n_seq * heads * s, device="cuda")
+    B.check(B.lib.lga_op_attention_fwd(dt, kind, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, None))
+    B.check(B.lib.lga_op_attention_bwd(dt, kind, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, None))
+    torch.cuda.synchronize()
+    tol_f, tol_b = (1e-5, 2e-5) if dt == F32 else (1e-2, 2e-2)
+    assert rel_err(to_host(out), out_ref) < tol_f
+    assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < (1e-5 if dt == F32 else 1e-3) * max(1.0, np.abs(lse_ref).max())
+    got = to_host(dqkv)
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < tol_b, name
+
+
+def test_attention_mfma_rejects_unsupported_head_size():
+    t = torch.zeros(4096, device="cuda", dtype=torch.bfloat16)
+    l = torch.zeros(64, device="cuda")
+    rc = B.lib.lga_op_attention_fwd(BF16, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 48, None)
+    assert rc == B.LGA_ERR_SHAPE
+    rc = B.lib.lga_op_attention_fwd(F32, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 64, None)
+    assert rc == B.LGA_ERR_SHAPE
+
+
+@pytest.mark.parametrize("n,with16", [(1003, True), (4096, True), (7, False), (0, False)])
+def test_adam_kernel_against_closed_form(n, with16):
+    rng = np.random.default_rng(n)
+    w = rng.standard_normal(n).astype(np.float32)
+    m = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    v = (0.01 * rng.random(n)).astype(np.float32)
+    g = rng.standard_normal(n).astype(np.float32)
+    hp = B.lga_adam(3e-3, 0.9, 0.999, 1e-8, 7)
+    ohp = O.AdamHyper(lr=float(np.float32(3e-3)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)),
+                      eps=float(np.float32(1e-8)), step=7)
+    w_ref, m_ref, v_ref = O.adam_update(w.astype(np.float64), m.astype(np.float64), v.astype(np.float64),
+                                        g.astype(np.float64), ohp)
+    wd, md, vd, gd = fvec(w), fvec(m), fvec(v), fvec(g)
+    w16 = torch.zeros(max(n, 1), device="cuda", dtype=torch.bfloat16)
+    import ctypes
+    B.check(B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(),
+                              w16.data_ptr() if with16 else None, n, ctypes.byref(hp), None))
+    torch.cuda.synchronize()
+    if n == 0:
+        return
+    assert rel_err(wd.cpu().numpy(), w_ref) < 1e-6
+    assert rel_err(md.cpu().numpy(), m_ref) < 1e-6
+    assert rel_err(vd.cpu().numpy(), v_ref) < 1e-6
+    if with16:
+        assert np.array_equal(to_host(w16)[:n], S.round_to_bf16(wd.cpu().numpy()).astype(np.float64))
+
+
+def test_adam_kernel_hand_worked_values():
+    # same numbers as the oracle's pin: w=0.5 m=0.1 v=0.04 g=-0.2 lr=0.01 b1=0.9 b2=0.99 t=2 -> w'=0.49740139...
+    import ctypes
+    wd, md, vd, gd = fvec([0.5]), fvec([0.1]), fvec([0.04]), fvec([-0.2])
+    hp = B.lga_adam(0.01, 0.9, 0.99, 1e-8, 2)
+    B.check(B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(), None, 1, ctypes.byref(hp), None))
+    torch.cuda.synchronize()
+    assert abs(float(wd[0]) - 0.4974013907589168) < 2e-7
+    assert abs(float(md[0]) - 0.07) < 1e-7 and abs(float(vd[0]) - 0.04) < 1e-7
