@@ -159,6 +159,21 @@ int lga_arena_bytes(const lga_config *cfg, uint64_t *bytes);
 /* p_l for cfg: 4 d^2 + 2 d d_I + 9 d + d_I (= 12 d^2 + 13 d when d_I = 4 d, Table B.1). */
 int lga_params_per_layer(const lga_config *cfg, uint64_t *count);
 
+/* Per-kernel timing of the library's own launches, for the benchmark's roofline figures.
+ * Between lga_profile_begin and lga_profile_end every kernel launch of this library (on any stack
+ * of the calling process) is bracketed by a HIP event pair on its stream.  lga_profile_end
+ * synchronises the stack's stream and returns one record per kernel name, sorted by total time:
+ * launches, summed event time in ms, and the summed algorithmic flops and HBM bytes of those
+ * launches (each operand read once, each result written once).  out holds `capacity` records;
+ * *count receives the number of distinct kernels (which may exceed capacity). */
+typedef struct lga_kernel_stat {
+    char name[112];
+    uint64_t launches;
+    double ms, flops, bytes;
+} lga_kernel_stat;
+int lga_profile_begin(lga_stack *stack);
+int lga_profile_end(lga_stack *stack, lga_kernel_stat *out, int32_t capacity, int32_t *count);
+
 const char *lga_last_error(void);
 
 #ifdef __cplusplus

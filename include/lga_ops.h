@@ -32,8 +32,8 @@ enum lga_epilogue {
  * the bulk of the computation).
  *  a_kmajor != 0: A is stored [M][lda], k contiguous; else [K][lda], m contiguous.
  *  b_kmajor != 0: B is stored [N][ldb], k contiguous; else [K][ldb], n contiguous.
- * LGA_FP32: any shape.  LGA_BF16 (MFMA kernel): lda, ldb, ldc, N - and M when A is m-contiguous -
- * must be multiples of 8, K a multiple of 8, all pointers 16-byte aligned, and the layout/epilogue
+ * LGA_FP32: any shape.  LGA_BF16 (MFMA kernel): lda, ldb, ldc, N - and M when A is m-contiguous, K
+ * when either operand is k-contiguous - must be multiples of 8, all pointers 16-byte aligned, and the layout/epilogue
  * pair must be one the layer uses: (k,n-major) with STORE/BIAS/BIAS_RESID/BIAS_GELU, (k,k-major)
  * with STORE/MUL_DGELU, (m,n-major) with STORE/ACCUM_F32.  Otherwise LGA_ERR_SHAPE. */
 int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilogue, int32_t M, int32_t N, int32_t K,

@@ -40,6 +40,11 @@ class lga_adam(C.Structure):
                 ("step", C.c_int32)]
 
 
+class lga_kernel_stat(C.Structure):
+    _fields_ = [("name", C.c_char * 112), ("launches", C.c_uint64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
 class LgaError(RuntimeError):
     def __init__(self, code: int, message: str):
         super().__init__(f"{_STATUS_NAMES.get(code, code)}: {message}")
@@ -71,6 +76,8 @@ SIGNATURES = {
     "lga_arena_bytes": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_params_per_layer": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_last_error": (C.c_char_p, []),
+    "lga_profile_begin": (C.c_int, [_vp]),
+    "lga_profile_end": (C.c_int, [_vp, _P(lga_kernel_stat), _i32, _P(_i32)]),
     "lga_op_gemm": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _i32,
                               _vp, _vp, _f32, _vp]),
     "lga_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
@@ -199,6 +206,16 @@ class Stack:
 
     def checkpoint(self, boundary: int):
         return self._borrow(lib.lga_checkpoint, boundary)
+
+    def profile_begin(self):
+        check(lib.lga_profile_begin(self._h))
+
+    def profile_end(self, capacity: int = 64):
+        arr = (lga_kernel_stat * capacity)()
+        n = _i32()
+        check(lib.lga_profile_end(self._h, arr, capacity, C.byref(n)))
+        return [dict(name=arr[i].name.decode(), launches=arr[i].launches, ms=arr[i].ms, flops=arr[i].flops,
+                     bytes=arr[i].bytes) for i in range(min(n.value, capacity))]
 
     def moments(self, layer: int):
         m, v, n = _vp(), _vp(), C.c_size_t()

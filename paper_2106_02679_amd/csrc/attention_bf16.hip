@@ -16,6 +16,8 @@
 //   forward      S^T = K Q^T ; P^T = softmax ; O^T += V^T P^T           streams K, V^T
 //   dQ kernel    S^T = K Q^T ; dP^T = V dO^T ; dS^T ; dQ^T += K^T dS^T   streams K, V, K^T
 //   dK/dV kernel S = Q K^T ; dP = dO V^T ; dV^T += dO^T P ; dK^T += Q^T dS   streams Q, dO, Q^T, dO^T
+#include <cstdio>
+
 #include "kernels.h"
 
 namespace lga {
@@ -445,14 +447,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
 
 template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
     dim3 grid((sh.s + 127) / 128, sh.n_seq * sh.heads);
+    char name[64];
+    snprintf(name, sizeof(name), "attn_fwd_kernel<%d>", DH);
+    const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * 0.5;      // causal (query, key) pairs
+    const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;         // bytes of one [tokens, d] bf16 tensor
+    ProfScope scope(name, 4.0 * pairs * DH, 4.0 * act, s);
     hipLaunchKernelGGL((attn_fwd_kernel<DH>), grid, dim3(256), 0, s, qkv, out, lse, sh);
 }
 template <int DH>
 void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *dout, bf16 *dqkv, AttnShape sh,
             hipStream_t s) {
     dim3 grid((sh.s + 127) / 128, sh.n_seq * sh.heads);
-    hipLaunchKernelGGL((attn_bwd_dq_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
-    hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+    char name[64];
+    const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * 0.5;
+    const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;
+    {
+        snprintf(name, sizeof(name), "attn_bwd_dq_kernel<%d>", DH);
+        ProfScope scope(name, 6.0 * pairs * DH, 5.0 * act, s);
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+    }
+    {
+        snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
+        ProfScope scope(name, 8.0 * pairs * DH, 6.0 * act, s);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+    }
 }
 
 }  // namespace
@@ -479,7 +497,10 @@ void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, co
         return;
     }
     const size_t items = (size_t)sh.n_seq * sh.s * sh.heads;
-    hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, out, dout, delta, sh);
+    {
+        ProfScope scope("attn_delta_kernel", 2.0 * items * sh.dh, 4.0 * items * sh.dh, s);
+        hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, out, dout, delta, sh);
+    }
     switch (sh.dh) {
         case 32: bwd_dh<32>(qkv, lse, delta, dout, dqkv, sh, s); break;
         case 64: bwd_dh<64>(qkv, lse, delta, dout, dqkv, sh, s); break;

@@ -158,6 +158,7 @@ template <class T> void launch_attn_fwd_simple(const T *qkv, T *out, float *lse,
     const size_t blocks = (size_t)sh.n_seq * sh.heads * sh.s;
     if (blocks == 0) return;
     const size_t smem = (size_t)(sh.dh + sh.s) * sizeof(float);
+    ProfScope scope("attn_fwd_simple_kernel", 2.0 * blocks * sh.s * sh.dh, 4.0 * sizeof(T) * blocks * sh.dh, s);
     hipLaunchKernelGGL((attn_fwd_simple_kernel<T>), dim3((unsigned)blocks), dim3(64), smem, s, qkv, out, lse, sh);
 }
 template void launch_attn_fwd_simple<float>(const float *, float *, float *, AttnShape, hipStream_t);
@@ -170,6 +171,7 @@ void launch_attn_bwd_simple(const T *qkv, const T *out, const float *lse, const 
     if (blocks == 0) return;
     const size_t smem_q = (size_t)(2 * sh.dh + sh.s) * sizeof(float);
     const size_t smem_kv = (size_t)(2 * sh.dh + 2 * sh.s) * sizeof(float);
+    ProfScope scope("attn_bwd_simple_kernels", 7.0 * blocks * sh.s * sh.dh, 9.0 * sizeof(T) * blocks * sh.dh, s);
     hipLaunchKernelGGL((attn_bwd_dq_simple_kernel<T>), dim3((unsigned)blocks), dim3(64), smem_q, s, qkv, out, lse,
                        dout, dqkv, delta, sh);
     hipLaunchKernelGGL((attn_bwd_dkv_simple_kernel<T>), dim3((unsigned)blocks), dim3(64), smem_kv, s, qkv, lse, dout,

@@ -16,6 +16,8 @@
 // stores are then 8 bytes (bf16) or 16 bytes (fp32) per lane.
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs)
 // works on a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse.
+#include <cstdio>
+
 #include "kernels.h"
 
 namespace lga {
@@ -260,6 +262,13 @@ void launch_one(const GemmParams<bf16> &p, hipStream_t s) {
                                   (int)smem);
         attr_set = true;
     }
+    char name[96];
+    snprintf(name, sizeof(name), "gemm_bf16_kernel<%d, %d, %s, %s, %d>", BM, BN, A_KM ? "true" : "false",
+             B_KM ? "true" : "false", EPI);
+    const double mn = (double)p.M * p.N;
+    const double out_bytes = EPI == EPI_ACCUM_F32 ? (p.beta != 0.f ? 8.0 : 4.0) : (EPI == EPI_BIAS_GELU ? 4.0 : 2.0);
+    const double aux_bytes = (EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU) ? 2.0 : 0.0;
+    ProfScope scope(name, 2.0 * mn * p.K, 2.0 * ((double)p.M * p.K + (double)p.K * p.N) + mn * (out_bytes + aux_bytes), s);
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, p, tiles_m, tiles_n);
 }
 

@@ -81,6 +81,8 @@ void launch_gemm_f32(const GemmParams<float> &p, bool a_kmajor, bool b_kmajor, E
     const long sam = a_kmajor ? p.lda : 1, sak = a_kmajor ? 1 : p.lda;
     const long sbn = b_kmajor ? p.ldb : 1, sbk = b_kmajor ? 1 : p.ldb;
     dim3 grid((p.N + TN - 1) / TN, (p.M + TM - 1) / TM), block(256);
+    const double mn = (double)p.M * p.N;
+    ProfScope scope("gemm_f32_kernel", 2.0 * mn * p.K, 4.0 * ((double)p.M * p.K + (double)p.K * p.N + mn), s);
     switch (epi) {
         case EPI_STORE: hipLaunchKernelGGL(gemm_f32_kernel<EPI_STORE>, grid, block, 0, s, p, sam, sak, sbk, sbn); break;
         case EPI_BIAS: hipLaunchKernelGGL(gemm_f32_kernel<EPI_BIAS>, grid, block, 0, s, p, sam, sak, sbk, sbn); break;

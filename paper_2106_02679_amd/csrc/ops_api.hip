@@ -53,8 +53,9 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
         p.bias = bias; p.aux = static_cast<const float *>(aux); p.beta = beta;
         launch_gemm_f32(p, akm, bkm, e, s);
     } else {
-        if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || K % 8 || (!akm && M % 8))
-            return err(LGA_ERR_SHAPE, "bf16 GEMM needs lda, ldb, ldc, N, K (and M for m-contiguous A) to be multiples of 8");
+        if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || ((akm || bkm) && K % 8) || (!akm && M % 8))
+            return err(LGA_ERR_SHAPE, "bf16 GEMM needs lda, ldb, ldc, N (K if an operand is k-contiguous, M if A is "
+                                      "m-contiguous) to be multiples of 8");
         if (!a16(A) || !a16(B) || !a16(out) || !a16(out2) || !a16(outf) || !a16(bias) || !a16(aux))
             return err(LGA_ERR_SHAPE, "bf16 GEMM needs 16-byte aligned pointers");
         bool ok = false;
@@ -166,7 +167,7 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
 
 int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_t n, const lga_adam *adam,
                 void *stream) {
-    if (!w || !m || !v || !g || !adam) return err(LGA_ERR_ARG, "NULL argument");
+    if (!adam || (n > 0 && (!w || !m || !v || !g))) return err(LGA_ERR_ARG, "NULL argument");
     if (adam->step < 1) return err(LGA_ERR_STATE, "Adam step t must be >= 1");
     launch_adam(w, m, v, g, static_cast<bf16 *>(w16), n, adam->lr, adam->beta1, adam->beta2, adam->eps, adam->step,
                 reinterpret_cast<hipStream_t>(stream));

@@ -1,0 +1,47 @@
+// Optional per-launch timing: when enabled, every kernel launcher brackets its launch with a HIP
+// event pair on the launch stream; lga_profile_end() aggregates them per kernel name.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+namespace lga {
+
+struct LaunchRecord {
+    std::string name;
+    double flops, bytes;
+    hipEvent_t start, stop;
+};
+
+struct LaunchProfiler {
+    bool enabled = false;
+    std::vector<LaunchRecord> records;
+};
+
+LaunchProfiler &profiler();
+
+// RAII bracket around one launch.  flops / bytes are the algorithmic work of that launch.
+class ProfScope {
+  public:
+    ProfScope(const char *name, double flops, double bytes, hipStream_t s) : stream_(s), active_(profiler().enabled) {
+        if (!active_) return;
+        LaunchRecord r{name, flops, bytes, nullptr, nullptr};
+        if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {
+            active_ = false;
+            return;
+        }
+        (void)hipEventRecord(r.start, stream_);
+        profiler().records.push_back(r);
+    }
+    ~ProfScope() {
+        if (active_) (void)hipEventRecord(profiler().records.back().stop, stream_);
+    }
+
+  private:
+    hipStream_t stream_;
+    bool active_;
+};
+
+}  // namespace lga

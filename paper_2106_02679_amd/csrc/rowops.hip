@@ -279,6 +279,7 @@ inline int grid_for(size_t work_items, int block, int max_blocks = 256 * 16) {
 void launch_cast_f32_to_bf16(const float *src, bf16 *dst, size_t n, hipStream_t s) {
     if (n == 0) return;
     const size_t n4 = (aligned16(src) && (reinterpret_cast<uintptr_t>(dst) & 7u) == 0) ? n / 4 : 0;   // vector part
+    ProfScope scope("cast_kernel", 0.0, 6.0 * n, s);
     hipLaunchKernelGGL(cast_kernel, dim3(grid_for(n / 4 + 1, 256)), dim3(256), 0, s, src, dst, n, n4);
 }
 
@@ -297,6 +298,7 @@ void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, floa
                           int d, float eps, hipStream_t s) {
     if (rows == 0) return;
     constexpr int V = VecOf<T>::N;
+    ProfScope scope("layernorm_fwd_kernel", 8.0 * rows * d, 2.0 * sizeof(T) * rows * (double)d, s);
     if (d % V == 0 && aligned16(x) && aligned16(y))
         hipLaunchKernelGGL((layernorm_fwd_kernel<T, V>), dim3(rows), dim3(256), 0, s, x, g, b, y, mean, rstd, d, eps);
     else
@@ -312,6 +314,7 @@ void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const f
                              const T *resid, T *dx, int rows, int d, hipStream_t s) {
     if (rows == 0) return;
     constexpr int V = VecOf<T>::N;
+    ProfScope scope("layernorm_bwd_dx_kernel", 14.0 * rows * d, 4.0 * sizeof(T) * rows * (double)d, s);
     if (d % V == 0 && aligned16(dy) && aligned16(x) && aligned16(resid) && aligned16(dx))
         hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
                            dx, d);
@@ -334,6 +337,8 @@ void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd,
                    float beta, float *out0, float *out1, float *partial, hipStream_t s) {
     if (cols == 0) return;
     constexpr int VMAX = VecOf<T>::N;
+    ProfScope scope(out1 ? "colsum_kernels(with xhat)" : "colsum_kernels", (out1 ? 4.0 : 1.0) * rows * cols,
+                    (out1 ? 2.0 : 1.0) * sizeof(T) * rows * (double)cols, s);
     const int chunks = rows > 0 ? (rows + kColsumRows - 1) / kColsumRows : 0;
     const bool vec = (cols % VMAX == 0) && (ld % VMAX == 0) && aligned16(a) && (x == nullptr || aligned16(x));
     if (chunks > 0) {
@@ -375,6 +380,7 @@ void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t
     c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
     c.lr = lr;
     c.eps = eps;
+    ProfScope scope("adam_kernel", 12.0 * n, (w16 ? 30.0 : 28.0) * n, s);
     const bool vec = aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
                      (reinterpret_cast<uintptr_t>(w16) & 7u) == 0;
     const size_t n4 = vec ? n / 4 : 0;

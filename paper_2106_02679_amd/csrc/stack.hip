@@ -5,6 +5,9 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
+#include <cstring>
+#include <map>
 #include <new>
 #include <string>
 #include <type_traits>
@@ -27,6 +30,10 @@ int fail(int code, const std::string &msg) {
 
 namespace lga {
 int set_last_error(int code, const char *msg) { return fail(code, msg); }
+LaunchProfiler &profiler() {
+    static LaunchProfiler p;
+    return p;
+}
 }  // namespace lga
 
 namespace {
@@ -550,6 +557,50 @@ int lga_checkpoint(lga_stack *st, int32_t boundary, const void **dev_ptr, size_t
     if (boundary < 0 || boundary > st->cfg.n_layers) return fail(LGA_ERR_ARG, "boundary index out of range");
     *dev_ptr = st->ckpt(boundary);
     if (bytes) *bytes = st->T * st->cfg.d_model * st->esz();
+    return LGA_OK;
+}
+
+int lga_profile_begin(lga_stack *st) {
+    if (!st) return fail(LGA_ERR_ARG, "stack is NULL");
+    LaunchProfiler &p = profiler();
+    for (auto &r : p.records) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    p.records.clear();
+    p.enabled = true;
+    return LGA_OK;
+}
+
+int lga_profile_end(lga_stack *st, lga_kernel_stat *out, int32_t capacity, int32_t *count) {
+    if (!st || !count || (capacity > 0 && !out) || capacity < 0) return fail(LGA_ERR_ARG, "bad argument");
+    LaunchProfiler &p = profiler();
+    p.enabled = false;
+    LGA_HIP(hipStreamSynchronize(st->stream));
+    std::map<std::string, lga_kernel_stat> agg;
+    for (auto &r : p.records) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            lga_kernel_stat &k = agg[r.name];
+            if (k.launches == 0) {
+                std::memset(&k, 0, sizeof(k));
+                std::strncpy(k.name, r.name.c_str(), sizeof(k.name) - 1);
+            }
+            k.launches += 1;
+            k.ms += ms;
+            k.flops += r.flops;
+            k.bytes += r.bytes;
+        }
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    p.records.clear();
+    (void)hipGetLastError();
+    std::vector<lga_kernel_stat> v;
+    for (auto &kv : agg) v.push_back(kv.second);
+    std::sort(v.begin(), v.end(), [](const lga_kernel_stat &a, const lga_kernel_stat &b) { return a.ms > b.ms; });
+    *count = (int32_t)v.size();
+    for (int32_t i = 0; i < capacity && i < (int32_t)v.size(); ++i) out[i] = v[i];
     return LGA_OK;
 }
 

@@ -8,6 +8,11 @@ Gates (relative Frobenius error per compared tensor):
   sign function: a zero-initialised tensor's new value is +-lr per entry, so a few sign flips of
   near-zero gradients dominate its relative error; those tensors are covered by the flat-vector gate
   and by the Adam kernel's own closed-form test instead.
+  The key bias is the method's degenerate case: softmax does not change when every score of a row
+  moves by the same amount, so the gradient of the K third of b_qkv is identically zero.  Exact
+  arithmetic leaves those entries unchanged; any rounding noise above Adam's eps turns into +-lr.
+  They are therefore left out of the updated-weight comparison, and instead their gradient is
+  checked to vanish against the Q-bias gradient (fp32 mode).
 """
 import numpy as np
 import pytest
@@ -25,6 +30,10 @@ GATE = {"fp32": 1e-5, "bf16": 2e-2}
 
 def compare_with_oracle(w, got, ref, gate, adam, zero_init=True):
     sl = S.tensor_slices(w.d_model, w.d_ff)
+    d = w.d_model
+    k_bias = slice(sl["b_qkv"].start + d, sl["b_qkv"].start + 2 * d)
+    keep = np.ones(w.params_per_layer, dtype=bool)
+    keep[k_bias] = False
     worst = {}
     for bnd in range(w.n_layers + 1):
         worst[f"act{bnd}"] = rel_err(got["boundaries"][bnd], ref.boundaries[bnd])
@@ -35,15 +44,22 @@ def compare_with_oracle(w, got, ref, gate, adam, zero_init=True):
             continue
         for name in S.PARAM_ORDER:
             worst[f"g{l}.{name}"] = rel_err(got["grads"][l][sl[name]], ref.grads[l][sl[name]])
+        q_bias = slice(sl["b_qkv"].start, sl["b_qkv"].start + d)
+        if w.dtype == "fp32":
+            assert np.linalg.norm(got["grads"][l][k_bias]) < 1e-4 * np.linalg.norm(got["grads"][l][q_bias])
+        assert np.linalg.norm(ref.grads[l][k_bias]) < 1e-12 * np.linalg.norm(ref.grads[l][q_bias])
     if adam is not None:
         for l in range(w.n_layers):
-            worst[f"w{l}"] = rel_err(got["params"][l], ref.new_params[l])
+            worst[f"w{l}"] = rel_err(got["params"][l][keep], ref.new_params[l][keep])
             worst[f"m{l}"] = rel_err(got["m"][l], ref.new_m[l])
             worst[f"v{l}"] = rel_err(got["v"][l], ref.new_v[l])
             for name in S.PARAM_ORDER:
                 if zero_init and name not in S.MATRICES and name not in S.GAINS:
                     continue
-                worst[f"w{l}.{name}"] = rel_err(got["params"][l][sl[name]], ref.new_params[l][sl[name]])
+                sel = np.zeros(w.params_per_layer, dtype=bool)
+                sel[sl[name]] = True
+                sel &= keep
+                worst[f"w{l}.{name}"] = rel_err(got["params"][l][sel], ref.new_params[l][sel])
     bad = {k: v for k, v in worst.items() if not v < gate}
     assert not bad, f"over the {gate} gate: {bad}; worst overall {max(worst.values()):.3e}"
     return worst
