@@ -296,3 +296,16 @@ def test_adam_first_step_is_signed_unit_step_and_zero_gradient_is_a_fixed_point(
     assert np.allclose(m, 0.1 * g) and np.allclose(v, 0.001 * g * g)
     # literal: first entry moves by lr * 3/(3+1e-8)
     assert abs((w0[0] - w[0]) - 1e-3 * (1 - 1e-8 / 3)) < 1e-15
+
+
+def test_key_bias_gradient_vanishes_identically():
+    # Softmax does not change when every score of a row moves by the same amount, and adding a
+    # constant vector c to every key moves row i's scores by q_i . c: so dL/d(key bias) = 0.
+    shape = tiny_shape(d_l=2, d_m=8, d_a=2, d_s=6, b_mu=2, n_mu=2)
+    x, G, params = tiny_problem(shape)
+    res = O.step_microbatch_major(x, G, params, shape)
+    sl = S.tensor_slices(shape.d_m, shape.d_I)
+    d = shape.d_m
+    for l in range(shape.d_l):
+        gb = res.grads[l][sl["b_qkv"]]
+        assert np.abs(gb[d:2 * d]).max() < 1e-13 * np.abs(gb[:d]).max()
