@@ -45,41 +45,70 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[
     }
 }
 
-// Global -> register staging of one operand tile (ROWS logical rows x 64 k).
+// Global -> register staging of one operand tile (ROWS logical rows x 64 k) through buffer loads.
+// The buffer resource is re-based to the tile's (row0, k0) origin for every k tile, so per-lane
+// offsets stay small and loop-invariant; a lane whose row or k index is out of range gets an
+// offset beyond num_records, for which the hardware returns zeros without touching memory.
 //   KMAJOR: storage [rows][ld], k contiguous.  Thread t: chunk t%8, rows t/8 + 32*i.
-//   else:   storage [k][ld], row index contiguous.  Thread t owns 8x8 blocks: rows 8*(blk%(ROWS/8)).., k 8*(blk/(ROWS/8))..
-template <int ROWS, bool KMAJOR> struct Stager {
-    static constexpr int NV = KMAJOR ? ROWS / 32 : (ROWS / 256 > 0 ? ROWS / 256 : 1) * 8;
-    u32x4 v[NV];
+//   else:   storage [k][ld], row index contiguous.  Thread t owns the 8x8 block with rows
+//           8*(t%(ROWS/8)).., k 8*(t/(ROWS/8)).., transposed in registers before the LDS store.
+constexpr int kBufRange = 0x40000000;          // 1 GiB window; valid offsets are far below it
+constexpr int kBufPoison = 0x7FFFFF00;         // always out of range
 
-    __device__ __forceinline__ void load(const bf16 *__restrict__ base, int ld, int row0, int nrows, int k0, int K) {
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, kBufRange, 0x00020000);
+}
+
+template <int ROWS, bool KMAJOR> struct Stager {
+    static constexpr int NV = KMAJOR ? ROWS / 32 : 8;
+    static constexpr int NOFF = KMAJOR ? NV : 1;
+    static_assert(KMAJOR || ROWS <= 256, "one 8x8 block per thread");
+    u32x4 v[NV];
+    int off[NOFF];       // per-load byte offset inside the tile, or the poison offset for invalid rows
+    int ld2;             // leading dimension in bytes
+
+    __device__ __forceinline__ void init(int ld, int row0, int nrows) {
+        const int tid = threadIdx.x;
+        ld2 = ld * 2;
+        if constexpr (KMAJOR) {
+            const int voff = (tid >> 3) * ld2 + (tid & 7) * 16;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) off[i] = (row0 + (tid >> 3) + 32 * i < nrows) ? voff : kBufPoison;
+        } else {
+            constexpr int CB = ROWS / 8;
+            const int r = (tid % CB) * 8, kb = tid / CB;
+            off[0] = (tid < ROWS && row0 + r < nrows) ? kb * 8 * ld2 + r * 2 : kBufPoison;
+        }
+    }
+
+    // base: address of element (row0, k0) of the operand.  Full k tile: no k test.
+    __device__ __forceinline__ void load(const bf16 *base) {
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(base);
+        if constexpr (KMAJOR) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[i], i * 32 * ld2, 0);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[0], j * ld2, 0);
+        }
+    }
+
+    // Last, partial k tile: krem = K - k0 < 64 valid k; the rest reads as zero.
+    __device__ __forceinline__ void load_tail(const bf16 *base, int krem) {
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(base);
         const int tid = threadIdx.x;
         if constexpr (KMAJOR) {
-            const int chunk = tid & 7;
-            const int k = k0 + chunk * 8;
+            const int kmask = ((tid & 7) * 8 < krem) ? 0 : kBufPoison;     // OR-ing the poison keeps it out of range
 #pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int r = row0 + (tid >> 3) + 32 * i;
-                if (r < nrows && k < K)
-                    v[i] = *reinterpret_cast<const u32x4 *>(base + (size_t)r * ld + k);
-                else
-                    v[i] = u32x4{0, 0, 0, 0};
-            }
+            for (int i = 0; i < NV; ++i)
+                v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[i] | kmask, i * 32 * ld2, 0);
         } else {
-            constexpr int CB = ROWS / 8;   // column blocks
+            constexpr int CB = ROWS / 8;
+            const int kb = tid / CB;
 #pragma unroll
-            for (int b = 0; b < NV / 8; ++b) {
-                const int blk = tid + 256 * b;
-                const int r = row0 + (blk % CB) * 8;
-                const int kb = blk / CB;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int k = k0 + kb * 8 + j;
-                    if (blk < ROWS && r < nrows && k < K)
-                        v[b * 8 + j] = *reinterpret_cast<const u32x4 *>(base + (size_t)k * ld + r);
-                    else
-                        v[b * 8 + j] = u32x4{0, 0, 0, 0};
-                }
+            for (int j = 0; j < 8; ++j) {
+                const int kmask = (kb * 8 + j < krem) ? 0 : kBufPoison;
+                v[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, off[0] | kmask, j * ld2, 0);
             }
         }
     }
@@ -95,18 +124,12 @@ template <int ROWS, bool KMAJOR> struct Stager {
             }
         } else {
             constexpr int CB = ROWS / 8;
+            if (ROWS >= 256 || tid < ROWS) {
+                u32x4 out[8];
+                transpose8x8(v, out);
+                const int r = (tid % CB) * 8, kb = tid / CB;
 #pragma unroll
-            for (int b = 0; b < NV / 8; ++b) {
-                const int blk = tid + 256 * b;
-                if (blk < ROWS) {
-                    u32x4 in[8], out[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) in[j] = v[b * 8 + j];
-                    transpose8x8(in, out);
-                    const int r = (blk % CB) * 8, kb = blk / CB;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(lds + lds_off(r + c, kb)) = out[c];
-                }
+                for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(lds + lds_off(r + c, kb)) = out[c];
             }
         }
     }
@@ -197,40 +220,155 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
 
     Stager<BM, A_KM> sa;
     Stager<BN, B_KM> sb;
-    const int nk = (p.K + BK - 1) / BK;
-    sa.load(p.A, p.lda, m0, p.M, 0, p.K);
-    sb.load(p.B, p.ldb, n0, p.N, 0, p.K);
+    sa.init(p.lda, m0, p.M);
+    sb.init(p.ldb, n0, p.N);
+    // element (row0, k) of each operand: k-major rows advance by 1 per k, the others by ld per k
+    const bf16 *a_ptr = A_KM ? p.A + (size_t)m0 * p.lda : p.A + m0;
+    const bf16 *b_ptr = B_KM ? p.B + (size_t)n0 * p.ldb : p.B + n0;
+    const size_t a_step = A_KM ? (size_t)BK : (size_t)BK * p.lda;
+    const size_t b_step = B_KM ? (size_t)BK : (size_t)BK * p.ldb;
+    const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
+    auto load_tile = [&](int t) {
+        if (t < nk_full) {
+            sa.load(a_ptr + (size_t)t * a_step);
+            sb.load(b_ptr + (size_t)t * b_step);
+        } else {
+            sa.load_tail(a_ptr + (size_t)t * a_step, p.K - t * BK);
+            sb.load_tail(b_ptr + (size_t)t * b_step, p.K - t * BK);
+        }
+    };
+
+    bf16x8 af[2][FM], bf[2][FN];
+    auto load_frags = [&](int buf, const bf16 *a_lds, const bf16 *b_lds, int ks) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+            af[buf][i] = *reinterpret_cast<const bf16x8 *>(a_lds + lds_off(wm * WM + i * 32 + lrow, 2 * ks + lhalf));
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            bf[buf][j] = *reinterpret_cast<const bf16x8 *>(b_lds + lds_off(wn * WN + j * 32 + lrow, 2 * ks + lhalf));
+    };
+
+    load_tile(0);
     sa.store(As(0));
     sb.store(Bs(0));
     __syncthreads();
+    load_frags(0, As(0), Bs(0), 0);
 
-    for (int kt = 0; kt < nk; ++kt) {
+    // MFMAs of one k step for accumulator rows [i0, i1) of the wavefront tile
+    auto mfma_rows = [&](int fb, int i0, int i1) {
+#pragma unroll
+        for (int i = i0; i < i1; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fb][j], af[fb][i], acc[i][j], 0, 0, 0);
+    };
+    auto mfma_step = [&](int fb) { mfma_rows(fb, 0, FM); };
+
+    // Instruction-mix hints for the scheduler (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 LDS read,
+    // 0x200 LDS write): spread the memory instructions of a k step evenly under its MFMAs.  A CU's
+    // texture-address unit takes 16 cycles per 16-byte-per-lane load, so the global loads are
+    // issued at no more than one per two MFMAs (64 cycles) per wavefront.
+    constexpr int NMF = FM * FN, NDR = FM + FN;
+    constexpr int NVA = Stager<BM, A_KM>::NV, NVB = Stager<BN, B_KM>::NV;
+    constexpr bool kHints = NMF % NDR == 0 && NMF % NVA == 0 && NMF % NVB == 0 && FM % 2 == 0 &&
+                            (NMF / 2) % NDR == 0 && (NVA + NVB) % (NMF / 2) == 0;
+
+    int kt = 0;
+    // Main loop: the next k tile exists and is full, so the body is straight-line code.
+    //   step 0 : MFMAs | global loads of A(kt+1) | LDS reads of step 1's operands
+    //   step 1 : MFMAs | global loads of B(kt+1) | LDS reads of step 2's operands
+    //   step 2 : MFMAs | LDS reads of step 3's operands
+    //   step 3a: first half of the MFMAs | LDS writes of tile kt+1 into the other stage
+    //   barrier
+    //   step 3b: second half of the MFMAs | LDS reads of tile kt+1's step-0 operands
+    for (; kt + 1 < nk_full; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            sa.load(p.A, p.lda, m0, p.M, (kt + 1) * BK, p.K);
-            sb.load(p.B, p.ldb, n0, p.N, (kt + 1) * BK, p.K);
+        const bf16 *a_lds = As(cur), *b_lds = Bs(cur);
+        bf16 *a_nxt = As(cur ^ 1), *b_nxt = Bs(cur ^ 1);
+
+        sa.load(a_ptr + (size_t)(kt + 1) * a_step);
+        load_frags(1, a_lds, b_lds, 1);
+        mfma_step(0);
+        if constexpr (kHints) {
+#pragma unroll
+            for (int i = 0; i < NMF; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i % (NMF / NVA) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (i % (NMF / NDR) == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
+        __builtin_amdgcn_sched_barrier(0);
+
+        sb.load(b_ptr + (size_t)(kt + 1) * b_step);
+        load_frags(0, a_lds, b_lds, 2);
+        mfma_step(1);
+        if constexpr (kHints) {
+#pragma unroll
+            for (int i = 0; i < NMF; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (i % (NMF / NVB) == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (i % (NMF / NDR) == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        load_frags(1, a_lds, b_lds, 3);
+        mfma_step(0);
+        if constexpr (kHints) {
+#pragma unroll
+            for (int i = 0; i < NDR; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, NMF / NDR, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        sa.store(a_nxt);
+        sb.store(b_nxt);
+        mfma_rows(1, 0, FM / 2);
+        if constexpr (kHints) {
+#pragma unroll
+            for (int i = 0; i < NMF / 2; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, (NVA + NVB) / (NMF / 2), 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+
+        load_frags(0, a_nxt, b_nxt, 0);
+        mfma_rows(1, FM / 2, FM);
+        if constexpr (kHints) {
+#pragma unroll
+            for (int i = 0; i < NDR; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, NMF / 2 / NDR, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // Remaining tiles (the last full one, and a partial one if K is not a multiple of 64).
+    for (; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) load_tile(kt + 1);
         const bf16 *a_lds = As(cur), *b_lds = Bs(cur);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[FM], bf[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(a_lds + lds_off(wm * WM + i * 32 + lrow, 2 * ks + lhalf));
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                bf[j] = *reinterpret_cast<const bf16x8 *>(b_lds + lds_off(wn * WN + j * 32 + lrow, 2 * ks + lhalf));
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+            const int fb = ks & 1;
+            if (ks + 1 < BK / 16) {
+                load_frags(fb ^ 1, a_lds, b_lds, ks + 1);
+            } else {
+                if (more) {
+                    sa.store(As(cur ^ 1));
+                    sb.store(Bs(cur ^ 1));
+                }
+                __syncthreads();
+                if (more) load_frags(fb ^ 1, As(cur ^ 1), Bs(cur ^ 1), 0);
+            }
+            mfma_step(fb);
         }
-        if (kt + 1 < nk) {
-            sa.store(As(cur ^ 1));
-            sb.store(Bs(cur ^ 1));
-        }
-        __syncthreads();
     }
 
     // ---- epilogue: lane holds row m = lrow, columns n = 8*q + 4*lhalf + (0..3) of each 32x32 block
