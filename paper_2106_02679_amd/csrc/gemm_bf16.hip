@@ -25,6 +25,9 @@ namespace lga {
 namespace {
 
 constexpr int BK = 64;           // k elements per stage
+#ifndef LGA_GEMM_DBG
+#define LGA_GEMM_DBG 0           // timing experiments only: 1 = no global loads, 2 = also no LDS stores/barrier, 3 = MFMA only
+#endif
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 4)) & 7; }
 
@@ -286,8 +289,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         const bf16 *a_lds = As(cur), *b_lds = Bs(cur);
         bf16 *a_nxt = As(cur ^ 1), *b_nxt = Bs(cur ^ 1);
 
-        sa.load(a_ptr + (size_t)(kt + 1) * a_step);
-        load_frags(1, a_lds, b_lds, 1);
+        if (LGA_GEMM_DBG < 1) sa.load(a_ptr + (size_t)(kt + 1) * a_step);
+        if (LGA_GEMM_DBG < 3) load_frags(1, a_lds, b_lds, 1);
         mfma_step(0);
         if constexpr (kHints) {
 #pragma unroll
@@ -299,8 +302,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        sb.load(b_ptr + (size_t)(kt + 1) * b_step);
-        load_frags(0, a_lds, b_lds, 2);
+        if (LGA_GEMM_DBG < 1) sb.load(b_ptr + (size_t)(kt + 1) * b_step);
+        if (LGA_GEMM_DBG < 3) load_frags(0, a_lds, b_lds, 2);
         mfma_step(1);
         if constexpr (kHints) {
 #pragma unroll
@@ -312,7 +315,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        load_frags(1, a_lds, b_lds, 3);
+        if (LGA_GEMM_DBG < 3) load_frags(1, a_lds, b_lds, 3);
         mfma_step(0);
         if constexpr (kHints) {
 #pragma unroll
@@ -323,8 +326,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        sa.store(a_nxt);
-        sb.store(b_nxt);
+        if (LGA_GEMM_DBG < 2) {
+            sa.store(a_nxt);
+            sb.store(b_nxt);
+        }
         mfma_rows(1, 0, FM / 2);
         if constexpr (kHints) {
 #pragma unroll
@@ -334,10 +339,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
+        if (LGA_GEMM_DBG < 2) __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
 
-        load_frags(0, a_nxt, b_nxt, 0);
+        if (LGA_GEMM_DBG < 3) load_frags(0, a_nxt, b_nxt, 0);
         mfma_rows(1, FM / 2, FM);
         if constexpr (kHints) {
 #pragma unroll
