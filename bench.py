@@ -39,6 +39,21 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic(workload, kernel):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.rstrip("\n").split("\t")
+                if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, sample_tokens):
     """Time the oracle (as it stands) on a one-layer, one-micro-batch sample of the same layer shape."""
     import numpy as np
@@ -132,7 +147,8 @@ def main():
         roof = {"bound": "mfma" if dt == B.LGA_BF16 else "alu", "achieved": dom["flops"] / dom["ms"] / 1e9,
                 "peak": peak, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(w.name, dom["name"]) if group == DEFAULT_GROUP[args.config] else None
+    roof["algorithmic_bytes_per_launch"] = dom["bytes"] / dom["launches"]
     roof["kernel"] = dom["name"]
     roof["launches"] = dom["launches"]
     roof["avg_launch_ms"] = per_launch_ms
