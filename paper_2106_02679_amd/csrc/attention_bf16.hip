@@ -119,7 +119,7 @@ __device__ __forceinline__ bf16x8 pack_bf16(const f32x16 &v, int kk) {
 // ============================================================================================
 // Forward.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ out,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ out,
                                                        float *__restrict__ lse, AttnShape sh) {
     constexpr int KT = 64;                 // keys per streamed tile
     constexpr int NK = DH / 16, NC = DH / 32;
@@ -169,34 +169,41 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16 *__restrict__ 
                     st[kb] = MFMA(frag_nat<DH>(Ks, kb * 32 + lrow, ks, half), qf[ks], st[kb]);
             }
         }
-        // scale into the log2 domain, mask, running max
-        float mx = m_run;
+        // Running max in the log2 domain (scores * c2).  Only tiles that touch the diagonal need the mask.
+        if (k0 + KT - 1 > qw0) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (!(kb < nkb && key <= q)) st[kb][r] = -INFINITY;
+                }
+        }
+        float raw = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                const float v = (kb < nkb && key <= q) ? st[kb][r] * c2 : -INFINITY;
-                st[kb][r] = v;
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float alpha = exp2f(m_run - mx);       // 0 on the first tile (m_run = -inf, mx finite)
+            for (int r = 0; r < 16; ++r) raw = fmaxf(raw, st[kb][r]);
+        raw = fmaxf(raw, __shfl_xor(raw, 32, 64));
+        const float mx = fmaxf(m_run, raw * c2);     // finite from the first tile on: key 0 is visible to every query
+        const float alpha = __builtin_amdgcn_exp2f(m_run - mx);       // 0 on the first tile (m_run = -inf)
         m_run = mx;
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = exp2f(st[kb][r] - mx);
+                const float p = __builtin_amdgcn_exp2f(fmaf(st[kb][r], c2, -mx));
                 st[kb][r] = p;
                 psum += p;
             }
         l_run = l_run * alpha + psum;
+        if (__any(alpha != 1.0f)) {                  // the max rarely moves after the first tiles
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+                for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+        }
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             if (kb < nkb) {
@@ -252,7 +259,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict_
 // ============================================================================================
 // dQ.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
                                                           const float *__restrict__ delta,
                                                           const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
                                                           AttnShape sh) {
@@ -282,7 +289,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict
         dof[ks] = frag_global(dorow, ks, half, qvalid);
     }
     const size_t stat = ((size_t)b * sh.heads + h) * sh.s + q;
-    const float lse2 = qvalid ? lse[stat] * kLog2e : 0.f;
+    const float lse2 = qvalid ? lse[stat] * kLog2e : INFINITY;     // invalid rows: p = exp2(-inf) = 0
     const float dl = qvalid ? delta[stat] : 0.f;
     const float scale = rsqrtf((float)DH);
     const float c2 = scale * kLog2e;
@@ -309,10 +316,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16 *__restrict
             st = MFMA(frag_nat<DH>(Ks, lrow, ks, half), qf[ks], st);
             dpt = MFMA(frag_nat<DH>(Vs, lrow, ks, half), dof[ks], dpt);
         }
+        const bool diag = k0 + KT - 1 > qw0;        // some (query, key) pair of this tile is masked
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int key = k0 + 8 * (r >> 2) + 4 * half + (r & 3);
-            const float p = (key <= q && qvalid) ? exp2f(st[r] * c2 - lse2) : 0.f;
+            float p = __builtin_amdgcn_exp2f(fmaf(st[r], c2, -lse2));
+            if (diag && key > q) p = 0.f;
             st[r] = p * (dpt[r] - dl);
         }
 #pragma unroll
@@ -411,7 +420,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
             for (int i = 0; i < 4; ++i) {
                 const int r = 4 * g + i;
                 const int qq = q0 + 8 * g + 4 * half + i;
-                const float p = (qq >= key && qq < sh.s && kvalid) ? exp2f(s_[r] * c2 - l4[i]) : 0.f;
+                const float p = (qq >= key && qq < sh.s && kvalid) ? __builtin_amdgcn_exp2f(fmaf(s_[r], c2, -l4[i])) : 0.f;
                 pr[r] = p;
                 s_[r] = p * (dp[r] - d4[i]);
             }
