@@ -144,7 +144,7 @@ int lga_step_mbmajor(lga_stack *stack, const void *x, const void *dy, void *y, v
  * counters.  order is enum lga_order.
  *  param_bytes  HBM bytes of parameter traffic: 16-bit weight reads by the forward, recompute and
  *               input-gradient GEMM families per group, plus Adam's read of w, m, v and write of
- *               w, m, v and the 16-bit copy.
+ *               w, m, v, the 16-bit copy and the transposed 16-bit copy of the matrices.
  *  grad_bytes   HBM bytes of fp32 gradient-buffer traffic: read-modify-write per group (write
  *               only for a layer's first group) plus Adam's read.
  *  flops        executed flops: GEMMs 2 flop per token per parameter for forward, recompute

@@ -34,8 +34,9 @@ enum lga_epilogue {
  *  b_kmajor != 0: B is stored [N][ldb], k contiguous; else [K][ldb], n contiguous.
  * LGA_FP32: any shape.  LGA_BF16 (MFMA kernel): lda, ldb, ldc, N - and M when A is m-contiguous, K
  * when either operand is k-contiguous - must be multiples of 8, all pointers 16-byte aligned, and the layout/epilogue
- * pair must be one the layer uses: (k,n-major) with STORE/BIAS/BIAS_RESID/BIAS_GELU, (k,k-major)
- * with STORE/MUL_DGELU, (m,n-major) with STORE/ACCUM_F32.  Otherwise LGA_ERR_SHAPE. */
+ * pair must be one that is built: (k,k-major) with any epilogue - the layout the layer stack itself
+ * uses for all three GEMM families -, (k,n-major) with STORE/BIAS/BIAS_RESID/BIAS_GELU, (m,n-major) with
+ * STORE/ACCUM_F32.  Otherwise LGA_ERR_SHAPE. */
 int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilogue, int32_t M, int32_t N, int32_t K,
                 const void *A, int32_t lda, const void *B, int32_t ldb, void *out, void *out2, float *outf,
                 int32_t ldc, const float *bias, const void *aux, float beta, void *stream);
@@ -52,6 +53,11 @@ int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const flo
 int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const float *mean, const float *rstd,
                          const float *g, const void *resid, void *dx, float *dgamma, float *dbeta, float beta,
                          float *scratch, int32_t rows, int32_t d, void *stream);
+
+/* out[c][r] = in[r][c] for bfloat16 matrices (in: [R][ldi], out: [C][ldo]); R, C, ldi, ldo multiples of 8,
+ * 16-byte aligned.  The stack keeps a transposed 16-bit copy of each weight matrix and transposes the
+ * two operands of every weight-gradient GEMM so that all GEMM operands are k-contiguous. */
+int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo, void *stream);
 
 /* out[c] = beta*out[c] + sum_r a[r,c]  (bias gradients).  a: [rows][ld]. */
 int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int32_t ld, float beta, float *out,

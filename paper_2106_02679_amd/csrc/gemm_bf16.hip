@@ -437,11 +437,14 @@ void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, E
             case EPI_STORE: launch_tiles<true, false, EPI_STORE>(p, s); return;
             default: break;
         }
-    } else if (a_kmajor && b_kmajor) {    // input gradient
+    } else if (a_kmajor && b_kmajor) {    // both operands k-contiguous: the layout the layer stack uses
         switch (epi) {
             case EPI_STORE: launch_tiles<true, true, EPI_STORE>(p, s); return;
+            case EPI_BIAS: launch_tiles<true, true, EPI_BIAS>(p, s); return;
+            case EPI_BIAS_RESID: launch_tiles<true, true, EPI_BIAS_RESID>(p, s); return;
+            case EPI_BIAS_GELU: launch_tiles<true, true, EPI_BIAS_GELU>(p, s); return;
             case EPI_MUL_DGELU: launch_tiles<true, true, EPI_MUL_DGELU>(p, s); return;
-            default: break;
+            case EPI_ACCUM_F32: launch_tiles<true, true, EPI_ACCUM_F32>(p, s); return;
         }
     } else if (!a_kmajor && !b_kmajor) {  // weight gradient
         if (epi == EPI_ACCUM_F32) { launch_tiles<false, false, EPI_ACCUM_F32>(p, s); return; }

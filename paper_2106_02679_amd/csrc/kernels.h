@@ -33,6 +33,9 @@ template <class T>
 void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd, int rows, int cols, int ld,
                    float beta, float *out0, float *out1, float *partial, hipStream_t s);
 
+// out[c][r] = in[r][c] for bf16 matrices; R, C, ldi, ldo multiples of 8, 16-byte aligned bases.
+void launch_transpose_bf16(const bf16 *in, bf16 *out, int R, int C, long ldi, long ldo, hipStream_t s);
+
 // Adam update of n parameters in place; optionally also writes the bf16 copy of the new weights.
 void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t n, float lr, float beta1,
                  float beta2, float eps, int step, hipStream_t s);

@@ -60,7 +60,7 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
             return err(LGA_ERR_SHAPE, "bf16 GEMM needs 16-byte aligned pointers");
         bool ok = false;
         if (akm && !bkm) ok = e == EPI_STORE || e == EPI_BIAS || e == EPI_BIAS_RESID || e == EPI_BIAS_GELU;
-        else if (akm && bkm) ok = e == EPI_STORE || e == EPI_MUL_DGELU;
+        else if (akm && bkm) ok = true;
         else if (!akm && !bkm) ok = e == EPI_STORE || e == EPI_ACCUM_F32;
         if (!ok) return err(LGA_ERR_SHAPE, "bf16 GEMM: this layout/epilogue pair is not built");
         GemmParams<bf16> p{};
@@ -106,6 +106,16 @@ int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const flo
                                       static_cast<const bf16 *>(resid), static_cast<bf16 *>(dx), rows, d, s);
     }
     return done("lga_op_layernorm_bwd");
+}
+
+int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo, void *stream) {
+    if (R < 0 || C < 0 || ldi < C || ldo < R) return err(LGA_ERR_SHAPE, "bad shape");
+    if (R % 8 || C % 8 || ldi % 8 || ldo % 8 || !a16(in) || !a16(out))
+        return err(LGA_ERR_SHAPE, "transpose needs sizes and leading dimensions that are multiples of 8, 16-byte aligned");
+    if ((!in || !out) && R > 0 && C > 0) return err(LGA_ERR_ARG, "NULL argument");
+    launch_transpose_bf16(static_cast<const bf16 *>(in), static_cast<bf16 *>(out), R, C, ldi, ldo,
+                          reinterpret_cast<hipStream_t>(stream));
+    return done("lga_op_transpose");
 }
 
 uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols) {

@@ -266,6 +266,50 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float 
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// out[c][r] = in[r][c] for 16-bit elements.  A block moves a 128 x 128 tile: each thread loads one
+// 8x8 block (16-byte row pieces, lanes along the contiguous direction), transposes it in registers,
+// parks it in LDS, and the block then writes whole 256-byte row segments of the output.
+constexpr int kTrTile = 128;
+constexpr int kTrPitch = kTrTile + 8;     // elements; keeps 16-byte alignment and skews the banks
+
+__global__ __launch_bounds__(256) void transpose16_kernel(const bf16 *__restrict__ in, bf16 *__restrict__ out, int R,
+                                                          int C, long ldi, long ldo) {
+    __shared__ __attribute__((aligned(16))) bf16 tile[kTrTile * kTrPitch];     // [c][r]
+    const int r0 = blockIdx.y * kTrTile, c0 = blockIdx.x * kTrTile;
+    const int tid = threadIdx.x;
+    {
+        const int cb = tid & 15, rb = tid >> 4;           // 16 x 16 blocks of 8 x 8
+        u32x4 v[8], t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = r0 + rb * 8 + j, c = c0 + cb * 8;
+            v[j] = u32x4{0, 0, 0, 0};
+            if (r < R && c < C) v[j] = *reinterpret_cast<const u32x4 *>(in + (size_t)r * ldi + c);
+        }
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t x = v[2 * p][q], y = v[2 * p + 1][q];
+                t[2 * q][p] = (x & 0xFFFFu) | (y << 16);
+                t[2 * q + 1][p] = (x >> 16) | (y & 0xFFFF0000u);
+            }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<u32x4 *>(tile + (cb * 8 + i) * kTrPitch + rb * 8) = t[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int c = (tid >> 4) + 16 * j, rch = tid & 15;
+        const int gc = c0 + c, gr = r0 + rch * 8;
+        if (gc < C && gr < R)
+            *reinterpret_cast<u32x4 *>(out + (size_t)gc * ldo + gr) =
+                *reinterpret_cast<const u32x4 *>(tile + c * kTrPitch + rch * 8);
+    }
+}
+
 inline int grid_for(size_t work_items, int block, int max_blocks = 256 * 16) {
     size_t b = (work_items + block - 1) / block;
     if (b < 1) b = 1;
@@ -367,6 +411,13 @@ template void launch_colsum<float>(const float *, const float *, const float *, 
                                    float *, float *, float *, hipStream_t);
 template void launch_colsum<bf16>(const bf16 *, const bf16 *, const float *, const float *, int, int, int, float,
                                   float *, float *, float *, hipStream_t);
+
+void launch_transpose_bf16(const bf16 *in, bf16 *out, int R, int C, long ldi, long ldo, hipStream_t s) {
+    if (R == 0 || C == 0) return;
+    ProfScope scope("transpose16_kernel", 0.0, 4.0 * R * (double)C, s);
+    dim3 grid((C + kTrTile - 1) / kTrTile, (R + kTrTile - 1) / kTrTile);
+    hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldi, ldo);
+}
 
 void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t n, float lr, float beta1,
                  float beta2, float eps, int step, hipStream_t s) {

@@ -91,6 +91,8 @@ int validate_config(const lga_config *c) {
         if (dh % 32 != 0) return fail(LGA_ERR_SHAPE, "bf16 mode needs head size d_h to be a multiple of 32");
         if (c->d_model % 8 != 0 || c->d_ff % 8 != 0)
             return fail(LGA_ERR_SHAPE, "bf16 mode needs d_model and d_ff to be multiples of 8");
+        if (((long)c->group * c->micro_batch * c->seq_len) % 8 != 0)
+            return fail(LGA_ERR_SHAPE, "bf16 mode needs group * micro_batch * seq_len to be a multiple of 8");
     }
     // kernels index rows and columns with int and elements with size_t
     const double tokens_group = (double)c->group * c->micro_batch * c->seq_len;
@@ -101,7 +103,7 @@ int validate_config(const lga_config *c) {
 
 // Arena plan: one allocation, every sub-buffer 256-byte aligned.
 struct Plan {
-    size_t w, m, v, grad, w16, ckpt, dact;
+    size_t w, m, v, grad, w16, w16t, ckpt, dact, xT, dyT;
     size_t h, qkv, a, x1, h2, u, gl, du, dh2, dx1, da, dqkv, dh;
     size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
     size_t total;
@@ -121,6 +123,7 @@ Plan make_plan(const lga_config &c) {
     p.v = take(L * P * 4);
     p.grad = take((c.retain_grads ? L : 1) * P * 4);
     p.w16 = take(c.dtype == LGA_BF16 ? L * P * 2 : 0);
+    p.w16t = take(c.dtype == LGA_BF16 ? L * P * 2 : 0);      // each matrix transposed, at its canonical offset
     p.ckpt = take((L + 1) * T * d * esz);
     p.dact = take(T * d * esz);
     p.h = take(t * d * esz);
@@ -136,6 +139,8 @@ Plan make_plan(const lga_config &c) {
     p.da = take(t * d * esz);
     p.dqkv = take(t * 3 * d * esz);
     p.dh = take(t * d * esz);
+    p.xT = take(c.dtype == LGA_BF16 ? t * f * 2 : 0);                           // [in][t] copy of a dW GEMM's input
+    p.dyT = take(c.dtype == LGA_BF16 ? t * std::max<size_t>(3 * d, f) * 2 : 0);  // [out][t] copy of its output gradient
     p.mean1 = take(t * 4);
     p.rstd1 = take(t * 4);
     p.mean2 = take(t * 4);
@@ -166,6 +171,7 @@ struct lga_stack {
     float *m(int l) const { return at<float>(plan.m) + (size_t)l * P; }
     float *v(int l) const { return at<float>(plan.v) + (size_t)l * P; }
     bf16 *w16(int l) const { return at<bf16>(plan.w16) + (size_t)l * P; }
+    bf16 *w16t(int l) const { return at<bf16>(plan.w16t) + (size_t)l * P; }
     int grad_slot(int l) const { return cfg.retain_grads ? l : 0; }
     float *grad(int l) const { return at<float>(plan.grad) + (size_t)grad_slot(l) * P; }
     size_t esz() const { return cfg.dtype == LGA_BF16 ? 2 : 4; }
@@ -185,6 +191,19 @@ template <class T> const T *gemm_weights(const lga_stack *st, int l) {
     else return st->w16(l);
 }
 
+// Refresh layer l's transposed 16-bit matrices ([out][in]) from its 16-bit copy ([in][out]): the
+// forward GEMMs read them so that both of their operands are k-contiguous.
+void refresh_transposed_weights(lga_stack *st, int l) {
+    const int d = st->cfg.d_model, f = st->cfg.d_ff;
+    const LayerLayout &o = st->lay;
+    const bf16 *w = st->w16(l);
+    bf16 *wt = st->w16t(l);
+    launch_transpose_bf16(w + o.w_qkv, wt + o.w_qkv, d, 3 * d, 3 * d, d, st->stream);
+    launch_transpose_bf16(w + o.w_o, wt + o.w_o, d, d, d, d, st->stream);
+    launch_transpose_bf16(w + o.w_1, wt + o.w_1, d, f, f, d, st->stream);
+    launch_transpose_bf16(w + o.w_2, wt + o.w_2, f, d, d, f, st->stream);
+}
+
 // Forward of layer l on one micro-batch group (paper section 5 "Model"; pre-LN residual form).
 // x_in: [t, d] group slice of the layer's input checkpoint.  y_out: group slice of the next
 // checkpoint, or NULL when this is the backward pass's recompute (the second feed-forward GEMM's
@@ -202,29 +221,37 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     float *lse = st->at<float>(st->plan.lse);
     const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
 
+    // y[t, out] = x[t, in] W[in, out]: fp32 mode reads W as stored; bf16 mode reads the transposed copy
+    // W^T[out, in], so both operands are k-contiguous.
+    constexpr bool kBf16 = !std::is_same<T, float>::value;
+    const T *pwt = pw;
+    if constexpr (kBf16) pwt = st->w16t(l);
+    auto fwd_gemm = [&](GemmParams<T> g, size_t w_off, int in, int out, Epilogue e) {
+        g.M = t; g.N = out; g.K = in; g.lda = in; g.ldc = out;
+        g.B = pwt + w_off;
+        g.ldb = kBf16 ? in : out;
+        gemm<T>(g, true, kBf16, e, s);
+    };
+
     launch_layernorm_fwd<T>(x_in, pf + o.ln1_g, pf + o.ln1_b, h, st->at<float>(st->plan.mean1),
                             st->at<float>(st->plan.rstd1), t, d, c.ln_eps, s);
     GemmParams<T> g{};
-    g.A = h; g.lda = d; g.B = pw + o.w_qkv; g.ldb = 3 * d; g.M = t; g.N = 3 * d; g.K = d;
-    g.out = qkv; g.ldc = 3 * d; g.bias = pf + o.b_qkv;
-    gemm<T>(g, true, false, EPI_BIAS, s);
+    g.A = h; g.out = qkv; g.bias = pf + o.b_qkv;
+    fwd_gemm(g, o.w_qkv, d, 3 * d, EPI_BIAS);
     if constexpr (std::is_same<T, float>::value) launch_attn_fwd_simple<float>(qkv, a, lse, ash, s);
     else launch_attn_fwd_bf16(qkv, a, lse, ash, s);
     g = GemmParams<T>{};
-    g.A = a; g.lda = d; g.B = pw + o.w_o; g.ldb = d; g.M = t; g.N = d; g.K = d;
-    g.out = x1; g.ldc = d; g.bias = pf + o.b_o; g.aux = x_in;
-    gemm<T>(g, true, false, EPI_BIAS_RESID, s);
+    g.A = a; g.out = x1; g.bias = pf + o.b_o; g.aux = x_in;
+    fwd_gemm(g, o.w_o, d, d, EPI_BIAS_RESID);
     launch_layernorm_fwd<T>(x1, pf + o.ln2_g, pf + o.ln2_b, h2, st->at<float>(st->plan.mean2),
                             st->at<float>(st->plan.rstd2), t, d, c.ln_eps, s);
     g = GemmParams<T>{};
-    g.A = h2; g.lda = d; g.B = pw + o.w_1; g.ldb = f; g.M = t; g.N = f; g.K = d;
-    g.out = gl; g.out2 = u; g.ldc = f; g.bias = pf + o.b_1;
-    gemm<T>(g, true, false, EPI_BIAS_GELU, s);
+    g.A = h2; g.out = gl; g.out2 = u; g.bias = pf + o.b_1;
+    fwd_gemm(g, o.w_1, d, f, EPI_BIAS_GELU);
     if (y_out) {
         g = GemmParams<T>{};
-        g.A = gl; g.lda = f; g.B = pw + o.w_2; g.ldb = d; g.M = t; g.N = d; g.K = f;
-        g.out = y_out; g.ldc = d; g.bias = pf + o.b_2; g.aux = x1;
-        gemm<T>(g, true, false, EPI_BIAS_RESID, s);
+        g.A = gl; g.out = y_out; g.bias = pf + o.b_2; g.aux = x1;
+        fwd_gemm(g, o.w_2, f, d, EPI_BIAS_RESID);
     }
 }
 
@@ -249,11 +276,23 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     float *partial = st->at<float>(st->plan.partial);
     const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
 
+    // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over the group's tokens.  bf16 mode first
+    // writes X^T [in][t] and dY^T [out][t] (two HBM-bound passes, ~1 % of the GEMM's time) so that the
+    // GEMM reads both operands k-contiguous.
     auto wgrad = [&](const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off) {
         GemmParams<T> g{};
-        g.A = X; g.lda = in; g.B = dY; g.ldb = out; g.M = in; g.N = out; g.K = t;
+        g.M = in; g.N = out; g.K = t;
         g.outf = gbuf + w_off; g.ldc = out; g.beta = beta;
-        gemm<T>(g, false, false, EPI_ACCUM_F32, s);
+        if constexpr (std::is_same<T, float>::value) {
+            g.A = X; g.lda = in; g.B = dY; g.ldb = out;
+            gemm<T>(g, false, false, EPI_ACCUM_F32, s);
+        } else {
+            bf16 *xT = st->at<bf16>(st->plan.xT), *dyT = st->at<bf16>(st->plan.dyT);
+            launch_transpose_bf16(X, xT, t, in, in, t, s);
+            launch_transpose_bf16(dY, dyT, t, out, out, t, s);
+            g.A = xT; g.lda = t; g.B = dyT; g.ldb = t;
+            gemm<T>(g, true, true, EPI_ACCUM_F32, s);
+        }
         launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, out, beta, gbuf + b_off, nullptr, partial, s);
     };
     auto dgrad = [&](const T *dY, int out, size_t w_off, int in, T *dX, Epilogue e, const T *aux) {
@@ -288,6 +327,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
 void adam_layer(lga_stack *st, int l, const lga_adam &hp) {
     launch_adam(st->w(l), st->m(l), st->v(l), st->grad(l), st->cfg.dtype == LGA_BF16 ? st->w16(l) : nullptr, st->P,
                 hp.lr, hp.beta1, hp.beta2, hp.eps, hp.step, st->stream);
+    if (st->cfg.dtype == LGA_BF16) refresh_transposed_weights(st, l);
 }
 
 int check_adam(const lga_adam *a) {
@@ -408,7 +448,8 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
     const uint64_t wsz = cfg->dtype == LGA_BF16 ? 2 : 4;
     // Adam: read w, m, v (12 B), write w, m, v (12 B) and the 16-bit copy; per group the GEMM families
     // read the matrices: forward all four, recompute all but W_2, input gradient all four.
-    const uint64_t adam_param = 24 * P + (cfg->dtype == LGA_BF16 ? 2 * P : 0);
+    // bf16 mode also writes the 16-bit copy (2 B) and re-reads / writes the matrices once for the transposed copy
+    const uint64_t adam_param = 24 * P + (cfg->dtype == LGA_BF16 ? 2 * P + 4 * Pm : 0);
     const uint64_t per_group_param = wsz * (3 * Pm - df);
     if (param_bytes) *param_bytes = L * (adam_param + groups * per_group_param);
     // gradient buffer: first group writes (4 B), later groups read-modify-write (8 B); Adam reads (4 B)
@@ -473,7 +514,10 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
             launch_fill_normal(w + st->lay.w_2, f * d, 0.02f, seed + 3, st->stream);
         }
     }
-    if (cfg->dtype == LGA_BF16) launch_cast_f32_to_bf16(st->w(0), st->w16(0), LP, st->stream);   // restore
+    if (cfg->dtype == LGA_BF16) {
+        launch_cast_f32_to_bf16(st->w(0), st->w16(0), LP, st->stream);   // restore
+        for (int l = 0; l < cfg->n_layers; ++l) refresh_transposed_weights(st, l);
+    }
     if ((e = hipStreamSynchronize(st->stream)) != hipSuccess) return bail(e, "init sync");
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "init kernels");
     *out = st;

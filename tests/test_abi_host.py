@@ -75,7 +75,7 @@ def test_arena_holds_state_checkpoints_and_scratch():
     T = 32 * 2048
     state = 12 * 4 * P                              # appendix C.3: 12 p bytes of fp32 parameters and moments
     one_grad_buffer = 4 * P
-    copies16 = 2 * 4 * P
+    copies16 = 2 * 2 * 4 * P                        # 16-bit weights and their transposed copy
     ckpts = 2 * 5 * T * 12288 + 2 * T * 12288       # L+1 boundaries and the running activation gradient
     total = B.arena_bytes(c)
     assert total > state + one_grad_buffer + copies16 + ckpts

@@ -54,6 +54,12 @@ GEMM_CASES = [
     (BF16, 1, 0, B.LGA_EPI_BIAS_GELU, 190, 264, 128),
     (BF16, 1, 1, B.LGA_EPI_STORE, 300, 200, 392),
     (BF16, 1, 1, B.LGA_EPI_MUL_DGELU, 131, 256, 136),
+    (BF16, 1, 1, B.LGA_EPI_BIAS, 300, 392, 200),
+    (BF16, 1, 1, B.LGA_EPI_BIAS_RESID, 257, 136, 72),
+    (BF16, 1, 1, B.LGA_EPI_BIAS_GELU, 190, 264, 128),
+    (BF16, 1, 1, B.LGA_EPI_ACCUM_F32, 200, 392, 304),
+    (BF16, 1, 1, B.LGA_EPI_ACCUM_F32, 4104, 8200, 200),
+    (BF16, 1, 1, B.LGA_EPI_BIAS_GELU, 4100, 8200, 136),
     (BF16, 0, 0, B.LGA_EPI_ACCUM_F32, 200, 392, 300),
     (BF16, 0, 0, B.LGA_EPI_STORE, 136, 72, 1000),
     # >= 512 tiles of 256x256: the large-tile kernel, with ragged edges in m, n and k
@@ -113,6 +119,20 @@ def test_gemm_against_oracle_matmul(case):
         assert rel_err(outf.cpu().numpy().astype(np.float64)[:, :N], acc) < 1e-5
     if epi != B.LGA_EPI_ACCUM_F32:
         assert np.all(to_host(out)[:, N:] == 0)                                # padding untouched
+
+
+@pytest.mark.parametrize("R,C,pad", [(8, 8, 0), (136, 264, 8), (1000, 128, 0), (128, 3000, 16)])
+def test_transpose(R, C, pad):
+    rng = np.random.default_rng(R * C)
+    a = rnd(rng, (R, C + pad), BF16)
+    ad = to_dev(a, BF16)
+    out = empty_dev((C, R + pad), BF16)
+    out.zero_()
+    B.check(B.lib.lga_op_transpose(ad.data_ptr(), out.data_ptr(), R, C, C + pad, R + pad, None))
+    torch.cuda.synchronize()
+    got = to_host(out)
+    assert np.array_equal(got[:, :R], a[:, :C].T.astype(np.float64))
+    assert np.all(got[:, R:] == 0)
 
 
 def test_gemm_empty_and_rejected_arguments():
