@@ -55,8 +55,9 @@ constexpr float kGeluA = 0.044715f;
 
 __device__ __forceinline__ float tanh_fast(float z) {
     // tanh(z) = 1 - 2 / (exp(2z) + 1); saturates correctly for large |z|
-    const float e = __expf(2.0f * z);
-    return 1.0f - 2.0f / (e + 1.0f);
+    // v_exp_f32 and v_rcp_f32 (1 ulp each) instead of the full-precision exp and division
+    const float e = __builtin_amdgcn_exp2f(z * 2.8853900817779268f);      // exp(2 z) = 2^(2 z log2 e)
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
 }
 __device__ __forceinline__ float gelu_f(float u) {
     const float z = kGeluC * (u + kGeluA * u * u * u);

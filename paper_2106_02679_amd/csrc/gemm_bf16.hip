@@ -17,6 +17,7 @@
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs)
 // works on a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse.
 #include <cstdio>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -25,9 +26,6 @@ namespace lga {
 namespace {
 
 constexpr int BK = 64;           // k elements per stage
-#ifndef LGA_GEMM_DBG
-#define LGA_GEMM_DBG 0           // timing experiments only: 1 = no global loads, 2 = also no LDS stores/barrier, 3 = MFMA only
-#endif
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 4)) & 7; }
 
@@ -289,8 +287,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         const bf16 *a_lds = As(cur), *b_lds = Bs(cur);
         bf16 *a_nxt = As(cur ^ 1), *b_nxt = Bs(cur ^ 1);
 
-        if (LGA_GEMM_DBG < 1) sa.load(a_ptr + (size_t)(kt + 1) * a_step);
-        if (LGA_GEMM_DBG < 3) load_frags(1, a_lds, b_lds, 1);
+        sa.load(a_ptr + (size_t)(kt + 1) * a_step);
+        load_frags(1, a_lds, b_lds, 1);
         mfma_step(0);
         if constexpr (kHints) {
 #pragma unroll
@@ -302,8 +300,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        if (LGA_GEMM_DBG < 1) sb.load(b_ptr + (size_t)(kt + 1) * b_step);
-        if (LGA_GEMM_DBG < 3) load_frags(0, a_lds, b_lds, 2);
+        sb.load(b_ptr + (size_t)(kt + 1) * b_step);
+        load_frags(0, a_lds, b_lds, 2);
         mfma_step(1);
         if constexpr (kHints) {
 #pragma unroll
@@ -315,7 +313,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        if (LGA_GEMM_DBG < 3) load_frags(1, a_lds, b_lds, 3);
+        load_frags(1, a_lds, b_lds, 3);
         mfma_step(0);
         if constexpr (kHints) {
 #pragma unroll
@@ -326,10 +324,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        if (LGA_GEMM_DBG < 2) {
-            sa.store(a_nxt);
-            sb.store(b_nxt);
-        }
+        sa.store(a_nxt);
+        sb.store(b_nxt);
         mfma_rows(1, 0, FM / 2);
         if constexpr (kHints) {
 #pragma unroll
@@ -339,10 +335,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (LGA_GEMM_DBG < 2) __syncthreads();
+        __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
 
-        if (LGA_GEMM_DBG < 3) load_frags(0, a_nxt, b_nxt, 0);
+        load_frags(0, a_nxt, b_nxt, 0);
         mfma_rows(1, FM / 2, FM);
         if constexpr (kHints) {
 #pragma unroll
@@ -394,20 +390,205 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
     }
 }
 
+// ============================================================================================
+// Both operands k-contiguous: global -> LDS without passing through registers.
+//
+// `buffer_load_dwordx4 ... lds` writes lane L's 16 bytes at (LDS base in M0) + 16 L, so one
+// wavefront instruction fills 8 consecutive 128-byte tile rows.  The XOR swizzle of the tile is
+// obtained on the global side: lane L, which lands in physical chunk L%8 of row r, fetches logical
+// chunk (L%8) ^ swz(r) of that row.  No staging registers, no LDS store instructions, no waits on
+// individual loads: the next k tile streams into the other LDS stage while this one is multiplied,
+// and one vmcnt(0) + barrier per tile publishes it.
+template <int BM, int BN, int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParams<bf16> p, int tiles_m, int tiles_n) {
+    constexpr int NW = WGM * WGN;                   // wavefronts per workgroup, WGM x WGN over the tile
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int NIA = BM / (8 * NW), NIB = BN / (8 * NW);     // DMA instructions per wavefront per operand tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    auto As = [&](int s) { return lds + (size_t)s * (BM + BN) * BK; };
+    auto Bs = [&](int s) { return lds + (size_t)s * (BM + BN) * BK + BM * BK; };
+
+    const int ntiles = tiles_m * tiles_n;
+    int tile;
+    {
+        const int pid = blockIdx.x, xcd = pid & 7, local = pid >> 3;
+        const int base = ntiles >> 3, rem = ntiles & 7;
+        tile = xcd * base + (xcd < rem ? xcd : rem) + local;
+    }
+    constexpr int GROUP_M = 8;
+    const int group_size = GROUP_M * tiles_n;
+    const int gid = tile / group_size;
+    const int first_m = gid * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int tm = first_m + (tile % group_size) % gsz;
+    const int tn = (tile % group_size) / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // Loop-invariant per-lane byte offsets of the DMA loads inside an operand tile (or the poison
+    // offset for rows beyond the matrix, which the hardware answers with zeros).
+    const int lda2 = p.lda * 2, ldb2 = p.ldb * 2;
+    int offA[NIA], offB[NIB];
+#pragma unroll
+    for (int i = 0; i < NIA; ++i) {
+        const int r = (i * NW + wave) * 8 + (lane >> 3);
+        offA[i] = (m0 + r < p.M) ? r * lda2 + (((lane & 7) ^ swz(r)) << 4) : kBufPoison;
+    }
+#pragma unroll
+    for (int i = 0; i < NIB; ++i) {
+        const int r = (i * NW + wave) * 8 + (lane >> 3);
+        offB[i] = (n0 + r < p.N) ? r * ldb2 + (((lane & 7) ^ swz(r)) << 4) : kBufPoison;
+    }
+    const bf16 *a_ptr = p.A + (size_t)m0 * p.lda;
+    const bf16 *b_ptr = p.B + (size_t)n0 * p.ldb;
+    const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
+
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+    // The NIA + NIB DMA instructions of one k tile (A's first, then B's), issued in slices [j0, j1) so that
+    // they can be spread over a whole iteration: the CU's texture-address unit needs 16 cycles for each.
+    // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
+    constexpr int NI = NIA + NIB;
+    auto dma_slice = [&](int stage, int kt, int krem, int j0, int j1) {
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_ptr + (size_t)kt * BK);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_ptr + (size_t)kt * BK);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            if (j < j0 || j >= j1) continue;
+            const bool is_a = j < NIA;
+            const int i = is_a ? j : j - NIA;
+            int off = is_a ? offA[i] : offB[i];
+            if (krem < BK) off |= ((((lane & 7) ^ swz((i * NW + wave) * 8 + (lane >> 3))) * 8 < krem) ? 0 : kBufPoison);
+            bf16 *dst = (is_a ? As(stage) : Bs(stage)) + (i * NW + wave) * 8 * BK;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? ra : rb, (lds_ptr)dst, 16, off, 0, 0, 0);
+        }
+    };
+    // MFMA operands of the four k steps of a tile, one register buffer each: a step's operands are read
+    // from LDS two steps (32 MFMAs) ahead, which rides out the LDS latency spikes that the incoming DMA
+    // traffic causes.
+    bf16x8 af[4][FM], bf[4][FN];
+    auto load_frags = [&](int ks, int stage) {
+        const bf16 *a_lds = As(stage), *b_lds = Bs(stage);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+            af[ks][i] = *reinterpret_cast<const bf16x8 *>(a_lds + lds_off(wm * WM + i * 32 + lrow, 2 * ks + lhalf));
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            bf[ks][j] = *reinterpret_cast<const bf16x8 *>(b_lds + lds_off(wn * WN + j * 32 + lrow, 2 * ks + lhalf));
+    };
+    auto mfma_step = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+    };
+    constexpr int kWaitVm0 = 0x0F70;     // s_waitcnt vmcnt(0) only (expcnt and lgkmcnt fields at their maximum)
+
+    // prologue: tile 0 published, tile 1 in flight, operands of steps 0 and 1 in registers
+    dma_slice(0, 0, p.K, 0, NI);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __syncthreads();
+    if (nk > 1) dma_slice(1, 1, p.K - BK, 0, NI);
+    load_frags(0, 0);
+    load_frags(1, 0);
+
+    constexpr int NMF = FM * FN, NDR = FM + FN;
+    // Issue pattern: after MFMA number i of a group of `nm`, the share of `n` other instructions (mask) that
+    // keeps them evenly spread (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 LDS read).
+#define LGA_SPREAD(mask, n, nm, i)                                                         \
+    do {                                                                                    \
+        if ((((i) + 1) * (n)) / (nm) - ((i) * (n)) / (nm) >= 1) __builtin_amdgcn_sched_group_barrier(mask, 1, 0); \
+        if ((((i) + 1) * (n)) / (nm) - ((i) * (n)) / (nm) >= 2) __builtin_amdgcn_sched_group_barrier(mask, 1, 0); \
+    } while (0)
+#define LGA_STEP_HINTS(nvm)                                        \
+    _Pragma("unroll") for (int i = 0; i < NMF; ++i) {              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         \
+        LGA_SPREAD(0x020, nvm, NMF, i);                            \
+        LGA_SPREAD(0x100, NDR, NMF, i);                            \
+    }                                                              \
+    __builtin_amdgcn_sched_barrier(0)
+
+    // One k tile.  STRAIGHT: tiles kt+1 and kt+2 exist and are full, so nothing is tested.
+    //   step 0: MFMAs | LDS reads of step 2's operands
+    //   step 1: MFMAs | LDS reads of step 3's operands
+    //   vmcnt(0) + barrier: tile kt+1 (loaded since the previous iteration's step 2) is published, and nobody
+    //   reads this tile's stage any more
+    //   step 2: MFMAs | first half of the loads of tile kt+2, into this tile's stage | LDS reads of tile kt+1's step 0
+    //   step 3: MFMAs | second half of those loads | LDS reads of tile kt+1's step 1
+    auto k_tile = [&](int kt, auto straight_c) {
+        constexpr bool STRAIGHT = decltype(straight_c)::value;
+        const int cur = kt & 1;
+        const bool more1 = STRAIGHT || kt + 1 < nk, more2 = STRAIGHT || kt + 2 < nk;
+        const int krem2 = STRAIGHT ? BK : p.K - (kt + 2) * BK;
+
+        load_frags(2, cur);
+        mfma_step(0);
+        if constexpr (STRAIGHT) { LGA_STEP_HINTS(0); }
+        load_frags(3, cur);
+        mfma_step(1);
+        if constexpr (STRAIGHT) { LGA_STEP_HINTS(0); }
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        if (more2) dma_slice(cur, kt + 2, krem2, 0, NI / 2);
+        if (more1) load_frags(0, cur ^ 1);
+        mfma_step(2);
+        if constexpr (STRAIGHT) { LGA_STEP_HINTS(NI / 2); }
+        if (more2) dma_slice(cur, kt + 2, krem2, NI / 2, NI);
+        if (more1) load_frags(1, cur ^ 1);
+        mfma_step(3);
+        if constexpr (STRAIGHT) { LGA_STEP_HINTS(NI - NI / 2); }
+    };
+    int kt = 0;
+    for (; kt + 2 < nk_full; ++kt) k_tile(kt, std::true_type{});      // straight-line main loop
+    for (; kt < nk; ++kt) k_tile(kt, std::false_type{});              // the last tiles, with tests
+#undef LGA_STEP_HINTS
+#undef LGA_SPREAD
+
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int m = m0 + wm * WM + i * 32 + lrow;
+        if (m >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * lhalf;
+                if (n >= p.N) continue;
+                const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                epilogue4<EPI>(p, m, n, v);
+            }
+        }
+    }
+}
+
 template <int BM, int BN, bool A_KM, bool B_KM, int EPI>
 void launch_one(const GemmParams<bf16> &p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
-    auto kern = gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI>;
-    static bool attr_set = false;   // per instantiation
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)smem);
-        attr_set = true;
-    }
+    void (*kern)(GemmParams<bf16>, int, int) = gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI>;
+    if constexpr (A_KM && B_KM && BM == 256) kern = gemm_bf16_dma_kernel<BM, BN, 2, 2, EPI>;
     char name[96];
-    snprintf(name, sizeof(name), "gemm_bf16_kernel<%d, %d, %s, %s, %d>", BM, BN, A_KM ? "true" : "false",
-             B_KM ? "true" : "false", EPI);
+    if (A_KM && B_KM && BM == 256)
+        snprintf(name, sizeof(name), "gemm_bf16_dma_kernel<%d, %d, %d>", BM, BN, EPI);
+    else
+        snprintf(name, sizeof(name), "gemm_bf16_kernel<%d, %d, %s, %s, %d>", BM, BN, A_KM ? "true" : "false",
+                 B_KM ? "true" : "false", EPI);
     const double mn = (double)p.M * p.N;
     const double out_bytes = EPI == EPI_ACCUM_F32 ? (p.beta != 0.f ? 8.0 : 4.0) : (EPI == EPI_BIAS_GELU ? 4.0 : 2.0);
     const double aux_bytes = (EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU) ? 2.0 : 0.0;
