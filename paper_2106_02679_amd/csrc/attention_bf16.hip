@@ -347,19 +347,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
 
 // ============================================================================================
 // dK, dV.  grid.x = key blocks of 128 (smallest index first: it has the most queries), grid.y = n_seq * heads.
+// Query tiles of 64 are streamed through LDS.  Each thread owns 8x8 blocks of Q and dO: it loads them once
+// from global memory (prefetched into registers one tile ahead, under the previous tile's MFMAs) and stores
+// them twice, as they are and transposed.
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
                                                            const float *__restrict__ delta,
                                                            const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
                                                            AttnShape sh) {
-    constexpr int QT = 32;
+    constexpr int QT = 64;
     constexpr int NK = DH / 16, NC = DH / 32;
-    __shared__ __attribute__((aligned(16))) bf16 Qs[QT * DH];
-    __shared__ __attribute__((aligned(16))) bf16 dOs[QT * DH];
-    __shared__ __attribute__((aligned(16))) bf16 Qt[DH * QT];
-    __shared__ __attribute__((aligned(16))) bf16 dOt[DH * QT];
-    __shared__ __attribute__((aligned(16))) float lse_s[QT];
-    __shared__ __attribute__((aligned(16))) float dl_s[QT];
+    constexpr int NBLK = 2 * (QT / 8) * (DH / 8);       // 8x8 blocks of Q and of dO per tile
+    constexpr int NB = (NBLK + 255) / 256;              // blocks per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *Qs = reinterpret_cast<bf16 *>(smem_raw);      // [QT][DH]
+    bf16 *dOs = Qs + QT * DH;                           // [QT][DH]
+    bf16 *Qt = dOs + QT * DH;                           // [DH][QT]
+    bf16 *dOt = Qt + QT * DH;                           // [DH][QT]
+    float *lse_s = reinterpret_cast<float *>(dOt + QT * DH);   // [QT]
+    float *dl_s = lse_s + QT;                                   // [QT]
 
     const int kb128 = blockIdx.x;
     const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
@@ -389,50 +395,97 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) dk[c][r] = dv[c][r] = 0.f;
 
-    // queries that can see any key of this block: [kb128*128, s), walked in tiles of 32
-    for (int q0 = kb128 * 128; q0 < sh.s; q0 += QT) {
-        __syncthreads();
-        load_nat<QT, DH>(Qs, seq + (size_t)q0 * pitch, pitch, sh.s - q0);
-        load_nat<QT, DH>(dOs, doseq + (size_t)q0 * d, d, sh.s - q0);
-        load_tr<QT, DH>(Qt, seq + (size_t)q0 * pitch, pitch, sh.s - q0);
-        load_tr<QT, DH>(dOt, doseq + (size_t)q0 * d, d, sh.s - q0);
-        if (threadIdx.x < QT) {
-            const int qq = q0 + threadIdx.x;
-            lse_s[threadIdx.x] = qq < sh.s ? lse[stat0 + qq] * kLog2e : 0.f;
-            dl_s[threadIdx.x] = qq < sh.s ? delta[stat0 + qq] : 0.f;
-        }
-        __syncthreads();
-        if (q0 + QT - 1 < kw0) continue;            // every query of the tile precedes this wavefront's keys
-        f32x16 s_, dp;
+    // staging: block blk < NBLK/2 belongs to Q, the rest to dO; (pb, db) = (8-row group, 8-column group)
+    u32x4 stg[NB][8];
+    float stg_lse = 0.f, stg_dl = 0.f;
+    auto prefetch = [&](int q0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s_[r] = dp[r] = 0.f;
+        for (int r = 0; r < NB; ++r) {
+            const int blk = threadIdx.x + 256 * r;
+            const bool is_q = blk < NBLK / 2;
+            const int bb = is_q ? blk : blk - NBLK / 2;
+            const int db = bb % (DH / 8), pb = bb / (DH / 8);
+            const bf16 *src = is_q ? seq + (size_t)q0 * pitch : doseq + (size_t)q0 * d;
+            const size_t sp = is_q ? pitch : (size_t)d;
 #pragma unroll
-        for (int ks = 0; ks < NK; ++ks) {
-            s_ = MFMA(frag_nat<DH>(Qs, lrow, ks, half), kf[ks], s_);
-            dp = MFMA(frag_nat<DH>(dOs, lrow, ks, half), vf[ks], dp);
-        }
-        f32x16 pr;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + 8 * g + 4 * half);
-            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dl_s + 8 * g + 4 * half);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = 4 * g + i;
-                const int qq = q0 + 8 * g + 4 * half + i;
-                const float p = (qq >= key && qq < sh.s && kvalid) ? __builtin_amdgcn_exp2f(fmaf(s_[r], c2, -l4[i])) : 0.f;
-                pr[r] = p;
-                s_[r] = p * (dp[r] - d4[i]);
+            for (int j = 0; j < 8; ++j) {
+                const int row = pb * 8 + j;
+                stg[r][j] = u32x4{0, 0, 0, 0};
+                if (blk < NBLK && q0 + row < sh.s)
+                    stg[r][j] = *reinterpret_cast<const u32x4 *>(src + (size_t)row * sp + db * 8);
             }
         }
+        if (threadIdx.x < QT) {
+            const int qq = q0 + threadIdx.x;
+            stg_lse = qq < sh.s ? lse[stat0 + qq] * kLog2e : 0.f;
+            stg_dl = qq < sh.s ? delta[stat0 + qq] : 0.f;
+        }
+    };
+    auto commit = [&]() {
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 pf = pack_bf16(pr, kk);
-            const bf16x8 dsf = pack_bf16(s_, kk);
+        for (int r = 0; r < NB; ++r) {
+            const int blk = threadIdx.x + 256 * r;
+            if (blk >= NBLK) continue;
+            const bool is_q = blk < NBLK / 2;
+            const int bb = is_q ? blk : blk - NBLK / 2;
+            const int db = bb % (DH / 8), pb = bb / (DH / 8);
+            bf16 *nat = is_q ? Qs : dOs, *tr = is_q ? Qt : dOt;
+            u32x4 t[8];
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                dv[c] = MFMA(frag_tr<QT>(dOt, c * 32 + lrow, kk, half), pf, dv[c]);
-                dk[c] = MFMA(frag_tr<QT>(Qt, c * 32 + lrow, kk, half), dsf, dk[c]);
+            for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4 *>(nat + nat_off<DH>(pb * 8 + j, db)) = stg[r][j];
+            transpose8x8(stg[r], t);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(tr + tr_off<QT>(db * 8 + c, pb)) = t[c];
+        }
+        if (threadIdx.x < QT) {
+            lse_s[threadIdx.x] = stg_lse;
+            dl_s[threadIdx.x] = stg_dl;
+        }
+    };
+
+    // queries that can see any key of this block: [kb128*128, s), walked in tiles of 64
+    const int qbeg = kb128 * 128;
+    prefetch(qbeg);
+    for (int q0 = qbeg; q0 < sh.s; q0 += QT) {
+        __syncthreads();                 // everyone is done with the previous tile
+        commit();
+        __syncthreads();
+        if (q0 + QT < sh.s) prefetch(q0 + QT);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int qs = q0 + qb * 32;                 // first query of this 32-query sub-tile
+            if (qs + 31 < kw0 || qs >= sh.s) continue;   // all its queries precede this wavefront's keys, or are past the end
+            f32x16 s_, dp;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s_[r] = dp[r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < NK; ++ks) {
+                s_ = MFMA(frag_nat<DH>(Qs, qb * 32 + lrow, ks, half), kf[ks], s_);
+                dp = MFMA(frag_nat<DH>(dOs, qb * 32 + lrow, ks, half), vf[ks], dp);
+            }
+            f32x16 pr;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + qb * 32 + 8 * g + 4 * half);
+                const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dl_s + qb * 32 + 8 * g + 4 * half);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 4 * g + i;
+                    const int qq = qs + 8 * g + 4 * half + i;
+                    const float p = (qq >= key && qq < sh.s && kvalid) ? __builtin_amdgcn_exp2f(fmaf(s_[r], c2, -l4[i])) : 0.f;
+                    pr[r] = p;
+                    s_[r] = p * (dp[r] - d4[i]);
+                }
+            }
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 pf = pack_bf16(pr, kk);
+                const bf16x8 dsf = pack_bf16(s_, kk);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) {
+                    dv[c] = MFMA(frag_tr<QT>(dOt, c * 32 + lrow, 2 * qb + kk, half), pf, dv[c]);
+                    dk[c] = MFMA(frag_tr<QT>(Qt, c * 32 + lrow, 2 * qb + kk, half), dsf, dk[c]);
+                }
             }
         }
     }
@@ -478,7 +531,14 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
     {
         snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
         ProfScope scope(name, 8.0 * pairs * DH, 6.0 * act, s);
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+        constexpr int smem = 4 * 64 * DH * 2 + 2 * 64 * 4;      // four 64 x DH tiles and the row statistics
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_kernel<DH>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH>), grid, dim3(256), smem, s, qkv, lse, delta, dout, dqkv, sh);
     }
 }
 
