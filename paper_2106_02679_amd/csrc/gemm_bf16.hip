@@ -1,21 +1,25 @@
-// bf16 MFMA GEMM for gfx950, fp32 accumulate: C[M,N] = sum_k A(m,k) B(k,n) + epilogue.
+// bf16 MFMA GEMMs for gfx950, fp32 accumulate: C[M,N] = sum_k A(m,k) B(k,n) + epilogue.
 //
-// One kernel template serves the three GEMM families of a transformer layer:
-//   forward          Y[t,out]  = X[t,in]  W[in,out]      A k-major, B n-major
-//   input gradient   dX[t,in]  = dY[t,out] W[in,out]^T    A k-major, B k-major
-//   weight gradient  dW[in,out] (+)= X[t,in]^T dY[t,out]  A m-major, B n-major, K = tokens
-// (appendix C.1: each is 2 flop per token per parameter).
+// The three GEMM families of a transformer layer (appendix C.1: each is 2 flop per token per parameter)
+//   forward          Y[t,out]  = X[t,in]  W[in,out]
+//   input gradient   dX[t,in]  = dY[t,out] W[in,out]^T
+//   weight gradient  dW[in,out] (+)= X[t,in]^T dY[t,out]      K = tokens of the micro-batch group
+// are all run by the layer stack with BOTH operands k-contiguous (it keeps a transposed 16-bit copy of
+// every weight matrix and transposes the two operands of a weight-gradient GEMM beforehand).  That layout
+// is served by gemm_bf16_dma_kernel: 256 threads = 4 wavefronts (2x2) on a 256x256x64 tile,
+// v_mfma_f32_32x32x16_bf16, tiles moved global -> LDS without passing through registers.
 //
-// Design: 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN block tile, K step 64,
-// v_mfma_f32_32x32x16_bf16.  Both operands sit in LDS k-contiguous (8 chunks of 16 B per row,
-// XOR-swizzled against bank conflicts), so every MFMA operand is one 16-byte LDS read.  An
-// operand that is not k-contiguous in HBM is transposed in registers (8x8 blocks of 16-bit
-// values) on its way from global memory to LDS.  Two LDS stages; the global loads of tile
-// k+1 are in flight while tile k is multiplied.  The MFMA is issued with the B tile as its
-// first operand so that each lane ends up with 4 consecutive n of one row m: row-major
-// stores are then 8 bytes (bf16) or 16 bytes (fp32) per lane.
-// Workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs)
-// works on a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse.
+// gemm_bf16_kernel is the register-staged predecessor and still serves the other operand layouts of
+// the op-level API and the small (128x128-tile) problems: both operands sit in LDS k-contiguous
+// (8 chunks of 16 B per row, XOR-swizzled against bank conflicts), so every MFMA operand is one 16-byte
+// LDS read; an operand that is not k-contiguous in HBM is transposed in registers (8x8 blocks of 16-bit
+// values) on its way from global memory to LDS; two LDS stages; the global loads of tile k+1 are in
+// flight while tile k is multiplied.
+//
+// Common to both: the MFMA is issued with the B tile as its first operand so that each lane ends up with
+// 4 consecutive n of one row m (row-major stores of 8 bytes (bf16) or 16 bytes (fp32) per lane, epilogues
+// fused); workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) works on
+// a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse.
 #include <cstdio>
 #include <type_traits>
 

@@ -31,6 +31,16 @@ def rel_err(a: np.ndarray, ref: np.ndarray) -> float:
     return float(num / den) if den > 0 else float(num)
 
 
+def updatable_mask(w: S.Workload) -> np.ndarray:
+    """Entries of a layer's flat parameter vector whose Adam update is well defined: everything but
+    the key third of b_qkv, whose gradient is identically zero (softmax ignores a per-row score shift),
+    so that its first-step update lr*g/(|g|+eps) is +-lr times the sign of rounding noise."""
+    sl = S.tensor_slices(w.d_model, w.d_ff)
+    keep = np.ones(w.params_per_layer, dtype=bool)
+    keep[sl["b_qkv"].start + w.d_model: sl["b_qkv"].start + 2 * w.d_model] = False
+    return keep
+
+
 def dtype_code(w: S.Workload) -> int:
     return B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
 
