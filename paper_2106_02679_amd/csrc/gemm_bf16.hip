@@ -409,10 +409,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / 32, FN = WN / 32;
     constexpr int NIA = BM / (8 * NW), NIB = BN / (8 * NW);     // DMA instructions per wavefront per operand tile
+    static_assert(BM == BN, "the operand ring below uses one slot size for both operands");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
-    auto As = [&](int s) { return lds + (size_t)s * (BM + BN) * BK; };
-    auto Bs = [&](int s) { return lds + (size_t)s * (BM + BN) * BK + BM * BK; };
+    // LDS is a ring of kSlots operand tiles of BM x BK.  Operand tiles enter it in the order A(0), B(0), A(1),
+    // B(1), ...: A(kt) sits in slot (2 kt) mod kSlots and B(kt) in the next one.  Five slots hold two whole k
+    // tiles plus half of a third, which is what lets the loads of A(kt+2) start before tile kt is retired.
+    constexpr int kSlots = 5;
+    constexpr int kSlotElems = BM * BK;
+    auto slot = [&](int q) { return lds + q * kSlotElems; };
+    auto wrap = [](int q) { return q >= kSlots ? q - kSlots : q; };
 
     const int ntiles = tiles_m * tiles_n;
     int tile;
@@ -462,107 +468,124 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
 
     typedef __attribute__((address_space(3))) void *lds_ptr;
-    // The NIA + NIB DMA instructions of one k tile (A's first, then B's), issued in slices [j0, j1) so that
-    // they can be spread over a whole iteration: the CU's texture-address unit needs 16 cycles for each.
+    // DMA instructions [j0, j1) of one operand tile (k tile kt of A or of B) into ring slot q.  They are issued
+    // in slices so that they can be spread over the whole iteration: the CU's texture-address unit needs at
+    // least 16 cycles for each, and a wavefront whose load finds its queue full stalls, MFMAs included.
     // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
-    constexpr int NI = NIA + NIB;
-    auto dma_slice = [&](int stage, int kt, int krem, int j0, int j1) {
-        const __amdgpu_buffer_rsrc_t ra = make_rsrc(a_ptr + (size_t)kt * BK);
-        const __amdgpu_buffer_rsrc_t rb = make_rsrc(b_ptr + (size_t)kt * BK);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            if (j < j0 || j >= j1) continue;
-            const bool is_a = j < NIA;
-            const int i = is_a ? j : j - NIA;
-            int off = is_a ? offA[i] : offB[i];
-            if (krem < BK) off |= ((((lane & 7) ^ swz((i * NW + wave) * 8 + (lane >> 3))) * 8 < krem) ? 0 : kBufPoison);
-            bf16 *dst = (is_a ? As(stage) : Bs(stage)) + (i * NW + wave) * 8 * BK;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_a ? ra : rb, (lds_ptr)dst, 16, off, 0, 0, 0);
-        }
+    // One DMA instruction: rows [(i NW + wave) 8, +8) of operand tile kt (A if is_a, else B) into ring slot q.
+    // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
+    auto dma_one = [&](bool is_a, int q, int kt, int krem, int i) {
+        const __amdgpu_buffer_rsrc_t r = make_rsrc((is_a ? a_ptr : b_ptr) + (size_t)kt * BK);
+        int off = is_a ? offA[i] : offB[i];
+        if (krem < BK) off |= ((((lane & 7) ^ swz((i * NW + wave) * 8 + (lane >> 3))) * 8 < krem) ? 0 : kBufPoison);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)(slot(q) + (i * NW + wave) * 8 * BK), 16, off, 0, 0, 0);
     };
     // MFMA operands of the four k steps of a tile, one register buffer each: a step's operands are read
     // from LDS two steps (32 MFMAs) ahead, which rides out the LDS latency spikes that the incoming DMA
-    // traffic causes.
+    // traffic causes.  qa is the ring slot of the tile's A operand; its B operand is in the next slot.
     bf16x8 af[4][FM], bf[4][FN];
-    auto load_frags = [&](int ks, int stage) {
-        const bf16 *a_lds = As(stage), *b_lds = Bs(stage);
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-            af[ks][i] = *reinterpret_cast<const bf16x8 *>(a_lds + lds_off(wm * WM + i * 32 + lrow, 2 * ks + lhalf));
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-            bf[ks][j] = *reinterpret_cast<const bf16x8 *>(b_lds + lds_off(wn * WN + j * 32 + lrow, 2 * ks + lhalf));
+    // LDS byte address of an operand chunk, kept to one register per operand: with 128-row wavefront tiles the
+    // swizzle term of row (tile row 0 + 32 i + lrow) is (lane part) ^ (2 i), so chunk 2 ks + lhalf of block i
+    // lies at (lane address) ^ (((2 ks) ^ (2 i)) << 4) plus a compile-time offset.
+    static_assert(WM % 128 == 0 && WN % 128 == 0, "swizzle split below assumes 128-row wavefront tiles");
+    const int lane_sw = lhalf ^ ((lrow >> 1) & 7) ^ (lrow >> 4);
+    const int lane_a = ((wm * WM + lrow) * BK + lane_sw * 8) * 2;
+    const int lane_b = ((wn * WN + lrow) * BK + lane_sw * 8) * 2;
+    // operand f of step ks (f < FM: A block f, else B block f - FM) of the tile whose A operand is in slot qa
+    auto load_frag = [&](int ks, int qa, int f) {
+        if (f < FM) {
+            const int va = lane_a + qa * (kSlotElems * 2);
+            af[ks][f] = *reinterpret_cast<const bf16x8 *>(smem_raw + ((va ^ ((((2 * ks) ^ (2 * f)) & 7) << 4)) + f * 32 * BK * 2));
+        } else {
+            const int j = f - FM, vb = lane_b + wrap(qa + 1) * (kSlotElems * 2);
+            bf[ks][j] = *reinterpret_cast<const bf16x8 *>(smem_raw + ((vb ^ ((((2 * ks) ^ (2 * j)) & 7) << 4)) + j * 32 * BK * 2));
+        }
     };
-    auto mfma_step = [&](int ks) {
+    auto load_frags = [&](int ks, int qa) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+        for (int f = 0; f < FM + FN; ++f) load_frag(ks, qa, f);
     };
-    constexpr int kWaitVm0 = 0x0F70;     // s_waitcnt vmcnt(0) only (expcnt and lgkmcnt fields at their maximum)
+    // s_waitcnt immediates (vmcnt in bits 3:0, expcnt 6:4 left at its maximum, lgkmcnt 11:8 = 0): all LDS reads
+    // returned and every load landed, or every load but the newest NIA landed.
+    constexpr int kWaitVm0 = 0x0070;
+    static_assert(NIA < 16, "vmcnt immediate below uses the low four bits only");
+    constexpr int kWaitVmA = 0x0070 | NIA;
 
     // prologue: tile 0 published, tile 1 in flight, operands of steps 0 and 1 in registers
-    dma_slice(0, 0, p.K, 0, NI);
+#pragma unroll
+    for (int i = 0; i < NIA; ++i) dma_one(true, 0, 0, p.K, i);
+#pragma unroll
+    for (int i = 0; i < NIB; ++i) dma_one(false, 1, 0, p.K, i);
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();
-    if (nk > 1) dma_slice(1, 1, p.K - BK, 0, NI);
+    if (nk > 1) {
+#pragma unroll
+        for (int i = 0; i < NIA; ++i) dma_one(true, 2, 1, p.K - BK, i);
+#pragma unroll
+        for (int i = 0; i < NIB; ++i) dma_one(false, 3, 1, p.K - BK, i);
+    }
     load_frags(0, 0);
     load_frags(1, 0);
 
-    constexpr int NMF = FM * FN, NDR = FM + FN;
-    // Issue pattern: after MFMA number i of a group of `nm`, the share of `n` other instructions (mask) that
-    // keeps them evenly spread (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 LDS read).
-#define LGA_SPREAD(mask, n, nm, i)                                                         \
-    do {                                                                                    \
-        if ((((i) + 1) * (n)) / (nm) - ((i) * (n)) / (nm) >= 1) __builtin_amdgcn_sched_group_barrier(mask, 1, 0); \
-        if ((((i) + 1) * (n)) / (nm) - ((i) * (n)) / (nm) >= 2) __builtin_amdgcn_sched_group_barrier(mask, 1, 0); \
-    } while (0)
-#define LGA_STEP_HINTS(nvm)                                        \
-    _Pragma("unroll") for (int i = 0; i < NMF; ++i) {              \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         \
-        LGA_SPREAD(0x020, nvm, NMF, i);                            \
-        LGA_SPREAD(0x100, NDR, NMF, i);                            \
-    }                                                              \
-    __builtin_amdgcn_sched_barrier(0)
+    // One k step = FM groups of FN MFMAs (one A block against all B blocks).  After each group the wavefront
+    // issues its share of the step's other work: DMA instructions [g DPG, (g+1) DPG) of operand tile `dkt`
+    // and two of the 8 LDS operand reads for step `rks`.  The order is pinned (sched_barrier) because the
+    // compiler otherwise clumps the loads, and a wavefront that issues several loads in a row right after the
+    // barrier, together with the three others, finds the load queue full and stalls with its MFMAs behind it.
+    static_assert(NIA % (2 * FM) == 0 && NIB % (2 * FM) == 0 && (FM + FN) % FM == 0, "work shares per MFMA group");
+    constexpr int RPG = (FM + FN + FM - 2) / (FM - 1);      // LDS reads after each group but the last, which gets none
+    auto k_step = [&](int ks, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, int dfirst, int dpg,
+                      bool do_read, int rks, int rqa) {
+#pragma unroll
+        for (int g = 0; g < FM; ++g) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                acc[g][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks][j], af[ks][g], acc[g][j], 0, 0, 0);
+            if (do_dma) {
+#pragma unroll
+                for (int u = 0; u < dpg; ++u) dma_one(dma_is_a, dq, dkt, dkrem, dfirst + g * dpg + u);
+            }
+            if (do_read) {
+#pragma unroll
+                for (int f = g * RPG; f < (g + 1) * RPG && f < FM + FN; ++f) load_frag(rks, rqa, f);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
 
-    // One k tile.  STRAIGHT: tiles kt+1 and kt+2 exist and are full, so nothing is tested.
-    //   step 0: MFMAs | LDS reads of step 2's operands
-    //   step 1: MFMAs | LDS reads of step 3's operands
-    //   vmcnt(0) + barrier: tile kt+1 (loaded since the previous iteration's step 2) is published, and nobody
-    //   reads this tile's stage any more
-    //   step 2: MFMAs | first half of the loads of tile kt+2, into this tile's stage | LDS reads of tile kt+1's step 0
-    //   step 3: MFMAs | second half of those loads | LDS reads of tile kt+1's step 1
-    auto k_tile = [&](int kt, auto straight_c) {
+    // One k tile whose A operand is in ring slot qa.  STRAIGHT: tiles kt+1 and kt+2 exist and are full, so
+    // nothing is tested.  Every step issues the same mix, so the load queue never sees a burst:
+    //   step 0: MFMAs | LDS reads of step 2's operands | first half of A(kt+2)'s loads, into the free slot
+    //   step 1: MFMAs | LDS reads of step 3's operands | second half of A(kt+2)'s loads
+    //   wait for all loads but A(kt+2)'s + barrier: tile kt+1 is published, and nobody reads tile kt's slots
+    //   any more
+    //   step 2: MFMAs | LDS reads of tile kt+1's step 0 | first half of B(kt+2)'s loads, into A(kt)'s slot
+    //   step 3: MFMAs | LDS reads of tile kt+1's step 1 | second half of B(kt+2)'s loads
+    auto k_tile = [&](int kt, int qa, auto straight_c) {
         constexpr bool STRAIGHT = decltype(straight_c)::value;
-        const int cur = kt & 1;
         const bool more1 = STRAIGHT || kt + 1 < nk, more2 = STRAIGHT || kt + 2 < nk;
         const int krem2 = STRAIGHT ? BK : p.K - (kt + 2) * BK;
+        const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);      // A(kt+1), A(kt+2); B(kt+2) goes to qa
+        constexpr int DA = NIA / (2 * FM), DB = NIB / (2 * FM);
 
-        load_frags(2, cur);
-        mfma_step(0);
-        if constexpr (STRAIGHT) { LGA_STEP_HINTS(0); }
-        load_frags(3, cur);
-        mfma_step(1);
-        if constexpr (STRAIGHT) { LGA_STEP_HINTS(0); }
+        k_step(0, more2, true, qa2, kt + 2, krem2, 0, DA, true, 2, qa);
+        k_step(1, more2, true, qa2, kt + 2, krem2, NIA / 2, DA, true, 3, qa);
+        // A bare s_barrier: __syncthreads() would add a fence that waits for every load, A(kt+2)'s included.
+        // The LDS reads above must have returned before other wavefronts may overwrite those slots.
+        if (more2)
+            __builtin_amdgcn_s_waitcnt(kWaitVmA);
+        else
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        if (more2) dma_slice(cur, kt + 2, krem2, 0, NI / 2);
-        if (more1) load_frags(0, cur ^ 1);
-        mfma_step(2);
-        if constexpr (STRAIGHT) { LGA_STEP_HINTS(NI / 2); }
-        if (more2) dma_slice(cur, kt + 2, krem2, NI / 2, NI);
-        if (more1) load_frags(1, cur ^ 1);
-        mfma_step(3);
-        if constexpr (STRAIGHT) { LGA_STEP_HINTS(NI - NI / 2); }
+        k_step(2, more2, false, qa, kt + 2, krem2, 0, DB, more1, 0, qa1);
+        k_step(3, more2, false, qa, kt + 2, krem2, NIB / 2, DB, more1, 1, qa1);
     };
-    int kt = 0;
-    for (; kt + 2 < nk_full; ++kt) k_tile(kt, std::true_type{});      // straight-line main loop
-    for (; kt < nk; ++kt) k_tile(kt, std::false_type{});              // the last tiles, with tests
-#undef LGA_STEP_HINTS
-#undef LGA_SPREAD
+    int kt = 0, qa = 0;
+    for (; kt + 2 < nk_full; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::true_type{});      // straight-line main loop
+    for (; kt < nk; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::false_type{});              // the last tiles, with tests
 
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
@@ -584,7 +607,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
 template <int BM, int BN, bool A_KM, bool B_KM, int EPI>
 void launch_one(const GemmParams<bf16> &p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+    size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
+    if constexpr (A_KM && B_KM && BM == 256) smem = (size_t)5 * BM * BK * sizeof(bf16);     // the DMA kernel's operand ring
     void (*kern)(GemmParams<bf16>, int, int) = gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI>;
     if constexpr (A_KM && B_KM && BM == 256) kern = gemm_bf16_dma_kernel<BM, BN, 2, 2, EPI>;
     char name[96];
