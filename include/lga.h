@@ -74,6 +74,13 @@ typedef struct lga_config {
                              order and by unfused Adam when n_layers > 1); 0: a single layer-sized
                              buffer, reused layer after layer (appendix C.3: gradient storage made
                              negligible by updating a layer's weights at once) */
+    int32_t wgrad_groups; /* bf16 mode, layered order: consecutive groups of a layer whose weight-gradient
+                             GEMMs are merged into one that contracts over all their tokens (their
+                             transposed operands are kept side by side until then: 2 (2 d_ff + 8 d_model)
+                             bytes per token, counted by lga_arena_bytes).  The sum over micro-batches then happens in
+                             the GEMM's k loop instead of by read-modify-write of the fp32 buffer.
+                             1 = no merging, 0 = automatic (as many as keep those operand buffers within
+                             a quarter of the rest of the arena), at most n_micro / group. */
     float ln_eps;         /* LayerNorm epsilon, inside the root (1e-5 in the benchmarks) */
     void *stream;         /* hipStream_t, borrowed; NULL = default stream */
 } lga_config;

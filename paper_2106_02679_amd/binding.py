@@ -32,7 +32,8 @@ _STATUS_NAMES = {0: "LGA_OK", -1: "LGA_ERR_ARG", -2: "LGA_ERR_SHAPE", -3: "LGA_E
 class lga_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
                 ("seq_len", C.c_int32), ("micro_batch", C.c_int32), ("n_micro", C.c_int32), ("dtype", C.c_int32),
-                ("group", C.c_int32), ("retain_grads", C.c_int32), ("ln_eps", C.c_float), ("stream", C.c_void_p)]
+                ("group", C.c_int32), ("retain_grads", C.c_int32), ("wgrad_groups", C.c_int32), ("ln_eps", C.c_float),
+                ("stream", C.c_void_p)]
 
 
 class lga_adam(C.Structure):
@@ -131,9 +132,9 @@ def check(code: int) -> None:
 
 
 def make_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group=1, retain_grads=0,
-                ln_eps=1e-5, stream: Optional[int] = None) -> lga_config:
+                ln_eps=1e-5, stream: Optional[int] = None, wgrad_groups=0) -> lga_config:
     return lga_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group, retain_grads,
-                      ln_eps, stream)
+                      wgrad_groups, ln_eps, stream)
 
 
 def params_per_layer(cfg: lga_config) -> int:

@@ -83,6 +83,8 @@ int validate_config(const lga_config *c) {
     if (c->d_model % c->n_heads != 0) return fail(LGA_ERR_SHAPE, "d_model must be a multiple of n_heads");
     if (c->group < 1 || c->group > c->n_micro || c->n_micro % c->group != 0)
         return fail(LGA_ERR_SHAPE, "group must be in 1..n_micro and divide n_micro");
+    if (c->wgrad_groups < 0 || c->wgrad_groups > c->n_micro / c->group)
+        return fail(LGA_ERR_SHAPE, "wgrad_groups must be 0 (automatic) or in 1..n_micro/group");
     if (!(c->ln_eps >= 0.f)) return fail(LGA_ERR_ARG, "ln_eps must be >= 0");
     if (c->dtype == LGA_FP32 && (2.0 * c->seq_len + 2.0 * c->d_model / c->n_heads) * 4 > 60000)
         return fail(LGA_ERR_SHAPE, "fp32 mode: seq_len too long for the one-wavefront attention kernel's LDS rows");
@@ -103,7 +105,10 @@ int validate_config(const lga_config *c) {
 
 // Arena plan: one allocation, every sub-buffer 256-byte aligned.
 struct Plan {
-    size_t w, m, v, grad, w16, w16t, ckpt, dact, xT, dyT;
+    size_t w, m, v, grad, w16, w16t, ckpt, dact;
+    size_t xT[4], dyT[4];      // transposed operands of the four weight-gradient GEMMs (bf16 mode)
+    int wgrad_groups;          // groups whose tokens one weight-gradient GEMM contracts over
+    size_t ldk;                // row pitch (elements) of the transposed operands
     size_t h, qkv, a, x1, h2, u, gl, du, dh2, dx1, da, dqkv, dh;
     size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
     size_t total;
@@ -139,8 +144,26 @@ Plan make_plan(const lga_config &c) {
     p.da = take(t * d * esz);
     p.dqkv = take(t * 3 * d * esz);
     p.dh = take(t * d * esz);
-    p.xT = take(c.dtype == LGA_BF16 ? t * f * 2 : 0);                           // [in][t] copy of a dW GEMM's input
-    p.dyT = take(c.dtype == LGA_BF16 ? t * std::max<size_t>(3 * d, f) * 2 : 0);  // [out][t] copy of its output gradient
+    // Transposed operands of the weight-gradient GEMMs: [in][ldk] copies of their inputs and [out][ldk]
+    // copies of their output gradients, wgrad_groups groups side by side along the token axis.  The pitch
+    // is padded by 64 elements: the unpadded one is a large power of two, which maps every row of an
+    // operand tile to the same memory channel.
+    const size_t groups = (size_t)c.n_micro / c.group;
+    const size_t rows = 2 * f + 8 * d;                      // in + out over the four matrices
+    size_t wb = c.wgrad_groups ? (size_t)c.wgrad_groups : 1;
+    if (c.dtype == LGA_BF16 && c.wgrad_groups == 0) {
+        // automatic: as many groups as keep these buffers within a quarter of everything else
+        wb = groups;
+        while (wb > 1 && rows * (wb * t + 64) * 2 > off / 4) --wb;
+    }
+    p.wgrad_groups = (int)wb;
+    p.ldk = wb * t + 64;
+    const int wg_in[4] = {(int)f, (int)d, (int)d, (int)d};          // W_2, W_1, W_o, W_qkv
+    const int wg_out[4] = {(int)d, (int)f, (int)d, (int)(3 * d)};
+    for (int i = 0; i < 4; ++i) {
+        p.xT[i] = take(c.dtype == LGA_BF16 ? (size_t)wg_in[i] * p.ldk * 2 : 0);
+        p.dyT[i] = take(c.dtype == LGA_BF16 ? (size_t)wg_out[i] * p.ldk * 2 : 0);
+    }
     p.mean1 = take(t * 4);
     p.rstd1 = take(t * 4);
     p.mean2 = take(t * 4);
@@ -255,10 +278,25 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     }
 }
 
+// How one group's weight gradients enter the layer's fp32 gradient buffer.
+struct GradStep {
+    float beta;       // vectors (biases, LayerNorm): 0 for the layer's first group, then 1
+    float beta_mat;   // matrices: 0 for the first weight-gradient GEMM of the layer, then 1
+    int slot;         // bf16 mode: position of this group's tokens in the transposed operand buffers
+    bool flush;       // bf16 mode: run the matrix GEMMs now, over slots 0..slot
+};
+
 // Backward of layer l on one group whose intermediates were just recomputed by layer_forward.
 // dy: [t, d] group slice of the running activation gradient, overwritten with dx.
-// gbuf: the layer's fp32 gradient buffer (canonical layout); beta = 0 for the layer's first group.
-template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *dy, float *gbuf, float beta) {
+// gbuf: the layer's fp32 gradient buffer (canonical layout).
+//
+// bf16 mode merges the weight-gradient GEMMs of consecutive groups of a layer (possible because the
+// layered order visits all micro-batches of a layer back to back): each group only appends its
+// transposed operands, and one GEMM then contracts over all their tokens.  The accumulation over
+// micro-batches that the fp32 buffer would do by read-modify-write happens inside the GEMM's
+// k loop instead, so the buffer is touched once per merged GEMM rather than once per group.
+template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *dy, float *gbuf, GradStep gs) {
+    const float beta = gs.beta;
     const lga_config &c = st->cfg;
     const int d = c.d_model, f = c.d_ff, t = (int)st->t;
     const LayerLayout &o = st->lay;
@@ -276,22 +314,27 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     float *partial = st->at<float>(st->plan.partial);
     const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
 
-    // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over the group's tokens.  bf16 mode first
-    // writes X^T [in][t] and dY^T [out][t] (two HBM-bound passes, ~1 % of the GEMM's time) so that the
-    // GEMM reads both operands k-contiguous.
-    auto wgrad = [&](const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off) {
+    // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over tokens.  bf16 mode first writes X^T [in][.]
+    // and dY^T [out][.] (two HBM-bound passes, ~1 % of the GEMM's time) so that the GEMM reads both
+    // operands k-contiguous; `which` names the matrix's pair of transposed buffers.
+    auto wgrad = [&](int which, const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off) {
         GemmParams<T> g{};
-        g.M = in; g.N = out; g.K = t;
-        g.outf = gbuf + w_off; g.ldc = out; g.beta = beta;
+        g.M = in; g.N = out;
+        g.outf = gbuf + w_off; g.ldc = out;
         if constexpr (std::is_same<T, float>::value) {
+            g.K = t; g.beta = beta;
             g.A = X; g.lda = in; g.B = dY; g.ldb = out;
             gemm<T>(g, false, false, EPI_ACCUM_F32, s);
         } else {
-            bf16 *xT = st->at<bf16>(st->plan.xT), *dyT = st->at<bf16>(st->plan.dyT);
-            launch_transpose_bf16(X, xT, t, in, in, t, s);
-            launch_transpose_bf16(dY, dyT, t, out, out, t, s);
-            g.A = xT; g.lda = t; g.B = dyT; g.ldb = t;
-            gemm<T>(g, true, true, EPI_ACCUM_F32, s);
+            const int ldk = (int)st->plan.ldk;
+            bf16 *xT = st->at<bf16>(st->plan.xT[which]), *dyT = st->at<bf16>(st->plan.dyT[which]);
+            launch_transpose_bf16(X, xT + (size_t)gs.slot * t, t, in, in, ldk, s);
+            launch_transpose_bf16(dY, dyT + (size_t)gs.slot * t, t, out, out, ldk, s);
+            if (gs.flush) {
+                g.K = (gs.slot + 1) * t; g.beta = gs.beta_mat;
+                g.A = xT; g.lda = ldk; g.B = dyT; g.ldb = ldk;
+                gemm<T>(g, true, true, EPI_ACCUM_F32, s);
+            }
         }
         launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, out, beta, gbuf + b_off, nullptr, partial, s);
     };
@@ -303,21 +346,21 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     };
 
     // y = x1 + gelu(u) W2 + b2
-    wgrad(gl, f, dy, d, o.w_2, o.b_2);
+    wgrad(0, gl, f, dy, d, o.w_2, o.b_2);
     dgrad(dy, d, o.w_2, f, du, EPI_MUL_DGELU, u);            // du = (dy W2^T) * gelu'(u)
     // u = h2 W1 + b1
-    wgrad(h2, d, du, f, o.w_1, o.b_1);
+    wgrad(1, h2, d, du, f, o.w_1, o.b_1);
     dgrad(du, f, o.w_1, d, dh2, EPI_STORE, nullptr);
     // h2 = LN2(x1); dx1 = dy + LN2'(dh2)
     launch_colsum<T>(dh2, x1, mean2, rstd2, t, d, d, beta, gbuf + o.ln2_b, gbuf + o.ln2_g, partial, s);
     launch_layernorm_bwd_dx<T>(dh2, x1, mean2, rstd2, pf + o.ln2_g, dy, dx1, t, d, s);
     // x1 = x + a Wo + bo
-    wgrad(a, d, dx1, d, o.w_o, o.b_o);
+    wgrad(2, a, d, dx1, d, o.w_o, o.b_o);
     dgrad(dx1, d, o.w_o, d, da, EPI_STORE, nullptr);
     if constexpr (std::is_same<T, float>::value) launch_attn_bwd_simple<float>(qkv, a, lse, da, dqkv, delta, ash, s);
     else launch_attn_bwd_bf16(qkv, a, lse, da, dqkv, delta, ash, s);
     // qkv = h Wqkv + bqkv
-    wgrad(h, d, dqkv, 3 * d, o.w_qkv, o.b_qkv);
+    wgrad(3, h, d, dqkv, 3 * d, o.w_qkv, o.b_qkv);
     dgrad(dqkv, 3 * d, o.w_qkv, d, dh, EPI_STORE, nullptr);
     // h = LN1(x); dx = dx1 + LN1'(dh)
     launch_colsum<T>(dh, x_in, mean1, rstd1, t, d, d, beta, gbuf + o.ln1_b, gbuf + o.ln1_g, partial, s);
@@ -372,7 +415,9 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
         st->grad_owner[st->grad_slot(l)] = -1;
         for (int gi = 0; gi < groups; ++gi) {
             layer_forward<T>(st, l, in + gi * gstride, nullptr);                       // recompute
-            layer_backward<T>(st, l, in + gi * gstride, dact + gi * gstride, gbuf, gi == 0 ? 0.f : 1.f);
+            const int wb = st->plan.wgrad_groups;
+            const GradStep gs{gi == 0 ? 0.f : 1.f, gi < wb ? 0.f : 1.f, gi % wb, gi % wb == wb - 1 || gi == groups - 1};
+            layer_backward<T>(st, l, in + gi * gstride, dact + gi * gstride, gbuf, gs);
         }
         st->grad_owner[st->grad_slot(l)] = l;
         if (fused) adam_layer(st, l, *fused);              // update as soon as the layer's gradient is complete
@@ -398,7 +443,9 @@ int step_mbmajor_t(lga_stack *st, const void *x, const void *dy, void *y, void *
         for (int l = c.n_layers - 1; l >= 0; --l) {
             const T *in = reinterpret_cast<const T *>(st->ckpt(l)) + mu * gstride;
             layer_forward<T>(st, l, in, nullptr);
-            layer_backward<T>(st, l, in, dact + mu * gstride, st->grad(l), mu == 0 ? 0.f : 1.f);
+            // layers alternate here, so every weight-gradient GEMM runs at once on its own micro-batch
+            const GradStep gs{mu == 0 ? 0.f : 1.f, mu == 0 ? 0.f : 1.f, 0, true};
+            layer_backward<T>(st, l, in, dact + mu * gstride, st->grad(l), gs);
         }
     }
     for (int l = 0; l < c.n_layers; ++l) st->grad_owner[l] = l;
@@ -452,8 +499,16 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
     const uint64_t adam_param = 24 * P + (cfg->dtype == LGA_BF16 ? 2 * P + 4 * Pm : 0);
     const uint64_t per_group_param = wsz * (3 * Pm - df);
     if (param_bytes) *param_bytes = L * (adam_param + groups * per_group_param);
-    // gradient buffer: first group writes (4 B), later groups read-modify-write (8 B); Adam reads (4 B)
-    if (grad_bytes) *grad_bytes = L * (4 * P + 4 * P + (groups - 1) * 8 * P);
+    // gradient buffer: the first pass over it writes (4 B), later ones read-modify-write (8 B); Adam reads
+    // (4 B).  Vectors take one pass per group; matrices one per weight-gradient GEMM, which in the layered
+    // bf16 path covers wgrad_groups groups.
+    uint64_t mat_passes = groups;
+    if (order == LGA_ORDER_LAYERED && cfg->dtype == LGA_BF16) {
+        const uint64_t wb = make_plan(*cfg).wgrad_groups;
+        mat_passes = (groups + wb - 1) / wb;
+    }
+    if (grad_bytes)
+        *grad_bytes = L * (4 * P + 4 * P + (groups - 1) * 8 * (P - Pm) + (mat_passes - 1) * 8 * Pm);
     if (flops) {
         const double tokens = (double)cfg->n_micro * cfg->micro_batch * cfg->seq_len;
         const double gemm = 2.0 * tokens * (double)L * (4.0 * Pm - df);                 // fwd, recompute - W_2, dX, dW

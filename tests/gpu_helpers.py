@@ -61,11 +61,11 @@ def oracle_adam(a: B.lga_adam) -> O.AdamHyper:
 
 
 def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layered", adam=None, fused=True,
-                 want_ckpt=True):
+                 want_ckpt=True, wgrad_groups=0):
     """One training step through the C ABI.  Returns a dict of float64 numpy results."""
     dt = dtype_code(w)
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
-                        group=group, retain_grads=retain)
+                        group=group, retain_grads=retain, wgrad_groups=wgrad_groups)
     st = B.Stack(cfg, np.concatenate(params))
     P = B.params_per_layer(cfg)
     xd, Gd = to_dev(x, dt), to_dev(G, dt)

@@ -70,7 +70,7 @@ def test_null_arguments():
 
 def test_arena_holds_state_checkpoints_and_scratch():
     c = cfg(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
-            dtype=B.LGA_BF16, group=2, retain_grads=0)
+            dtype=B.LGA_BF16, group=2, retain_grads=0, wgrad_groups=1)
     P = 12 * 12288 ** 2 + 13 * 12288
     T = 32 * 2048
     state = 12 * 4 * P                              # appendix C.3: 12 p bytes of fp32 parameters and moments
@@ -83,8 +83,21 @@ def test_arena_holds_state_checkpoints_and_scratch():
     assert total < 288e9
     # keeping every layer's gradient costs exactly (L-1) more buffers
     c2 = cfg(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
-             dtype=B.LGA_BF16, group=2, retain_grads=1)
+             dtype=B.LGA_BF16, group=2, retain_grads=1, wgrad_groups=1)
     assert abs((B.arena_bytes(c2) - total) - 3 * 4 * P) < 4096
+    # merging the weight-gradient GEMMs of w groups keeps w - 1 more groups of transposed operands:
+    # 2 bytes x (2 d_ff + 8 d_model) rows x group tokens each
+    c4 = cfg(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
+             dtype=B.LGA_BF16, group=2, retain_grads=0, wgrad_groups=4)
+    per_group = 2 * (2 * 49152 + 8 * 12288) * (2 * 2048)
+    assert abs((B.arena_bytes(c4) - total) - 3 * per_group) < 65536
+    # automatic choice: bounded by a quarter of everything else, and never beyond the number of groups
+    ca = cfg(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
+             dtype=B.LGA_BF16, group=2, retain_grads=0, wgrad_groups=0)
+    auto = B.arena_bytes(ca)
+    assert total <= auto <= 1.25 * total
+    assert auto - total <= 15 * per_group + 65536
+    assert B.lib.lga_arena_bytes(C.byref(cfg(wgrad_groups=5)), C.byref(C.c_uint64())) == B.LGA_ERR_SHAPE   # > n_micro / group
 
 
 def test_traffic_model_layered_is_independent_of_micro_batch_count_when_fully_grouped():
@@ -101,6 +114,14 @@ def test_traffic_model_layered_is_independent_of_micro_batch_count_when_fully_gr
     Pm = 12 * 1024 ** 2
     assert gm == 8 * P + 31 * 8 * P                   # first write + Adam read, then read-modify-write per micro-batch
     assert g32 == 8 * P
+    # layered, 8 groups of 4: vectors are read-modify-written per group, matrices once per merged GEMM
+    def grads(w):
+        c = cfg(n_layers=1, d_model=1024, n_heads=8, d_ff=4096, seq_len=128, micro_batch=1, n_micro=32,
+                dtype=B.LGA_BF16, group=4, retain_grads=0, wgrad_groups=w)
+        return B.traffic_model(c, B.LGA_ORDER_LAYERED)[1]
+    assert grads(1) == 8 * P + 7 * 8 * P
+    assert grads(4) == 8 * P + 7 * 8 * (P - Pm) + 1 * 8 * Pm
+    assert grads(8) == 8 * P + 7 * 8 * (P - Pm)
     assert pm - p32 == 31 * 2 * (3 * Pm - 1024 * 4096)
     assert fm == f32_
 

@@ -119,6 +119,24 @@ def test_orders_and_group_sizes_agree_on_the_gpu():
             assert rel_err(other["v"][l], base["v"][l]) < 1e-5, kwargs
 
 
+@pytest.mark.parametrize("wgrad_groups", [1, 2, 3, 0])
+def test_merged_weight_gradient_gemms_match_oracle_and_each_other(wgrad_groups):
+    """bf16, 6 groups of one micro-batch: the weight-gradient GEMMs of 1, 2, 3 (a ragged last batch would
+    appear with 4) or all groups merged.  Every choice must pass the oracle gate, and the gradients of
+    all choices agree up to fp32 re-association."""
+    w = S.Workload("wgrad_merge_bf16", 2, 128, 4, 512, 96, 1, 6, "bf16")
+    x, G, params = S.make_inputs(w, seed=21)
+    adam = adam_struct()
+    ref = O.step_microbatch_major(x, G, params, oracle_shape(w), oracle_adam(adam))
+    got = run_gpu_step(w, x, G, params, group=1, retain=1, adam=adam, wgrad_groups=wgrad_groups)
+    compare_with_oracle(w, got, ref, GATE["bf16"], adam)
+    base = run_gpu_step(w, x, G, params, group=1, retain=1, adam=adam, wgrad_groups=4)     # batches of 4 and 2
+    assert np.array_equal(base["boundaries"], got["boundaries"])
+    assert np.array_equal(base["dx"], got["dx"])
+    for l in range(w.n_layers):
+        assert rel_err(got["grads"][l], base["grads"][l]) < 1e-5
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
