@@ -17,6 +17,7 @@
 //   dQ kernel    S^T = K Q^T ; dP^T = V dO^T ; dS^T ; dQ^T += K^T dS^T   streams K, V, K^T
 //   dK/dV kernel S = Q K^T ; dP = dO V^T ; dV^T += dO^T P ; dK^T += Q^T dS   streams Q, dO, Q^T, dO^T
 #include <cstdio>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -116,121 +117,338 @@ __device__ __forceinline__ bf16x8 pack_bf16(const f32x16 &v, int kk) {
 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
 
+// ---- direct-to-LDS tile loads and transposing LDS reads --------------------------------------
+// buffer_load_dwordx4 ... lds writes lane L's 16 bytes at (LDS base) + 16 L; rows beyond the sequence get
+// an offset outside the buffer's range, which the hardware answers with zeros.
+constexpr int kBufRange = 0x40000000;
+constexpr int kBufPoison = 0x7FFFFF00;
+typedef __attribute__((address_space(3))) void *lds_ptr;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, kBufRange, 0x00020000);
+}
+// Tiles that are filled by DMA keep their rows at a padded pitch instead of an XOR swizzle, so that every
+// MFMA operand address is one per-lane base plus a compile-time offset (swizzled addresses each need
+// their own register, and the compiler keeps them all live across the key loop).
+//   pitch_rd<DH>  rows read with ds_read_b128 (lane = row): 16 bytes of padding rotate the banks row by row
+//   pitch_tr<DH>  rows read with the transposing ds_read_b64_tr_b16, one pass of which covers 4 consecutive
+//                 rows x 64 bytes: power-of-two row sizes get 64 bytes of padding, the others already stagger
+template <int DH> constexpr int pitch_rd() { return DH + 8; }
+template <int DH> constexpr int pitch_tr() { return (DH == 64 || DH == 128) ? DH + 32 : DH; }
+
+// Per-lane part of the address of a transposed operand read from a NATURAL tile [position][pitch]:
+// within each group of 16 lanes, lane i passes the address of 4 consecutive values and receives, with lane
+// i pointing at (row i/4, columns 4 (i%4) ..+3), column i of rows 0..3.
+template <int PITCH> __device__ __forceinline__ int tr_lane_off(int lane) {
+    const int i = lane & 15;
+    return (4 * (lane >> 5) + (i >> 2)) * PITCH + 16 * ((lane >> 4) & 1) + 4 * (i & 3);
+}
+// MFMA first operand "row n = 32 c + lrow of the transposed tile, k element e <-> streamed position
+// 16 kk + 8 (e/4) + 4 half + e%4" (the permutation that matches a 32x32 MFMA result used as second operand).
+// base = tile + tr_lane_off(lane).
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+template <int PITCH> __device__ __forceinline__ bf16x8 frag_nat_tr(const bf16 *base, int c, int kk) {
+    // Issued as inline assembly: the compiler makes the builtin form wait for every outstanding
+    // direct-to-LDS load first (it cannot tell which LDS bytes those write), which would serialise the
+    // tile prefetch.  The price: the compiler does not count these reads in lgkmcnt, so wait_tr_reads()
+    // must stand between them and their first use.
+    const uint32_t addr = (uint32_t)(uintptr_t)base;        // low 32 bits of a generic LDS pointer = LDS address
+    u32x2 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "i"((16 * kk * PITCH + 32 * c) * 2));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "i"(((16 * kk + 8) * PITCH + 32 * c) * 2));
+    const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, v);
+}
+// All LDS reads issued so far have returned; the operands listed are tied to the wait so that no use of
+// them can be scheduled above it.
+template <int N> __device__ __forceinline__ void wait_tr_reads(bf16x8 (&f)[N]) {
+    static_assert(N <= 10, "operand list below");
+    if constexpr (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]));
+    else if constexpr (N == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
+    else if constexpr (N == 6)
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]));
+    else if constexpr (N == 8)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+    else if constexpr (N == 10)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]),
+                       "+v"(f[8]), "+v"(f[9]));
+    else static_assert(N == 2, "unsupported operand count");
+}
+// DMA of a ROWS x DH tile (global row pitch gp2 bytes) into LDS rows of PITCH elements.  The tile is
+// ROWS * (PITCH / 8) slots of 16 bytes, filled 64 at a time; instruction j covers slots [64 j, 64 j + 64).
+// Slots that are padding, and rows at or beyond nvalid, get the poison offset (zeros).
+template <int ROWS, int DH, int PITCH> struct TileDma {
+    static constexpr int SLOTS = PITCH / 8;                 // per row
+    static constexpr int NI = (ROWS * SLOTS + 63) / 64;     // instructions that carry data
+    static constexpr int NJ = (NI + 3) / 4;                 // per wavefront (4 wavefronts): every wavefront issues NJ,
+                                                            // so that "all but the newest tile" is one vmcnt value
+    static constexpr int ELEMS = NJ * 4 * 512;              // LDS elements to reserve: 4 NJ instructions of 1 KB
+    int row[NJ], off[NJ];
+    __device__ __forceinline__ void init(int wave, int lane, int gp2) {
+#pragma unroll
+        for (int i = 0; i < NJ; ++i) {
+            const int slot = (i * 4 + wave) * 64 + lane, r = slot / SLOTS, pc = slot % SLOTS;
+            row[i] = (pc < DH / 8 && r < ROWS) ? r : 0x7FFFFFFF;    // padding slots never pass the row test
+            off[i] = r * gp2 + (pc << 4);
+        }
+    }
+    __device__ __forceinline__ void issue(const bf16 *src, bf16 *dst, int nvalid, int wave) const {
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
+#pragma unroll
+        for (int i = 0; i < NJ; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(dst + (i * 4 + wave) * 512), 16,
+                                                     row[i] < nvalid ? off[i] : kBufPoison, 0, 0, 0);
+    }
+};
+
 // ============================================================================================
-// Forward.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
+// Forward.  grid.x = query blocks of 256 (largest first), grid.y = n_seq * heads.
+//
+// A wavefront owns 64 queries as two sub-blocks of 32, so every K and V operand it reads from LDS
+// feeds two MFMAs; one wavefront per SIMD, with registers for both sub-blocks' output accumulators.
+// Key tiles of 64 (K and V as stored, rows of DH) stream from global memory straight into one of two
+// LDS stages while the other is multiplied; one barrier per tile publishes it.  V^T operands come from
+// the natural V tile through the transposing LDS read.  The online softmax runs per (sub-block, 32 keys).
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ out,
+__global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ out,
                                                        float *__restrict__ lse, AttnShape sh) {
     constexpr int KT = 64;                 // keys per streamed tile
     constexpr int NK = DH / 16, NC = DH / 32;
-    __shared__ __attribute__((aligned(16))) bf16 Ks[KT * DH];
-    __shared__ __attribute__((aligned(16))) bf16 Vt[DH * KT];
+    constexpr int PK = pitch_rd<DH>(), PV = pitch_tr<DH>();    // LDS row pitches of the K and V tiles
+    typedef TileDma<KT, DH, PK> DmaK;
+    typedef TileDma<KT, DH, PV> DmaV;
+    constexpr int STAGE = DmaK::ELEMS + DmaV::ELEMS;            // elements per stage: K tile, then V tile
+    constexpr int NSTAGE = 3;
+    constexpr int kWaitOlder = 0x0070 | (DmaK::NJ + DmaV::NJ);  // s_waitcnt lgkmcnt(0) vmcnt(loads of one tile): older tiles landed
+    static_assert(DmaK::NJ + DmaV::NJ < 16, "vmcnt immediate uses the low four bits only");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
 
-    const int qblocks = (sh.s + 127) / 128;
+    const int qblocks = (sh.s + 255) / 256;
     const int qb = qblocks - 1 - blockIdx.x;
     const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
     const int d = sh.heads * DH;
     const size_t pitch = 3 * (size_t)d;
     const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
-    const int qw0 = qb * 128 + wave * 32;          // first query of this wavefront
-    const int q = qw0 + lrow;
-    const bool qvalid = q < sh.s;
+    const int qw0 = qb * 256 + wave * 64;          // first query of this wavefront
 
-    bf16x8 qf[NK];
+    bf16x8 qf[2][NK];
 #pragma unroll
-    for (int ks = 0; ks < NK; ++ks) qf[ks] = frag_global(seq + (size_t)q * pitch, ks, half, qvalid);
-
-    f32x16 oacc[NC];
+    for (int u = 0; u < 2; ++u) {
+        const int q = qw0 + 32 * u + lrow;
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+        for (int ks = 0; ks < NK; ++ks) qf[u][ks] = frag_global(seq + (size_t)q * pitch, ks, half, q < sh.s);
+    }
+    // Softmax reference per query, in the log2 domain.  It is FIXED once the query's first 32 keys are seen
+    // (p = 2^(score - m_ref) is then exact up to a common factor that the final division removes), so the
+    // output accumulators are never rescaled - they live in accumulation registers that only MFMAs touch.
+    // A score some 100 (log2 units) above the reference would overflow fp32: a row sum beyond 1e30 makes the
+    // whole workgroup start over with the reference raised by kRefStep (never seen on real activations).
+    constexpr float kRefStep = 64.f;
+    f32x16 oacc[2][NC];
+    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2];
     const float c2 = rsqrtf((float)DH) * kLog2e;
+    // Plain (not volatile) so that the compiler keeps it an LDS access, which waits for no global load; the
+    // barriers' memory clobbers make every read after them a fresh one.
+    __shared__ int restart_flag[1];
+    if (threadIdx.x == 0) restart_flag[0] = 0;
 
-    const int kend = min(sh.s, qb * 128 + 128);     // keys needed by this block: [0, kend)
-    for (int k0 = 0; k0 < kend; k0 += KT) {
-        __syncthreads();
-        load_nat<KT, DH>(Ks, seq + (size_t)k0 * pitch + d, pitch, sh.s - k0);
-        load_tr<KT, DH>(Vt, seq + (size_t)k0 * pitch + 2 * d, pitch, sh.s - k0);
-        __syncthreads();
-        if (k0 > qw0 + 31) continue;               // whole tile is in this wavefront's future
-        f32x16 st[2];
-        const int nkb = (k0 + 32 > qw0 + 31) ? 1 : 2;   // second 32-key block may be entirely masked
+    // ---- tile loader ------------------------------------------------------------------------
+    DmaK dk;
+    DmaV dv;
+    dk.init(wave, lane, (int)(pitch * 2));
+    dv.init(wave, lane, (int)(pitch * 2));
+    auto dma_tile = [&](int k0, int stage) {
+        bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
+        dk.issue(seq + (size_t)k0 * pitch + d, Ks, sh.s - k0, wave);
+        dv.issue(seq + (size_t)k0 * pitch + 2 * d, Vs, sh.s - k0, wave);
+    };
+    const int koff = lrow * PK + 8 * half;              // per-lane part of a K operand's address
+    const int voff = tr_lane_off<PV>(lane);             // ... and of a V^T operand's
+
+    // ---- one key tile -------------------------------------------------------------------------
+    // Four units n = 2 kb + u (key block kb of 32, query sub-block u), each: S = NK MFMAs, the
+    // exponentials (VALU), P V = 2 NC MFMAs.  MFMAs of one unit and exponentials of another are
+    // independent, so they are issued interleaved - a few MFMAs, then a quarter of a unit's exponentials -
+    // and the matrix pipe works under the VALU instructions of the same wavefront:
+    //     slot   0      1        2          3          4       5
+    //     MFMA   S(0)   S(1)     S(2) PV(0) S(3) PV(1) PV(2)   PV(3)
+    //     VALU          exp(0)   exp(1)     exp(2)     exp(3)
+    // LDS operand reads are issued a slot or more ahead of the MFMAs that need them.  The issue order is
+    // pinned (sched_barrier).  With tiles and wavefront query ranges both aligned to 64, a tile is either
+    // fully visible or the diagonal one (k0 == qw0), where masked probabilities are forced to zero.
+    bf16x8 kf[2][NK], vf[2][2 * NC], pf[4][2];     // K operands [kb], V^T operands [kb], P operands [unit]
+    f32x16 st[4];                                  // scores, then probabilities, per unit
+    auto read_k = [&](const bf16 *Ks, int kb) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int ks = 0; ks < NK; ++ks) kf[kb][ks] = *reinterpret_cast<const bf16x8 *>(Ks + kb * 32 * PK + 16 * ks);
+    };
+    auto read_v = [&](const bf16 *Vs, int kb) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) st[kb][r] = 0.f;
-            if (kb < nkb) {
+        for (int j2 = 0; j2 < 2; ++j2)
 #pragma unroll
-                for (int ks = 0; ks < NK; ++ks)
-                    st[kb] = MFMA(frag_nat<DH>(Ks, kb * 32 + lrow, ks, half), qf[ks], st[kb]);
+            for (int c = 0; c < NC; ++c) vf[kb][j2 * NC + c] = frag_nat_tr<PV>(Vs, c, 2 * kb + j2);
+    };
+    auto s_group = [&](int n, int g) {             // quarter g of unit n's S MFMAs
+        const int kb = n >> 1, u = n & 1;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            if (ks < g * NK / 4 || ks >= (g + 1) * NK / 4) continue;
+            if (ks == 0) {
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                st[n] = MFMA(kf[kb][ks], qf[u][ks], zero);
+            } else {
+                st[n] = MFMA(kf[kb][ks], qf[u][ks], st[n]);
             }
         }
-        // Running max in the log2 domain (scores * c2).  Only tiles that touch the diagonal need the mask.
-        if (k0 + KT - 1 > qw0) {
+    };
+    auto pv_group = [&](int n, int g) {            // quarter g of unit n's P V MFMAs
+        const int kb = n >> 1, u = n & 1;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (!(kb < nkb && key <= q)) st[kb][r] = -INFINITY;
-                }
+        for (int jc = 0; jc < 2 * NC; ++jc) {
+            if (jc < g * 2 * NC / 4 || jc >= (g + 1) * 2 * NC / 4) continue;
+            oacc[u][jc % NC] = MFMA(vf[kb][jc], pf[n][jc / NC], oacc[u][jc % NC]);
         }
-        float raw = -INFINITY;
+    };
+    auto exp_group_t = [&](int n, int g, int k0, auto diag_c) {    // quarter g of unit n's exponentials
+        constexpr bool diag = decltype(diag_c)::value;
+        const int kb = n >> 1, u = n & 1;
+        // key of score register r is visible iff 8 (r / 4) + r % 4 <= qrel
+        const int qrel = qw0 + 32 * u + lrow - (k0 + 32 * kb + 4 * half);
+        if (g == 0 && kb == 0 && k0 == 0) {
+            // the query's first 32 keys fix its softmax reference (key 0 is visible to every query)
+            float raw = -INFINITY;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int r = 0; r < 16; ++r)
+                if (!diag || 8 * (r >> 2) + (r & 3) <= qrel) raw = fmaxf(raw, st[n][r]);
+            raw = fmaxf(raw, __shfl_xor(raw, 32, 64)) * c2;
+            if (m_ref[u] == -INFINITY) m_ref[u] = raw;           // kept when the workgroup starts over
+        }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) raw = fmaxf(raw, st[kb][r]);
-        raw = fmaxf(raw, __shfl_xor(raw, 32, 64));
-        const float mx = fmaxf(m_run, raw * c2);     // finite from the first tile on: key 0 is visible to every query
-        const float alpha = __builtin_amdgcn_exp2f(m_run - mx);       // 0 on the first tile (m_run = -inf)
-        m_run = mx;
-        float psum = 0.f;
+        for (int r = 4 * g; r < 4 * g + 4; ++r) {
+            float p = __builtin_amdgcn_exp2f(fmaf(st[n][r], c2, -m_ref[u]));
+            if (diag && 8 * (r >> 2) + (r & 3) > qrel) p = 0.f;
+            st[n][r] = p;
+            l_run[u] += p;
+        }
+        if (g == 1) pf[n][0] = pack_bf16(st[n], 0);
+        if (g == 3) pf[n][1] = pack_bf16(st[n], 1);
+    };
+    // the mask test is compiled only into the diagonal tile's copy; the branch encloses VALU work only, so the
+    // accumulators' MFMAs stay on one path
+    auto exp_group = [&](int n, int g, int k0, bool diag) {
+        if (diag) exp_group_t(n, g, k0, std::true_type{});
+        else exp_group_t(n, g, k0, std::false_type{});
+    };
+    auto tile = [&](int k0, int stage) {
+        const bf16 *Ks = lds + stage * STAGE + koff, *Vs = lds + stage * STAGE + DmaK::ELEMS + voff;
+        const bool diag = k0 == qw0;
+        read_k(Ks, 0);
+        read_k(Ks, 1);
+        read_v(Vs, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int g = 0; g < 4; ++g) {                  // slot 0
+            s_group(0, g);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(st[kb][r], c2, -mx));
-                st[kb][r] = p;
-                psum += p;
-            }
-        l_run = l_run * alpha + psum;
-        if (__any(alpha != 1.0f)) {                  // the max rarely moves after the first tiles
+        for (int g = 0; g < 4; ++g) {                  // slot 1
+            s_group(1, g);
+            exp_group(0, g, k0, diag);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_tr_reads(vf[0]);
+        read_v(Vs, 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {                  // slot 2
+            s_group(2, g);
+            pv_group(0, g);
+            exp_group(1, g, k0, diag);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {                  // slot 3
+            s_group(3, g);
+            pv_group(1, g);
+            exp_group(2, g, k0, diag);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        wait_tr_reads(vf[1]);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {                  // slot 4
+            pv_group(2, g);
+            exp_group(3, g, k0, diag);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) pv_group(3, g);    // slot 5
+        // overflow guard: a sum this large means that some score was far above the reference
+        if (__any(!(l_run[0] < 1.0e30f) || !(l_run[1] < 1.0e30f))) restart_flag[0] = 1;
+    };
+
+    const int kend = min(sh.s, qb * 256 + 256);     // keys needed by this block: [0, kend)
+    for (;;) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            l_run[u] = 0.f;
 #pragma unroll
             for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+                for (int r = 0; r < 16; ++r) oacc[u][c][r] = 0.f;
         }
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            if (kb < nkb) {
-#pragma unroll
-                for (int j2 = 0; j2 < 2; ++j2) {
-                    const bf16x8 pf = pack_bf16(st[kb], j2);
-#pragma unroll
-                    for (int c = 0; c < NC; ++c)
-                        oacc[c] = MFMA(frag_tr<KT>(Vt, c * 32 + lrow, 2 * kb + j2, half), pf, oacc[c]);
-                }
-            }
+        // three LDS stages: tile k0 is multiplied while tiles k0 + KT and k0 + 2 KT are in flight
+        dma_tile(0, 0);
+        if (KT < kend) dma_tile(KT, 1);
+        int stage = 0;
+        bool again = false;
+        for (int k0 = 0; k0 < kend; k0 += KT, stage = stage == NSTAGE - 1 ? 0 : stage + 1) {
+            // Bare s_barrier (a __syncthreads() fence would wait for the tile still in flight too): this
+            // wavefront's part of tile k0 has landed and its LDS reads of the previous tile have returned.
+            if (k0 + KT < kend)
+                __builtin_amdgcn_s_waitcnt(kWaitOlder);
+            else
+                __builtin_amdgcn_s_waitcnt(0x0070);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();  // tile k0 is published; everyone has finished the tile before it, whose
+            asm volatile("" ::: "memory"); // stage the next loads overwrite
+            if (restart_flag[0]) { again = true; break; }
+            if (k0 + 2 * KT < kend) dma_tile(k0 + 2 * KT, stage == 0 ? NSTAGE - 1 : stage - 1);
+            if (k0 > qw0 + 63) continue;           // whole tile is in this wavefront's future
+            tile(k0, stage);
         }
+        __syncthreads();                            // the last tile may have raised the flag as well
+        if (!again && !restart_flag[0]) break;
+        // start over with a larger reference
+        __builtin_amdgcn_s_waitcnt(0x0F70);         // loads of tiles that were still in flight
+        __syncthreads();
+        if (threadIdx.x == 0) restart_flag[0] = 0;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) m_ref[u] += kRefStep;
     }
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (qvalid) {
-        const float inv = 1.0f / l_tot;
-        bf16 *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * DH;
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
+    for (int u = 0; u < 2; ++u) {
+        const int q = qw0 + 32 * u + lrow;
+        const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+        if (q < sh.s) {
+            const float inv = 1.0f / l_tot;
+            bf16 *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * DH;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                bf16x4 o;
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[c][4 * g + i] * inv);
-                *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
-            }
-        if (half == 0) lse[((size_t)b * sh.heads + h) * sh.s + q] = m_run * kLn2 + logf(l_tot);
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 o;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[u][c][4 * g + i] * inv);
+                    *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+                }
+            if (half == 0) lse[((size_t)b * sh.heads + h) * sh.s + q] = m_ref[u] * kLn2 + logf(l_tot);
+        }
     }
 }
 
@@ -508,13 +726,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
 }
 
 template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
-    dim3 grid((sh.s + 127) / 128, sh.n_seq * sh.heads);
+    dim3 grid((sh.s + 255) / 256, sh.n_seq * sh.heads);
     char name[64];
     snprintf(name, sizeof(name), "attn_fwd_kernel<%d>", DH);
     const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * 0.5;      // causal (query, key) pairs
     const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;         // bytes of one [tokens, d] bf16 tensor
     ProfScope scope(name, 4.0 * pairs * DH, 4.0 * act, s);
-    hipLaunchKernelGGL((attn_fwd_kernel<DH>), grid, dim3(256), 0, s, qkv, out, lse, sh);
+    // three stages of a 64-key K tile and V tile
+    constexpr int smem = 3 * (TileDma<64, DH, pitch_rd<DH>()>::ELEMS + TileDma<64, DH, pitch_tr<DH>()>::ELEMS) * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_kernel<DH>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_fwd_kernel<DH>), grid, dim3(256), smem, s, qkv, out, lse, sh);
 }
 template <int DH>
 void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *dout, bf16 *dqkv, AttnShape sh,
