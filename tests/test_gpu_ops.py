@@ -254,6 +254,40 @@ def test_attention_forward_and_backward(case):
         assert rel_err(got[:, sl], dqkv_ref[:, sl]) < tol_b, name
 
 
+@pytest.mark.parametrize("dh", [64, 128])
+def test_attention_with_scores_that_keep_growing_along_the_keys(dh):
+    """The forward kernel fixes each query's softmax reference at its first 32 keys.  Here later keys score
+    more than 100 (log2 units) above those, which the kernel must survive by starting over with a larger
+    reference: outputs, log-sum-exp and the backward (which uses that log-sum-exp) still match the oracle."""
+    n_seq, s, heads = 1, 320, 2
+    d = heads * dh
+    rng = np.random.default_rng(77 + dh)
+    qkv = rng.standard_normal((n_seq * s, 3 * d)).astype(np.float32)
+    ramp = 0.25 * np.arange(s, dtype=np.float32)                  # key j scores about j/4 nats with every query
+    for h in range(heads):
+        qkv[:, h * dh] = math.sqrt(dh)                            # q[:, 0] = sqrt(dh)
+        qkv[:, d + h * dh] = ramp                                 # k[j, 0] = j / 4
+    qkv = S.round_to_bf16(qkv)
+    dout = rnd(rng, (n_seq * s, d), BF16)
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh)
+    assert ((lse_ref[..., -1] - lse_ref[..., 31]) * math.log2(math.e) > 100).all()      # the case is what it claims
+    qd, dod = to_dev(qkv, BF16), to_dev(dout, BF16)
+    out, dqkv = empty_dev((n_seq * s, d), BF16), empty_dev((n_seq * s, 3 * d), BF16)
+    lse = torch.empty(n_seq * heads * s, device="cuda")
+    delta = torch.empty(n_seq * heads * s, device="cuda")
+    B.check(B.lib.lga_op_attention_fwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, None))
+    B.check(B.lib.lga_op_attention_bwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, None))
+    torch.cuda.synchronize()
+    assert np.isfinite(to_host(out)).all()
+    assert rel_err(to_host(out), out_ref) < 1e-2
+    assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < 1e-3 * np.abs(lse_ref).max()
+    got = to_host(dqkv)
+    # near one-hot probabilities times keys of size ~80: the bf16 rounding of dS weighs more than on ordinary inputs
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < 4e-2, name
+
+
 def test_attention_mfma_rejects_unsupported_head_size():
     t = torch.zeros(4096, device="cuda", dtype=torch.bfloat16)
     l = torch.zeros(64, device="cuda")
