@@ -276,123 +276,135 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     // independent, so they are issued interleaved - a few MFMAs, then a quarter of a unit's exponentials -
     // and the matrix pipe works under the VALU instructions of the same wavefront:
     //     slot   0      1        2          3          4       5
-    //     MFMA   S(0)   S(1)     S(2) PV(0) S(3) PV(1) PV(2)   PV(3)
+    //     MFMA   S(0)   S(1)     PV(0) S(2) PV(1) S(3) PV(2)   PV(3)
     //     VALU          exp(0)   exp(1)     exp(2)     exp(3)
-    // LDS operand reads are issued a slot or more ahead of the MFMAs that need them.  The issue order is
+    // One set of K operand registers and one of V^T operand registers: the second key block's are read as
+    // soon as the first block's last MFMA is issued, under the other work of the slot.  The issue order is
     // pinned (sched_barrier).  With tiles and wavefront query ranges both aligned to 64, a tile is either
     // fully visible or the diagonal one (k0 == qw0), where masked probabilities are forced to zero.
-    bf16x8 kf[2][NK], vf[2][2 * NC], pf[4][2];     // K operands [kb], V^T operands [kb], P operands [unit]
-    f32x16 st[4];                                  // scores, then probabilities, per unit
+    bf16x8 kf[NK], vf[2 * NC], pf[4][2];           // K operands and V^T operands of one key block, P operands [unit]
+    f32x16 st[4];                                  // scores per unit
+    float pr[2][8];                                // probabilities of half a unit, until they are packed
     auto read_k = [&](const bf16 *Ks, int kb) {
 #pragma unroll
-        for (int ks = 0; ks < NK; ++ks) kf[kb][ks] = *reinterpret_cast<const bf16x8 *>(Ks + kb * 32 * PK + 16 * ks);
+        for (int ks = 0; ks < NK; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(Ks + kb * 32 * PK + 16 * ks);
     };
     auto read_v = [&](const bf16 *Vs, int kb) {
 #pragma unroll
         for (int j2 = 0; j2 < 2; ++j2)
 #pragma unroll
-            for (int c = 0; c < NC; ++c) vf[kb][j2 * NC + c] = frag_nat_tr<PV>(Vs, c, 2 * kb + j2);
+            for (int c = 0; c < NC; ++c) vf[j2 * NC + c] = frag_nat_tr<PV>(Vs, c, 2 * kb + j2);
     };
     auto s_group = [&](int n, int g) {             // quarter g of unit n's S MFMAs
-        const int kb = n >> 1, u = n & 1;
+        const int u = n & 1;
 #pragma unroll
         for (int ks = 0; ks < NK; ++ks) {
             if (ks < g * NK / 4 || ks >= (g + 1) * NK / 4) continue;
             if (ks == 0) {
                 const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                st[n] = MFMA(kf[kb][ks], qf[u][ks], zero);
+                st[n] = MFMA(kf[ks], qf[u][ks], zero);
             } else {
-                st[n] = MFMA(kf[kb][ks], qf[u][ks], st[n]);
+                st[n] = MFMA(kf[ks], qf[u][ks], st[n]);
             }
         }
     };
     auto pv_group = [&](int n, int g) {            // quarter g of unit n's P V MFMAs
-        const int kb = n >> 1, u = n & 1;
+        const int u = n & 1;
 #pragma unroll
         for (int jc = 0; jc < 2 * NC; ++jc) {
             if (jc < g * 2 * NC / 4 || jc >= (g + 1) * 2 * NC / 4) continue;
-            oacc[u][jc % NC] = MFMA(vf[kb][jc], pf[n][jc / NC], oacc[u][jc % NC]);
+            oacc[u][jc % NC] = MFMA(vf[jc], pf[n][jc / NC], oacc[u][jc % NC]);
         }
     };
-    auto exp_group_t = [&](int n, int g, int k0, auto diag_c) {    // quarter g of unit n's exponentials
-        constexpr bool diag = decltype(diag_c)::value;
+    // MASKED: probabilities of keys beyond the query are forced to zero (the diagonal part of the sequence);
+    // the other copy has no test at all.
+    auto exp_group = [&](int n, int g, int k0, auto masked_c) {    // quarter g of unit n's exponentials
+        constexpr bool MASKED = decltype(masked_c)::value;
         const int kb = n >> 1, u = n & 1;
         // key of score register r is visible iff 8 (r / 4) + r % 4 <= qrel
         const int qrel = qw0 + 32 * u + lrow - (k0 + 32 * kb + 4 * half);
-        if (g == 0 && kb == 0 && k0 == 0) {
-            // the query's first 32 keys fix its softmax reference (key 0 is visible to every query)
-            float raw = -INFINITY;
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (!diag || 8 * (r >> 2) + (r & 3) <= qrel) raw = fmaxf(raw, st[n][r]);
-            raw = fmaxf(raw, __shfl_xor(raw, 32, 64)) * c2;
-            if (m_ref[u] == -INFINITY) m_ref[u] = raw;           // kept when the workgroup starts over
-        }
 #pragma unroll
         for (int r = 4 * g; r < 4 * g + 4; ++r) {
             float p = __builtin_amdgcn_exp2f(fmaf(st[n][r], c2, -m_ref[u]));
-            if (diag && 8 * (r >> 2) + (r & 3) > qrel) p = 0.f;
-            st[n][r] = p;
+            if (MASKED && 8 * (r >> 2) + (r & 3) > qrel) p = 0.f;
+            pr[n & 1][r & 7] = p;           // kept apart from the scores, which sit in accumulation registers
             l_run[u] += p;
         }
-        if (g == 1) pf[n][0] = pack_bf16(st[n], 0);
-        if (g == 3) pf[n][1] = pack_bf16(st[n], 1);
+        if (g & 1) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[n][g >> 1][e] = (bf16)pr[n & 1][e];
+        }
     };
-    // the mask test is compiled only into the diagonal tile's copy; the branch encloses VALU work only, so the
-    // accumulators' MFMAs stay on one path
-    auto exp_group = [&](int n, int g, int k0, bool diag) {
-        if (diag) exp_group_t(n, g, k0, std::true_type{});
-        else exp_group_t(n, g, k0, std::false_type{});
-    };
-    auto tile = [&](int k0, int stage) {
+    // No branch inside: with two code paths through the MFMAs the compiler merges their accumulator
+    // registers with hundreds of copies per tile.
+    auto tile = [&](int k0, int stage, auto masked_c) {
         const bf16 *Ks = lds + stage * STAGE + koff, *Vs = lds + stage * STAGE + DmaK::ELEMS + voff;
-        const bool diag = k0 == qw0;
         read_k(Ks, 0);
-        read_k(Ks, 1);
         read_v(Vs, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {                  // slot 0
+        for (int g = 0; g < 4; ++g) {                  // slot 0: S(0)
             s_group(0, g);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {                  // slot 1
+        for (int g = 0; g < 4; ++g) {                  // slot 1: S(1) | exp(0)
             s_group(1, g);
-            exp_group(0, g, k0, diag);
+            exp_group(0, g, k0, masked_c);
             __builtin_amdgcn_sched_barrier(0);
         }
-        wait_tr_reads(vf[0]);
-        read_v(Vs, 1);
+        wait_tr_reads(vf);                             // issued at the start of the tile, long since returned
+        __builtin_amdgcn_sched_barrier(0);
+        read_k(Ks, 1);                                 // the K operand registers are free again: second key block
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {                  // slot 2
-            s_group(2, g);
-            pv_group(0, g);
-            exp_group(1, g, k0, diag);
+        for (int n = 0; n < 2; ++n) {                  // slots 2, 3: PV(n) then S(n + 2) | exp(n + 1)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (g < 2) {
+                    pv_group(n, 2 * g);
+                    pv_group(n, 2 * g + 1);
+                } else {
+                    s_group(n + 2, 2 * (g - 2));
+                    s_group(n + 2, 2 * (g - 2) + 1);
+                }
+                exp_group(n + 1, g, k0, masked_c);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        read_v(Vs, 1);                                 // ... and so are the V^T operand registers
+        __builtin_amdgcn_sched_barrier(0);
+        exp_group(3, 0, k0, masked_c);                 // slot 4: exp(3) | PV(2), the reads' latency under exp first
+        exp_group(3, 1, k0, masked_c);
+        wait_tr_reads(vf);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int g = 2; g < 4; ++g) {
+            pv_group(2, 2 * (g - 2));
+            pv_group(2, 2 * (g - 2) + 1);
+            exp_group(3, g, k0, masked_c);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {                  // slot 3
-            s_group(3, g);
-            pv_group(1, g);
-            exp_group(2, g, k0, diag);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        wait_tr_reads(vf[1]);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {                  // slot 4
-            pv_group(2, g);
-            exp_group(3, g, k0, diag);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int g = 0; g < 4; ++g) pv_group(3, g);    // slot 5
+        for (int g = 0; g < 4; ++g) pv_group(3, g);    // slot 5: PV(3)
         // overflow guard: a sum this large means that some score was far above the reference
         if (__any(!(l_run[0] < 1.0e30f) || !(l_run[1] < 1.0e30f))) restart_flag[0] = 1;
     };
+    // wait for this wavefront's part of the oldest tile in flight (`newer`: a younger one is in flight too),
+    // then a bare s_barrier - a __syncthreads() fence would wait for the younger tile as well.  After it the
+    // tile is published and everyone has finished the tile before it, whose stage the next loads overwrite.
+    auto publish = [&](bool newer) {
+        if (newer)
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);
+        else
+            __builtin_amdgcn_s_waitcnt(0x0070);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
 
     const int kend = min(sh.s, qb * 256 + 256);     // keys needed by this block: [0, kend)
+    const int kfull = qb * 256;                     // tiles before it are fully visible to every wavefront
     for (;;) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -405,25 +417,42 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
         // three LDS stages: tile k0 is multiplied while tiles k0 + KT and k0 + 2 KT are in flight
         dma_tile(0, 0);
         if (KT < kend) dma_tile(KT, 1);
-        int stage = 0;
-        bool again = false;
-        for (int k0 = 0; k0 < kend; k0 += KT, stage = stage == NSTAGE - 1 ? 0 : stage + 1) {
-            // Bare s_barrier (a __syncthreads() fence would wait for the tile still in flight too): this
-            // wavefront's part of tile k0 has landed and its LDS reads of the previous tile have returned.
-            if (k0 + KT < kend)
-                __builtin_amdgcn_s_waitcnt(kWaitOlder);
-            else
-                __builtin_amdgcn_s_waitcnt(0x0070);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();  // tile k0 is published; everyone has finished the tile before it, whose
-            asm volatile("" ::: "memory"); // stage the next loads overwrite
-            if (restart_flag[0]) { again = true; break; }
-            if (k0 + 2 * KT < kend) dma_tile(k0 + 2 * KT, stage == 0 ? NSTAGE - 1 : stage - 1);
-            if (k0 > qw0 + 63) continue;           // whole tile is in this wavefront's future
-            tile(k0, stage);
+        if (m_ref[0] == -INFINITY) {
+            // First attempt: the scores of each query's first 32 keys fix its softmax reference (key 0 is
+            // visible to every query; for the first queries of the sequence these keys are partly masked).
+            publish(KT < kend);
+            read_k(lds + koff, 0);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                s_group(0, g);
+                s_group(1, g);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int qrel = qw0 + 32 * u + lrow - 4 * half;
+                float raw = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (8 * (r >> 2) + (r & 3) <= qrel) raw = fmaxf(raw, st[u][r]);
+                m_ref[u] = fmaxf(raw, __shfl_xor(raw, 32, 64)) * c2;
+            }
         }
-        __syncthreads();                            // the last tile may have raised the flag as well
-        if (!again && !restart_flag[0]) break;
+        // No early exit on the restart flag: an attempt that is going to be repeated just runs to its end
+        // (rare enough not to matter), which keeps both loops free of side exits - with those the compiler
+        // copies the whole output accumulator at every iteration.
+        int stage = 0, k0 = 0;
+        for (; k0 < kfull; k0 += KT, stage = stage == NSTAGE - 1 ? 0 : stage + 1) {      // fully visible tiles
+            publish(true);
+            dma_tile(k0 + 2 * KT, stage == 0 ? NSTAGE - 1 : stage - 1);
+            tile(k0, stage, std::false_type{});
+        }
+        for (; k0 < kend; k0 += KT, stage = stage == NSTAGE - 1 ? 0 : stage + 1) {       // the diagonal part
+            publish(k0 + KT < kend);
+            if (k0 + 2 * KT < kend) dma_tile(k0 + 2 * KT, stage == 0 ? NSTAGE - 1 : stage - 1);
+            if (k0 <= qw0) tile(k0, stage, std::true_type{});
+        }
+        __syncthreads();
+        if (!restart_flag[0]) break;
         // start over with a larger reference
         __builtin_amdgcn_s_waitcnt(0x0F70);         // loads of tiles that were still in flight
         __syncthreads();
