@@ -132,7 +132,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base) {
 //   pitch_rd<DH>  rows read with ds_read_b128 (lane = row): 16 bytes of padding rotate the banks row by row
 //   pitch_tr<DH>  rows read with the transposing ds_read_b64_tr_b16, one pass of which covers 4 consecutive
 //                 rows x 64 bytes: power-of-two row sizes get 64 bytes of padding, the others already stagger
+//   pitch_both<DH> rows read both ways: an odd number of 16-byte slots (ds_read_b128 conflict-free) that is 5 or 13
+//                 modulo 16, which leaves the transposing read with two-way conflicts on a few lanes only
 template <int DH> constexpr int pitch_rd() { return DH + 8; }
+template <int DH> constexpr int pitch_both() { return DH <= 32 ? 40 : DH <= 96 ? 104 : 168; }
 template <int DH> constexpr int pitch_tr() { return (DH == 64 || DH == 128) ? DH + 32 : DH; }
 
 // Per-lane part of the address of a transposed operand read from a NATURAL tile [position][pitch]:
@@ -481,6 +484,17 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     }
 }
 
+// Explicit instantiations: the host compiler does not always emit the launch stub of a kernel template from its
+// use in the launcher below alone.
+#define LGA_INSTANTIATE_FWD(DH) \
+    template __global__ void attn_fwd_kernel<DH>(const bf16 *, bf16 *, float *, AttnShape)
+LGA_INSTANTIATE_FWD(32);
+LGA_INSTANTIATE_FWD(64);
+LGA_INSTANTIATE_FWD(96);
+LGA_INSTANTIATE_FWD(128);
+LGA_INSTANTIATE_FWD(160);
+#undef LGA_INSTANTIATE_FWD
+
 // ============================================================================================
 // delta[b, h, q] = sum_c dO[q, h*DH + c] * O[q, h*DH + c].  One wavefront per (token, head).
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict__ out, const bf16 *__restrict__ dout,
@@ -505,16 +519,24 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict_
 
 // ============================================================================================
 // dQ.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
-template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+//
+// A wavefront owns 32 queries (Q and dO operands in registers); key tiles of 64 (K and V as stored) stream
+// from global memory straight into one of two LDS stages while the other is multiplied, one barrier per
+// tile.  K^T operands come from the natural K tile through the transposing LDS read.  Two workgroups per
+// CU, so that one's MFMAs run under the other's VALU work.
+template <int DH, int OCC>
+__global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
                                                           const float *__restrict__ delta,
                                                           const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
                                                           AttnShape sh) {
-    constexpr int KT = 32;
+    constexpr int KT = 64;
     constexpr int NK = DH / 16, NC = DH / 32;
-    __shared__ __attribute__((aligned(16))) bf16 Ks[KT * DH];
-    __shared__ __attribute__((aligned(16))) bf16 Vs[KT * DH];
-    __shared__ __attribute__((aligned(16))) bf16 Kt[DH * KT];
+    constexpr int PK = pitch_both<DH>(), PV = pitch_rd<DH>();
+    typedef TileDma<KT, DH, PK> DmaK;
+    typedef TileDma<KT, DH, PV> DmaV;
+    constexpr int STAGE = DmaK::ELEMS + DmaV::ELEMS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
 
     const int qblocks = (sh.s + 127) / 128;
     const int qb = qblocks - 1 - blockIdx.x;
@@ -522,7 +544,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
     const int d = sh.heads * DH;
     const size_t pitch = 3 * (size_t)d;
     const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int qw0 = qb * 128 + wave * 32;
     const int q = qw0 + lrow;
@@ -547,35 +569,74 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
 
+    DmaK dk;
+    DmaV dv;
+    dk.init(wave, lane, (int)(pitch * 2));
+    dv.init(wave, lane, (int)(pitch * 2));
+    auto dma_tile = [&](int k0, int stage) {
+        bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
+        dk.issue(seq + (size_t)k0 * pitch + d, Ks, sh.s - k0, wave);
+        dv.issue(seq + (size_t)k0 * pitch + 2 * d, Vs, sh.s - k0, wave);
+    };
+    const int koff = lrow * PK + 8 * half, voff = lrow * PV + 8 * half;   // per-lane parts of the operand addresses
+    const int ktoff = tr_lane_off<PK>(lane);
+
     const int kend = min(sh.s, qb * 128 + 128);
-    for (int k0 = 0; k0 < kend; k0 += KT) {
-        __syncthreads();
-        load_nat<KT, DH>(Ks, seq + (size_t)k0 * pitch + d, pitch, sh.s - k0);
-        load_nat<KT, DH>(Vs, seq + (size_t)k0 * pitch + 2 * d, pitch, sh.s - k0);
-        load_tr<KT, DH>(Kt, seq + (size_t)k0 * pitch + d, pitch, sh.s - k0);
-        __syncthreads();
-        if (k0 > qw0 + 31) continue;
-        f32x16 st, dpt;
+    dma_tile(0, 0);
+    int stage = 0;
+    for (int k0 = 0; k0 < kend; k0 += KT, stage ^= 1) {
+        // this wavefront's part of tile k0 has landed and its LDS reads of the previous tile have returned; after
+        // the barrier the tile is published and the other stage is free for the next one
+        __builtin_amdgcn_s_waitcnt(0x0070);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (k0 + KT < kend) dma_tile(k0 + KT, stage ^ 1);
+        if (k0 > qw0 + 31) continue;               // whole tile is in this wavefront's future
+        const bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st[r] = dpt[r] = 0.f;
+        for (int kb = 0; kb < 2; ++kb) {
+            const int kbs = k0 + 32 * kb;          // first key of this block of 32
+            if (kbs > qw0) continue;               // in the future of all 32 queries (both are multiples of 32)
+            bf16x8 kf[NK], vfr[NK], ktf[2 * NC];
 #pragma unroll
-        for (int ks = 0; ks < NK; ++ks) {
-            st = MFMA(frag_nat<DH>(Ks, lrow, ks, half), qf[ks], st);
-            dpt = MFMA(frag_nat<DH>(Vs, lrow, ks, half), dof[ks], dpt);
-        }
-        const bool diag = k0 + KT - 1 > qw0;        // some (query, key) pair of this tile is masked
+            for (int ks = 0; ks < NK; ++ks) {
+                kf[ks] = *reinterpret_cast<const bf16x8 *>(Ks + koff + kb * 32 * PK + 16 * ks);
+                vfr[ks] = *reinterpret_cast<const bf16x8 *>(Vs + voff + kb * 32 * PV + 16 * ks);
+            }
+            f32x16 st, dpt;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = k0 + 8 * (r >> 2) + 4 * half + (r & 3);
-            float p = __builtin_amdgcn_exp2f(fmaf(st[r], c2, -lse2));
-            if (diag && key > q) p = 0.f;
-            st[r] = p * (dpt[r] - dl);
-        }
+            for (int ks = 0; ks < NK; ++ks) {
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                st = MFMA(kf[ks], qf[ks], ks == 0 ? zero : st);
+                dpt = MFMA(vfr[ks], dof[ks], ks == 0 ? zero : dpt);
+            }
+            // the K^T operands take over the registers of the K and V operands; their latency passes under the
+            // exponentials
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const bf16x8 dsf = pack_bf16(st, kk);
+            for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-            for (int c = 0; c < NC; ++c) acc[c] = MFMA(frag_tr<KT>(Kt, c * 32 + lrow, kk, half), dsf, acc[c]);
+                for (int c = 0; c < NC; ++c) ktf[kk * NC + c] = frag_nat_tr<PK>(Ks + ktoff, c, 2 * kb + kk);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kbs == qw0) {                       // the diagonal block: keys beyond the query are masked
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float p = __builtin_amdgcn_exp2f(fmaf(st[r], c2, -lse2));
+                    if (8 * (r >> 2) + 4 * half + (r & 3) > lrow) p = 0.f;
+                    st[r] = p * (dpt[r] - dl);
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st[r] = __builtin_amdgcn_exp2f(fmaf(st[r], c2, -lse2)) * (dpt[r] - dl);
+            }
+            wait_tr_reads(ktf);
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const bf16x8 dsf = pack_bf16(st, kk);
+#pragma unroll
+                for (int c = 0; c < NC; ++c) acc[c] = MFMA(ktf[kk * NC + c], dsf, acc[c]);
+            }
         }
     }
     if (qvalid) {
@@ -591,6 +652,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16 *__restr
             }
     }
 }
+
+#define LGA_INSTANTIATE_DQ(DH, OCC)                                                                                  \
+    template __global__ void attn_bwd_dq_kernel<DH, OCC>(const bf16 *, const float *, const float *, const bf16 *, \
+                                                         bf16 *, AttnShape)
+LGA_INSTANTIATE_DQ(32, 2);
+LGA_INSTANTIATE_DQ(64, 2);
+LGA_INSTANTIATE_DQ(96, 2);
+LGA_INSTANTIATE_DQ(128, 2);
+LGA_INSTANTIATE_DQ(160, 1);
+#undef LGA_INSTANTIATE_DQ
 
 // ============================================================================================
 // dK, dV.  grid.x = key blocks of 128 (smallest index first: it has the most queries), grid.y = n_seq * heads.
@@ -781,7 +852,16 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
     {
         snprintf(name, sizeof(name), "attn_bwd_dq_kernel<%d>", DH);
         ProfScope scope(name, 6.0 * pairs * DH, 5.0 * act, s);
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH>), grid, dim3(256), 0, s, qkv, lse, delta, dout, dqkv, sh);
+        constexpr int kOccDq = DH <= 128 ? 2 : 1;     // workgroups per CU the register budget is set for
+        // two stages of a 64-key K tile and V tile
+        constexpr int smem_dq = 2 * (TileDma<64, DH, pitch_both<DH>()>::ELEMS + TileDma<64, DH, pitch_rd<DH>()>::ELEMS) * 2;
+        static bool attr_set_dq = false;
+        if (!attr_set_dq) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dq_kernel<DH, kOccDq>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq);
+            attr_set_dq = true;
+        }
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, kOccDq>), grid, dim3(256), smem_dq, s, qkv, lse, delta, dout, dqkv, sh);
     }
     {
         snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
