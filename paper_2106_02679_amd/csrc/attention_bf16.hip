@@ -664,26 +664,104 @@ LGA_INSTANTIATE_DQ(160, 1);
 #undef LGA_INSTANTIATE_DQ
 
 // ============================================================================================
+// Tiles that are read both ways - rows with ds_read_b128 and transposed with ds_read_b64_tr_b16 - keep the
+// unpadded pitch DH and an XOR swizzle of the 16-byte chunk index that is free of bank conflicts for both:
+// 16 consecutive rows put one logical chunk into 16 different bank groups, and 4 consecutive rows (from a
+// multiple of 4) put an aligned group of 4 chunks into 4 different ones.
+template <int DH> __device__ __forceinline__ int sw_both(int row) {
+    if constexpr (DH == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+    else if constexpr (DH == 64) return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+    else return (row >> 2) & 3;              // 32, 96, 160: the row pitch already staggers groups of 4 chunks
+}
+// DMA of a ROWS x DH tile (global row pitch gp2 bytes) into such a tile: lane L of instruction j fills chunk
+// slot 64 j + L = row * (DH / 8) + physical chunk, with the logical chunk that the swizzle maps there.
+template <int ROWS, int DH> struct TileDmaSw {
+    static constexpr int NCH = DH / 8;
+    static constexpr int NI = ROWS * NCH / 64;              // instructions per tile
+    static constexpr int NJ = (NI + 3) / 4;                 // per wavefront, at most
+    static constexpr int ELEMS = ROWS * DH;
+    static_assert((ROWS * NCH) % 64 == 0, "tile is a whole number of DMA instructions");
+    int row[NJ], off[NJ];
+    __device__ __forceinline__ void init(int wave, int lane, int gp2) {
+#pragma unroll
+        for (int i = 0; i < NJ; ++i) {
+            const int slot = (i * 4 + wave) * 64 + lane, r = slot / NCH, pc = slot % NCH;
+            row[i] = r;
+            off[i] = r * gp2 + ((pc ^ sw_both<DH>(r)) << 4);
+        }
+    }
+    __device__ __forceinline__ void issue(const bf16 *src, bf16 *dst, int nvalid, int wave) const {
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
+#pragma unroll
+        for (int i = 0; i < NJ; ++i) {
+            const int j = i * 4 + wave;
+            if (j >= NI) continue;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(dst + j * 512), 16, row[i] < nvalid ? off[i] : kBufPoison,
+                                                     0, 0, 0);
+        }
+    }
+};
+// Per-lane address parts (elements) of the two kinds of operand read from such a tile.  The swizzle splits
+// into a part that XORs the chunk group (DH = 64, 128 only) and one that XORs within the group, which leaves
+// few distinct lane values; everything else is a compile-time offset.
+template <int DH> struct BothAddr {
+    static constexpr int NG = DH == 128 ? 4 : DH == 64 ? 2 : 1;     // chunk groups the swizzle permutes
+    int nb[NG][2];      // natural read: [chunk group][ks & 1]
+    int tb[NG][2];      // transposed read: [32-column block c (if NG > 1)][second half of the 16 positions]
+    __device__ __forceinline__ void init(int lane) {
+        const int lrow = lane & 31, half = lane >> 5, i = lane & 15, g = (lane >> 4) & 1;
+        const int s = sw_both<DH>(lrow), s_hi = s >> 2, s_lo = s & 3;
+#pragma unroll
+        for (int a = 0; a < NG; ++a)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) nb[a][e] = lrow * DH + 32 * (a ^ s_hi) + (((2 * e + half) ^ s_lo) << 3);
+#pragma unroll
+        for (int sec = 0; sec < 2; ++sec) {
+            const int row = 8 * sec + 4 * half + (i >> 2);           // + 16 kk, which does not change the swizzle
+            const int t = sw_both<DH>(row), t_hi = t >> 2, t_lo = t & 3;
+            const int b = 2 * g + ((i & 3) >> 1);
+#pragma unroll
+            for (int c = 0; c < NG; ++c) tb[c][sec] = row * DH + 32 * (c ^ t_hi) + ((b ^ t_lo) << 3) + 4 * (i & 1);
+        }
+    }
+    // MFMA first operand: row 32 u + lrow of the tile, k = 16 ks + 8 half + (0..7)
+    __device__ __forceinline__ bf16x8 nat(const bf16 *tile, int u, int ks) const {
+        const int a = ks >> 1;
+        return *reinterpret_cast<const bf16x8 *>(tile + 32 * u * DH + nb[NG > 1 ? a : 0][ks & 1] + (NG > 1 ? 0 : 32 * a));
+    }
+    // MFMA first operand "row 32 c + lrow of the transposed tile, k element e <-> tile row 16 kk + 8 (e/4) + 4 half + e%4"
+    __device__ __forceinline__ bf16x8 tr(const bf16 *tile, int c, int kk) const {
+        const uint32_t a0 = (uint32_t)(uintptr_t)(tile + tb[NG > 1 ? c : 0][0]);
+        const uint32_t a1 = (uint32_t)(uintptr_t)(tile + tb[NG > 1 ? c : 0][1]);
+        u32x2 lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a0), "i"((16 * kk * DH + (NG > 1 ? 0 : 32 * c)) * 2));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a1), "i"((16 * kk * DH + (NG > 1 ? 0 : 32 * c)) * 2));
+        const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+        return __builtin_bit_cast(bf16x8, v);
+    }
+};
+
+// ============================================================================================
 // dK, dV.  grid.x = key blocks of 128 (smallest index first: it has the most queries), grid.y = n_seq * heads.
-// Query tiles of 64 are streamed through LDS.  Each thread owns 8x8 blocks of Q and dO: it loads them once
-// from global memory (prefetched into registers one tile ahead, under the previous tile's MFMAs) and stores
-// them twice, as they are and transposed.
+//
+// A wavefront owns 32 keys (K and V operands in registers, dK and dV accumulators); query tiles of 64 (Q and
+// dO as stored) stream from global memory straight into one of three LDS stages, one barrier per tile.  Every
+// tile is read both ways: rows for S = Q K^T and dP = dO V^T, transposed for dV^T += dO^T P and dK^T += Q^T dS.
+// The first two query tiles of a key block contain its diagonal (masked, partly skipped); all later ones are
+// fully visible and go through a loop without tests.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
-                                                           const float *__restrict__ delta,
-                                                           const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
-                                                           AttnShape sh) {
-    constexpr int QT = 64;
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+                                                              const float *__restrict__ delta,
+                                                              const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
+                                                              AttnShape sh) {
+    constexpr int QT = 64, NST = 3;
     constexpr int NK = DH / 16, NC = DH / 32;
-    constexpr int NBLK = 2 * (QT / 8) * (DH / 8);       // 8x8 blocks of Q and of dO per tile
-    constexpr int NB = (NBLK + 255) / 256;              // blocks per thread
+    typedef TileDmaSw<QT, DH> Dma;
+    constexpr int TILE = Dma::ELEMS, STAGE = 2 * TILE;          // Q tile, then dO tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *Qs = reinterpret_cast<bf16 *>(smem_raw);      // [QT][DH]
-    bf16 *dOs = Qs + QT * DH;                           // [QT][DH]
-    bf16 *Qt = dOs + QT * DH;                           // [DH][QT]
-    bf16 *dOt = Qt + QT * DH;                           // [DH][QT]
-    float *lse_s = reinterpret_cast<float *>(dOt + QT * DH);   // [QT]
-    float *dl_s = lse_s + QT;                                   // [QT]
+    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    float *lse_s = reinterpret_cast<float *>(lds + NST * STAGE);     // [NST][QT]  log-sum-exp, log2 domain, negated
+    float *dl_s = lse_s + NST * QT;                                  // [NST][QT]  delta
 
     const int kb128 = blockIdx.x;
     const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
@@ -691,7 +769,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
     const size_t pitch = 3 * (size_t)d;
     const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
     const bf16 *doseq = dout + (size_t)b * sh.s * d + (size_t)h * DH;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int kw0 = kb128 * 128 + wave * 32;        // first key of this wavefront
     const int key = kw0 + lrow;
@@ -713,99 +791,145 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
 #pragma unroll
         for (int r = 0; r < 16; ++r) dk[c][r] = dv[c][r] = 0.f;
 
-    // staging: block blk < NBLK/2 belongs to Q, the rest to dO; (pb, db) = (8-row group, 8-column group)
-    u32x4 stg[NB][8];
-    float stg_lse = 0.f, stg_dl = 0.f;
-    auto prefetch = [&](int q0) {
-#pragma unroll
-        for (int r = 0; r < NB; ++r) {
-            const int blk = threadIdx.x + 256 * r;
-            const bool is_q = blk < NBLK / 2;
-            const int bb = is_q ? blk : blk - NBLK / 2;
-            const int db = bb % (DH / 8), pb = bb / (DH / 8);
-            const bf16 *src = is_q ? seq + (size_t)q0 * pitch : doseq + (size_t)q0 * d;
-            const size_t sp = is_q ? pitch : (size_t)d;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int row = pb * 8 + j;
-                stg[r][j] = u32x4{0, 0, 0, 0};
-                if (blk < NBLK && q0 + row < sh.s)
-                    stg[r][j] = *reinterpret_cast<const u32x4 *>(src + (size_t)row * sp + db * 8);
-            }
-        }
-        if (threadIdx.x < QT) {
-            const int qq = q0 + threadIdx.x;
-            stg_lse = qq < sh.s ? lse[stat0 + qq] * kLog2e : 0.f;
-            stg_dl = qq < sh.s ? delta[stat0 + qq] : 0.f;
-        }
+    Dma dq_, do_;
+    dq_.init(wave, lane, (int)(pitch * 2));
+    do_.init(wave, lane, d * 2);
+    BothAddr<DH> ad;
+    ad.init(lane);
+    // Tile t holds queries [qbeg + 64 t, +64).  Its row statistics go through registers: wavefront 0 fetches the
+    // log-sum-exps, wavefront 1 the deltas, one tile ahead of the tile data, and they are stored to LDS before
+    // the barrier that publishes the tile.
+    const int qbeg = kb128 * 128;
+    const int ntiles = (sh.s - qbeg + QT - 1) / QT;
+    auto dma_tile = [&](int t, int stage) {
+        const int q0 = qbeg + QT * t;
+        dq_.issue(seq + (size_t)q0 * pitch, lds + stage * STAGE, sh.s - q0, wave);
+        do_.issue(doseq + (size_t)q0 * d, lds + stage * STAGE + TILE, sh.s - q0, wave);
     };
-    auto commit = [&]() {
-#pragma unroll
-        for (int r = 0; r < NB; ++r) {
-            const int blk = threadIdx.x + 256 * r;
-            if (blk >= NBLK) continue;
-            const bool is_q = blk < NBLK / 2;
-            const int bb = is_q ? blk : blk - NBLK / 2;
-            const int db = bb % (DH / 8), pb = bb / (DH / 8);
-            bf16 *nat = is_q ? Qs : dOs, *tr = is_q ? Qt : dOt;
-            u32x4 t[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4 *>(nat + nat_off<DH>(pb * 8 + j, db)) = stg[r][j];
-            transpose8x8(stg[r], t);
-#pragma unroll
-            for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(tr + tr_off<QT>(db * 8 + c, pb)) = t[c];
-        }
-        if (threadIdx.x < QT) {
-            lse_s[threadIdx.x] = stg_lse;
-            dl_s[threadIdx.x] = stg_dl;
-        }
+    auto load_stat = [&](int t) -> float {
+        const int qq = qbeg + QT * t + lane;
+        if (wave == 0) return qq < sh.s ? -lse[stat0 + qq] * kLog2e : 0.f;
+        if (wave == 1) return qq < sh.s ? delta[stat0 + qq] : 0.f;
+        return 0.f;
+    };
+    auto store_stat = [&](int stage, float v) {
+        if (wave == 0) lse_s[stage * QT + lane] = v;
+        if (wave == 1) dl_s[stage * QT + lane] = v;
     };
 
-    // queries that can see any key of this block: [kb128*128, s), walked in tiles of 64
-    const int qbeg = kb128 * 128;
-    prefetch(qbeg);
-    for (int q0 = qbeg; q0 < sh.s; q0 += QT) {
-        __syncthreads();                 // everyone is done with the previous tile
-        commit();
-        __syncthreads();
-        if (q0 + QT < sh.s) prefetch(q0 + QT);
+    // one (32 keys x 32 queries) unit of tile `stage`: query rows [32 u, 32 u + 32) of the tile, first query qs
+    auto unit = [&](int stage, int u, int qs, auto masked_c) {
+        constexpr bool MASKED = decltype(masked_c)::value;
+        const bf16 *Qs = lds + stage * STAGE, *dOs = Qs + TILE;
+        bf16x8 qn[NK], don[NK];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int qs = q0 + qb * 32;                 // first query of this 32-query sub-tile
-            if (qs + 31 < kw0 || qs >= sh.s) continue;   // all its queries precede this wavefront's keys, or are past the end
-            f32x16 s_, dp;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s_[r] = dp[r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < NK; ++ks) {
-                s_ = MFMA(frag_nat<DH>(Qs, qb * 32 + lrow, ks, half), kf[ks], s_);
-                dp = MFMA(frag_nat<DH>(dOs, qb * 32 + lrow, ks, half), vf[ks], dp);
-            }
-            f32x16 pr;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + qb * 32 + 8 * g + 4 * half);
-                const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dl_s + qb * 32 + 8 * g + 4 * half);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int r = 4 * g + i;
-                    const int qq = qs + 8 * g + 4 * half + i;
-                    const float p = (qq >= key && qq < sh.s && kvalid) ? __builtin_amdgcn_exp2f(fmaf(s_[r], c2, -l4[i])) : 0.f;
-                    pr[r] = p;
-                    s_[r] = p * (dp[r] - d4[i]);
-                }
-            }
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 pf = pack_bf16(pr, kk);
-                const bf16x8 dsf = pack_bf16(s_, kk);
-#pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    dv[c] = MFMA(frag_tr<QT>(dOt, c * 32 + lrow, 2 * qb + kk, half), pf, dv[c]);
-                    dk[c] = MFMA(frag_tr<QT>(Qt, c * 32 + lrow, 2 * qb + kk, half), dsf, dk[c]);
-                }
-            }
+        for (int ks = 0; ks < NK; ++ks) {
+            qn[ks] = ad.nat(Qs, u, ks);
+            don[ks] = ad.nat(dOs, u, ks);
         }
+        f32x4 l4[4], d4[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            l4[g] = *reinterpret_cast<const f32x4 *>(lse_s + stage * QT + 32 * u + 8 * g + 4 * half);
+            d4[g] = *reinterpret_cast<const f32x4 *>(dl_s + stage * QT + 32 * u + 8 * g + 4 * half);
+        }
+        f32x16 s_, dp;
+#pragma unroll
+        for (int ks = 0; ks < NK; ++ks) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            s_ = MFMA(qn[ks], kf[ks], ks == 0 ? zero : s_);
+            dp = MFMA(don[ks], vf[ks], ks == 0 ? zero : dp);
+        }
+        // the transposed operands take over the registers of the row operands; their latency passes under the
+        // exponentials
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 dot[2 * NC], qt[2 * NC];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                dot[kk * NC + c] = ad.tr(dOs, c, 2 * u + kk);
+                qt[kk * NC + c] = ad.tr(Qs, c, 2 * u + kk);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 pr;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = 4 * g + i;
+                float p = __builtin_amdgcn_exp2f(fmaf(s_[r], c2, l4[g][i]));
+                if (MASKED && qs + 8 * g + 4 * half + i < key) p = 0.f;
+                pr[r] = p;
+                s_[r] = p * (dp[r] - d4[g][i]);
+            }
+        bf16x8 pf[2], dsf[2];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            pf[kk] = pack_bf16(pr, kk);
+            dsf[kk] = pack_bf16(s_, kk);
+        }
+        wait_tr_reads(dot);
+        wait_tr_reads(qt);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                dv[c] = MFMA(dot[kk * NC + c], pf[kk], dv[c]);
+                dk[c] = MFMA(qt[kk * NC + c], dsf[kk], dk[c]);
+            }
+    };
+    // wait for this wavefront's part of the oldest tile in flight (`newer`: a younger one is in flight too),
+    // then a bare s_barrier - a __syncthreads() fence would wait for the younger tile as well
+    constexpr int kLoadsPerTile = 2 * Dma::NJ;      // upper bound of what a wavefront issues per tile
+    static_assert(Dma::NI % 4 == 0 && kLoadsPerTile < 16, "every wavefront issues the same number of loads per tile");
+    auto publish = [&](bool newer) {
+        if (newer)
+            __builtin_amdgcn_s_waitcnt(0x0070 | kLoadsPerTile);
+        else
+            __builtin_amdgcn_s_waitcnt(0x0070);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    // tile t is multiplied while tiles t + 1 and t + 2 are in flight
+    float stat = load_stat(0);
+    dma_tile(0, 0);
+    store_stat(0, stat);
+    if (ntiles > 1) {
+        stat = load_stat(1);
+        dma_tile(1, 1);
+    }
+    // start of every iteration: tile t + 1's statistics go to LDS (published by the barrier after next... by
+    // the next iteration's barrier), tile t is published, tile t + 2 is requested
+    auto advance = [&](int t, int stage) {
+        const int next = stage == NST - 1 ? 0 : stage + 1, after = next == NST - 1 ? 0 : next + 1;
+        if (t + 1 < ntiles) store_stat(next, stat);
+        publish(t + 1 < ntiles);
+        if (t + 2 < ntiles) {
+            stat = load_stat(t + 2);
+            dma_tile(t + 2, after);
+        }
+    };
+    // Two loops in sequence rather than one with two kinds of iteration: with two code paths through the
+    // MFMAs in one loop the compiler merges their accumulator registers with copies at every iteration.
+    int stage = 0, t = 0;
+    for (; t < 2 && t < ntiles; ++t, stage = stage == NST - 1 ? 0 : stage + 1) {      // the diagonal part
+        advance(t, stage);
+        const int q0 = qbeg + QT * t;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int qs = q0 + 32 * u;
+            if (qs + 31 < kw0 || qs >= sh.s) continue;      // all its queries precede this wavefront's keys, or are past the end
+            unit(stage, u, qs, std::true_type{});
+        }
+    }
+    for (; t < ntiles; ++t, stage = stage == NST - 1 ? 0 : stage + 1) {               // fully visible tiles
+        advance(t, stage);
+        const int q0 = qbeg + QT * t;
+        unit(stage, 0, q0, std::false_type{});
+        unit(stage, 1, q0 + 32, std::false_type{});
     }
     if (kvalid) {
         bf16 *orow = dqkv + ((size_t)b * sh.s + key) * pitch + (size_t)h * DH;
@@ -824,6 +948,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16 *__restric
             }
     }
 }
+#define LGA_INSTANTIATE_DKV(DH)                                                                                \
+    template __global__ void attn_bwd_dkv_kernel<DH>(const bf16 *, const float *, const float *, const bf16 *, \
+                                                     bf16 *, AttnShape)
+LGA_INSTANTIATE_DKV(32);
+LGA_INSTANTIATE_DKV(64);
+LGA_INSTANTIATE_DKV(96);
+LGA_INSTANTIATE_DKV(128);
+LGA_INSTANTIATE_DKV(160);
+#undef LGA_INSTANTIATE_DKV
 
 template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
     dim3 grid((sh.s + 255) / 256, sh.n_seq * sh.heads);
@@ -866,7 +999,7 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
     {
         snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
         ProfScope scope(name, 8.0 * pairs * DH, 6.0 * act, s);
-        constexpr int smem = 4 * 64 * DH * 2 + 2 * 64 * 4;      // four 64 x DH tiles and the row statistics
+        constexpr int smem = 3 * (2 * 64 * DH * 2 + 2 * 64 * 4);   // three stages of a Q tile, a dO tile and the row statistics
         static bool attr_set = false;
         if (!attr_set) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_kernel<DH>),
