@@ -625,9 +625,10 @@ void launch_one(const GemmParams<bf16> &p, hipStream_t s) {
 }
 
 template <bool A_KM, bool B_KM, int EPI> void launch_tiles(const GemmParams<bf16> &p, hipStream_t s) {
-    // Large tiles when they still give every CU at least two workgroups; smaller ones otherwise.
+    // Large tiles when they fill the 256 CUs at least about once (the direct-to-LDS kernel is so much faster per
+    // tile that a partly idle second round still wins); smaller ones otherwise.
     const long big = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-    if (big >= 512)
+    if (big >= 224)
         launch_one<256, 256, A_KM, B_KM, EPI>(p, s);
     else
         launch_one<128, 128, A_KM, B_KM, EPI>(p, s);
