@@ -64,8 +64,8 @@ def _run(w, group, x, dy, want_layer0_params):
 def test_cfg3_sampled_prefix_parity_and_regrouping():
     w = S.CONFIGS[3]
     free, _ = torch.cuda.mem_get_info()
-    if free < 160e9:
-        pytest.skip("needs about 150 GB of free HBM")
+    if free < 185e9:
+        pytest.skip("needs about 175 GB of free HBM")
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     gen = torch.Generator(device="cuda").manual_seed(0)
     x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(torch.bfloat16)
