@@ -33,6 +33,10 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="index into the five benchmark configurations")
     ap.add_argument("--group", type=int, default=0, help="micro-batches per kernel launch (0 = default for the config)")
     ap.add_argument("--order", choices=["layered", "mbmajor"], default="layered")
+    ap.add_argument("--overlap", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="bits: 1 = restores, 2 = per-layer Adam steps on the library's second stream beside the layer sweeps")
+    ap.add_argument("--param-buffers", type=int, default=0,
+                    help="16-bit parameter buffers kept (0 = one per layer); fewer makes the orders differ in restore traffic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=64)
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
@@ -95,7 +99,8 @@ def main():
     while w.n_micro % group:
         group -= 1
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
-                        group=group, retain_grads=1 if args.order == "mbmajor" else 0)
+                        group=group, retain_grads=1 if args.order == "mbmajor" else 0, param_buffers=args.param_buffers,
+                        overlap=args.overlap)
     torch.cuda.set_device(0)
     tdt = torch.bfloat16 if dt == B.LGA_BF16 else torch.float32
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
@@ -118,6 +123,7 @@ def main():
         step(t); t += 1
     torch.cuda.synchronize()
     st.profile_begin()
+    restores0 = st.restore_count()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
@@ -126,6 +132,7 @@ def main():
     torch.cuda.synchronize()
     ms_total = e0.elapsed_time(e1)
     stats = st.profile_end()
+    restores = (st.restore_count() - restores0) / args.steps
     ms_step = ms_total / args.steps
 
     order = B.LGA_ORDER_LAYERED if args.order == "layered" else B.LGA_ORDER_MICROBATCH_MAJOR
@@ -165,7 +172,9 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model, "n_heads": w.n_heads,
                    "d_ff": w.d_ff, "seq_len": w.seq_len, "micro_batch": w.micro_batch, "n_micro": w.n_micro,
-                   "group": group, "order": args.order, "tokens_per_step": tokens},
+                   "group": group, "order": args.order, "tokens_per_step": tokens,
+                   "param_buffers": args.param_buffers or w.n_layers, "overlap": args.overlap},
+        "restores_per_step": restores,
         "tflops_executed": flops_exec / ms_step / 1e9,
         "pct_peak_executed": 100.0 * flops_exec / ms_step / 1e9 / peak,
         "pct_peak_paper_flops": 100.0 * flops_paper / ms_step / 1e9 / peak,     # 8 p + 9 s^2 d accounting

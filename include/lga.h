@@ -55,6 +55,9 @@ enum lga_status {
     LGA_ERR_HIP = -5    /* HIP runtime error (no device, launch failure) */
 };
 
+/* Work the library may run on a second stream of its own (lga_config.overlap). */
+enum lga_overlap { LGA_OVERLAP_NONE = 0, LGA_OVERLAP_RESTORE = 1, LGA_OVERLAP_ADAM = 2 };
+
 /* Order in which (layer, micro-batch) pairs are visited. */
 enum lga_order { LGA_ORDER_LAYERED = 0, LGA_ORDER_MICROBATCH_MAJOR = 1 };
 
@@ -81,6 +84,22 @@ typedef struct lga_config {
                              the GEMM's k loop instead of by read-modify-write of the fp32 buffer.
                              1 = no merging, 0 = automatic (as many as keep those operand buffers within
                              a quarter of the rest of the arena), at most n_micro / group. */
+    int32_t param_buffers; /* bf16 mode: how many layers' 16-bit parameter copies are kept (figure 2, table C.1:
+                             parameter buffers).  0 = one per layer: nothing is ever restored, every Adam step
+                             rewrites its layer's copies.  With fewer, layer l uses buffer l % param_buffers and
+                             its fp32 masters are cast again ("restore") whenever another layer has used that
+                             buffer since: once per layer and pass in the layered order, once per layer, pass
+                             and micro-batch in the micro-batch-major order.  Results do not depend on it. */
+    int32_t overlap;      /* bits of enum lga_overlap.  If any is set the library creates a second stream (default
+                             priority) and runs on it, beside the layer sweeps on `stream`:
+                             LGA_OVERLAP_RESTORE  the restore of the next layer's 16-bit parameters while the
+                                                  current layer's sweep runs (param_buffers < n_layers; table C.1);
+                             LGA_OVERLAP_ADAM     each layer's fused Adam step of lga_backward_layered while the
+                                                  next layer's backward sweep runs; needs a second gradient
+                                                  buffer when retain_grads = 0, so two layers' gradients stay
+                                                  readable afterwards.
+                             Every entry point still returns with all its work ordered on `stream`: a caller that
+                             synchronises `stream` sees everything finished.  Results do not depend on it. */
     float ln_eps;         /* LayerNorm epsilon, inside the root (1e-5 in the benchmarks) */
     void *stream;         /* hipStream_t, borrowed; NULL = default stream */
 } lga_config;
@@ -147,11 +166,17 @@ int lga_checkpoint(lga_stack *stack, int32_t boundary, const void **dev_ptr, siz
  * Same kernels as the layered calls.  Requires retain_grads == 1 and group == 1. */
 int lga_step_mbmajor(lga_stack *stack, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam);
 
+/* Number of restores (casts of one layer's parameters into a 16-bit parameter buffer, section 2.5 /
+ * figure 2) the stack has done since it was created; the initial fill is not counted.  count: host. */
+int lga_restore_count(lga_stack *stack, uint64_t *count);
+
 /* Host-only analytic model of one step (no device needed), for printing beside measured
  * counters.  order is enum lga_order.
  *  param_bytes  HBM bytes of parameter traffic: 16-bit weight reads by the forward, recompute and
  *               input-gradient GEMM families per group, plus Adam's read of w, m, v and write of
- *               w, m, v, the 16-bit copy and the transposed 16-bit copy of the matrices.
+ *               w, m, v, the 16-bit copy and the transposed 16-bit copy of the matrices, plus - with
+ *               param_buffers < n_layers - the restores of a steady-state step (figure 2: constant in
+ *               n_micro for the layered order, proportional to it for the micro-batch-major order).
  *  grad_bytes   HBM bytes of fp32 gradient-buffer traffic: read-modify-write per group (write
  *               only for a layer's first group) plus Adam's read.
  *  flops        executed flops: GEMMs 2 flop per token per parameter for forward, recompute

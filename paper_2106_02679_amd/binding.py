@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "liblga.so")
 
 LGA_FP32, LGA_BF16 = 0, 1
 LGA_OK, LGA_ERR_ARG, LGA_ERR_SHAPE, LGA_ERR_OOM, LGA_ERR_STATE, LGA_ERR_HIP = 0, -1, -2, -3, -4, -5
+LGA_OVERLAP_NONE, LGA_OVERLAP_RESTORE, LGA_OVERLAP_ADAM = 0, 1, 2
 LGA_ORDER_LAYERED, LGA_ORDER_MICROBATCH_MAJOR = 0, 1
 (LGA_EPI_STORE, LGA_EPI_BIAS, LGA_EPI_BIAS_RESID, LGA_EPI_BIAS_GELU, LGA_EPI_MUL_DGELU,
  LGA_EPI_ACCUM_F32) = range(6)
@@ -32,7 +33,8 @@ _STATUS_NAMES = {0: "LGA_OK", -1: "LGA_ERR_ARG", -2: "LGA_ERR_SHAPE", -3: "LGA_E
 class lga_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
                 ("seq_len", C.c_int32), ("micro_batch", C.c_int32), ("n_micro", C.c_int32), ("dtype", C.c_int32),
-                ("group", C.c_int32), ("retain_grads", C.c_int32), ("wgrad_groups", C.c_int32), ("ln_eps", C.c_float),
+                ("group", C.c_int32), ("retain_grads", C.c_int32), ("wgrad_groups", C.c_int32), ("param_buffers", C.c_int32),
+                ("overlap", C.c_int32), ("ln_eps", C.c_float),
                 ("stream", C.c_void_p)]
 
 
@@ -75,6 +77,7 @@ SIGNATURES = {
     "lga_step_mbmajor": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _P(lga_adam)]),
     "lga_traffic_model": (C.c_int, [_P(lga_config), _i32, _P(_u64), _P(_u64), _P(C.c_double)]),
     "lga_arena_bytes": (C.c_int, [_P(lga_config), _P(_u64)]),
+    "lga_restore_count": (C.c_int, [_vp, _P(_u64)]),
     "lga_params_per_layer": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_last_error": (C.c_char_p, []),
     "lga_profile_begin": (C.c_int, [_vp]),
@@ -132,9 +135,9 @@ def check(code: int) -> None:
 
 
 def make_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group=1, retain_grads=0,
-                ln_eps=1e-5, stream: Optional[int] = None, wgrad_groups=0) -> lga_config:
+                ln_eps=1e-5, stream: Optional[int] = None, wgrad_groups=0, param_buffers=0, overlap=0) -> lga_config:
     return lga_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group, retain_grads,
-                      wgrad_groups, ln_eps, stream)
+                      wgrad_groups, param_buffers, overlap, ln_eps, stream)
 
 
 def params_per_layer(cfg: lga_config) -> int:
@@ -208,6 +211,11 @@ class Stack:
 
     def checkpoint(self, boundary: int):
         return self._borrow(lib.lga_checkpoint, boundary)
+
+    def restore_count(self) -> int:
+        out = _u64()
+        check(lib.lga_restore_count(self._h, C.byref(out)))
+        return out.value
 
     def profile_begin(self):
         check(lib.lga_profile_begin(self._h))

@@ -85,6 +85,9 @@ int validate_config(const lga_config *c) {
         return fail(LGA_ERR_SHAPE, "group must be in 1..n_micro and divide n_micro");
     if (c->wgrad_groups < 0 || c->wgrad_groups > c->n_micro / c->group)
         return fail(LGA_ERR_SHAPE, "wgrad_groups must be 0 (automatic) or in 1..n_micro/group");
+    if (c->param_buffers < 0 || c->param_buffers > c->n_layers)
+        return fail(LGA_ERR_SHAPE, "param_buffers must be 0 (one per layer) or in 1..n_layers");
+    if (c->overlap < 0 || c->overlap > 3) return fail(LGA_ERR_ARG, "overlap must be a combination of LGA_OVERLAP_* bits");
     if (!(c->ln_eps >= 0.f)) return fail(LGA_ERR_ARG, "ln_eps must be >= 0");
     if (c->dtype == LGA_FP32 && (2.0 * c->seq_len + 2.0 * c->d_model / c->n_heads) * 4 > 60000)
         return fail(LGA_ERR_SHAPE, "fp32 mode: seq_len too long for the one-wavefront attention kernel's LDS rows");
@@ -126,9 +129,10 @@ Plan make_plan(const lga_config &c) {
     p.w = take(L * P * 4);
     p.m = take(L * P * 4);
     p.v = take(L * P * 4);
-    p.grad = take((c.retain_grads ? L : 1) * P * 4);
-    p.w16 = take(c.dtype == LGA_BF16 ? L * P * 2 : 0);
-    p.w16t = take(c.dtype == LGA_BF16 ? L * P * 2 : 0);      // each matrix transposed, at its canonical offset
+    p.grad = take((c.retain_grads ? L : (c.overlap & LGA_OVERLAP_ADAM) ? std::min<size_t>(2, L) : 1) * P * 4);
+    const size_t nbuf = c.param_buffers ? (size_t)c.param_buffers : L;     // layers whose 16-bit copies are resident
+    p.w16 = take(c.dtype == LGA_BF16 ? nbuf * P * 2 : 0);
+    p.w16t = take(c.dtype == LGA_BF16 ? nbuf * P * 2 : 0);   // each matrix transposed, at its canonical offset
     p.ckpt = take((L + 1) * T * d * esz);
     p.dact = take(T * d * esz);
     p.h = take(t * d * esz);
@@ -188,14 +192,24 @@ struct lga_stack {
     size_t P, T, t;          // params per layer, tokens per step, tokens per group
     bool have_forward;
     std::vector<int> grad_owner;   // which layer's gradient each gradient buffer currently holds (-1: none)
+    int ngrad;                     // gradient buffers: layer l uses buffer l % ngrad
+    // overlap mode: Adam steps and restores run on a second stream beside the layer sweeps
+    hipStream_t aux;
+    hipEvent_t ev_fork;                        // "everything enqueued on the main stream so far"
+    std::vector<hipEvent_t> ev_w16, ev_grad;   // last write of each 16-bit parameter buffer / last read of each gradient buffer on aux
+    std::vector<char> w16_pending, grad_pending;   // the main stream has not waited for that event yet
+    int nbuf;                      // 16-bit parameter buffers: layer l uses buffer l % nbuf
+    std::vector<int> w16_owner;    // which layer's 16-bit copies each of them currently holds (-1: none)
+    uint64_t restores;             // casts of a layer's parameters into a buffer since creation
 
     template <class X> X *at(size_t off) const { return reinterpret_cast<X *>(arena + off); }
     float *w(int l) const { return at<float>(plan.w) + (size_t)l * P; }
     float *m(int l) const { return at<float>(plan.m) + (size_t)l * P; }
     float *v(int l) const { return at<float>(plan.v) + (size_t)l * P; }
-    bf16 *w16(int l) const { return at<bf16>(plan.w16) + (size_t)l * P; }
-    bf16 *w16t(int l) const { return at<bf16>(plan.w16t) + (size_t)l * P; }
-    int grad_slot(int l) const { return cfg.retain_grads ? l : 0; }
+    bf16 *w16(int l) const { return at<bf16>(plan.w16) + (size_t)(l % nbuf) * P; }
+    bf16 *w16t(int l) const { return at<bf16>(plan.w16t) + (size_t)(l % nbuf) * P; }
+    bool w16_resident(int l) const { return w16_owner[l % nbuf] == l; }
+    int grad_slot(int l) const { return l % ngrad; }
     float *grad(int l) const { return at<float>(plan.grad) + (size_t)grad_slot(l) * P; }
     size_t esz() const { return cfg.dtype == LGA_BF16 ? 2 : 4; }
     char *ckpt(int boundary) const { return arena + plan.ckpt + (size_t)boundary * T * cfg.d_model * esz(); }
@@ -216,15 +230,80 @@ template <class T> const T *gemm_weights(const lga_stack *st, int l) {
 
 // Refresh layer l's transposed 16-bit matrices ([out][in]) from its 16-bit copy ([in][out]): the
 // forward GEMMs read them so that both of their operands are k-contiguous.
-void refresh_transposed_weights(lga_stack *st, int l) {
+void refresh_transposed_weights(lga_stack *st, int l, hipStream_t s) {
     const int d = st->cfg.d_model, f = st->cfg.d_ff;
     const LayerLayout &o = st->lay;
     const bf16 *w = st->w16(l);
     bf16 *wt = st->w16t(l);
-    launch_transpose_bf16(w + o.w_qkv, wt + o.w_qkv, d, 3 * d, 3 * d, d, st->stream);
-    launch_transpose_bf16(w + o.w_o, wt + o.w_o, d, d, d, d, st->stream);
-    launch_transpose_bf16(w + o.w_1, wt + o.w_1, d, f, f, d, st->stream);
-    launch_transpose_bf16(w + o.w_2, wt + o.w_2, f, d, d, f, st->stream);
+    launch_transpose_bf16(w + o.w_qkv, wt + o.w_qkv, d, 3 * d, 3 * d, d, s);
+    launch_transpose_bf16(w + o.w_o, wt + o.w_o, d, d, d, d, s);
+    launch_transpose_bf16(w + o.w_1, wt + o.w_1, d, f, f, d, s);
+    launch_transpose_bf16(w + o.w_2, wt + o.w_2, f, d, d, f, s);
+}
+
+// ---- overlap mode plumbing -----------------------------------------------------------------------
+// Work given to the second stream starts after everything enqueued on the main stream so far.
+void fork_aux(lga_stack *st) {
+    (void)hipEventRecord(st->ev_fork, st->stream);
+    (void)hipStreamWaitEvent(st->aux, st->ev_fork, 0);
+}
+// The main stream waits for the second stream's last write of a 16-bit parameter buffer / last read of a
+// gradient buffer, if it has not done so yet.
+void wait_w16(lga_stack *st, int slot) {
+    if (!st->w16_pending[slot]) return;
+    (void)hipStreamWaitEvent(st->stream, st->ev_w16[slot], 0);
+    st->w16_pending[slot] = 0;
+}
+void wait_grad(lga_stack *st, int slot) {
+    if (!st->grad_pending[slot]) return;
+    (void)hipStreamWaitEvent(st->stream, st->ev_grad[slot], 0);
+    st->grad_pending[slot] = 0;
+}
+void join_aux(lga_stack *st) {
+    for (size_t i = 0; i < st->w16_pending.size(); ++i) wait_w16(st, (int)i);
+    for (size_t i = 0; i < st->grad_pending.size(); ++i) wait_grad(st, (int)i);
+}
+void release_stack(lga_stack *st) {
+    if (st->aux) (void)hipStreamSynchronize(st->aux);
+    for (hipEvent_t ev : st->ev_w16) if (ev) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : st->ev_grad) if (ev) (void)hipEventDestroy(ev);
+    if (st->ev_fork) (void)hipEventDestroy(st->ev_fork);
+    if (st->aux) (void)hipStreamDestroy(st->aux);
+    if (st->arena) (void)hipFree(st->arena);
+    delete st;
+}
+
+// "Restore" of the paper's figure 2 and table C.1: make the 16-bit copies of layer l's parameters available
+// before the layer is used.  With one buffer per layer they always are (every Adam step rewrites them); with
+// fewer (param_buffers), the layer's fp32 masters are cast into its buffer whenever another layer has used it
+// in the meantime - once per layer and pass in the layered order, once per layer, pass AND micro-batch in the
+// micro-batch-major order.
+void restore_weights(lga_stack *st, int l) {
+    const int slot = l % st->nbuf;
+    hipStream_t s = st->stream;
+    if (st->cfg.overlap) {
+        fork_aux(st);               // the buffer's previous layer is no longer read by anything enqueued after this
+        s = st->aux;
+    }
+    launch_cast_f32_to_bf16(st->w(l), st->w16(l), st->P, s);
+    st->w16_owner[slot] = l;
+    refresh_transposed_weights(st, l, s);
+    if (st->cfg.overlap) {
+        (void)hipEventRecord(st->ev_w16[slot], st->aux);
+        st->w16_pending[slot] = 1;
+    }
+    ++st->restores;
+}
+void ensure_weights(lga_stack *st, int l) {
+    if (st->cfg.dtype != LGA_BF16) return;
+    if (!st->w16_resident(l)) restore_weights(st, l);
+    if (st->cfg.overlap) wait_w16(st, l % st->nbuf);
+}
+// Overlap mode: start restoring layer `next` while layer `cur`'s sweep, enqueued after this call, runs.
+void prefetch_weights(lga_stack *st, int next, int cur) {
+    if (st->cfg.dtype != LGA_BF16 || !st->cfg.overlap || next < 0 || next >= st->cfg.n_layers) return;
+    if (st->w16_resident(next) || next % st->nbuf == cur % st->nbuf) return;
+    restore_weights(st, next);
 }
 
 // Forward of layer l on one micro-batch group (paper section 5 "Model"; pre-LN residual form).
@@ -367,10 +446,27 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     launch_layernorm_bwd_dx<T>(dh, x_in, mean1, rstd1, pf + o.ln1_g, dx1, dy, t, d, s);
 }
 
-void adam_layer(lga_stack *st, int l, const lga_adam &hp) {
-    launch_adam(st->w(l), st->m(l), st->v(l), st->grad(l), st->cfg.dtype == LGA_BF16 ? st->w16(l) : nullptr, st->P,
-                hp.lr, hp.beta1, hp.beta2, hp.eps, hp.step, st->stream);
-    if (st->cfg.dtype == LGA_BF16) refresh_transposed_weights(st, l);
+// async: on the second stream, after everything enqueued so far (overlap mode, fused Adam of the layered order)
+void adam_layer(lga_stack *st, int l, const lga_adam &hp, bool async = false) {
+    hipStream_t s = st->stream;
+    if (async) {
+        fork_aux(st);
+        s = st->aux;
+    }
+    // the 16-bit copies are rewritten only if the layer still owns its buffer; otherwise the next use restores them
+    const bool copies = st->cfg.dtype == LGA_BF16 && st->w16_resident(l);
+    if (copies && !async && st->cfg.overlap) wait_w16(st, l % st->nbuf);
+    launch_adam(st->w(l), st->m(l), st->v(l), st->grad(l), copies ? st->w16(l) : nullptr, st->P,
+                hp.lr, hp.beta1, hp.beta2, hp.eps, hp.step, s);
+    if (copies) refresh_transposed_weights(st, l, s);
+    if (async) {
+        (void)hipEventRecord(st->ev_grad[st->grad_slot(l)], st->aux);
+        st->grad_pending[st->grad_slot(l)] = 1;
+        if (copies) {
+            (void)hipEventRecord(st->ev_w16[l % st->nbuf], st->aux);
+            st->w16_pending[l % st->nbuf] = 1;
+        }
+    }
 }
 
 int check_adam(const lga_adam *a) {
@@ -395,6 +491,8 @@ template <class T> int forward_layered_t(lga_stack *st, const void *x, void *y) 
     for (int l = 0; l < c.n_layers; ++l) {                 // layers outside ...
         const T *in = reinterpret_cast<const T *>(st->ckpt(l));
         T *out = reinterpret_cast<T *>(st->ckpt(l + 1));
+        ensure_weights(st, l);
+        prefetch_weights(st, l + 1, l);
         for (int gi = 0; gi < groups; ++gi)                 // ... micro-batches inside
             layer_forward<T>(st, l, in + gi * gstride, out + gi * gstride);
     }
@@ -413,6 +511,9 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
         const T *in = reinterpret_cast<const T *>(st->ckpt(l));
         float *gbuf = st->grad(l);
         st->grad_owner[st->grad_slot(l)] = -1;
+        if (c.overlap) wait_grad(st, st->grad_slot(l));     // an earlier layer's Adam step may still be reading this buffer
+        ensure_weights(st, l);
+        prefetch_weights(st, l - 1, l);
         for (int gi = 0; gi < groups; ++gi) {
             layer_forward<T>(st, l, in + gi * gstride, nullptr);                       // recompute
             const int wb = st->plan.wgrad_groups;
@@ -420,8 +521,10 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
             layer_backward<T>(st, l, in + gi * gstride, dact + gi * gstride, gbuf, gs);
         }
         st->grad_owner[st->grad_slot(l)] = l;
-        if (fused) adam_layer(st, l, *fused);              // update as soon as the layer's gradient is complete
+        // update as soon as the layer's gradient is complete; in overlap mode beside the next layer's sweep
+        if (fused) adam_layer(st, l, *fused, (c.overlap & LGA_OVERLAP_ADAM) != 0);
     }
+    if (c.overlap) join_aux(st);                            // later work on the main stream sees every update
     if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
     if (fused) st->have_forward = false;                    // checkpoints no longer match the weights
     return finish("lga_backward_layered");
@@ -437,11 +540,14 @@ int step_mbmajor_t(lga_stack *st, const void *x, const void *dy, void *y, void *
     const size_t gstride = st->t * c.d_model;               // group == 1: one micro-batch
     for (int l = 0; l < c.n_layers; ++l) st->grad_owner[l] = -1;
     for (int mu = 0; mu < c.n_micro; ++mu) {                // micro-batches outside ...
-        for (int l = 0; l < c.n_layers; ++l)                // ... layers inside
+        for (int l = 0; l < c.n_layers; ++l) {              // ... layers inside
+            ensure_weights(st, l);
             layer_forward<T>(st, l, reinterpret_cast<const T *>(st->ckpt(l)) + mu * gstride,
                              reinterpret_cast<T *>(st->ckpt(l + 1)) + mu * gstride);
+        }
         for (int l = c.n_layers - 1; l >= 0; --l) {
             const T *in = reinterpret_cast<const T *>(st->ckpt(l)) + mu * gstride;
+            ensure_weights(st, l);
             layer_forward<T>(st, l, in, nullptr);
             // layers alternate here, so every weight-gradient GEMM runs at once on its own micro-batch
             const GradStep gs{mu == 0 ? 0.f : 1.f, mu == 0 ? 0.f : 1.f, 0, true};
@@ -453,6 +559,7 @@ int step_mbmajor_t(lga_stack *st, const void *x, const void *dy, void *y, void *
     if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
     if (adam)
         for (int l = 0; l < c.n_layers; ++l) adam_layer(st, l, *adam);
+    if (c.overlap) join_aux(st);
     st->have_forward = (adam == nullptr);
     return finish("lga_step_mbmajor");
 }
@@ -496,9 +603,32 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
     // Adam: read w, m, v (12 B), write w, m, v (12 B) and the 16-bit copy; per group the GEMM families
     // read the matrices: forward all four, recompute all but W_2, input gradient all four.
     // bf16 mode also writes the 16-bit copy (2 B) and re-reads / writes the matrices once for the transposed copy
-    const uint64_t adam_param = 24 * P + (cfg->dtype == LGA_BF16 ? 2 * P + 4 * Pm : 0);
+    const uint64_t copies = cfg->dtype == LGA_BF16 ? 2 * P + 4 * Pm : 0;
     const uint64_t per_group_param = wsz * (3 * Pm - df);
-    if (param_bytes) *param_bytes = L * (adam_param + groups * per_group_param);
+    // Restores of a steady-state step (param_buffers < n_layers): a layer's masters are cast again (read 4 B, write
+    // 2 B per parameter, plus the transposed copy) whenever another layer has used its buffer since.  Counted by
+    // walking the order's sequence of layer visits for two steps and keeping the second.
+    const int nbuf = cfg->param_buffers ? cfg->param_buffers : cfg->n_layers;
+    uint64_t restores = 0, adam_copies = L;
+    if (cfg->dtype == LGA_BF16 && nbuf < cfg->n_layers) {
+        std::vector<int> owner(nbuf);
+        for (int i = 0; i < nbuf; ++i) owner[i] = i;
+        auto visit = [&](int l) {
+            if (owner[l % nbuf] != l) { owner[l % nbuf] = l; ++restores; }
+        };
+        const int passes = order == LGA_ORDER_LAYERED ? 1 : cfg->n_micro;
+        for (int step = 0; step < 2; ++step) {
+            restores = 0;
+            for (int pass = 0; pass < passes; ++pass) {
+                for (int l = 0; l < cfg->n_layers; ++l) visit(l);
+                for (int l = cfg->n_layers - 1; l >= 0; --l) visit(l);
+            }
+        }
+        // the micro-batch-major order runs Adam for all layers at the end: only the resident ones get fresh copies
+        if (order == LGA_ORDER_MICROBATCH_MAJOR) adam_copies = nbuf;
+    }
+    if (param_bytes)
+        *param_bytes = L * (24 * P + groups * per_group_param) + adam_copies * copies + restores * (4 * P + copies);
     // gradient buffer: the first pass over it writes (4 B), later ones read-modify-write (8 B); Adam reads
     // (4 B).  Vectors take one pass per group; matrices one per weight-gradient GEMM, which in the layered
     // bf16 path covers wgrad_groups groups.
@@ -520,6 +650,12 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
     return LGA_OK;
 }
 
+int lga_restore_count(lga_stack *st, uint64_t *count) {
+    if (!st || !count) return fail(LGA_ERR_ARG, "NULL argument");
+    *count = st->restores;
+    return LGA_OK;
+}
+
 int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **out) {
     if (!out) return fail(LGA_ERR_ARG, "out is NULL");
     *out = nullptr;
@@ -534,7 +670,15 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
     st->T = (size_t)cfg->n_micro * cfg->micro_batch * cfg->seq_len;
     st->t = (size_t)cfg->group * cfg->micro_batch * cfg->seq_len;
     st->have_forward = false;
-    st->grad_owner.assign(cfg->retain_grads ? cfg->n_layers : 1, -1);
+    st->ngrad = cfg->retain_grads ? cfg->n_layers : (cfg->overlap & LGA_OVERLAP_ADAM) ? std::min(2, cfg->n_layers) : 1;
+    st->aux = nullptr;
+    st->ev_fork = nullptr;
+    st->nbuf = cfg->param_buffers ? cfg->param_buffers : cfg->n_layers;
+    st->grad_owner.assign(st->ngrad, -1);
+    st->w16_owner.assign(st->nbuf, -1);
+    st->w16_pending.assign(st->nbuf, 0);
+    st->grad_pending.assign(st->ngrad, 0);
+    st->restores = 0;
     st->arena = nullptr;
     hipError_t e = hipMalloc(reinterpret_cast<void **>(&st->arena), st->plan.total);
     if (e != hipSuccess) {
@@ -545,10 +689,20 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
     }
     auto bail = [&](hipError_t err, const char *what) {
         std::string msg = std::string(what) + ": " + hipGetErrorString(err);
-        (void)hipFree(st->arena);
-        delete st;
+        release_stack(st);
         return fail(LGA_ERR_HIP, msg);
     };
+    if (cfg->overlap) {
+        // second stream (default priority) and the events that order it against the main stream
+        if ((e = hipStreamCreateWithFlags(&st->aux, hipStreamNonBlocking)) != hipSuccess) return bail(e, "create stream");
+        if ((e = hipEventCreateWithFlags(&st->ev_fork, hipEventDisableTiming)) != hipSuccess) return bail(e, "create event");
+        st->ev_w16.assign(st->nbuf, nullptr);
+        st->ev_grad.assign(st->ngrad, nullptr);
+        for (auto &ev : st->ev_w16)
+            if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "create event");
+        for (auto &ev : st->ev_grad)
+            if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "create event");
+    }
     const size_t LP = (size_t)cfg->n_layers * st->P;
     if ((e = hipMemsetAsync(st->m(0), 0, LP * 4, st->stream)) != hipSuccess) return bail(e, "clear m");
     if ((e = hipMemsetAsync(st->v(0), 0, LP * 4, st->stream)) != hipSuccess) return bail(e, "clear v");
@@ -569,10 +723,10 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
             launch_fill_normal(w + st->lay.w_2, f * d, 0.02f, seed + 3, st->stream);
         }
     }
-    if (cfg->dtype == LGA_BF16) {
-        launch_cast_f32_to_bf16(st->w(0), st->w16(0), LP, st->stream);   // restore
-        for (int l = 0; l < cfg->n_layers; ++l) refresh_transposed_weights(st, l);
-    }
+    st->cfg.overlap = 0;                                            // the initial fill runs on the main stream
+    for (int l = 0; l < st->nbuf; ++l) ensure_weights(st, l);       // section 2.5: converted to 16 bits before use
+    st->cfg.overlap = cfg->overlap;
+    st->restores = 0;
     if ((e = hipStreamSynchronize(st->stream)) != hipSuccess) return bail(e, "init sync");
     if ((e = hipGetLastError()) != hipSuccess) return bail(e, "init kernels");
     *out = st;
@@ -582,8 +736,7 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
 void lga_destroy_stack(lga_stack *st) {
     if (!st) return;
     (void)hipStreamSynchronize(st->stream);
-    if (st->arena) (void)hipFree(st->arena);
-    delete st;
+    release_stack(st);
 }
 
 int lga_forward_layered(lga_stack *st, const void *x, void *y) {

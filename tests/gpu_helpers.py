@@ -61,11 +61,12 @@ def oracle_adam(a: B.lga_adam) -> O.AdamHyper:
 
 
 def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layered", adam=None, fused=True,
-                 want_ckpt=True, wgrad_groups=0):
+                 want_ckpt=True, wgrad_groups=0, param_buffers=0, overlap=0):
     """One training step through the C ABI.  Returns a dict of float64 numpy results."""
     dt = dtype_code(w)
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
-                        group=group, retain_grads=retain, wgrad_groups=wgrad_groups)
+                        group=group, retain_grads=retain, wgrad_groups=wgrad_groups, param_buffers=param_buffers,
+                        overlap=overlap)
     st = B.Stack(cfg, np.concatenate(params))
     P = B.params_per_layer(cfg)
     xd, Gd = to_dev(x, dt), to_dev(G, dt)
@@ -110,6 +111,7 @@ def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layer
             out["m"].append(B.read_device(mp, n).astype(np.float64))
             out["v"].append(B.read_device(vp, n).astype(np.float64))
         assert n == P
+        out["restores"] = st.restore_count()
     finally:
         st.close()
     return out

@@ -126,6 +126,34 @@ def test_traffic_model_layered_is_independent_of_micro_batch_count_when_fully_gr
     assert fm == f32_
 
 
+def test_traffic_model_restores_are_constant_in_n_when_layered_and_proportional_otherwise():
+    """Figure 2 / table C.1 with two parameter buffers for a deeper stack: the layered order restores each layer
+    about once per pass whatever the number of micro-batches; the micro-batch-major order once per pass and
+    micro-batch."""
+    L, d, f = 6, 1024, 4096
+    P, Pm = 12 * d * d + 13 * d, 12 * d * d
+    restore = 4 * P + 2 * P + 4 * Pm                   # read masters, write the 16-bit copy, re-read / write its transpose
+
+    def extra(n, order, buffers):
+        kw = dict(n_layers=L, d_model=d, n_heads=8, d_ff=f, seq_len=128, micro_batch=1, n_micro=n, dtype=B.LGA_BF16,
+                  group=1, retain_grads=1)
+        full = B.traffic_model(cfg(param_buffers=0, **kw), order)[0]
+        return B.traffic_model(cfg(param_buffers=buffers, **kw), order)[0] - full
+
+    # layered, 2 buffers, 6 layers: forward restores layers 2..5 (0, 1 are left from the previous backward), backward 3..0
+    assert extra(8, B.LGA_ORDER_LAYERED, 2) == 8 * restore
+    assert extra(64, B.LGA_ORDER_LAYERED, 2) == 8 * restore
+    # micro-batch-major: the same 8 for every micro-batch (each ends with layers 1 and 0 resident); Adam at the
+    # end of the step refreshes only those two layers' copies
+    for n in (8, 64):
+        assert extra(n, B.LGA_ORDER_MICROBATCH_MAJOR, 2) == 8 * n * restore - (L - 2) * (2 * P + 4 * Pm)
+    assert extra(8, B.LGA_ORDER_LAYERED, L) == 0
+    assert B.lib.lga_arena_bytes(C.byref(cfg(param_buffers=3)), C.byref(C.c_uint64())) == B.LGA_ERR_SHAPE   # > n_layers
+    # the arena shrinks by the copies of the layers that are no longer resident
+    kw = dict(n_layers=L, d_model=d, n_heads=8, d_ff=f, seq_len=128, micro_batch=1, n_micro=8, dtype=B.LGA_BF16)
+    assert abs((B.arena_bytes(cfg(**kw)) - B.arena_bytes(cfg(param_buffers=2, **kw))) - (L - 2) * 4 * P) < 4096
+
+
 def test_flop_model_against_the_papers_count():
     # Appendix C.1: 8 flop per token per parameter with full recompute.  The library skips the second
     # feed-forward GEMM in recompute (its output is not needed), i.e. executes 8 - 2 * (d d_I / p_matrices).

@@ -137,6 +137,57 @@ def test_merged_weight_gradient_gemms_match_oracle_and_each_other(wgrad_groups):
         assert rel_err(got["grads"][l], base["grads"][l]) < 1e-5
 
 
+def test_parameter_buffer_budget_changes_traffic_not_results():
+    """Two 16-bit parameter buffers for a 4-layer stack (figure 2, table C.1): every output is bit-identical to
+    the run with one buffer per layer, in both orders; the number of restores per step is 2 (L - 2) in the layered
+    order whatever n_mu is, and 2 (L - 2) n_mu in the micro-batch-major order."""
+    w = S.Workload("budget_bf16", 4, 64, 2, 256, 64, 1, 6, "bf16")
+    x, G, params = S.make_inputs(w, seed=13)
+    adam = adam_struct()
+    for order, group, per_step in (("layered", 2, 2 * (4 - 2)), ("mbmajor", 1, 2 * (4 - 2) * 6)):
+        full = run_gpu_step(w, x, G, params, group=group, retain=1, order=order, adam=adam)
+        tight = run_gpu_step(w, x, G, params, group=group, retain=1, order=order, adam=adam, param_buffers=2)
+        assert full["restores"] == 0
+        assert tight["restores"] == per_step, (order, tight["restores"])
+        for key in ("y", "dx", "boundaries"):
+            assert np.array_equal(full[key], tight[key]), (order, key)
+        for l in range(w.n_layers):
+            for key in ("grads", "params", "m", "v"):
+                assert np.array_equal(full[key][l], tight[key][l]), (order, key, l)
+    ref = O.step_microbatch_major(x, G, params, oracle_shape(w), oracle_adam(adam))
+    compare_with_oracle(w, tight, ref, GATE["bf16"], adam)
+
+
+@pytest.mark.parametrize("retain,param_buffers,overlap", [(0, 0, 3), (1, 0, 2), (0, 2, 3), (0, 2, 1), (0, 1, 3)])
+def test_overlap_mode_changes_timing_not_results(retain, param_buffers, overlap):
+    """Adam steps and restores on the library's second stream (overlap = 1): every output is bit-identical to the
+    single-stream run, repeatedly, for one or several gradient buffers and with or without a parameter-buffer
+    budget; with a single-buffer budget the restores cannot be prefetched but must still be ordered."""
+    w = S.Workload("overlap_bf16", 4, 128, 2, 512, 128, 1, 4, "bf16")
+    x, G, params = S.make_inputs(w, seed=17)
+    adam = adam_struct()
+    base = run_gpu_step(w, x, G, params, group=2, retain=retain, adam=adam, param_buffers=param_buffers)
+    for attempt in range(3):
+        got = run_gpu_step(w, x, G, params, group=2, retain=retain, adam=adam, param_buffers=param_buffers,
+                           overlap=overlap)
+        for key in ("y", "dx", "boundaries"):
+            assert np.array_equal(base[key], got[key]), (attempt, key)
+        for l in range(w.n_layers):
+            for key in ("params", "m", "v"):
+                assert np.array_equal(base[key][l], got[key][l]), (attempt, key, l)
+            if base["grads"][l] is not None:
+                assert np.array_equal(base["grads"][l], got["grads"][l]), (attempt, l)
+        assert got["restores"] == base["restores"]
+    # with one gradient buffer, overlapping the Adam steps keeps two: layers 0 and 1 stay readable
+    if retain == 0:
+        assert (got["grads"][1] is not None) == bool(overlap & 2) and got["grads"][2] is None
+    mb = run_gpu_step(w, x, G, params, group=1, retain=1, order="mbmajor", adam=adam, param_buffers=param_buffers,
+                      overlap=overlap)
+    mb0 = run_gpu_step(w, x, G, params, group=1, retain=1, order="mbmajor", adam=adam, param_buffers=param_buffers)
+    for l in range(w.n_layers):
+        assert np.array_equal(mb["params"][l], mb0["params"][l])
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
