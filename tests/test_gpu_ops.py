@@ -227,6 +227,9 @@ ATTN_CASES = [
     (F32, 0, 2, 37, 3, 16), (F32, 0, 1, 1, 1, 8), (BF16, 0, 2, 70, 2, 32),
     (BF16, 1, 2, 200, 2, 32), (BF16, 1, 1, 333, 3, 64), (BF16, 1, 2, 256, 2, 128), (BF16, 1, 1, 130, 2, 160),
     (BF16, 1, 1, 1, 1, 64), (BF16, 1, 3, 64, 1, 96),
+    # long enough for the loops over fully visible tiles and for the LDS stages to wrap around, ragged ends
+    (BF16, 1, 1, 1100, 2, 128), (BF16, 1, 2, 640, 1, 64), (BF16, 1, 1, 777, 1, 96), (BF16, 1, 1, 520, 1, 160),
+    (BF16, 1, 1, 600, 1, 32),
 ]
 
 
