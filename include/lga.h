@@ -166,6 +166,27 @@ int lga_checkpoint(lga_stack *stack, int32_t boundary, const void **dev_ptr, siz
  * Same kernels as the layered calls.  Requires retain_grads == 1 and group == 1. */
 int lga_step_mbmajor(lga_stack *stack, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam);
 
+/* Modular layer sets (section 3, modular pipeline parallelism: a device holds layers k, k + n_l, ... and each
+ * layer's input arrives from another device).  One layer's share of the layer-major sweeps:
+ *
+ * lga_forward_layer   runs layer `layer` over all n_micro micro-batches (in groups, like lga_forward_layered).
+ *                     x_in: device, [n_micro, micro_batch, seq_len, d_model] of the configured dtype; it is copied
+ *                     into the layer's input checkpoint (boundary `layer`), from which the backward pass recomputes
+ *                     - unless x_in already is that checkpoint's address (lga_checkpoint), then nothing is copied.
+ *                     x_out: device, same shape, receives the layer's output; NULL leaves it in boundary layer + 1.
+ * lga_backward_layer  recomputes the layer from its input checkpoint, back-propagates dy (device, same shape) through
+ *                     it for all micro-batches, accumulates the layer's fp32 gradient and, if fused != NULL, applies
+ *                     Adam to the layer at once.  dx (device, same shape, or NULL) receives the input gradient.
+ *                     With fused == NULL the gradient stays readable (lga_grads, lga_adam_step_layer) until another
+ *                     layer's backward reuses its buffer (retain_grads == 0: the very next one).
+ *
+ * Calling lga_forward_layer for layers 0 .. L-1, feeding each output to the next, and lga_backward_layer for
+ * L-1 .. 0 likewise computes exactly what lga_forward_layered / lga_backward_layered compute (same kernels, same
+ * order).  LGA_ERR_STATE: lga_backward_layer without a forward of that layer since its weights last changed.
+ * x_in / x_out / dy / dx are caller-owned and only read / written during the call's enqueued work. */
+int lga_forward_layer(lga_stack *stack, int32_t layer, const void *x_in, void *x_out);
+int lga_backward_layer(lga_stack *stack, int32_t layer, const void *dy, void *dx, const lga_adam *fused);
+
 /* Number of restores (casts of one layer's parameters into a 16-bit parameter buffer, section 2.5 /
  * figure 2) the stack has done since it was created; the initial fill is not counted.  count: host. */
 int lga_restore_count(lga_stack *stack, uint64_t *count);

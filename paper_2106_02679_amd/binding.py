@@ -75,6 +75,8 @@ SIGNATURES = {
     "lga_moments": (C.c_int, [_vp, _i32, _P(_vp), _P(_vp), _P(C.c_size_t)]),
     "lga_checkpoint": (C.c_int, [_vp, _i32, _P(_vp), _P(C.c_size_t)]),
     "lga_step_mbmajor": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _P(lga_adam)]),
+    "lga_forward_layer": (C.c_int, [_vp, _i32, _vp, _vp]),
+    "lga_backward_layer": (C.c_int, [_vp, _i32, _vp, _vp, _P(lga_adam)]),
     "lga_traffic_model": (C.c_int, [_P(lga_config), _i32, _P(_u64), _P(_u64), _P(C.c_double)]),
     "lga_arena_bytes": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_restore_count": (C.c_int, [_vp, _P(_u64)]),
@@ -194,6 +196,12 @@ class Stack:
 
     def step_mbmajor(self, x_ptr, dy_ptr, y_ptr, dx_ptr, adam: Optional[lga_adam]):
         check(lib.lga_step_mbmajor(self._h, x_ptr, dy_ptr, y_ptr, dx_ptr, C.byref(adam) if adam is not None else None))
+
+    def forward_layer(self, layer: int, x_in_ptr: int, x_out_ptr: Optional[int]):
+        check(lib.lga_forward_layer(self._h, layer, x_in_ptr, x_out_ptr))
+
+    def backward_layer(self, layer: int, dy_ptr: int, dx_ptr: Optional[int], adam: Optional[lga_adam]):
+        check(lib.lga_backward_layer(self._h, layer, dy_ptr, dx_ptr, C.byref(adam) if adam is not None else None))
 
     def adam_step_layer(self, layer: int, adam: lga_adam):
         check(lib.lga_adam_step_layer(self._h, layer, C.byref(adam)))

@@ -190,7 +190,14 @@ struct lga_stack {
     hipStream_t stream;
     char *arena;
     size_t P, T, t;          // params per layer, tokens per step, tokens per group
-    bool have_forward;
+    // input_valid[l]: boundary l holds the input layer l's last forward saw, and the layer's weights have not
+    // changed since - what the layer's backward (which recomputes from that input) needs
+    std::vector<char> input_valid;
+    bool have_forward() const {
+        for (char ok : input_valid) if (!ok) return false;
+        return true;
+    }
+    void set_forward(bool ok) { std::fill(input_valid.begin(), input_valid.end(), (char)ok); }
     std::vector<int> grad_owner;   // which layer's gradient each gradient buffer currently holds (-1: none)
     int ngrad;                     // gradient buffers: layer l uses buffer l % ngrad
     // overlap mode: Adam steps and restores run on a second stream beside the layer sweeps
@@ -526,8 +533,51 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
     }
     if (c.overlap) join_aux(st);                            // later work on the main stream sees every update
     if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
-    if (fused) st->have_forward = false;                    // checkpoints no longer match the weights
+    if (fused) st->set_forward(false);                      // checkpoints no longer match the weights
     return finish("lga_backward_layered");
+}
+
+// One layer's share of the layer-major sweeps, with the layer's input (forward) and output gradient (backward)
+// arriving from outside the stack: what a device of the modular pipeline (section 3) runs for each of its layers.
+template <class T> int forward_layer_t(lga_stack *st, int l, const void *x_in, void *x_out) {
+    const lga_config &c = st->cfg;
+    const size_t act_bytes = st->T * c.d_model * sizeof(T);
+    if (x_in != st->ckpt(l))
+        LGA_HIP(hipMemcpyAsync(st->ckpt(l), x_in, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    const T *in = reinterpret_cast<const T *>(st->ckpt(l));
+    T *out = reinterpret_cast<T *>(x_out ? x_out : st->ckpt(l + 1));
+    const int groups = c.n_micro / c.group;
+    const size_t gstride = st->t * c.d_model;
+    ensure_weights(st, l);
+    for (int gi = 0; gi < groups; ++gi) layer_forward<T>(st, l, in + gi * gstride, out + gi * gstride);
+    return finish("lga_forward_layer");
+}
+
+template <class T> int backward_layer_t(lga_stack *st, int l, const void *dy, void *dx, const lga_adam *fused) {
+    const lga_config &c = st->cfg;
+    const size_t act_bytes = st->T * c.d_model * sizeof(T);
+    T *dact = st->at<T>(st->plan.dact);
+    LGA_HIP(hipMemcpyAsync(dact, dy, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    const int groups = c.n_micro / c.group;
+    const size_t gstride = st->t * c.d_model;
+    const T *in = reinterpret_cast<const T *>(st->ckpt(l));
+    st->grad_owner[st->grad_slot(l)] = -1;
+    if (c.overlap) wait_grad(st, st->grad_slot(l));
+    ensure_weights(st, l);
+    for (int gi = 0; gi < groups; ++gi) {
+        layer_forward<T>(st, l, in + gi * gstride, nullptr);                           // recompute
+        const int wb = st->plan.wgrad_groups;
+        const GradStep gs{gi == 0 ? 0.f : 1.f, gi < wb ? 0.f : 1.f, gi % wb, gi % wb == wb - 1 || gi == groups - 1};
+        layer_backward<T>(st, l, in + gi * gstride, dact + gi * gstride, st->grad(l), gs);
+    }
+    st->grad_owner[st->grad_slot(l)] = l;
+    if (fused) {
+        adam_layer(st, l, *fused, (c.overlap & LGA_OVERLAP_ADAM) != 0);
+        st->input_valid[l] = 0;
+    }
+    if (c.overlap) join_aux(st);
+    if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    return finish("lga_backward_layer");
 }
 
 template <class T>
@@ -560,7 +610,7 @@ int step_mbmajor_t(lga_stack *st, const void *x, const void *dy, void *y, void *
     if (adam)
         for (int l = 0; l < c.n_layers; ++l) adam_layer(st, l, *adam);
     if (c.overlap) join_aux(st);
-    st->have_forward = (adam == nullptr);
+    st->set_forward(adam == nullptr);
     return finish("lga_step_mbmajor");
 }
 
@@ -669,7 +719,7 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
     st->P = st->lay.total;
     st->T = (size_t)cfg->n_micro * cfg->micro_batch * cfg->seq_len;
     st->t = (size_t)cfg->group * cfg->micro_batch * cfg->seq_len;
-    st->have_forward = false;
+    st->input_valid.assign(cfg->n_layers, 0);
     st->ngrad = cfg->retain_grads ? cfg->n_layers : (cfg->overlap & LGA_OVERLAP_ADAM) ? std::min(2, cfg->n_layers) : 1;
     st->aux = nullptr;
     st->ev_fork = nullptr;
@@ -742,19 +792,43 @@ void lga_destroy_stack(lga_stack *st) {
 int lga_forward_layered(lga_stack *st, const void *x, void *y) {
     if (!st || !x) return fail(LGA_ERR_ARG, "NULL argument");
     int rc = st->cfg.dtype == LGA_BF16 ? forward_layered_t<bf16>(st, x, y) : forward_layered_t<float>(st, x, y);
-    if (rc == LGA_OK) st->have_forward = true;
+    if (rc == LGA_OK) st->set_forward(true);
     return rc;
 }
 
 int lga_backward_layered(lga_stack *st, const void *dy, void *dx, const lga_adam *fused) {
     if (!st || !dy) return fail(LGA_ERR_ARG, "NULL argument");
-    if (!st->have_forward) return fail(LGA_ERR_STATE, "lga_backward_layered needs a preceding forward pass");
+    if (!st->have_forward()) return fail(LGA_ERR_STATE, "lga_backward_layered needs a preceding forward pass");
     if (!fused && !st->cfg.retain_grads && st->cfg.n_layers > 1)
         return fail(LGA_ERR_STATE, "unfused backward with a single gradient buffer would lose all but one layer's gradient");
     if (fused)
         if (int rc = check_adam(fused)) return rc;
     return st->cfg.dtype == LGA_BF16 ? backward_layered_t<bf16>(st, dy, dx, fused)
                                      : backward_layered_t<float>(st, dy, dx, fused);
+}
+
+int lga_forward_layer(lga_stack *st, int32_t layer, const void *x_in, void *x_out) {
+    if (int rc = check_layer(st, layer)) return rc;
+    if (!x_in) return fail(LGA_ERR_ARG, "x_in is NULL");
+    int rc = st->cfg.dtype == LGA_BF16 ? forward_layer_t<bf16>(st, layer, x_in, x_out)
+                                       : forward_layer_t<float>(st, layer, x_in, x_out);
+    if (rc == LGA_OK) {
+        st->input_valid[layer] = 1;
+        // the next boundary now holds this layer's output (or nothing new): not an input the next layer has seen
+        if (!x_out && layer + 1 < st->cfg.n_layers) st->input_valid[layer + 1] = 0;
+    }
+    return rc;
+}
+
+int lga_backward_layer(lga_stack *st, int32_t layer, const void *dy, void *dx, const lga_adam *fused) {
+    if (int rc = check_layer(st, layer)) return rc;
+    if (!dy) return fail(LGA_ERR_ARG, "dy is NULL");
+    if (!st->input_valid[layer])
+        return fail(LGA_ERR_STATE, "lga_backward_layer needs a preceding forward of this layer with its current weights");
+    if (fused)
+        if (int rc = check_adam(fused)) return rc;
+    return st->cfg.dtype == LGA_BF16 ? backward_layer_t<bf16>(st, layer, dy, dx, fused)
+                                     : backward_layer_t<float>(st, layer, dy, dx, fused);
 }
 
 int lga_step_mbmajor(lga_stack *st, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam) {
@@ -774,7 +848,7 @@ int lga_adam_step_layer(lga_stack *st, int32_t layer, const lga_adam *adam) {
     if (st->grad_owner[st->grad_slot(layer)] != layer)
         return fail(LGA_ERR_STATE, "no accumulated gradient is available for this layer");
     adam_layer(st, layer, *adam);
-    st->have_forward = false;
+    st->input_valid[layer] = 0;
     return finish("lga_adam_step_layer");
 }
 
