@@ -13,7 +13,9 @@ What is computed, and where the paper defines it:
   X_[x] family (d_m = x^2, d_l = x) fixes the exact per-layer inventory at
   12 d_m^2 + 13 d_m: every one of the four linear maps carries a bias and both
   layer norms carry gain and bias.  The build's workload is the decoder
-  (causal) pre-LN variant the paper says its results carry over to.
+  (causal) pre-LN variant the paper says its results carry over to; the
+  paper's own encoder differs in that every position attends to the whole
+  sequence (`StackShape.causal = False`).
 * Gradient accumulation: the batch is cut into n_mu micro-batches that are
   processed one after the other between two weight updates (section 2.5), the
   gradients being summed.  This file's main driver, `step_microbatch_major`,
@@ -68,6 +70,7 @@ class StackShape:
     b_mu: int         # sequences per micro-batch
     n_mu: int         # micro-batches per step
     ln_eps: float = 1e-5
+    causal: bool = True   # decoder: position i attends to j <= i; False: the encoder of section 5, no mask
 
     @property
     def d_h(self) -> int:
@@ -150,23 +153,31 @@ def layer_norm_backward(dy: np.ndarray, xhat: np.ndarray, rstd: np.ndarray, g: n
     return dx, dg, db
 
 
-def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray):
-    """Softmax attention per sequence and head; position i attends to j <= i.
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, causal: bool):
+    """Softmax attention per sequence and head; position i attends to j <= i (causal,
+    the decoder) or to every position of its sequence (the encoder of section 5).
 
     q, k, v: [b, heads, s, d_h].  Scores are scaled by 1/sqrt(d_h).
     Returns the output [b, heads, s, d_h] and the probabilities.
     """
     s, d_h = q.shape[-2], q.shape[-1]
     scores = (q @ np.swapaxes(k, -1, -2)) / math.sqrt(d_h)
-    future = np.triu(np.ones((s, s), dtype=bool), k=1)
-    scores = np.where(future, -np.inf, scores)
+    if causal:
+        future = np.triu(np.ones((s, s), dtype=bool), k=1)
+        scores = np.where(future, -np.inf, scores)
     scores = scores - scores.max(axis=-1, keepdims=True)
     e = np.exp(scores)
     prob = e / e.sum(axis=-1, keepdims=True)
     return prob @ v, prob
 
 
+def causal_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray):
+    return attention(q, k, v, True)
+
+
 def causal_attention_backward(dout, q, k, v, prob):
+    """Backward of `attention` given its probabilities: masked positions have probability 0,
+    so the same formula serves both variants."""
     d_h = q.shape[-1]
     dv = np.swapaxes(prob, -1, -2) @ dout
     dprob = dout @ np.swapaxes(v, -1, -2)
@@ -192,7 +203,7 @@ def _merge_heads(t: np.ndarray) -> np.ndarray:
 # pre-LN residual form, causal)
 # --------------------------------------------------------------------------
 
-def layer_forward(x: np.ndarray, p: Dict[str, np.ndarray], d_a: int, eps: float):
+def layer_forward(x: np.ndarray, p: Dict[str, np.ndarray], d_a: int, eps: float, causal: bool = True):
     """x: [b, s, d_m] -> (y, cache of every intermediate)."""
     d = x.shape[-1]
     h, xhat1, rstd1 = layer_norm(x, p["ln1_g"], p["ln1_b"], eps)
@@ -200,7 +211,7 @@ def layer_forward(x: np.ndarray, p: Dict[str, np.ndarray], d_a: int, eps: float)
     q = _split_heads(qkv[..., 0:d], d_a)
     k = _split_heads(qkv[..., d:2 * d], d_a)
     v = _split_heads(qkv[..., 2 * d:3 * d], d_a)
-    att, prob = causal_attention(q, k, v)
+    att, prob = attention(q, k, v, causal)
     a = _merge_heads(att)
     x1 = x + a @ p["w_o"] + p["b_o"]
     h2, xhat2, rstd2 = layer_norm(x1, p["ln2_g"], p["ln2_b"], eps)
@@ -318,7 +329,7 @@ def step_microbatch_major(x, G, flat_params, shape: StackShape, adam: Optional[A
         bounds[0, mu] = act
         caches = []
         for l in range(L):
-            act, cache = layer_forward(act, layers[l], shape.d_a, shape.ln_eps)
+            act, cache = layer_forward(act, layers[l], shape.d_a, shape.ln_eps, shape.causal)
             caches.append(cache)
             bounds[l + 1, mu] = act
         loss += float((act * G[mu]).sum())
@@ -350,7 +361,7 @@ def step_layered(x, G, flat_params, shape: StackShape, adam: Optional[AdamHyper]
     bounds[0] = x
     for l in range(L):
         for mu in range(shape.n_mu):
-            bounds[l + 1, mu], _ = layer_forward(bounds[l, mu], layers[l], shape.d_a, shape.ln_eps)
+            bounds[l + 1, mu], _ = layer_forward(bounds[l, mu], layers[l], shape.d_a, shape.ln_eps, shape.causal)
     loss = float((bounds[L] * G).sum())
     d = G.copy()
     grads: List[Optional[np.ndarray]] = [None] * L
@@ -360,7 +371,7 @@ def step_layered(x, G, flat_params, shape: StackShape, adam: Optional[AdamHyper]
     for l in reversed(range(L)):
         gl = np.zeros(params_per_layer(shape.d_m, shape.d_I), dtype=F64)
         for mu in range(shape.n_mu):
-            _, cache = layer_forward(bounds[l, mu], layers[l], shape.d_a, shape.ln_eps)   # recompute
+            _, cache = layer_forward(bounds[l, mu], layers[l], shape.d_a, shape.ln_eps, shape.causal)   # recompute
             d[mu], g = layer_backward(d[mu], cache, layers[l], shape.d_a)
             gl += flatten_layer(g)
         grads[l] = gl
@@ -383,7 +394,7 @@ def loss_only(x, G, flat_params, shape: StackShape) -> float:
     for mu in range(x.shape[0]):
         act = x[mu]
         for l in range(shape.d_l):
-            act, _ = layer_forward(act, layers[l], shape.d_a, shape.ln_eps)
+            act, _ = layer_forward(act, layers[l], shape.d_a, shape.ln_eps, shape.causal)
         total += float((act * G[mu]).sum())
     return total
 

@@ -23,8 +23,8 @@ def _read_table(name):
     return rows
 
 
-def tiny_shape(d_l=2, d_m=8, d_a=2, d_s=5, b_mu=2, n_mu=3):
-    return O.StackShape(d_l=d_l, d_m=d_m, d_a=d_a, d_I=4 * d_m, d_s=d_s, b_mu=b_mu, n_mu=n_mu)
+def tiny_shape(d_l=2, d_m=8, d_a=2, d_s=5, b_mu=2, n_mu=3, causal=True):
+    return O.StackShape(d_l=d_l, d_m=d_m, d_a=d_a, d_I=4 * d_m, d_s=d_s, b_mu=b_mu, n_mu=n_mu, causal=causal)
 
 
 def tiny_problem(shape, seed=3, weight_std=0.3, bias_std=0.2):
@@ -162,6 +162,53 @@ def test_attention_is_causal_and_matches_brute_force():
     assert np.array_equal(out[:, :, :3], out2[:, :, :3])
 
 
+def test_full_attention_equal_scores_give_sequence_mean_and_brute_force():
+    """The encoder variant (section 5): no mask.  Equal scores average V over the whole sequence; random
+    scores match the definition written as loops; and every output depends on the last position."""
+    rng = np.random.default_rng(4)
+    b, h, s, dh = 2, 2, 5, 3
+    v = rng.standard_normal((b, h, s, dh))
+    out, prob = O.attention(np.zeros((b, h, s, dh)), rng.standard_normal((b, h, s, dh)), v, False)
+    assert np.allclose(out, np.broadcast_to(v.mean(axis=2, keepdims=True), v.shape), atol=1e-14)
+    assert np.allclose(prob, 1.0 / s)
+    q, k = (rng.standard_normal((b, h, s, dh)) for _ in range(2))
+    out, _ = O.attention(q, k, v, False)
+    ref = np.zeros_like(out)
+    for bi in range(b):
+        for hi in range(h):
+            for i in range(s):
+                w = [math.exp(sum(q[bi, hi, i, c] * k[bi, hi, j, c] for c in range(dh)) / math.sqrt(dh)) for j in range(s)]
+                z = sum(w)
+                for c in range(dh):
+                    ref[bi, hi, i, c] = sum(w[j] * v[bi, hi, j, c] for j in range(s)) / z
+    assert np.allclose(out, ref, atol=1e-13)
+    v2 = v.copy(); v2[:, :, -1] += 1.0
+    out2, _ = O.attention(q, k, v2, False)
+    assert (np.abs(out2 - out).max(axis=-1) > 1e-6).all()
+    # the causal variant keeps its first position blind to it
+    c1, _ = O.attention(q, k, v, True); c2, _ = O.attention(q, k, v2, True)
+    assert np.array_equal(c1[:, :, :-1], c2[:, :, :-1])
+
+
+def test_encoder_stack_is_equivariant_under_permutations_of_the_positions():
+    """Without a mask nothing in the stack knows the order of the positions (there is no positional input):
+    permuting them permutes outputs and input gradients and leaves the summed weight gradients unchanged.
+    With the causal mask that symmetry is broken."""
+    shape = tiny_shape(d_l=2, d_m=8, d_a=2, d_s=6, b_mu=2, n_mu=2, causal=False)
+    x, G, params = tiny_problem(shape)
+    perm = np.array([3, 0, 5, 1, 4, 2])
+    a = O.step_microbatch_major(x, G, params, shape)
+    b = O.step_microbatch_major(x[:, :, perm], G[:, :, perm], params, shape)
+    assert np.allclose(a.boundaries[:, :, :, perm], b.boundaries, rtol=1e-12, atol=1e-13)
+    assert np.allclose(a.dx[:, :, perm], b.dx, rtol=1e-11, atol=1e-13)
+    for l in range(shape.d_l):
+        assert np.allclose(a.grads[l], b.grads[l], rtol=1e-10, atol=1e-12)
+    causal = tiny_shape(d_l=2, d_m=8, d_a=2, d_s=6, b_mu=2, n_mu=2)
+    c = O.step_microbatch_major(x, G, params, causal)
+    d = O.step_microbatch_major(x[:, :, perm], G[:, :, perm], params, causal)
+    assert not np.allclose(c.boundaries[:, :, :, perm], d.boundaries, rtol=1e-3, atol=1e-3)
+
+
 def test_sequences_in_a_micro_batch_do_not_mix():
     shape = tiny_shape(d_l=1, n_mu=1)
     x, G, params = tiny_problem(shape)
@@ -173,8 +220,9 @@ def test_sequences_in_a_micro_batch_do_not_mix():
 
 # ---------------------------------------------------------------- backward formulas
 
-def test_gradients_by_central_finite_differences():
-    shape = tiny_shape(d_l=2, d_m=8, d_a=2, d_s=5, b_mu=2, n_mu=2)
+@pytest.mark.parametrize("causal", [True, False])
+def test_gradients_by_central_finite_differences(causal):
+    shape = tiny_shape(d_l=2, d_m=8, d_a=2, d_s=5, b_mu=2, n_mu=2, causal=causal)
     x, G, params = tiny_problem(shape)
     res = O.step_microbatch_major(x, G, params, shape)
     assert abs(res.loss - O.loss_only(x, G, params, shape)) < 1e-9
@@ -203,10 +251,11 @@ def test_gradients_by_central_finite_differences():
     assert worst < 2e-7, worst
 
 
-def test_against_autograd_built_from_library_routines():
+@pytest.mark.parametrize("causal", [True, False])
+def test_against_autograd_built_from_library_routines(causal):
     torch = pytest.importorskip("torch")
     F = torch.nn.functional
-    shape = tiny_shape(d_l=2, d_m=16, d_a=4, d_s=7, b_mu=2, n_mu=2)
+    shape = tiny_shape(d_l=2, d_m=16, d_a=4, d_s=7, b_mu=2, n_mu=2, causal=causal)
     x, G, params = tiny_problem(shape)
     res = O.step_microbatch_major(x, G, params, shape)
     sl = S.tensor_slices(shape.d_m, shape.d_I)
@@ -223,7 +272,7 @@ def test_against_autograd_built_from_library_routines():
             h = F.layer_norm(a, (d,), P["ln1_g"], P["ln1_b"], shape.ln_eps)
             qkv = F.linear(h, P["w_qkv"].T, P["b_qkv"])
             q, k, v = (t.reshape(shape.b_mu, shape.d_s, H, d // H).transpose(1, 2) for t in qkv.split(d, dim=-1))
-            att = F.scaled_dot_product_attention(q, k, v, is_causal=True)
+            att = F.scaled_dot_product_attention(q, k, v, is_causal=causal)
             att = att.transpose(1, 2).reshape(shape.b_mu, shape.d_s, d)
             a = a + F.linear(att, P["w_o"].T, P["b_o"])
             h2 = F.layer_norm(a, (d,), P["ln2_g"], P["ln2_b"], shape.ln_eps)
@@ -253,8 +302,9 @@ def test_accumulation_over_micro_batches_equals_full_batch_gradient():
     assert np.allclose(merge(acc.boundaries[-1]), full.boundaries[-1], rtol=1e-13, atol=1e-13)
 
 
-def test_layered_order_equals_micro_batch_major_order_including_early_adam():
-    shape = tiny_shape(d_l=3, n_mu=3)
+@pytest.mark.parametrize("causal", [True, False])
+def test_layered_order_equals_micro_batch_major_order_including_early_adam(causal):
+    shape = tiny_shape(d_l=3, n_mu=3, causal=causal)
     x, G, params = tiny_problem(shape)
     rng = np.random.default_rng(5)
     m0 = [0.1 * rng.standard_normal(p.size) for p in params]
