@@ -31,6 +31,12 @@ def parse():
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=3, help="index into the five benchmark configurations")
+    ap.add_argument("--x-family", type=int, default=0, metavar="X",
+                    help="instead of --config: the paper's X_[x] model (table B.1), all x layers, micro-batches of one "
+                         "sequence; --n-micro sets how many")
+    ap.add_argument("--n-micro", type=int, default=32, help="micro-batches per step of the --x-family workload")
+    ap.add_argument("--attention", choices=["causal", "full"], default="causal",
+                    help="full: the paper's encoder, no mask (the benchmark configurations are causal decoders)")
     ap.add_argument("--group", type=int, default=0, help="micro-batches per kernel launch (0 = default for the config)")
     ap.add_argument("--order", choices=["layered", "mbmajor"], default="layered")
     ap.add_argument("--overlap", type=int, default=0, choices=[0, 1, 2, 3],
@@ -58,7 +64,7 @@ def measured_traffic(workload, kernel):
     return None
 
 
-def cpu_baseline(w, sample_tokens):
+def cpu_baseline(w, sample_tokens, causal=True):
     """Time the oracle (as it stands) on a one-layer, one-micro-batch sample of the same layer shape."""
     import numpy as np
     import synth_inputs as S
@@ -71,7 +77,7 @@ def cpu_baseline(w, sample_tokens):
     s = min(w.seq_len, sample_tokens)
     sw = S.Workload(w.name + "_cpu_sample", 1, w.d_model, w.n_heads, w.d_ff, s, 1, 1, w.dtype)
     x, G, params = S.make_inputs(sw, seed=0)
-    shape = O.StackShape(d_l=1, d_m=sw.d_model, d_a=sw.n_heads, d_I=sw.d_ff, d_s=s, b_mu=1, n_mu=1)
+    shape = O.StackShape(d_l=1, d_m=sw.d_model, d_a=sw.n_heads, d_I=sw.d_ff, d_s=s, b_mu=1, n_mu=1, causal=causal)
     t0 = time.perf_counter()
     O.step_microbatch_major(x, G, params, shape, O.AdamHyper())
     dt = time.perf_counter() - t0
@@ -91,16 +97,19 @@ def main():
     import synth_inputs as S
     from paper_2106_02679_amd import binding as B
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = S.CONFIGS[args.config]
+    w = S.x_family(args.x_family, args.n_micro) if args.x_family else S.CONFIGS[args.config]
     dt = B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
-    group = args.group or DEFAULT_GROUP[args.config]
+    # default group: the benchmark configurations' own, else about 4096 tokens per launch
+    default_group = max(1, 4096 // (w.micro_batch * w.seq_len)) if args.x_family else DEFAULT_GROUP[args.config]
+    group = args.group or default_group
+    causal = args.attention == "causal"
     if args.order == "mbmajor":
         group = 1
     while w.n_micro % group:
         group -= 1
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
                         group=group, retain_grads=1 if args.order == "mbmajor" else 0, param_buffers=args.param_buffers,
-                        overlap=args.overlap)
+                        overlap=args.overlap, attention=B.LGA_ATTN_CAUSAL if causal else B.LGA_ATTN_FULL)
     torch.cuda.set_device(0)
     tdt = torch.bfloat16 if dt == B.LGA_BF16 else torch.float32
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
@@ -140,9 +149,11 @@ def main():
     P = w.params_per_layer
     tokens = w.tokens
     seqs = w.n_micro * w.micro_batch
-    # the paper's count: 8 flop per token per parameter (appendix C.1) plus the causal attention products
-    flops_paper = 8.0 * tokens * P * w.n_layers + 9.0 * seqs * w.n_layers * w.seq_len ** 2 * w.d_model
-    flops_model = 6.0 * tokens * P * w.n_layers + 7.0 * seqs * w.n_layers * w.seq_len ** 2 * w.d_model
+    # the paper's count: 8 flop per token per parameter (appendix C.1) plus the attention products (2 forward,
+    # 2 recompute, 5 backward; s^2 d flop each with the causal mask, twice that without)
+    pair_factor = 1.0 if causal else 2.0
+    flops_paper = 8.0 * tokens * P * w.n_layers + 9.0 * pair_factor * seqs * w.n_layers * w.seq_len ** 2 * w.d_model
+    flops_model = 6.0 * tokens * P * w.n_layers + 7.0 * pair_factor * seqs * w.n_layers * w.seq_len ** 2 * w.d_model
     peak = PEAK_BF16_TFLOPS if dt == B.LGA_BF16 else PEAK_FP32_TFLOPS
 
     dom = stats[0]
@@ -154,7 +165,7 @@ def main():
         roof = {"bound": "mfma" if dt == B.LGA_BF16 else "alu", "achieved": dom["flops"] / dom["ms"] / 1e9,
                 "peak": peak, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = measured_traffic(w.name, dom["name"]) if group == DEFAULT_GROUP[args.config] else None
+    roof["traffic"] = measured_traffic(w.name, dom["name"]) if (group == default_group and causal) else None
     roof["algorithmic_bytes_per_launch"] = dom["bytes"] / dom["launches"]
     roof["kernel"] = dom["name"]
     roof["launches"] = dom["launches"]
@@ -172,7 +183,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model, "n_heads": w.n_heads,
                    "d_ff": w.d_ff, "seq_len": w.seq_len, "micro_batch": w.micro_batch, "n_micro": w.n_micro,
-                   "group": group, "order": args.order, "tokens_per_step": tokens,
+                   "group": group, "order": args.order, "attention": args.attention, "tokens_per_step": tokens,
                    "param_buffers": args.param_buffers or w.n_layers, "overlap": args.overlap},
         "restores_per_step": restores,
         "tflops_executed": flops_exec / ms_step / 1e9,
@@ -193,7 +204,7 @@ def main():
     del x, dy
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_tokens)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_tokens, causal)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

@@ -58,6 +58,10 @@ enum lga_status {
 /* Work the library may run on a second stream of its own (lga_config.overlap). */
 enum lga_overlap { LGA_OVERLAP_NONE = 0, LGA_OVERLAP_RESTORE = 1, LGA_OVERLAP_ADAM = 2 };
 
+/* Which positions a position attends to (lga_config.attention).  The benchmark workloads are causal decoders; the
+ * paper's own model (section 5, "Model") is an encoder, whose positions attend to their whole sequence. */
+enum lga_attention { LGA_ATTN_CAUSAL = 0, LGA_ATTN_FULL = 1 };
+
 /* Order in which (layer, micro-batch) pairs are visited. */
 enum lga_order { LGA_ORDER_LAYERED = 0, LGA_ORDER_MICROBATCH_MAJOR = 1 };
 
@@ -100,6 +104,7 @@ typedef struct lga_config {
                                                   readable afterwards.
                              Every entry point still returns with all its work ordered on `stream`: a caller that
                              synchronises `stream` sees everything finished.  Results do not depend on it. */
+    int32_t attention;    /* enum lga_attention: LGA_ATTN_CAUSAL (0) decoder, LGA_ATTN_FULL encoder (no mask) */
     float ln_eps;         /* LayerNorm epsilon, inside the root (1e-5 in the benchmarks) */
     void *stream;         /* hipStream_t, borrowed; NULL = default stream */
 } lga_config;
@@ -121,7 +126,9 @@ typedef struct lga_adam {
  * Adam moments start at zero.  The 16-bit parameter copy of every layer is produced here
  * (section 2.5: parameters are converted to 16 bits before use) and refreshed by each Adam step.
  * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in bf16 mode,
- * d_h % 32 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  LGA_ERR_OOM if the arena does not fit. */
+ * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes 32, 64, 96, 128 and 160 have MFMA attention kernels in
+ * bf16 mode; other head sizes, and the fp32 mode, use a one-wavefront-per-position kernel that is meant for checking,
+ * not for speed, and limits seq_len (2 seq_len + 2 d_h <= 15000).  LGA_ERR_OOM if the arena does not fit. */
 int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **out);
 
 void lga_destroy_stack(lga_stack *stack);
@@ -202,7 +209,7 @@ int lga_restore_count(lga_stack *stack, uint64_t *count);
  *               only for a layer's first group) plus Adam's read.
  *  flops        executed flops: GEMMs 2 flop per token per parameter for forward, recompute
  *               (which skips the second feed-forward GEMM), input gradient and weight gradient
- *               (appendix C.1), plus the causal attention products the paper neglects. */
+ *               (appendix C.1), plus the attention products the paper neglects (half of them with the causal mask). */
 int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_bytes, uint64_t *grad_bytes,
                       double *flops);
 

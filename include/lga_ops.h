@@ -64,18 +64,19 @@ int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int3
                   float *scratch, void *stream);
 uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols);
 
-/* Causal softmax attention per (sequence, head), scores scaled by 1/sqrt(d_h).
+/* Softmax attention per (sequence, head), scores scaled by 1/sqrt(d_h) (section 5, "Model").
+ * causal != 0: position i attends to positions j <= i (decoder); causal == 0: to the whole sequence (encoder).
  *  qkv  [n_seq*s, 3*heads*dh]: columns [Q | K | V], head h at columns h*dh inside each third
  *  out  [n_seq*s, heads*dh]
  *  lse  [n_seq, heads, s] float: log sum_j exp(scaled score_ij)
  * kind 0: one-wavefront-per-position kernel (any dtype, any dh); kind 1: MFMA kernel with
  * LDS-resident online softmax (LGA_BF16, dh in {32, 64, 96, 128, 160}). */
 int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out, float *lse, int32_t n_seq,
-                         int32_t s, int32_t heads, int32_t dh, void *stream);
+                         int32_t s, int32_t heads, int32_t dh, int32_t causal, void *stream);
 /* dqkv [n_seq*s, 3*heads*dh] written; delta [n_seq, heads, s] float scratch (written). */
 int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const void *out, const float *lse,
                          const void *dout, void *dqkv, float *delta, int32_t n_seq, int32_t s, int32_t heads,
-                         int32_t dh, void *stream);
+                         int32_t dh, int32_t causal, void *stream);
 
 /* One Adam update of n parameters in place (w, m, v fp32; g fp32 read-only); if w16 != NULL the new
  * weights are also written as bfloat16 (section 2.5: 16-bit copy for the next use). */

@@ -22,6 +22,7 @@ LIB_PATH = os.path.join(_HERE, "liblga.so")
 LGA_FP32, LGA_BF16 = 0, 1
 LGA_OK, LGA_ERR_ARG, LGA_ERR_SHAPE, LGA_ERR_OOM, LGA_ERR_STATE, LGA_ERR_HIP = 0, -1, -2, -3, -4, -5
 LGA_OVERLAP_NONE, LGA_OVERLAP_RESTORE, LGA_OVERLAP_ADAM = 0, 1, 2
+LGA_ATTN_CAUSAL, LGA_ATTN_FULL = 0, 1
 LGA_ORDER_LAYERED, LGA_ORDER_MICROBATCH_MAJOR = 0, 1
 (LGA_EPI_STORE, LGA_EPI_BIAS, LGA_EPI_BIAS_RESID, LGA_EPI_BIAS_GELU, LGA_EPI_MUL_DGELU,
  LGA_EPI_ACCUM_F32) = range(6)
@@ -34,7 +35,7 @@ class lga_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
                 ("seq_len", C.c_int32), ("micro_batch", C.c_int32), ("n_micro", C.c_int32), ("dtype", C.c_int32),
                 ("group", C.c_int32), ("retain_grads", C.c_int32), ("wgrad_groups", C.c_int32), ("param_buffers", C.c_int32),
-                ("overlap", C.c_int32), ("ln_eps", C.c_float),
+                ("overlap", C.c_int32), ("attention", C.c_int32), ("ln_eps", C.c_float),
                 ("stream", C.c_void_p)]
 
 
@@ -92,8 +93,8 @@ SIGNATURES = {
     "lga_op_transpose": (C.c_int, [_vp, _vp, _i32, _i32, C.c_int64, C.c_int64, _vp]),
     "lga_op_colsum": (C.c_int, [_i32, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "lga_op_colsum_scratch_floats": (_u64, [_i32, _i32]),
-    "lga_op_attention_fwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
-    "lga_op_attention_bwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp]),
+    "lga_op_attention_fwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "lga_op_attention_bwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
     "lga_op_adam": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _u64, _P(lga_adam), _vp]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
@@ -137,9 +138,10 @@ def check(code: int) -> None:
 
 
 def make_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group=1, retain_grads=0,
-                ln_eps=1e-5, stream: Optional[int] = None, wgrad_groups=0, param_buffers=0, overlap=0) -> lga_config:
+                ln_eps=1e-5, stream: Optional[int] = None, wgrad_groups=0, param_buffers=0, overlap=0,
+                attention=0) -> lga_config:
     return lga_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group, retain_grads,
-                      wgrad_groups, param_buffers, overlap, ln_eps, stream)
+                      wgrad_groups, param_buffers, overlap, attention, ln_eps, stream)
 
 
 def params_per_layer(cfg: lga_config) -> int:

@@ -1,5 +1,6 @@
-// Causal attention for gfx950 in bf16 with fp32 accumulation: forward with an online softmax, and a
-// deterministic two-kernel backward (no float atomics).
+// Softmax attention for gfx950 in bf16 with fp32 accumulation: forward with an online softmax, and a
+// deterministic two-kernel backward (no float atomics).  Causal (decoder: position i sees j <= i) or unmasked
+// (encoder: every position sees its whole sequence; only keys past the end of a ragged last tile are masked).
 //
 // All three kernels are built the same way.  A wavefront owns 32-position blocks of one (sequence, head) and
 // lane l owns position l%32 of a block, so every softmax statistic and row sum is lane-local (only the two
@@ -134,8 +135,25 @@ template <int ROWS, int DH, int PITCH> struct TileDma {
     }
 };
 
+// Workgroup -> ((sequence, head), block rank) for a 1-D grid of n_seq * heads * nblocks workgroups, which the
+// hardware hands out in index order.  With the causal mask a (sequence, head)'s blocks differ in length by up to
+// the number of blocks: rank is the slow index, so every (sequence, head)'s longest block (rank 0) starts before
+// anyone's second longest and the launch ends on the shortest ones.  Without the mask all blocks are equally
+// long: rank is the fast index, so the blocks that stream the same keys and values run at the same time and
+// share them in the caches.
+__device__ __forceinline__ void block_of(const AttnShape &sh, int nblocks, int &bh, int &rank) {
+    const int bhs = sh.n_seq * sh.heads;
+    if (sh.causal) {
+        bh = blockIdx.x % bhs;
+        rank = blockIdx.x / bhs;
+    } else {
+        rank = blockIdx.x % nblocks;
+        bh = blockIdx.x / nblocks;
+    }
+}
+
 // ============================================================================================
-// Forward.  grid.x = query blocks of 256 (largest first), grid.y = n_seq * heads.
+// Forward.  One workgroup per (sequence, head, block of 256 queries), see block_of(); rank 0 = the last block.
 //
 // A wavefront owns 64 queries as two sub-blocks of 32, so every K and V operand it reads from LDS
 // feeds two MFMAs; one wavefront per SIMD, with registers for both sub-blocks' output accumulators.
@@ -158,14 +176,20 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
 
     const int qblocks = (sh.s + 255) / 256;
-    const int qb = qblocks - 1 - blockIdx.x;
-    const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
+    int bh, rank;
+    block_of(sh, qblocks, bh, rank);
+    const int qb = qblocks - 1 - rank;
+    const int h = bh % sh.heads, b = bh / sh.heads;
     const int d = sh.heads * DH;
     const size_t pitch = 3 * (size_t)d;
     const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int qw0 = qb * 256 + wave * 64;          // first query of this wavefront
+    const bool causal = sh.causal != 0;
+    // Last visible key of sub-block u's lanes = vis_u(u) + vis_lane + 4 half: the query itself, or the end of the sequence.
+    const int vis_lane = (causal ? lrow : 0) - 4 * half;
+    auto vis_u = [&](int u) { return causal ? qw0 + 32 * u : sh.s - 1; };
 
     bf16x8 qf[2][NK];
 #pragma unroll
@@ -247,13 +271,13 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
             oacc[u][jc % NC] = MFMA(vf[jc], pf[n][jc / NC], oacc[u][jc % NC]);
         }
     };
-    // MASKED: probabilities of keys beyond the query are forced to zero (the diagonal part of the sequence);
-    // the other copy has no test at all.
+    // MASKED: probabilities of keys beyond the last visible one are forced to zero (the diagonal part of the
+    // sequence, or the ragged last tile of an unmasked sequence); the other copy has no test at all.
     auto exp_group = [&](int n, int g, int k0, auto masked_c) {    // quarter g of unit n's exponentials
         constexpr bool MASKED = decltype(masked_c)::value;
         const int kb = n >> 1, u = n & 1;
         // key of score register r is visible iff 8 (r / 4) + r % 4 <= qrel
-        const int qrel = qw0 + 32 * u + lrow - (k0 + 32 * kb + 4 * half);
+        const int qrel = vis_u(u) + vis_lane - (k0 + 32 * kb);
 #pragma unroll
         for (int r = 4 * g; r < 4 * g + 4; ++r) {
             float p = __builtin_amdgcn_exp2f(fmaf(st[n][r], c2, -m_ref[u]));
@@ -334,8 +358,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
         asm volatile("" ::: "memory");
     };
 
-    const int kend = min(sh.s, qb * 256 + 256);     // keys needed by this block: [0, kend)
-    const int kfull = qb * 256;                     // tiles before it are fully visible to every wavefront
+    const int kend = causal ? min(sh.s, qb * 256 + 256) : sh.s;      // keys needed by this block: [0, kend)
+    const int kfull = causal ? qb * 256 : sh.s / KT * KT;           // tiles before it are fully visible to every wavefront
     for (;;) {
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -359,7 +383,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
             }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int qrel = qw0 + 32 * u + lrow - 4 * half;
+                const int qrel = vis_u(u) + vis_lane;
                 float raw = -INFINITY;
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
@@ -379,7 +403,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
         for (; k0 < kend; k0 += KT, stage = stage == NSTAGE - 1 ? 0 : stage + 1) {       // the diagonal part
             publish(k0 + KT < kend);
             if (k0 + 2 * KT < kend) dma_tile(k0 + 2 * KT, stage == 0 ? NSTAGE - 1 : stage - 1);
-            if (k0 <= qw0) tile(k0, stage, std::true_type{});
+            if (!causal || k0 <= qw0) tile(k0, stage, std::true_type{});
         }
         __syncthreads();
         if (!restart_flag[0]) break;
@@ -445,7 +469,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict_
 }
 
 // ============================================================================================
-// dQ.  grid.x = query blocks of 128 (largest first), grid.y = n_seq * heads.
+// dQ.  One workgroup per (sequence, head, block of 128 queries), see block_of(); rank 0 = the last block.
 //
 // A wavefront owns 32 queries (Q and dO operands in registers); key tiles of 64 (K and V as stored) stream
 // from global memory straight into one of two LDS stages while the other is multiplied, one barrier per
@@ -466,8 +490,10 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
 
     const int qblocks = (sh.s + 127) / 128;
-    const int qb = qblocks - 1 - blockIdx.x;
-    const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
+    int bh, rank;
+    block_of(sh, qblocks, bh, rank);
+    const int qb = qblocks - 1 - rank;
+    const int h = bh % sh.heads, b = bh / sh.heads;
     const int d = sh.heads * DH;
     const size_t pitch = 3 * (size_t)d;
     const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
@@ -508,7 +534,8 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     const int koff = lrow * PK + 8 * half, voff = lrow * PV + 8 * half;   // per-lane parts of the operand addresses
     const int ktoff = tr_lane_off<PK>(lane);
 
-    const int kend = min(sh.s, qb * 128 + 128);
+    const bool causal = sh.causal != 0;
+    const int kend = causal ? min(sh.s, qb * 128 + 128) : sh.s;
     dma_tile(0, 0);
     int stage = 0;
     for (int k0 = 0; k0 < kend; k0 += KT, stage ^= 1) {
@@ -519,12 +546,15 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (k0 + KT < kend) dma_tile(k0 + KT, stage ^ 1);
-        if (k0 > qw0 + 31) continue;               // whole tile is in this wavefront's future
+        if (causal && k0 > qw0 + 31) continue;     // whole tile is in this wavefront's future
         const bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             const int kbs = k0 + 32 * kb;          // first key of this block of 32
-            if (kbs > qw0) continue;               // in the future of all 32 queries (both are multiples of 32)
+            // in the future of all 32 queries (both are multiples of 32), or past the end of the sequence
+            if (causal ? kbs > qw0 : kbs >= sh.s) continue;
+            // last visible key of this lane's query, relative to the block: the query itself, or the end of the sequence
+            const int klast = causal ? qw0 + lrow - kbs : sh.s - 1 - kbs;
             bf16x8 kf[NK], vfr[NK], ktf[2 * NC];
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
@@ -546,11 +576,11 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
 #pragma unroll
                 for (int c = 0; c < NC; ++c) ktf[kk * NC + c] = frag_nat_tr<PK>(Ks + ktoff, c, 2 * kb + kk);
             __builtin_amdgcn_sched_barrier(0);
-            if (kbs == qw0) {                       // the diagonal block: keys beyond the query are masked
+            if (causal ? kbs == qw0 : kbs + 32 > sh.s) {     // the diagonal block, or the ragged last one: masked keys
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float p = __builtin_amdgcn_exp2f(fmaf(st[r], c2, -lse2));
-                    if (8 * (r >> 2) + 4 * half + (r & 3) > lrow) p = 0.f;
+                    if (8 * (r >> 2) + 4 * half + (r & 3) > klast) p = 0.f;
                     st[r] = p * (dpt[r] - dl);
                 }
             } else {
@@ -669,13 +699,15 @@ template <int DH> struct BothAddr {
 };
 
 // ============================================================================================
-// dK, dV.  grid.x = key blocks of 128 (smallest index first: it has the most queries), grid.y = n_seq * heads.
+// dK, dV.  One workgroup per (sequence, head, block of 128 keys), see block_of(); rank = key block index (with the
+// causal mask the first key block has the most queries).
 //
 // A wavefront owns 32 keys (K and V operands in registers, dK and dV accumulators); query tiles of 64 (Q and
 // dO as stored) stream from global memory straight into one of three LDS stages, one barrier per tile.  Every
 // tile is read both ways: rows for S = Q K^T and dP = dO V^T, transposed for dV^T += dO^T P and dK^T += Q^T dS.
-// The first two query tiles of a key block contain its diagonal (masked, partly skipped); all later ones are
-// fully visible and go through a loop without tests.
+// With the causal mask the first two query tiles of a key block contain its diagonal (masked, partly skipped); all
+// later ones - without the mask, all tiles from the start of the sequence - are fully visible and go through a loop
+// without tests (rows past the end of the sequence are zero and carry zero statistics: they add nothing).
 template <int DH>
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
                                                               const float *__restrict__ delta,
@@ -690,8 +722,9 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     float *lse_s = reinterpret_cast<float *>(lds + NST * STAGE);     // [NST][QT]  log-sum-exp, log2 domain, negated
     float *dl_s = lse_s + NST * QT;                                  // [NST][QT]  delta
 
-    const int kb128 = blockIdx.x;
-    const int h = blockIdx.y % sh.heads, b = blockIdx.y / sh.heads;
+    int bh, kb128;
+    block_of(sh, (sh.s + 127) / 128, bh, kb128);
+    const int h = bh % sh.heads, b = bh / sh.heads;
     const int d = sh.heads * DH;
     const size_t pitch = 3 * (size_t)d;
     const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
@@ -723,10 +756,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     do_.init(wave, lane, d * 2);
     BothAddr<DH> ad;
     ad.init(lane);
-    // Tile t holds queries [qbeg + 64 t, +64).  Its row statistics go through registers: wavefront 0 fetches the
+    const bool causal = sh.causal != 0;
+    // Tile t holds queries [qbeg + 64 t, +64); with the causal mask, queries before the key block see none of its keys.  Its row statistics go through registers: wavefront 0 fetches the
     // log-sum-exps, wavefront 1 the deltas, one tile ahead of the tile data, and they are stored to LDS before
     // the barrier that publishes the tile.
-    const int qbeg = kb128 * 128;
+    const int qbeg = causal ? kb128 * 128 : 0;
     const int ntiles = (sh.s - qbeg + QT - 1) / QT;
     auto dma_tile = [&](int t, int stage) {
         const int q0 = qbeg + QT * t;
@@ -842,7 +876,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     // Two loops in sequence rather than one with two kinds of iteration: with two code paths through the
     // MFMAs in one loop the compiler merges their accumulator registers with copies at every iteration.
     int stage = 0, t = 0;
-    for (; t < 2 && t < ntiles; ++t, stage = stage == NST - 1 ? 0 : stage + 1) {      // the diagonal part
+    const int ndiag = causal ? 2 : 0;
+    for (; t < ndiag && t < ntiles; ++t, stage = stage == NST - 1 ? 0 : stage + 1) {  // the diagonal part
         advance(t, stage);
         const int q0 = qbeg + QT * t;
 #pragma unroll
@@ -886,10 +921,10 @@ LGA_INSTANTIATE_DKV(160);
 #undef LGA_INSTANTIATE_DKV
 
 template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
-    dim3 grid((sh.s + 255) / 256, sh.n_seq * sh.heads);
+    dim3 grid((unsigned)(sh.n_seq * sh.heads) * ((sh.s + 255) / 256));
     char name[64];
     snprintf(name, sizeof(name), "attn_fwd_kernel<%d>", DH);
-    const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * 0.5;      // causal (query, key) pairs
+    const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * (sh.causal ? 0.5 : 1.0);      // visible (query, key) pairs
     const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;         // bytes of one [tokens, d] bf16 tensor
     ProfScope scope(name, 4.0 * pairs * DH, 4.0 * act, s);
     // three stages of a 64-key K tile and V tile
@@ -905,9 +940,9 @@ template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape 
 template <int DH>
 void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *dout, bf16 *dqkv, AttnShape sh,
             hipStream_t s) {
-    dim3 grid((sh.s + 127) / 128, sh.n_seq * sh.heads);
+    dim3 grid((unsigned)(sh.n_seq * sh.heads) * ((sh.s + 127) / 128));
     char name[64];
-    const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * 0.5;
+    const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * (sh.causal ? 0.5 : 1.0);
     const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;
     {
         snprintf(name, sizeof(name), "attn_bwd_dq_kernel<%d>", DH);

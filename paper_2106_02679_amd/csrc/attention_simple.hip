@@ -1,4 +1,4 @@
-// Causal attention, correctness-mode kernels: one wavefront per (sequence, head, position).
+// Softmax attention (causal or unmasked), correctness-mode kernels: one wavefront per (sequence, head, position).
 // Scores, softmax and all sums in fp32; T is the storage type.  Used by the fp32 mode; the
 // bf16 mode runs the MFMA kernels in attention_bf16.hip.
 #include "kernels.h"
@@ -24,8 +24,9 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T *__restrict
     const float scale = rsqrtf((float)sh.dh);
     for (int c = lane; c < sh.dh; c += 64) qs[c] = to_f32(base[(size_t)i * row3 + c]);
     __syncthreads();
+    const int jend = sh.causal ? i + 1 : sh.s;      // keys [0, jend) are visible
     float mx = -INFINITY;
-    for (int j = lane; j <= i; j += 64) {
+    for (int j = lane; j < jend; j += 64) {
         const T *kr = base + (size_t)j * row3 + d;
         float acc = 0.f;
         for (int c = 0; c < sh.dh; ++c) acc = fmaf(qs[c], to_f32(kr[c]), acc);
@@ -35,7 +36,7 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T *__restrict
     }
     mx = wave_max(mx);
     float sum = 0.f;
-    for (int j = lane; j <= i; j += 64) {
+    for (int j = lane; j < jend; j += 64) {
         const float e = expf(ps[j] - mx);
         ps[j] = e;
         sum += e;
@@ -45,13 +46,13 @@ __global__ __launch_bounds__(64) void attn_fwd_simple_kernel(const T *__restrict
     const float inv = 1.0f / sum;
     for (int c = lane; c < sh.dh; c += 64) {
         float acc = 0.f;
-        for (int j = 0; j <= i; ++j) acc = fmaf(ps[j], to_f32(base[(size_t)j * row3 + 2 * d + c]), acc);
+        for (int j = 0; j < jend; ++j) acc = fmaf(ps[j], to_f32(base[(size_t)j * row3 + 2 * d + c]), acc);
         out[((size_t)b * sh.s + i) * d + (size_t)h * sh.dh + c] = from_f32<T>(acc * inv);
     }
     if (lane == 0) lse[((size_t)b * sh.heads + h) * sh.s + i] = mx + logf(sum);
 }
 
-// delta_i = sum_c dO_i[c] O_i[c];  dQ_i = scale * sum_{j<=i} dS_ij K_j,  dS_ij = P_ij (dO_i.V_j - delta_i)
+// (causal case written out) delta_i = sum_c dO_i[c] O_i[c];  dQ_i = scale * sum_{j<=i} dS_ij K_j,  dS_ij = P_ij (dO_i.V_j - delta_i)
 template <class T>
 __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(const T *__restrict__ qkv, const T *__restrict__ out,
                                                                 const float *__restrict__ lse,
@@ -82,7 +83,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(const T *__restr
     if (lane == 0) delta[stat] = dl;
     const float l = lse[stat];
     __syncthreads();
-    for (int j = lane; j <= i; j += 64) {
+    const int jend = sh.causal ? i + 1 : sh.s;
+    for (int j = lane; j < jend; j += 64) {
         const T *kr = base + (size_t)j * row3 + d;
         const T *vr = base + (size_t)j * row3 + 2 * d;
         float sc = 0.f, dp = 0.f;
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simple_kernel(const T *__restr
     __syncthreads();
     for (int c = lane; c < sh.dh; c += 64) {
         float acc = 0.f;
-        for (int j = 0; j <= i; ++j) acc = fmaf(ds[j], to_f32(base[(size_t)j * row3 + d + c]), acc);
+        for (int j = 0; j < jend; ++j) acc = fmaf(ds[j], to_f32(base[(size_t)j * row3 + d + c]), acc);
         dqkv[((size_t)b * sh.s + i) * row3 + (size_t)h * sh.dh + c] = from_f32<T>(acc * scale);
     }
 }
@@ -127,7 +129,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(const T *__rest
     }
     __syncthreads();
     const size_t stat0 = ((size_t)b * sh.heads + h) * sh.s;
-    for (int i = j + lane; i < sh.s; i += 64) {
+    const int ibeg = sh.causal ? j : 0;             // queries [ibeg, s) see key j
+    for (int i = ibeg + lane; i < sh.s; i += 64) {
         const T *qr = base + (size_t)i * row3;
         const T *gr = dob + (size_t)i * d;
         float sc = 0.f, dp = 0.f;
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simple_kernel(const T *__rest
     __syncthreads();
     for (int c = lane; c < sh.dh; c += 64) {
         float dv = 0.f, dk = 0.f;
-        for (int i = j; i < sh.s; ++i) {
+        for (int i = ibeg; i < sh.s; ++i) {
             dv = fmaf(ps[i], to_f32(dob[(size_t)i * d + c]), dv);
             dk = fmaf(ds[i], to_f32(base[(size_t)i * row3 + c]), dk);
         }

@@ -53,8 +53,9 @@ void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, E
 // qkv: [tokens, 3 d] with columns [Q | K | V], head h at columns h*dh inside each third; tokens =
 // n_seq * s, each sequence attends only to itself.  out: [tokens, d].  lse: [n_seq, heads, s] holds
 // log(sum_j exp(score_ij)) of the scaled scores.  d = heads * dh.
+// causal != 0: position i attends to j <= i (decoder); 0: to its whole sequence (encoder).
 struct AttnShape {
-    int n_seq, s, heads, dh;
+    int n_seq, s, heads, dh, causal;
 };
 template <class T> void launch_attn_fwd_simple(const T *qkv, T *out, float *lse, AttnShape sh, hipStream_t s);
 // dqkv: [tokens, 3 d]; delta: scratch [n_seq, heads, s] (row sums of dout * out).

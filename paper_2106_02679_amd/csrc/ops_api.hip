@@ -137,14 +137,15 @@ int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int3
 }
 
 int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out, float *lse, int32_t n_seq,
-                         int32_t s_len, int32_t heads, int32_t dh, void *stream) {
+                         int32_t s_len, int32_t heads, int32_t dh, int32_t causal, void *stream) {
     if (!dtype_ok(dtype) || (kind != 0 && kind != 1)) return err(LGA_ERR_ARG, "bad dtype or kind");
     if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if ((double)n_seq * heads * ((s_len + 127) / 128) > 2.0e9) return err(LGA_ERR_SHAPE, "sizes overflow the index range");
     if (!qkv || !out || !lse) return err(LGA_ERR_ARG, "NULL argument");
     if (kind == 1 && (dtype != LGA_BF16 || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out)))
         return err(LGA_ERR_SHAPE, "MFMA attention needs bf16, 16-byte aligned tensors and d_h in {32,64,96,128,160}");
     if ((size_t)(dh + s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
-    const AttnShape sh{n_seq, s_len, heads, dh};
+    const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (kind == 1) launch_attn_fwd_bf16(static_cast<const bf16 *>(qkv), static_cast<bf16 *>(out), lse, sh, s);
     else if (dtype == LGA_FP32) launch_attn_fwd_simple<float>(static_cast<const float *>(qkv), static_cast<float *>(out), lse, sh, s);
@@ -154,14 +155,15 @@ int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out
 
 int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const void *out, const float *lse,
                          const void *dout, void *dqkv, float *delta, int32_t n_seq, int32_t s_len, int32_t heads,
-                         int32_t dh, void *stream) {
+                         int32_t dh, int32_t causal, void *stream) {
     if (!dtype_ok(dtype) || (kind != 0 && kind != 1)) return err(LGA_ERR_ARG, "bad dtype or kind");
     if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if ((double)n_seq * heads * ((s_len + 127) / 128) > 2.0e9) return err(LGA_ERR_SHAPE, "sizes overflow the index range");
     if (!qkv || !out || !lse || !dout || !dqkv || !delta) return err(LGA_ERR_ARG, "NULL argument");
     if (kind == 1 && (dtype != LGA_BF16 || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out) || !a16(dout) || !a16(dqkv)))
         return err(LGA_ERR_SHAPE, "MFMA attention needs bf16, 16-byte aligned tensors and d_h in {32,64,96,128,160}");
     if ((size_t)(2 * dh + 2 * s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
-    const AttnShape sh{n_seq, s_len, heads, dh};
+    const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (kind == 1)
         launch_attn_bwd_bf16(static_cast<const bf16 *>(qkv), static_cast<const bf16 *>(out), lse,

@@ -88,12 +88,18 @@ int validate_config(const lga_config *c) {
     if (c->param_buffers < 0 || c->param_buffers > c->n_layers)
         return fail(LGA_ERR_SHAPE, "param_buffers must be 0 (one per layer) or in 1..n_layers");
     if (c->overlap < 0 || c->overlap > 3) return fail(LGA_ERR_ARG, "overlap must be a combination of LGA_OVERLAP_* bits");
+    if (c->attention != LGA_ATTN_CAUSAL && c->attention != LGA_ATTN_FULL)
+        return fail(LGA_ERR_ARG, "attention must be LGA_ATTN_CAUSAL or LGA_ATTN_FULL");
     if (!(c->ln_eps >= 0.f)) return fail(LGA_ERR_ARG, "ln_eps must be >= 0");
     if (c->dtype == LGA_FP32 && (2.0 * c->seq_len + 2.0 * c->d_model / c->n_heads) * 4 > 60000)
         return fail(LGA_ERR_SHAPE, "fp32 mode: seq_len too long for the one-wavefront attention kernel's LDS rows");
     if (c->dtype == LGA_BF16) {
         const int dh = c->d_model / c->n_heads;
-        if (dh % 32 != 0) return fail(LGA_ERR_SHAPE, "bf16 mode needs head size d_h to be a multiple of 32");
+        if (dh % 8 != 0) return fail(LGA_ERR_SHAPE, "bf16 mode needs head size d_h to be a multiple of 8");
+        // head sizes without an MFMA attention kernel go through the one-wavefront kernels, like the fp32 mode
+        if (!attn_bf16_supports(dh) && (2.0 * c->seq_len + 2.0 * dh) * 4 > 60000)
+            return fail(LGA_ERR_SHAPE, "seq_len too long for the one-wavefront attention kernel's LDS rows (head size "
+                                       "without an MFMA attention kernel)");
         if (c->d_model % 8 != 0 || c->d_ff % 8 != 0)
             return fail(LGA_ERR_SHAPE, "bf16 mode needs d_model and d_ff to be multiples of 8");
         if (((long)c->group * c->micro_batch * c->seq_len) % 8 != 0)
@@ -101,7 +107,7 @@ int validate_config(const lga_config *c) {
     }
     // kernels index rows and columns with int and elements with size_t
     const double tokens_group = (double)c->group * c->micro_batch * c->seq_len;
-    if (tokens_group > 1.0e9 || 3.0 * c->d_model > 2.0e9 || (double)c->n_heads * c->micro_batch * c->group > 2.0e9)
+    if (tokens_group > 1.0e9 || 3.0 * c->d_model > 2.0e9 || (double)c->n_heads * c->micro_batch * c->group * ((c->seq_len + 127) / 128) > 2.0e9)
         return fail(LGA_ERR_SHAPE, "sizes overflow the index range");
     return LGA_OK;
 }
@@ -328,7 +334,7 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     T *x1 = st->at<T>(st->plan.x1), *h2 = st->at<T>(st->plan.h2), *u = st->at<T>(st->plan.u);
     T *gl = st->at<T>(st->plan.gl);
     float *lse = st->at<float>(st->plan.lse);
-    const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
+    const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads, c.attention == LGA_ATTN_CAUSAL};
 
     // y[t, out] = x[t, in] W[in, out]: fp32 mode reads W as stored; bf16 mode reads the transposed copy
     // W^T[out, in], so both operands are k-contiguous.
@@ -398,7 +404,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     float *mean2 = st->at<float>(st->plan.mean2), *rstd2 = st->at<float>(st->plan.rstd2);
     float *lse = st->at<float>(st->plan.lse), *delta = st->at<float>(st->plan.delta);
     float *partial = st->at<float>(st->plan.partial);
-    const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads};
+    const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads, c.attention == LGA_ATTN_CAUSAL};
 
     // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over tokens.  bf16 mode first writes X^T [in][.]
     // and dY^T [out][.] (two HBM-bound passes, ~1 % of the GEMM's time) so that the GEMM reads both
@@ -693,8 +699,10 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
         const double tokens = (double)cfg->n_micro * cfg->micro_batch * cfg->seq_len;
         const double gemm = 2.0 * tokens * (double)L * (4.0 * Pm - df);                 // fwd, recompute - W_2, dX, dW
         const double seqs = (double)cfg->n_micro * cfg->micro_batch;
-        // causal products executed: forward 2, recompute 2, dQ kernel 3, dK/dV kernel 4, each s^2 d_m flop
-        const double attn = 11.0 * seqs * (double)L * (double)cfg->seq_len * cfg->seq_len * cfg->d_model;
+        // attention products executed: forward 2, recompute 2, dQ kernel 3, dK/dV kernel 4, each s^2 d_m flop with
+        // the causal mask (half of the pairs are skipped), twice that without
+        const double attn = (cfg->attention == LGA_ATTN_CAUSAL ? 11.0 : 22.0) * seqs * (double)L * (double)cfg->seq_len *
+                            cfg->seq_len * cfg->d_model;
         *flops = gemm + attn;
     }
     return LGA_OK;

@@ -1,7 +1,7 @@
 """Per-kernel benchmark of the layer stack's GEMM shapes and attention calls on one GPU.
 
     python -m paper_2106_02679_amd.opbench gemm      [--config 3] [--group 4] [--only NAME] [--iters 8]
-    python -m paper_2106_02679_amd.opbench attention [--config 3] [--group 4] [--only fwd|bwd] [--iters 8]
+    python -m paper_2106_02679_amd.opbench attention [--config 3] [--group 4] [--only fwd|bwd] [--iters 8] [--full]
 
 Every call goes through the C ABI's one-entry-point-per-kernel functions (lga_op_gemm, lga_op_attention_*),
 on synthetic N(0, 1) activations and N(0, 0.02^2) weights of the benchmark configuration's shapes.  Times are
@@ -87,19 +87,20 @@ def run_attention(args):
     delta = torch.empty(n_seq * heads * s, device="cuda")
 
     def fwd():
-        B.check(B.lib.lga_op_attention_fwd(B.LGA_BF16, 1, qkv.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, None))
+        B.check(B.lib.lga_op_attention_fwd(B.LGA_BF16, 1, qkv.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, causal, None))
 
     def bwd():
         B.check(B.lib.lga_op_attention_bwd(B.LGA_BF16, 1, qkv.data_ptr(), out.data_ptr(), lse.data_ptr(), dout.data_ptr(),
-                                           dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, None))
-    pairs = n_seq * heads * s * s / 2.0            # causal (query, key) pairs
+                                           dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, causal, None))
+    causal = 0 if args.full else 1
+    pairs = n_seq * heads * s * s / (2.0 if causal else 1.0)            # visible (query, key) pairs
     fwd()
     for name, fn, flops in (("fwd", fwd, 4 * pairs * dh), ("bwd", bwd, 14 * pairs * dh)):
         if args.only and args.only != name:
             continue
         ms = _time(fn, args.iters)
         print(f"attention {name} n_seq={n_seq} s={s} heads={heads} d_h={dh}: {ms:8.3f} ms {flops / ms / 1e9:8.1f} TFLOP/s "
-              f"(causal flops)", flush=True)
+              f"({'causal' if causal else 'unmasked'}, executed flops)", flush=True)
 
 
 def main():
@@ -110,6 +111,7 @@ def main():
     ap.add_argument("--wgrad-groups", type=int, default=0, help="groups merged into one weight-gradient GEMM (0: all)")
     ap.add_argument("--only", default=None)
     ap.add_argument("--iters", type=int, default=8)
+    ap.add_argument("--full", action="store_true", help="attention without the causal mask (encoder)")
     args = ap.parse_args()
     import torch
     assert torch.cuda.is_available(), "opbench needs a GPU"

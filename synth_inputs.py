@@ -63,6 +63,14 @@ CONFIGS: Tuple[Workload, ...] = (
 )
 
 
+def x_family(x: int, n_micro: int, micro_batch: int = 1, n_layers: int = 0, dtype: str = "bf16") -> Workload:
+    """Shape of the paper's X_[x] model family (appendix B, table B.1): d_a = x/2 heads of size d_h = 2x,
+    d_l = x layers (or `n_layers` of them), d_s = 16x, d_m = x^2, d_I = 4x^2."""
+    if x < 2 or x % 2:
+        raise ValueError("x must be even and >= 2")
+    return Workload(f"X{x}", n_layers or x, x * x, x // 2, 4 * x * x, 16 * x, micro_batch, n_micro, dtype)
+
+
 def parity_slice(w: Workload, n_layers: int = 1, n_micro: int = 2, seq_len: int = 256) -> Workload:
     """Same width, heads, feed-forward width and dtype; fewer layers, micro-batches, tokens."""
     return Workload(w.name + "_slice", n_layers, w.d_model, w.n_heads, w.d_ff, seq_len,

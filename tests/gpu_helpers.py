@@ -45,9 +45,9 @@ def dtype_code(w: S.Workload) -> int:
     return B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
 
 
-def oracle_shape(w: S.Workload) -> O.StackShape:
+def oracle_shape(w: S.Workload, causal: bool = True) -> O.StackShape:
     return O.StackShape(d_l=w.n_layers, d_m=w.d_model, d_a=w.n_heads, d_I=w.d_ff, d_s=w.seq_len,
-                        b_mu=w.micro_batch, n_mu=w.n_micro)
+                        b_mu=w.micro_batch, n_mu=w.n_micro, causal=causal)
 
 
 def adam_struct(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=1) -> B.lga_adam:
@@ -61,12 +61,12 @@ def oracle_adam(a: B.lga_adam) -> O.AdamHyper:
 
 
 def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layered", adam=None, fused=True,
-                 want_ckpt=True, wgrad_groups=0, param_buffers=0, overlap=0):
+                 want_ckpt=True, wgrad_groups=0, param_buffers=0, overlap=0, attention=0):
     """One training step through the C ABI.  Returns a dict of float64 numpy results."""
     dt = dtype_code(w)
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
                         group=group, retain_grads=retain, wgrad_groups=wgrad_groups, param_buffers=param_buffers,
-                        overlap=overlap)
+                        overlap=overlap, attention=attention)
     st = B.Stack(cfg, np.concatenate(params))
     P = B.params_per_layer(cfg)
     xd, Gd = to_dev(x, dt), to_dev(G, dt)

@@ -206,14 +206,15 @@ def test_column_sums(dt, rows, cols, ld):
     assert rel_err(out.cpu().numpy(), a[:, :cols].astype(np.float64).sum(0)) < 1e-5
 
 
-def attention_reference(qkv, dout, n_seq, s, heads, dh):
+def attention_reference(qkv, dout, n_seq, s, heads, dh, causal=True):
     d = heads * dh
     t = qkv.astype(np.float64).reshape(n_seq, s, 3, heads, dh)
     q, k, v = (t[:, :, i].transpose(0, 2, 1, 3) for i in range(3))
-    out, prob = O.causal_attention(q, k, v)
+    out, prob = O.attention(q, k, v, causal)
     scores = (q @ np.swapaxes(k, -1, -2)) / math.sqrt(dh)
-    mask = np.triu(np.ones((s, s), dtype=bool), 1)
-    scores = np.where(mask, -np.inf, scores)
+    if causal:
+        mask = np.triu(np.ones((s, s), dtype=bool), 1)
+        scores = np.where(mask, -np.inf, scores)
     mx = scores.max(-1, keepdims=True)
     lse = (mx + np.log(np.exp(scores - mx).sum(-1, keepdims=True)))[..., 0]
     do = dout.astype(np.float64).reshape(n_seq, s, heads, dh).transpose(0, 2, 1, 3)
@@ -231,23 +232,34 @@ ATTN_CASES = [
     (BF16, 1, 1, 1100, 2, 128), (BF16, 1, 2, 640, 1, 64), (BF16, 1, 1, 777, 1, 96), (BF16, 1, 1, 520, 1, 160),
     (BF16, 1, 1, 600, 1, 32),
 ]
+# the encoder variant (no mask): whole tiles, ragged last tiles of every residue class that matters (a last
+# key block that is partly / wholly past the end), sequences shorter than a block, every head size
+FULL_CASES = [
+    (F32, 0, 2, 37, 3, 16), (F32, 0, 1, 1, 1, 8), (BF16, 0, 1, 70, 2, 32),
+    (BF16, 1, 2, 256, 2, 128), (BF16, 1, 1, 333, 3, 64), (BF16, 1, 2, 200, 2, 32), (BF16, 1, 1, 130, 2, 160),
+    (BF16, 1, 1, 1, 1, 64), (BF16, 1, 3, 64, 1, 96), (BF16, 1, 1, 31, 2, 128), (BF16, 1, 1, 97, 1, 64),
+    (BF16, 1, 1, 1100, 2, 128), (BF16, 1, 2, 640, 1, 64), (BF16, 1, 1, 777, 1, 96), (BF16, 1, 1, 520, 1, 160),
+    (BF16, 1, 1, 600, 1, 32),
+]
 
 
-@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "-".join(map(str, c)))
+@pytest.mark.parametrize("case", [c + (True,) for c in ATTN_CASES] + [c + (False,) for c in FULL_CASES],
+                         ids=lambda c: "-".join(map(str, c[:-1])) + ("-causal" if c[-1] else "-full"))
 def test_attention_forward_and_backward(case):
-    dt, kind, n_seq, s, heads, dh = case
+    dt, kind, n_seq, s, heads, dh, causal = case
     d = heads * dh
-    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    rng = np.random.default_rng(hash(case[:-1]) % (2 ** 32))
     qkv = rnd(rng, (n_seq * s, 3 * d), dt)
     dout = rnd(rng, (n_seq * s, d), dt)
-    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh)
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh, causal)
     qd, dod = to_dev(qkv, dt), to_dev(dout, dt)
     out, dqkv = empty_dev((n_seq * s, d), dt), empty_dev((n_seq * s, 3 * d), dt)
     lse = torch.empty(n_seq * heads * s, device="cuda")
     delta = torch.empty(n_seq * heads * s, device="cuda")
-    B.check(B.lib.lga_op_attention_fwd(dt, kind, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, None))
+    B.check(B.lib.lga_op_attention_fwd(dt, kind, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+                                       int(causal), None))
     B.check(B.lib.lga_op_attention_bwd(dt, kind, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
-                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, None))
+                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), None))
     torch.cuda.synchronize()
     tol_f, tol_b = (1e-5, 2e-5) if dt == F32 else (1e-2, 2e-2)
     assert rel_err(to_host(out), out_ref) < tol_f
@@ -257,8 +269,8 @@ def test_attention_forward_and_backward(case):
         assert rel_err(got[:, sl], dqkv_ref[:, sl]) < tol_b, name
 
 
-@pytest.mark.parametrize("dh", [64, 128])
-def test_attention_with_scores_that_keep_growing_along_the_keys(dh):
+@pytest.mark.parametrize("dh,causal", [(64, True), (128, True), (128, False)])
+def test_attention_with_scores_that_keep_growing_along_the_keys(dh, causal):
     """The forward kernel fixes each query's softmax reference at its first 32 keys.  Here later keys score
     more than 100 (log2 units) above those, which the kernel must survive by starting over with a larger
     reference: outputs, log-sum-exp and the backward (which uses that log-sum-exp) still match the oracle."""
@@ -272,15 +284,19 @@ def test_attention_with_scores_that_keep_growing_along_the_keys(dh):
         qkv[:, d + h * dh] = ramp                                 # k[j, 0] = j / 4
     qkv = S.round_to_bf16(qkv)
     dout = rnd(rng, (n_seq * s, d), BF16)
-    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh)
-    assert ((lse_ref[..., -1] - lse_ref[..., 31]) * math.log2(math.e) > 100).all()      # the case is what it claims
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh, causal)
+    # the case is what it claims: the last query's log-sum-exp lies > 100 log2 units above its first 32 scores
+    t4 = qkv.astype(np.float64).reshape(n_seq, s, 3, heads, dh)
+    first = np.einsum("bhc,bkhc->bhk", t4[:, -1, 0], t4[:, :32, 1]) / math.sqrt(dh)
+    assert ((lse_ref[..., -1] - first.max(-1)) * math.log2(math.e) > 100).all()
     qd, dod = to_dev(qkv, BF16), to_dev(dout, BF16)
     out, dqkv = empty_dev((n_seq * s, d), BF16), empty_dev((n_seq * s, 3 * d), BF16)
     lse = torch.empty(n_seq * heads * s, device="cuda")
     delta = torch.empty(n_seq * heads * s, device="cuda")
-    B.check(B.lib.lga_op_attention_fwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, None))
+    B.check(B.lib.lga_op_attention_fwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+                                       int(causal), None))
     B.check(B.lib.lga_op_attention_bwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
-                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, None))
+                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), None))
     torch.cuda.synchronize()
     assert np.isfinite(to_host(out)).all()
     assert rel_err(to_host(out), out_ref) < 1e-2
@@ -294,9 +310,9 @@ def test_attention_with_scores_that_keep_growing_along_the_keys(dh):
 def test_attention_mfma_rejects_unsupported_head_size():
     t = torch.zeros(4096, device="cuda", dtype=torch.bfloat16)
     l = torch.zeros(64, device="cuda")
-    rc = B.lib.lga_op_attention_fwd(BF16, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 48, None)
+    rc = B.lib.lga_op_attention_fwd(BF16, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 48, 1, None)
     assert rc == B.LGA_ERR_SHAPE
-    rc = B.lib.lga_op_attention_fwd(F32, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 64, None)
+    rc = B.lib.lga_op_attention_fwd(F32, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 64, 1, None)
     assert rc == B.LGA_ERR_SHAPE
 
 

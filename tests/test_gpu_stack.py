@@ -102,6 +102,59 @@ def test_bf16_small_stacks_match_oracle(dh, group):
     print(f"dh={dh} group={group} worst rel err {max(worst.values()):.3e}")
 
 
+@pytest.mark.parametrize("dtype,dh,group", [("fp32", 10, 2), ("bf16", 64, 1), ("bf16", 128, 2), ("bf16", 160, 4)])
+def test_encoder_stacks_without_the_causal_mask_match_oracle(dtype, dh, group):
+    """The paper's own model (section 5): an encoder, every position attends to its whole sequence.  Sequence
+    length 100: ragged against the kernels' 32- and 64-position tiles."""
+    heads = 3 if dtype == "fp32" else 2
+    d = heads * dh
+    w = S.Workload(f"encoder_{dtype}_dh{dh}", 2, d, heads, 4 * d, 100, 2, 4, dtype)
+    x, G, params = S.make_inputs(w, seed=23, bias_std=0.02)
+    adam = adam_struct()
+    ref = O.step_microbatch_major(x, G, params, oracle_shape(w, causal=False), oracle_adam(adam))
+    got = run_gpu_step(w, x, G, params, group=group, retain=1, adam=adam, attention=B.LGA_ATTN_FULL)
+    worst = compare_with_oracle(w, got, ref, GATE[dtype], adam, zero_init=False)
+    print(f"encoder {dtype} dh={dh} worst rel err {max(worst.values()):.3e}")
+    # and the mask does matter: the decoder run of the same inputs differs
+    # (weights of std 0.02 make attention a small part of the residual stream; seen above the fp32 gate only)
+    if dtype == "fp32":
+        dec = run_gpu_step(w, x, G, params, group=group, retain=1, adam=adam)
+        assert rel_err(dec["y"], got["y"]) > 100 * GATE["fp32"]
+    mb = run_gpu_step(w, x, G, params, group=1, retain=1, order="mbmajor", adam=adam, attention=B.LGA_ATTN_FULL)
+    if group == 1:
+        assert np.array_equal(mb["boundaries"], got["boundaries"])
+    for l in range(w.n_layers):
+        assert rel_err(mb["grads"][l], got["grads"][l]) < 1e-5
+
+
+@pytest.mark.parametrize("x_,layers,causal", [(16, 4, False), (16, 2, True)])
+def test_x_family_shapes_match_oracle(x_, layers, causal):
+    """The X_[x] family of table B.1 / appendix B: d_a = x/2, d_h = 2x, d_s = 16x, d_m = x^2, d_I = 4x^2 (d_l = x,
+    cut here to a few layers so that the bf16 gate, which grows with depth, stays the one used everywhere)."""
+    w = S.Workload(f"X{x_}", layers, x_ * x_, x_ // 2, 4 * x_ * x_, 16 * x_, 1, 2, "bf16")
+    assert w.d_model // w.n_heads == 2 * x_
+    x, G, params = S.make_inputs(w, seed=29)
+    adam = adam_struct()
+    ref = O.step_microbatch_major(x, G, params, oracle_shape(w, causal=causal), oracle_adam(adam))
+    got = run_gpu_step(w, x, G, params, group=2, retain=1, adam=adam, attention=0 if causal else B.LGA_ATTN_FULL)
+    worst = compare_with_oracle(w, got, ref, GATE["bf16"], adam)
+    print(f"X_{x_} ({layers} layers, causal={causal}) worst rel err {max(worst.values()):.3e}")
+
+
+@pytest.mark.parametrize("dh,causal", [(24, True), (216, False)])
+def test_head_sizes_without_an_mfma_kernel_use_the_generic_attention_kernels(dh, causal):
+    """bf16 mode with a head size outside {32, 64, 96, 128, 160} (X_108 of table B.1 has d_h = 216): the
+    one-wavefront attention kernels serve it, everything else is unchanged."""
+    heads = 2 if dh < 100 else 1
+    d = heads * dh
+    w = S.Workload(f"oddhead_dh{dh}", 1, d, heads, 4 * d, 72, 1, 2, "bf16")
+    x, G, params = S.make_inputs(w, seed=37)
+    adam = adam_struct()
+    ref = O.step_microbatch_major(x, G, params, oracle_shape(w, causal=causal), oracle_adam(adam))
+    got = run_gpu_step(w, x, G, params, group=1, retain=1, adam=adam, attention=0 if causal else B.LGA_ATTN_FULL)
+    compare_with_oracle(w, got, ref, GATE["bf16"], adam)
+
+
 def test_orders_and_group_sizes_agree_on_the_gpu():
     """Layered order with g = 1, 2, n and micro-batch-major order give the same step up to fp32
     re-association of the gradient sums (activations are bit-identical: same kernels, same inputs)."""
