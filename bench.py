@@ -43,6 +43,8 @@ def parse():
                     help="bits: 1 = restores, 2 = per-layer Adam steps on the library's second stream beside the layer sweeps")
     ap.add_argument("--param-buffers", type=int, default=0,
                     help="16-bit parameter buffers kept (0 = one per layer); fewer makes the orders differ in restore traffic")
+    ap.add_argument("--offload", action="store_true",
+                    help="keep the layer-boundary activations in pinned host memory (two slots on the device)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=64)
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
@@ -109,7 +111,8 @@ def main():
         group -= 1
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
                         group=group, retain_grads=1 if args.order == "mbmajor" else 0, param_buffers=args.param_buffers,
-                        overlap=args.overlap, attention=B.LGA_ATTN_CAUSAL if causal else B.LGA_ATTN_FULL)
+                        overlap=args.overlap, attention=B.LGA_ATTN_CAUSAL if causal else B.LGA_ATTN_FULL,
+                        offload_checkpoints=1 if args.offload else 0)
     torch.cuda.set_device(0)
     tdt = torch.bfloat16 if dt == B.LGA_BF16 else torch.float32
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
@@ -184,8 +187,12 @@ def main():
         "config": {"workload": w.name, "n_layers": w.n_layers, "d_model": w.d_model, "n_heads": w.n_heads,
                    "d_ff": w.d_ff, "seq_len": w.seq_len, "micro_batch": w.micro_batch, "n_micro": w.n_micro,
                    "group": group, "order": args.order, "attention": args.attention, "tokens_per_step": tokens,
-                   "param_buffers": args.param_buffers or w.n_layers, "overlap": args.overlap},
+                   "param_buffers": args.param_buffers or w.n_layers, "overlap": args.overlap,
+                   "offload_checkpoints": bool(args.offload)},
         "restores_per_step": restores,
+        "device_arena_bytes": B.arena_bytes(cfg), "pinned_host_bytes": B.host_bytes(cfg),
+        # checkpoint offload: every boundary goes to the host once, all but the top two come back once
+        "pcie_bytes_per_step": (2 * w.n_layers * tokens * w.d_model * (2 if dt == B.LGA_BF16 else 4)) if args.offload else 0,
         "tflops_executed": flops_exec / ms_step / 1e9,
         "pct_peak_executed": 100.0 * flops_exec / ms_step / 1e9 / peak,
         "pct_peak_paper_flops": 100.0 * flops_paper / ms_step / 1e9 / peak,     # 8 p + 9 s^2 d accounting

@@ -105,6 +105,14 @@ typedef struct lga_config {
                              Every entry point still returns with all its work ordered on `stream`: a caller that
                              synchronises `stream` sees everything finished.  Results do not depend on it. */
     int32_t attention;    /* enum lga_attention: LGA_ATTN_CAUSAL (0) decoder, LGA_ATTN_FULL encoder (no mask) */
+    int32_t offload_checkpoints; /* 1: the layer-boundary activations (activation checkpoints, section 2.5) live in
+                             pinned host memory that the library allocates; the device keeps two boundary-sized
+                             slots (appendix C, "CPU-GPU transfers": checkpoint offload).  In the layered order each
+                             boundary crosses the bus once per pass as one transfer of all micro-batches, on a second
+                             stream of the library's own (default priority): to the host beside the next layer's
+                             forward sweep, back beside the previous layer's backward sweep.  lga_checkpoint then
+                             returns host addresses.  Not available to lga_step_mbmajor.  Results do not depend
+                             on it.  0: every boundary stays on the device. */
     float ln_eps;         /* LayerNorm epsilon, inside the root (1e-5 in the benchmarks) */
     void *stream;         /* hipStream_t, borrowed; NULL = default stream */
 } lga_config;
@@ -164,7 +172,9 @@ int lga_params(lga_stack *stack, int32_t layer, const float **dev_master, size_t
 int lga_moments(lga_stack *stack, int32_t layer, float **dev_m, float **dev_v, size_t *count);
 
 /* Borrow boundary activation `boundary` (0 = stack input ... n_layers = stack output) for all
- * micro-batches: [n_micro, micro_batch, seq_len, d_model] of the configured dtype. */
+ * micro-batches: [n_micro, micro_batch, seq_len, d_model] of the configured dtype.  A device address, or with
+ * offload_checkpoints a pinned host address (a valid source for hipMemcpy with hipMemcpyDefault); either way the
+ * data is complete once the stack's stream has been synchronised after the call that produced it. */
 int lga_checkpoint(lga_stack *stack, int32_t boundary, const void **dev_ptr, size_t *bytes);
 
 /* The comparison order (section 2.5, standard gradient accumulation): each micro-batch goes
@@ -215,6 +225,10 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
 
 /* Bytes of device memory lga_init_stack would allocate for cfg (host arithmetic only). */
 int lga_arena_bytes(const lga_config *cfg, uint64_t *bytes);
+
+/* Bytes of pinned host memory lga_init_stack would allocate for cfg: the boundary activations when
+ * offload_checkpoints is set, else 0 (host arithmetic only). */
+int lga_host_bytes(const lga_config *cfg, uint64_t *bytes);
 
 /* p_l for cfg: 4 d^2 + 2 d d_I + 9 d + d_I (= 12 d^2 + 13 d when d_I = 4 d, Table B.1). */
 int lga_params_per_layer(const lga_config *cfg, uint64_t *count);

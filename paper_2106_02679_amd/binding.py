@@ -35,7 +35,8 @@ class lga_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("d_ff", C.c_int32),
                 ("seq_len", C.c_int32), ("micro_batch", C.c_int32), ("n_micro", C.c_int32), ("dtype", C.c_int32),
                 ("group", C.c_int32), ("retain_grads", C.c_int32), ("wgrad_groups", C.c_int32), ("param_buffers", C.c_int32),
-                ("overlap", C.c_int32), ("attention", C.c_int32), ("ln_eps", C.c_float),
+                ("overlap", C.c_int32), ("attention", C.c_int32), ("offload_checkpoints", C.c_int32),
+                ("ln_eps", C.c_float),
                 ("stream", C.c_void_p)]
 
 
@@ -80,6 +81,7 @@ SIGNATURES = {
     "lga_backward_layer": (C.c_int, [_vp, _i32, _vp, _vp, _P(lga_adam)]),
     "lga_traffic_model": (C.c_int, [_P(lga_config), _i32, _P(_u64), _P(_u64), _P(C.c_double)]),
     "lga_arena_bytes": (C.c_int, [_P(lga_config), _P(_u64)]),
+    "lga_host_bytes": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_restore_count": (C.c_int, [_vp, _P(_u64)]),
     "lga_params_per_layer": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_last_error": (C.c_char_p, []),
@@ -109,11 +111,11 @@ _hip.hipMemcpy.argtypes = [_vp, _vp, C.c_size_t, C.c_int]
 
 
 def read_device(ptr: int, count: int, dtype="float32"):
-    """Blocking copy of `count` elements at device address `ptr` into a new numpy array.
+    """Blocking copy of `count` elements at device (or pinned host) address `ptr` into a new numpy array.
     Synchronise the stream that produced the data first."""
     import numpy as np
     out = np.empty(count, dtype=dtype)
-    rc = _hip.hipMemcpy(out.ctypes.data_as(_vp), ptr, out.nbytes, 2)   # hipMemcpyDeviceToHost
+    rc = _hip.hipMemcpy(out.ctypes.data_as(_vp), ptr, out.nbytes, 4)   # hipMemcpyDefault: the runtime tells from ptr
     if rc != 0:
         raise RuntimeError(f"hipMemcpy device->host failed with HIP error {rc}")
     return out
@@ -139,9 +141,9 @@ def check(code: int) -> None:
 
 def make_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group=1, retain_grads=0,
                 ln_eps=1e-5, stream: Optional[int] = None, wgrad_groups=0, param_buffers=0, overlap=0,
-                attention=0) -> lga_config:
+                attention=0, offload_checkpoints=0) -> lga_config:
     return lga_config(n_layers, d_model, n_heads, d_ff, seq_len, micro_batch, n_micro, dtype, group, retain_grads,
-                      wgrad_groups, param_buffers, overlap, attention, ln_eps, stream)
+                      wgrad_groups, param_buffers, overlap, attention, offload_checkpoints, ln_eps, stream)
 
 
 def params_per_layer(cfg: lga_config) -> int:
@@ -153,6 +155,12 @@ def params_per_layer(cfg: lga_config) -> int:
 def arena_bytes(cfg: lga_config) -> int:
     out = _u64()
     check(lib.lga_arena_bytes(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def host_bytes(cfg: lga_config) -> int:
+    out = _u64()
+    check(lib.lga_host_bytes(C.byref(cfg), C.byref(out)))
     return out.value
 
 

@@ -88,6 +88,7 @@ int validate_config(const lga_config *c) {
     if (c->param_buffers < 0 || c->param_buffers > c->n_layers)
         return fail(LGA_ERR_SHAPE, "param_buffers must be 0 (one per layer) or in 1..n_layers");
     if (c->overlap < 0 || c->overlap > 3) return fail(LGA_ERR_ARG, "overlap must be a combination of LGA_OVERLAP_* bits");
+    if (c->offload_checkpoints != 0 && c->offload_checkpoints != 1) return fail(LGA_ERR_ARG, "offload_checkpoints must be 0 or 1");
     if (c->attention != LGA_ATTN_CAUSAL && c->attention != LGA_ATTN_FULL)
         return fail(LGA_ERR_ARG, "attention must be LGA_ATTN_CAUSAL or LGA_ATTN_FULL");
     if (!(c->ln_eps >= 0.f)) return fail(LGA_ERR_ARG, "ln_eps must be >= 0");
@@ -139,7 +140,7 @@ Plan make_plan(const lga_config &c) {
     const size_t nbuf = c.param_buffers ? (size_t)c.param_buffers : L;     // layers whose 16-bit copies are resident
     p.w16 = take(c.dtype == LGA_BF16 ? nbuf * P * 2 : 0);
     p.w16t = take(c.dtype == LGA_BF16 ? nbuf * P * 2 : 0);   // each matrix transposed, at its canonical offset
-    p.ckpt = take((L + 1) * T * d * esz);
+    p.ckpt = take((c.offload_checkpoints ? std::min<size_t>(2, L + 1) : L + 1) * T * d * esz);
     p.dact = take(T * d * esz);
     p.h = take(t * d * esz);
     p.qkv = take(t * 3 * d * esz);
@@ -211,6 +212,11 @@ struct lga_stack {
     hipEvent_t ev_fork;                        // "everything enqueued on the main stream so far"
     std::vector<hipEvent_t> ev_w16, ev_grad;   // last write of each 16-bit parameter buffer / last read of each gradient buffer on aux
     std::vector<char> w16_pending, grad_pending;   // the main stream has not waited for that event yet
+    // checkpoint offload: all boundaries live in pinned host memory; the device keeps two slots, boundary b in slot b % 2
+    char *host_ckpt;
+    int dev_boundary[2];           // which boundary each device slot holds (-1: none)
+    hipEvent_t ev_ck[2];           // last transfer (either direction) of each slot on aux
+    char ck_pending[2];            // the main stream has not waited for that event yet
     int nbuf;                      // 16-bit parameter buffers: layer l uses buffer l % nbuf
     std::vector<int> w16_owner;    // which layer's 16-bit copies each of them currently holds (-1: none)
     uint64_t restores;             // casts of a layer's parameters into a buffer since creation
@@ -225,7 +231,12 @@ struct lga_stack {
     int grad_slot(int l) const { return l % ngrad; }
     float *grad(int l) const { return at<float>(plan.grad) + (size_t)grad_slot(l) * P; }
     size_t esz() const { return cfg.dtype == LGA_BF16 ? 2 : 4; }
-    char *ckpt(int boundary) const { return arena + plan.ckpt + (size_t)boundary * T * cfg.d_model * esz(); }
+    size_t boundary_bytes() const { return T * cfg.d_model * esz(); }
+    // device address of a boundary activation (offload mode: of the slot it lives in while it is on the device)
+    char *ckpt(int boundary) const {
+        return arena + plan.ckpt + (size_t)(cfg.offload_checkpoints ? boundary % 2 : boundary) * boundary_bytes();
+    }
+    char *host_boundary(int boundary) const { return host_ckpt + (size_t)boundary * boundary_bytes(); }
 };
 
 namespace {
@@ -276,12 +287,49 @@ void join_aux(lga_stack *st) {
     for (size_t i = 0; i < st->w16_pending.size(); ++i) wait_w16(st, (int)i);
     for (size_t i = 0; i < st->grad_pending.size(); ++i) wait_grad(st, (int)i);
 }
+// ---- checkpoint offload (appendix C, "CPU-GPU transfers") ------------------------------------------------
+// Transfers run on the second stream, ordered against the main stream by one event per device slot.
+void wait_slot(lga_stack *st, int slot) {
+    if (!st->ck_pending[slot]) return;
+    (void)hipStreamWaitEvent(st->stream, st->ev_ck[slot], 0);
+    st->ck_pending[slot] = 0;
+}
+// Boundary b, complete on the device once everything enqueued on the main stream so far has run, goes to the host.
+void save_boundary(lga_stack *st, int b) {
+    fork_aux(st);
+    (void)hipMemcpyAsync(st->host_boundary(b), st->ckpt(b), st->boundary_bytes(), hipMemcpyDeviceToHost, st->aux);
+    (void)hipEventRecord(st->ev_ck[b % 2], st->aux);
+    st->ck_pending[b % 2] = 1;
+}
+// Boundary b comes back into its slot, whose present content nothing enqueued after this call uses any more.  The
+// copy starts when the main stream reaches this point and runs beside what is enqueued next.
+void fetch_boundary(lga_stack *st, int b) {
+    if (st->dev_boundary[b % 2] == b) return;
+    fork_aux(st);
+    if (st->ck_pending[b % 2]) (void)hipStreamWaitEvent(st->aux, st->ev_ck[b % 2], 0);   // same stream: ordered anyway
+    (void)hipMemcpyAsync(st->ckpt(b), st->host_boundary(b), st->boundary_bytes(), hipMemcpyHostToDevice, st->aux);
+    (void)hipEventRecord(st->ev_ck[b % 2], st->aux);
+    st->ck_pending[b % 2] = 1;
+    st->dev_boundary[b % 2] = b;
+}
+// The main stream is about to overwrite boundary b's slot with that boundary: the slot's last transfer must be over.
+void claim_slot(lga_stack *st, int b) {
+    wait_slot(st, b % 2);
+    st->dev_boundary[b % 2] = b;
+}
+void join_offload(lga_stack *st) {
+    wait_slot(st, 0);
+    wait_slot(st, 1);
+}
+
 void release_stack(lga_stack *st) {
     if (st->aux) (void)hipStreamSynchronize(st->aux);
     for (hipEvent_t ev : st->ev_w16) if (ev) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : st->ev_grad) if (ev) (void)hipEventDestroy(ev);
     if (st->ev_fork) (void)hipEventDestroy(st->ev_fork);
+    for (hipEvent_t ev : st->ev_ck) if (ev) (void)hipEventDestroy(ev);
     if (st->aux) (void)hipStreamDestroy(st->aux);
+    if (st->host_ckpt) (void)hipHostFree(st->host_ckpt);
     if (st->arena) (void)hipFree(st->arena);
     delete st;
 }
@@ -498,18 +546,26 @@ int finish(const char *what) {
 template <class T> int forward_layered_t(lga_stack *st, const void *x, void *y) {
     const lga_config &c = st->cfg;
     const size_t act_bytes = st->T * c.d_model * sizeof(T);
+    const bool offload = c.offload_checkpoints != 0;
+    if (offload) claim_slot(st, 0);
     LGA_HIP(hipMemcpyAsync(st->ckpt(0), x, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    if (offload) save_boundary(st, 0);
     const int groups = c.n_micro / c.group;
     const size_t gstride = st->t * c.d_model;
     for (int l = 0; l < c.n_layers; ++l) {                 // layers outside ...
+        // offload mode: boundary l + 1 takes the slot of boundary l - 1, which is on its way to the host since the
+        // end of layer l - 2's sweep; its own copy to the host then runs beside layer l + 1's sweep
+        if (offload) claim_slot(st, l + 1);
         const T *in = reinterpret_cast<const T *>(st->ckpt(l));
         T *out = reinterpret_cast<T *>(st->ckpt(l + 1));
         ensure_weights(st, l);
         prefetch_weights(st, l + 1, l);
         for (int gi = 0; gi < groups; ++gi)                 // ... micro-batches inside
             layer_forward<T>(st, l, in + gi * gstride, out + gi * gstride);
+        if (offload) save_boundary(st, l + 1);
     }
     if (y) LGA_HIP(hipMemcpyAsync(y, st->ckpt(c.n_layers), act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    if (offload) join_offload(st);
     return finish("lga_forward_layered");
 }
 
@@ -521,6 +577,13 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
     const int groups = c.n_micro / c.group;
     const size_t gstride = st->t * c.d_model;
     for (int l = c.n_layers - 1; l >= 0; --l) {
+        if (c.offload_checkpoints) {
+            // the layer's input comes back from the host (the top layer's is still there after a forward sweep); the
+            // next layer's is requested now and travels beside this layer's sweep, into the slot of boundary l + 1
+            fetch_boundary(st, l);
+            wait_slot(st, l % 2);
+            if (l > 0) fetch_boundary(st, l - 1);
+        }
         const T *in = reinterpret_cast<const T *>(st->ckpt(l));
         float *gbuf = st->grad(l);
         st->grad_owner[st->grad_slot(l)] = -1;
@@ -538,6 +601,7 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
         if (fused) adam_layer(st, l, *fused, (c.overlap & LGA_OVERLAP_ADAM) != 0);
     }
     if (c.overlap) join_aux(st);                            // later work on the main stream sees every update
+    if (c.offload_checkpoints) join_offload(st);
     if (dx) LGA_HIP(hipMemcpyAsync(dx, dact, act_bytes, hipMemcpyDeviceToDevice, st->stream));
     if (fused) st->set_forward(false);                      // checkpoints no longer match the weights
     return finish("lga_backward_layered");
@@ -548,14 +612,30 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
 template <class T> int forward_layer_t(lga_stack *st, int l, const void *x_in, void *x_out) {
     const lga_config &c = st->cfg;
     const size_t act_bytes = st->T * c.d_model * sizeof(T);
-    if (x_in != st->ckpt(l))
+    const bool offload = c.offload_checkpoints != 0;
+    if (offload) {
+        if (x_in == st->host_boundary(l)) {                 // the borrowed checkpoint itself: bring it back if it is away
+            fetch_boundary(st, l);
+            wait_slot(st, l % 2);
+        } else {
+            claim_slot(st, l);
+            LGA_HIP(hipMemcpyAsync(st->ckpt(l), x_in, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+            save_boundary(st, l);
+        }
+        if (!x_out) claim_slot(st, l + 1);
+    } else if (x_in != st->ckpt(l)) {
         LGA_HIP(hipMemcpyAsync(st->ckpt(l), x_in, act_bytes, hipMemcpyDeviceToDevice, st->stream));
+    }
     const T *in = reinterpret_cast<const T *>(st->ckpt(l));
     T *out = reinterpret_cast<T *>(x_out ? x_out : st->ckpt(l + 1));
     const int groups = c.n_micro / c.group;
     const size_t gstride = st->t * c.d_model;
     ensure_weights(st, l);
     for (int gi = 0; gi < groups; ++gi) layer_forward<T>(st, l, in + gi * gstride, out + gi * gstride);
+    if (offload) {
+        if (!x_out) save_boundary(st, l + 1);
+        join_offload(st);
+    }
     return finish("lga_forward_layer");
 }
 
@@ -566,6 +646,10 @@ template <class T> int backward_layer_t(lga_stack *st, int l, const void *dy, vo
     LGA_HIP(hipMemcpyAsync(dact, dy, act_bytes, hipMemcpyDeviceToDevice, st->stream));
     const int groups = c.n_micro / c.group;
     const size_t gstride = st->t * c.d_model;
+    if (c.offload_checkpoints) {
+        fetch_boundary(st, l);
+        wait_slot(st, l % 2);
+    }
     const T *in = reinterpret_cast<const T *>(st->ckpt(l));
     st->grad_owner[st->grad_slot(l)] = -1;
     if (c.overlap) wait_grad(st, st->grad_slot(l));
@@ -644,6 +728,15 @@ int lga_arena_bytes(const lga_config *cfg, uint64_t *bytes) {
     if (!bytes) return fail(LGA_ERR_ARG, "NULL argument");
     if (int rc = validate_config(cfg)) return rc;
     *bytes = make_plan(*cfg).total;
+    return LGA_OK;
+}
+
+int lga_host_bytes(const lga_config *cfg, uint64_t *bytes) {
+    if (!bytes) return fail(LGA_ERR_ARG, "NULL argument");
+    if (int rc = validate_config(cfg)) return rc;
+    const uint64_t boundary = (uint64_t)cfg->n_micro * cfg->micro_batch * cfg->seq_len * cfg->d_model *
+                              (cfg->dtype == LGA_BF16 ? 2 : 4);
+    *bytes = cfg->offload_checkpoints ? (uint64_t)(cfg->n_layers + 1) * boundary : 0;
     return LGA_OK;
 }
 
@@ -731,6 +824,12 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
     st->ngrad = cfg->retain_grads ? cfg->n_layers : (cfg->overlap & LGA_OVERLAP_ADAM) ? std::min(2, cfg->n_layers) : 1;
     st->aux = nullptr;
     st->ev_fork = nullptr;
+    st->host_ckpt = nullptr;
+    for (int i = 0; i < 2; ++i) {
+        st->dev_boundary[i] = -1;
+        st->ev_ck[i] = nullptr;
+        st->ck_pending[i] = 0;
+    }
     st->nbuf = cfg->param_buffers ? cfg->param_buffers : cfg->n_layers;
     st->grad_owner.assign(st->ngrad, -1);
     st->w16_owner.assign(st->nbuf, -1);
@@ -750,10 +849,24 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
         release_stack(st);
         return fail(LGA_ERR_HIP, msg);
     };
-    if (cfg->overlap) {
-        // second stream (default priority) and the events that order it against the main stream
+    if (cfg->overlap || cfg->offload_checkpoints) {
+        // second stream (default priority) and the event that orders it behind the main stream
         if ((e = hipStreamCreateWithFlags(&st->aux, hipStreamNonBlocking)) != hipSuccess) return bail(e, "create stream");
         if ((e = hipEventCreateWithFlags(&st->ev_fork, hipEventDisableTiming)) != hipSuccess) return bail(e, "create event");
+    }
+    if (cfg->offload_checkpoints) {
+        // pinned (allocated as such, not registered afterwards) so that the copies run asynchronously
+        const size_t bytes = (size_t)(cfg->n_layers + 1) * st->boundary_bytes();
+        if ((e = hipHostMalloc(reinterpret_cast<void **>(&st->host_ckpt), bytes, hipHostMallocDefault)) != hipSuccess) {
+            std::string msg = std::string("hipHostMalloc of ") + std::to_string(bytes) + " bytes: " + hipGetErrorString(e);
+            release_stack(st);
+            (void)hipGetLastError();
+            return fail(LGA_ERR_OOM, msg);
+        }
+        for (auto &ev : st->ev_ck)
+            if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "create event");
+    }
+    if (cfg->overlap) {
         st->ev_w16.assign(st->nbuf, nullptr);
         st->ev_grad.assign(st->ngrad, nullptr);
         for (auto &ev : st->ev_w16)
@@ -843,6 +956,9 @@ int lga_step_mbmajor(lga_stack *st, const void *x, const void *dy, void *y, void
     if (!st || !x || !dy) return fail(LGA_ERR_ARG, "NULL argument");
     if (!st->cfg.retain_grads) return fail(LGA_ERR_STATE, "micro-batch-major order needs retain_grads = 1");
     if (st->cfg.group != 1) return fail(LGA_ERR_STATE, "micro-batch-major order needs group = 1");
+    if (st->cfg.offload_checkpoints)
+        return fail(LGA_ERR_STATE, "the micro-batch-major order keeps every boundary on the device: not available with "
+                                   "offload_checkpoints");
     if (adam)
         if (int rc = check_adam(adam)) return rc;
     return st->cfg.dtype == LGA_BF16 ? step_mbmajor_t<bf16>(st, x, dy, y, dx, adam)
@@ -889,8 +1005,8 @@ int lga_moments(lga_stack *st, int32_t layer, float **dev_m, float **dev_v, size
 int lga_checkpoint(lga_stack *st, int32_t boundary, const void **dev_ptr, size_t *bytes) {
     if (!st || !dev_ptr) return fail(LGA_ERR_ARG, "NULL argument");
     if (boundary < 0 || boundary > st->cfg.n_layers) return fail(LGA_ERR_ARG, "boundary index out of range");
-    *dev_ptr = st->ckpt(boundary);
-    if (bytes) *bytes = st->T * st->cfg.d_model * st->esz();
+    *dev_ptr = st->cfg.offload_checkpoints ? st->host_boundary(boundary) : st->ckpt(boundary);
+    if (bytes) *bytes = st->boundary_bytes();
     return LGA_OK;
 }
 

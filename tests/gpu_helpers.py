@@ -61,12 +61,13 @@ def oracle_adam(a: B.lga_adam) -> O.AdamHyper:
 
 
 def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layered", adam=None, fused=True,
-                 want_ckpt=True, wgrad_groups=0, param_buffers=0, overlap=0, attention=0):
+                 want_ckpt=True, wgrad_groups=0, param_buffers=0, overlap=0, attention=0,
+                 offload=0, steps=1):
     """One training step through the C ABI.  Returns a dict of float64 numpy results."""
     dt = dtype_code(w)
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
                         group=group, retain_grads=retain, wgrad_groups=wgrad_groups, param_buffers=param_buffers,
-                        overlap=overlap, attention=attention)
+                        overlap=overlap, attention=attention, offload_checkpoints=offload)
     st = B.Stack(cfg, np.concatenate(params))
     P = B.params_per_layer(cfg)
     xd, Gd = to_dev(x, dt), to_dev(G, dt)
@@ -74,6 +75,12 @@ def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layer
     out = {"grads": [None] * w.n_layers}
     np_dt = "float32"
     try:
+        for extra in range(steps - 1):                    # earlier steps of a multi-step run (fused Adam, layered order)
+            st.forward_layered(xd.data_ptr(), yd.data_ptr())
+            st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), B.lga_adam(adam.lr, adam.beta1, adam.beta2, adam.eps,
+                                                                          adam.step + extra))
+        if steps > 1:
+            adam = B.lga_adam(adam.lr, adam.beta1, adam.beta2, adam.eps, adam.step + steps - 1)
         if order == "layered":
             st.forward_layered(xd.data_ptr(), yd.data_ptr())
             st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam if (adam is not None and fused) else None)

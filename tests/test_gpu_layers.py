@@ -28,15 +28,16 @@ def _read_layer_state(st, l):
     return [B.read_device(p, n).copy() for p in (ptr, mp, vp)]
 
 
-@pytest.mark.parametrize("dtype,via_checkpoints", [("fp32", False), ("bf16", False), ("bf16", True)])
-def test_per_layer_calls_chain_to_the_sweeps(dtype, via_checkpoints):
+@pytest.mark.parametrize("dtype,via_checkpoints,offload", [("fp32", False, 0), ("bf16", False, 0), ("bf16", True, 0),
+                                                           ("bf16", False, 1), ("bf16", True, 1)])
+def test_per_layer_calls_chain_to_the_sweeps(dtype, via_checkpoints, offload):
     w = S.Workload("chain", 3, 128, 4, 512, 80, 1, 4, dtype)
     x, G, params = S.make_inputs(w, seed=31)
     adam = adam_struct()
     base = run_gpu_step(w, x, G, params, group=2, retain=0, adam=adam)
     dt = dtype_code(w)
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt, group=2,
-                        retain_grads=0)
+                        retain_grads=0, offload_checkpoints=offload)
     st = B.Stack(cfg, np.concatenate(params))
     try:
         cur, nxt = to_dev(x, dt), empty_dev(x.shape, dt)

@@ -241,6 +241,37 @@ def test_overlap_mode_changes_timing_not_results(retain, param_buffers, overlap)
         assert np.array_equal(mb["params"][l], mb0["params"][l])
 
 
+@pytest.mark.parametrize("layers,group,overlap,dtype", [(4, 2, 0, "bf16"), (3, 1, 3, "bf16"), (1, 4, 0, "bf16"), (5, 2, 0, "fp32")])
+def test_checkpoint_offload_changes_placement_not_results(layers, group, overlap, dtype):
+    """Boundary activations in pinned host memory, two slots on the device (appendix C, "CPU-GPU transfers"): every
+    output - including every boundary, now read back from the host - is bit-identical to the resident run, over two
+    consecutive steps on one stack (the slots carry state from the backward pass into the next forward pass), and
+    the device arena shrinks by the boundaries that moved out."""
+    w = S.Workload("offload", layers, 64, 2, 256, 72, 1, 4, dtype)
+    x, G, params = S.make_inputs(w, seed=19)
+    adam = adam_struct()
+    kw = dict(group=group, retain=0, adam=adam, overlap=overlap, steps=2)
+    base = run_gpu_step(w, x, G, params, **kw)
+    got = run_gpu_step(w, x, G, params, offload=1, **kw)
+    for key in ("y", "dx", "boundaries"):
+        assert np.array_equal(base[key], got[key]), key
+    for l in range(layers):
+        for key in ("params", "m", "v"):
+            assert np.array_equal(base[key][l], got[key][l]), (key, l)
+    assert np.array_equal(base["grads"][0], got["grads"][0])
+    dt = B.LGA_BF16 if dtype == "bf16" else B.LGA_FP32
+    mk = lambda off: B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt,
+                                   group=group, overlap=overlap, offload_checkpoints=off)
+    boundary = w.tokens * w.d_model * (2 if dtype == "bf16" else 4)
+    assert B.host_bytes(mk(0)) == 0 and B.host_bytes(mk(1)) == (layers + 1) * boundary
+    saved = B.arena_bytes(mk(0)) - B.arena_bytes(mk(1))
+    assert (layers - 1) * boundary <= saved <= (layers - 1) * (boundary + 256)
+    if layers == 4:
+        with pytest.raises(B.LgaError) as e:
+            run_gpu_step(w, x, G, params, group=1, retain=1, order="mbmajor", adam=adam, offload=1)
+        assert e.value.code == B.LGA_ERR_STATE
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
