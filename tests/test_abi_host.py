@@ -48,7 +48,7 @@ def test_parameter_count_follows_table_b1_closed_form():
     (dict(group=0), B.LGA_ERR_SHAPE), (dict(group=8), B.LGA_ERR_SHAPE), (dict(dtype=7), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=48, d_ff=192), B.LGA_ERR_SHAPE),    # d_h = 12 is not a multiple of 8
     (dict(dtype=B.LGA_BF16, seq_len=8192), B.LGA_ERR_SHAPE),           # d_h = 16 has no MFMA kernel: sequence limit
-    (dict(attention=2), B.LGA_ERR_ARG),
+    (dict(attention=2), B.LGA_ERR_ARG), (dict(offload_checkpoints=2), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=128, n_heads=4, d_ff=500), B.LGA_ERR_SHAPE),
     (dict(seq_len=0), B.LGA_ERR_SHAPE),
 ])
@@ -166,6 +166,26 @@ def test_flop_model_against_the_papers_count():
     attn = 11.0 * (4 * 2) * 3 * 64 * 64 * 1024
     assert abs(flops - (gemm + attn)) / flops < 1e-12
     assert abs(gemm / (8.0 * tokens * 3 * Pm) - (1 - 1 / 12)) < 1e-12
+
+
+def test_flop_model_doubles_the_attention_products_without_the_causal_mask():
+    kw = dict(n_layers=3, d_model=1024, n_heads=8, d_ff=4096, seq_len=64, micro_batch=2, n_micro=4, dtype=B.LGA_BF16)
+    _, _, causal = B.traffic_model(cfg(**kw), B.LGA_ORDER_LAYERED)
+    _, _, full = B.traffic_model(cfg(attention=B.LGA_ATTN_FULL, **kw), B.LGA_ORDER_LAYERED)
+    assert abs((full - causal) - 11.0 * (4 * 2) * 3 * 64 * 64 * 1024) / full < 1e-12
+
+
+def test_checkpoint_offload_moves_the_boundaries_to_pinned_host_memory():
+    kw = dict(n_layers=4, d_model=12288, n_heads=96, d_ff=49152, seq_len=2048, micro_batch=1, n_micro=32,
+              dtype=B.LGA_BF16, group=4)
+    boundary = 32 * 2048 * 12288 * 2
+    assert B.host_bytes(cfg(**kw)) == 0
+    assert B.host_bytes(cfg(offload_checkpoints=1, **kw)) == 5 * boundary
+    # the device keeps two slots instead of L + 1 boundaries
+    assert abs((B.arena_bytes(cfg(**kw)) - B.arena_bytes(cfg(offload_checkpoints=1, **kw))) - 3 * boundary) < 4096
+    one = dict(kw, n_layers=1)
+    assert B.arena_bytes(cfg(**one)) == B.arena_bytes(cfg(offload_checkpoints=1, **one))
+    assert B.lib.lga_host_bytes(C.byref(cfg(**kw)), None) == B.LGA_ERR_ARG
 
 
 def test_init_without_a_gpu_reports_a_hip_error_instead_of_crashing():
