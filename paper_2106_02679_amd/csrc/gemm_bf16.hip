@@ -184,6 +184,46 @@ __device__ __forceinline__ void epilogue4(const GemmParams<bf16> &p, int m, int 
     }
 }
 
+// The same for 8 consecutive n of one row, with 16-byte accesses (bf16 outputs only): n, ldc multiples of 8 and
+// 16-byte aligned tensors.
+template <int EPI>
+__device__ __forceinline__ void epilogue8(const GemmParams<bf16> &p, int m, int n, const f32x4 &lo, const f32x4 &hi) {
+    static_assert(EPI != EPI_ACCUM_F32, "bf16 outputs only");
+    const size_t idx = (size_t)m * p.ldc + n;
+    float r[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
+        const f32x4 b0 = *reinterpret_cast<const f32x4 *>(p.bias + n), b1 = *reinterpret_cast<const f32x4 *>(p.bias + n + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            r[i] += b0[i];
+            r[4 + i] += b1[i];
+        }
+    }
+    if constexpr (EPI == EPI_BIAS_RESID) {
+        const bf16x8 x = *reinterpret_cast<const bf16x8 *>(p.aux + idx);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] += (float)x[i];
+    }
+    if constexpr (EPI == EPI_MUL_DGELU) {
+        const bf16x8 u = *reinterpret_cast<const bf16x8 *>(p.aux + idx);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] *= gelu_grad_f((float)u[i]);
+    }
+    if constexpr (EPI == EPI_BIAS_GELU) {
+        bf16x8 u;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            u[i] = (bf16)r[i];
+            r[i] = gelu_f(r[i]);
+        }
+        *reinterpret_cast<bf16x8 *>(p.out2 + idx) = u;
+    }
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (bf16)r[i];
+    *reinterpret_cast<bf16x8 *>(p.out + idx) = o;
+}
+
 template <int BM, int BN, bool A_KM, bool B_KM, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int tiles_m, int tiles_n) {
     constexpr int WM = BM / 2, WN = BN / 2;     // wavefront tile
@@ -587,6 +627,44 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     for (; kt + 2 < nk_full; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::true_type{});      // straight-line main loop
     for (; kt < nk; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::false_type{});              // the last tiles, with tests
 
+    if constexpr (EPI != EPI_ACCUM_F32) {
+        // bf16 outputs: a lane holds 4 consecutive n of 16 different (row, column group) places, so storing from
+        // the accumulators writes 16-byte runs per row and instruction - partial cache lines that reach memory in
+        // pieces (measured: up to 2.3 x the output bytes) and scattered reads of the residual / pre-activation.
+        // Instead each wavefront passes its results, 32 rows at a time, through a private piece of the (now idle)
+        // operand ring and stores whole rows: 16 lanes x 16 bytes = 256 contiguous bytes, 4 rows per instruction.
+        const auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
+        const bool wide = ((p.N | p.ldc) & 7) == 0 && al16(p.out) && (EPI != EPI_BIAS_GELU || al16(p.out2)) &&
+                          ((EPI != EPI_BIAS_RESID && EPI != EPI_MUL_DGELU) || al16(p.aux)) &&
+                          ((EPI != EPI_BIAS && EPI != EPI_BIAS_RESID && EPI != EPI_BIAS_GELU) || al16(p.bias));
+        if (wide) {
+            constexpr int SP = WN + 4;                                  // staging pitch in floats
+            static_assert(4 * 32 * SP * 4 <= 5 * BM * BK * 2, "staging fits in the operand ring");
+            __syncthreads();                                            // every wavefront has left the main loop
+            float *stage = reinterpret_cast<float *>(smem_raw) + wave * (32 * SP);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                        *reinterpret_cast<f32x4 *>(stage + lrow * SP + j * 32 + 8 * q + 4 * lhalf) = v;
+                    }
+                asm volatile("" ::: "memory");                          // LDS operations of one wavefront execute in order
+#pragma unroll
+                for (int it = 0; it < 8; ++it) {
+                    const int row = it * 4 + (lane >> 4), c8 = lane & 15;
+                    const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + 8 * c8;
+                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8);
+                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8 + 4);
+                    if (m < p.M && n < p.N) epilogue8<EPI>(p, m, n, lo, hi);
+                }
+                asm volatile("" ::: "memory");
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int m = m0 + wm * WM + i * 32 + lrow;
