@@ -41,6 +41,17 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
                 const void *A, int32_t lda, const void *B, int32_t ldb, void *out, void *out2, float *outf,
                 int32_t ldc, const float *bias, const void *aux, float beta, void *stream);
 
+/* The weight-gradient GEMM as the layer stack runs it (section 3: one accumulation per layer over all micro-batches'
+ * tokens): outf[M,N] = beta * outf + sum_k A[m][k] B[n][k], bf16 operands with k contiguous ([M][lda], [N][ldb]), fp32
+ * result.  When the output has too few 256 x 256 tiles to occupy the chip (narrow layers) and `scratch` (device, at
+ * least lga_op_gemm_splitk_slices(M, N, K) * M * N floats, 16-byte aligned) is given, the k range is cut into that many
+ * slices that run as separate workgroups and are then summed in slice order (deterministic); otherwise, or with
+ * scratch == NULL, it is lga_op_gemm with LGA_EPI_ACCUM_F32.  Alignment rules as for lga_op_gemm. */
+int lga_op_gemm_splitk(int32_t M, int32_t N, int32_t K, const void *A, int32_t lda, const void *B, int32_t ldb,
+                       float *outf, int32_t ldc, float beta, float *scratch, uint64_t scratch_floats, void *stream);
+/* Number of k slices lga_op_gemm_splitk would use (1 = no split); K = 0: the most any K would give. */
+int32_t lga_op_gemm_splitk_slices(int32_t M, int32_t N, int32_t K);
+
 /* LayerNorm over rows of length d (biased variance, eps inside the root): y = (x-mean)*rstd*g + b.
  * mean, rstd: [rows] float, written. */
 int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const float *b, void *y, float *mean,

@@ -89,6 +89,8 @@ SIGNATURES = {
     "lga_profile_end": (C.c_int, [_vp, _P(lga_kernel_stat), _i32, _P(_i32)]),
     "lga_op_gemm": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _i32,
                               _vp, _vp, _f32, _vp]),
+    "lga_op_gemm_splitk": (C.c_int, [_i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _i32, _f32, _vp, _u64, _vp]),
+    "lga_op_gemm_splitk_slices": (_i32, [_i32, _i32, _i32]),
     "lga_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "lga_op_layernorm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _i32,
                                        _vp]),

@@ -92,6 +92,12 @@ template <class T> struct GemmParams {
     const float *bias;
     const T *aux;    // leading dimension ldc
     float beta;
+    // EPI_ACCUM_F32 with few output tiles: scratch for partial results of slices of the k range (see
+    // gemm_splitk_slices); NULL or too small = never split.
+    float *partial;
+    size_t partial_floats;
+    // set by the launcher when it splits: number of k slices, k elements per slice (a multiple of 64)
+    int ksplit, kchunk;
 };
 
 }  // namespace lga

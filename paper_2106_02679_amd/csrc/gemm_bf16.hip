@@ -20,6 +20,7 @@
 // 4 consecutive n of one row m (row-major stores of 8 bytes (bf16) or 16 bytes (fp32) per lane, epilogues
 // fused); workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) works on
 // a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse.
+#include <algorithm>
 #include <cstdio>
 #include <type_traits>
 
@@ -463,9 +464,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     const int ntiles = tiles_m * tiles_n;
     int tile;
     {
+        // with a split k range there are ksplit work items per tile, slice-major
+        const int nwork = (EPI == EPI_ACCUM_F32 && p.ksplit > 1) ? ntiles * p.ksplit : ntiles;
         const int pid = blockIdx.x, xcd = pid & 7, local = pid >> 3;
-        const int base = ntiles >> 3, rem = ntiles & 7;
+        const int base = nwork >> 3, rem = nwork & 7;
         tile = xcd * base + (xcd < rem ? xcd : rem) + local;
+    }
+    if constexpr (EPI == EPI_ACCUM_F32) {
+        if (p.ksplit > 1) {
+            // this workgroup multiplies slice z of the k range into partial result z ([M][N], dense)
+            const int z = tile / ntiles, k0 = z * p.kchunk;
+            tile -= z * ntiles;
+            p.A += k0;
+            p.B += k0;
+            p.K = min(p.K - k0, p.kchunk);
+            p.outf = p.partial + (size_t)z * p.M * p.N;
+            p.ldc = p.N;
+            p.beta = 0.f;
+        }
     }
     constexpr int GROUP_M = 8;
     const int group_size = GROUP_M * tiles_n;
@@ -699,20 +715,70 @@ void launch_one(const GemmParams<bf16> &p, hipStream_t s) {
     const double out_bytes = EPI == EPI_ACCUM_F32 ? (p.beta != 0.f ? 8.0 : 4.0) : (EPI == EPI_BIAS_GELU ? 4.0 : 2.0);
     const double aux_bytes = (EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU) ? 2.0 : 0.0;
     ProfScope scope(name, 2.0 * mn * p.K, 2.0 * ((double)p.M * p.K + (double)p.K * p.N) + mn * (out_bytes + aux_bytes), s);
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, s, p, tiles_m, tiles_n);
+    const int work = tiles_m * tiles_n * (p.ksplit > 1 ? p.ksplit : 1);
+    hipLaunchKernelGGL(kern, dim3(work), dim3(256), smem, s, p, tiles_m, tiles_n);
+}
+
+// out[m, n] = beta * out[m, n] + sum_z partial[z][m][n]; the slices are added in index order (deterministic).
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ partial, int slices, size_t stride,
+                                                            float *__restrict__ out, int M, int N, int ldc, float beta) {
+    const size_t quads = (size_t)M * (N / 4);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < quads; i += (size_t)gridDim.x * 256) {
+        const size_t m = i / (N / 4), n = (i % (N / 4)) * 4;
+        f32x4 acc = *reinterpret_cast<const f32x4 *>(partial + m * N + n);
+        for (int z = 1; z < slices; ++z) acc += *reinterpret_cast<const f32x4 *>(partial + z * stride + m * N + n);
+        float *o = out + m * ldc + n;
+        if (beta != 0.f) acc += beta * *reinterpret_cast<const f32x4 *>(o);
+        *reinterpret_cast<f32x4 *>(o) = acc;
+    }
 }
 
 template <bool A_KM, bool B_KM, int EPI> void launch_tiles(const GemmParams<bf16> &p, hipStream_t s) {
     // Large tiles when they fill the 256 CUs at least about once (the direct-to-LDS kernel is so much faster per
     // tile that a partly idle second round still wins); smaller ones otherwise.
     const long big = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-    if (big >= 224)
+    if constexpr (A_KM && B_KM && EPI == EPI_ACCUM_F32) {
+        // A weight-gradient GEMM of a narrow layer: few output tiles, very long k.  The k range is cut into slices
+        // that run as separate work items of the large-tile kernel and are summed afterwards.
+        const int slices = gemm_splitk_slices(p.M, p.N, p.K);
+        if (slices > 1 && p.partial && (size_t)slices * p.M * p.N <= p.partial_floats && p.N % 4 == 0 && p.ldc % 4 == 0 &&
+            (reinterpret_cast<uintptr_t>(p.outf) & 15) == 0) {
+            GemmParams<bf16> q = p;
+            q.kchunk = ((p.K + slices - 1) / slices + BK - 1) / BK * BK;
+            q.ksplit = (p.K + q.kchunk - 1) / q.kchunk;          // rounding the slice length up may have emptied the last ones
+            launch_one<256, 256, A_KM, B_KM, EPI>(q, s);
+            ProfScope scope("splitk_reduce_kernel", (double)q.ksplit * p.M * p.N,
+                            4.0 * p.M * p.N * (q.ksplit + (p.beta != 0.f ? 2.0 : 1.0)), s);
+            const size_t quads = (size_t)p.M * (p.N / 4);
+            const unsigned blocks = (unsigned)std::min<size_t>((quads + 255) / 256, 256 * 16);
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, s, p.partial, q.ksplit, (size_t)p.M * p.N,
+                               p.outf, p.M, p.N, p.ldc, p.beta);
+            return;
+        }
+    }
+    if (big >= 128)
         launch_one<256, 256, A_KM, B_KM, EPI>(p, s);
     else
         launch_one<128, 128, A_KM, B_KM, EPI>(p, s);
 }
 
 }  // namespace
+
+int gemm_splitk_slices(int M, int N, int K) {
+    const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+    if (tiles >= 224) return 1;                              // the output alone occupies the chip
+    // Work items = tiles x slices run in rounds of 256 (one per CU).  Take the fewest slices (their partial results
+    // are written and read again) whose last round is within a tenth of the best filled one.
+    long cap = 32;
+    if (K > 0) cap = std::min<long>(cap, K / 1024);          // at least 16 k tiles per slice
+    cap = std::max<long>(cap, 1);
+    auto fill = [&](long s) { return (double)(tiles * s) / (256.0 * ((tiles * s + 255) / 256)); };
+    double best = 0.0;
+    for (long s = 1; s <= cap; ++s) best = std::max(best, fill(s));
+    for (long s = 1; s <= cap; ++s)
+        if (fill(s) >= 0.9 * best) return (int)s;
+    return 1;
+}
 
 void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s) {
     if (p.M == 0 || p.N == 0) return;

@@ -48,6 +48,10 @@ void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t
 void launch_gemm_f32(const GemmParams<float> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
 // bf16 MFMA kernel, fp32 accumulate.  Needs lda, ldb, ldc, N multiples of 8 and 16-byte aligned bases.
 void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
+// Into how many slices of the k range launch_gemm_bf16 cuts an fp32-accumulating, k-contiguous GEMM whose output has
+// too few 256 x 256 tiles to occupy the chip (1 = not at all); it then needs slices * M * N floats of scratch.
+// k = 0 asks for the largest count any k would give (for sizing the scratch).
+int gemm_splitk_slices(int M, int N, int K);
 
 // ---- causal attention --------------------------------------------------------------------
 // qkv: [tokens, 3 d] with columns [Q | K | V], head h at columns h*dh inside each third; tokens =

@@ -73,6 +73,28 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
     return done("lga_op_gemm");
 }
 
+int32_t lga_op_gemm_splitk_slices(int32_t M, int32_t N, int32_t K) {
+    if (M < 1 || N < 1 || K < 0) return 1;
+    return gemm_splitk_slices(M, N, K);
+}
+
+int lga_op_gemm_splitk(int32_t M, int32_t N, int32_t K, const void *A, int32_t lda, const void *B, int32_t ldb,
+                       float *outf, int32_t ldc, float beta, float *scratch, uint64_t scratch_floats, void *stream) {
+    if (M < 0 || N < 0 || K < 0) return err(LGA_ERR_SHAPE, "negative size");
+    if (!A || !B || !outf) return err(LGA_ERR_ARG, "NULL argument");
+    if (lda < K || ldb < K || ldc < N) return err(LGA_ERR_SHAPE, "leading dimension too small");
+    if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || K % 8)
+        return err(LGA_ERR_SHAPE, "bf16 GEMM needs lda, ldb, ldc, N and K to be multiples of 8");
+    if (!a16(A) || !a16(B) || !a16(outf) || !a16(scratch)) return err(LGA_ERR_SHAPE, "bf16 GEMM needs 16-byte aligned pointers");
+    GemmParams<bf16> p{};
+    p.A = static_cast<const bf16 *>(A); p.B = static_cast<const bf16 *>(B);
+    p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.outf = outf; p.beta = beta;
+    p.partial = scratch; p.partial_floats = scratch ? scratch_floats : 0;
+    launch_gemm_bf16(p, true, true, EPI_ACCUM_F32, reinterpret_cast<hipStream_t>(stream));
+    return done("lga_op_gemm_splitk");
+}
+
 int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const float *b, void *y, float *mean,
                          float *rstd, int32_t rows, int32_t d, float eps, void *stream) {
     if (!dtype_ok(dtype)) return err(LGA_ERR_ARG, "bad dtype");

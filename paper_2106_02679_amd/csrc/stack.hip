@@ -121,6 +121,7 @@ struct Plan {
     size_t ldk;                // row pitch (elements) of the transposed operands
     size_t h, qkv, a, x1, h2, u, gl, du, dh2, dx1, da, dqkv, dh;
     size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
+    size_t splitk, splitk_floats;   // partial results of weight-gradient GEMMs whose k range is split (narrow layers)
     size_t total;
 };
 
@@ -175,6 +176,13 @@ Plan make_plan(const lga_config &c) {
         p.xT[i] = take(c.dtype == LGA_BF16 ? (size_t)wg_in[i] * p.ldk * 2 : 0);
         p.dyT[i] = take(c.dtype == LGA_BF16 ? (size_t)wg_out[i] * p.ldk * 2 : 0);
     }
+    p.splitk_floats = 0;
+    if (c.dtype == LGA_BF16)
+        for (int i = 0; i < 4; ++i) {
+            const size_t slices = (size_t)gemm_splitk_slices(wg_in[i], wg_out[i], 0);
+            if (slices > 1) p.splitk_floats = std::max(p.splitk_floats, slices * wg_in[i] * wg_out[i]);
+        }
+    p.splitk = take(p.splitk_floats * 4);
     p.mean1 = take(t * 4);
     p.rstd1 = take(t * 4);
     p.mean2 = take(t * 4);
@@ -473,6 +481,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
             if (gs.flush) {
                 g.K = (gs.slot + 1) * t; g.beta = gs.beta_mat;
                 g.A = xT; g.lda = ldk; g.B = dyT; g.ldb = ldk;
+                g.partial = st->at<float>(st->plan.splitk); g.partial_floats = st->plan.splitk_floats;
                 gemm<T>(g, true, true, EPI_ACCUM_F32, s);
             }
         }

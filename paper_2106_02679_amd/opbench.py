@@ -61,12 +61,20 @@ def run_gemm(args):
         aux = torch.randn(M, N, device="cuda", dtype=bf) if epi in (2, 4) else None
         ptr = lambda x: x.data_ptr() if x is not None else None
 
+        slices = B.lib.lga_op_gemm_splitk_slices(M, N, K) if epi == 5 else 1
+        scratch = torch.empty(slices * M * N, device="cuda") if slices > 1 else None
+
         def call():
-            B.check(B.lib.lga_op_gemm(B.LGA_BF16, 1, 1, epi, M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, ptr(out), ptr(out2),
-                                      ptr(outf), N, bias.data_ptr(), ptr(aux), 0.0, None))
+            if epi == 5:      # the weight-gradient GEMM as the stack runs it (k range split when the output is small)
+                B.check(B.lib.lga_op_gemm_splitk(M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, outf.data_ptr(), N, 0.0,
+                                                 ptr(scratch), slices * M * N, None))
+            else:
+                B.check(B.lib.lga_op_gemm(B.LGA_BF16, 1, 1, epi, M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, ptr(out),
+                                          ptr(out2), ptr(outf), N, bias.data_ptr(), ptr(aux), 0.0, None))
         ms = _time(call, args.iters)
-        print(f"{name:<28} M={M:<6} N={N:<6} K={K:<6} {ms:9.3f} ms {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s", flush=True)
-        del A, Bm, out, out2, outf, aux
+        print(f"{name:<28} M={M:<6} N={N:<6} K={K:<6} {ms:9.3f} ms {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s"
+              + (f"  ({slices} k slices)" if slices > 1 else ""), flush=True)
+        del A, Bm, out, out2, outf, aux, scratch
         torch.cuda.empty_cache()
 
 

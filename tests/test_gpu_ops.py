@@ -121,6 +121,49 @@ def test_gemm_against_oracle_matmul(case):
         assert np.all(to_host(out)[:, N:] == 0)                                # padding untouched
 
 
+@pytest.mark.parametrize("M,N,K,beta", [(768, 768, 8192, 1.0), (320, 264, 5000, 0.0), (1032, 520, 40000, 1.0),
+                                        (256, 256, 1024 * 32 + 8, 0.0), (768, 2304, 1000, 1.0)])
+def test_weight_gradient_gemm_with_split_k_range(M, N, K, beta):
+    """Narrow outputs with a long contraction (the weight-gradient GEMMs of narrow layers): the k range is cut into
+    slices that run as separate workgroups.  Against the fp64 product, against the unsplit kernel, twice (the
+    scratch keeps the previous call's partial results), and bit-reproducibly; the last case is too short to split."""
+    rng = np.random.default_rng(M + N + K)
+    lda, ldb, ldc = K + 8, K + 16, N + 8
+    A, Bm = rnd(rng, (M, lda), BF16), rnd(rng, (N, ldb), BF16)
+    acc = A[:, :K].astype(np.float64) @ Bm[:, :K].astype(np.float64).T
+    old = rng.standard_normal((M, ldc)).astype(np.float32)
+    slices = B.lib.lga_op_gemm_splitk_slices(M, N, K)
+    assert (slices > 1) == (K >= 2048)
+    assert slices <= B.lib.lga_op_gemm_splitk_slices(M, N, 0)
+    Ad, Bd = to_dev(A, BF16), to_dev(Bm, BF16)
+    scratch = torch.full((slices * M * N,), float("nan"), device="cuda")
+    ref = beta * old[:, :N].astype(np.float64) + acc
+    results = []
+    for attempt in range(2):
+        outf = fvec(old)
+        B.check(B.lib.lga_op_gemm_splitk(M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta,
+                                         scratch.data_ptr(), scratch.numel(), None))
+        torch.cuda.synchronize()
+        got = outf.cpu().numpy()
+        assert rel_err(got[:, :N], ref) < 1e-5
+        assert np.array_equal(got[:, N:], old[:, N:])                          # padding untouched
+        results.append(got)
+    assert np.array_equal(results[0], results[1])
+    outf = fvec(old)
+    B.check(B.lib.lga_op_gemm_splitk(M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta, None, 0,
+                                     None))                                    # no scratch: the unsplit kernel
+    torch.cuda.synchronize()
+    assert rel_err(outf.cpu().numpy()[:, :N], results[0][:, :N]) < 1e-5
+    # scratch too small for the slices: falls back to the unsplit kernel instead of overrunning it
+    if slices > 1:
+        small = torch.zeros(M * N, device="cuda")
+        outf = fvec(old)
+        B.check(B.lib.lga_op_gemm_splitk(M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta,
+                                         small.data_ptr(), small.numel(), None))
+        torch.cuda.synchronize()
+        assert rel_err(outf.cpu().numpy()[:, :N], ref) < 1e-5
+
+
 @pytest.mark.parametrize("R,C,pad", [(8, 8, 0), (136, 264, 8), (1000, 128, 0), (128, 3000, 16)])
 def test_transpose(R, C, pad):
     rng = np.random.default_rng(R * C)
