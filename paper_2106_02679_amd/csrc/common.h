@@ -53,21 +53,21 @@ __device__ __forceinline__ float block_sum(float v, float *scratch) {
 constexpr float kGeluC = 0.7978845608028654f;
 constexpr float kGeluA = 0.044715f;
 
-__device__ __forceinline__ float tanh_fast(float z) {
-    // tanh(z) = 1 - 2 / (exp(2z) + 1); saturates correctly for large |z|
-    // v_exp_f32 and v_rcp_f32 (1 ulp each) instead of the full-precision exp and division
-    const float e = __builtin_amdgcn_exp2f(z * 2.8853900817779268f);      // exp(2 z) = 2^(2 z log2 e)
-    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+// Written with the logistic function: 0.5 (1 + tanh z) = 1 / (1 + exp(-2 z)) =: s, so
+//   gelu(u) = u s,   gelu'(u) = s + u s (1 - s) 2 z'(u),   z'(u) = c (1 + 3 a u^2).
+// v_exp_f32 and v_rcp_f32 (1 ulp each) instead of the full-precision exp and division; exp overflows to +inf for
+// very negative z, whose reciprocal is the correct limit 0.
+__device__ __forceinline__ float gelu_logistic(float u, float u2) {
+    constexpr float k = -2.0f * kGeluC * 1.4426950408889634f;            // exp(-2 z) = 2^(k u (1 + a u^2))
+    const float e = __builtin_amdgcn_exp2f((k * u) * fmaf(kGeluA, u2, 1.0f));
+    return __builtin_amdgcn_rcpf(e + 1.0f);
 }
-__device__ __forceinline__ float gelu_f(float u) {
-    const float z = kGeluC * (u + kGeluA * u * u * u);
-    return 0.5f * u * (1.0f + tanh_fast(z));
-}
+__device__ __forceinline__ float gelu_f(float u) { return u * gelu_logistic(u, u * u); }
 __device__ __forceinline__ float gelu_grad_f(float u) {
-    const float z = kGeluC * (u + kGeluA * u * u * u);
-    const float th = tanh_fast(z);
-    const float dz = kGeluC * (1.0f + 3.0f * kGeluA * u * u);
-    return 0.5f * (1.0f + th) + 0.5f * u * (1.0f - th * th) * dz;
+    const float u2 = u * u;
+    const float s = gelu_logistic(u, u2);
+    const float dz2 = fmaf(6.0f * kGeluA * kGeluC, u2, 2.0f * kGeluC);   // 2 z'(u)
+    return fmaf(u * fmaf(-s, s, s), dz2, s);
 }
 
 // ---- GEMM epilogues ----------------------------------------------------------------------
