@@ -168,6 +168,15 @@ def main():
         roof = {"bound": "mfma" if dt == B.LGA_BF16 else "alu", "achieved": dom["flops"] / dom["ms"] / 1e9,
                 "peak": peak, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    if roof["bound"] == "mfma":
+        # calibration, measured live: what the chip sustains with nothing but MFMAs on register operands with random
+        # mantissas and signs (its power management holds the clock below nominal on such data)
+        import ctypes as C
+        sink = torch.empty(65536, device="cuda")
+        tf = C.c_double()
+        B.check(B.lib.lga_op_mfma_rate(800000, 0, sink.data_ptr(), C.byref(tf), None))
+        roof["mfma_only_rate_random_operands"] = tf.value
+        roof["frac_of_mfma_only_rate"] = roof["achieved"] / tf.value
     roof["traffic"] = measured_traffic(w.name, dom["name"]) if (group == default_group and causal) else None
     roof["algorithmic_bytes_per_launch"] = dom["bytes"] / dom["launches"]
     roof["kernel"] = dom["name"]

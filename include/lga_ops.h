@@ -94,6 +94,13 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
 int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_t n, const lga_adam *adam,
                 void *stream);
 
+/* Calibration for the benchmark tools: the bf16 MFMA rate (TFLOP/s, executed) that the GPU sustains on register
+ * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 16 v_mfma_f32_32x32x16_bf16 back to
+ * back, no memory traffic.  constant_operands != 0: all operand values 1.0 (approaches the nominal peak);
+ * 0: values around +-1 with random mantissas and signs (what the power management allows on realistic data).
+ * sink: device, >= 65536 floats, overwritten.  Synchronous: returns after the kernel has run.  tflops: host. */
+int lga_op_mfma_rate(int32_t iters, int32_t constant_operands, float *sink, double *tflops, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -91,6 +91,7 @@ SIGNATURES = {
                               _vp, _vp, _f32, _vp]),
     "lga_op_gemm_splitk": (C.c_int, [_i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _i32, _f32, _vp, _u64, _vp]),
     "lga_op_gemm_splitk_slices": (_i32, [_i32, _i32, _i32]),
+    "lga_op_mfma_rate": (C.c_int, [_i32, _i32, _vp, _P(C.c_double), _vp]),
     "lga_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "lga_op_layernorm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _i32,
                                        _vp]),

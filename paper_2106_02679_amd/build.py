@@ -18,7 +18,7 @@ OUT_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblga.so")
 
 SOURCES = ["rowops.hip", "gemm_f32.hip", "gemm_bf16.hip", "attention_simple.hip", "attention_bf16.hip",
-           "stack.hip", "ops_api.hip"]
+           "stack.hip", "ops_api.hip", "mfma_rate.hip"]
 
 # -packed-fp32-ops is switched off for the device pass; the host pass warns that it does not know the feature.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

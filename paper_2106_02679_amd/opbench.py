@@ -2,6 +2,7 @@
 
     python -m paper_2106_02679_amd.opbench gemm      [--config 3] [--group 4] [--only NAME] [--iters 8]
     python -m paper_2106_02679_amd.opbench attention [--config 3] [--group 4] [--only fwd|bwd] [--iters 8] [--full]
+    python -m paper_2106_02679_amd.opbench mfma      (the MFMA rate the chip sustains on register operands alone)
 
 Every call goes through the C ABI's one-entry-point-per-kernel functions (lga_op_gemm, lga_op_attention_*),
 on synthetic N(0, 1) activations and N(0, 0.02^2) weights of the benchmark configuration's shapes.  Times are
@@ -111,9 +112,22 @@ def run_attention(args):
               f"({'causal' if causal else 'unmasked'}, executed flops)", flush=True)
 
 
+def run_mfma(args):
+    import ctypes as C
+    import torch
+    from paper_2106_02679_amd import binding as B
+    sink = torch.empty(65536, device="cuda")
+    for constant in (1, 0):
+        for iters in (400000, 4000000):
+            tf = C.c_double()
+            B.check(B.lib.lga_op_mfma_rate(iters, constant, sink.data_ptr(), C.byref(tf), None))
+            print(f"register-only v_mfma_f32_32x32x16_bf16, {'constant' if constant else 'random  '} operands, "
+                  f"{iters * 16} MFMAs per wavefront: {tf.value:8.1f} TFLOP/s", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["gemm", "attention"])
+    ap.add_argument("what", choices=["gemm", "attention", "mfma"])
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--group", type=int, default=4)
     ap.add_argument("--wgrad-groups", type=int, default=0, help="groups merged into one weight-gradient GEMM (0: all)")
@@ -123,7 +137,7 @@ def main():
     args = ap.parse_args()
     import torch
     assert torch.cuda.is_available(), "opbench needs a GPU"
-    (run_gemm if args.what == "gemm" else run_attention)(args)
+    {"gemm": run_gemm, "attention": run_attention, "mfma": run_mfma}[args.what](args)
 
 
 if __name__ == "__main__":
