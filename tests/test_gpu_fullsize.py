@@ -7,8 +7,9 @@ attention is causal, hence the first P positions of a sequence at the first laye
 only on the first P input positions of that sequence and on layer 0's parameters.  The oracle's
 layer forward on those prefixes is compared with the library's checkpoint (bf16 gate 2e-2).
 Beyond the samples, properties that hold at any size are checked: the whole step is reproduced
-by a differently grouped run (activations bit-identical, gradients equal up to fp32
-re-association), and the key-bias gradient vanishes against the query-bias gradient.
+by a differently grouped run that also keeps its boundary activations in pinned host memory
+(activations bit-identical, gradients equal up to fp32 re-association), and the key-bias gradient
+vanishes against the query-bias gradient.
 """
 import numpy as np
 import pytest
@@ -24,9 +25,9 @@ from gpu_helpers import rel_err
 PREFIX = 48
 
 
-def _run(w, group, x, dy, want_layer0_params):
+def _run(w, group, x, dy, want_layer0_params, offload=0):
     cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, B.LGA_BF16,
-                        group=group, retain_grads=0)
+                        group=group, retain_grads=0, offload_checkpoints=offload)
     st = B.Stack(cfg)
     out = {}
     try:
@@ -84,8 +85,9 @@ def test_cfg3_sampled_prefix_parity_and_regrouping():
     # --- the degenerate key-bias gradient
     d = w.d_model
     assert np.linalg.norm(a["g_bqkv"][d:2 * d]) < 5e-2 * np.linalg.norm(a["g_bqkv"][:d])
-    # --- same step with another grouping: same kernels per token, different fp32 summation order
-    b = _run(w, 2, x, dy, False)
+    # --- same step with another grouping (same kernels per token, different fp32 summation order) and with the
+    # boundary activations offloaded to the host (1.6 GB per boundary, read back from there)
+    b = _run(w, 2, x, dy, False, offload=1)
     assert np.array_equal(a["y_head"], b["y_head"])
     for mu in a["samples"]:
         assert np.array_equal(a["samples"][mu], b["samples"][mu])
