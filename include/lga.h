@@ -134,9 +134,10 @@ typedef struct lga_adam {
  * Adam moments start at zero.  The 16-bit parameter copy of every layer is produced here
  * (section 2.5: parameters are converted to 16 bits before use) and refreshed by each Adam step.
  * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in bf16 mode,
- * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes 32, 64, 96, 128 and 160 have MFMA attention kernels in
- * bf16 mode; other head sizes, and the fp32 mode, use a one-wavefront-per-position kernel that is meant for checking,
- * not for speed, and limits seq_len (2 seq_len + 2 d_h <= 15000).  LGA_ERR_OOM if the arena does not fit. */
+ * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes up to 160 have MFMA attention kernels in bf16 mode
+ * (built for 32, 64, 96, 128, 160; sizes in between run in the next larger one); larger head sizes, and the fp32
+ * mode, use a one-wavefront-per-position kernel that is meant for checking, not for speed, and limits seq_len
+ * (2 seq_len + 2 d_h <= 15000).  LGA_ERR_OOM if the arena does not fit. */
 int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **out);
 
 void lga_destroy_stack(lga_stack *stack);

@@ -81,7 +81,8 @@ uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols);
  *  out  [n_seq*s, heads*dh]
  *  lse  [n_seq, heads, s] float: log sum_j exp(scaled score_ij)
  * kind 0: one-wavefront-per-position kernel (any dtype, any dh); kind 1: MFMA kernel with
- * LDS-resident online softmax (LGA_BF16, dh in {32, 64, 96, 128, 160}). */
+ * LDS-resident online softmax (LGA_BF16, dh a multiple of 8 up to 160; head sizes other than 32, 64, 96, 128, 160
+ * run in the next larger of those kernels with the extra columns read as zeros). */
 int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out, float *lse, int32_t n_seq,
                          int32_t s, int32_t heads, int32_t dh, int32_t causal, void *stream);
 /* dqkv [n_seq*s, 3*heads*dh] written; delta [n_seq, heads, s] float scratch (written). */

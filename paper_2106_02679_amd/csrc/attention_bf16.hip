@@ -31,9 +31,10 @@ namespace {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// Second operand straight from global memory: 8 contiguous bf16 of one row (zero if the row is invalid).
-__device__ __forceinline__ bf16x8 frag_global(const bf16 *row_ptr, int ks, int half, bool valid) {
-    if (!valid) return bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+// Second operand straight from global memory: 8 contiguous bf16 of one row (zero if the row is invalid or the
+// columns lie beyond the head size dh, a multiple of 8 that may be smaller than the kernel's padded DH).
+__device__ __forceinline__ bf16x8 frag_global(const bf16 *row_ptr, int ks, int half, bool valid, int dh) {
+    if (!valid || 16 * ks + 8 * half >= dh) return bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     return *reinterpret_cast<const bf16x8 *>(row_ptr + 16 * ks + 8 * half);
 }
 // 32x32 fp32 result registers 8*kk .. 8*kk+7 -> bf16 second operand.
@@ -118,11 +119,12 @@ template <int ROWS, int DH, int PITCH> struct TileDma {
                                                             // so that "all but the newest tile" is one vmcnt value
     static constexpr int ELEMS = NJ * 4 * 512;              // LDS elements to reserve: 4 NJ instructions of 1 KB
     int row[NJ], off[NJ];
-    __device__ __forceinline__ void init(int wave, int lane, int gp2) {
+    // dh <= DH: the head size in memory; columns from dh on are padding like the rest of the pitch
+    __device__ __forceinline__ void init(int wave, int lane, int gp2, int dh) {
 #pragma unroll
         for (int i = 0; i < NJ; ++i) {
             const int slot = (i * 4 + wave) * 64 + lane, r = slot / SLOTS, pc = slot % SLOTS;
-            row[i] = (pc < DH / 8 && r < ROWS) ? r : 0x7FFFFFFF;    // padding slots never pass the row test
+            row[i] = (pc < dh / 8 && r < ROWS) ? r : 0x7FFFFFFF;    // padding slots never pass the row test
             off[i] = r * gp2 + (pc << 4);
         }
     }
@@ -180,9 +182,10 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     block_of(sh, qblocks, bh, rank);
     const int qb = qblocks - 1 - rank;
     const int h = bh % sh.heads, b = bh / sh.heads;
-    const int d = sh.heads * DH;
+    const int dh = sh.dh;                           // head size in memory: a multiple of 8, DH - 24 <= dh <= DH
+    const int d = sh.heads * dh;
     const size_t pitch = 3 * (size_t)d;
-    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
+    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int qw0 = qb * 256 + wave * 64;          // first query of this wavefront
@@ -196,7 +199,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     for (int u = 0; u < 2; ++u) {
         const int q = qw0 + 32 * u + lrow;
 #pragma unroll
-        for (int ks = 0; ks < NK; ++ks) qf[u][ks] = frag_global(seq + (size_t)q * pitch, ks, half, q < sh.s);
+        for (int ks = 0; ks < NK; ++ks) qf[u][ks] = frag_global(seq + (size_t)q * pitch, ks, half, q < sh.s, dh);
     }
     // Softmax reference per query, in the log2 domain.  It is FIXED once the query's first 32 keys are seen
     // (p = 2^(score - m_ref) is then exact up to a common factor that the final division removes), so the
@@ -206,7 +209,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     constexpr float kRefStep = 64.f;
     f32x16 oacc[2][NC];
     float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2];
-    const float c2 = rsqrtf((float)DH) * kLog2e;
+    const float c2 = rsqrtf((float)dh) * kLog2e;
     // Plain (not volatile) so that the compiler keeps it an LDS access, which waits for no global load; the
     // barriers' memory clobbers make every read after them a fresh one.
     __shared__ int restart_flag[1];
@@ -215,8 +218,8 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     // ---- tile loader ------------------------------------------------------------------------
     DmaK dk;
     DmaV dv;
-    dk.init(wave, lane, (int)(pitch * 2));
-    dv.init(wave, lane, (int)(pitch * 2));
+    dk.init(wave, lane, (int)(pitch * 2), dh);
+    dv.init(wave, lane, (int)(pitch * 2), dh);
     auto dma_tile = [&](int k0, int stage) {
         bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
         dk.issue(seq + (size_t)k0 * pitch + d, Ks, sh.s - k0, wave);
@@ -420,7 +423,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
         const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
         if (q < sh.s) {
             const float inv = 1.0f / l_tot;
-            bf16 *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * DH;
+            bf16 *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * dh;
 #pragma unroll
             for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -428,7 +431,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
                     bf16x4 o;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[u][c][4 * g + i] * inv);
-                    *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+                    if (c * 32 + 8 * g + 4 * half < dh) *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
                 }
             if (half == 0) lse[((size_t)b * sh.heads + h) * sh.s + q] = m_ref[u] * kLn2 + logf(l_tot);
         }
@@ -494,9 +497,10 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     block_of(sh, qblocks, bh, rank);
     const int qb = qblocks - 1 - rank;
     const int h = bh % sh.heads, b = bh / sh.heads;
-    const int d = sh.heads * DH;
+    const int dh = sh.dh;                           // head size in memory, <= DH
+    const int d = sh.heads * dh;
     const size_t pitch = 3 * (size_t)d;
-    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
+    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int qw0 = qb * 128 + wave * 32;
@@ -504,16 +508,16 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     const bool qvalid = q < sh.s;
 
     bf16x8 qf[NK], dof[NK];
-    const bf16 *dorow = dout + ((size_t)b * sh.s + q) * d + (size_t)h * DH;
+    const bf16 *dorow = dout + ((size_t)b * sh.s + q) * d + (size_t)h * dh;
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
-        qf[ks] = frag_global(seq + (size_t)q * pitch, ks, half, qvalid);
-        dof[ks] = frag_global(dorow, ks, half, qvalid);
+        qf[ks] = frag_global(seq + (size_t)q * pitch, ks, half, qvalid, dh);
+        dof[ks] = frag_global(dorow, ks, half, qvalid, dh);
     }
     const size_t stat = ((size_t)b * sh.heads + h) * sh.s + q;
     const float lse2 = qvalid ? lse[stat] * kLog2e : INFINITY;     // invalid rows: p = exp2(-inf) = 0
     const float dl = qvalid ? delta[stat] : 0.f;
-    const float scale = rsqrtf((float)DH);
+    const float scale = rsqrtf((float)dh);
     const float c2 = scale * kLog2e;
 
     f32x16 acc[NC];
@@ -524,8 +528,8 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
 
     DmaK dk;
     DmaV dv;
-    dk.init(wave, lane, (int)(pitch * 2));
-    dv.init(wave, lane, (int)(pitch * 2));
+    dk.init(wave, lane, (int)(pitch * 2), dh);
+    dv.init(wave, lane, (int)(pitch * 2), dh);
     auto dma_tile = [&](int k0, int stage) {
         bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
         dk.issue(seq + (size_t)k0 * pitch + d, Ks, sh.s - k0, wave);
@@ -597,7 +601,7 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
         }
     }
     if (qvalid) {
-        bf16 *orow = dqkv + ((size_t)b * sh.s + q) * pitch + (size_t)h * DH;
+        bf16 *orow = dqkv + ((size_t)b * sh.s + q) * pitch + (size_t)h * dh;
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -605,7 +609,7 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
                 bf16x4 o;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) o[i] = (bf16)(acc[c][4 * g + i] * scale);
-                *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+                if (c * 32 + 8 * g + 4 * half < dh) *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
             }
     }
 }
@@ -639,11 +643,12 @@ template <int ROWS, int DH> struct TileDmaSw {
     static constexpr int ELEMS = ROWS * DH;
     static_assert((ROWS * NCH) % 64 == 0, "tile is a whole number of DMA instructions");
     int row[NJ], off[NJ];
-    __device__ __forceinline__ void init(int wave, int lane, int gp2) {
+    // dh <= DH: the head size in memory; logical chunks from dh / 8 on are padding (zeros)
+    __device__ __forceinline__ void init(int wave, int lane, int gp2, int dh) {
 #pragma unroll
         for (int i = 0; i < NJ; ++i) {
             const int slot = (i * 4 + wave) * 64 + lane, r = slot / NCH, pc = slot % NCH;
-            row[i] = r;
+            row[i] = (pc ^ sw_both<DH>(r)) < dh / 8 ? r : 0x7FFFFFFF;
             off[i] = r * gp2 + ((pc ^ sw_both<DH>(r)) << 4);
         }
     }
@@ -725,10 +730,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     int bh, kb128;
     block_of(sh, (sh.s + 127) / 128, bh, kb128);
     const int h = bh % sh.heads, b = bh / sh.heads;
-    const int d = sh.heads * DH;
+    const int dh = sh.dh;                           // head size in memory, <= DH
+    const int d = sh.heads * dh;
     const size_t pitch = 3 * (size_t)d;
-    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * DH;
-    const bf16 *doseq = dout + (size_t)b * sh.s * d + (size_t)h * DH;
+    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
+    const bf16 *doseq = dout + (size_t)b * sh.s * d + (size_t)h * dh;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int kw0 = kb128 * 128 + wave * 32;        // first key of this wavefront
@@ -738,10 +744,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     bf16x8 kf[NK], vf[NK];
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
-        kf[ks] = frag_global(seq + (size_t)key * pitch + d, ks, half, kvalid);
-        vf[ks] = frag_global(seq + (size_t)key * pitch + 2 * d, ks, half, kvalid);
+        kf[ks] = frag_global(seq + (size_t)key * pitch + d, ks, half, kvalid, dh);
+        vf[ks] = frag_global(seq + (size_t)key * pitch + 2 * d, ks, half, kvalid, dh);
     }
-    const float scale = rsqrtf((float)DH);
+    const float scale = rsqrtf((float)dh);
     const float c2 = scale * kLog2e;
     const size_t stat0 = ((size_t)b * sh.heads + h) * sh.s;
 
@@ -752,8 +758,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
         for (int r = 0; r < 16; ++r) dk[c][r] = dv[c][r] = 0.f;
 
     Dma dq_, do_;
-    dq_.init(wave, lane, (int)(pitch * 2));
-    do_.init(wave, lane, d * 2);
+    dq_.init(wave, lane, (int)(pitch * 2), dh);
+    do_.init(wave, lane, d * 2, dh);
     BothAddr<DH> ad;
     ad.init(lane);
     const bool causal = sh.causal != 0;
@@ -894,7 +900,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
         unit(stage, 1, q0 + 32, std::false_type{});
     }
     if (kvalid) {
-        bf16 *orow = dqkv + ((size_t)b * sh.s + key) * pitch + (size_t)h * DH;
+        bf16 *orow = dqkv + ((size_t)b * sh.s + key) * pitch + (size_t)h * dh;
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -905,8 +911,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
                     ok[i] = (bf16)(dk[c][4 * g + i] * scale);
                     ov[i] = (bf16)dv[c][4 * g + i];
                 }
-                *reinterpret_cast<bf16x4 *>(orow + d + c * 32 + 8 * g + 4 * half) = ok;
-                *reinterpret_cast<bf16x4 *>(orow + 2 * d + c * 32 + 8 * g + 4 * half) = ov;
+                if (c * 32 + 8 * g + 4 * half < dh) {
+                    *reinterpret_cast<bf16x4 *>(orow + d + c * 32 + 8 * g + 4 * half) = ok;
+                    *reinterpret_cast<bf16x4 *>(orow + 2 * d + c * 32 + 8 * g + 4 * half) = ov;
+                }
             }
     }
 }
@@ -925,8 +933,8 @@ template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape 
     char name[64];
     snprintf(name, sizeof(name), "attn_fwd_kernel<%d>", DH);
     const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * (sh.causal ? 0.5 : 1.0);      // visible (query, key) pairs
-    const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;         // bytes of one [tokens, d] bf16 tensor
-    ProfScope scope(name, 4.0 * pairs * DH, 4.0 * act, s);
+    const double act = (double)sh.n_seq * sh.s * sh.heads * sh.dh * 2.0;      // bytes of one [tokens, d] bf16 tensor
+    ProfScope scope(name, 4.0 * pairs * sh.dh, 4.0 * act, s);
     // three stages of a 64-key K tile and V tile
     constexpr int smem = 3 * (TileDma<64, DH, pitch_rd<DH>()>::ELEMS + TileDma<64, DH, pitch_tr<DH>()>::ELEMS) * 2;
     static bool attr_set = false;
@@ -943,10 +951,10 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
     dim3 grid((unsigned)(sh.n_seq * sh.heads) * ((sh.s + 127) / 128));
     char name[64];
     const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * (sh.causal ? 0.5 : 1.0);
-    const double act = (double)sh.n_seq * sh.s * sh.heads * DH * 2.0;
+    const double act = (double)sh.n_seq * sh.s * sh.heads * sh.dh * 2.0;
     {
         snprintf(name, sizeof(name), "attn_bwd_dq_kernel<%d>", DH);
-        ProfScope scope(name, 6.0 * pairs * DH, 5.0 * act, s);
+        ProfScope scope(name, 6.0 * pairs * sh.dh, 5.0 * act, s);
         constexpr int kOccDq = DH <= 128 ? 2 : 1;     // workgroups per CU the register budget is set for
         // two stages of a 64-key K tile and V tile
         constexpr int smem_dq = 2 * (TileDma<64, DH, pitch_both<DH>()>::ELEMS + TileDma<64, DH, pitch_rd<DH>()>::ELEMS) * 2;
@@ -960,7 +968,7 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
     }
     {
         snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
-        ProfScope scope(name, 8.0 * pairs * DH, 6.0 * act, s);
+        ProfScope scope(name, 8.0 * pairs * sh.dh, 6.0 * act, s);
         constexpr int smem = 3 * (2 * 64 * DH * 2 + 2 * 64 * 4);   // three stages of a Q tile, a dO tile and the row statistics
         static bool attr_set = false;
         if (!attr_set) {
@@ -974,17 +982,23 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
 
 }  // namespace
 
-bool attn_bf16_supports(int dh) { return dh == 32 || dh == 64 || dh == 96 || dh == 128 || dh == 160; }
+// Head sizes 32, 64, 96, 128, 160 have kernels; any other multiple of 8 up to 160 runs in the next larger one with
+// its extra columns read as zeros and not written.
+bool attn_bf16_supports(int dh) { return dh >= 8 && dh <= 160 && dh % 8 == 0; }
+static int padded_dh(int dh) { return (dh + 31) / 32 * 32; }
 
 void launch_attn_fwd_bf16(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
     if (sh.n_seq == 0 || sh.s == 0) return;
-    switch (sh.dh) {
+    if (!attn_bf16_supports(sh.dh)) {
+        launch_attn_fwd_simple<bf16>(qkv, out, lse, sh, s);
+        return;
+    }
+    switch (padded_dh(sh.dh)) {
         case 32: fwd_dh<32>(qkv, out, lse, sh, s); break;
         case 64: fwd_dh<64>(qkv, out, lse, sh, s); break;
         case 96: fwd_dh<96>(qkv, out, lse, sh, s); break;
         case 128: fwd_dh<128>(qkv, out, lse, sh, s); break;
         case 160: fwd_dh<160>(qkv, out, lse, sh, s); break;
-        default: launch_attn_fwd_simple<bf16>(qkv, out, lse, sh, s); break;
     }
 }
 
@@ -1000,7 +1014,7 @@ void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, co
         ProfScope scope("attn_delta_kernel", 2.0 * items * sh.dh, 4.0 * items * sh.dh, s);
         hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, out, dout, delta, sh);
     }
-    switch (sh.dh) {
+    switch (padded_dh(sh.dh)) {
         case 32: bwd_dh<32>(qkv, lse, delta, dout, dqkv, sh, s); break;
         case 64: bwd_dh<64>(qkv, lse, delta, dout, dqkv, sh, s); break;
         case 96: bwd_dh<96>(qkv, lse, delta, dout, dqkv, sh, s); break;

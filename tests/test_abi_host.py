@@ -47,7 +47,7 @@ def test_parameter_count_follows_table_b1_closed_form():
     (dict(n_layers=0), B.LGA_ERR_SHAPE), (dict(d_model=65), B.LGA_ERR_SHAPE), (dict(group=3), B.LGA_ERR_SHAPE),
     (dict(group=0), B.LGA_ERR_SHAPE), (dict(group=8), B.LGA_ERR_SHAPE), (dict(dtype=7), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=48, d_ff=192), B.LGA_ERR_SHAPE),    # d_h = 12 is not a multiple of 8
-    (dict(dtype=B.LGA_BF16, seq_len=8192), B.LGA_ERR_SHAPE),           # d_h = 16 has no MFMA kernel: sequence limit
+    (dict(dtype=B.LGA_BF16, d_model=1024, d_ff=4096, seq_len=8192), B.LGA_ERR_SHAPE),   # d_h = 256 > 160: no MFMA attention kernel, sequence limit of the generic one
     (dict(attention=2), B.LGA_ERR_ARG), (dict(offload_checkpoints=2), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=128, n_heads=4, d_ff=500), B.LGA_ERR_SHAPE),
     (dict(seq_len=0), B.LGA_ERR_SHAPE),

@@ -274,6 +274,9 @@ ATTN_CASES = [
     # long enough for the loops over fully visible tiles and for the LDS stages to wrap around, ragged ends
     (BF16, 1, 1, 1100, 2, 128), (BF16, 1, 2, 640, 1, 64), (BF16, 1, 1, 777, 1, 96), (BF16, 1, 1, 520, 1, 160),
     (BF16, 1, 1, 600, 1, 32),
+    # head sizes between the kernels' own (32, 64, 96, 128, 160): run in the next larger kernel, extra columns as zeros
+    (BF16, 1, 2, 200, 2, 152), (BF16, 1, 1, 333, 3, 72), (BF16, 1, 1, 130, 2, 8), (BF16, 1, 1, 97, 2, 40),
+    (BF16, 1, 1, 300, 2, 104),
 ]
 # the encoder variant (no mask): whole tiles, ragged last tiles of every residue class that matters (a last
 # key block that is partly / wholly past the end), sequences shorter than a block, every head size
@@ -282,7 +285,7 @@ FULL_CASES = [
     (BF16, 1, 2, 256, 2, 128), (BF16, 1, 1, 333, 3, 64), (BF16, 1, 2, 200, 2, 32), (BF16, 1, 1, 130, 2, 160),
     (BF16, 1, 1, 1, 1, 64), (BF16, 1, 3, 64, 1, 96), (BF16, 1, 1, 31, 2, 128), (BF16, 1, 1, 97, 1, 64),
     (BF16, 1, 1, 1100, 2, 128), (BF16, 1, 2, 640, 1, 64), (BF16, 1, 1, 777, 1, 96), (BF16, 1, 1, 520, 1, 160),
-    (BF16, 1, 1, 600, 1, 32),
+    (BF16, 1, 1, 600, 1, 32), (BF16, 1, 2, 200, 2, 152), (BF16, 1, 1, 333, 3, 72), (BF16, 1, 1, 97, 2, 40),
 ]
 
 
@@ -353,8 +356,9 @@ def test_attention_with_scores_that_keep_growing_along_the_keys(dh, causal):
 def test_attention_mfma_rejects_unsupported_head_size():
     t = torch.zeros(4096, device="cuda", dtype=torch.bfloat16)
     l = torch.zeros(64, device="cuda")
-    rc = B.lib.lga_op_attention_fwd(BF16, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 48, 1, None)
-    assert rc == B.LGA_ERR_SHAPE
+    for dh in (168, 320, 12):            # above 160, or not a multiple of 8
+        rc = B.lib.lga_op_attention_fwd(BF16, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, dh, 1, None)
+        assert rc == B.LGA_ERR_SHAPE
     rc = B.lib.lga_op_attention_fwd(F32, 1, t.data_ptr(), t.data_ptr(), l.data_ptr(), 1, 4, 1, 64, 1, None)
     assert rc == B.LGA_ERR_SHAPE
 

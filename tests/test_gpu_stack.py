@@ -141,10 +141,11 @@ def test_x_family_shapes_match_oracle(x_, layers, causal):
     print(f"X_{x_} ({layers} layers, causal={causal}) worst rel err {max(worst.values()):.3e}")
 
 
-@pytest.mark.parametrize("dh,causal", [(24, True), (216, False)])
-def test_head_sizes_without_an_mfma_kernel_use_the_generic_attention_kernels(dh, causal):
-    """bf16 mode with a head size outside {32, 64, 96, 128, 160} (X_108 of table B.1 has d_h = 216): the
-    one-wavefront attention kernels serve it, everything else is unchanged."""
+@pytest.mark.parametrize("dh,causal", [(24, True), (152, True), (216, False)])
+def test_head_sizes_between_and_beyond_the_attention_kernels_own(dh, causal):
+    """bf16 mode with a head size outside {32, 64, 96, 128, 160}: up to 160 (T-NLG of table B.1 has d_h = 152) the
+    next larger MFMA kernel serves it with zero columns; beyond (X_108 has d_h = 216) the one-wavefront attention
+    kernels do; everything else is unchanged."""
     heads = 2 if dh < 100 else 1
     d = heads * dh
     w = S.Workload(f"oddhead_dh{dh}", 1, d, heads, 4 * d, 72, 1, 2, "bf16")
