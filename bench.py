@@ -122,13 +122,25 @@ def main():
     st = B.Stack(cfg)                     # weights filled on the device: N(0, 0.02^2), gains 1, biases 0
     torch.cuda.synchronize()
 
-    def step(t):
+    marks = []      # per timed step: events at its start, between the sweeps, at its end
+
+    def step(t, timed=False):
         adam = B.lga_adam(1e-3, 0.9, 0.999, 1e-8, t)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timed else None
+        if timed:
+            ev[0].record()
         if args.order == "layered":
             st.forward_layered(x.data_ptr(), None)
+            if timed:
+                ev[1].record()
             st.backward_layered(dy.data_ptr(), None, adam)
         else:
             st.step_mbmajor(x.data_ptr(), dy.data_ptr(), None, None, adam)
+            if timed:
+                ev[1].record()
+        if timed:
+            ev[2].record()
+            marks.append(ev)
 
     t = 1
     for _ in range(args.warmup):
@@ -139,13 +151,15 @@ def main():
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        step(t); t += 1
+        step(t, timed=True); t += 1
     e1.record()
     torch.cuda.synchronize()
     ms_total = e0.elapsed_time(e1)
     stats = st.profile_end()
     restores = (st.restore_count() - restores0) / args.steps
     ms_step = ms_total / args.steps
+    step_ms = [m[0].elapsed_time(m[2]) for m in marks]
+    fwd_ms = [m[0].elapsed_time(m[1]) for m in marks]
 
     order = B.LGA_ORDER_LAYERED if args.order == "layered" else B.LGA_ORDER_MICROBATCH_MAJOR
     param_bytes, grad_bytes, flops_exec = B.traffic_model(cfg, order)
@@ -198,6 +212,11 @@ def main():
                    "group": group, "order": args.order, "attention": args.attention, "tokens_per_step": tokens,
                    "param_buffers": args.param_buffers or w.n_layers, "overlap": args.overlap,
                    "offload_checkpoints": bool(args.offload)},
+        "ms_per_step_min": min(step_ms), "ms_per_step_max": max(step_ms),
+        # layered order: forward sweep / backward sweep with recompute and the per-layer Adam steps (mean over the steps)
+        "phase_ms": ({"forward": sum(fwd_ms) / len(fwd_ms), "backward_with_adam": ms_step - sum(fwd_ms) / len(fwd_ms),
+                      "adam_kernels": sum(k["ms"] for k in stats if k["name"].startswith("adam")) / args.steps}
+                     if args.order == "layered" else None),
         "restores_per_step": restores,
         "device_arena_bytes": B.arena_bytes(cfg), "pinned_host_bytes": B.host_bytes(cfg),
         # checkpoint offload: every boundary goes to the host once, all but the top two come back once
