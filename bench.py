@@ -34,7 +34,9 @@ def parse():
     ap.add_argument("--x-family", type=int, default=0, metavar="X",
                     help="instead of --config: the paper's X_[x] model (table B.1), all x layers, micro-batches of one "
                          "sequence; --n-micro sets how many")
-    ap.add_argument("--n-micro", type=int, default=32, help="micro-batches per step of the --x-family workload")
+    ap.add_argument("--n-micro", type=int, default=0,
+                    help="micro-batches per step: of the --x-family workload (default 32), or instead of the benchmark "
+                         "configuration's own (for traffic-versus-n measurements; the workload name then says so)")
     ap.add_argument("--attention", choices=["causal", "full"], default="causal",
                     help="full: the paper's encoder, no mask (the benchmark configurations are causal decoders)")
     ap.add_argument("--group", type=int, default=0, help="micro-batches per kernel launch (0 = default for the config)")
@@ -99,7 +101,10 @@ def main():
     import synth_inputs as S
     from paper_2106_02679_amd import binding as B
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = S.x_family(args.x_family, args.n_micro) if args.x_family else S.CONFIGS[args.config]
+    w = S.x_family(args.x_family, args.n_micro or 32) if args.x_family else S.CONFIGS[args.config]
+    if args.n_micro and not args.x_family and args.n_micro != w.n_micro:
+        w = S.Workload(f"{w.name}_n{args.n_micro}", w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch,
+                       args.n_micro, w.dtype)
     dt = B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
     # default group: the benchmark configurations' own, else about 4096 tokens per launch
     default_group = max(1, 4096 // (w.micro_batch * w.seq_len)) if args.x_family else DEFAULT_GROUP[args.config]
