@@ -1,6 +1,8 @@
 // HBM-bound kernels of the layer stack: parameter cast, LayerNorm forward / backward, column
 // sums (bias and LayerNorm-affine gradients), Adam, counter-based weight fill.
 // All arithmetic is fp32; T (float or bf16) is only the storage type of activations.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace lga {
@@ -108,6 +110,85 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T *__restrict_
 #pragma unroll
         for (int i = 0; i < V; ++i) o[i] = (v[i] - mean) * rstd * g[c + i] + b[c + i];
         store_pack<T, V>(yr + c, o);
+    }
+}
+
+// The same with a block walking over many rows and everything it needs more than once in registers: each thread
+// keeps its NP packs of the row (one global read of x instead of three) and, if CACHE_GB, its gains and biases (read
+// per row they are 8 bytes per element of L2 traffic against 4 bytes of x and y).  Wide rows use large blocks, so
+// that a thread holds few packs and many wavefronts fit on a CU.  d <= TH * V * NP.  The forward pass and the
+// recompute of the backward pass run the same variant, so they still agree bit for bit.
+template <class T, int V, int TH, int NP, bool CACHE_GB>
+__global__ __launch_bounds__(TH) void layernorm_fwd_rows_kernel(const T *__restrict__ x, const float *__restrict__ g,
+                                                                 const float *__restrict__ b, T *__restrict__ y,
+                                                                 float *__restrict__ mean_out, float *__restrict__ rstd_out,
+                                                                 int rows, int d, float eps) {
+    __shared__ float red[16];
+    constexpr int NG = CACHE_GB ? NP : 1;
+    float gv[NG][V], bv[NG][V];
+    if constexpr (CACHE_GB) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+#pragma unroll
+                for (int q = 0; q < V / 4; ++q) {
+                    float t4[4], u4[4];
+                    load_pack<float, 4>(g + c + 4 * q, t4);
+                    load_pack<float, 4>(b + c + 4 * q, u4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        gv[p][4 * q + i] = t4[i];
+                        bv[p][4 * q + i] = u4[i];
+                    }
+                }
+            }
+        }
+    }
+    for (size_t row = blockIdx.x; row < (size_t)rows; row += gridDim.x) {
+        const T *xr = x + row * (size_t)d;
+        T *yr = y + row * (size_t)d;
+        float xv[NP][V];
+        float s = 0.f;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+                load_pack<T, V>(xr + c, xv[p]);
+#pragma unroll
+                for (int i = 0; i < V; ++i) s += xv[p][i];
+            }
+        }
+        const float mean = block_sum(s, red) / (float)d;
+        float q = 0.f;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) q += (xv[p][i] - mean) * (xv[p][i] - mean);
+            }
+        }
+        const float var = block_sum(q, red) / (float)d;
+        const float rstd = rsqrtf(var + eps);
+        if (threadIdx.x == 0) {
+            mean_out[row] = mean;
+            rstd_out[row] = rstd;
+        }
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+                float o[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const float gi = CACHE_GB ? gv[CACHE_GB ? p : 0][i] : g[c + i];
+                    const float bi = CACHE_GB ? bv[CACHE_GB ? p : 0][i] : b[c + i];
+                    o[i] = (xv[p][i] - mean) * rstd * gi + bi;
+                }
+                store_pack<T, V>(yr + c, o);
+            }
+        }
     }
 }
 
@@ -343,7 +424,18 @@ void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, floa
     if (rows == 0) return;
     constexpr int V = VecOf<T>::N;
     ProfScope scope("layernorm_fwd_kernel", 8.0 * rows * d, 2.0 * sizeof(T) * rows * (double)d, s);
-    if (d % V == 0 && aligned16(x) && aligned16(y))
+    if (d % V == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b) && d <= 1024 * V * 4) {
+        // rows are dealt to a fixed number of blocks (enough to fill every CU), which keep what they reuse in registers
+#define LGA_LN_ROWS(TH, NP) \
+        hipLaunchKernelGGL((layernorm_fwd_rows_kernel<T, V, TH, NP, true>), dim3((unsigned)std::min(rows, 256 * (2048 / TH))), \
+                           dim3(TH), 0, s, x, g, b, y, mean, rstd, rows, d, eps)
+        if (d <= 256 * V) LGA_LN_ROWS(256, 1);
+        else if (d <= 512 * V) LGA_LN_ROWS(512, 1);
+        else if (d <= 1024 * V) LGA_LN_ROWS(1024, 1);
+        else if (d <= 1024 * V * 2) LGA_LN_ROWS(1024, 2);
+        else LGA_LN_ROWS(1024, 4);
+#undef LGA_LN_ROWS
+    } else if (d % V == 0 && aligned16(x) && aligned16(y))
         hipLaunchKernelGGL((layernorm_fwd_kernel<T, V>), dim3(rows), dim3(256), 0, s, x, g, b, y, mean, rstd, d, eps);
     else
         hipLaunchKernelGGL((layernorm_fwd_kernel<T, 1>), dim3(rows), dim3(256), 0, s, x, g, b, y, mean, rstd, d, eps);
