@@ -1,6 +1,7 @@
-"""GPU checks at the benchmark's full size (cfg3: 4 layers, d = 12288, 96 heads, d_ff = 49152,
-seq 2048, 32 micro-batches) in the launch configuration bench.py times (layered order, group 4,
-single gradient buffer, fused Adam, device-filled weights).
+"""GPU checks at the benchmark configurations' full sizes - cfg3, which bench.py times (4 layers, d = 12288,
+96 heads, d_ff = 49152, seq 2048, 32 micro-batches), and the two smaller bf16 configurations cfg1 and
+cfg2 - in the launch configuration bench.py uses (layered order, group 4, single gradient buffer,
+fused Adam, device-filled weights).
 
 The fp64 oracle cannot run this size, so it checks sampled outputs it can compute one by one:
 attention is causal, hence the first P positions of a sequence at the first layer boundary depend
@@ -62,11 +63,14 @@ def _run(w, group, x, dy, want_layer0_params, offload=0):
     return out
 
 
-def test_cfg3_sampled_prefix_parity_and_regrouping():
-    w = S.CONFIGS[3]
+@pytest.mark.parametrize("config", [1, 2, 3])
+def test_full_size_sampled_prefix_parity_and_regrouping(config):
+    w = S.CONFIGS[config]
     free, _ = torch.cuda.mem_get_info()
-    if free < 185e9:
-        pytest.skip("needs about 175 GB of free HBM")
+    need = B.arena_bytes(B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro,
+                                       B.LGA_BF16, group=4)) + 6 * w.tokens * w.d_model * 2 + 4e9
+    if free < need:
+        pytest.skip(f"needs about {need / 1e9:.0f} GB of free HBM")
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     gen = torch.Generator(device="cuda").manual_seed(0)
     x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(torch.bfloat16)
@@ -79,7 +83,7 @@ def test_cfg3_sampled_prefix_parity_and_regrouping():
         xin = x[mu, 0, :PREFIX].float().cpu().numpy().astype(np.float64)[None]
         ref, _ = O.layer_forward(xin, p0, w.n_heads, 1e-5)
         err = rel_err(got, ref[0])
-        print(f"cfg3 boundary 1, micro-batch {mu}, first {PREFIX} positions: rel err {err:.3e}")
+        print(f"{w.name} boundary 1, micro-batch {mu}, first {PREFIX} positions: rel err {err:.3e}")
         assert err < 2e-2
     del p0
     # --- the degenerate key-bias gradient
