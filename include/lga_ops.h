@@ -97,10 +97,11 @@ int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_
 
 /* Calibration for the benchmark tools: the bf16 MFMA rate (TFLOP/s, executed) that the GPU sustains on register
  * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 16 v_mfma_f32_32x32x16_bf16 back to
- * back, no memory traffic.  constant_operands != 0: all operand values 1.0 (approaches the nominal peak);
- * 0: values around +-1 with random mantissas and signs (what the power management allows on realistic data).
+ * back, no memory traffic.  mode 0: operand values around +-1 with random mantissas and signs (what the power
+ * management allows on realistic data); 1: all operand values 1.0 (approaches the nominal peak); 2: as 0, with the
+ * operands re-read from LDS as a 256 x 256 GEMM tile of 2 x 2 wavefronts must (eight 16-byte reads per 16 MFMAs).
  * sink: device, >= 65536 floats, overwritten.  Synchronous: returns after the kernel has run.  tflops: host. */
-int lga_op_mfma_rate(int32_t iters, int32_t constant_operands, float *sink, double *tflops, void *stream);
+int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream);
 
 #ifdef __cplusplus
 }

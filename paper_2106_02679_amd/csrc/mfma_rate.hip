@@ -1,7 +1,9 @@
 // Calibration: the bf16 MFMA rate the chip sustains on register operands alone - no memory, no LDS, nothing but
 // v_mfma_f32_32x32x16_bf16 back to back on every SIMD.  With constant operands this reaches the nominal peak; with
 // random mantissas and signs the chip's power management holds the clock lower, and that rate - not the
-// nominal one - is what a GEMM on real activations can approach.  Used by the benchmark tools only.
+// nominal one - is what a GEMM on real activations can approach.  A third mode re-reads the operands from LDS the
+// way a 2 x 2-wavefront 256 x 256 GEMM tile must (eight 16-byte reads per 16 MFMAs, issued 16 MFMAs ahead): what is
+// left once the operands have to come from somewhere.  Used by the benchmark tools only.
 #include <cstdio>
 
 #include "kernels.h"
@@ -10,10 +12,29 @@
 namespace lga {
 namespace {
 
-__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iters, int constant_operands) {
+constexpr int kLdsChunks = 8192;        // 128 KB of operand data in LDS (mode 2)
+
+// mode 0: random register operands; 1: constant register operands; 2: random operands re-read from LDS
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iters) {
+    constexpr int constant_operands = MODE == 1;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    u32x4 *lds = reinterpret_cast<u32x4 *>(smem);
     // operand registers: values around +-1 with random mantissas and signs, or all ones
     bf16x8 a[4], b[4];
     unsigned s = (threadIdx.x + 1) * 2654435761u ^ (blockIdx.x * 40503u);
+    if constexpr (MODE == 2) {
+        for (int i = threadIdx.x; i < kLdsChunks; i += 256) {
+            u32x4 v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                s = s * 1664525u + 1013904223u;
+                v[j] = (s & 0x807f807fu) | 0x3f003f00u;
+            }
+            lds[i] = v;
+        }
+        __syncthreads();
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         u32x4 va, vb;
@@ -34,12 +55,31 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iter
     for (int i = 0; i < 16; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    for (int it = 0; it < iters; ++it) {
+    bf16x8 a2[4], b2[4];
+    int off = threadIdx.x;
+    auto fetch = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[i] = __builtin_bit_cast(bf16x8, lds[(off + 256 * i) & (kLdsChunks - 1)]);
+            fb[i] = __builtin_bit_cast(bf16x8, lds[(off + 256 * (i + 4) + 1024) & (kLdsChunks - 1)]);
+        }
+        off += 2048;
+    };
+    for (int it = 0; it < iters; it += 2) {
+        // two groups of 16 MFMAs per turn; in mode 2 each group's operands are read while the other group runs
+        if constexpr (MODE == 2) fetch(a2, b2);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
+        if constexpr (MODE == 2) fetch(a, b);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(MODE == 2 ? a2[i] : a[i], MODE == 2 ? b2[j] : b[j],
+                                                                         acc[i * 4 + j], 0, 0, 0);
     }
     float t = 0.f;
 #pragma unroll
@@ -52,9 +92,10 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iter
 }  // namespace
 }  // namespace lga
 
-extern "C" int lga_op_mfma_rate(int32_t iters, int32_t constant_operands, float *sink, double *tflops, void *stream) {
+extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 1 || iters > (1 << 24) || !sink || !tflops) return LGA_ERR_ARG;
+    if (iters < 2 || iters > (1 << 24) || mode < 0 || mode > 2 || !sink || !tflops) return LGA_ERR_ARG;
+    iters &= ~1;                                            // the loop does two groups of 16 MFMAs per turn
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -67,7 +108,17 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t constant_operands, float 
         return LGA_ERR_HIP;
     }
     (void)hipEventRecord(e0, s);
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3(cus), dim3(256), 0, s, sink, iters, constant_operands);
+    if (mode == 0) hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(cus), dim3(256), 0, s, sink, iters);
+    else if (mode == 1) hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(cus), dim3(256), 0, s, sink, iters);
+    else {
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<2>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsChunks * 16);
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(cus), dim3(256), kLdsChunks * 16, s, sink, iters);
+    }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);
     float ms = 0.f;

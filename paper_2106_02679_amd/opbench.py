@@ -117,12 +117,13 @@ def run_mfma(args):
     import torch
     from paper_2106_02679_amd import binding as B
     sink = torch.empty(65536, device="cuda")
-    for constant in (1, 0):
+    what = {1: "constant register operands", 0: "random register operands  ", 2: "random operands via LDS   "}
+    for mode in (1, 0, 2):
         for iters in (400000, 4000000):
             tf = C.c_double()
-            B.check(B.lib.lga_op_mfma_rate(iters, constant, sink.data_ptr(), C.byref(tf), None))
-            print(f"register-only v_mfma_f32_32x32x16_bf16, {'constant' if constant else 'random  '} operands, "
-                  f"{iters * 16} MFMAs per wavefront: {tf.value:8.1f} TFLOP/s", flush=True)
+            B.check(B.lib.lga_op_mfma_rate(iters, mode, sink.data_ptr(), C.byref(tf), None))
+            print(f"v_mfma_f32_32x32x16_bf16 only, {what[mode]}, {iters * 16} MFMAs per wavefront: "
+                  f"{tf.value:8.1f} TFLOP/s", flush=True)
 
 
 def main():
