@@ -273,6 +273,24 @@ def test_checkpoint_offload_changes_placement_not_results(layers, group, overlap
         assert e.value.code == B.LGA_ERR_STATE
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_three_consecutive_steps_match_oracle(dtype):
+    """Adam state carried from step to step: moments, bias corrections with t = 1, 2, 3, and - in bf16 mode - the
+    16-bit parameter copies that each update rewrites and the next forward pass reads."""
+    w = S.Workload(f"steps_{dtype}", 2, 64, 2, 256, 40, 2, 2, dtype)
+    x, G, params = S.make_inputs(w, seed=43, weight_std=0.05, bias_std=0.05)
+    adam = adam_struct(lr=2e-3)
+    shape = oracle_shape(w)
+    p, m, v = [q.astype(np.float64) for q in params], None, None
+    for t in (1, 2, 3):
+        hp = O.AdamHyper(lr=float(np.float32(adam.lr)), beta1=float(np.float32(adam.beta1)),
+                         beta2=float(np.float32(adam.beta2)), eps=float(np.float32(adam.eps)), step=t)
+        ref = O.step_microbatch_major(x, G, p, shape, hp, m, v)
+        p, m, v = ref.new_params, ref.new_m, ref.new_v
+    got = run_gpu_step(w, x, G, params, group=2, retain=1, adam=adam, steps=3)
+    compare_with_oracle(w, got, ref, GATE[dtype], adam, zero_init=False)
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
