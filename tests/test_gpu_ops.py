@@ -66,6 +66,10 @@ GEMM_CASES = [
     (BF16, 1, 0, B.LGA_EPI_BIAS, 4100, 8200, 136),
     (BF16, 1, 1, B.LGA_EPI_STORE, 4100, 8200, 72),
     (BF16, 0, 0, B.LGA_EPI_ACCUM_F32, 4104, 8200, 200),
+    # the large-tile kernel's row-store epilogues that read a second tensor, ragged in m and n
+    (BF16, 1, 1, B.LGA_EPI_MUL_DGELU, 4100, 8200, 72),
+    (BF16, 1, 1, B.LGA_EPI_BIAS_RESID, 4100, 8200, 72),
+    (BF16, 1, 1, B.LGA_EPI_BIAS, 2050, 16392, 200),
 ]
 
 
