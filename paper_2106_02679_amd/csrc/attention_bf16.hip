@@ -450,24 +450,34 @@ LGA_INSTANTIATE_FWD(160);
 #undef LGA_INSTANTIATE_FWD
 
 // ============================================================================================
-// delta[b, h, q] = sum_c dO[q, h*DH + c] * O[q, h*DH + c].  One wavefront per (token, head).
+// delta[b, h, q] = sum_c dO[q, h*dh + c] * O[q, h*dh + c].  out and dout are [tokens][heads * dh]: consecutive
+// (token, head) items are consecutive runs of dh elements.  A thread multiplies one 16-byte chunk of each tensor
+// (fully coalesced), the chunk sums go through LDS, and one thread per item adds its dh / 8 of them in order.
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict__ out, const bf16 *__restrict__ dout,
-                                                         float *__restrict__ delta, AttnShape sh) {
-    const int lane = threadIdx.x & 63;
-    const size_t item = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);     // token * heads + head
-    const size_t total = (size_t)sh.n_seq * sh.s * sh.heads;
-    if (item >= total) return;
-    const int h = item % sh.heads;
-    const size_t tok = item / sh.heads;
-    const size_t off = tok * ((size_t)sh.heads * sh.dh) + (size_t)h * sh.dh;
+                                                         float *__restrict__ delta, AttnShape sh, int items_per_block) {
+    __shared__ float part[256];
+    const int cpi = sh.dh / 8;                                            // chunks per item
+    const size_t items = (size_t)sh.n_seq * sh.s * sh.heads;
+    const size_t item0 = (size_t)blockIdx.x * items_per_block;
+    const int tid = threadIdx.x;
+    const size_t chunk = item0 * cpi + tid;                               // index into the tensors as arrays of 16-byte chunks
     float acc = 0.f;
-    for (int c = lane * 2; c < sh.dh; c += 128) {
-        acc += (float)out[off + c] * (float)dout[off + c] + (float)out[off + c + 1] * (float)dout[off + c + 1];
+    if (tid < items_per_block * cpi && chunk < items * cpi) {
+        const bf16x8 o = *reinterpret_cast<const bf16x8 *>(out + chunk * 8);
+        const bf16x8 g = *reinterpret_cast<const bf16x8 *>(dout + chunk * 8);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc += (float)o[i] * (float)g[i];
     }
-    acc = wave_sum(acc);
-    if (lane == 0) {
+    part[tid] = acc;
+    __syncthreads();
+    if (tid < items_per_block && item0 + tid < items) {
+        float t = 0.f;
+        for (int c = 0; c < cpi; ++c) t += part[tid * cpi + c];
+        const size_t item = item0 + tid;                                  // token * heads + head
+        const int h = item % sh.heads;
+        const size_t tok = item / sh.heads;
         const size_t bb = tok / sh.s, qq = tok % sh.s;
-        delta[(bb * sh.heads + h) * sh.s + qq] = acc;
+        delta[(bb * sh.heads + h) * sh.s + qq] = t;
     }
 }
 
@@ -1012,7 +1022,9 @@ void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, co
     const size_t items = (size_t)sh.n_seq * sh.s * sh.heads;
     {
         ProfScope scope("attn_delta_kernel", 2.0 * items * sh.dh, 4.0 * items * sh.dh, s);
-        hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + 3) / 4)), dim3(256), 0, s, out, dout, delta, sh);
+        const int items_per_block = 256 / (sh.dh / 8);                  // dh is a multiple of 8, at most 160
+        hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + items_per_block - 1) / items_per_block)), dim3(256), 0,
+                           s, out, dout, delta, sh, items_per_block);
     }
     switch (padded_dh(sh.dh)) {
         case 32: bwd_dh<32>(qkv, lse, delta, dout, dqkv, sh, s); break;

@@ -123,7 +123,18 @@ __global__ __launch_bounds__(TH) void layernorm_fwd_rows_kernel(const T *__restr
                                                                  const float *__restrict__ b, T *__restrict__ y,
                                                                  float *__restrict__ mean_out, float *__restrict__ rstd_out,
                                                                  int rows, int d, float eps) {
-    __shared__ float red[16];
+    // Two scratch rows used in turn: a sum's barrier also separates the other row's readers from its next writers,
+    // so each block-wide sum costs one barrier.
+    __shared__ float red[2][16];
+    auto sum_all = [&](float v, int which) {
+        v = wave_sum(v);
+        if ((threadIdx.x & 63) == 0) red[which][threadIdx.x >> 6] = v;
+        __syncthreads();
+        float t = 0.f;
+#pragma unroll
+        for (int i = 0; i < TH / 64; ++i) t += red[which][i];
+        return t;
+    };
     constexpr int NG = CACHE_GB ? NP : 1;
     float gv[NG][V], bv[NG][V];
     if constexpr (CACHE_GB) {
@@ -145,8 +156,19 @@ __global__ __launch_bounds__(TH) void layernorm_fwd_rows_kernel(const T *__restr
             }
         }
     }
-    for (size_t row = blockIdx.x; row < (size_t)rows; row += gridDim.x) {
+    // The next row's packs are requested before this row's two block-wide sums, so that loads stay in flight while
+    // the block waits at its barriers.
+    Pack<T, V> nxt[NP];
+    auto request = [&](size_t row) {
         const T *xr = x + row * (size_t)d;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) nxt[p] = *reinterpret_cast<const Pack<T, V> *>(xr + c);
+        }
+    };
+    if (blockIdx.x < (unsigned)rows) request(blockIdx.x);
+    for (size_t row = blockIdx.x; row < (size_t)rows; row += gridDim.x) {
         T *yr = y + row * (size_t)d;
         float xv[NP][V];
         float s = 0.f;
@@ -154,12 +176,15 @@ __global__ __launch_bounds__(TH) void layernorm_fwd_rows_kernel(const T *__restr
         for (int p = 0; p < NP; ++p) {
             const int c = (p * TH + threadIdx.x) * V;
             if (c < d) {
-                load_pack<T, V>(xr + c, xv[p]);
 #pragma unroll
-                for (int i = 0; i < V; ++i) s += xv[p][i];
+                for (int i = 0; i < V; ++i) {
+                    xv[p][i] = to_f32(nxt[p].v[i]);
+                    s += xv[p][i];
+                }
             }
         }
-        const float mean = block_sum(s, red) / (float)d;
+        if (row + gridDim.x < (size_t)rows) request(row + gridDim.x);
+        const float mean = sum_all(s, 0) / (float)d;
         float q = 0.f;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
@@ -169,7 +194,7 @@ __global__ __launch_bounds__(TH) void layernorm_fwd_rows_kernel(const T *__restr
                 for (int i = 0; i < V; ++i) q += (xv[p][i] - mean) * (xv[p][i] - mean);
             }
         }
-        const float var = block_sum(q, red) / (float)d;
+        const float var = sum_all(q, 1) / (float)d;
         const float rstd = rsqrtf(var + eps);
         if (threadIdx.x == 0) {
             mean_out[row] = mean;
@@ -234,6 +259,95 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const T *__restri
     }
 }
 
+// The same with a block walking over many rows: dy, x and the residual of a row are read once and kept in
+// registers, the gains too, the next row is requested before this row's block-wide sums, and the two sums share one
+// barrier (two scratch rows used in turn).  d <= TH * V * NP.
+template <class T, int V, int TH, int NP>
+__global__ __launch_bounds__(TH) void layernorm_bwd_dx_rows_kernel(const T *__restrict__ dy, const T *__restrict__ x,
+                                                                   const float *__restrict__ mean,
+                                                                   const float *__restrict__ rstd,
+                                                                   const float *__restrict__ g, const T *resid, T *dx,
+                                                                   int rows, int d) {
+    __shared__ float red[2][2][16];
+    float gv[NP][V];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int c = (p * TH + threadIdx.x) * V;
+        if (c < d) {
+#pragma unroll
+            for (int q = 0; q < V / 4; ++q) {
+                float t4[4];
+                load_pack<float, 4>(g + c + 4 * q, t4);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) gv[p][4 * q + i] = t4[i];
+            }
+        }
+    }
+    Pack<T, V> na[NP], nx[NP], nr[NP];
+    float nmu = 0.f, nrs = 0.f;
+    auto request = [&](size_t row) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+                na[p] = *reinterpret_cast<const Pack<T, V> *>(dy + row * (size_t)d + c);
+                nx[p] = *reinterpret_cast<const Pack<T, V> *>(x + row * (size_t)d + c);
+                nr[p] = *reinterpret_cast<const Pack<T, V> *>(resid + row * (size_t)d + c);
+            }
+        }
+        nmu = mean[row];
+        nrs = rstd[row];
+    };
+    if (blockIdx.x < (unsigned)rows) request(blockIdx.x);
+    int turn = 0;
+    for (size_t row = blockIdx.x; row < (size_t)rows; row += gridDim.x, turn ^= 1) {
+        float gd[NP][V], xh[NP][V], r[NP][V];
+        const float rs = nrs, mu = nmu;
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    gd[p][i] = to_f32(na[p].v[i]) * gv[p][i];
+                    xh[p][i] = (to_f32(nx[p].v[i]) - mu) * rs;
+                    r[p][i] = to_f32(nr[p].v[i]);
+                    s1 += gd[p][i];
+                    s2 += gd[p][i] * xh[p][i];
+                }
+            }
+        }
+        if (row + gridDim.x < (size_t)rows) request(row + gridDim.x);
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        if ((threadIdx.x & 63) == 0) {
+            red[turn][0][threadIdx.x >> 6] = s1;
+            red[turn][1][threadIdx.x >> 6] = s2;
+        }
+        __syncthreads();
+        float t1 = 0.f, t2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < TH / 64; ++i) {
+            t1 += red[turn][0][i];
+            t2 += red[turn][1][i];
+        }
+        t1 /= (float)d;
+        t2 /= (float)d;
+        T *dxr = dx + row * (size_t)d;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+                float o[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i) o[i] = r[p][i] + rs * (gd[p][i] - t1 - xh[p][i] * t2);
+                store_pack<T, V>(dxr + c, o);
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Column sums, pass 1: block (32 column-threads x 8 row-threads) reduces kColsumRows rows of a
 // strip of 32*V columns into partial[row_chunk][2][cols].
@@ -287,17 +401,31 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict
     }
 }
 
-__global__ void colsum_final_kernel(const float *__restrict__ partial, int chunks, int cols, float beta,
-                                    float *out0, float *out1) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= cols) return;
+// Pass 2: block = 64 columns x 4 groups of row chunks (group q adds chunks q, q + 4, ...), combined through LDS in
+// group order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partial, int chunks, int cols,
+                                                           float beta, float *out0, float *out1) {
+    __shared__ float red[2][4][64];
+    const int tx = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + tx;
     float t0 = 0.f, t1 = 0.f;
-    for (int k = 0; k < chunks; ++k) {
-        t0 += partial[((size_t)k * 2 + 0) * cols + c];
-        if (out1) t1 += partial[((size_t)k * 2 + 1) * cols + c];
+    if (c < cols) {
+        for (int k = q; k < chunks; k += 4) {
+            t0 += partial[((size_t)k * 2 + 0) * cols + c];
+            if (out1) t1 += partial[((size_t)k * 2 + 1) * cols + c];
+        }
     }
-    out0[c] = (beta == 0.f ? 0.f : beta * out0[c]) + t0;
-    if (out1) out1[c] = (beta == 0.f ? 0.f : beta * out1[c]) + t1;
+    red[0][q][tx] = t0;
+    red[1][q][tx] = t1;
+    __syncthreads();
+    if (q == 0 && c < cols) {
+        t0 = (red[0][0][tx] + red[0][1][tx]) + (red[0][2][tx] + red[0][3][tx]);
+        out0[c] = (beta == 0.f ? 0.f : beta * out0[c]) + t0;
+        if (out1) {
+            t1 = (red[1][0][tx] + red[1][1][tx]) + (red[1][2][tx] + red[1][3][tx]);
+            out1[c] = (beta == 0.f ? 0.f : beta * out1[c]) + t1;
+        }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -451,7 +579,18 @@ void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const f
     if (rows == 0) return;
     constexpr int V = VecOf<T>::N;
     ProfScope scope("layernorm_bwd_dx_kernel", 14.0 * rows * d, 4.0 * sizeof(T) * rows * (double)d, s);
-    if (d % V == 0 && aligned16(dy) && aligned16(x) && aligned16(resid) && aligned16(dx))
+    const bool vec = d % V == 0 && aligned16(dy) && aligned16(x) && aligned16(resid) && aligned16(dx);
+    if (vec && aligned16(g) && d <= 1024 * V * 4) {
+#define LGA_LNB_ROWS(TH, NP) \
+        hipLaunchKernelGGL((layernorm_bwd_dx_rows_kernel<T, V, TH, NP>), dim3((unsigned)std::min(rows, 256 * (2048 / TH))), \
+                           dim3(TH), 0, s, dy, x, mean, rstd, g, resid, dx, rows, d)
+        if (d <= 256 * V) LGA_LNB_ROWS(256, 1);
+        else if (d <= 512 * V) LGA_LNB_ROWS(512, 1);
+        else if (d <= 1024 * V) LGA_LNB_ROWS(1024, 1);
+        else if (d <= 1024 * V * 2) LGA_LNB_ROWS(1024, 2);
+        else LGA_LNB_ROWS(1024, 4);
+#undef LGA_LNB_ROWS
+    } else if (vec)
         hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
                            dx, d);
     else
@@ -496,7 +635,7 @@ void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd,
                                    cols, ld, partial);
         }
     }
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, partial, chunks, cols, beta,
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 63) / 64), dim3(256), 0, s, partial, chunks, cols, beta,
                        out0, out1);
 }
 template void launch_colsum<float>(const float *, const float *, const float *, const float *, int, int, int, float,
