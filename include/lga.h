@@ -107,7 +107,7 @@ typedef struct lga_config {
     int32_t attention;    /* enum lga_attention: LGA_ATTN_CAUSAL (0) decoder, LGA_ATTN_FULL encoder (no mask) */
     int32_t offload_checkpoints; /* 1: the layer-boundary activations (activation checkpoints, section 2.5) live in
                              pinned host memory that the library allocates; the device keeps two boundary-sized
-                             slots (appendix C, "CPU-GPU transfers": checkpoint offload).  In the layered order each
+                             slots (appendix C.5, "CPU-GPU transfers": checkpoint offload).  In the layered order each
                              boundary crosses the bus once per pass as one transfer of all micro-batches, on a second
                              stream of the library's own (default priority): to the host beside the next layer's
                              forward sweep, back beside the previous layer's backward sweep.  lga_checkpoint then
@@ -184,7 +184,7 @@ int lga_checkpoint(lga_stack *stack, int32_t boundary, const void **dev_ptr, siz
  * Same kernels as the layered calls.  Requires retain_grads == 1 and group == 1. */
 int lga_step_mbmajor(lga_stack *stack, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam);
 
-/* Modular layer sets (section 3, modular pipeline parallelism: a device holds layers k, k + n_l, ... and each
+/* Modular layer sets (section 4, modular pipeline parallelism: a device holds layers k, k + n_l, ... and each
  * layer's input arrives from another device).  One layer's share of the layer-major sweeps:
  *
  * lga_forward_layer   runs layer `layer` over all n_micro micro-batches (in groups, like lga_forward_layered).

@@ -295,7 +295,7 @@ void join_aux(lga_stack *st) {
     for (size_t i = 0; i < st->w16_pending.size(); ++i) wait_w16(st, (int)i);
     for (size_t i = 0; i < st->grad_pending.size(); ++i) wait_grad(st, (int)i);
 }
-// ---- checkpoint offload (appendix C, "CPU-GPU transfers") ------------------------------------------------
+// ---- checkpoint offload (appendix C.5, "CPU-GPU transfers") ------------------------------------------------
 // Transfers run on the second stream, ordered against the main stream by one event per device slot.
 void wait_slot(lga_stack *st, int slot) {
     if (!st->ck_pending[slot]) return;
@@ -617,7 +617,7 @@ template <class T> int backward_layered_t(lga_stack *st, const void *dy, void *d
 }
 
 // One layer's share of the layer-major sweeps, with the layer's input (forward) and output gradient (backward)
-// arriving from outside the stack: what a device of the modular pipeline (section 3) runs for each of its layers.
+// arriving from outside the stack: what a device of the modular pipeline (section 4) runs for each of its layers.
 template <class T> int forward_layer_t(lga_stack *st, int l, const void *x_in, void *x_out) {
     const lga_config &c = st->cfg;
     const size_t act_bytes = st->T * c.d_model * sizeof(T);

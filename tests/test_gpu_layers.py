@@ -1,6 +1,6 @@
 """GPU tests of the per-layer entry points (lga_forward_layer / lga_backward_layer): one layer's share of the
 layer-major sweeps with its input and output gradient arriving from outside the stack, as on a device of the
-modular pipeline (section 3), where the layers a device holds are not neighbours.
+modular pipeline (section 4), where the layers a device holds are not neighbours.
 
   * chained over layers 0 .. L-1 and back they reproduce lga_forward_layered / lga_backward_layered bit for bit;
   * fed with unrelated inputs per layer, in an interleaved order, each layer matches the fp64 oracle's

@@ -244,7 +244,7 @@ def test_overlap_mode_changes_timing_not_results(retain, param_buffers, overlap)
 
 @pytest.mark.parametrize("layers,group,overlap,dtype", [(4, 2, 0, "bf16"), (3, 1, 3, "bf16"), (1, 4, 0, "bf16"), (5, 2, 0, "fp32")])
 def test_checkpoint_offload_changes_placement_not_results(layers, group, overlap, dtype):
-    """Boundary activations in pinned host memory, two slots on the device (appendix C, "CPU-GPU transfers"): every
+    """Boundary activations in pinned host memory, two slots on the device (appendix C.5, "CPU-GPU transfers"): every
     output - including every boundary, now read back from the host - is bit-identical to the resident run, over two
     consecutive steps on one stack (the slots carry state from the backward pass into the next forward pass), and
     the device arena shrinks by the boundaries that moved out."""
