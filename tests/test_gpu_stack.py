@@ -46,8 +46,8 @@ def compare_with_oracle(w, got, ref, gate, adam, zero_init=True):
             worst[f"g{l}.{name}"] = rel_err(got["grads"][l][sl[name]], ref.grads[l][sl[name]])
         q_bias = slice(sl["b_qkv"].start, sl["b_qkv"].start + d)
         if w.dtype == "fp32":
-            assert np.linalg.norm(got["grads"][l][k_bias]) < 1e-4 * np.linalg.norm(got["grads"][l][q_bias])
-        assert np.linalg.norm(ref.grads[l][k_bias]) < 1e-12 * np.linalg.norm(ref.grads[l][q_bias])
+            assert np.linalg.norm(got["grads"][l][k_bias]) <= 1e-4 * np.linalg.norm(got["grads"][l][q_bias])
+        assert np.linalg.norm(ref.grads[l][k_bias]) <= 1e-12 * np.linalg.norm(ref.grads[l][q_bias])
     if adam is not None:
         for l in range(w.n_layers):
             worst[f"w{l}"] = rel_err(got["params"][l][keep], ref.new_params[l][keep])
@@ -289,6 +289,31 @@ def test_three_consecutive_steps_match_oracle(dtype):
         p, m, v = ref.new_params, ref.new_m, ref.new_v
     got = run_gpu_step(w, x, G, params, group=2, retain=1, adam=adam, steps=3)
     compare_with_oracle(w, got, ref, GATE[dtype], adam, zero_init=False)
+
+
+@pytest.mark.parametrize("name,args,group", [
+    ("single_position", (1, 64, 2, 256, 1, 8, 2, "bf16"), 1),          # sequences of one token: attention returns V
+    ("single_everything", (1, 32, 1, 128, 8, 1, 1, "bf16"), 1),        # one layer, one head, one micro-batch
+    ("narrow_ffn", (2, 64, 2, 72, 24, 1, 3, "bf16"), 3),               # d_I = 72: neither 4 d nor a multiple of 32
+    ("wide_ffn_fp32", (1, 12, 3, 100, 7, 2, 2, "fp32"), 2),            # fp32: nothing has to be a multiple of anything
+    ("many_micro_batches", (1, 32, 1, 128, 8, 1, 24, "bf16"), 8),      # 24 micro-batches in groups of 8
+])
+def test_degenerate_and_unusual_shapes_match_oracle(name, args, group):
+    w = S.Workload(name, *args)
+    x, G, params = S.make_inputs(w, seed=53, weight_std=0.05, bias_std=0.02)
+    adam = adam_struct()
+    ref = O.step_microbatch_major(x, G, params, oracle_shape(w), oracle_adam(adam))
+    got = run_gpu_step(w, x, G, params, group=group, retain=1, adam=adam)
+    compare_with_oracle(w, got, ref, GATE[w.dtype], adam, zero_init=False)
+    if w.seq_len == 1:
+        # with one position per sequence the attention output is V itself: boundary 1 can be written down directly
+        p0 = O.unflatten_layer(params[0].astype(np.float64), w.d_model, w.d_ff)
+        h, _, _ = O.layer_norm(x.astype(np.float64), p0["ln1_g"], p0["ln1_b"], 1e-5)
+        v = (h @ p0["w_qkv"] + p0["b_qkv"])[..., 2 * w.d_model:]
+        x1 = x + v @ p0["w_o"] + p0["b_o"]
+        h2, _, _ = O.layer_norm(x1, p0["ln2_g"], p0["ln2_b"], 1e-5)
+        y = x1 + O.gelu(h2 @ p0["w_1"] + p0["b_1"]) @ p0["w_2"] + p0["b_2"]
+        assert rel_err(got["boundaries"][1], y) < GATE[w.dtype]
 
 
 def test_runs_are_bit_reproducible():
