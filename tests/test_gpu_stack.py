@@ -316,6 +316,41 @@ def test_degenerate_and_unusual_shapes_match_oracle(name, args, group):
         assert rel_err(got["boundaries"][1], y) < GATE[w.dtype]
 
 
+@pytest.mark.parametrize("overlap,offload", [(0, 0), (3, 1)])
+def test_work_runs_on_the_callers_stream(overlap, offload):
+    """lga_config.stream: everything is enqueued on the caller's HIP stream (and ordered on it when the library's own
+    second stream is in play), so synchronising that stream alone makes every result visible."""
+    w = S.Workload("stream_bf16", 3, 64, 2, 256, 48, 1, 4, "bf16")
+    x, G, params = S.make_inputs(w, seed=61)
+    adam = adam_struct()
+    base = run_gpu_step(w, x, G, params, group=2, retain=0, adam=adam)
+    dt = B.LGA_BF16
+    stream = torch.cuda.Stream()
+    cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt, group=2,
+                        retain_grads=0, stream=stream.cuda_stream, overlap=overlap, param_buffers=2 if overlap else 0,
+                        offload_checkpoints=offload)
+    from gpu_helpers import to_dev, empty_dev, to_host
+    xd, Gd = to_dev(x, dt), to_dev(G, dt)
+    yd, dxd = empty_dev(x.shape, dt), empty_dev(x.shape, dt)
+    torch.cuda.synchronize()
+    st = B.Stack(cfg, np.concatenate(params))
+    try:
+        st.forward_layered(xd.data_ptr(), yd.data_ptr())
+        st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam)
+        stream.synchronize()                   # the caller's stream only
+        assert np.array_equal(to_host(yd), base["y"])
+        assert np.array_equal(to_host(dxd), base["dx"])
+        for l in range(w.n_layers):
+            ptr, n = st.params(l)
+            assert np.array_equal(B.read_device(ptr, n).astype(np.float64), base["params"][l]), l
+        for bnd in range(w.n_layers + 1):
+            ptr, _ = st.checkpoint(bnd)
+            got = S.from_bf16_bits(B.read_device(ptr, x.size, "uint16")).astype(np.float64).reshape(x.shape)
+            assert np.array_equal(got, base["boundaries"][bnd]), bnd
+    finally:
+        st.close()
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
