@@ -351,6 +351,63 @@ def test_work_runs_on_the_callers_stream(overlap, offload):
         st.close()
 
 
+@pytest.mark.skip(reason="graph capture is not a supported use yet: this small step was captured and replayed bit-identically, "
+                         "but capturing a benchmark-sized step (cfg1, large-tile GEMMs with 160 KB of dynamic LDS) did not "
+                         "return within three minutes and the cause is not established; kept off the GPU until it is")
+def test_a_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """The whole step (copies, kernels, no memsets) enqueued on the caller's stream under graph capture; the graph is
+    replayed three times with eager work and synchronisations in between, and every replay is compared with the
+    same sequence of eager steps (Adam's step number is baked into the captured launch, so the eager run repeats it)."""
+    w = S.Workload("graph_bf16", 2, 64, 2, 256, 48, 1, 4, "bf16")
+    x, G, params = S.make_inputs(w, seed=67)
+    dt = B.LGA_BF16
+    from gpu_helpers import to_dev, empty_dev, to_host
+
+    def fresh(stream_ptr):
+        cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt, group=2,
+                            retain_grads=0, stream=stream_ptr)
+        return B.Stack(cfg, np.concatenate(params))
+
+    xd, Gd = to_dev(x, dt), to_dev(G, dt)
+    adam1, adam2 = adam_struct(step=1), adam_struct(step=2)
+    # eager reference: one step with t = 1 (the warm-up below), then three with t = 2
+    ref = fresh(None)
+    ys, ws = [], []
+    yr, dxr = empty_dev(x.shape, dt), empty_dev(x.shape, dt)
+    try:
+        for t in (adam1, adam2, adam2, adam2):
+            ref.forward_layered(xd.data_ptr(), yr.data_ptr())
+            ref.backward_layered(Gd.data_ptr(), dxr.data_ptr(), t)
+            torch.cuda.synchronize()
+            ys.append((to_host(yr), to_host(dxr)))
+            ptr, n = ref.params(0)
+            ws.append(B.read_device(ptr, n).copy())
+    finally:
+        ref.close()
+    stream = torch.cuda.Stream()
+    st = fresh(stream.cuda_stream)
+    yd, dxd = empty_dev(x.shape, dt), empty_dev(x.shape, dt)
+    try:
+        st.forward_layered(xd.data_ptr(), yd.data_ptr())          # warm-up outside the graph (also sets kernel attributes)
+        st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam1)
+        stream.synchronize()
+        assert np.array_equal(to_host(yd), ys[0][0])
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            st.forward_layered(xd.data_ptr(), yd.data_ptr())
+            st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam2)
+        for k in (1, 2, 3):
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(to_host(yd), ys[k][0]), k
+            assert np.array_equal(to_host(dxd), ys[k][1]), k
+            ptr, n = st.params(0)
+            assert np.array_equal(B.read_device(ptr, n), ws[k]), k
+            scratch = torch.randn(1 << 16, device="cuda").sum().item()      # eager work between the replays
+    finally:
+        st.close()
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
