@@ -552,7 +552,9 @@ void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, floa
     if (rows == 0) return;
     constexpr int V = VecOf<T>::N;
     ProfScope scope("layernorm_fwd_kernel", 8.0 * rows * d, 2.0 * sizeof(T) * rows * (double)d, s);
-    if (d % V == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b) && d <= 1024 * V * 4) {
+    // (rows wider than two packs per thread of a 1024-thread block would leave one block per CU: the one-row-per-block
+    // kernel, with its many small blocks, is faster there)
+    if (d % V == 0 && aligned16(x) && aligned16(y) && aligned16(g) && aligned16(b) && d <= 1024 * V * 2) {
         // rows are dealt to a fixed number of blocks (enough to fill every CU), which keep what they reuse in registers
 #define LGA_LN_ROWS(TH, NP) \
         hipLaunchKernelGGL((layernorm_fwd_rows_kernel<T, V, TH, NP, true>), dim3((unsigned)std::min(rows, 256 * (2048 / TH))), \
@@ -560,8 +562,7 @@ void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, floa
         if (d <= 256 * V) LGA_LN_ROWS(256, 1);
         else if (d <= 512 * V) LGA_LN_ROWS(512, 1);
         else if (d <= 1024 * V) LGA_LN_ROWS(1024, 1);
-        else if (d <= 1024 * V * 2) LGA_LN_ROWS(1024, 2);
-        else LGA_LN_ROWS(1024, 4);
+        else LGA_LN_ROWS(1024, 2);
 #undef LGA_LN_ROWS
     } else if (d % V == 0 && aligned16(x) && aligned16(y))
         hipLaunchKernelGGL((layernorm_fwd_kernel<T, V>), dim3(rows), dim3(256), 0, s, x, g, b, y, mean, rstd, d, eps);
@@ -580,15 +581,14 @@ void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const f
     constexpr int V = VecOf<T>::N;
     ProfScope scope("layernorm_bwd_dx_kernel", 14.0 * rows * d, 4.0 * sizeof(T) * rows * (double)d, s);
     const bool vec = d % V == 0 && aligned16(dy) && aligned16(x) && aligned16(resid) && aligned16(dx);
-    if (vec && aligned16(g) && d <= 1024 * V * 4) {
+    if (vec && aligned16(g) && d <= 1024 * V * 2) {
 #define LGA_LNB_ROWS(TH, NP) \
         hipLaunchKernelGGL((layernorm_bwd_dx_rows_kernel<T, V, TH, NP>), dim3((unsigned)std::min(rows, 256 * (2048 / TH))), \
                            dim3(TH), 0, s, dy, x, mean, rstd, g, resid, dx, rows, d)
         if (d <= 256 * V) LGA_LNB_ROWS(256, 1);
         else if (d <= 512 * V) LGA_LNB_ROWS(512, 1);
         else if (d <= 1024 * V) LGA_LNB_ROWS(1024, 1);
-        else if (d <= 1024 * V * 2) LGA_LNB_ROWS(1024, 2);
-        else LGA_LNB_ROWS(1024, 4);
+        else LGA_LNB_ROWS(1024, 2);
 #undef LGA_LNB_ROWS
     } else if (vec)
         hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
