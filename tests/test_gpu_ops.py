@@ -200,7 +200,12 @@ def test_gemm_empty_and_rejected_arguments():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("dt,rows,d", [(F32, 37, 70), (F32, 5, 1), (BF16, 130, 256), (BF16, 33, 1000), (BF16, 3, 12288)])
+@pytest.mark.parametrize("dt,rows,d", [
+    (F32, 37, 70), (F32, 5, 1), (BF16, 130, 256), (BF16, 33, 1000), (BF16, 3, 12288),
+    # more rows than blocks (a block walks over several rows, requesting the next one early), every block size,
+    # a ragged second pack, a row too wide for the row-walking kernels, the vector path of the fp32 mode
+    (BF16, 5000, 3072), (BF16, 3000, 8192), (BF16, 700, 10000), (BF16, 40, 25600), (F32, 2500, 4096), (BF16, 2100, 768),
+])
 def test_layernorm_forward_and_backward(dt, rows, d):
     rng = np.random.default_rng(rows * 1000 + d)
     x = rnd(rng, (rows, d), dt, 2.0) + (0.5 if dt == F32 else 0.0)
