@@ -191,7 +191,7 @@ def main():
         # calibration, measured live: what the chip sustains with nothing but MFMAs on register operands with random
         # mantissas and signs (its power management holds the clock below nominal on such data)
         import ctypes as C
-        sink = torch.empty(65536, device="cuda")
+        sink = torch.ones(65536 + (4 << 20) // 4, device="cuda")
         tf = C.c_double()
         B.check(B.lib.lga_op_mfma_rate(800000, 0, sink.data_ptr(), C.byref(tf), None))
         roof["mfma_only_rate_random_operands"] = tf.value

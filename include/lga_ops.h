@@ -99,8 +99,11 @@ int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_
  * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 16 v_mfma_f32_32x32x16_bf16 back to
  * back, no memory traffic.  mode 0: operand values around +-1 with random mantissas and signs (what the power
  * management allows on realistic data); 1: all operand values 1.0 (approaches the nominal peak); 2: as 0, with the
- * operands re-read from LDS as a 256 x 256 GEMM tile of 2 x 2 wavefronts must (eight 16-byte reads per 16 MFMAs).
- * sink: device, >= 65536 floats, overwritten.  Synchronous: returns after the kernel has run.  tflops: host. */
+ * operands re-read from LDS as a 256 x 256 GEMM tile of 2 x 2 wavefronts must (eight 16-byte reads per 16 MFMAs);
+ * 3: as 2, plus the direct-to-LDS loads that fill such a tile (64 KB per 64 MFMAs of each wavefront, from a 4 MB
+ * window that stays in L2); 4: as 3, plus a workgroup barrier per k tile.
+ * sink: device, >= 65536 floats + 4 MB (1 114 112 floats): the first 65536 are overwritten, modes 3 and 4 read the
+ * rest (any finite contents).  Synchronous: returns after the kernel has run.  tflops: host. */
 int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream);
 
 #ifdef __cplusplus

@@ -3,7 +3,10 @@
 // random mantissas and signs the chip's power management holds the clock lower, and that rate - not the
 // nominal one - is what a GEMM on real activations can approach.  A third mode re-reads the operands from LDS the
 // way a 2 x 2-wavefront 256 x 256 GEMM tile must (eight 16-byte reads per 16 MFMAs, issued 16 MFMAs ahead): what is
-// left once the operands have to come from somewhere.  Used by the benchmark tools only.
+// left once the operands have to come from somewhere.  Modes 3 and 4 add what fills LDS in a GEMM - direct-to-LDS
+// loads of 64 KB per 64 MFMAs of each wavefront, from a 4 MB window that stays in L2 - and the barrier per k tile:
+// together the structural ceiling of an output-stationary 256 x 256 tile kernel on this chip, before a byte has
+// come from HBM.  Used by the benchmark tools only.
 #include <cstdio>
 
 #include "kernels.h"
@@ -14,16 +17,20 @@ namespace {
 
 constexpr int kLdsChunks = 8192;        // 128 KB of operand data in LDS (mode 2)
 
-// mode 0: random register operands; 1: constant register operands; 2: random operands re-read from LDS
+// mode 0: random register operands; 1: constant register operands; 2: random operands re-read from LDS;
+// 3: as 2, plus direct-to-LDS loads at a GEMM tile's rate; 4: as 3, plus a barrier per k tile
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+constexpr int kDmaWindow = 4 << 20;       // bytes of source data the loads of modes 3 and 4 walk over (L2-resident)
+
 template <int MODE>
-__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iters) {
+__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const unsigned *src, int iters) {
     constexpr int constant_operands = MODE == 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     u32x4 *lds = reinterpret_cast<u32x4 *>(smem);
     // operand registers: values around +-1 with random mantissas and signs, or all ones
     bf16x8 a[4], b[4];
     unsigned s = (threadIdx.x + 1) * 2654435761u ^ (blockIdx.x * 40503u);
-    if constexpr (MODE == 2) {
+    if constexpr (MODE >= 2) {
         for (int i = threadIdx.x; i < kLdsChunks; i += 256) {
             u32x4 v;
 #pragma unroll
@@ -57,29 +64,49 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iter
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
     bf16x8 a2[4], b2[4];
     int off = threadIdx.x;
+    // operand data lives in the first half of the 128 KB of LDS; modes 3 and 4 stream into the second half
     auto fetch = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[4]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            fa[i] = __builtin_bit_cast(bf16x8, lds[(off + 256 * i) & (kLdsChunks - 1)]);
-            fb[i] = __builtin_bit_cast(bf16x8, lds[(off + 256 * (i + 4) + 1024) & (kLdsChunks - 1)]);
+            fa[i] = __builtin_bit_cast(bf16x8, lds[(off + 256 * i) & (kLdsChunks / 2 - 1)]);
+            fb[i] = __builtin_bit_cast(bf16x8, lds[(off + 256 * (i + 4) + 1024) & (kLdsChunks / 2 - 1)]);
         }
         off += 2048;
     };
-    for (int it = 0; it < iters; it += 2) {
-        // two groups of 16 MFMAs per turn; in mode 2 each group's operands are read while the other group runs
-        if constexpr (MODE == 2) fetch(a2, b2);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned *>(src), 0, kDmaWindow, 0x00020000);
+    unsigned goff = (blockIdx.x * 65536u + wave * 16384u) & (kDmaWindow - 1);
+    for (int it = 0; it < iters; it += 4) {
+        // one "k tile": four groups of 16 MFMAs; in modes >= 2 each group's operands are read while the previous group
+        // runs; in modes >= 3 each wavefront also issues its 16 KB share of the tile's 64 KB of direct-to-LDS loads
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int q = 0; q < 4; ++q) {
+            if constexpr (MODE >= 3) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 4 + j], 0, 0, 0);
-        if constexpr (MODE == 2) fetch(a, b);
+                for (int j = 0; j < 4; ++j)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        rs, (lds_ptr_t)(smem + kLdsChunks * 8 + wave * 16384 + (q * 4 + j) * 1024), 16,
+                        (int)((goff + (q * 4 + j) * 1024 + lane * 16) & (kDmaWindow - 1)), 0, 0, 0);
+            }
+            if constexpr (MODE >= 2) {
+                if (q & 1) fetch(a, b);
+                else fetch(a2, b2);
+            }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(MODE == 2 ? a2[i] : a[i], MODE == 2 ? b2[j] : b[j],
-                                                                         acc[i * 4 + j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((MODE >= 2 && (q & 1)) ? a2[i] : a[i],
+                                                                             (MODE >= 2 && (q & 1)) ? b2[j] : b[j],
+                                                                             acc[i * 4 + j], 0, 0, 0);
+        }
+        goff = (goff + 65536u * 7u) & (kDmaWindow - 1);
+        if constexpr (MODE >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | 15);     // at most one tile's loads in flight
+        if constexpr (MODE == 4) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
     }
     float t = 0.f;
 #pragma unroll
@@ -94,8 +121,10 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iter
 
 extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 2 || iters > (1 << 24) || mode < 0 || mode > 2 || !sink || !tflops) return LGA_ERR_ARG;
-    iters &= ~1;                                            // the loop does two groups of 16 MFMAs per turn
+    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 4 || !sink || !tflops) return LGA_ERR_ARG;
+    iters &= ~3;                                            // the loop does four groups of 16 MFMAs per turn
+    // results go to the first 65536 floats of sink; modes 3 and 4 read the kDmaWindow bytes after them
+    const unsigned *src = reinterpret_cast<const unsigned *>(sink + 65536);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
@@ -108,16 +137,20 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         return LGA_ERR_HIP;
     }
     (void)hipEventRecord(e0, s);
-    if (mode == 0) hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(cus), dim3(256), 0, s, sink, iters);
-    else if (mode == 1) hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(cus), dim3(256), 0, s, sink, iters);
-    else {
-        static bool attr_set = false;
-        if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<2>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, kLdsChunks * 16);
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(cus), dim3(256), kLdsChunks * 16, s, sink, iters);
+    constexpr int kSmem = kLdsChunks * 16;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+        attr_set = true;
+    }
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(mfma_rate_kernel<0>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 1: hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 2: hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
+        case 3: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
+        default: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
     }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);

@@ -116,9 +116,10 @@ def run_mfma(args):
     import ctypes as C
     import torch
     from paper_2106_02679_amd import binding as B
-    sink = torch.empty(65536, device="cuda")
-    what = {1: "constant register operands", 0: "random register operands  ", 2: "random operands via LDS   "}
-    for mode in (1, 0, 2):
+    sink = torch.ones(65536 + (4 << 20) // 4, device="cuda")
+    what = {1: "constant register operands", 0: "random register operands  ", 2: "random operands via LDS   ",
+            3: "... + direct-to-LDS loads ", 4: "... + a barrier per k tile"}
+    for mode in (1, 0, 2, 3, 4):
         for iters in (400000, 4000000):
             tf = C.c_double()
             B.check(B.lib.lga_op_mfma_rate(iters, mode, sink.data_ptr(), C.byref(tf), None))
