@@ -47,6 +47,9 @@ def parse():
                     help="16-bit parameter buffers kept (0 = one per layer); fewer makes the orders differ in restore traffic")
     ap.add_argument("--offload", action="store_true",
                     help="keep the layer-boundary activations in pinned host memory (two slots on the device)")
+    ap.add_argument("--fp16", action="store_true",
+                    help="run the 16-bit configuration in IEEE half instead of bfloat16, with a loss scale of 1024 and "
+                         "the per-layer non-finite test before each Adam step (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=64)
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
@@ -105,7 +108,11 @@ def main():
     if args.n_micro and not args.x_family and args.n_micro != w.n_micro:
         w = S.Workload(f"{w.name}_n{args.n_micro}", w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch,
                        args.n_micro, w.dtype)
-    dt = B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
+    if args.fp16 and w.dtype == "bf16":
+        w = S.Workload(w.name.replace("bf16", "fp16"), w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch,
+                       w.n_micro, "fp16")
+    dt = {"fp32": B.LGA_FP32, "bf16": B.LGA_BF16, "fp16": B.LGA_FP16}[w.dtype]
+    is16 = dt != B.LGA_FP32
     # default group: the benchmark configurations' own, else about 4096 tokens per launch
     default_group = max(1, 4096 // (w.micro_batch * w.seq_len)) if args.x_family else DEFAULT_GROUP[args.config]
     group = args.group or default_group
@@ -119,18 +126,19 @@ def main():
                         overlap=args.overlap, attention=B.LGA_ATTN_CAUSAL if causal else B.LGA_ATTN_FULL,
                         offload_checkpoints=1 if args.offload else 0)
     torch.cuda.set_device(0)
-    tdt = torch.bfloat16 if dt == B.LGA_BF16 else torch.float32
+    tdt = {B.LGA_FP32: torch.float32, B.LGA_BF16: torch.bfloat16, B.LGA_FP16: torch.float16}[dt]
+    loss_scale = 1024.0 if dt == B.LGA_FP16 else 0.0
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     gen = torch.Generator(device="cuda").manual_seed(0)
     x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)
-    dy = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)
+    dy = (torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen) * (loss_scale or 1.0)).to(tdt)
     st = B.Stack(cfg)                     # weights filled on the device: N(0, 0.02^2), gains 1, biases 0
     torch.cuda.synchronize()
 
     marks = []      # per timed step: events at its start, between the sweeps, at its end
 
     def step(t, timed=False):
-        adam = B.lga_adam(1e-3, 0.9, 0.999, 1e-8, t)
+        adam = B.lga_adam(1e-3, 0.9, 0.999, 1e-8, t, loss_scale, 1 if loss_scale else 0)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timed else None
         if timed:
             ev[0].record()
@@ -176,7 +184,7 @@ def main():
     pair_factor = 1.0 if causal else 2.0
     flops_paper = 8.0 * tokens * P * w.n_layers + 9.0 * pair_factor * seqs * w.n_layers * w.seq_len ** 2 * w.d_model
     flops_model = 6.0 * tokens * P * w.n_layers + 7.0 * pair_factor * seqs * w.n_layers * w.seq_len ** 2 * w.d_model
-    peak = PEAK_BF16_TFLOPS if dt == B.LGA_BF16 else PEAK_FP32_TFLOPS
+    peak = PEAK_BF16_TFLOPS if is16 else PEAK_FP32_TFLOPS          # bf16 and fp16 MFMA: the same dense peak
 
     dom = stats[0]
     per_launch_ms = dom["ms"] / dom["launches"]
@@ -184,7 +192,7 @@ def main():
     if is_hbm:
         roof = {"bound": "hbm", "achieved": dom["bytes"] / dom["ms"] / 1e6, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
     else:
-        roof = {"bound": "mfma" if dt == B.LGA_BF16 else "alu", "achieved": dom["flops"] / dom["ms"] / 1e9,
+        roof = {"bound": "mfma" if is16 else "alu", "achieved": dom["flops"] / dom["ms"] / 1e9,
                 "peak": peak, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     if roof["bound"] == "mfma":
@@ -225,7 +233,7 @@ def main():
         "restores_per_step": restores,
         "device_arena_bytes": B.arena_bytes(cfg), "pinned_host_bytes": B.host_bytes(cfg),
         # checkpoint offload: every boundary goes to the host once, all but the top two come back once
-        "pcie_bytes_per_step": (2 * w.n_layers * tokens * w.d_model * (2 if dt == B.LGA_BF16 else 4)) if args.offload else 0,
+        "pcie_bytes_per_step": (2 * w.n_layers * tokens * w.d_model * (2 if is16 else 4)) if args.offload else 0,
         "tflops_executed": flops_exec / ms_step / 1e9,
         "pct_peak_executed": 100.0 * flops_exec / ms_step / 1e9 / peak,
         "pct_peak_paper_flops": 100.0 * flops_paper / ms_step / 1e9 / peak,     # 8 p + 9 s^2 d accounting

@@ -28,7 +28,7 @@
  * Gradients, moments and parameters are all exposed in this same layout.
  *
  * Activation tensors x, y, dy, dx are [n_micro, micro_batch, seq_len, d_model], contiguous,
- * of the configured dtype (float, or bfloat16 stored as 16-bit).
+ * of the configured dtype (float, or bfloat16 / IEEE half stored as 16-bit).
  */
 #ifndef LGA_H
 #define LGA_H
@@ -43,8 +43,12 @@ extern "C" {
 typedef struct lga_stack lga_stack; /* opaque, library-owned */
 
 /* Activation / GEMM-input type.  Master weights, gradients and Adam moments are always fp32
- * (section 2.2: bulk of the computation in 16 bits, weights stored and updated in fp32). */
-enum lga_dtype { LGA_FP32 = 0, LGA_BF16 = 1 };
+ * (section 2.2: bulk of the computation in 16 bits, weights stored and updated in fp32).
+ * LGA_BF16 and LGA_FP16 run the same kernels on the two 16-bit formats section 2.2 names: bfloat16 has fp32's exponent
+ * range; IEEE half (5 exponent bits, largest value 65504) has three more mantissa bits and needs the gradients scaled
+ * (lga_adam.loss_scale, lga_loss_scaler_update) so that they neither underflow nor overflow.  Every shape rule stated
+ * below for "the 16-bit modes" holds for both. */
+enum lga_dtype { LGA_FP32 = 0, LGA_BF16 = 1, LGA_FP16 = 2 };
 
 enum lga_status {
     LGA_OK = 0,
@@ -118,11 +122,38 @@ typedef struct lga_config {
 } lga_config;
 
 /* Adam hyper-parameters (section 5 "Training": Adam assumed; Kingma-Ba form with bias
- * correction, no weight decay, eps added to sqrt(v_hat)).  step is t >= 1. */
+ * correction, no weight decay, eps added to sqrt(v_hat)).  step is t >= 1.
+ * Gradient scaling (section 2.2: with half precision the gradients are scaled dynamically against underflow and
+ * overflow).  The caller multiplies the output gradient dy by loss_scale before the backward pass; every Adam step
+ * then divides the accumulated fp32 gradient by loss_scale before using it (0 and 1 both mean no scaling, and leave
+ * the arithmetic exactly as without it).  lga_grads keeps returning the scaled gradient.
+ * skip_nonfinite = 1: before a layer is updated its accumulated gradient is tested for infinities and NaNs; if it
+ * holds any, that layer's update is left out as a whole - parameters, moments and 16-bit copies keep their values -
+ * and the layer is reported by lga_nonfinite_layers.  With the per-layer update fused into the layer-major backward
+ * pass the decision is per layer by necessity: layers above the one whose gradient overflowed have already been
+ * updated, and every layer below it receives the non-finite activation gradient and is skipped too.  A caller that
+ * wants all-or-nothing steps sets retain_grads, runs the backward pass unfused, asks lga_grads_nonfinite, and only
+ * when that reports no layer calls lga_adam_step_layer for every layer. */
 typedef struct lga_adam {
     float lr, beta1, beta2, eps;
     int32_t step;
+    float loss_scale;       /* 0 or 1: none */
+    int32_t skip_nonfinite; /* 0 or 1 */
 } lga_adam;
+
+/* Dynamic loss scale, host side (section 2.2; the usual rule of mixed precision training: back off at once when
+ * a step overflowed, grow again after growth_interval steps in a row that did not).
+ *   overflowed != 0:  scale = max(scale * backoff, min_scale), good_steps = 0
+ *   else:             good_steps += 1; when it reaches growth_interval: scale = min(scale * growth, max_scale),
+ *                     good_steps = 0
+ * Typical: scale 65536, growth 2, backoff 0.5, growth_interval 2000, min_scale 1, max_scale 2^24.
+ * LGA_ERR_ARG unless scale > 0, growth >= 1, 0 < backoff <= 1, growth_interval >= 1, 0 < min_scale <= max_scale,
+ * good_steps >= 0.  Touches no device. */
+typedef struct lga_loss_scaler {
+    float scale, growth, backoff, min_scale, max_scale;
+    int32_t growth_interval, good_steps;
+} lga_loss_scaler;
+int lga_loss_scaler_update(lga_loss_scaler *scaler, int32_t overflowed);
 
 /* Create a stack.
  *  cfg          host, copied.
@@ -230,6 +261,19 @@ int lga_arena_bytes(const lga_config *cfg, uint64_t *bytes);
 /* Bytes of pinned host memory lga_init_stack would allocate for cfg: the boundary activations when
  * offload_checkpoints is set, else 0 (host arithmetic only). */
 int lga_host_bytes(const lga_config *cfg, uint64_t *bytes);
+
+/* Which layers' most recent Adam step with skip_nonfinite = 1 found a non-finite gradient and was left out.
+ *  flags  host, n_layers int32 (1 = left out), or NULL.   count  host, receives how many.
+ * A layer's flag is rewritten by each of its Adam steps that has skip_nonfinite = 1 and is 0 before the first.
+ * Synchronises the stack's stream. */
+int lga_nonfinite_layers(lga_stack *stack, int32_t *flags, int32_t *count);
+
+/* Tests the accumulated gradient of every layer that currently holds one (all layers after an unfused backward
+ * pass with retain_grads = 1; else the one layer whose gradient lga_grads would return) for infinities and NaNs.
+ *  flags  host, n_layers int32 (1 = holds a non-finite value; 0 also for layers without a gradient), or NULL.
+ *  count  host, receives how many layers were flagged.
+ * Changes nothing but the flags lga_nonfinite_layers reports.  Synchronises the stack's stream. */
+int lga_grads_nonfinite(lga_stack *stack, int32_t *flags, int32_t *count);
 
 /* p_l for cfg: 4 d^2 + 2 d d_I + 9 d + d_I (= 12 d^2 + 13 d when d_I = 4 d, Table B.1). */
 int lga_params_per_layer(const lga_config *cfg, uint64_t *count);

@@ -6,7 +6,8 @@
  * CPU oracle at small, ragged shapes.  Same conventions as lga.h: int status codes, validation on
  * the host before any launch, `stream` is a borrowed hipStream_t (NULL = default), calls enqueue
  * and return.  dtype is enum lga_dtype and selects the storage type of activation tensors
- * (float or bfloat16); statistics, biases, gains and gradients of parameters are always float.
+ * (float, bfloat16 or IEEE half); statistics, biases, gains and gradients of parameters are always float.
+ * "16-bit" below means LGA_BF16 or LGA_FP16: the same kernels on either format.
  */
 #ifndef LGA_OPS_H
 #define LGA_OPS_H
@@ -32,7 +33,7 @@ enum lga_epilogue {
  * the bulk of the computation).
  *  a_kmajor != 0: A is stored [M][lda], k contiguous; else [K][lda], m contiguous.
  *  b_kmajor != 0: B is stored [N][ldb], k contiguous; else [K][ldb], n contiguous.
- * LGA_FP32: any shape.  LGA_BF16 (MFMA kernel): lda, ldb, ldc, N - and M when A is m-contiguous, K
+ * LGA_FP32: any shape.  16-bit (MFMA kernel): lda, ldb, ldc, N - and M when A is m-contiguous, K
  * when either operand is k-contiguous - must be multiples of 8, all pointers 16-byte aligned, and the layout/epilogue
  * pair must be one that is built: (k,k-major) with any epilogue - the layout the layer stack itself
  * uses for all three GEMM families -, (k,n-major) with STORE/BIAS/BIAS_RESID/BIAS_GELU, (m,n-major) with
@@ -42,13 +43,13 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
                 int32_t ldc, const float *bias, const void *aux, float beta, void *stream);
 
 /* The weight-gradient GEMM as the layer stack runs it (section 3: one accumulation per layer over all micro-batches'
- * tokens): outf[M,N] = beta * outf + sum_k A[m][k] B[n][k], bf16 operands with k contiguous ([M][lda], [N][ldb]), fp32
+ * tokens): outf[M,N] = beta * outf + sum_k A[m][k] B[n][k], 16-bit operands (dtype) with k contiguous ([M][lda], [N][ldb]), fp32
  * result.  When the output has too few 256 x 256 tiles to occupy the chip (narrow layers) and `scratch` (device, at
  * least lga_op_gemm_splitk_slices(M, N, K) * M * N floats, 16-byte aligned) is given, the k range is cut into that many
  * slices that run as separate workgroups and are then summed in slice order (deterministic); otherwise, or with
  * scratch == NULL, it is lga_op_gemm with LGA_EPI_ACCUM_F32.  Alignment rules as for lga_op_gemm. */
-int lga_op_gemm_splitk(int32_t M, int32_t N, int32_t K, const void *A, int32_t lda, const void *B, int32_t ldb,
-                       float *outf, int32_t ldc, float beta, float *scratch, uint64_t scratch_floats, void *stream);
+int lga_op_gemm_splitk(int32_t dtype, int32_t M, int32_t N, int32_t K, const void *A, int32_t lda, const void *B,
+                       int32_t ldb, float *outf, int32_t ldc, float beta, float *scratch, uint64_t scratch_floats, void *stream);
 /* Number of k slices lga_op_gemm_splitk would use (1 = no split); K = 0: the most any K would give. */
 int32_t lga_op_gemm_splitk_slices(int32_t M, int32_t N, int32_t K);
 
@@ -65,7 +66,7 @@ int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const flo
                          const float *g, const void *resid, void *dx, float *dgamma, float *dbeta, float beta,
                          float *scratch, int32_t rows, int32_t d, void *stream);
 
-/* out[c][r] = in[r][c] for bfloat16 matrices (in: [R][ldi], out: [C][ldo]); R, C, ldi, ldo multiples of 8,
+/* out[c][r] = in[r][c] for matrices of 16-bit elements of either format (in: [R][ldi], out: [C][ldo]); R, C, ldi, ldo multiples of 8,
  * 16-byte aligned.  The stack keeps a transposed 16-bit copy of each weight matrix and transposes the
  * two operands of every weight-gradient GEMM so that all GEMM operands are k-contiguous. */
 int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo, void *stream);
@@ -81,7 +82,7 @@ uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols);
  *  out  [n_seq*s, heads*dh]
  *  lse  [n_seq, heads, s] float: log sum_j exp(scaled score_ij)
  * kind 0: one-wavefront-per-position kernel (any dtype, any dh); kind 1: MFMA kernel with
- * LDS-resident online softmax (LGA_BF16, dh a multiple of 8 up to 160; head sizes other than 32, 64, 96, 128, 160
+ * LDS-resident online softmax (16-bit, dh a multiple of 8 up to 160; head sizes other than 32, 64, 96, 128, 160
  * run in the next larger of those kernels with the extra columns read as zeros). */
 int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out, float *lse, int32_t n_seq,
                          int32_t s, int32_t heads, int32_t dh, int32_t causal, void *stream);
@@ -91,9 +92,11 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
                          int32_t dh, int32_t causal, void *stream);
 
 /* One Adam update of n parameters in place (w, m, v fp32; g fp32 read-only); if w16 != NULL the new
- * weights are also written as bfloat16 (section 2.5: 16-bit copy for the next use). */
-int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_t n, const lga_adam *adam,
-                void *stream);
+ * weights are also written in the 16-bit format w16_dtype (section 2.5: 16-bit copy for the next use).
+ * adam->loss_scale divides the gradient first; with adam->skip_nonfinite, *nonfinite (device int32, required then)
+ * is set to whether g holds an infinity or NaN, and if it does nothing else is written (see lga_adam). */
+int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t w16_dtype, uint64_t n,
+                const lga_adam *adam, int32_t *nonfinite, void *stream);
 
 /* Calibration for the benchmark tools: the bf16 MFMA rate (TFLOP/s, executed) that the GPU sustains on register
  * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 16 v_mfma_f32_32x32x16_bf16 back to

@@ -30,6 +30,13 @@ What is computed, and where the paper defines it:
 * Adam with fp32-equivalent state (sections 2.5, 5; appendix C.3).  The paper
   only names the optimizer; the variant is Kingma & Ba's with bias correction,
   no weight decay, eps added to the root of the corrected second moment.
+* Gradient scaling for half precision (section 2.2 only says that gradients
+  are scaled dynamically against under- and overflow): the output gradient
+  arrives multiplied by a loss scale, Adam divides by it, an update whose
+  gradient holds an infinity or NaN is left out, and `LossScaler` halves the
+  scale after such a step and doubles it after a run of clean ones.  In fp64
+  the scaling itself changes nothing (exactly nothing for powers of two),
+  which is the pin.
 
 Readings taken where the paper is silent (GELU in its tanh form, LayerNorm
 with biased variance and eps inside the root, softmax scale 1/sqrt(d_h), sum
@@ -266,16 +273,52 @@ class AdamHyper:
     beta2: float = 0.999
     eps: float = 1e-8
     step: int = 1     # t >= 1, the number of the update being applied
+    # Gradient scaling for half precision (section 2.2): g arrives multiplied by loss_scale and is divided by it
+    # before use; with skip_nonfinite an update whose gradient holds an infinity or a NaN is not applied at all.
+    loss_scale: float = 1.0
+    skip_nonfinite: bool = False
+
+
+def adam_skips(g, hp: AdamHyper) -> bool:
+    """Whether the update with gradient g is left out (overflowed gradient, section 2.2)."""
+    return bool(hp.skip_nonfinite and not np.all(np.isfinite(g)))
 
 
 def adam_update(w, m, v, g, hp: AdamHyper):
     """One Adam update; returns new (w, m, v).  No weight decay."""
+    if adam_skips(g, hp):
+        return np.array(w, dtype=F64), np.array(m, dtype=F64), np.array(v, dtype=F64)
+    g = np.asarray(g, dtype=F64) / hp.loss_scale
     m_new = hp.beta1 * m + (1.0 - hp.beta1) * g
     v_new = hp.beta2 * v + (1.0 - hp.beta2) * g * g
     m_hat = m_new / (1.0 - hp.beta1 ** hp.step)
     v_hat = v_new / (1.0 - hp.beta2 ** hp.step)
     w_new = w - hp.lr * m_hat / (np.sqrt(v_hat) + hp.eps)
     return w_new, m_new, v_new
+
+
+@dataclass
+class LossScaler:
+    """Dynamic loss scale (section 2.2 says the gradients are scaled dynamically; the rule is the customary one of
+    mixed precision training: halve at once after an overflow, double after a run of clean steps)."""
+    scale: float = 65536.0
+    growth: float = 2.0
+    backoff: float = 0.5
+    min_scale: float = 1.0
+    max_scale: float = 2.0 ** 24
+    growth_interval: int = 2000
+    good_steps: int = 0
+
+
+def loss_scaler_update(s: LossScaler, overflowed: bool) -> None:
+    if overflowed:
+        s.scale = max(s.scale * s.backoff, s.min_scale)
+        s.good_steps = 0
+        return
+    s.good_steps += 1
+    if s.good_steps >= s.growth_interval:
+        s.scale = min(s.scale * s.growth, s.max_scale)
+        s.good_steps = 0
 
 
 # --------------------------------------------------------------------------
@@ -291,6 +334,7 @@ class StepResult:
     new_m: Optional[List[np.ndarray]] = None
     new_v: Optional[List[np.ndarray]] = None
     loss: float = 0.0
+    skipped: Optional[List[bool]] = None   # per layer: update left out (AdamHyper.skip_nonfinite)
 
 
 def _as_layers(flat_params: Sequence[np.ndarray], shape: StackShape):
@@ -341,6 +385,7 @@ def step_microbatch_major(x, G, flat_params, shape: StackShape, adam: Optional[A
     res = StepResult(boundaries=bounds, grads=grads, dx=dx, loss=loss)
     if adam is not None:
         res.new_params, res.new_m, res.new_v = _apply_adam(flat_params, grads, adam, m0, v0)
+        res.skipped = [adam_skips(g, adam) for g in grads]
     return res
 
 
@@ -383,6 +428,7 @@ def step_layered(x, G, flat_params, shape: StackShape, adam: Optional[AdamHyper]
     res = StepResult(boundaries=bounds, grads=grads, dx=d, loss=loss)
     if adam is not None:
         res.new_params, res.new_m, res.new_v = new_w, new_m, new_v
+        res.skipped = [adam_skips(g, adam) for g in grads]
     return res
 
 

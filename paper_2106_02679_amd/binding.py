@@ -19,7 +19,7 @@ import torch  # noqa: F401  (device memory and streams for the callers)
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblga.so")
 
-LGA_FP32, LGA_BF16 = 0, 1
+LGA_FP32, LGA_BF16, LGA_FP16 = 0, 1, 2
 LGA_OK, LGA_ERR_ARG, LGA_ERR_SHAPE, LGA_ERR_OOM, LGA_ERR_STATE, LGA_ERR_HIP = 0, -1, -2, -3, -4, -5
 LGA_OVERLAP_NONE, LGA_OVERLAP_RESTORE, LGA_OVERLAP_ADAM = 0, 1, 2
 LGA_ATTN_CAUSAL, LGA_ATTN_FULL = 0, 1
@@ -42,7 +42,12 @@ class lga_config(C.Structure):
 
 class lga_adam(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("step", C.c_int32)]
+                ("step", C.c_int32), ("loss_scale", C.c_float), ("skip_nonfinite", C.c_int32)]
+
+
+class lga_loss_scaler(C.Structure):
+    _fields_ = [("scale", C.c_float), ("growth", C.c_float), ("backoff", C.c_float), ("min_scale", C.c_float),
+                ("max_scale", C.c_float), ("growth_interval", C.c_int32), ("good_steps", C.c_int32)]
 
 
 class lga_kernel_stat(C.Structure):
@@ -89,7 +94,7 @@ SIGNATURES = {
     "lga_profile_end": (C.c_int, [_vp, _P(lga_kernel_stat), _i32, _P(_i32)]),
     "lga_op_gemm": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _i32,
                               _vp, _vp, _f32, _vp]),
-    "lga_op_gemm_splitk": (C.c_int, [_i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _i32, _f32, _vp, _u64, _vp]),
+    "lga_op_gemm_splitk": (C.c_int, [_i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _i32, _f32, _vp, _u64, _vp]),
     "lga_op_gemm_splitk_slices": (_i32, [_i32, _i32, _i32]),
     "lga_op_mfma_rate": (C.c_int, [_i32, _i32, _vp, _P(C.c_double), _vp]),
     "lga_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
@@ -100,7 +105,10 @@ SIGNATURES = {
     "lga_op_colsum_scratch_floats": (_u64, [_i32, _i32]),
     "lga_op_attention_fwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
     "lga_op_attention_bwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
-    "lga_op_adam": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _u64, _P(lga_adam), _vp]),
+    "lga_op_adam": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _u64, _P(lga_adam), _vp, _vp]),
+    "lga_nonfinite_layers": (C.c_int, [_vp, _P(_i32), _P(_i32)]),
+    "lga_grads_nonfinite": (C.c_int, [_vp, _P(_i32), _P(_i32)]),
+    "lga_loss_scaler_update": (C.c_int, [_P(lga_loss_scaler), _i32]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(lib, _name)
@@ -232,6 +240,21 @@ class Stack:
 
     def checkpoint(self, boundary: int):
         return self._borrow(lib.lga_checkpoint, boundary)
+
+    def _layer_flags(self, fn):
+        flags = (C.c_int32 * self.cfg.n_layers)()
+        count = C.c_int32()
+        check(fn(self._h, flags, C.byref(count)))
+        assert count.value == sum(flags)
+        return list(flags)
+
+    def nonfinite_layers(self):
+        """Per layer: 1 if its last Adam step with skip_nonfinite was left out."""
+        return self._layer_flags(lib.lga_nonfinite_layers)
+
+    def grads_nonfinite(self):
+        """Per layer: 1 if the gradient it currently holds has a non-finite value."""
+        return self._layer_flags(lib.lga_grads_nonfinite)
 
     def restore_count(self) -> int:
         out = _u64()

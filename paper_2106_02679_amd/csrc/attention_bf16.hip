@@ -1,4 +1,4 @@
-// Softmax attention for gfx950 in bf16 with fp32 accumulation: forward with an online softmax, and a
+// Softmax attention for gfx950 on 16-bit tensors (element type E: bf16, or f16 = IEEE half) with fp32 accumulation: forward with an online softmax, and a
 // deterministic two-kernel backward (no float atomics).  Causal (decoder: position i sees j <= i) or unmasked
 // (encoder: every position sees its whole sequence; only keys past the end of a ragged last tile are masked).
 //
@@ -33,19 +33,20 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 // Second operand straight from global memory: 8 contiguous bf16 of one row (zero if the row is invalid or the
 // columns lie beyond the head size dh, a multiple of 8 that may be smaller than the kernel's padded DH).
-__device__ __forceinline__ bf16x8 frag_global(const bf16 *row_ptr, int ks, int half, bool valid, int dh) {
-    if (!valid || 16 * ks + 8 * half >= dh) return bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-    return *reinterpret_cast<const bf16x8 *>(row_ptr + 16 * ks + 8 * half);
+template <class E> __device__ __forceinline__ x8<E> frag_global(const E *row_ptr, int ks, int half, bool valid, int dh) {
+    if (!valid || 16 * ks + 8 * half >= dh) return x8<E>{0, 0, 0, 0, 0, 0, 0, 0};
+    return *reinterpret_cast<const x8<E> *>(row_ptr + 16 * ks + 8 * half);
 }
-// 32x32 fp32 result registers 8*kk .. 8*kk+7 -> bf16 second operand.
-__device__ __forceinline__ bf16x8 pack_bf16(const f32x16 &v, int kk) {
-    bf16x8 o;
+// 32x32 fp32 result registers 8*kk .. 8*kk+7 -> 16-bit second operand.
+template <class E> __device__ __forceinline__ x8<E> pack16(const f32x16 &v, int kk) {
+    x8<E> o;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = (bf16)v[8 * kk + e];
+    for (int e = 0; e < 8; ++e) o[e] = (E)v[8 * kk + e];
     return o;
 }
 
-#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+// inside the kernels, whose element type is E
+#define MFMA(a, b, c) mfma_32x32x16<E>((a), (b), (c))
 
 // ---- direct-to-LDS tile loads and transposing LDS reads --------------------------------------
 // buffer_load_dwordx4 ... lds writes lane L's 16 bytes at (LDS base) + 16 L; rows beyond the sequence get
@@ -80,7 +81,7 @@ template <int PITCH> __device__ __forceinline__ int tr_lane_off(int lane) {
 // base = tile + tr_lane_off(lane).
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
-template <int PITCH> __device__ __forceinline__ bf16x8 frag_nat_tr(const bf16 *base, int c, int kk) {
+template <int PITCH, class E> __device__ __forceinline__ x8<E> frag_nat_tr(const E *base, int c, int kk) {
     // Issued as inline assembly: the compiler makes the builtin form wait for every outstanding
     // direct-to-LDS load first (it cannot tell which LDS bytes those write), which would serialise the
     // tile prefetch.  The price: the compiler does not count these reads in lgkmcnt, so wait_tr_reads()
@@ -90,11 +91,11 @@ template <int PITCH> __device__ __forceinline__ bf16x8 frag_nat_tr(const bf16 *b
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "i"((16 * kk * PITCH + 32 * c) * 2));
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "i"(((16 * kk + 8) * PITCH + 32 * c) * 2));
     const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
-    return __builtin_bit_cast(bf16x8, v);
+    return __builtin_bit_cast(x8<E>, v);
 }
 // All LDS reads issued so far have returned; the operands listed are tied to the wait so that no use of
 // them can be scheduled above it.
-template <int N> __device__ __forceinline__ void wait_tr_reads(bf16x8 (&f)[N]) {
+template <class V, int N> __device__ __forceinline__ void wait_tr_reads(V (&f)[N]) {
     static_assert(N <= 10, "operand list below");
     if constexpr (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]));
     else if constexpr (N == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
@@ -128,11 +129,12 @@ template <int ROWS, int DH, int PITCH> struct TileDma {
             off[i] = r * gp2 + (pc << 4);
         }
     }
-    __device__ __forceinline__ void issue(const bf16 *src, bf16 *dst, int nvalid, int wave) const {
+    // src, dst: tiles of 16-bit elements of either format
+    __device__ __forceinline__ void issue(const void *src, void *dst, int nvalid, int wave) const {
         const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
 #pragma unroll
         for (int i = 0; i < NJ; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(dst + (i * 4 + wave) * 512), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(static_cast<char *>(dst) + (i * 4 + wave) * 1024), 16,
                                                      row[i] < nvalid ? off[i] : kBufPoison, 0, 0, 0);
     }
 };
@@ -162,8 +164,8 @@ __device__ __forceinline__ void block_of(const AttnShape &sh, int nblocks, int &
 // Key tiles of 64 (K and V as stored, rows of DH) stream from global memory straight into one of two
 // LDS stages while the other is multiplied; one barrier per tile publishes it.  V^T operands come from
 // the natural V tile through the transposing LDS read.  The online softmax runs per (sub-block, 32 keys).
-template <int DH>
-__global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict__ qkv, bf16 *__restrict__ out,
+template <int DH, class E>
+__global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ qkv, E *__restrict__ out,
                                                        float *__restrict__ lse, AttnShape sh) {
     constexpr int KT = 64;                 // keys per streamed tile
     constexpr int NK = DH / 16, NC = DH / 32;
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     constexpr int kWaitOlder = 0x0070 | (DmaK::NJ + DmaV::NJ);  // s_waitcnt lgkmcnt(0) vmcnt(loads of one tile): older tiles landed
     static_assert(DmaK::NJ + DmaV::NJ < 16, "vmcnt immediate uses the low four bits only");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    E *lds = reinterpret_cast<E *>(smem_raw);
 
     const int qblocks = (sh.s + 255) / 256;
     int bh, rank;
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     const int dh = sh.dh;                           // head size in memory: a multiple of 8, DH - 24 <= dh <= DH
     const int d = sh.heads * dh;
     const size_t pitch = 3 * (size_t)d;
-    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
+    const E *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int qw0 = qb * 256 + wave * 64;          // first query of this wavefront
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     const int vis_lane = (causal ? lrow : 0) - 4 * half;
     auto vis_u = [&](int u) { return causal ? qw0 + 32 * u : sh.s - 1; };
 
-    bf16x8 qf[2][NK];
+    x8<E> qf[2][NK];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const int q = qw0 + 32 * u + lrow;
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     dk.init(wave, lane, (int)(pitch * 2), dh);
     dv.init(wave, lane, (int)(pitch * 2), dh);
     auto dma_tile = [&](int k0, int stage) {
-        bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
+        E *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
         dk.issue(seq + (size_t)k0 * pitch + d, Ks, sh.s - k0, wave);
         dv.issue(seq + (size_t)k0 * pitch + 2 * d, Vs, sh.s - k0, wave);
     };
@@ -240,14 +242,14 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
     // soon as the first block's last MFMA is issued, under the other work of the slot.  The issue order is
     // pinned (sched_barrier).  With tiles and wavefront query ranges both aligned to 64, a tile is either
     // fully visible or the diagonal one (k0 == qw0), where masked probabilities are forced to zero.
-    bf16x8 kf[NK], vf[2 * NC], pf[4][2];           // K operands and V^T operands of one key block, P operands [unit]
+    x8<E> kf[NK], vf[2 * NC], pf[4][2];           // K operands and V^T operands of one key block, P operands [unit]
     f32x16 st[4];                                  // scores per unit
     float pr[2][8];                                // probabilities of half a unit, until they are packed
-    auto read_k = [&](const bf16 *Ks, int kb) {
+    auto read_k = [&](const E *Ks, int kb) {
 #pragma unroll
-        for (int ks = 0; ks < NK; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(Ks + kb * 32 * PK + 16 * ks);
+        for (int ks = 0; ks < NK; ++ks) kf[ks] = *reinterpret_cast<const x8<E> *>(Ks + kb * 32 * PK + 16 * ks);
     };
-    auto read_v = [&](const bf16 *Vs, int kb) {
+    auto read_v = [&](const E *Vs, int kb) {
 #pragma unroll
         for (int j2 = 0; j2 < 2; ++j2)
 #pragma unroll
@@ -290,13 +292,13 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
         }
         if (g & 1) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[n][g >> 1][e] = (bf16)pr[n & 1][e];
+            for (int e = 0; e < 8; ++e) pf[n][g >> 1][e] = (E)pr[n & 1][e];
         }
     };
     // No branch inside: with two code paths through the MFMAs the compiler merges their accumulator
     // registers with hundreds of copies per tile.
     auto tile = [&](int k0, int stage, auto masked_c) {
-        const bf16 *Ks = lds + stage * STAGE + koff, *Vs = lds + stage * STAGE + DmaK::ELEMS + voff;
+        const E *Ks = lds + stage * STAGE + koff, *Vs = lds + stage * STAGE + DmaK::ELEMS + voff;
         read_k(Ks, 0);
         read_v(Vs, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -423,15 +425,15 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
         const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
         if (q < sh.s) {
             const float inv = 1.0f / l_tot;
-            bf16 *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * dh;
+            E *orow = out + ((size_t)b * sh.s + q) * d + (size_t)h * dh;
 #pragma unroll
             for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    bf16x4 o;
+                    x4<E> o;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) o[i] = (bf16)(oacc[u][c][4 * g + i] * inv);
-                    if (c * 32 + 8 * g + 4 * half < dh) *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+                    for (int i = 0; i < 4; ++i) o[i] = (E)(oacc[u][c][4 * g + i] * inv);
+                    if (c * 32 + 8 * g + 4 * half < dh) *reinterpret_cast<x4<E> *>(orow + c * 32 + 8 * g + 4 * half) = o;
                 }
             if (half == 0) lse[((size_t)b * sh.heads + h) * sh.s + q] = m_ref[u] * kLn2 + logf(l_tot);
         }
@@ -440,20 +442,13 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const bf16 *__restrict
 
 // Explicit instantiations: the host compiler does not always emit the launch stub of a kernel template from its
 // use in the launcher below alone.
-#define LGA_INSTANTIATE_FWD(DH) \
-    template __global__ void attn_fwd_kernel<DH>(const bf16 *, bf16 *, float *, AttnShape)
-LGA_INSTANTIATE_FWD(32);
-LGA_INSTANTIATE_FWD(64);
-LGA_INSTANTIATE_FWD(96);
-LGA_INSTANTIATE_FWD(128);
-LGA_INSTANTIATE_FWD(160);
-#undef LGA_INSTANTIATE_FWD
 
 // ============================================================================================
 // delta[b, h, q] = sum_c dO[q, h*dh + c] * O[q, h*dh + c].  out and dout are [tokens][heads * dh]: consecutive
 // (token, head) items are consecutive runs of dh elements.  A thread multiplies one 16-byte chunk of each tensor
 // (fully coalesced), the chunk sums go through LDS, and one thread per item adds its dh / 8 of them in order.
-__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict__ out, const bf16 *__restrict__ dout,
+template <class E>
+__global__ __launch_bounds__(256) void attn_delta_kernel(const E *__restrict__ out, const E *__restrict__ dout,
                                                          float *__restrict__ delta, AttnShape sh, int items_per_block) {
     __shared__ float part[256];
     const int cpi = sh.dh / 8;                                            // chunks per item
@@ -463,8 +458,8 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict_
     const size_t chunk = item0 * cpi + tid;                               // index into the tensors as arrays of 16-byte chunks
     float acc = 0.f;
     if (tid < items_per_block * cpi && chunk < items * cpi) {
-        const bf16x8 o = *reinterpret_cast<const bf16x8 *>(out + chunk * 8);
-        const bf16x8 g = *reinterpret_cast<const bf16x8 *>(dout + chunk * 8);
+        const x8<E> o = *reinterpret_cast<const x8<E> *>(out + chunk * 8);
+        const x8<E> g = *reinterpret_cast<const x8<E> *>(dout + chunk * 8);
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc += (float)o[i] * (float)g[i];
     }
@@ -488,10 +483,10 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16 *__restrict_
 // from global memory straight into one of two LDS stages while the other is multiplied, one barrier per
 // tile.  K^T operands come from the natural K tile through the transposing LDS read.  Two workgroups per
 // CU, so that one's MFMAs run under the other's VALU work.
-template <int DH, int OCC>
-__global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+template <int DH, int OCC, class E>
+__global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const E *__restrict__ qkv, const float *__restrict__ lse,
                                                           const float *__restrict__ delta,
-                                                          const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
+                                                          const E *__restrict__ dout, E *__restrict__ dqkv,
                                                           AttnShape sh) {
     constexpr int KT = 64;
     constexpr int NK = DH / 16, NC = DH / 32;
@@ -500,7 +495,7 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     typedef TileDma<KT, DH, PV> DmaV;
     constexpr int STAGE = DmaK::ELEMS + DmaV::ELEMS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    E *lds = reinterpret_cast<E *>(smem_raw);
 
     const int qblocks = (sh.s + 127) / 128;
     int bh, rank;
@@ -510,15 +505,15 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     const int dh = sh.dh;                           // head size in memory, <= DH
     const int d = sh.heads * dh;
     const size_t pitch = 3 * (size_t)d;
-    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
+    const E *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int qw0 = qb * 128 + wave * 32;
     const int q = qw0 + lrow;
     const bool qvalid = q < sh.s;
 
-    bf16x8 qf[NK], dof[NK];
-    const bf16 *dorow = dout + ((size_t)b * sh.s + q) * d + (size_t)h * dh;
+    x8<E> qf[NK], dof[NK];
+    const E *dorow = dout + ((size_t)b * sh.s + q) * d + (size_t)h * dh;
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
         qf[ks] = frag_global(seq + (size_t)q * pitch, ks, half, qvalid, dh);
@@ -541,7 +536,7 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
     dk.init(wave, lane, (int)(pitch * 2), dh);
     dv.init(wave, lane, (int)(pitch * 2), dh);
     auto dma_tile = [&](int k0, int stage) {
-        bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
+        E *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
         dk.issue(seq + (size_t)k0 * pitch + d, Ks, sh.s - k0, wave);
         dv.issue(seq + (size_t)k0 * pitch + 2 * d, Vs, sh.s - k0, wave);
     };
@@ -561,7 +556,7 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
         asm volatile("" ::: "memory");
         if (k0 + KT < kend) dma_tile(k0 + KT, stage ^ 1);
         if (causal && k0 > qw0 + 31) continue;     // whole tile is in this wavefront's future
-        const bf16 *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
+        const E *Ks = lds + stage * STAGE, *Vs = Ks + DmaK::ELEMS;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             const int kbs = k0 + 32 * kb;          // first key of this block of 32
@@ -569,11 +564,11 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
             if (causal ? kbs > qw0 : kbs >= sh.s) continue;
             // last visible key of this lane's query, relative to the block: the query itself, or the end of the sequence
             const int klast = causal ? qw0 + lrow - kbs : sh.s - 1 - kbs;
-            bf16x8 kf[NK], vfr[NK], ktf[2 * NC];
+            x8<E> kf[NK], vfr[NK], ktf[2 * NC];
 #pragma unroll
             for (int ks = 0; ks < NK; ++ks) {
-                kf[ks] = *reinterpret_cast<const bf16x8 *>(Ks + koff + kb * 32 * PK + 16 * ks);
-                vfr[ks] = *reinterpret_cast<const bf16x8 *>(Vs + voff + kb * 32 * PV + 16 * ks);
+                kf[ks] = *reinterpret_cast<const x8<E> *>(Ks + koff + kb * 32 * PK + 16 * ks);
+                vfr[ks] = *reinterpret_cast<const x8<E> *>(Vs + voff + kb * 32 * PV + 16 * ks);
             }
             f32x16 st, dpt;
 #pragma unroll
@@ -604,35 +599,26 @@ __global__ __launch_bounds__(256, OCC) void attn_bwd_dq_kernel(const bf16 *__res
             wait_tr_reads(ktf);
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const bf16x8 dsf = pack_bf16(st, kk);
+                const x8<E> dsf = pack16<E>(st, kk);
 #pragma unroll
                 for (int c = 0; c < NC; ++c) acc[c] = MFMA(ktf[kk * NC + c], dsf, acc[c]);
             }
         }
     }
     if (qvalid) {
-        bf16 *orow = dqkv + ((size_t)b * sh.s + q) * pitch + (size_t)h * dh;
+        E *orow = dqkv + ((size_t)b * sh.s + q) * pitch + (size_t)h * dh;
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                bf16x4 o;
+                x4<E> o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (bf16)(acc[c][4 * g + i] * scale);
-                if (c * 32 + 8 * g + 4 * half < dh) *reinterpret_cast<bf16x4 *>(orow + c * 32 + 8 * g + 4 * half) = o;
+                for (int i = 0; i < 4; ++i) o[i] = (E)(acc[c][4 * g + i] * scale);
+                if (c * 32 + 8 * g + 4 * half < dh) *reinterpret_cast<x4<E> *>(orow + c * 32 + 8 * g + 4 * half) = o;
             }
     }
 }
 
-#define LGA_INSTANTIATE_DQ(DH, OCC)                                                                                  \
-    template __global__ void attn_bwd_dq_kernel<DH, OCC>(const bf16 *, const float *, const float *, const bf16 *, \
-                                                         bf16 *, AttnShape)
-LGA_INSTANTIATE_DQ(32, 2);
-LGA_INSTANTIATE_DQ(64, 2);
-LGA_INSTANTIATE_DQ(96, 2);
-LGA_INSTANTIATE_DQ(128, 2);
-LGA_INSTANTIATE_DQ(160, 1);
-#undef LGA_INSTANTIATE_DQ
 
 // ============================================================================================
 // Tiles that are read both ways - rows with ds_read_b128 and transposed with ds_read_b64_tr_b16 - keep the
@@ -662,13 +648,14 @@ template <int ROWS, int DH> struct TileDmaSw {
             off[i] = r * gp2 + ((pc ^ sw_both<DH>(r)) << 4);
         }
     }
-    __device__ __forceinline__ void issue(const bf16 *src, bf16 *dst, int nvalid, int wave) const {
+    // src, dst: tiles of 16-bit elements of either format
+    __device__ __forceinline__ void issue(const void *src, void *dst, int nvalid, int wave) const {
         const __amdgpu_buffer_rsrc_t rs = make_rsrc(src);
 #pragma unroll
         for (int i = 0; i < NJ; ++i) {
             const int j = i * 4 + wave;
             if (j >= NI) continue;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(dst + j * 512), 16, row[i] < nvalid ? off[i] : kBufPoison,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr)(static_cast<char *>(dst) + j * 1024), 16, row[i] < nvalid ? off[i] : kBufPoison,
                                                      0, 0, 0);
         }
     }
@@ -697,19 +684,19 @@ template <int DH> struct BothAddr {
         }
     }
     // MFMA first operand: row 32 u + lrow of the tile, k = 16 ks + 8 half + (0..7)
-    __device__ __forceinline__ bf16x8 nat(const bf16 *tile, int u, int ks) const {
+    template <class E> __device__ __forceinline__ x8<E> nat(const E *tile, int u, int ks) const {
         const int a = ks >> 1;
-        return *reinterpret_cast<const bf16x8 *>(tile + 32 * u * DH + nb[NG > 1 ? a : 0][ks & 1] + (NG > 1 ? 0 : 32 * a));
+        return *reinterpret_cast<const x8<E> *>(tile + 32 * u * DH + nb[NG > 1 ? a : 0][ks & 1] + (NG > 1 ? 0 : 32 * a));
     }
     // MFMA first operand "row 32 c + lrow of the transposed tile, k element e <-> tile row 16 kk + 8 (e/4) + 4 half + e%4"
-    __device__ __forceinline__ bf16x8 tr(const bf16 *tile, int c, int kk) const {
+    template <class E> __device__ __forceinline__ x8<E> tr(const E *tile, int c, int kk) const {
         const uint32_t a0 = (uint32_t)(uintptr_t)(tile + tb[NG > 1 ? c : 0][0]);
         const uint32_t a1 = (uint32_t)(uintptr_t)(tile + tb[NG > 1 ? c : 0][1]);
         u32x2 lo, hi;
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a0), "i"((16 * kk * DH + (NG > 1 ? 0 : 32 * c)) * 2));
         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a1), "i"((16 * kk * DH + (NG > 1 ? 0 : 32 * c)) * 2));
         const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
-        return __builtin_bit_cast(bf16x8, v);
+        return __builtin_bit_cast(x8<E>, v);
     }
 };
 
@@ -723,17 +710,17 @@ template <int DH> struct BothAddr {
 // With the causal mask the first two query tiles of a key block contain its diagonal (masked, partly skipped); all
 // later ones - without the mask, all tiles from the start of the sequence - are fully visible and go through a loop
 // without tests (rows past the end of the sequence are zero and carry zero statistics: they add nothing).
-template <int DH>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__restrict__ qkv, const float *__restrict__ lse,
+template <int DH, class E>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const E *__restrict__ qkv, const float *__restrict__ lse,
                                                               const float *__restrict__ delta,
-                                                              const bf16 *__restrict__ dout, bf16 *__restrict__ dqkv,
+                                                              const E *__restrict__ dout, E *__restrict__ dqkv,
                                                               AttnShape sh) {
     constexpr int QT = 64, NST = 3;
     constexpr int NK = DH / 16, NC = DH / 32;
     typedef TileDmaSw<QT, DH> Dma;
     constexpr int TILE = Dma::ELEMS, STAGE = 2 * TILE;          // Q tile, then dO tile
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    E *lds = reinterpret_cast<E *>(smem_raw);
     float *lse_s = reinterpret_cast<float *>(lds + NST * STAGE);     // [NST][QT]  log-sum-exp, log2 domain, negated
     float *dl_s = lse_s + NST * QT;                                  // [NST][QT]  delta
 
@@ -743,15 +730,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     const int dh = sh.dh;                           // head size in memory, <= DH
     const int d = sh.heads * dh;
     const size_t pitch = 3 * (size_t)d;
-    const bf16 *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
-    const bf16 *doseq = dout + (size_t)b * sh.s * d + (size_t)h * dh;
+    const E *seq = qkv + (size_t)b * sh.s * pitch + (size_t)h * dh;
+    const E *doseq = dout + (size_t)b * sh.s * d + (size_t)h * dh;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lrow = lane & 31, half = lane >> 5;
     const int kw0 = kb128 * 128 + wave * 32;        // first key of this wavefront
     const int key = kw0 + lrow;
     const bool kvalid = key < sh.s;
 
-    bf16x8 kf[NK], vf[NK];
+    x8<E> kf[NK], vf[NK];
 #pragma unroll
     for (int ks = 0; ks < NK; ++ks) {
         kf[ks] = frag_global(seq + (size_t)key * pitch + d, ks, half, kvalid, dh);
@@ -797,8 +784,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
     // one (32 keys x 32 queries) unit of tile `stage`: query rows [32 u, 32 u + 32) of the tile, first query qs
     auto unit = [&](int stage, int u, int qs, auto masked_c) {
         constexpr bool MASKED = decltype(masked_c)::value;
-        const bf16 *Qs = lds + stage * STAGE, *dOs = Qs + TILE;
-        bf16x8 qn[NK], don[NK];
+        const E *Qs = lds + stage * STAGE, *dOs = Qs + TILE;
+        x8<E> qn[NK], don[NK];
 #pragma unroll
         for (int ks = 0; ks < NK; ++ks) {
             qn[ks] = ad.nat(Qs, u, ks);
@@ -820,7 +807,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
         // the transposed operands take over the registers of the row operands; their latency passes under the
         // exponentials
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 dot[2 * NC], qt[2 * NC];
+        x8<E> dot[2 * NC], qt[2 * NC];
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -840,11 +827,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
                 pr[r] = p;
                 s_[r] = p * (dp[r] - d4[g][i]);
             }
-        bf16x8 pf[2], dsf[2];
+        x8<E> pf[2], dsf[2];
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            pf[kk] = pack_bf16(pr, kk);
-            dsf[kk] = pack_bf16(s_, kk);
+            pf[kk] = pack16<E>(pr, kk);
+            dsf[kk] = pack16<E>(s_, kk);
         }
         wait_tr_reads(dot);
         wait_tr_reads(qt);
@@ -910,35 +897,46 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(const bf16 *__rest
         unit(stage, 1, q0 + 32, std::false_type{});
     }
     if (kvalid) {
-        bf16 *orow = dqkv + ((size_t)b * sh.s + key) * pitch + (size_t)h * dh;
+        E *orow = dqkv + ((size_t)b * sh.s + key) * pitch + (size_t)h * dh;
 #pragma unroll
         for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                bf16x4 ok, ov;
+                x4<E> ok, ov;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    ok[i] = (bf16)(dk[c][4 * g + i] * scale);
-                    ov[i] = (bf16)dv[c][4 * g + i];
+                    ok[i] = (E)(dk[c][4 * g + i] * scale);
+                    ov[i] = (E)dv[c][4 * g + i];
                 }
                 if (c * 32 + 8 * g + 4 * half < dh) {
-                    *reinterpret_cast<bf16x4 *>(orow + d + c * 32 + 8 * g + 4 * half) = ok;
-                    *reinterpret_cast<bf16x4 *>(orow + 2 * d + c * 32 + 8 * g + 4 * half) = ov;
+                    *reinterpret_cast<x4<E> *>(orow + d + c * 32 + 8 * g + 4 * half) = ok;
+                    *reinterpret_cast<x4<E> *>(orow + 2 * d + c * 32 + 8 * g + 4 * half) = ov;
                 }
             }
     }
 }
-#define LGA_INSTANTIATE_DKV(DH)                                                                                \
-    template __global__ void attn_bwd_dkv_kernel<DH>(const bf16 *, const float *, const float *, const bf16 *, \
-                                                     bf16 *, AttnShape)
-LGA_INSTANTIATE_DKV(32);
-LGA_INSTANTIATE_DKV(64);
-LGA_INSTANTIATE_DKV(96);
-LGA_INSTANTIATE_DKV(128);
-LGA_INSTANTIATE_DKV(160);
-#undef LGA_INSTANTIATE_DKV
 
-template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
+// Explicit instantiations: the host compiler does not always emit the launch stub of a kernel template from its
+// use in the launchers below alone.
+#define LGA_INSTANTIATE_KERNELS(DH, OCC, E)                                                                          \
+    template __global__ void attn_fwd_kernel<DH, E>(const E *, E *, float *, AttnShape);                             \
+    template __global__ void attn_bwd_dq_kernel<DH, OCC, E>(const E *, const float *, const float *, const E *, E *, \
+                                                            AttnShape);                                              \
+    template __global__ void attn_bwd_dkv_kernel<DH, E>(const E *, const float *, const float *, const E *, E *,     \
+                                                        AttnShape)
+#define LGA_INSTANTIATE_TYPE(E)                                                                            \
+    template __global__ void attn_delta_kernel<E>(const E *, const E *, float *, AttnShape, int);          \
+    LGA_INSTANTIATE_KERNELS(32, 2, E);                                                                     \
+    LGA_INSTANTIATE_KERNELS(64, 2, E);                                                                     \
+    LGA_INSTANTIATE_KERNELS(96, 2, E);                                                                     \
+    LGA_INSTANTIATE_KERNELS(128, 2, E);                                                                    \
+    LGA_INSTANTIATE_KERNELS(160, 1, E)
+LGA_INSTANTIATE_TYPE(bf16);
+LGA_INSTANTIATE_TYPE(f16);
+#undef LGA_INSTANTIATE_TYPE
+#undef LGA_INSTANTIATE_KERNELS
+
+template <int DH, class E> void fwd_dh(const E *qkv, E *out, float *lse, AttnShape sh, hipStream_t s) {
     dim3 grid((unsigned)(sh.n_seq * sh.heads) * ((sh.s + 255) / 256));
     char name[64];
     snprintf(name, sizeof(name), "attn_fwd_kernel<%d>", DH);
@@ -949,14 +947,14 @@ template <int DH> void fwd_dh(const bf16 *qkv, bf16 *out, float *lse, AttnShape 
     constexpr int smem = 3 * (TileDma<64, DH, pitch_rd<DH>()>::ELEMS + TileDma<64, DH, pitch_tr<DH>()>::ELEMS) * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_kernel<DH>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_kernel<DH, E>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         attr_set = true;
     }
-    hipLaunchKernelGGL((attn_fwd_kernel<DH>), grid, dim3(256), smem, s, qkv, out, lse, sh);
+    hipLaunchKernelGGL((attn_fwd_kernel<DH, E>), grid, dim3(256), smem, s, qkv, out, lse, sh);
 }
-template <int DH>
-void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *dout, bf16 *dqkv, AttnShape sh,
+template <int DH, class E>
+void bwd_dh(const E *qkv, const float *lse, const float *delta, const E *dout, E *dqkv, AttnShape sh,
             hipStream_t s) {
     dim3 grid((unsigned)(sh.n_seq * sh.heads) * ((sh.s + 127) / 128));
     char name[64];
@@ -970,11 +968,11 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
         constexpr int smem_dq = 2 * (TileDma<64, DH, pitch_both<DH>()>::ELEMS + TileDma<64, DH, pitch_rd<DH>()>::ELEMS) * 2;
         static bool attr_set_dq = false;
         if (!attr_set_dq) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dq_kernel<DH, kOccDq>),
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dq_kernel<DH, kOccDq, E>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq);
             attr_set_dq = true;
         }
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, kOccDq>), grid, dim3(256), smem_dq, s, qkv, lse, delta, dout, dqkv, sh);
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, kOccDq, E>), grid, dim3(256), smem_dq, s, qkv, lse, delta, dout, dqkv, sh);
     }
     {
         snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
@@ -982,11 +980,11 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
         constexpr int smem = 3 * (2 * 64 * DH * 2 + 2 * 64 * 4);   // three stages of a Q tile, a dO tile and the row statistics
         static bool attr_set = false;
         if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_kernel<DH>),
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_kernel<DH, E>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             attr_set = true;
         }
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH>), grid, dim3(256), smem, s, qkv, lse, delta, dout, dqkv, sh);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, E>), grid, dim3(256), smem, s, qkv, lse, delta, dout, dqkv, sh);
     }
 }
 
@@ -997,42 +995,51 @@ void bwd_dh(const bf16 *qkv, const float *lse, const float *delta, const bf16 *d
 bool attn_bf16_supports(int dh) { return dh >= 8 && dh <= 160 && dh % 8 == 0; }
 static int padded_dh(int dh) { return (dh + 31) / 32 * 32; }
 
-void launch_attn_fwd_bf16(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s) {
+template <class E> void launch_attn_fwd_mfma(const E *qkv, E *out, float *lse, AttnShape sh, hipStream_t s) {
     if (sh.n_seq == 0 || sh.s == 0) return;
     if (!attn_bf16_supports(sh.dh)) {
-        launch_attn_fwd_simple<bf16>(qkv, out, lse, sh, s);
+        launch_attn_fwd_simple<E>(qkv, out, lse, sh, s);
         return;
     }
     switch (padded_dh(sh.dh)) {
-        case 32: fwd_dh<32>(qkv, out, lse, sh, s); break;
-        case 64: fwd_dh<64>(qkv, out, lse, sh, s); break;
-        case 96: fwd_dh<96>(qkv, out, lse, sh, s); break;
-        case 128: fwd_dh<128>(qkv, out, lse, sh, s); break;
-        case 160: fwd_dh<160>(qkv, out, lse, sh, s); break;
+        case 32: fwd_dh<32, E>(qkv, out, lse, sh, s); break;
+        case 64: fwd_dh<64, E>(qkv, out, lse, sh, s); break;
+        case 96: fwd_dh<96, E>(qkv, out, lse, sh, s); break;
+        case 128: fwd_dh<128, E>(qkv, out, lse, sh, s); break;
+        case 160: fwd_dh<160, E>(qkv, out, lse, sh, s); break;
     }
 }
 
-void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, const bf16 *dout, bf16 *dqkv,
+template <class E>
+void launch_attn_bwd_mfma(const E *qkv, const E *out, const float *lse, const E *dout, E *dqkv,
                           float *delta, AttnShape sh, hipStream_t s) {
     if (sh.n_seq == 0 || sh.s == 0) return;
     if (!attn_bf16_supports(sh.dh)) {
-        launch_attn_bwd_simple<bf16>(qkv, out, lse, dout, dqkv, delta, sh, s);
+        launch_attn_bwd_simple<E>(qkv, out, lse, dout, dqkv, delta, sh, s);
         return;
     }
     const size_t items = (size_t)sh.n_seq * sh.s * sh.heads;
     {
         ProfScope scope("attn_delta_kernel", 2.0 * items * sh.dh, 4.0 * items * sh.dh, s);
         const int items_per_block = 256 / (sh.dh / 8);                  // dh is a multiple of 8, at most 160
-        hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((items + items_per_block - 1) / items_per_block)), dim3(256), 0,
+        hipLaunchKernelGGL(attn_delta_kernel<E>, dim3((unsigned)((items + items_per_block - 1) / items_per_block)), dim3(256), 0,
                            s, out, dout, delta, sh, items_per_block);
     }
     switch (padded_dh(sh.dh)) {
-        case 32: bwd_dh<32>(qkv, lse, delta, dout, dqkv, sh, s); break;
-        case 64: bwd_dh<64>(qkv, lse, delta, dout, dqkv, sh, s); break;
-        case 96: bwd_dh<96>(qkv, lse, delta, dout, dqkv, sh, s); break;
-        case 128: bwd_dh<128>(qkv, lse, delta, dout, dqkv, sh, s); break;
-        case 160: bwd_dh<160>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 32: bwd_dh<32, E>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 64: bwd_dh<64, E>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 96: bwd_dh<96, E>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 128: bwd_dh<128, E>(qkv, lse, delta, dout, dqkv, sh, s); break;
+        case 160: bwd_dh<160, E>(qkv, lse, delta, dout, dqkv, sh, s); break;
     }
 }
+
+#define LGA_INSTANTIATE_ATTN(E)                                                                          \
+    template void launch_attn_fwd_mfma<E>(const E *, E *, float *, AttnShape, hipStream_t);               \
+    template void launch_attn_bwd_mfma<E>(const E *, const E *, const float *, const E *, E *, float *, \
+                                          AttnShape, hipStream_t)
+LGA_INSTANTIATE_ATTN(bf16);
+LGA_INSTANTIATE_ATTN(f16);
+#undef LGA_INSTANTIATE_ATTN
 
 }  // namespace lga

@@ -1,6 +1,6 @@
 // Softmax attention (causal or unmasked), correctness-mode kernels: one wavefront per (sequence, head, position).
 // Scores, softmax and all sums in fp32; T is the storage type.  Used by the fp32 mode; the
-// bf16 mode runs the MFMA kernels in attention_bf16.hip.
+// The 16-bit modes run the MFMA kernels in attention_bf16.hip.
 #include "kernels.h"
 
 namespace lga {
@@ -166,6 +166,7 @@ template <class T> void launch_attn_fwd_simple(const T *qkv, T *out, float *lse,
 }
 template void launch_attn_fwd_simple<float>(const float *, float *, float *, AttnShape, hipStream_t);
 template void launch_attn_fwd_simple<bf16>(const bf16 *, bf16 *, float *, AttnShape, hipStream_t);
+template void launch_attn_fwd_simple<f16>(const f16 *, f16 *, float *, AttnShape, hipStream_t);
 
 template <class T>
 void launch_attn_bwd_simple(const T *qkv, const T *out, const float *lse, const T *dout, T *dqkv, float *delta,
@@ -183,6 +184,8 @@ void launch_attn_bwd_simple(const T *qkv, const T *out, const float *lse, const 
 template void launch_attn_bwd_simple<float>(const float *, const float *, const float *, const float *, float *,
                                             float *, AttnShape, hipStream_t);
 template void launch_attn_bwd_simple<bf16>(const bf16 *, const bf16 *, const float *, const bf16 *, bf16 *, float *,
+                                           AttnShape, hipStream_t);
+template void launch_attn_bwd_simple<f16>(const f16 *, const f16 *, const float *, const f16 *, f16 *, float *,
                                            AttnShape, hipStream_t);
 
 }  // namespace lga

@@ -9,6 +9,10 @@ namespace lga {
 typedef __bf16 bf16;
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16;        // IEEE half (section 2.2: the 16-bit format whose gradients need dynamic scaling)
+// 4- and 8-element vectors of a 16-bit element type E (bf16 or f16)
+template <class E> using x4 = E __attribute__((ext_vector_type(4)));
+template <class E> using x8 = E __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -22,6 +26,17 @@ __device__ __forceinline__ float to_f32(bf16 v) { return static_cast<float>(v); 
 template <class T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return static_cast<bf16>(v); }
+__device__ __forceinline__ float to_f32(f16 v) { return static_cast<float>(v); }
+template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return static_cast<f16>(v); }
+
+// ---- the 32 x 32 x 16 matrix instruction for either 16-bit element type, fp32 accumulate ----
+template <class E> __device__ __forceinline__ f32x16 mfma_32x32x16(x8<E> a, x8<E> b, f32x16 c);
+template <> __device__ __forceinline__ f32x16 mfma_32x32x16<bf16>(x8<bf16> a, x8<bf16> b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x16 mfma_32x32x16<f16>(x8<f16> a, x8<f16> b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
 
 // ---- wave / block reductions -------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {

@@ -1,4 +1,7 @@
-// bf16 MFMA GEMMs for gfx950, fp32 accumulate: C[M,N] = sum_k A(m,k) B(k,n) + epilogue.
+// 16-bit MFMA GEMMs for gfx950, fp32 accumulate: C[M,N] = sum_k A(m,k) B(k,n) + epilogue.
+// Every kernel here takes the element type E as its last template argument: bf16 (the default 16-bit mode, from
+// which the kernels have their names) or f16 (IEEE half); the two differ in the matrix instruction and in the
+// conversions of the epilogues, nothing else.
 //
 // The three GEMM families of a transformer layer (appendix C.1: each is 2 flop per token per parameter)
 //   forward          Y[t,out]  = X[t,in]  W[in,out]
@@ -88,7 +91,7 @@ template <int ROWS, bool KMAJOR> struct Stager {
     }
 
     // base: address of element (row0, k0) of the operand.  Full k tile: no k test.
-    __device__ __forceinline__ void load(const bf16 *base) {
+    __device__ __forceinline__ void load(const void *base) {
         const __amdgpu_buffer_rsrc_t rs = make_rsrc(base);
         if constexpr (KMAJOR) {
 #pragma unroll
@@ -100,7 +103,7 @@ template <int ROWS, bool KMAJOR> struct Stager {
     }
 
     // Last, partial k tile: krem = K - k0 < 64 valid k; the rest reads as zero.
-    __device__ __forceinline__ void load_tail(const bf16 *base, int krem) {
+    __device__ __forceinline__ void load_tail(const void *base, int krem) {
         const __amdgpu_buffer_rsrc_t rs = make_rsrc(base);
         const int tid = threadIdx.x;
         if constexpr (KMAJOR) {
@@ -119,7 +122,7 @@ template <int ROWS, bool KMAJOR> struct Stager {
         }
     }
 
-    __device__ __forceinline__ void store(bf16 *lds) const {
+    template <class E> __device__ __forceinline__ void store(E *lds) const {
         const int tid = threadIdx.x;
         if constexpr (KMAJOR) {
             const int chunk = tid & 7;
@@ -141,8 +144,8 @@ template <int ROWS, bool KMAJOR> struct Stager {
     }
 };
 
-template <int EPI>
-__device__ __forceinline__ void epilogue4(const GemmParams<bf16> &p, int m, int n, const float (&a)[4]) {
+template <int EPI, class E>
+__device__ __forceinline__ void epilogue4(const GemmParams<E> &p, int m, int n, const float (&a)[4]) {
     const size_t idx = (size_t)m * p.ldc + n;
     if constexpr (EPI == EPI_ACCUM_F32) {
         f32x4 o = {a[0], a[1], a[2], a[3]};
@@ -160,36 +163,36 @@ __device__ __forceinline__ void epilogue4(const GemmParams<bf16> &p, int m, int 
             for (int i = 0; i < 4; ++i) r[i] += b[i];
         }
         if constexpr (EPI == EPI_BIAS_RESID) {
-            const bf16x4 x = *reinterpret_cast<const bf16x4 *>(p.aux + idx);
+            const x4<E> x = *reinterpret_cast<const x4<E> *>(p.aux + idx);
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] += (float)x[i];
         }
         if constexpr (EPI == EPI_MUL_DGELU) {
-            const bf16x4 u = *reinterpret_cast<const bf16x4 *>(p.aux + idx);
+            const x4<E> u = *reinterpret_cast<const x4<E> *>(p.aux + idx);
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] *= gelu_grad_f((float)u[i]);
         }
         if constexpr (EPI == EPI_BIAS_GELU) {
-            bf16x4 u;
+            x4<E> u;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                u[i] = (bf16)r[i];
+                u[i] = (E)r[i];
                 r[i] = gelu_f(r[i]);
             }
-            *reinterpret_cast<bf16x4 *>(p.out2 + idx) = u;
+            *reinterpret_cast<x4<E> *>(p.out2 + idx) = u;
         }
-        bf16x4 o;
+        x4<E> o;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o[i] = (bf16)r[i];
-        *reinterpret_cast<bf16x4 *>(p.out + idx) = o;
+        for (int i = 0; i < 4; ++i) o[i] = (E)r[i];
+        *reinterpret_cast<x4<E> *>(p.out + idx) = o;
     }
 }
 
 // The same for 8 consecutive n of one row, with 16-byte accesses (bf16 outputs only): n, ldc multiples of 8 and
 // 16-byte aligned tensors.
-template <int EPI>
-__device__ __forceinline__ void epilogue8(const GemmParams<bf16> &p, int m, int n, const f32x4 &lo, const f32x4 &hi) {
-    static_assert(EPI != EPI_ACCUM_F32, "bf16 outputs only");
+template <int EPI, class E>
+__device__ __forceinline__ void epilogue8(const GemmParams<E> &p, int m, int n, const f32x4 &lo, const f32x4 &hi) {
+    static_assert(EPI != EPI_ACCUM_F32, "16-bit outputs only");
     const size_t idx = (size_t)m * p.ldc + n;
     float r[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
@@ -201,36 +204,36 @@ __device__ __forceinline__ void epilogue8(const GemmParams<bf16> &p, int m, int 
         }
     }
     if constexpr (EPI == EPI_BIAS_RESID) {
-        const bf16x8 x = *reinterpret_cast<const bf16x8 *>(p.aux + idx);
+        const x8<E> x = *reinterpret_cast<const x8<E> *>(p.aux + idx);
 #pragma unroll
         for (int i = 0; i < 8; ++i) r[i] += (float)x[i];
     }
     if constexpr (EPI == EPI_MUL_DGELU) {
-        const bf16x8 u = *reinterpret_cast<const bf16x8 *>(p.aux + idx);
+        const x8<E> u = *reinterpret_cast<const x8<E> *>(p.aux + idx);
 #pragma unroll
         for (int i = 0; i < 8; ++i) r[i] *= gelu_grad_f((float)u[i]);
     }
     if constexpr (EPI == EPI_BIAS_GELU) {
-        bf16x8 u;
+        x8<E> u;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            u[i] = (bf16)r[i];
+            u[i] = (E)r[i];
             r[i] = gelu_f(r[i]);
         }
-        *reinterpret_cast<bf16x8 *>(p.out2 + idx) = u;
+        *reinterpret_cast<x8<E> *>(p.out2 + idx) = u;
     }
-    bf16x8 o;
+    x8<E> o;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[i] = (bf16)r[i];
-    *reinterpret_cast<bf16x8 *>(p.out + idx) = o;
+    for (int i = 0; i < 8; ++i) o[i] = (E)r[i];
+    *reinterpret_cast<x8<E> *>(p.out + idx) = o;
 }
 
-template <int BM, int BN, bool A_KM, bool B_KM, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int tiles_m, int tiles_n) {
+template <int BM, int BN, bool A_KM, bool B_KM, int EPI, class E>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int tiles_m, int tiles_n) {
     constexpr int WM = BM / 2, WN = BN / 2;     // wavefront tile
     constexpr int FM = WM / 32, FN = WN / 32;   // 32x32 MFMA blocks per wavefront
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    E *lds = reinterpret_cast<E *>(smem_raw);
     // stage s: A at s*(BM+BN)*BK, B right after it
     auto As = [&](int s) { return lds + (size_t)s * (BM + BN) * BK; };
     auto Bs = [&](int s) { return lds + (size_t)s * (BM + BN) * BK + BM * BK; };
@@ -269,8 +272,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
     sa.init(p.lda, m0, p.M);
     sb.init(p.ldb, n0, p.N);
     // element (row0, k) of each operand: k-major rows advance by 1 per k, the others by ld per k
-    const bf16 *a_ptr = A_KM ? p.A + (size_t)m0 * p.lda : p.A + m0;
-    const bf16 *b_ptr = B_KM ? p.B + (size_t)n0 * p.ldb : p.B + n0;
+    const E *a_ptr = A_KM ? p.A + (size_t)m0 * p.lda : p.A + m0;
+    const E *b_ptr = B_KM ? p.B + (size_t)n0 * p.ldb : p.B + n0;
     const size_t a_step = A_KM ? (size_t)BK : (size_t)BK * p.lda;
     const size_t b_step = B_KM ? (size_t)BK : (size_t)BK * p.ldb;
     const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
@@ -284,14 +287,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         }
     };
 
-    bf16x8 af[2][FM], bf[2][FN];
-    auto load_frags = [&](int buf, const bf16 *a_lds, const bf16 *b_lds, int ks) {
+    x8<E> af[2][FM], bf[2][FN];
+    auto load_frags = [&](int buf, const E *a_lds, const E *b_lds, int ks) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
-            af[buf][i] = *reinterpret_cast<const bf16x8 *>(a_lds + lds_off(wm * WM + i * 32 + lrow, 2 * ks + lhalf));
+            af[buf][i] = *reinterpret_cast<const x8<E> *>(a_lds + lds_off(wm * WM + i * 32 + lrow, 2 * ks + lhalf));
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-            bf[buf][j] = *reinterpret_cast<const bf16x8 *>(b_lds + lds_off(wn * WN + j * 32 + lrow, 2 * ks + lhalf));
+            bf[buf][j] = *reinterpret_cast<const x8<E> *>(b_lds + lds_off(wn * WN + j * 32 + lrow, 2 * ks + lhalf));
     };
 
     load_tile(0);
@@ -306,7 +309,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         for (int i = i0; i < i1; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[fb][j], af[fb][i], acc[i][j], 0, 0, 0);
+                acc[i][j] = mfma_32x32x16<E>(bf[fb][j], af[fb][i], acc[i][j]);
     };
     auto mfma_step = [&](int fb) { mfma_rows(fb, 0, FM); };
 
@@ -329,8 +332,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
     //   step 3b: second half of the MFMAs | LDS reads of tile kt+1's step-0 operands
     for (; kt + 1 < nk_full; ++kt) {
         const int cur = kt & 1;
-        const bf16 *a_lds = As(cur), *b_lds = Bs(cur);
-        bf16 *a_nxt = As(cur ^ 1), *b_nxt = Bs(cur ^ 1);
+        const E *a_lds = As(cur), *b_lds = Bs(cur);
+        E *a_nxt = As(cur ^ 1), *b_nxt = Bs(cur ^ 1);
 
         sa.load(a_ptr + (size_t)(kt + 1) * a_step);
         load_frags(1, a_lds, b_lds, 1);
@@ -399,7 +402,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
         const int cur = kt & 1;
         const bool more = kt + 1 < nk;
         if (more) load_tile(kt + 1);
-        const bf16 *a_lds = As(cur), *b_lds = Bs(cur);
+        const E *a_lds = As(cur), *b_lds = Bs(cur);
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             const int fb = ks & 1;
@@ -429,7 +432,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
                 const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * lhalf;
                 if (n >= p.N) continue;
                 const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                epilogue4<EPI>(p, m, n, v);
+                epilogue4<EPI, E>(p, m, n, v);
             }
         }
     }
@@ -444,15 +447,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<bf16> p, int 
 // chunk (L%8) ^ swz(r) of that row.  No staging registers, no LDS store instructions, no waits on
 // individual loads: the next k tile streams into the other LDS stage while this one is multiplied,
 // and one vmcnt(0) + barrier per tile publishes it.
-template <int BM, int BN, int WGM, int WGN, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParams<bf16> p, int tiles_m, int tiles_n) {
+template <int BM, int BN, int WGM, int WGN, int EPI, class E>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParams<E> p, int tiles_m, int tiles_n) {
     constexpr int NW = WGM * WGN;                   // wavefronts per workgroup, WGM x WGN over the tile
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int FM = WM / 32, FN = WN / 32;
     constexpr int NIA = BM / (8 * NW), NIB = BN / (8 * NW);     // DMA instructions per wavefront per operand tile
     static_assert(BM == BN, "the operand ring below uses one slot size for both operands");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16 *lds = reinterpret_cast<bf16 *>(smem_raw);
+    E *lds = reinterpret_cast<E *>(smem_raw);
     // LDS is a ring of kSlots operand tiles of BM x BK.  Operand tiles enter it in the order A(0), B(0), A(1),
     // B(1), ...: A(kt) sits in slot (2 kt) mod kSlots and B(kt) in the next one.  Five slots hold two whole k
     // tiles plus half of a third, which is what lets the loads of A(kt+2) start before tile kt is retired.
@@ -519,8 +522,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         const int r = (i * NW + wave) * 8 + (lane >> 3);
         offB[i] = (n0 + r < p.N) ? r * ldb2 + (((lane & 7) ^ swz(r)) << 4) : kBufPoison;
     }
-    const bf16 *a_ptr = p.A + (size_t)m0 * p.lda;
-    const bf16 *b_ptr = p.B + (size_t)n0 * p.ldb;
+    const E *a_ptr = p.A + (size_t)m0 * p.lda;
+    const E *b_ptr = p.B + (size_t)n0 * p.ldb;
     const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
 
     typedef __attribute__((address_space(3))) void *lds_ptr;
@@ -539,7 +542,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     // MFMA operands of the four k steps of a tile, one register buffer each: a step's operands are read
     // from LDS two steps (32 MFMAs) ahead, which rides out the LDS latency spikes that the incoming DMA
     // traffic causes.  qa is the ring slot of the tile's A operand; its B operand is in the next slot.
-    bf16x8 af[4][FM], bf[4][FN];
+    x8<E> af[4][FM], bf[4][FN];
     // LDS byte address of an operand chunk, kept to one register per operand: with 128-row wavefront tiles the
     // swizzle term of row (tile row 0 + 32 i + lrow) is (lane part) ^ (2 i), so chunk 2 ks + lhalf of block i
     // lies at (lane address) ^ (((2 ks) ^ (2 i)) << 4) plus a compile-time offset.
@@ -551,10 +554,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     auto load_frag = [&](int ks, int qa, int f) {
         if (f < FM) {
             const int va = lane_a + qa * (kSlotElems * 2);
-            af[ks][f] = *reinterpret_cast<const bf16x8 *>(smem_raw + ((va ^ ((((2 * ks) ^ (2 * f)) & 7) << 4)) + f * 32 * BK * 2));
+            af[ks][f] = *reinterpret_cast<const x8<E> *>(smem_raw + ((va ^ ((((2 * ks) ^ (2 * f)) & 7) << 4)) + f * 32 * BK * 2));
         } else {
             const int j = f - FM, vb = lane_b + wrap(qa + 1) * (kSlotElems * 2);
-            bf[ks][j] = *reinterpret_cast<const bf16x8 *>(smem_raw + ((vb ^ ((((2 * ks) ^ (2 * j)) & 7) << 4)) + j * 32 * BK * 2));
+            bf[ks][j] = *reinterpret_cast<const x8<E> *>(smem_raw + ((vb ^ ((((2 * ks) ^ (2 * j)) & 7) << 4)) + j * 32 * BK * 2));
         }
     };
     auto load_frags = [&](int ks, int qa) {
@@ -596,7 +599,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         for (int g = 0; g < FM; ++g) {
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                acc[g][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[ks][j], af[ks][g], acc[g][j], 0, 0, 0);
+                acc[g][j] = mfma_32x32x16<E>(bf[ks][j], af[ks][g], acc[g][j]);
             if (do_dma) {
 #pragma unroll
                 for (int u = 0; u < dpg; ++u) dma_one(dma_is_a, dq, dkt, dkrem, dfirst + g * dpg + u);
@@ -674,7 +677,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
                     const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + 8 * c8;
                     const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8);
                     const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8 + 4);
-                    if (m < p.M && n < p.N) epilogue8<EPI>(p, m, n, lo, hi);
+                    if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi);
                 }
                 asm volatile("" ::: "memory");
             }
@@ -692,24 +695,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
                 const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * lhalf;
                 if (n >= p.N) continue;
                 const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                epilogue4<EPI>(p, m, n, v);
+                epilogue4<EPI, E>(p, m, n, v);
             }
         }
     }
 }
 
-template <int BM, int BN, bool A_KM, bool B_KM, int EPI>
-void launch_one(const GemmParams<bf16> &p, hipStream_t s) {
+template <int BM, int BN, bool A_KM, bool B_KM, int EPI, class E>
+void launch_one(const GemmParams<E> &p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16);
-    if constexpr (A_KM && B_KM && BM == 256) smem = (size_t)5 * BM * BK * sizeof(bf16);     // the DMA kernel's operand ring
-    void (*kern)(GemmParams<bf16>, int, int) = gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI>;
-    if constexpr (A_KM && B_KM && BM == 256) kern = gemm_bf16_dma_kernel<BM, BN, 2, 2, EPI>;
+    size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(E);
+    if constexpr (A_KM && B_KM && BM == 256) smem = (size_t)5 * BM * BK * sizeof(E);     // the DMA kernel's operand ring
+    void (*kern)(GemmParams<E>, int, int) = gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI, E>;
+    if constexpr (A_KM && B_KM && BM == 256) kern = gemm_bf16_dma_kernel<BM, BN, 2, 2, EPI, E>;
     char name[96];
+    const char *et = std::is_same<E, bf16>::value ? "bf16" : "f16";       // profile names: gemm_bf16_... or gemm_f16_...
     if (A_KM && B_KM && BM == 256)
-        snprintf(name, sizeof(name), "gemm_bf16_dma_kernel<%d, %d, %d>", BM, BN, EPI);
+        snprintf(name, sizeof(name), "gemm_%s_dma_kernel<%d, %d, %d>", et, BM, BN, EPI);
     else
-        snprintf(name, sizeof(name), "gemm_bf16_kernel<%d, %d, %s, %s, %d>", BM, BN, A_KM ? "true" : "false",
+        snprintf(name, sizeof(name), "gemm_%s_kernel<%d, %d, %s, %s, %d>", et, BM, BN, A_KM ? "true" : "false",
                  B_KM ? "true" : "false", EPI);
     const double mn = (double)p.M * p.N;
     const double out_bytes = EPI == EPI_ACCUM_F32 ? (p.beta != 0.f ? 8.0 : 4.0) : (EPI == EPI_BIAS_GELU ? 4.0 : 2.0);
@@ -733,7 +737,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     }
 }
 
-template <bool A_KM, bool B_KM, int EPI> void launch_tiles(const GemmParams<bf16> &p, hipStream_t s) {
+template <bool A_KM, bool B_KM, int EPI, class E> void launch_tiles(const GemmParams<E> &p, hipStream_t s) {
     // Large tiles when they fill the 256 CUs at least about once (the direct-to-LDS kernel is so much faster per
     // tile that a partly idle second round still wins); smaller ones otherwise.
     const long big = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
@@ -743,10 +747,10 @@ template <bool A_KM, bool B_KM, int EPI> void launch_tiles(const GemmParams<bf16
         const int slices = gemm_splitk_slices(p.M, p.N, p.K);
         if (slices > 1 && p.partial && (size_t)slices * p.M * p.N <= p.partial_floats && p.N % 4 == 0 && p.ldc % 4 == 0 &&
             (reinterpret_cast<uintptr_t>(p.outf) & 15) == 0) {
-            GemmParams<bf16> q = p;
+            GemmParams<E> q = p;
             q.kchunk = ((p.K + slices - 1) / slices + BK - 1) / BK * BK;
             q.ksplit = (p.K + q.kchunk - 1) / q.kchunk;          // rounding the slice length up may have emptied the last ones
-            launch_one<256, 256, A_KM, B_KM, EPI>(q, s);
+            launch_one<256, 256, A_KM, B_KM, EPI, E>(q, s);
             ProfScope scope("splitk_reduce_kernel", (double)q.ksplit * p.M * p.N,
                             4.0 * p.M * p.N * (q.ksplit + (p.beta != 0.f ? 2.0 : 1.0)), s);
             const size_t quads = (size_t)p.M * (p.N / 4);
@@ -757,9 +761,9 @@ template <bool A_KM, bool B_KM, int EPI> void launch_tiles(const GemmParams<bf16
         }
     }
     if (big >= 128)
-        launch_one<256, 256, A_KM, B_KM, EPI>(p, s);
+        launch_one<256, 256, A_KM, B_KM, EPI, E>(p, s);
     else
-        launch_one<128, 128, A_KM, B_KM, EPI>(p, s);
+        launch_one<128, 128, A_KM, B_KM, EPI, E>(p, s);
 }
 
 }  // namespace
@@ -780,32 +784,35 @@ int gemm_splitk_slices(int M, int N, int K) {
     return 1;
 }
 
-void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s) {
+template <class E>
+void launch_gemm_mfma(const GemmParams<E> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s) {
     if (p.M == 0 || p.N == 0) return;
     // The three operand layouts the layer uses; every epilogue is tied to the family that needs it.
     if (a_kmajor && !b_kmajor) {          // forward
         switch (epi) {
-            case EPI_BIAS: launch_tiles<true, false, EPI_BIAS>(p, s); return;
-            case EPI_BIAS_RESID: launch_tiles<true, false, EPI_BIAS_RESID>(p, s); return;
-            case EPI_BIAS_GELU: launch_tiles<true, false, EPI_BIAS_GELU>(p, s); return;
-            case EPI_STORE: launch_tiles<true, false, EPI_STORE>(p, s); return;
+            case EPI_BIAS: launch_tiles<true, false, EPI_BIAS, E>(p, s); return;
+            case EPI_BIAS_RESID: launch_tiles<true, false, EPI_BIAS_RESID, E>(p, s); return;
+            case EPI_BIAS_GELU: launch_tiles<true, false, EPI_BIAS_GELU, E>(p, s); return;
+            case EPI_STORE: launch_tiles<true, false, EPI_STORE, E>(p, s); return;
             default: break;
         }
     } else if (a_kmajor && b_kmajor) {    // both operands k-contiguous: the layout the layer stack uses
         switch (epi) {
-            case EPI_STORE: launch_tiles<true, true, EPI_STORE>(p, s); return;
-            case EPI_BIAS: launch_tiles<true, true, EPI_BIAS>(p, s); return;
-            case EPI_BIAS_RESID: launch_tiles<true, true, EPI_BIAS_RESID>(p, s); return;
-            case EPI_BIAS_GELU: launch_tiles<true, true, EPI_BIAS_GELU>(p, s); return;
-            case EPI_MUL_DGELU: launch_tiles<true, true, EPI_MUL_DGELU>(p, s); return;
-            case EPI_ACCUM_F32: launch_tiles<true, true, EPI_ACCUM_F32>(p, s); return;
+            case EPI_STORE: launch_tiles<true, true, EPI_STORE, E>(p, s); return;
+            case EPI_BIAS: launch_tiles<true, true, EPI_BIAS, E>(p, s); return;
+            case EPI_BIAS_RESID: launch_tiles<true, true, EPI_BIAS_RESID, E>(p, s); return;
+            case EPI_BIAS_GELU: launch_tiles<true, true, EPI_BIAS_GELU, E>(p, s); return;
+            case EPI_MUL_DGELU: launch_tiles<true, true, EPI_MUL_DGELU, E>(p, s); return;
+            case EPI_ACCUM_F32: launch_tiles<true, true, EPI_ACCUM_F32, E>(p, s); return;
         }
     } else if (!a_kmajor && !b_kmajor) {  // weight gradient
-        if (epi == EPI_ACCUM_F32) { launch_tiles<false, false, EPI_ACCUM_F32>(p, s); return; }
-        if (epi == EPI_STORE) { launch_tiles<false, false, EPI_STORE>(p, s); return; }
+        if (epi == EPI_ACCUM_F32) { launch_tiles<false, false, EPI_ACCUM_F32, E>(p, s); return; }
+        if (epi == EPI_STORE) { launch_tiles<false, false, EPI_STORE, E>(p, s); return; }
     }
     // Unsupported combination: callers validate before launching, so reaching this is a bug.
     abort();
 }
+template void launch_gemm_mfma<bf16>(const GemmParams<bf16> &, bool, bool, Epilogue, hipStream_t);
+template void launch_gemm_mfma<f16>(const GemmParams<f16> &, bool, bool, Epilogue, hipStream_t);
 
 }  // namespace lga

@@ -8,8 +8,8 @@
 namespace lga {
 
 // ---- element-wise / row kernels (rowops.hip) ---------------------------------------------
-// fp32 -> bf16 copy of a parameter vector ("restore": parameters converted to 16 bits before use).
-void launch_cast_f32_to_bf16(const float *src, bf16 *dst, size_t n, hipStream_t s);
+// fp32 -> 16-bit copy of a parameter vector ("restore": parameters converted to 16 bits before use); E = bf16 or f16.
+template <class E> void launch_cast_f32_to_16(const float *src, E *dst, size_t n, hipStream_t s);
 // Counter-based N(0, std^2) fill: element i gets a value that depends only on (seed, i).
 void launch_fill_normal(float *dst, size_t n, float std, uint64_t seed, hipStream_t s);
 void launch_fill_const(float *dst, size_t n, float value, hipStream_t s);
@@ -33,12 +33,19 @@ template <class T>
 void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd, int rows, int cols, int ld,
                    float beta, float *out0, float *out1, float *partial, hipStream_t s);
 
-// out[c][r] = in[r][c] for bf16 matrices; R, C, ldi, ldo multiples of 8, 16-byte aligned bases.
-void launch_transpose_bf16(const bf16 *in, bf16 *out, int R, int C, long ldi, long ldo, hipStream_t s);
+// out[c][r] = in[r][c] for matrices of 16-bit elements of any format; R, C, ldi, ldo multiples of 8, 16-byte
+// aligned bases.
+void launch_transpose16(const void *in, void *out, int R, int C, long ldi, long ldo, hipStream_t s);
 
-// Adam update of n parameters in place; optionally also writes the bf16 copy of the new weights.
-void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t n, float lr, float beta1,
-                 float beta2, float eps, int step, hipStream_t s);
+// 1 into *flag if any of the n values is infinite or not a number (*flag is not cleared here).
+void launch_nonfinite_flag(const float *g, size_t n, int *flag, hipStream_t s);
+
+// Adam update of n parameters in place; optionally (w16 != NULL) also writes the 16-bit copy of the new weights in
+// format E (bf16 or f16).  The gradient is multiplied by grad_mul before use (1 / loss scale).  skip != NULL: the
+// whole update is left out when *skip != 0 (gradient found non-finite).
+template <class E>
+void launch_adam(float *w, float *m, float *v, const float *g, E *w16, size_t n, float lr, float beta1, float beta2,
+                 float eps, int step, float grad_mul, const int *skip, hipStream_t s);
 
 // ---- GEMMs -------------------------------------------------------------------------------
 // C[M,N] = sum_k A(m,k) B(k,n), then the epilogue.
@@ -46,9 +53,11 @@ void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t
 //   b_kmajor: B is stored [N][ldb] (k contiguous); otherwise [K][ldb] (n contiguous).
 // fp32 correctness-mode kernel (plain FMA, LDS tiles):
 void launch_gemm_f32(const GemmParams<float> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
-// bf16 MFMA kernel, fp32 accumulate.  Needs lda, ldb, ldc, N multiples of 8 and 16-byte aligned bases.
-void launch_gemm_bf16(const GemmParams<bf16> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
-// Into how many slices of the k range launch_gemm_bf16 cuts an fp32-accumulating, k-contiguous GEMM whose output has
+// 16-bit MFMA kernel (E = bf16 or f16), fp32 accumulate.  Needs lda, ldb, ldc, N multiples of 8 and 16-byte aligned
+// bases.
+template <class E>
+void launch_gemm_mfma(const GemmParams<E> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
+// Into how many slices of the k range launch_gemm_mfma cuts an fp32-accumulating, k-contiguous GEMM whose output has
 // too few 256 x 256 tiles to occupy the chip (1 = not at all); it then needs slices * M * N floats of scratch.
 // k = 0 asks for the largest count any k would give (for sizing the scratch).
 int gemm_splitk_slices(int M, int N, int K);
@@ -66,11 +75,12 @@ template <class T> void launch_attn_fwd_simple(const T *qkv, T *out, float *lse,
 template <class T>
 void launch_attn_bwd_simple(const T *qkv, const T *out, const float *lse, const T *dout, T *dqkv, float *delta,
                             AttnShape sh, hipStream_t s);
-// MFMA kernels with LDS-resident online softmax (bf16).  Head sizes other than those
+// MFMA kernels with LDS-resident online softmax (E = bf16 or f16).  Head sizes other than those
 // attn_bf16_supports() accepts are routed to the one-wavefront kernels above.
 bool attn_bf16_supports(int dh);
-void launch_attn_fwd_bf16(const bf16 *qkv, bf16 *out, float *lse, AttnShape sh, hipStream_t s);
-void launch_attn_bwd_bf16(const bf16 *qkv, const bf16 *out, const float *lse, const bf16 *dout, bf16 *dqkv,
-                          float *delta, AttnShape sh, hipStream_t s);
+template <class E> void launch_attn_fwd_mfma(const E *qkv, E *out, float *lse, AttnShape sh, hipStream_t s);
+template <class E>
+void launch_attn_bwd_mfma(const E *qkv, const E *out, const float *lse, const E *dout, E *dqkv, float *delta,
+                          AttnShape sh, hipStream_t s);
 
 }  // namespace lga

@@ -24,7 +24,16 @@ int done(const char *what) {
     return LGA_OK;
 }
 
-bool dtype_ok(int32_t dt) { return dt == LGA_FP32 || dt == LGA_BF16; }
+bool dtype_ok(int32_t dt) { return dt == LGA_FP32 || dt == LGA_BF16 || dt == LGA_FP16; }
+bool dtype16(int32_t dt) { return dt == LGA_BF16 || dt == LGA_FP16; }
+
+// body(E{}) with E = the 16-bit element type that dt names
+template <class F> void with16(int32_t dt, F &&body) {
+    if (dt == LGA_FP16) body(f16{});
+    else body(bf16{});
+}
+template <class E> const E *in16(const void *p) { return static_cast<const E *>(p); }
+template <class E> E *out16(void *p) { return static_cast<E *>(p); }
 
 }  // namespace
 
@@ -54,21 +63,24 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
         launch_gemm_f32(p, akm, bkm, e, s);
     } else {
         if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || ((akm || bkm) && K % 8) || (!akm && M % 8))
-            return err(LGA_ERR_SHAPE, "bf16 GEMM needs lda, ldb, ldc, N (K if an operand is k-contiguous, M if A is "
+            return err(LGA_ERR_SHAPE, "16-bit GEMM needs lda, ldb, ldc, N (K if an operand is k-contiguous, M if A is "
                                       "m-contiguous) to be multiples of 8");
         if (!a16(A) || !a16(B) || !a16(out) || !a16(out2) || !a16(outf) || !a16(bias) || !a16(aux))
-            return err(LGA_ERR_SHAPE, "bf16 GEMM needs 16-byte aligned pointers");
+            return err(LGA_ERR_SHAPE, "16-bit GEMM needs 16-byte aligned pointers");
         bool ok = false;
         if (akm && !bkm) ok = e == EPI_STORE || e == EPI_BIAS || e == EPI_BIAS_RESID || e == EPI_BIAS_GELU;
         else if (akm && bkm) ok = true;
         else if (!akm && !bkm) ok = e == EPI_STORE || e == EPI_ACCUM_F32;
-        if (!ok) return err(LGA_ERR_SHAPE, "bf16 GEMM: this layout/epilogue pair is not built");
-        GemmParams<bf16> p{};
-        p.A = static_cast<const bf16 *>(A); p.B = static_cast<const bf16 *>(B);
-        p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
-        p.out = static_cast<bf16 *>(out); p.out2 = static_cast<bf16 *>(out2); p.outf = outf;
-        p.bias = bias; p.aux = static_cast<const bf16 *>(aux); p.beta = beta;
-        launch_gemm_bf16(p, akm, bkm, e, s);
+        if (!ok) return err(LGA_ERR_SHAPE, "16-bit GEMM: this layout/epilogue pair is not built");
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            GemmParams<E> p{};
+            p.A = in16<E>(A); p.B = in16<E>(B);
+            p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+            p.out = out16<E>(out); p.out2 = out16<E>(out2); p.outf = outf;
+            p.bias = bias; p.aux = in16<E>(aux); p.beta = beta;
+            launch_gemm_mfma<E>(p, akm, bkm, e, s);
+        });
     }
     return done("lga_op_gemm");
 }
@@ -78,20 +90,24 @@ int32_t lga_op_gemm_splitk_slices(int32_t M, int32_t N, int32_t K) {
     return gemm_splitk_slices(M, N, K);
 }
 
-int lga_op_gemm_splitk(int32_t M, int32_t N, int32_t K, const void *A, int32_t lda, const void *B, int32_t ldb,
+int lga_op_gemm_splitk(int32_t dtype, int32_t M, int32_t N, int32_t K, const void *A, int32_t lda, const void *B, int32_t ldb,
                        float *outf, int32_t ldc, float beta, float *scratch, uint64_t scratch_floats, void *stream) {
+    if (!dtype16(dtype)) return err(LGA_ERR_ARG, "dtype must be LGA_BF16 or LGA_FP16");
     if (M < 0 || N < 0 || K < 0) return err(LGA_ERR_SHAPE, "negative size");
     if (!A || !B || !outf) return err(LGA_ERR_ARG, "NULL argument");
     if (lda < K || ldb < K || ldc < N) return err(LGA_ERR_SHAPE, "leading dimension too small");
     if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || K % 8)
-        return err(LGA_ERR_SHAPE, "bf16 GEMM needs lda, ldb, ldc, N and K to be multiples of 8");
-    if (!a16(A) || !a16(B) || !a16(outf) || !a16(scratch)) return err(LGA_ERR_SHAPE, "bf16 GEMM needs 16-byte aligned pointers");
-    GemmParams<bf16> p{};
-    p.A = static_cast<const bf16 *>(A); p.B = static_cast<const bf16 *>(B);
-    p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
-    p.outf = outf; p.beta = beta;
-    p.partial = scratch; p.partial_floats = scratch ? scratch_floats : 0;
-    launch_gemm_bf16(p, true, true, EPI_ACCUM_F32, reinterpret_cast<hipStream_t>(stream));
+        return err(LGA_ERR_SHAPE, "16-bit GEMM needs lda, ldb, ldc, N and K to be multiples of 8");
+    if (!a16(A) || !a16(B) || !a16(outf) || !a16(scratch)) return err(LGA_ERR_SHAPE, "16-bit GEMM needs 16-byte aligned pointers");
+    with16(dtype, [&](auto tag) {
+        using E = decltype(tag);
+        GemmParams<E> p{};
+        p.A = in16<E>(A); p.B = in16<E>(B);
+        p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+        p.outf = outf; p.beta = beta;
+        p.partial = scratch; p.partial_floats = scratch ? scratch_floats : 0;
+        launch_gemm_mfma<E>(p, true, true, EPI_ACCUM_F32, reinterpret_cast<hipStream_t>(stream));
+    });
     return done("lga_op_gemm_splitk");
 }
 
@@ -104,7 +120,10 @@ int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const flo
     if (dtype == LGA_FP32)
         launch_layernorm_fwd<float>(static_cast<const float *>(x), g, b, static_cast<float *>(y), mean, rstd, rows, d, eps, s);
     else
-        launch_layernorm_fwd<bf16>(static_cast<const bf16 *>(x), g, b, static_cast<bf16 *>(y), mean, rstd, rows, d, eps, s);
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            launch_layernorm_fwd<E>(in16<E>(x), g, b, out16<E>(y), mean, rstd, rows, d, eps, s);
+        });
     return done("lga_op_layernorm_fwd");
 }
 
@@ -122,10 +141,11 @@ int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const flo
         launch_layernorm_bwd_dx<float>(static_cast<const float *>(dy), static_cast<const float *>(x), mean, rstd, g,
                                        static_cast<const float *>(resid), static_cast<float *>(dx), rows, d, s);
     } else {
-        launch_colsum<bf16>(static_cast<const bf16 *>(dy), static_cast<const bf16 *>(x), mean, rstd, rows, d, d, beta,
-                            dbeta, dgamma, scratch, s);
-        launch_layernorm_bwd_dx<bf16>(static_cast<const bf16 *>(dy), static_cast<const bf16 *>(x), mean, rstd, g,
-                                      static_cast<const bf16 *>(resid), static_cast<bf16 *>(dx), rows, d, s);
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            launch_colsum<E>(in16<E>(dy), in16<E>(x), mean, rstd, rows, d, d, beta, dbeta, dgamma, scratch, s);
+            launch_layernorm_bwd_dx<E>(in16<E>(dy), in16<E>(x), mean, rstd, g, in16<E>(resid), out16<E>(dx), rows, d, s);
+        });
     }
     return done("lga_op_layernorm_bwd");
 }
@@ -135,8 +155,7 @@ int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ld
     if (R % 8 || C % 8 || ldi % 8 || ldo % 8 || !a16(in) || !a16(out))
         return err(LGA_ERR_SHAPE, "transpose needs sizes and leading dimensions that are multiples of 8, 16-byte aligned");
     if ((!in || !out) && R > 0 && C > 0) return err(LGA_ERR_ARG, "NULL argument");
-    launch_transpose_bf16(static_cast<const bf16 *>(in), static_cast<bf16 *>(out), R, C, ldi, ldo,
-                          reinterpret_cast<hipStream_t>(stream));
+    launch_transpose16(in, out, R, C, ldi, ldo, reinterpret_cast<hipStream_t>(stream));
     return done("lga_op_transpose");
 }
 
@@ -154,7 +173,10 @@ int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int3
     if (dtype == LGA_FP32)
         launch_colsum<float>(static_cast<const float *>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr, scratch, s);
     else
-        launch_colsum<bf16>(static_cast<const bf16 *>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr, scratch, s);
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            launch_colsum<E>(in16<E>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr, scratch, s);
+        });
     return done("lga_op_colsum");
 }
 
@@ -164,14 +186,19 @@ int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out
     if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
     if ((double)n_seq * heads * ((s_len + 127) / 128) > 2.0e9) return err(LGA_ERR_SHAPE, "sizes overflow the index range");
     if (!qkv || !out || !lse) return err(LGA_ERR_ARG, "NULL argument");
-    if (kind == 1 && (dtype != LGA_BF16 || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out)))
-        return err(LGA_ERR_SHAPE, "MFMA attention needs bf16, 16-byte aligned tensors and d_h a multiple of 8 up to 160");
+    if (kind == 1 && (!dtype16(dtype) || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out)))
+        return err(LGA_ERR_SHAPE, "MFMA attention needs a 16-bit dtype, 16-byte aligned tensors and d_h a multiple of 8 up to 160");
     if ((size_t)(dh + s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
     const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (kind == 1) launch_attn_fwd_bf16(static_cast<const bf16 *>(qkv), static_cast<bf16 *>(out), lse, sh, s);
-    else if (dtype == LGA_FP32) launch_attn_fwd_simple<float>(static_cast<const float *>(qkv), static_cast<float *>(out), lse, sh, s);
-    else launch_attn_fwd_simple<bf16>(static_cast<const bf16 *>(qkv), static_cast<bf16 *>(out), lse, sh, s);
+    if (dtype == LGA_FP32)
+        launch_attn_fwd_simple<float>(static_cast<const float *>(qkv), static_cast<float *>(out), lse, sh, s);
+    else
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            if (kind == 1) launch_attn_fwd_mfma<E>(in16<E>(qkv), out16<E>(out), lse, sh, s);
+            else launch_attn_fwd_simple<E>(in16<E>(qkv), out16<E>(out), lse, sh, s);
+        });
     return done("lga_op_attention_fwd");
 }
 
@@ -182,29 +209,43 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
     if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
     if ((double)n_seq * heads * ((s_len + 127) / 128) > 2.0e9) return err(LGA_ERR_SHAPE, "sizes overflow the index range");
     if (!qkv || !out || !lse || !dout || !dqkv || !delta) return err(LGA_ERR_ARG, "NULL argument");
-    if (kind == 1 && (dtype != LGA_BF16 || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out) || !a16(dout) || !a16(dqkv)))
-        return err(LGA_ERR_SHAPE, "MFMA attention needs bf16, 16-byte aligned tensors and d_h a multiple of 8 up to 160");
+    if (kind == 1 && (!dtype16(dtype) || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out) || !a16(dout) || !a16(dqkv)))
+        return err(LGA_ERR_SHAPE, "MFMA attention needs a 16-bit dtype, 16-byte aligned tensors and d_h a multiple of 8 up to 160");
     if ((size_t)(2 * dh + 2 * s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
     const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (kind == 1)
-        launch_attn_bwd_bf16(static_cast<const bf16 *>(qkv), static_cast<const bf16 *>(out), lse,
-                             static_cast<const bf16 *>(dout), static_cast<bf16 *>(dqkv), delta, sh, s);
-    else if (dtype == LGA_FP32)
+    if (dtype == LGA_FP32)
         launch_attn_bwd_simple<float>(static_cast<const float *>(qkv), static_cast<const float *>(out), lse,
                                       static_cast<const float *>(dout), static_cast<float *>(dqkv), delta, sh, s);
     else
-        launch_attn_bwd_simple<bf16>(static_cast<const bf16 *>(qkv), static_cast<const bf16 *>(out), lse,
-                                     static_cast<const bf16 *>(dout), static_cast<bf16 *>(dqkv), delta, sh, s);
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            if (kind == 1) launch_attn_bwd_mfma<E>(in16<E>(qkv), in16<E>(out), lse, in16<E>(dout), out16<E>(dqkv), delta, sh, s);
+            else launch_attn_bwd_simple<E>(in16<E>(qkv), in16<E>(out), lse, in16<E>(dout), out16<E>(dqkv), delta, sh, s);
+        });
     return done("lga_op_attention_bwd");
 }
 
-int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, uint64_t n, const lga_adam *adam,
-                void *stream) {
+int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t w16_dtype, uint64_t n,
+                const lga_adam *adam, int32_t *nonfinite, void *stream) {
     if (!adam || (n > 0 && (!w || !m || !v || !g))) return err(LGA_ERR_ARG, "NULL argument");
     if (adam->step < 1) return err(LGA_ERR_STATE, "Adam step t must be >= 1");
-    launch_adam(w, m, v, g, static_cast<bf16 *>(w16), n, adam->lr, adam->beta1, adam->beta2, adam->eps, adam->step,
-                reinterpret_cast<hipStream_t>(stream));
+    if (w16 && !dtype16(w16_dtype)) return err(LGA_ERR_ARG, "w16_dtype must be LGA_BF16 or LGA_FP16");
+    if (!(adam->loss_scale >= 0.f)) return err(LGA_ERR_ARG, "loss_scale must be >= 0");
+    if (adam->skip_nonfinite && !nonfinite) return err(LGA_ERR_ARG, "skip_nonfinite needs the nonfinite flag");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const float grad_mul = (adam->loss_scale > 0.f && adam->loss_scale != 1.f) ? 1.0f / adam->loss_scale : 1.0f;
+    int *flag = nullptr;
+    if (adam->skip_nonfinite) {
+        flag = nonfinite;
+        launch_fill_const(reinterpret_cast<float *>(flag), 1, 0.f, s);
+        launch_nonfinite_flag(g, n, flag, s);
+    }
+    with16(w16 ? w16_dtype : LGA_BF16, [&](auto tag) {
+        using E = decltype(tag);
+        launch_adam<E>(w, m, v, g, out16<E>(w16), n, adam->lr, adam->beta1, adam->beta2, adam->eps, adam->step, grad_mul,
+                       flag, s);
+    });
     return done("lga_op_adam");
 }
 

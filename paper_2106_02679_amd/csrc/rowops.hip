@@ -1,6 +1,6 @@
 // HBM-bound kernels of the layer stack: parameter cast, LayerNorm forward / backward, column
 // sums (bias and LayerNorm-affine gradients), Adam, counter-based weight fill.
-// All arithmetic is fp32; T (float or bf16) is only the storage type of activations.
+// All arithmetic is fp32; T (float, bf16 or f16) is only the storage type of activations.
 #include <algorithm>
 
 #include "kernels.h"
@@ -12,6 +12,7 @@ namespace {
 template <class T> struct VecOf;
 template <> struct VecOf<float> { static constexpr int N = 4; };
 template <> struct VecOf<bf16> { static constexpr int N = 8; };
+template <> struct VecOf<f16> { static constexpr int N = 8; };
 
 template <class T, int N> struct alignas(sizeof(T) * N) Pack { T v[N]; };
 
@@ -38,15 +39,31 @@ template <class T, int N> __device__ __forceinline__ void store_pack(T *p, const
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ------------------------------------------------------------------------------------------
-__global__ void cast_kernel(const float *__restrict__ src, bf16 *__restrict__ dst, size_t n, size_t n4) {
+template <class E>
+__global__ void cast_kernel(const float *__restrict__ src, E *__restrict__ dst, size_t n, size_t n4) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
         const f32x4 v = reinterpret_cast<const f32x4 *>(src)[i];
-        bf16x4 o;
-        o[0] = (bf16)v[0]; o[1] = (bf16)v[1]; o[2] = (bf16)v[2]; o[3] = (bf16)v[3];
-        reinterpret_cast<bf16x4 *>(dst)[i] = o;
+        x4<E> o;
+        o[0] = (E)v[0]; o[1] = (E)v[1]; o[2] = (E)v[2]; o[3] = (E)v[3];
+        reinterpret_cast<x4<E> *>(dst)[i] = o;
     }
-    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = (bf16)src[i];
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = (E)src[i];
+}
+
+// *flag = 1 if any of the n values is not finite.  Every thread that sees one stores the same 1 (plain vector store).
+__global__ __launch_bounds__(256) void nonfinite_flag_kernel(const float *__restrict__ g, size_t n, size_t n4,
+                                                             int *__restrict__ flag) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        const f32x4 v = reinterpret_cast<const f32x4 *>(g)[i];
+        // x - x is 0 for finite x and NaN for infinities and NaNs
+        const float t = (v[0] - v[0]) + (v[1] - v[1]) + (v[2] - v[2]) + (v[3] - v[3]);
+        bad |= !(t == 0.f);
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) bad |= !(g[i] - g[i] == 0.f);
+    if (bad) *flag = 1;
 }
 
 __global__ void fill_const_kernel(float *dst, size_t n, float value) {
@@ -432,6 +449,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restri
 // Adam: streams w, m, v, g once (16 B/param in, 12 B + 2 B out).
 struct AdamConsts {
     float beta1, beta2, omb1, omb2, inv_bc1, inv_bc2, lr, eps;
+    float grad_mul;        // the gradient is multiplied by this first (1 / loss scale; 1 = no scaling, exact)
 };
 
 __device__ __forceinline__ void adam_one(float &w, float &m, float &v, float g, const AdamConsts &c) {
@@ -442,9 +460,12 @@ __device__ __forceinline__ void adam_one(float &w, float &m, float &v, float g, 
     w = w - c.lr * mh / (sqrtf(vh) + c.eps);
 }
 
+template <class E>
 __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float *__restrict__ m,
                                                    float *__restrict__ v, const float *__restrict__ g,
-                                                   bf16 *__restrict__ w16, size_t n, size_t n4, AdamConsts c) {
+                                                   E *__restrict__ w16, size_t n, size_t n4, AdamConsts c,
+                                                   const int *__restrict__ skip) {
+    if (skip && *skip) return;          // the gradient held a non-finite value: this update is left out as a whole
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
         f32x4 wv = reinterpret_cast<f32x4 *>(w)[i];
@@ -454,7 +475,7 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float 
         float wa[4] = {wv[0], wv[1], wv[2], wv[3]}, ma[4] = {mv[0], mv[1], mv[2], mv[3]};
         float va[4] = {vv[0], vv[1], vv[2], vv[3]};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) adam_one(wa[k], ma[k], va[k], gv[k], c);
+        for (int k = 0; k < 4; ++k) adam_one(wa[k], ma[k], va[k], gv[k] * c.grad_mul, c);
         wv = {wa[0], wa[1], wa[2], wa[3]};
         mv = {ma[0], ma[1], ma[2], ma[3]};
         vv = {va[0], va[1], va[2], va[3]};
@@ -462,16 +483,16 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float 
         reinterpret_cast<f32x4 *>(m)[i] = mv;
         reinterpret_cast<f32x4 *>(v)[i] = vv;
         if (w16) {
-            bf16x4 o;
-            o[0] = (bf16)wa[0]; o[1] = (bf16)wa[1]; o[2] = (bf16)wa[2]; o[3] = (bf16)wa[3];
-            reinterpret_cast<bf16x4 *>(w16)[i] = o;
+            x4<E> o;
+            o[0] = (E)wa[0]; o[1] = (E)wa[1]; o[2] = (E)wa[2]; o[3] = (E)wa[3];
+            reinterpret_cast<x4<E> *>(w16)[i] = o;
         }
     }
     for (size_t i = n4 * 4 + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         float wa = w[i], ma = m[i], va = v[i];
-        adam_one(wa, ma, va, g[i], c);
+        adam_one(wa, ma, va, g[i] * c.grad_mul, c);
         w[i] = wa; m[i] = ma; v[i] = va;
-        if (w16) w16[i] = (bf16)wa;
+        if (w16) w16[i] = (E)wa;
     }
 }
 
@@ -482,9 +503,9 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float 
 constexpr int kTrTile = 128;
 constexpr int kTrPitch = kTrTile + 8;     // elements; keeps 16-byte alignment and skews the banks
 
-__global__ __launch_bounds__(256) void transpose16_kernel(const bf16 *__restrict__ in, bf16 *__restrict__ out, int R,
-                                                          int C, long ldi, long ldo) {
-    __shared__ __attribute__((aligned(16))) bf16 tile[kTrTile * kTrPitch];     // [c][r]
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
+                                                          int R, int C, long ldi, long ldo) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kTrTile * kTrPitch];     // [c][r]
     const int r0 = blockIdx.y * kTrTile, c0 = blockIdx.x * kTrTile;
     const int tid = threadIdx.x;
     {
@@ -529,11 +550,20 @@ inline int grid_for(size_t work_items, int block, int max_blocks = 256 * 16) {
 }  // namespace
 
 // ==========================================================================================
-void launch_cast_f32_to_bf16(const float *src, bf16 *dst, size_t n, hipStream_t s) {
+template <class E> void launch_cast_f32_to_16(const float *src, E *dst, size_t n, hipStream_t s) {
     if (n == 0) return;
     const size_t n4 = (aligned16(src) && (reinterpret_cast<uintptr_t>(dst) & 7u) == 0) ? n / 4 : 0;   // vector part
     ProfScope scope("cast_kernel", 0.0, 6.0 * n, s);
-    hipLaunchKernelGGL(cast_kernel, dim3(grid_for(n / 4 + 1, 256)), dim3(256), 0, s, src, dst, n, n4);
+    hipLaunchKernelGGL(cast_kernel<E>, dim3(grid_for(n / 4 + 1, 256)), dim3(256), 0, s, src, dst, n, n4);
+}
+template void launch_cast_f32_to_16<bf16>(const float *, bf16 *, size_t, hipStream_t);
+template void launch_cast_f32_to_16<f16>(const float *, f16 *, size_t, hipStream_t);
+
+void launch_nonfinite_flag(const float *g, size_t n, int *flag, hipStream_t s) {
+    if (n == 0) return;
+    ProfScope scope("nonfinite_flag_kernel", 0.0, 4.0 * n, s);
+    const size_t n4 = aligned16(g) ? n / 4 : 0;
+    hipLaunchKernelGGL(nonfinite_flag_kernel, dim3(grid_for(n / 4 + 1, 256, 256 * 8)), dim3(256), 0, s, g, n, n4, flag);
 }
 
 void launch_fill_normal(float *dst, size_t n, float std, uint64_t seed, hipStream_t s) {
@@ -573,6 +603,8 @@ template void launch_layernorm_fwd<float>(const float *, const float *, const fl
                                           int, float, hipStream_t);
 template void launch_layernorm_fwd<bf16>(const bf16 *, const float *, const float *, bf16 *, float *, float *, int,
                                          int, float, hipStream_t);
+template void launch_layernorm_fwd<f16>(const f16 *, const float *, const float *, f16 *, float *, float *, int,
+                                         int, float, hipStream_t);
 
 template <class T>
 void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const float *rstd, const float *g,
@@ -601,6 +633,8 @@ template void launch_layernorm_bwd_dx<float>(const float *, const float *, const
                                              const float *, const float *, float *, int, int, hipStream_t);
 template void launch_layernorm_bwd_dx<bf16>(const bf16 *, const bf16 *, const float *, const float *, const float *,
                                             const bf16 *, bf16 *, int, int, hipStream_t);
+template void launch_layernorm_bwd_dx<f16>(const f16 *, const f16 *, const float *, const float *, const float *,
+                                            const f16 *, f16 *, int, int, hipStream_t);
 
 size_t colsum_partial_floats(int rows, int cols) {
     const size_t chunks = ((size_t)rows + kColsumRows - 1) / kColsumRows;
@@ -642,16 +676,20 @@ template void launch_colsum<float>(const float *, const float *, const float *, 
                                    float *, float *, float *, hipStream_t);
 template void launch_colsum<bf16>(const bf16 *, const bf16 *, const float *, const float *, int, int, int, float,
                                   float *, float *, float *, hipStream_t);
+template void launch_colsum<f16>(const f16 *, const f16 *, const float *, const float *, int, int, int, float,
+                                  float *, float *, float *, hipStream_t);
 
-void launch_transpose_bf16(const bf16 *in, bf16 *out, int R, int C, long ldi, long ldo, hipStream_t s) {
+void launch_transpose16(const void *in, void *out, int R, int C, long ldi, long ldo, hipStream_t s) {
     if (R == 0 || C == 0) return;
     ProfScope scope("transpose16_kernel", 0.0, 4.0 * R * (double)C, s);
     dim3 grid((C + kTrTile - 1) / kTrTile, (R + kTrTile - 1) / kTrTile);
-    hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, s, in, out, R, C, ldi, ldo);
+    hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t *>(in),
+                       static_cast<uint16_t *>(out), R, C, ldi, ldo);
 }
 
-void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t n, float lr, float beta1,
-                 float beta2, float eps, int step, hipStream_t s) {
+template <class E>
+void launch_adam(float *w, float *m, float *v, const float *g, E *w16, size_t n, float lr, float beta1, float beta2,
+                 float eps, int step, float grad_mul, const int *skip, hipStream_t s) {
     if (n == 0) return;
     AdamConsts c;
     c.beta1 = beta1;
@@ -662,12 +700,17 @@ void launch_adam(float *w, float *m, float *v, const float *g, bf16 *w16, size_t
     c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)beta2, (double)step)));
     c.lr = lr;
     c.eps = eps;
+    c.grad_mul = grad_mul;
     ProfScope scope("adam_kernel", 12.0 * n, (w16 ? 30.0 : 28.0) * n, s);
     const bool vec = aligned16(w) && aligned16(m) && aligned16(v) && aligned16(g) &&
                      (reinterpret_cast<uintptr_t>(w16) & 7u) == 0;
     const size_t n4 = vec ? n / 4 : 0;
-    hipLaunchKernelGGL(adam_kernel, dim3(grid_for(n / 4 + 1, 256, 256 * 8)), dim3(256), 0, s, w, m, v, g, w16, n, n4,
-                       c);
+    hipLaunchKernelGGL(adam_kernel<E>, dim3(grid_for(n / 4 + 1, 256, 256 * 8)), dim3(256), 0, s, w, m, v, g, w16, n, n4,
+                       c, skip);
 }
+template void launch_adam<bf16>(float *, float *, float *, const float *, bf16 *, size_t, float, float, float, float,
+                                int, float, const int *, hipStream_t);
+template void launch_adam<f16>(float *, float *, float *, const float *, f16 *, size_t, float, float, float, float, int,
+                               float, const int *, hipStream_t);
 
 }  // namespace lga

@@ -76,7 +76,8 @@ LayerLayout make_layout(size_t d, size_t f) {
 
 int validate_config(const lga_config *c) {
     if (!c) return fail(LGA_ERR_ARG, "config is NULL");
-    if (c->dtype != LGA_FP32 && c->dtype != LGA_BF16) return fail(LGA_ERR_ARG, "dtype must be LGA_FP32 or LGA_BF16");
+    if (c->dtype != LGA_FP32 && c->dtype != LGA_BF16 && c->dtype != LGA_FP16)
+        return fail(LGA_ERR_ARG, "dtype must be LGA_FP32, LGA_BF16 or LGA_FP16");
     if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->d_ff < 1 || c->seq_len < 1 || c->micro_batch < 1 ||
         c->n_micro < 1)
         return fail(LGA_ERR_SHAPE, "every size must be >= 1");
@@ -94,17 +95,17 @@ int validate_config(const lga_config *c) {
     if (!(c->ln_eps >= 0.f)) return fail(LGA_ERR_ARG, "ln_eps must be >= 0");
     if (c->dtype == LGA_FP32 && (2.0 * c->seq_len + 2.0 * c->d_model / c->n_heads) * 4 > 60000)
         return fail(LGA_ERR_SHAPE, "fp32 mode: seq_len too long for the one-wavefront attention kernel's LDS rows");
-    if (c->dtype == LGA_BF16) {
+    if (c->dtype != LGA_FP32) {
         const int dh = c->d_model / c->n_heads;
-        if (dh % 8 != 0) return fail(LGA_ERR_SHAPE, "bf16 mode needs head size d_h to be a multiple of 8");
+        if (dh % 8 != 0) return fail(LGA_ERR_SHAPE, "the 16-bit modes need head size d_h to be a multiple of 8");
         // head sizes without an MFMA attention kernel go through the one-wavefront kernels, like the fp32 mode
         if (!attn_bf16_supports(dh) && (2.0 * c->seq_len + 2.0 * dh) * 4 > 60000)
             return fail(LGA_ERR_SHAPE, "seq_len too long for the one-wavefront attention kernel's LDS rows (head size "
                                        "without an MFMA attention kernel)");
         if (c->d_model % 8 != 0 || c->d_ff % 8 != 0)
-            return fail(LGA_ERR_SHAPE, "bf16 mode needs d_model and d_ff to be multiples of 8");
+            return fail(LGA_ERR_SHAPE, "the 16-bit modes need d_model and d_ff to be multiples of 8");
         if (((long)c->group * c->micro_batch * c->seq_len) % 8 != 0)
-            return fail(LGA_ERR_SHAPE, "bf16 mode needs group * micro_batch * seq_len to be a multiple of 8");
+            return fail(LGA_ERR_SHAPE, "the 16-bit modes need group * micro_batch * seq_len to be a multiple of 8");
     }
     // kernels index rows and columns with int and elements with size_t
     const double tokens_group = (double)c->group * c->micro_batch * c->seq_len;
@@ -116,12 +117,13 @@ int validate_config(const lga_config *c) {
 // Arena plan: one allocation, every sub-buffer 256-byte aligned.
 struct Plan {
     size_t w, m, v, grad, w16, w16t, ckpt, dact;
-    size_t xT[4], dyT[4];      // transposed operands of the four weight-gradient GEMMs (bf16 mode)
+    size_t xT[4], dyT[4];      // transposed operands of the four weight-gradient GEMMs (16-bit modes)
     int wgrad_groups;          // groups whose tokens one weight-gradient GEMM contracts over
     size_t ldk;                // row pitch (elements) of the transposed operands
     size_t h, qkv, a, x1, h2, u, gl, du, dh2, dx1, da, dqkv, dh;
     size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
     size_t splitk, splitk_floats;   // partial results of weight-gradient GEMMs whose k range is split (narrow layers)
+    size_t nonfinite;          // int per layer: the last checked Adam step found a non-finite gradient value
     size_t total;
 };
 
@@ -129,7 +131,8 @@ Plan make_plan(const lga_config &c) {
     Plan p{};
     const size_t d = c.d_model, f = c.d_ff, L = c.n_layers;
     const size_t P = make_layout(d, f).total;
-    const size_t esz = c.dtype == LGA_BF16 ? 2 : 4;
+    const bool is16 = c.dtype != LGA_FP32;
+    const size_t esz = is16 ? 2 : 4;
     const size_t T = (size_t)c.n_micro * c.micro_batch * c.seq_len;
     const size_t t = (size_t)c.group * c.micro_batch * c.seq_len;
     size_t off = 0;
@@ -139,8 +142,8 @@ Plan make_plan(const lga_config &c) {
     p.v = take(L * P * 4);
     p.grad = take((c.retain_grads ? L : (c.overlap & LGA_OVERLAP_ADAM) ? std::min<size_t>(2, L) : 1) * P * 4);
     const size_t nbuf = c.param_buffers ? (size_t)c.param_buffers : L;     // layers whose 16-bit copies are resident
-    p.w16 = take(c.dtype == LGA_BF16 ? nbuf * P * 2 : 0);
-    p.w16t = take(c.dtype == LGA_BF16 ? nbuf * P * 2 : 0);   // each matrix transposed, at its canonical offset
+    p.w16 = take(is16 ? nbuf * P * 2 : 0);
+    p.w16t = take(is16 ? nbuf * P * 2 : 0);   // each matrix transposed, at its canonical offset
     p.ckpt = take((c.offload_checkpoints ? std::min<size_t>(2, L + 1) : L + 1) * T * d * esz);
     p.dact = take(T * d * esz);
     p.h = take(t * d * esz);
@@ -163,7 +166,7 @@ Plan make_plan(const lga_config &c) {
     const size_t groups = (size_t)c.n_micro / c.group;
     const size_t rows = 2 * f + 8 * d;                      // in + out over the four matrices
     size_t wb = c.wgrad_groups ? (size_t)c.wgrad_groups : 1;
-    if (c.dtype == LGA_BF16 && c.wgrad_groups == 0) {
+    if (is16 && c.wgrad_groups == 0) {
         // automatic: as many groups as keep these buffers within a quarter of everything else
         wb = groups;
         while (wb > 1 && rows * (wb * t + 64) * 2 > off / 4) --wb;
@@ -173,11 +176,11 @@ Plan make_plan(const lga_config &c) {
     const int wg_in[4] = {(int)f, (int)d, (int)d, (int)d};          // W_2, W_1, W_o, W_qkv
     const int wg_out[4] = {(int)d, (int)f, (int)d, (int)(3 * d)};
     for (int i = 0; i < 4; ++i) {
-        p.xT[i] = take(c.dtype == LGA_BF16 ? (size_t)wg_in[i] * p.ldk * 2 : 0);
-        p.dyT[i] = take(c.dtype == LGA_BF16 ? (size_t)wg_out[i] * p.ldk * 2 : 0);
+        p.xT[i] = take(is16 ? (size_t)wg_in[i] * p.ldk * 2 : 0);
+        p.dyT[i] = take(is16 ? (size_t)wg_out[i] * p.ldk * 2 : 0);
     }
     p.splitk_floats = 0;
-    if (c.dtype == LGA_BF16)
+    if (is16)
         for (int i = 0; i < 4; ++i) {
             const size_t slices = (size_t)gemm_splitk_slices(wg_in[i], wg_out[i], 0);
             if (slices > 1) p.splitk_floats = std::max(p.splitk_floats, slices * wg_in[i] * wg_out[i]);
@@ -192,6 +195,7 @@ Plan make_plan(const lga_config &c) {
     p.delta = take(stats * 4);
     const size_t widest = std::max<size_t>(3 * d, f);
     p.partial = take(colsum_partial_floats((int)t, (int)widest) * 4);
+    p.nonfinite = take(L * 4);          // one flag per layer, see lga_adam.skip_nonfinite
     p.total = off;
     return p;
 }
@@ -233,12 +237,15 @@ struct lga_stack {
     float *w(int l) const { return at<float>(plan.w) + (size_t)l * P; }
     float *m(int l) const { return at<float>(plan.m) + (size_t)l * P; }
     float *v(int l) const { return at<float>(plan.v) + (size_t)l * P; }
-    bf16 *w16(int l) const { return at<bf16>(plan.w16) + (size_t)(l % nbuf) * P; }
-    bf16 *w16t(int l) const { return at<bf16>(plan.w16t) + (size_t)(l % nbuf) * P; }
+    // 16-bit parameter copies, in the configured 16-bit format (E = bf16 or f16; uint16_t where only bits move)
+    template <class E = uint16_t> E *w16(int l) const { return at<E>(plan.w16) + (size_t)(l % nbuf) * P; }
+    template <class E = uint16_t> E *w16t(int l) const { return at<E>(plan.w16t) + (size_t)(l % nbuf) * P; }
+    bool is16() const { return cfg.dtype != LGA_FP32; }
+    int *nonfinite(int l) const { return at<int>(plan.nonfinite) + l; }
     bool w16_resident(int l) const { return w16_owner[l % nbuf] == l; }
     int grad_slot(int l) const { return l % ngrad; }
     float *grad(int l) const { return at<float>(plan.grad) + (size_t)grad_slot(l) * P; }
-    size_t esz() const { return cfg.dtype == LGA_BF16 ? 2 : 4; }
+    size_t esz() const { return is16() ? 2 : 4; }
     size_t boundary_bytes() const { return T * cfg.d_model * esz(); }
     // device address of a boundary activation (offload mode: of the slot it lives in while it is on the device)
     char *ckpt(int boundary) const {
@@ -251,13 +258,13 @@ namespace {
 
 template <class T> void gemm(const GemmParams<T> &p, bool akm, bool bkm, Epilogue e, hipStream_t s) {
     if constexpr (std::is_same<T, float>::value) launch_gemm_f32(p, akm, bkm, e, s);
-    else launch_gemm_bf16(p, akm, bkm, e, s);
+    else launch_gemm_mfma<T>(p, akm, bkm, e, s);
 }
 
-// The weights the GEMMs read: fp32 masters in fp32 mode, the 16-bit copy in bf16 mode.
+// The weights the GEMMs read: fp32 masters in fp32 mode, the 16-bit copy in the 16-bit modes.
 template <class T> const T *gemm_weights(const lga_stack *st, int l) {
     if constexpr (std::is_same<T, float>::value) return st->w(l);
-    else return st->w16(l);
+    else return st->w16<T>(l);
 }
 
 // Refresh layer l's transposed 16-bit matrices ([out][in]) from its 16-bit copy ([in][out]): the
@@ -265,12 +272,12 @@ template <class T> const T *gemm_weights(const lga_stack *st, int l) {
 void refresh_transposed_weights(lga_stack *st, int l, hipStream_t s) {
     const int d = st->cfg.d_model, f = st->cfg.d_ff;
     const LayerLayout &o = st->lay;
-    const bf16 *w = st->w16(l);
-    bf16 *wt = st->w16t(l);
-    launch_transpose_bf16(w + o.w_qkv, wt + o.w_qkv, d, 3 * d, 3 * d, d, s);
-    launch_transpose_bf16(w + o.w_o, wt + o.w_o, d, d, d, d, s);
-    launch_transpose_bf16(w + o.w_1, wt + o.w_1, d, f, f, d, s);
-    launch_transpose_bf16(w + o.w_2, wt + o.w_2, f, d, d, f, s);
+    const uint16_t *w = st->w16(l);
+    uint16_t *wt = st->w16t(l);
+    launch_transpose16(w + o.w_qkv, wt + o.w_qkv, d, 3 * d, 3 * d, d, s);
+    launch_transpose16(w + o.w_o, wt + o.w_o, d, d, d, d, s);
+    launch_transpose16(w + o.w_1, wt + o.w_1, d, f, f, d, s);
+    launch_transpose16(w + o.w_2, wt + o.w_2, f, d, d, f, s);
 }
 
 // ---- overlap mode plumbing -----------------------------------------------------------------------
@@ -354,7 +361,8 @@ void restore_weights(lga_stack *st, int l) {
         fork_aux(st);               // the buffer's previous layer is no longer read by anything enqueued after this
         s = st->aux;
     }
-    launch_cast_f32_to_bf16(st->w(l), st->w16(l), st->P, s);
+    if (st->cfg.dtype == LGA_FP16) launch_cast_f32_to_16<f16>(st->w(l), st->w16<f16>(l), st->P, s);
+    else launch_cast_f32_to_16<bf16>(st->w(l), st->w16<bf16>(l), st->P, s);
     st->w16_owner[slot] = l;
     refresh_transposed_weights(st, l, s);
     if (st->cfg.overlap) {
@@ -364,13 +372,13 @@ void restore_weights(lga_stack *st, int l) {
     ++st->restores;
 }
 void ensure_weights(lga_stack *st, int l) {
-    if (st->cfg.dtype != LGA_BF16) return;
+    if (!st->is16()) return;
     if (!st->w16_resident(l)) restore_weights(st, l);
     if (st->cfg.overlap) wait_w16(st, l % st->nbuf);
 }
 // Overlap mode: start restoring layer `next` while layer `cur`'s sweep, enqueued after this call, runs.
 void prefetch_weights(lga_stack *st, int next, int cur) {
-    if (st->cfg.dtype != LGA_BF16 || !st->cfg.overlap || next < 0 || next >= st->cfg.n_layers) return;
+    if (!st->is16() || !st->cfg.overlap || next < 0 || next >= st->cfg.n_layers) return;
     if (st->w16_resident(next) || next % st->nbuf == cur % st->nbuf) return;
     restore_weights(st, next);
 }
@@ -396,7 +404,7 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     // W^T[out, in], so both operands are k-contiguous.
     constexpr bool kBf16 = !std::is_same<T, float>::value;
     const T *pwt = pw;
-    if constexpr (kBf16) pwt = st->w16t(l);
+    if constexpr (kBf16) pwt = st->w16t<T>(l);
     auto fwd_gemm = [&](GemmParams<T> g, size_t w_off, int in, int out, Epilogue e) {
         g.M = t; g.N = out; g.K = in; g.lda = in; g.ldc = out;
         g.B = pwt + w_off;
@@ -410,7 +418,7 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     g.A = h; g.out = qkv; g.bias = pf + o.b_qkv;
     fwd_gemm(g, o.w_qkv, d, 3 * d, EPI_BIAS);
     if constexpr (std::is_same<T, float>::value) launch_attn_fwd_simple<float>(qkv, a, lse, ash, s);
-    else launch_attn_fwd_bf16(qkv, a, lse, ash, s);
+    else launch_attn_fwd_mfma<T>(qkv, a, lse, ash, s);
     g = GemmParams<T>{};
     g.A = a; g.out = x1; g.bias = pf + o.b_o; g.aux = x_in;
     fwd_gemm(g, o.w_o, d, d, EPI_BIAS_RESID);
@@ -475,9 +483,9 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
             gemm<T>(g, false, false, EPI_ACCUM_F32, s);
         } else {
             const int ldk = (int)st->plan.ldk;
-            bf16 *xT = st->at<bf16>(st->plan.xT[which]), *dyT = st->at<bf16>(st->plan.dyT[which]);
-            launch_transpose_bf16(X, xT + (size_t)gs.slot * t, t, in, in, ldk, s);
-            launch_transpose_bf16(dY, dyT + (size_t)gs.slot * t, t, out, out, ldk, s);
+            T *xT = st->at<T>(st->plan.xT[which]), *dyT = st->at<T>(st->plan.dyT[which]);
+            launch_transpose16(X, xT + (size_t)gs.slot * t, t, in, in, ldk, s);
+            launch_transpose16(dY, dyT + (size_t)gs.slot * t, t, out, out, ldk, s);
             if (gs.flush) {
                 g.K = (gs.slot + 1) * t; g.beta = gs.beta_mat;
                 g.A = xT; g.lda = ldk; g.B = dyT; g.ldb = ldk;
@@ -507,7 +515,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     wgrad(2, a, d, dx1, d, o.w_o, o.b_o);
     dgrad(dx1, d, o.w_o, d, da, EPI_STORE, nullptr);
     if constexpr (std::is_same<T, float>::value) launch_attn_bwd_simple<float>(qkv, a, lse, da, dqkv, delta, ash, s);
-    else launch_attn_bwd_bf16(qkv, a, lse, da, dqkv, delta, ash, s);
+    else launch_attn_bwd_mfma<T>(qkv, a, lse, da, dqkv, delta, ash, s);
     // qkv = h Wqkv + bqkv
     wgrad(3, h, d, dqkv, 3 * d, o.w_qkv, o.b_qkv);
     dgrad(dqkv, 3 * d, o.w_qkv, d, dh, EPI_STORE, nullptr);
@@ -524,10 +532,24 @@ void adam_layer(lga_stack *st, int l, const lga_adam &hp, bool async = false) {
         s = st->aux;
     }
     // the 16-bit copies are rewritten only if the layer still owns its buffer; otherwise the next use restores them
-    const bool copies = st->cfg.dtype == LGA_BF16 && st->w16_resident(l);
+    const bool copies = st->is16() && st->w16_resident(l);
     if (copies && !async && st->cfg.overlap) wait_w16(st, l % st->nbuf);
-    launch_adam(st->w(l), st->m(l), st->v(l), st->grad(l), copies ? st->w16(l) : nullptr, st->P,
-                hp.lr, hp.beta1, hp.beta2, hp.eps, hp.step, s);
+    // Gradient scaling (section 2.2): the caller multiplied the output gradient by loss_scale, so the accumulated
+    // gradient is divided by it here; with skip_nonfinite the gradient is tested first and an update whose gradient
+    // overflowed is left out as a whole (parameters, moments and 16-bit copies keep their values).
+    const float grad_mul = (hp.loss_scale > 0.f && hp.loss_scale != 1.f) ? 1.0f / hp.loss_scale : 1.0f;
+    int *flag = nullptr;
+    if (hp.skip_nonfinite) {
+        flag = st->nonfinite(l);
+        launch_fill_const(reinterpret_cast<float *>(flag), 1, 0.f, s);        // all bits zero
+        launch_nonfinite_flag(st->grad(l), st->P, flag, s);
+    }
+    if (st->cfg.dtype == LGA_FP16)
+        launch_adam<f16>(st->w(l), st->m(l), st->v(l), st->grad(l), copies ? st->w16<f16>(l) : nullptr, st->P, hp.lr,
+                         hp.beta1, hp.beta2, hp.eps, hp.step, grad_mul, flag, s);
+    else
+        launch_adam<bf16>(st->w(l), st->m(l), st->v(l), st->grad(l), copies ? st->w16<bf16>(l) : nullptr, st->P, hp.lr,
+                          hp.beta1, hp.beta2, hp.eps, hp.step, grad_mul, flag, s);
     if (copies) refresh_transposed_weights(st, l, s);
     if (async) {
         (void)hipEventRecord(st->ev_grad[st->grad_slot(l)], st->aux);
@@ -543,6 +565,8 @@ int check_adam(const lga_adam *a) {
     if (a->step < 1) return fail(LGA_ERR_STATE, "Adam step t must be >= 1");
     if (!(a->beta1 >= 0.f && a->beta1 < 1.f && a->beta2 >= 0.f && a->beta2 < 1.f))
         return fail(LGA_ERR_ARG, "Adam betas must lie in [0, 1)");
+    if (!(a->loss_scale >= 0.f) || std::isinf(a->loss_scale)) return fail(LGA_ERR_ARG, "loss_scale must be finite and >= 0");
+    if (a->skip_nonfinite != 0 && a->skip_nonfinite != 1) return fail(LGA_ERR_ARG, "skip_nonfinite must be 0 or 1");
     return LGA_OK;
 }
 
@@ -744,7 +768,7 @@ int lga_host_bytes(const lga_config *cfg, uint64_t *bytes) {
     if (!bytes) return fail(LGA_ERR_ARG, "NULL argument");
     if (int rc = validate_config(cfg)) return rc;
     const uint64_t boundary = (uint64_t)cfg->n_micro * cfg->micro_batch * cfg->seq_len * cfg->d_model *
-                              (cfg->dtype == LGA_BF16 ? 2 : 4);
+                              (cfg->dtype != LGA_FP32 ? 2 : 4);
     *bytes = cfg->offload_checkpoints ? (uint64_t)(cfg->n_layers + 1) * boundary : 0;
     return LGA_OK;
 }
@@ -757,18 +781,19 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
     const uint64_t P = lay.total, Pm = lay.matrices, df = (uint64_t)cfg->d_model * cfg->d_ff;
     const uint64_t L = cfg->n_layers;
     const uint64_t groups = order == LGA_ORDER_LAYERED ? cfg->n_micro / cfg->group : cfg->n_micro;
-    const uint64_t wsz = cfg->dtype == LGA_BF16 ? 2 : 4;
+    const bool is16 = cfg->dtype != LGA_FP32;
+    const uint64_t wsz = is16 ? 2 : 4;
     // Adam: read w, m, v (12 B), write w, m, v (12 B) and the 16-bit copy; per group the GEMM families
     // read the matrices: forward all four, recompute all but W_2, input gradient all four.
-    // bf16 mode also writes the 16-bit copy (2 B) and re-reads / writes the matrices once for the transposed copy
-    const uint64_t copies = cfg->dtype == LGA_BF16 ? 2 * P + 4 * Pm : 0;
+    // the 16-bit modes also write the 16-bit copy (2 B) and re-reads / writes the matrices once for the transposed copy
+    const uint64_t copies = is16 ? 2 * P + 4 * Pm : 0;
     const uint64_t per_group_param = wsz * (3 * Pm - df);
     // Restores of a steady-state step (param_buffers < n_layers): a layer's masters are cast again (read 4 B, write
     // 2 B per parameter, plus the transposed copy) whenever another layer has used its buffer since.  Counted by
     // walking the order's sequence of layer visits for two steps and keeping the second.
     const int nbuf = cfg->param_buffers ? cfg->param_buffers : cfg->n_layers;
     uint64_t restores = 0, adam_copies = L;
-    if (cfg->dtype == LGA_BF16 && nbuf < cfg->n_layers) {
+    if (is16 && nbuf < cfg->n_layers) {
         std::vector<int> owner(nbuf);
         for (int i = 0; i < nbuf; ++i) owner[i] = i;
         auto visit = [&](int l) {
@@ -791,7 +816,7 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
     // (4 B).  Vectors take one pass per group; matrices one per weight-gradient GEMM, which in the layered
     // bf16 path covers wgrad_groups groups.
     uint64_t mat_passes = groups;
-    if (order == LGA_ORDER_LAYERED && cfg->dtype == LGA_BF16) {
+    if (order == LGA_ORDER_LAYERED && is16) {
         const uint64_t wb = make_plan(*cfg).wgrad_groups;
         mat_passes = (groups + wb - 1) / wb;
     }
@@ -919,9 +944,15 @@ void lga_destroy_stack(lga_stack *st) {
     release_stack(st);
 }
 
+// fn<T>(args) with T = the stack's activation type
+#define LGA_DISPATCH(st, fn, ...)                                   \
+    ((st)->cfg.dtype == LGA_BF16   ? fn<bf16>(__VA_ARGS__)          \
+     : (st)->cfg.dtype == LGA_FP16 ? fn<f16>(__VA_ARGS__)           \
+                                   : fn<float>(__VA_ARGS__))
+
 int lga_forward_layered(lga_stack *st, const void *x, void *y) {
     if (!st || !x) return fail(LGA_ERR_ARG, "NULL argument");
-    int rc = st->cfg.dtype == LGA_BF16 ? forward_layered_t<bf16>(st, x, y) : forward_layered_t<float>(st, x, y);
+    int rc = LGA_DISPATCH(st, forward_layered_t, st, x, y);
     if (rc == LGA_OK) st->set_forward(true);
     return rc;
 }
@@ -933,15 +964,13 @@ int lga_backward_layered(lga_stack *st, const void *dy, void *dx, const lga_adam
         return fail(LGA_ERR_STATE, "unfused backward with a single gradient buffer would lose all but one layer's gradient");
     if (fused)
         if (int rc = check_adam(fused)) return rc;
-    return st->cfg.dtype == LGA_BF16 ? backward_layered_t<bf16>(st, dy, dx, fused)
-                                     : backward_layered_t<float>(st, dy, dx, fused);
+    return LGA_DISPATCH(st, backward_layered_t, st, dy, dx, fused);
 }
 
 int lga_forward_layer(lga_stack *st, int32_t layer, const void *x_in, void *x_out) {
     if (int rc = check_layer(st, layer)) return rc;
     if (!x_in) return fail(LGA_ERR_ARG, "x_in is NULL");
-    int rc = st->cfg.dtype == LGA_BF16 ? forward_layer_t<bf16>(st, layer, x_in, x_out)
-                                       : forward_layer_t<float>(st, layer, x_in, x_out);
+    int rc = LGA_DISPATCH(st, forward_layer_t, st, layer, x_in, x_out);
     if (rc == LGA_OK) {
         st->input_valid[layer] = 1;
         // the next boundary now holds this layer's output (or nothing new): not an input the next layer has seen
@@ -957,8 +986,7 @@ int lga_backward_layer(lga_stack *st, int32_t layer, const void *dy, void *dx, c
         return fail(LGA_ERR_STATE, "lga_backward_layer needs a preceding forward of this layer with its current weights");
     if (fused)
         if (int rc = check_adam(fused)) return rc;
-    return st->cfg.dtype == LGA_BF16 ? backward_layer_t<bf16>(st, layer, dy, dx, fused)
-                                     : backward_layer_t<float>(st, layer, dy, dx, fused);
+    return LGA_DISPATCH(st, backward_layer_t, st, layer, dy, dx, fused);
 }
 
 int lga_step_mbmajor(lga_stack *st, const void *x, const void *dy, void *y, void *dx, const lga_adam *adam) {
@@ -970,8 +998,7 @@ int lga_step_mbmajor(lga_stack *st, const void *x, const void *dy, void *y, void
                                    "offload_checkpoints");
     if (adam)
         if (int rc = check_adam(adam)) return rc;
-    return st->cfg.dtype == LGA_BF16 ? step_mbmajor_t<bf16>(st, x, dy, y, dx, adam)
-                                     : step_mbmajor_t<float>(st, x, dy, y, dx, adam);
+    return LGA_DISPATCH(st, step_mbmajor_t, st, x, dy, y, dx, adam);
 }
 
 int lga_adam_step_layer(lga_stack *st, int32_t layer, const lga_adam *adam) {
@@ -1016,6 +1043,47 @@ int lga_checkpoint(lga_stack *st, int32_t boundary, const void **dev_ptr, size_t
     if (boundary < 0 || boundary > st->cfg.n_layers) return fail(LGA_ERR_ARG, "boundary index out of range");
     *dev_ptr = st->cfg.offload_checkpoints ? st->host_boundary(boundary) : st->ckpt(boundary);
     if (bytes) *bytes = st->boundary_bytes();
+    return LGA_OK;
+}
+
+int lga_nonfinite_layers(lga_stack *st, int32_t *flags, int32_t *count) {
+    if (!st || !count) return fail(LGA_ERR_ARG, "NULL argument");
+    join_aux(st);                       // Adam steps of the overlap mode run on the second stream
+    std::vector<int> host(st->cfg.n_layers);
+    LGA_HIP(hipMemcpyAsync(host.data(), st->nonfinite(0), host.size() * sizeof(int), hipMemcpyDeviceToHost, st->stream));
+    LGA_HIP(hipStreamSynchronize(st->stream));
+    int32_t n = 0;
+    for (int l = 0; l < st->cfg.n_layers; ++l) {
+        n += host[l] != 0;
+        if (flags) flags[l] = host[l] != 0;
+    }
+    *count = n;
+    return LGA_OK;
+}
+
+int lga_grads_nonfinite(lga_stack *st, int32_t *flags, int32_t *count) {
+    if (!st || !count) return fail(LGA_ERR_ARG, "NULL argument");
+    join_aux(st);
+    for (int l = 0; l < st->cfg.n_layers; ++l) {
+        launch_fill_const(reinterpret_cast<float *>(st->nonfinite(l)), 1, 0.f, st->stream);
+        if (st->grad_owner[st->grad_slot(l)] == l) launch_nonfinite_flag(st->grad(l), st->P, st->nonfinite(l), st->stream);
+    }
+    return lga_nonfinite_layers(st, flags, count);
+}
+
+int lga_loss_scaler_update(lga_loss_scaler *sc, int32_t overflowed) {
+    if (!sc) return fail(LGA_ERR_ARG, "scaler is NULL");
+    if (!(sc->scale > 0.f) || !(sc->growth >= 1.f) || !(sc->backoff > 0.f && sc->backoff <= 1.f) || sc->growth_interval < 1 ||
+        !(sc->min_scale > 0.f) || !(sc->max_scale >= sc->min_scale) || sc->good_steps < 0)
+        return fail(LGA_ERR_ARG, "loss scaler: need scale > 0, growth >= 1, 0 < backoff <= 1, growth_interval >= 1, "
+                                 "0 < min_scale <= max_scale, good_steps >= 0");
+    if (overflowed) {
+        sc->scale = std::max(sc->scale * sc->backoff, sc->min_scale);
+        sc->good_steps = 0;
+    } else if (++sc->good_steps >= sc->growth_interval) {
+        sc->scale = std::min(sc->scale * sc->growth, sc->max_scale);
+        sc->good_steps = 0;
+    }
     return LGA_OK;
 }
 

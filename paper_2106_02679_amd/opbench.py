@@ -67,7 +67,7 @@ def run_gemm(args):
 
         def call():
             if epi == 5:      # the weight-gradient GEMM as the stack runs it (k range split when the output is small)
-                B.check(B.lib.lga_op_gemm_splitk(M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, outf.data_ptr(), N, 0.0,
+                B.check(B.lib.lga_op_gemm_splitk(B.LGA_BF16, M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, outf.data_ptr(), N, 0.0,
                                                  ptr(scratch), slices * M * N, None))
             else:
                 B.check(B.lib.lga_op_gemm(B.LGA_BF16, 1, 1, epi, M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, ptr(out),

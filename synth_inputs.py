@@ -41,7 +41,7 @@ class Workload:
     seq_len: int
     micro_batch: int
     n_micro: int
-    dtype: str            # "fp32" or "bf16": activation / GEMM-input type on the GPU
+    dtype: str            # "fp32", "bf16" or "fp16": activation / GEMM-input type on the GPU
 
     @property
     def tokens(self) -> int:
@@ -116,16 +116,30 @@ def from_bf16_bits(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32).reshape(b.shape)
 
 
+def round_to_fp16(a: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest IEEE half (ties to even); result stays float32."""
+    return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def from_16bit_bits(b: np.ndarray, dtype: str) -> np.ndarray:
+    """uint16 bit patterns of a 16-bit workload's tensor -> float32."""
+    if dtype == "fp16":
+        return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+    return from_bf16_bits(b)
+
+
 def make_inputs(w: Workload, seed: int = 0, weight_std: float = 0.02, bias_std: float = 0.0):
     """Return (x, G, params): x and G float32 [n, b, s, d]; params a list of flat float32
-    vectors, one per layer, in canonical order.  In bf16 workloads x and G hold
-    bf16-representable values (so storing them as bf16 on the GPU loses nothing)."""
+    vectors, one per layer, in canonical order.  In 16-bit workloads x and G hold values
+    representable in the workload's format (so storing them in it on the GPU loses nothing)."""
     rng = np.random.Generator(np.random.PCG64(seed))
     shp = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     x = rng.standard_normal(shp).astype(np.float32)
     G = rng.standard_normal(shp).astype(np.float32)
     if w.dtype == "bf16":
         x, G = round_to_bf16(x), round_to_bf16(G)
+    elif w.dtype == "fp16":
+        x, G = round_to_fp16(x), round_to_fp16(G)
     shapes = tensor_shapes(w.d_model, w.d_ff)
     sl = tensor_slices(w.d_model, w.d_ff)
     params: List[np.ndarray] = []

@@ -10,13 +10,18 @@ from oracle import lga_oracle as O
 from paper_2106_02679_amd import binding as B
 
 
+TORCH_DTYPE = {B.LGA_FP32: torch.float32, B.LGA_BF16: torch.bfloat16, B.LGA_FP16: torch.float16}
+DTYPE_CODE = {"fp32": B.LGA_FP32, "bf16": B.LGA_BF16, "fp16": B.LGA_FP16}
+DTYPE_NAME = {v: k for k, v in DTYPE_CODE.items()}
+
+
 def to_dev(a: np.ndarray, dtype: int) -> torch.Tensor:
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-    return t.to(torch.bfloat16) if dtype == B.LGA_BF16 else t
+    return t.to(TORCH_DTYPE[dtype])
 
 
 def empty_dev(shape, dtype: int) -> torch.Tensor:
-    return torch.empty(shape, device="cuda", dtype=torch.bfloat16 if dtype == B.LGA_BF16 else torch.float32)
+    return torch.empty(shape, device="cuda", dtype=TORCH_DTYPE[dtype])
 
 
 def to_host(t: torch.Tensor) -> np.ndarray:
@@ -42,7 +47,7 @@ def updatable_mask(w: S.Workload) -> np.ndarray:
 
 
 def dtype_code(w: S.Workload) -> int:
-    return B.LGA_BF16 if w.dtype == "bf16" else B.LGA_FP32
+    return DTYPE_CODE[w.dtype]
 
 
 def oracle_shape(w: S.Workload, causal: bool = True) -> O.StackShape:
@@ -50,14 +55,57 @@ def oracle_shape(w: S.Workload, causal: bool = True) -> O.StackShape:
                         b_mu=w.micro_batch, n_mu=w.n_micro, causal=causal)
 
 
-def adam_struct(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=1) -> B.lga_adam:
-    return B.lga_adam(lr, beta1, beta2, eps, step)
+def adam_struct(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, step=1, loss_scale=0.0, skip_nonfinite=0) -> B.lga_adam:
+    return B.lga_adam(lr, beta1, beta2, eps, step, loss_scale, skip_nonfinite)
+
+
+def adam_at_step(a: B.lga_adam, step: int) -> B.lga_adam:
+    return B.lga_adam(a.lr, a.beta1, a.beta2, a.eps, step, a.loss_scale, a.skip_nonfinite)
 
 
 def oracle_adam(a: B.lga_adam) -> O.AdamHyper:
     """The oracle gets the hyper-parameters as they cross the ABI: rounded to float32."""
     return O.AdamHyper(lr=float(np.float32(a.lr)), beta1=float(np.float32(a.beta1)), beta2=float(np.float32(a.beta2)),
-                       eps=float(np.float32(a.eps)), step=int(a.step))
+                       eps=float(np.float32(a.eps)), step=int(a.step),
+                       loss_scale=float(np.float32(a.loss_scale)) or 1.0, skip_nonfinite=bool(a.skip_nonfinite))
+
+
+def compare_with_oracle(w, got, ref, gate, adam, zero_init=True):
+    sl = S.tensor_slices(w.d_model, w.d_ff)
+    d = w.d_model
+    k_bias = slice(sl["b_qkv"].start + d, sl["b_qkv"].start + 2 * d)
+    keep = np.ones(w.params_per_layer, dtype=bool)
+    keep[k_bias] = False
+    worst = {}
+    for bnd in range(w.n_layers + 1):
+        worst[f"act{bnd}"] = rel_err(got["boundaries"][bnd], ref.boundaries[bnd])
+    worst["y"] = rel_err(got["y"], ref.boundaries[-1])
+    worst["dx"] = rel_err(got["dx"], ref.dx)
+    for l in range(w.n_layers):
+        if got["grads"][l] is None:
+            continue
+        for name in S.PARAM_ORDER:
+            worst[f"g{l}.{name}"] = rel_err(got["grads"][l][sl[name]], ref.grads[l][sl[name]])
+        q_bias = slice(sl["b_qkv"].start, sl["b_qkv"].start + d)
+        if w.dtype == "fp32":
+            assert np.linalg.norm(got["grads"][l][k_bias]) <= 1e-4 * np.linalg.norm(got["grads"][l][q_bias])
+        assert np.linalg.norm(ref.grads[l][k_bias]) <= 1e-12 * np.linalg.norm(ref.grads[l][q_bias])
+    if adam is not None:
+        for l in range(w.n_layers):
+            worst[f"w{l}"] = rel_err(got["params"][l][keep], ref.new_params[l][keep])
+            worst[f"m{l}"] = rel_err(got["m"][l], ref.new_m[l])
+            # v is quadratic in the gradient, so a relative gradient error e shows up as 2e: gate at twice the gate
+            worst[f"v{l}(halved)"] = 0.5 * rel_err(got["v"][l], ref.new_v[l])
+            for name in S.PARAM_ORDER:
+                if zero_init and name not in S.MATRICES and name not in S.GAINS:
+                    continue
+                sel = np.zeros(w.params_per_layer, dtype=bool)
+                sel[sl[name]] = True
+                sel &= keep
+                worst[f"w{l}.{name}"] = rel_err(got["params"][l][sel], ref.new_params[l][sel])
+    bad = {k: v for k, v in worst.items() if not v < gate}
+    assert not bad, f"over the {gate} gate: {bad}; worst overall {max(worst.values()):.3e}"
+    return worst
 
 
 def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layered", adam=None, fused=True,
@@ -77,10 +125,9 @@ def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layer
     try:
         for extra in range(steps - 1):                    # earlier steps of a multi-step run (fused Adam, layered order)
             st.forward_layered(xd.data_ptr(), yd.data_ptr())
-            st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), B.lga_adam(adam.lr, adam.beta1, adam.beta2, adam.eps,
-                                                                          adam.step + extra))
+            st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam_at_step(adam, adam.step + extra))
         if steps > 1:
-            adam = B.lga_adam(adam.lr, adam.beta1, adam.beta2, adam.eps, adam.step + steps - 1)
+            adam = adam_at_step(adam, adam.step + steps - 1)
         if order == "layered":
             st.forward_layered(xd.data_ptr(), yd.data_ptr())
             st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), adam if (adam is not None and fused) else None)
@@ -104,9 +151,9 @@ def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layer
             ck = []
             for bnd in range(w.n_layers + 1):
                 ptr, nbytes = st.checkpoint(bnd)
-                if dt == B.LGA_BF16:
+                if dt != B.LGA_FP32:
                     bits = B.read_device(ptr, n_act, "uint16")
-                    ck.append(S.from_bf16_bits(bits).astype(np.float64).reshape(x.shape))
+                    ck.append(S.from_16bit_bits(bits, w.dtype).astype(np.float64).reshape(x.shape))
                 else:
                     ck.append(B.read_device(ptr, n_act, "float32").astype(np.float64).reshape(x.shape))
             out["boundaries"] = np.stack(ck)
@@ -119,6 +166,8 @@ def run_gpu_step(w: S.Workload, x, G, params, *, group=1, retain=0, order="layer
             out["v"].append(B.read_device(vp, n).astype(np.float64))
         assert n == P
         out["restores"] = st.restore_count()
+        if adam is not None and adam.skip_nonfinite:
+            out["skipped"] = st.nonfinite_layers()
     finally:
         st.close()
     return out

@@ -188,6 +188,38 @@ def test_checkpoint_offload_moves_the_boundaries_to_pinned_host_memory():
     assert B.lib.lga_host_bytes(C.byref(cfg(**kw)), None) == B.LGA_ERR_ARG
 
 
+def test_loss_scaler_matches_the_oracle_on_a_random_overflow_pattern():
+    import numpy as np
+    from oracle import lga_oracle as O
+    rng = np.random.default_rng(7)
+    c = B.lga_loss_scaler(65536.0, 2.0, 0.5, 1.0, 2.0 ** 24, 5, 0)
+    o = O.LossScaler(scale=65536.0, growth=2.0, backoff=0.5, min_scale=1.0, max_scale=2.0 ** 24, growth_interval=5)
+    for i in range(400):
+        ov = bool(rng.random() < (0.5 if 100 <= i < 160 else 0.05))
+        B.check(B.lib.lga_loss_scaler_update(C.byref(c), int(ov)))
+        O.loss_scaler_update(o, ov)
+        assert c.scale == o.scale and c.good_steps == o.good_steps, i
+    assert 1.0 <= c.scale <= 2.0 ** 24
+    for bad in (dict(scale=0.0), dict(growth=0.5), dict(backoff=0.0), dict(backoff=1.5), dict(growth_interval=0),
+                dict(min_scale=0.0), dict(max_scale=0.5)):
+        kw = dict(scale=8.0, growth=2.0, backoff=0.5, min_scale=1.0, max_scale=1024.0, growth_interval=2, good_steps=0)
+        kw.update(bad)
+        sc = B.lga_loss_scaler(**kw)
+        assert B.lib.lga_loss_scaler_update(C.byref(sc), 0) == B.LGA_ERR_ARG, bad
+    assert B.lib.lga_loss_scaler_update(None, 0) == B.LGA_ERR_ARG
+
+
+def test_half_precision_mode_is_sized_like_bf16_and_follows_the_same_shape_rules():
+    a = B.arena_bytes(cfg(dtype=B.LGA_BF16, seq_len=64))
+    b = B.arena_bytes(cfg(dtype=B.LGA_FP16, seq_len=64))
+    assert a == b
+    assert B.traffic_model(cfg(dtype=B.LGA_FP16, seq_len=64), B.LGA_ORDER_LAYERED) == \
+        B.traffic_model(cfg(dtype=B.LGA_BF16, seq_len=64), B.LGA_ORDER_LAYERED)
+    out = C.c_uint64()
+    assert B.lib.lga_arena_bytes(C.byref(cfg(dtype=B.LGA_FP16, d_model=60, n_heads=4)), C.byref(out)) == B.LGA_ERR_SHAPE
+    assert B.lib.lga_arena_bytes(C.byref(cfg(dtype=3)), C.byref(out)) == B.LGA_ERR_ARG
+
+
 def test_init_without_a_gpu_reports_a_hip_error_instead_of_crashing():
     import torch
     if torch.cuda.is_available():

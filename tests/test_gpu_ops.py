@@ -7,6 +7,8 @@ Tolerances (relative Frobenius norm of the error):
   error is the rounding of the stored result, unit roundoff 2^-8 => about 2^-9/sqrt(3)*sqrt(2) ~ 1.6e-3
   rms per element; 4e-3 leaves a factor 2.5.  Attention rounds P (and dS) to bf16 before its second
   product, adding a similar term per product: 1e-2 forward, 2e-2 backward (the build's bf16 gate).
+  fp16 storage (IEEE half): the same kernels with unit roundoff 2^-11, an eighth of bf16's: every 16-bit
+  tolerance divided by 8 (5e-4; attention 1.25e-3 forward, 2.5e-3 backward).
 """
 import math
 
@@ -21,13 +23,20 @@ import synth_inputs as S
 from paper_2106_02679_amd import binding as B
 from gpu_helpers import to_dev, empty_dev, to_host, rel_err
 
-F32, BF16 = B.LGA_FP32, B.LGA_BF16
-TOL_OUT = {F32: 1e-5, BF16: 4e-3}
+F32, BF16, F16 = B.LGA_FP32, B.LGA_BF16, B.LGA_FP16
+TOL_OUT = {F32: 1e-5, BF16: 4e-3, F16: 5e-4}
+TOL_ATTN = {F32: (1e-5, 2e-5), BF16: (1e-2, 2e-2), F16: (1.25e-3, 2.5e-3)}
+ROUND = {F32: lambda a: a, BF16: S.round_to_bf16, F16: S.round_to_fp16}
 
 
 def rnd(rng, shape, dt, scale=1.0):
     a = (scale * rng.standard_normal(shape)).astype(np.float32)
-    return S.round_to_bf16(a) if dt == BF16 else a
+    return ROUND[dt](a)
+
+
+def with_half(cases):
+    """The 16-bit cases of a list once more in IEEE half."""
+    return cases + [(F16,) + c[1:] for c in cases if c[0] == BF16]
 
 
 def fvec(a):
@@ -73,7 +82,7 @@ GEMM_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", GEMM_CASES, ids=lambda c: "-".join(map(str, c)))
+@pytest.mark.parametrize("case", with_half(GEMM_CASES), ids=lambda c: "-".join(map(str, c)))
 def test_gemm_against_oracle_matmul(case):
     dt, akm, bkm, epi, M, N, K = case
     rng = np.random.default_rng(hash(case) % (2 ** 32))
@@ -125,27 +134,29 @@ def test_gemm_against_oracle_matmul(case):
         assert np.all(to_host(out)[:, N:] == 0)                                # padding untouched
 
 
-@pytest.mark.parametrize("M,N,K,beta", [(768, 768, 8192, 1.0), (320, 264, 5000, 0.0), (1032, 520, 40000, 1.0),
-                                        (256, 256, 1024 * 32 + 8, 0.0), (768, 2304, 1000, 1.0)])
-def test_weight_gradient_gemm_with_split_k_range(M, N, K, beta):
+@pytest.mark.parametrize("dt,M,N,K,beta", [(BF16, 768, 768, 8192, 1.0), (BF16, 320, 264, 5000, 0.0),
+                                           (BF16, 1032, 520, 40000, 1.0), (BF16, 256, 256, 1024 * 32 + 8, 0.0),
+                                           (BF16, 768, 2304, 1000, 1.0), (F16, 768, 768, 8192, 1.0),
+                                           (F16, 320, 264, 5000, 0.0)])
+def test_weight_gradient_gemm_with_split_k_range(dt, M, N, K, beta):
     """Narrow outputs with a long contraction (the weight-gradient GEMMs of narrow layers): the k range is cut into
     slices that run as separate workgroups.  Against the fp64 product, against the unsplit kernel, twice (the
     scratch keeps the previous call's partial results), and bit-reproducibly; the last case is too short to split."""
     rng = np.random.default_rng(M + N + K)
     lda, ldb, ldc = K + 8, K + 16, N + 8
-    A, Bm = rnd(rng, (M, lda), BF16), rnd(rng, (N, ldb), BF16)
+    A, Bm = rnd(rng, (M, lda), dt), rnd(rng, (N, ldb), dt)
     acc = A[:, :K].astype(np.float64) @ Bm[:, :K].astype(np.float64).T
     old = rng.standard_normal((M, ldc)).astype(np.float32)
     slices = B.lib.lga_op_gemm_splitk_slices(M, N, K)
     assert (slices > 1) == (K >= 2048)
     assert slices <= B.lib.lga_op_gemm_splitk_slices(M, N, 0)
-    Ad, Bd = to_dev(A, BF16), to_dev(Bm, BF16)
+    Ad, Bd = to_dev(A, dt), to_dev(Bm, dt)
     scratch = torch.full((slices * M * N,), float("nan"), device="cuda")
     ref = beta * old[:, :N].astype(np.float64) + acc
     results = []
     for attempt in range(2):
         outf = fvec(old)
-        B.check(B.lib.lga_op_gemm_splitk(M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta,
+        B.check(B.lib.lga_op_gemm_splitk(dt, M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta,
                                          scratch.data_ptr(), scratch.numel(), None))
         torch.cuda.synchronize()
         got = outf.cpu().numpy()
@@ -154,7 +165,7 @@ def test_weight_gradient_gemm_with_split_k_range(M, N, K, beta):
         results.append(got)
     assert np.array_equal(results[0], results[1])
     outf = fvec(old)
-    B.check(B.lib.lga_op_gemm_splitk(M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta, None, 0,
+    B.check(B.lib.lga_op_gemm_splitk(dt, M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta, None, 0,
                                      None))                                    # no scratch: the unsplit kernel
     torch.cuda.synchronize()
     assert rel_err(outf.cpu().numpy()[:, :N], results[0][:, :N]) < 1e-5
@@ -162,7 +173,7 @@ def test_weight_gradient_gemm_with_split_k_range(M, N, K, beta):
     if slices > 1:
         small = torch.zeros(M * N, device="cuda")
         outf = fvec(old)
-        B.check(B.lib.lga_op_gemm_splitk(M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta,
+        B.check(B.lib.lga_op_gemm_splitk(dt, M, N, K, Ad.data_ptr(), lda, Bd.data_ptr(), ldb, outf.data_ptr(), ldc, beta,
                                          small.data_ptr(), small.numel(), None))
         torch.cuda.synchronize()
         assert rel_err(outf.cpu().numpy()[:, :N], ref) < 1e-5
@@ -205,12 +216,12 @@ def test_gemm_empty_and_rejected_arguments():
     # more rows than blocks (a block walks over several rows, requesting the next one early), every block size,
     # a ragged second pack, a row too wide for the row-walking kernels, the vector path of the fp32 mode
     (BF16, 5000, 3072), (BF16, 3000, 8192), (BF16, 700, 10000), (BF16, 40, 25600), (F32, 2500, 4096), (BF16, 2100, 768),
+    (F16, 130, 256), (F16, 33, 1000), (F16, 5000, 3072), (F16, 40, 25600),
 ])
 def test_layernorm_forward_and_backward(dt, rows, d):
     rng = np.random.default_rng(rows * 1000 + d)
     x = rnd(rng, (rows, d), dt, 2.0) + (0.5 if dt == F32 else 0.0)
-    if dt == BF16:
-        x = S.round_to_bf16(x)
+    x = ROUND[dt](x)
     g = (1 + 0.3 * rng.standard_normal(d)).astype(np.float32)
     b = (0.2 * rng.standard_normal(d)).astype(np.float32)
     dy = rnd(rng, (rows, d), dt)
@@ -241,7 +252,8 @@ def test_layernorm_forward_and_backward(dt, rows, d):
     assert rel_err(dbd.cpu().numpy(), old_b + db_ref) < 2e-5
 
 
-@pytest.mark.parametrize("dt,rows,cols,ld", [(F32, 300, 45, 50), (BF16, 1000, 264, 272), (BF16, 129, 8, 8), (F32, 0, 16, 16)])
+@pytest.mark.parametrize("dt,rows,cols,ld", [(F32, 300, 45, 50), (BF16, 1000, 264, 272), (BF16, 129, 8, 8), (F32, 0, 16, 16),
+                                             (F16, 1000, 264, 272)])
 def test_column_sums(dt, rows, cols, ld):
     rng = np.random.default_rng(rows + cols)
     a = rnd(rng, (max(rows, 1), ld), dt)[:rows]
@@ -298,7 +310,7 @@ FULL_CASES = [
 ]
 
 
-@pytest.mark.parametrize("case", [c + (True,) for c in ATTN_CASES] + [c + (False,) for c in FULL_CASES],
+@pytest.mark.parametrize("case", [c + (True,) for c in with_half(ATTN_CASES)] + [c + (False,) for c in with_half(FULL_CASES)],
                          ids=lambda c: "-".join(map(str, c[:-1])) + ("-causal" if c[-1] else "-full"))
 def test_attention_forward_and_backward(case):
     dt, kind, n_seq, s, heads, dh, causal = case
@@ -316,7 +328,7 @@ def test_attention_forward_and_backward(case):
     B.check(B.lib.lga_op_attention_bwd(dt, kind, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
                                        dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), None))
     torch.cuda.synchronize()
-    tol_f, tol_b = (1e-5, 2e-5) if dt == F32 else (1e-2, 2e-2)
+    tol_f, tol_b = TOL_ATTN[dt]
     assert rel_err(to_host(out), out_ref) < tol_f
     assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < (1e-5 if dt == F32 else 1e-3) * max(1.0, np.abs(lse_ref).max())
     got = to_host(dqkv)
@@ -372,7 +384,7 @@ def test_attention_mfma_rejects_unsupported_head_size():
     assert rc == B.LGA_ERR_SHAPE
 
 
-@pytest.mark.parametrize("n,with16", [(1003, True), (4096, True), (7, False), (0, False)])
+@pytest.mark.parametrize("n,with16", [(1003, BF16), (4096, BF16), (7, None), (0, None), (1003, F16), (4100, F16)])
 def test_adam_kernel_against_closed_form(n, with16):
     rng = np.random.default_rng(n)
     w = rng.standard_normal(n).astype(np.float32)
@@ -385,10 +397,10 @@ def test_adam_kernel_against_closed_form(n, with16):
     w_ref, m_ref, v_ref = O.adam_update(w.astype(np.float64), m.astype(np.float64), v.astype(np.float64),
                                         g.astype(np.float64), ohp)
     wd, md, vd, gd = fvec(w), fvec(m), fvec(v), fvec(g)
-    w16 = torch.zeros(max(n, 1), device="cuda", dtype=torch.bfloat16)
+    w16 = empty_dev((max(n, 1),), with16 or BF16).zero_()
     import ctypes
     B.check(B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(),
-                              w16.data_ptr() if with16 else None, n, ctypes.byref(hp), None))
+                              w16.data_ptr() if with16 else None, with16 or 0, n, ctypes.byref(hp), None, None))
     torch.cuda.synchronize()
     if n == 0:
         return
@@ -396,7 +408,7 @@ def test_adam_kernel_against_closed_form(n, with16):
     assert rel_err(md.cpu().numpy(), m_ref) < 1e-6
     assert rel_err(vd.cpu().numpy(), v_ref) < 1e-6
     if with16:
-        assert np.array_equal(to_host(w16)[:n], S.round_to_bf16(wd.cpu().numpy()).astype(np.float64))
+        assert np.array_equal(to_host(w16)[:n], ROUND[with16](wd.cpu().numpy()).astype(np.float64))
 
 
 def test_adam_kernel_hand_worked_values():
@@ -404,7 +416,47 @@ def test_adam_kernel_hand_worked_values():
     import ctypes
     wd, md, vd, gd = fvec([0.5]), fvec([0.1]), fvec([0.04]), fvec([-0.2])
     hp = B.lga_adam(0.01, 0.9, 0.99, 1e-8, 2)
-    B.check(B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(), None, 1, ctypes.byref(hp), None))
+    B.check(B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(), None, 0, 1, ctypes.byref(hp), None,
+                              None))
     torch.cuda.synchronize()
     assert abs(float(wd[0]) - 0.4974013907589168) < 2e-7
     assert abs(float(md[0]) - 0.07) < 1e-7 and abs(float(vd[0]) - 0.04) < 1e-7
+
+
+@pytest.mark.parametrize("n,bad_at,bad", [(5000, 4999, float("inf")), (5000, 0, float("nan")), (4099, 4098, float("-inf")),
+                                          (3, 1, float("nan")), (5000, None, 0.0)])
+def test_adam_kernel_with_loss_scale_and_non_finite_test(n, bad_at, bad):
+    """Gradient scaling (section 2.2): the gradient is divided by the loss scale; with skip_nonfinite one infinity or
+    NaN anywhere in it (first element, last element of the vector part, scalar tail) leaves the whole update out."""
+    import ctypes
+    rng = np.random.default_rng(n)
+    w = rng.standard_normal(n).astype(np.float32)
+    m = (0.1 * rng.standard_normal(n)).astype(np.float32)
+    v = (0.01 * rng.random(n)).astype(np.float32)
+    scale = 512.0
+    g = (scale * rng.standard_normal(n)).astype(np.float32)
+    if bad_at is not None:
+        g[bad_at] = bad
+    hp = B.lga_adam(3e-3, 0.9, 0.999, 1e-8, 7, scale, 1)
+    ohp = O.AdamHyper(lr=float(np.float32(3e-3)), beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)),
+                      eps=float(np.float32(1e-8)), step=7, loss_scale=scale, skip_nonfinite=True)
+    w_ref, m_ref, v_ref = O.adam_update(w.astype(np.float64), m.astype(np.float64), v.astype(np.float64),
+                                        g.astype(np.float64), ohp)
+    wd, md, vd, gd = fvec(w), fvec(m), fvec(v), fvec(g)
+    w16 = empty_dev((n,), F16).fill_(3.0)
+    flag = torch.full((1,), 77, device="cuda", dtype=torch.int32)
+    assert B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(), w16.data_ptr(), F16, n,
+                             ctypes.byref(hp), None, None) == B.LGA_ERR_ARG         # the flag is required
+    B.check(B.lib.lga_op_adam(wd.data_ptr(), md.data_ptr(), vd.data_ptr(), gd.data_ptr(), w16.data_ptr(), F16, n,
+                              ctypes.byref(hp), flag.data_ptr(), None))
+    torch.cuda.synchronize()
+    assert int(flag[0]) == (1 if bad_at is not None else 0)
+    if bad_at is not None:
+        assert O.adam_skips(g, ohp)
+        assert np.array_equal(wd.cpu().numpy(), w) and np.array_equal(md.cpu().numpy(), m) and np.array_equal(vd.cpu().numpy(), v)
+        assert np.all(to_host(w16) == 3.0)
+    else:
+        assert rel_err(wd.cpu().numpy(), w_ref) < 1e-6
+        assert rel_err(md.cpu().numpy(), m_ref) < 1e-6
+        assert rel_err(vd.cpu().numpy(), v_ref) < 1e-6
+        assert np.array_equal(to_host(w16), S.round_to_fp16(wd.cpu().numpy()).astype(np.float64))

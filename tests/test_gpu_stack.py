@@ -23,47 +23,9 @@ pytestmark = pytest.mark.gpu
 from oracle import lga_oracle as O
 import synth_inputs as S
 from paper_2106_02679_amd import binding as B
-from gpu_helpers import run_gpu_step, oracle_shape, adam_struct, oracle_adam, rel_err
+from gpu_helpers import run_gpu_step, oracle_shape, adam_struct, oracle_adam, rel_err, compare_with_oracle
 
 GATE = {"fp32": 1e-5, "bf16": 2e-2}
-
-
-def compare_with_oracle(w, got, ref, gate, adam, zero_init=True):
-    sl = S.tensor_slices(w.d_model, w.d_ff)
-    d = w.d_model
-    k_bias = slice(sl["b_qkv"].start + d, sl["b_qkv"].start + 2 * d)
-    keep = np.ones(w.params_per_layer, dtype=bool)
-    keep[k_bias] = False
-    worst = {}
-    for bnd in range(w.n_layers + 1):
-        worst[f"act{bnd}"] = rel_err(got["boundaries"][bnd], ref.boundaries[bnd])
-    worst["y"] = rel_err(got["y"], ref.boundaries[-1])
-    worst["dx"] = rel_err(got["dx"], ref.dx)
-    for l in range(w.n_layers):
-        if got["grads"][l] is None:
-            continue
-        for name in S.PARAM_ORDER:
-            worst[f"g{l}.{name}"] = rel_err(got["grads"][l][sl[name]], ref.grads[l][sl[name]])
-        q_bias = slice(sl["b_qkv"].start, sl["b_qkv"].start + d)
-        if w.dtype == "fp32":
-            assert np.linalg.norm(got["grads"][l][k_bias]) <= 1e-4 * np.linalg.norm(got["grads"][l][q_bias])
-        assert np.linalg.norm(ref.grads[l][k_bias]) <= 1e-12 * np.linalg.norm(ref.grads[l][q_bias])
-    if adam is not None:
-        for l in range(w.n_layers):
-            worst[f"w{l}"] = rel_err(got["params"][l][keep], ref.new_params[l][keep])
-            worst[f"m{l}"] = rel_err(got["m"][l], ref.new_m[l])
-            # v is quadratic in the gradient, so a relative gradient error e shows up as 2e: gate at twice the gate
-            worst[f"v{l}(halved)"] = 0.5 * rel_err(got["v"][l], ref.new_v[l])
-            for name in S.PARAM_ORDER:
-                if zero_init and name not in S.MATRICES and name not in S.GAINS:
-                    continue
-                sel = np.zeros(w.params_per_layer, dtype=bool)
-                sel[sl[name]] = True
-                sel &= keep
-                worst[f"w{l}.{name}"] = rel_err(got["params"][l][sel], ref.new_params[l][sel])
-    bad = {k: v for k, v in worst.items() if not v < gate}
-    assert not bad, f"over the {gate} gate: {bad}; worst overall {max(worst.values()):.3e}"
-    return worst
 
 
 def test_config0_tiny_fp32_stack_matches_oracle():

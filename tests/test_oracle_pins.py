@@ -348,6 +348,79 @@ def test_adam_first_step_is_signed_unit_step_and_zero_gradient_is_a_fixed_point(
     assert abs((w0[0] - w[0]) - 1e-3 * (1 - 1e-8 / 3)) < 1e-15
 
 
+# ---------------------------------------------------------------- gradient scaling (section 2.2)
+
+@pytest.mark.parametrize("order", ["mbmajor", "layered"])
+def test_a_power_of_two_loss_scale_changes_nothing_in_fp64(order):
+    # Scaling by 2^k is exact in binary floating point (no overflow in fp64 here), and every gradient is linear in
+    # the output gradient: the step with (G * S, loss_scale = S) equals the step with (G, no scaling) bit for bit,
+    # while the gradients it reports are S times larger.
+    shape = tiny_shape(d_l=2, n_mu=2)
+    x, G, params = tiny_problem(shape)
+    step = O.step_layered if order == "layered" else O.step_microbatch_major
+    hp = O.AdamHyper(lr=1e-2, step=3)
+    S_ = 1024.0
+    a = step(x, G, params, shape, hp)
+    b = step(x, G * S_, params, shape, O.AdamHyper(lr=1e-2, step=3, loss_scale=S_, skip_nonfinite=True))
+    assert b.skipped == [False] * shape.d_l
+    for l in range(shape.d_l):
+        assert np.array_equal(b.grads[l], S_ * a.grads[l])
+        assert np.array_equal(a.new_params[l], b.new_params[l])
+        assert np.array_equal(a.new_m[l], b.new_m[l]) and np.array_equal(a.new_v[l], b.new_v[l])
+    # a scale that is not a power of two: equal up to rounding only
+    c = step(x, G * 3.0, params, shape, O.AdamHyper(lr=1e-2, step=3, loss_scale=3.0))
+    for l in range(shape.d_l):
+        solid = np.abs(a.grads[l]) > 1e-9          # the key bias' gradient is rounding noise, its update a coin toss
+        assert np.allclose(a.new_params[l][solid], c.new_params[l][solid], rtol=1e-13, atol=1e-15)
+        assert np.allclose(a.new_m[l], c.new_m[l], rtol=1e-12, atol=1e-15)
+
+
+def test_an_update_with_a_non_finite_gradient_is_left_out_as_a_whole_only_when_asked():
+    w0, m0, v0 = np.array([0.5, -1.0, 2.0]), np.array([0.1, 0.0, -0.2]), np.array([0.04, 0.01, 0.0])
+    for bad in (np.inf, -np.inf, np.nan):
+        g = np.array([0.3, bad, -0.1])
+        w, m, v = O.adam_update(w0, m0, v0, g, O.AdamHyper(loss_scale=8.0, skip_nonfinite=True))
+        assert np.array_equal(w, w0) and np.array_equal(m, m0) and np.array_equal(v, v0)
+        assert O.adam_skips(g, O.AdamHyper(skip_nonfinite=True)) and not O.adam_skips(g, O.AdamHyper())
+        w, m, v = O.adam_update(w0, m0, v0, g, O.AdamHyper(loss_scale=8.0))
+        assert not np.isfinite(m[1]) and np.isfinite(w[0]) and w[0] != w0[0]      # without the test the value spreads
+    g = np.array([0.3, 1e300, -0.1])                                             # huge but finite: a normal update
+    assert not O.adam_skips(g, O.AdamHyper(skip_nonfinite=True))
+    # a step whose output gradient holds an infinity reaches every layer below it: all of them are left out
+    shape = tiny_shape(d_l=2, n_mu=2)
+    x, G, params = tiny_problem(shape)
+    G = G.copy()
+    G[1, 0, 2, 1] = np.inf
+    with np.errstate(invalid="ignore", over="ignore"):
+        r = O.step_layered(x, G, params, shape, O.AdamHyper(skip_nonfinite=True))
+    assert r.skipped == [True, True]
+    for l in range(shape.d_l):
+        assert np.array_equal(r.new_params[l], np.asarray(params[l], dtype=np.float64))
+        assert not r.new_m[l].any() and not r.new_v[l].any()
+
+
+def test_loss_scaler_follows_its_closed_form():
+    # n clean steps from scale s0 with growth interval k: s0 * 2^(n // k), capped; an overflow halves it (floored)
+    # and restarts the count
+    s = O.LossScaler(scale=4.0, growth_interval=3, max_scale=64.0, min_scale=1.0)
+    seen = []
+    for n in range(1, 16):
+        O.loss_scaler_update(s, False)
+        seen.append(s.scale)
+        assert s.scale == min(4.0 * 2.0 ** (n // 3), 64.0)
+    assert seen[-1] == 64.0
+    O.loss_scaler_update(s, False)                   # 16th clean step: one past a growth, count is 1
+    O.loss_scaler_update(s, True)
+    assert s.scale == 32.0 and s.good_steps == 0
+    O.loss_scaler_update(s, False); O.loss_scaler_update(s, False)
+    assert s.scale == 32.0 and s.good_steps == 2     # the overflow restarted the run of clean steps
+    O.loss_scaler_update(s, False)
+    assert s.scale == 64.0
+    for _ in range(10):
+        O.loss_scaler_update(s, True)
+    assert s.scale == 1.0                            # floor
+
+
 def test_key_bias_gradient_vanishes_identically():
     # Softmax does not change when every score of a row moves by the same amount, and adding a
     # constant vector c to every key moves row i's scores by q_i . c: so dL/d(key bias) = 0.
