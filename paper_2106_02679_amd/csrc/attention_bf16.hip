@@ -206,9 +206,16 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
     // Softmax reference per query, in the log2 domain.  It is FIXED once the query's first 32 keys are seen
     // (p = 2^(score - m_ref) is then exact up to a common factor that the final division removes), so the
     // output accumulators are never rescaled - they live in accumulation registers that only MFMAs touch.
-    // A score some 100 (log2 units) above the reference would overflow fp32: a row sum beyond 1e30 makes the
-    // whole workgroup start over with the reference raised by kRefStep (never seen on real activations).
-    constexpr float kRefStep = 64.f;
+    // A probability far above 1 must still fit the format P is rounded to for the second product - bf16 reaches
+    // as far as fp32, IEEE half ends at 65504 - and a probability is never larger than its row's running sum.  So a
+    // lane whose sum reaches kSumLimit makes the whole workgroup start over, each query with its reference raised
+    // by what its own sum asks for (to a sum of about 2^kTargetLog2), or by kRefStep if the sum overflowed fp32.
+    // On ordinary activations bf16 never restarts; half precision does when the keys beyond the first 32 score
+    // some 15 (log2 units) higher, which wide layers do reach.  The number of attempts is bounded, so that scores
+    // that are infinite or not numbers end in a non-finite output instead of an endless loop.
+    constexpr float kSumLimit = std::is_same<E, f16>::value ? 6.0e4f : 1.0e30f;
+    constexpr float kRefStep = 64.f, kTargetLog2 = 8.f;
+    constexpr int kMaxAttempts = 6;
     f32x16 oacc[2][NC];
     float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2];
     const float c2 = rsqrtf((float)dh) * kLog2e;
@@ -348,7 +355,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
 #pragma unroll
         for (int g = 0; g < 4; ++g) pv_group(3, g);    // slot 5: PV(3)
         // overflow guard: a sum this large means that some score was far above the reference
-        if (__any(!(l_run[0] < 1.0e30f) || !(l_run[1] < 1.0e30f))) restart_flag[0] = 1;
+        if (__any(!(l_run[0] < kSumLimit) || !(l_run[1] < kSumLimit))) restart_flag[0] = 1;
     };
     // wait for this wavefront's part of the oldest tile in flight (`newer`: a younger one is in flight too),
     // then a bare s_barrier - a __syncthreads() fence would wait for the younger tile as well.  After it the
@@ -365,7 +372,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
 
     const int kend = causal ? min(sh.s, qb * 256 + 256) : sh.s;      // keys needed by this block: [0, kend)
     const int kfull = causal ? qb * 256 : sh.s / KT * KT;           // tiles before it are fully visible to every wavefront
-    for (;;) {
+    for (int attempt = 1;; ++attempt) {
         const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -376,7 +383,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
         // three LDS stages: tile k0 is multiplied while tiles k0 + KT and k0 + 2 KT are in flight
         dma_tile(0, 0);
         if (KT < kend) dma_tile(KT, 1);
-        if (m_ref[0] == -INFINITY) {
+        if (attempt == 1) {                  // uniform over the workgroup: the block below holds a barrier
             // First attempt: the scores of each query's first 32 keys fix its softmax reference (key 0 is
             // visible to every query; for the first queries of the sequence these keys are partly masked).
             publish(KT < kend);
@@ -411,13 +418,18 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
             if (!causal || k0 <= qw0) tile(k0, stage, std::true_type{});
         }
         __syncthreads();
-        if (!restart_flag[0]) break;
-        // start over with a larger reference
+        if (!restart_flag[0] || attempt == kMaxAttempts) break;
+        // start over with larger references
         __builtin_amdgcn_s_waitcnt(0x0F70);         // loads of tiles that were still in flight
         __syncthreads();
         if (threadIdx.x == 0) restart_flag[0] = 0;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) m_ref[u] += kRefStep;
+        for (int u = 0; u < 2; ++u) {
+            const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);      // both lanes of a query see the same sum
+            float raise = 0.f;                                                // a query whose sum is fine keeps its reference
+            if (!(l_tot < 256.f)) raise = l_tot < 3.0e38f ? ceilf(__log2f(l_tot)) - kTargetLog2 : kRefStep;
+            m_ref[u] += raise;
+        }
     }
 #pragma unroll
     for (int u = 0; u < 2; ++u) {

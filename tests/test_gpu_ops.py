@@ -336,11 +336,13 @@ def test_attention_forward_and_backward(case):
         assert rel_err(got[:, sl], dqkv_ref[:, sl]) < tol_b, name
 
 
-@pytest.mark.parametrize("dh,causal", [(64, True), (128, True), (128, False)])
-def test_attention_with_scores_that_keep_growing_along_the_keys(dh, causal):
+@pytest.mark.parametrize("dt,dh,causal", [(BF16, 64, True), (BF16, 128, True), (BF16, 128, False), (F16, 64, True),
+                                          (F16, 128, False), (F16, 160, True)])
+def test_attention_with_scores_that_keep_growing_along_the_keys(dt, dh, causal):
     """The forward kernel fixes each query's softmax reference at its first 32 keys.  Here later keys score
     more than 100 (log2 units) above those, which the kernel must survive by starting over with a larger
-    reference: outputs, log-sum-exp and the backward (which uses that log-sum-exp) still match the oracle."""
+    reference: outputs, log-sum-exp and the backward (which uses that log-sum-exp) still match the oracle.
+    In half precision the probabilities must also stay below 65504, so the same happens after some 15 units."""
     n_seq, s, heads = 1, 320, 2
     d = heads * dh
     rng = np.random.default_rng(77 + dh)
@@ -349,29 +351,90 @@ def test_attention_with_scores_that_keep_growing_along_the_keys(dh, causal):
     for h in range(heads):
         qkv[:, h * dh] = math.sqrt(dh)                            # q[:, 0] = sqrt(dh)
         qkv[:, d + h * dh] = ramp                                 # k[j, 0] = j / 4
-    qkv = S.round_to_bf16(qkv)
-    dout = rnd(rng, (n_seq * s, d), BF16)
+    qkv = ROUND[dt](qkv)
+    dout = rnd(rng, (n_seq * s, d), dt)
     out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh, causal)
     # the case is what it claims: the last query's log-sum-exp lies > 100 log2 units above its first 32 scores
     t4 = qkv.astype(np.float64).reshape(n_seq, s, 3, heads, dh)
     first = np.einsum("bhc,bkhc->bhk", t4[:, -1, 0], t4[:, :32, 1]) / math.sqrt(dh)
     assert ((lse_ref[..., -1] - first.max(-1)) * math.log2(math.e) > 100).all()
-    qd, dod = to_dev(qkv, BF16), to_dev(dout, BF16)
-    out, dqkv = empty_dev((n_seq * s, d), BF16), empty_dev((n_seq * s, 3 * d), BF16)
+    qd, dod = to_dev(qkv, dt), to_dev(dout, dt)
+    out, dqkv = empty_dev((n_seq * s, d), dt), empty_dev((n_seq * s, 3 * d), dt)
     lse = torch.empty(n_seq * heads * s, device="cuda")
     delta = torch.empty(n_seq * heads * s, device="cuda")
-    B.check(B.lib.lga_op_attention_fwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+    B.check(B.lib.lga_op_attention_fwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
                                        int(causal), None))
-    B.check(B.lib.lga_op_attention_bwd(BF16, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+    B.check(B.lib.lga_op_attention_bwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
                                        dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), None))
     torch.cuda.synchronize()
     assert np.isfinite(to_host(out)).all()
-    assert rel_err(to_host(out), out_ref) < 1e-2
+    assert rel_err(to_host(out), out_ref) < TOL_ATTN[dt][0]
     assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < 1e-3 * np.abs(lse_ref).max()
     got = to_host(dqkv)
-    # near one-hot probabilities times keys of size ~80: the bf16 rounding of dS weighs more than on ordinary inputs
+    # near one-hot probabilities times keys of size ~80: the rounding of dS weighs more than on ordinary inputs
     for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
-        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < 4e-2, name
+        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < 2 * TOL_ATTN[dt][1], name
+
+
+@pytest.mark.parametrize("dt,dh,s,causal", [(F16, 128, 2048, True), (F16, 64, 1000, False), (BF16, 128, 2048, True)])
+def test_attention_with_the_score_spread_of_a_wide_layer(dt, dh, s, causal):
+    """Queries and keys of size ~2.2 per element, as d_model = 12288 gives with N(0, 0.02^2) weights: scores spread
+    by ~7 log2 units (one sigma), so among 2048 keys some lie 15 - 25 above the best of a query's first 32.  That
+    is nothing for bf16 and beyond 65504 for half precision, whose kernel must then start over."""
+    n_seq, heads = 1, 2
+    d = heads * dh
+    rng = np.random.default_rng(s + dh)
+    qkv = rng.standard_normal((n_seq * s, 3 * d)).astype(np.float32)
+    qkv[:, :2 * d] *= 2.2
+    qkv = ROUND[dt](qkv)
+    dout = rnd(rng, (n_seq * s, d), dt)
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh, causal)
+    t4 = qkv.astype(np.float64).reshape(n_seq, s, 3, heads, dh)
+    sc = np.einsum("bqhc,bkhc->bhqk", t4[:, :, 0], t4[:, :, 1]) / math.sqrt(dh) * math.log2(math.e)
+    if causal:
+        sc = np.where(np.tril(np.ones((s, s), dtype=bool)), sc, -np.inf)
+    assert ((sc.max(-1) - sc[..., :32].max(-1)) > 16).any()          # the case is what it claims
+    qd, dod = to_dev(qkv, dt), to_dev(dout, dt)
+    out, dqkv = empty_dev((n_seq * s, d), dt), empty_dev((n_seq * s, 3 * d), dt)
+    lse = torch.empty(n_seq * heads * s, device="cuda")
+    delta = torch.empty(n_seq * heads * s, device="cuda")
+    B.check(B.lib.lga_op_attention_fwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+                                       int(causal), None))
+    B.check(B.lib.lga_op_attention_bwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+                                       dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), None))
+    torch.cuda.synchronize()
+    assert np.isfinite(to_host(out)).all()
+    assert rel_err(to_host(out), out_ref) < TOL_ATTN[dt][0]
+    assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < 1e-3 * np.abs(lse_ref).max()
+    got = to_host(dqkv)
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < TOL_ATTN[dt][1], name
+
+
+@pytest.mark.parametrize("dt,bad", [(BF16, float("nan")), (BF16, float("inf")), (F16, float("nan")), (F16, float("-inf"))])
+def test_attention_forward_ends_on_non_finite_scores(dt, bad):
+    """A query or key that is infinite or not a number makes its row sums non-finite, which no larger softmax
+    reference can cure: the forward kernel gives up after a bounded number of attempts and returns a non-finite
+    output for the (sequence, head) blocks concerned; the other head's output is untouched by it."""
+    n_seq, s, heads, dh = 1, 300, 2, 64
+    d = heads * dh
+    rng = np.random.default_rng(5)
+    qkv = rnd(rng, (n_seq * s, 3 * d), dt)
+    dout = rnd(rng, (n_seq * s, d), dt)
+    out_ref, _, _ = attention_reference(qkv, dout, n_seq, s, heads, dh, True)
+    qkv[3, d + 5] = bad                                               # key 3 of head 0: seen by every query from 3 on
+    qd = to_dev(qkv, dt)
+    out = empty_dev((n_seq * s, d), dt)
+    lse = torch.empty(n_seq * heads * s, device="cuda")
+    B.check(B.lib.lga_op_attention_fwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh, 1, None))
+    torch.cuda.synchronize()
+    got = to_host(out)
+    if np.isnan(bad):
+        assert not np.isfinite(got[3:, :dh]).any()                    # every query that sees the key
+    else:
+        assert not np.isfinite(got[3:, :dh]).all()                    # those whose score with it is +inf
+    assert rel_err(got[:, dh:], out_ref[:, dh:]) < TOL_ATTN[dt][0]    # head 1
+    assert rel_err(got[:3, :dh], out_ref[:3, :dh]) < TOL_ATTN[dt][0]  # queries before the bad key (causal)
 
 
 def test_attention_mfma_rejects_unsupported_head_size():
