@@ -48,8 +48,8 @@ def parse():
     ap.add_argument("--offload", action="store_true",
                     help="keep the layer-boundary activations in pinned host memory (two slots on the device)")
     ap.add_argument("--fp16", action="store_true",
-                    help="run the 16-bit configuration in IEEE half instead of bfloat16, with a loss scale of 1024 and "
-                         "the per-layer non-finite test before each Adam step (not the headline)")
+                    help="run the 16-bit configuration in IEEE half instead of bfloat16, with the per-layer non-finite "
+                         "test before each Adam step (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=64)
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
@@ -127,7 +127,10 @@ def main():
                         offload_checkpoints=1 if args.offload else 0)
     torch.cuda.set_device(0)
     tdt = {B.LGA_FP32: torch.float32, B.LGA_BF16: torch.bfloat16, B.LGA_FP16: torch.float16}[dt]
-    loss_scale = 1024.0 if dt == B.LGA_FP16 else 0.0
+    # half precision: every Adam step tests its layer's gradient first; the synthetic output gradient has unit variance,
+    # thousands of times a real loss gradient, so it is its own "scaled" gradient (scale 1: nothing overflows, every
+    # update is applied - "skipped_layer_updates" in the output line says so)
+    loss_scale = 1.0 if dt == B.LGA_FP16 else 0.0
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     gen = torch.Generator(device="cuda").manual_seed(0)
     x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)
@@ -138,7 +141,7 @@ def main():
     marks = []      # per timed step: events at its start, between the sweeps, at its end
 
     def step(t, timed=False):
-        adam = B.lga_adam(1e-3, 0.9, 0.999, 1e-8, t, loss_scale, 1 if loss_scale else 0)
+        adam = B.lga_adam(1e-3, 0.9, 0.999, 1e-8, t, loss_scale, 1 if dt == B.LGA_FP16 else 0)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timed else None
         if timed:
             ev[0].record()
@@ -170,6 +173,7 @@ def main():
     ms_total = e0.elapsed_time(e1)
     stats = st.profile_end()
     restores = (st.restore_count() - restores0) / args.steps
+    skipped = sum(st.nonfinite_layers()) if dt == B.LGA_FP16 else 0       # layers whose last update was left out
     ms_step = ms_total / args.steps
     step_ms = [m[0].elapsed_time(m[2]) for m in marks]
     fwd_ms = [m[0].elapsed_time(m[1]) for m in marks]
@@ -231,6 +235,7 @@ def main():
                       "adam_kernels": sum(k["ms"] for k in stats if k["name"].startswith("adam")) / args.steps}
                      if args.order == "layered" else None),
         "restores_per_step": restores,
+        "skipped_layer_updates": skipped,
         "device_arena_bytes": B.arena_bytes(cfg), "pinned_host_bytes": B.host_bytes(cfg),
         # checkpoint offload: every boundary goes to the host once, all but the top two come back once
         "pcie_bytes_per_step": (2 * w.n_layers * tokens * w.d_model * (2 if is16 else 4)) if args.offload else 0,

@@ -215,6 +215,10 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
     // that are infinite or not numbers end in a non-finite output instead of an endless loop.
     constexpr float kSumLimit = std::is_same<E, f16>::value ? 6.0e4f : 1.0e30f;
     constexpr float kRefStep = 64.f, kTargetLog2 = 8.f;
+    // Half precision starts 6 units above the best of the first 32 scores: its probabilities then have 22 units of
+    // headroom instead of 16, which at the score spread of wide layers saves most restarts, and keys more than 8
+    // units below that best score become denormal (still exact to 2^-25 of the row's largest terms).
+    constexpr float kRefBias = std::is_same<E, f16>::value ? 6.f : 0.f;
     constexpr int kMaxAttempts = 6;
     f32x16 oacc[2][NC];
     float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2];
@@ -400,7 +404,7 @@ __global__ __launch_bounds__(256, 1) void attn_fwd_kernel(const E *__restrict__ 
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (8 * (r >> 2) + (r & 3) <= qrel) raw = fmaxf(raw, st[u][r]);
-                m_ref[u] = fmaxf(raw, __shfl_xor(raw, 32, 64)) * c2;
+                m_ref[u] = fmaxf(raw, __shfl_xor(raw, 32, 64)) * c2 + kRefBias;
             }
         }
         // No early exit on the restart flag: an attempt that is going to be repeated just runs to its end
