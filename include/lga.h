@@ -85,14 +85,14 @@ typedef struct lga_config {
                              order and by unfused Adam when n_layers > 1); 0: a single layer-sized
                              buffer, reused layer after layer (appendix C.3: gradient storage made
                              negligible by updating a layer's weights at once) */
-    int32_t wgrad_groups; /* bf16 mode, layered order: consecutive groups of a layer whose weight-gradient
+    int32_t wgrad_groups; /* 16-bit modes, layered order: consecutive groups of a layer whose weight-gradient
                              GEMMs are merged into one that contracts over all their tokens (their
                              transposed operands are kept side by side until then: 2 (2 d_ff + 8 d_model)
                              bytes per token, counted by lga_arena_bytes).  The sum over micro-batches then happens in
                              the GEMM's k loop instead of by read-modify-write of the fp32 buffer.
                              1 = no merging, 0 = automatic (as many as keep those operand buffers within
                              a quarter of the rest of the arena), at most n_micro / group. */
-    int32_t param_buffers; /* bf16 mode: how many layers' 16-bit parameter copies are kept (figure 2, table C.1:
+    int32_t param_buffers; /* 16-bit modes: how many layers' 16-bit parameter copies are kept (figure 2, table C.1:
                              parameter buffers).  0 = one per layer: nothing is ever restored, every Adam step
                              rewrites its layer's copies.  With fewer, layer l uses buffer l % param_buffers and
                              its fp32 masters are cast again ("restore") whenever another layer has used that
@@ -164,8 +164,8 @@ int lga_loss_scaler_update(lga_loss_scaler *scaler, int32_t overflowed);
  *  out          host, receives the handle.
  * Adam moments start at zero.  The 16-bit parameter copy of every layer is produced here
  * (section 2.5: parameters are converted to 16 bits before use) and refreshed by each Adam step.
- * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in bf16 mode,
- * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes up to 160 have MFMA attention kernels in bf16 mode
+ * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in the 16-bit modes,
+ * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes up to 160 have MFMA attention kernels in the 16-bit modes
  * (built for 32, 64, 96, 128, 160; sizes in between run in the next larger one); larger head sizes, and the fp32
  * mode, use a one-wavefront-per-position kernel that is meant for checking, not for speed, and limits seq_len
  * (2 seq_len + 2 d_h <= 15000).  LGA_ERR_OOM if the arena does not fit. */
