@@ -6,7 +6,8 @@
 // left once the operands have to come from somewhere.  Modes 3 and 4 add what fills LDS in a GEMM - direct-to-LDS
 // loads of 64 KB per 64 MFMAs of each wavefront, from a 4 MB window that stays in L2 - and the barrier per k tile:
 // together the structural ceiling of an output-stationary 256 x 256 tile kernel on this chip, before a byte has
-// come from HBM.  Used by the benchmark tools only.
+// come from HBM.  Mode 5 is mode 0 with v_mfma_f32_32x32x16_f16 on IEEE half operands, whose three more mantissa bits
+// toggle too.  Used by the benchmark tools only.
 #include <cstdio>
 
 #include "kernels.h"
@@ -18,7 +19,8 @@ namespace {
 constexpr int kLdsChunks = 8192;        // 128 KB of operand data in LDS (mode 2)
 
 // mode 0: random register operands; 1: constant register operands; 2: random operands re-read from LDS;
-// 3: as 2, plus direct-to-LDS loads at a GEMM tile's rate; 4: as 3, plus a barrier per k tile
+// 3: as 2, plus direct-to-LDS loads at a GEMM tile's rate; 4: as 3, plus a barrier per k tile;
+// 5: random register operands in IEEE half, the f16 instruction
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 constexpr int kDmaWindow = 4 << 20;       // bytes of source data the loads of modes 3 and 4 walk over (L2-resident)
 
@@ -30,7 +32,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
     // operand registers: values around +-1 with random mantissas and signs, or all ones
     bf16x8 a[4], b[4];
     unsigned s = (threadIdx.x + 1) * 2654435761u ^ (blockIdx.x * 40503u);
-    if constexpr (MODE >= 2) {
+    if constexpr (MODE >= 2 && MODE <= 4) {
         for (int i = threadIdx.x; i < kLdsChunks; i += 256) {
             u32x4 v;
 #pragma unroll
@@ -51,8 +53,9 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
             const unsigned x = s;
             s = s * 1664525u + 1013904223u;
             const unsigned y = s;
-            va[j] = constant_operands ? 0x3f803f80u : ((x & 0x807f807fu) | 0x3f003f00u);
-            vb[j] = constant_operands ? 0x3f803f80u : ((y & 0x807f807fu) | 0x3f003f00u);
+            // bf16: sign and 7 mantissa bits random, exponent of [0.5, 1); half: sign and 10 mantissa bits, same range
+            va[j] = constant_operands ? 0x3f803f80u : MODE == 5 ? ((x & 0x83ff83ffu) | 0x38003800u) : ((x & 0x807f807fu) | 0x3f003f00u);
+            vb[j] = constant_operands ? 0x3f803f80u : MODE == 5 ? ((y & 0x83ff83ffu) | 0x38003800u) : ((y & 0x807f807fu) | 0x3f003f00u);
         }
         a[i] = __builtin_bit_cast(bf16x8, va);
         b[i] = __builtin_bit_cast(bf16x8, vb);
@@ -81,27 +84,32 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
         // runs; in modes >= 3 each wavefront also issues its 16 KB share of the tile's 64 KB of direct-to-LDS loads
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if constexpr (MODE >= 3) {
+            if constexpr (MODE == 3 || MODE == 4) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(
                         rs, (lds_ptr_t)(smem + kLdsChunks * 8 + wave * 16384 + (q * 4 + j) * 1024), 16,
                         (int)((goff + (q * 4 + j) * 1024 + lane * 16) & (kDmaWindow - 1)), 0, 0, 0);
             }
-            if constexpr (MODE >= 2) {
+            if constexpr (MODE >= 2 && MODE <= 4) {
                 if (q & 1) fetch(a, b);
                 else fetch(a2, b2);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16((MODE >= 2 && (q & 1)) ? a2[i] : a[i],
-                                                                             (MODE >= 2 && (q & 1)) ? b2[j] : b[j],
-                                                                             acc[i * 4 + j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                    constexpr bool second = MODE >= 2 && MODE <= 4;       // operand sets alternate when they come from LDS
+                    const bf16x8 fa = (second && (q & 1)) ? a2[i] : a[i], fb = (second && (q & 1)) ? b2[j] : b[j];
+                    if constexpr (MODE == 5)
+                        acc[i * 4 + j] = mfma_32x32x16<f16>(__builtin_bit_cast(x8<f16>, fa), __builtin_bit_cast(x8<f16>, fb),
+                                                            acc[i * 4 + j]);
+                    else
+                        acc[i * 4 + j] = mfma_32x32x16<bf16>(fa, fb, acc[i * 4 + j]);
+                }
         }
         goff = (goff + 65536u * 7u) & (kDmaWindow - 1);
-        if constexpr (MODE >= 3) __builtin_amdgcn_s_waitcnt(0x0070 | 15);     // at most one tile's loads in flight
+        if constexpr (MODE == 3 || MODE == 4) __builtin_amdgcn_s_waitcnt(0x0070 | 15);     // at most one tile's loads in flight
         if constexpr (MODE == 4) {
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
@@ -121,7 +129,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
 
 extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 4 || !sink || !tflops) return LGA_ERR_ARG;
+    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 5 || !sink || !tflops) return LGA_ERR_ARG;
     iters &= ~3;                                            // the loop does four groups of 16 MFMAs per turn
     // results go to the first 65536 floats of sink; modes 3 and 4 read the kDmaWindow bytes after them
     const unsigned *src = reinterpret_cast<const unsigned *>(sink + 65536);
@@ -150,7 +158,8 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         case 1: hipLaunchKernelGGL(mfma_rate_kernel<1>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
         case 2: hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
         case 3: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
-        default: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
+        case 4: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
+        default: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
     }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);

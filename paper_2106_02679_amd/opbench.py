@@ -118,12 +118,12 @@ def run_mfma(args):
     from paper_2106_02679_amd import binding as B
     sink = torch.ones(65536 + (4 << 20) // 4, device="cuda")
     what = {1: "constant register operands", 0: "random register operands  ", 2: "random operands via LDS   ",
-            3: "... + direct-to-LDS loads ", 4: "... + a barrier per k tile"}
-    for mode in (1, 0, 2, 3, 4):
+            3: "... + direct-to-LDS loads ", 4: "... + a barrier per k tile", 5: "random registers, IEEE half"}
+    for mode in (1, 0, 5, 2, 3, 4):
         for iters in (400000, 4000000):
             tf = C.c_double()
             B.check(B.lib.lga_op_mfma_rate(iters, mode, sink.data_ptr(), C.byref(tf), None))
-            print(f"v_mfma_f32_32x32x16_bf16 only, {what[mode]}, {iters * 16} MFMAs per wavefront: "
+            print(f"v_mfma_f32_32x32x16_{'f16' if mode == 5 else 'bf16'} only, {what[mode]}, {iters * 16} MFMAs per wavefront: "
                   f"{tf.value:8.1f} TFLOP/s", flush=True)
 
 
