@@ -134,7 +134,7 @@ def main():
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     gen = torch.Generator(device="cuda").manual_seed(0)
     x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)
-    dy = (torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen) * (loss_scale or 1.0)).to(tdt)
+    dy = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)      # "scaled" by loss_scale = 1
     st = B.Stack(cfg)                     # weights filled on the device: N(0, 0.02^2), gains 1, biases 0
     torch.cuda.synchronize()
 
