@@ -91,6 +91,20 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
                          const void *dout, void *dqkv, float *delta, int32_t n_seq, int32_t s, int32_t heads,
                          int32_t dh, int32_t causal, void *stream);
 
+/* The same attention for head sizes beyond the fused kernels (table B.1's X_[x] family has d_h = 2 x: 216, 320), built
+ * from batched GEMMs over the heads with the score matrices in a workspace: S = Q K^T in fp32, a row kernel for the
+ * softmax (P rounded to 16 bits) and O = P V; backward S and dP = dO V^T in fp32, a row kernel for P, delta and dS, then
+ * dV = P^T dO, dQ = dS K, dK = dS^T Q.  Arguments and results as above (16-bit dtypes only).  s and dh multiples of 8,
+ * s <= 32768.  workspace: device, 256-byte aligned, at least lga_op_attention_gemm_workspace_bytes(s, 1) = 12 s^2 bytes;
+ * up to ..._bytes(s, heads) lets that many heads share each launch.  Contents are scratch. */
+uint64_t lga_op_attention_gemm_workspace_bytes(int32_t s, int32_t heads);
+int lga_op_attention_gemm_fwd(int32_t dtype, const void *qkv, void *out, float *lse, int32_t n_seq, int32_t s,
+                              int32_t heads, int32_t dh, int32_t causal, void *workspace, uint64_t workspace_bytes,
+                              void *stream);
+int lga_op_attention_gemm_bwd(int32_t dtype, const void *qkv, const void *out, const float *lse, const void *dout,
+                              void *dqkv, float *delta, int32_t n_seq, int32_t s, int32_t heads, int32_t dh,
+                              int32_t causal, void *workspace, uint64_t workspace_bytes, void *stream);
+
 /* One Adam update of n parameters in place (w, m, v fp32; g fp32 read-only); if w16 != NULL the new
  * weights are also written in the 16-bit format w16_dtype (section 2.5: 16-bit copy for the next use).
  * adam->loss_scale divides the gradient first; with adam->skip_nonfinite, *nonfinite (device int32, required then)

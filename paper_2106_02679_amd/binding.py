@@ -105,6 +105,10 @@ SIGNATURES = {
     "lga_op_colsum_scratch_floats": (_u64, [_i32, _i32]),
     "lga_op_attention_fwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
     "lga_op_attention_bwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "lga_op_attention_gemm_workspace_bytes": (_u64, [_i32, _i32]),
+    "lga_op_attention_gemm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _u64, _vp]),
+    "lga_op_attention_gemm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _u64,
+                                            _vp]),
     "lga_op_adam": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _i32, _u64, _P(lga_adam), _vp, _vp]),
     "lga_nonfinite_layers": (C.c_int, [_vp, _P(_i32), _P(_i32)]),
     "lga_grads_nonfinite": (C.c_int, [_vp, _P(_i32), _P(_i32)]),

@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblga.so")
 
-SOURCES = ["rowops.hip", "gemm_f32.hip", "gemm_bf16.hip", "attention_simple.hip", "attention_bf16.hip",
+SOURCES = ["rowops.hip", "gemm_f32.hip", "gemm_bf16.hip", "attention_simple.hip", "attention_bf16.hip", "attention_gemm.hip",
            "stack.hip", "ops_api.hip", "mfma_rate.hip"]
 
 # -packed-fp32-ops is switched off for the device pass; the host pass warns that it does not know the feature.

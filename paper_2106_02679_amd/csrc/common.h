@@ -113,6 +113,10 @@ template <class T> struct GemmParams {
     size_t partial_floats;
     // set by the launcher when it splits: number of k slices, k elements per slice (a multiple of 64)
     int ksplit, kchunk;
+    // batch > 1: that many independent products of the same shape in one launch; problem z reads A + z strideA and
+    // B + z strideB and writes every output (and reads aux) at + z strideC (elements).  Not combined with a split k range.
+    int batch;
+    long long strideA, strideB, strideC;
 };
 
 }  // namespace lga

@@ -228,6 +228,19 @@ __device__ __forceinline__ void epilogue8(const GemmParams<E> &p, int m, int n, 
     *reinterpret_cast<x8<E> *>(p.out + idx) = o;
 }
 
+// Batched launch: work item `tile` belongs to problem tile / ntiles; rebase the operands and outputs onto it.
+template <class E> __device__ __forceinline__ void select_problem(GemmParams<E> &p, int &tile, int ntiles) {
+    const int z = tile / ntiles;
+    tile -= z * ntiles;
+    p.A += z * p.strideA;
+    p.B += z * p.strideB;
+    const long long c = z * p.strideC;
+    if (p.out) p.out += c;
+    if (p.out2) p.out2 += c;
+    if (p.outf) p.outf += c;
+    if (p.aux) p.aux += c;
+}
+
 template <int BM, int BN, bool A_KM, bool B_KM, int EPI, class E>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int tiles_m, int tiles_n) {
     constexpr int WM = BM / 2, WN = BN / 2;     // wavefront tile
@@ -242,10 +255,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int til
     const int ntiles = tiles_m * tiles_n;
     int tile;
     {
+        const int nwork = p.batch > 1 ? ntiles * p.batch : ntiles;      // a batch is ntiles work items per problem
         const int pid = blockIdx.x, xcd = pid & 7, local = pid >> 3;
-        const int base = ntiles >> 3, rem = ntiles & 7;
+        const int base = nwork >> 3, rem = nwork & 7;
         tile = xcd * base + (xcd < rem ? xcd : rem) + local;
     }
+    if (p.batch > 1) select_problem(p, tile, ntiles);
     constexpr int GROUP_M = 8;
     const int group_size = GROUP_M * tiles_n;
     const int gid = tile / group_size;
@@ -468,11 +483,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     int tile;
     {
         // with a split k range there are ksplit work items per tile, slice-major
-        const int nwork = (EPI == EPI_ACCUM_F32 && p.ksplit > 1) ? ntiles * p.ksplit : ntiles;
+        const int nwork = (EPI == EPI_ACCUM_F32 && p.ksplit > 1) ? ntiles * p.ksplit : p.batch > 1 ? ntiles * p.batch : ntiles;
         const int pid = blockIdx.x, xcd = pid & 7, local = pid >> 3;
         const int base = nwork >> 3, rem = nwork & 7;
         tile = xcd * base + (xcd < rem ? xcd : rem) + local;
     }
+    if (p.batch > 1) select_problem(p, tile, ntiles);
     if constexpr (EPI == EPI_ACCUM_F32) {
         if (p.ksplit > 1) {
             // this workgroup multiplies slice z of the k range into partial result z ([M][N], dense)
@@ -718,8 +734,10 @@ void launch_one(const GemmParams<E> &p, hipStream_t s) {
     const double mn = (double)p.M * p.N;
     const double out_bytes = EPI == EPI_ACCUM_F32 ? (p.beta != 0.f ? 8.0 : 4.0) : (EPI == EPI_BIAS_GELU ? 4.0 : 2.0);
     const double aux_bytes = (EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU) ? 2.0 : 0.0;
-    ProfScope scope(name, 2.0 * mn * p.K, 2.0 * ((double)p.M * p.K + (double)p.K * p.N) + mn * (out_bytes + aux_bytes), s);
-    const int work = tiles_m * tiles_n * (p.ksplit > 1 ? p.ksplit : 1);
+    const double nb = p.batch > 1 ? p.batch : 1;
+    ProfScope scope(name, nb * 2.0 * mn * p.K,
+                    nb * (2.0 * ((double)p.M * p.K + (double)p.K * p.N) + mn * (out_bytes + aux_bytes)), s);
+    const int work = tiles_m * tiles_n * (p.ksplit > 1 ? p.ksplit : p.batch > 1 ? p.batch : 1);
     hipLaunchKernelGGL(kern, dim3(work), dim3(256), smem, s, p, tiles_m, tiles_n);
 }
 
@@ -744,7 +762,7 @@ template <bool A_KM, bool B_KM, int EPI, class E> void launch_tiles(const GemmPa
     if constexpr (A_KM && B_KM && EPI == EPI_ACCUM_F32) {
         // A weight-gradient GEMM of a narrow layer: few output tiles, very long k.  The k range is cut into slices
         // that run as separate work items of the large-tile kernel and are summed afterwards.
-        const int slices = gemm_splitk_slices(p.M, p.N, p.K);
+        const int slices = p.batch > 1 ? 1 : gemm_splitk_slices(p.M, p.N, p.K);
         if (slices > 1 && p.partial && (size_t)slices * p.M * p.N <= p.partial_floats && p.N % 4 == 0 && p.ldc % 4 == 0 &&
             (reinterpret_cast<uintptr_t>(p.outf) & 15) == 0) {
             GemmParams<E> q = p;
@@ -759,6 +777,16 @@ template <bool A_KM, bool B_KM, int EPI, class E> void launch_tiles(const GemmPa
                                p.outf, p.M, p.N, p.ldc, p.beta);
             return;
         }
+    }
+    if (p.batch > 1) {
+        // many small problems (the products of attention, one per head): enough work items either way, so take the
+        // tile size that pads the output less, the large one on a tie
+        const double pad256 = (double)big * 65536.0, pad128 = (double)((p.M + 127) / 128) * ((p.N + 127) / 128) * 16384.0;
+        if (big * p.batch >= 128 && pad256 <= 1.15 * pad128)
+            launch_one<256, 256, A_KM, B_KM, EPI, E>(p, s);
+        else
+            launch_one<128, 128, A_KM, B_KM, EPI, E>(p, s);
+        return;
     }
     if (big >= 128)
         launch_one<256, 256, A_KM, B_KM, EPI, E>(p, s);

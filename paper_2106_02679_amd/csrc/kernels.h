@@ -83,4 +83,16 @@ template <class E>
 void launch_attn_bwd_mfma(const E *qkv, const E *out, const float *lse, const E *dout, E *dqkv, float *delta,
                           AttnShape sh, hipStream_t s);
 
+// The same attention for head sizes without a fused kernel, built from batched GEMMs and two row kernels
+// (attention_gemm.hip).  Needs s and dh to be multiples of 8 and a workspace of at least
+// attn_gemm_workspace_bytes(s, 1) bytes (256-byte aligned); more workspace, up to attn_gemm_workspace_bytes(s, heads),
+// lets more heads share a launch.
+size_t attn_gemm_workspace_bytes(int s, int heads);
+bool attn_gemm_supports(AttnShape sh, size_t ws_bytes);
+template <class E>
+void launch_attn_fwd_gemm(const E *qkv, E *out, float *lse, AttnShape sh, void *ws, size_t ws_bytes, hipStream_t s);
+template <class E>
+void launch_attn_bwd_gemm(const E *qkv, const E *out, const float *lse, const E *dout, E *dqkv, float *delta,
+                          AttnShape sh, void *ws, size_t ws_bytes, hipStream_t s);
+
 }  // namespace lga

@@ -226,6 +226,53 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
     return done("lga_op_attention_bwd");
 }
 
+uint64_t lga_op_attention_gemm_workspace_bytes(int32_t s_len, int32_t heads) {
+    if (s_len < 1 || heads < 1) return 0;
+    return attn_gemm_workspace_bytes(s_len, heads);
+}
+
+static int check_attention_gemm(int32_t dtype, int32_t n_seq, int32_t s_len, int32_t heads, int32_t dh, const void *ws,
+                                uint64_t ws_bytes) {
+    if (!dtype16(dtype)) return err(LGA_ERR_ARG, "dtype must be LGA_BF16 or LGA_FP16");
+    if (n_seq < 0 || s_len < 1 || heads < 1 || dh < 1) return err(LGA_ERR_SHAPE, "bad shape");
+    if (s_len % 8 || dh % 8 || s_len > 32768) return err(LGA_ERR_SHAPE, "GEMM-built attention needs s and d_h to be multiples of 8, s <= 32768");
+    if (3.0 * heads * dh > 2.0e9) return err(LGA_ERR_SHAPE, "sizes overflow the index range");
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < attn_gemm_workspace_bytes(s_len, 1))
+        return err(LGA_ERR_ARG, "workspace must be 256-byte aligned and hold at least one head (12 s^2 bytes)");
+    return LGA_OK;
+}
+
+int lga_op_attention_gemm_fwd(int32_t dtype, const void *qkv, void *out, float *lse, int32_t n_seq, int32_t s_len,
+                              int32_t heads, int32_t dh, int32_t causal, void *workspace, uint64_t workspace_bytes,
+                              void *stream) {
+    if (int rc = check_attention_gemm(dtype, n_seq, s_len, heads, dh, workspace, workspace_bytes)) return rc;
+    if (!qkv || !out || !lse) return err(LGA_ERR_ARG, "NULL argument");
+    if (!a16(qkv) || !a16(out)) return err(LGA_ERR_SHAPE, "GEMM-built attention needs 16-byte aligned tensors");
+    const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    with16(dtype, [&](auto tag) {
+        using E = decltype(tag);
+        launch_attn_fwd_gemm<E>(in16<E>(qkv), out16<E>(out), lse, sh, workspace, workspace_bytes, s);
+    });
+    return done("lga_op_attention_gemm_fwd");
+}
+
+int lga_op_attention_gemm_bwd(int32_t dtype, const void *qkv, const void *out, const float *lse, const void *dout,
+                              void *dqkv, float *delta, int32_t n_seq, int32_t s_len, int32_t heads, int32_t dh,
+                              int32_t causal, void *workspace, uint64_t workspace_bytes, void *stream) {
+    if (int rc = check_attention_gemm(dtype, n_seq, s_len, heads, dh, workspace, workspace_bytes)) return rc;
+    if (!qkv || !out || !lse || !dout || !dqkv || !delta) return err(LGA_ERR_ARG, "NULL argument");
+    if (!a16(qkv) || !a16(out) || !a16(dout) || !a16(dqkv)) return err(LGA_ERR_SHAPE, "GEMM-built attention needs 16-byte aligned tensors");
+    const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    with16(dtype, [&](auto tag) {
+        using E = decltype(tag);
+        launch_attn_bwd_gemm<E>(in16<E>(qkv), in16<E>(out), lse, in16<E>(dout), out16<E>(dqkv), delta, sh, workspace,
+                                workspace_bytes, s);
+    });
+    return done("lga_op_attention_gemm_bwd");
+}
+
 int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t w16_dtype, uint64_t n,
                 const lga_adam *adam, int32_t *nonfinite, void *stream) {
     if (!adam || (n > 0 && (!w || !m || !v || !g))) return err(LGA_ERR_ARG, "NULL argument");

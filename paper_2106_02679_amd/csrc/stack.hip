@@ -98,8 +98,9 @@ int validate_config(const lga_config *c) {
     if (c->dtype != LGA_FP32) {
         const int dh = c->d_model / c->n_heads;
         if (dh % 8 != 0) return fail(LGA_ERR_SHAPE, "the 16-bit modes need head size d_h to be a multiple of 8");
-        // head sizes without an MFMA attention kernel go through the one-wavefront kernels, like the fp32 mode
-        if (!attn_bf16_supports(dh) && (2.0 * c->seq_len + 2.0 * dh) * 4 > 60000)
+        // head sizes without a fused attention kernel run the GEMM-built attention if seq_len is a multiple of 8
+        // (at most 32768), else the one-wavefront kernels, like the fp32 mode
+        if (!attn_bf16_supports(dh) && (c->seq_len % 8 != 0 || c->seq_len > 32768) && (2.0 * c->seq_len + 2.0 * dh) * 4 > 60000)
             return fail(LGA_ERR_SHAPE, "seq_len too long for the one-wavefront attention kernel's LDS rows (head size "
                                        "without an MFMA attention kernel)");
         if (c->d_model % 8 != 0 || c->d_ff % 8 != 0)
@@ -124,6 +125,7 @@ struct Plan {
     size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
     size_t splitk, splitk_floats;   // partial results of weight-gradient GEMMs whose k range is split (narrow layers)
     size_t nonfinite;          // int per layer: the last checked Adam step found a non-finite gradient value
+    size_t attn_ws, attn_ws_bytes;  // workspace of the GEMM-built attention (head sizes without a fused kernel)
     size_t total;
 };
 
@@ -196,6 +198,14 @@ Plan make_plan(const lga_config &c) {
     const size_t widest = std::max<size_t>(3 * d, f);
     p.partial = take(colsum_partial_floats((int)t, (int)widest) * 4);
     p.nonfinite = take(L * 4);          // one flag per layer, see lga_adam.skip_nonfinite
+    // head sizes without a fused attention kernel: score matrices of as many heads of one sequence as fit 4 GiB
+    p.attn_ws_bytes = 0;
+    if (is16 && !attn_bf16_supports((int)(d / c.n_heads)) && c.seq_len % 8 == 0 && c.seq_len <= 32768) {
+        const size_t per_head = attn_gemm_workspace_bytes(c.seq_len, 1);
+        const size_t heads = std::min<size_t>(c.n_heads, std::max<size_t>(1, ((size_t)4 << 30) / per_head));
+        p.attn_ws_bytes = heads * per_head;
+    }
+    p.attn_ws = take(p.attn_ws_bytes);
     p.total = off;
     return p;
 }
@@ -418,6 +428,8 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     g.A = h; g.out = qkv; g.bias = pf + o.b_qkv;
     fwd_gemm(g, o.w_qkv, d, 3 * d, EPI_BIAS);
     if constexpr (std::is_same<T, float>::value) launch_attn_fwd_simple<float>(qkv, a, lse, ash, s);
+    else if (!attn_bf16_supports(ash.dh) && attn_gemm_supports(ash, st->plan.attn_ws_bytes))
+        launch_attn_fwd_gemm<T>(qkv, a, lse, ash, st->arena + st->plan.attn_ws, st->plan.attn_ws_bytes, s);
     else launch_attn_fwd_mfma<T>(qkv, a, lse, ash, s);
     g = GemmParams<T>{};
     g.A = a; g.out = x1; g.bias = pf + o.b_o; g.aux = x_in;
@@ -515,6 +527,8 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     wgrad(2, a, d, dx1, d, o.w_o, o.b_o);
     dgrad(dx1, d, o.w_o, d, da, EPI_STORE, nullptr);
     if constexpr (std::is_same<T, float>::value) launch_attn_bwd_simple<float>(qkv, a, lse, da, dqkv, delta, ash, s);
+    else if (!attn_bf16_supports(ash.dh) && attn_gemm_supports(ash, st->plan.attn_ws_bytes))
+        launch_attn_bwd_gemm<T>(qkv, a, lse, da, dqkv, delta, ash, st->arena + st->plan.attn_ws, st->plan.attn_ws_bytes, s);
     else launch_attn_bwd_mfma<T>(qkv, a, lse, da, dqkv, delta, ash, s);
     // qkv = h Wqkv + bqkv
     wgrad(3, h, d, dqkv, 3 * d, o.w_qkv, o.b_qkv);

@@ -47,7 +47,9 @@ def test_parameter_count_follows_table_b1_closed_form():
     (dict(n_layers=0), B.LGA_ERR_SHAPE), (dict(d_model=65), B.LGA_ERR_SHAPE), (dict(group=3), B.LGA_ERR_SHAPE),
     (dict(group=0), B.LGA_ERR_SHAPE), (dict(group=8), B.LGA_ERR_SHAPE), (dict(dtype=7), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=48, d_ff=192), B.LGA_ERR_SHAPE),    # d_h = 12 is not a multiple of 8
-    (dict(dtype=B.LGA_BF16, d_model=1024, d_ff=4096, seq_len=8192), B.LGA_ERR_SHAPE),   # d_h = 256 > 160: no MFMA attention kernel, sequence limit of the generic one
+    # d_h = 256 > 160 has no fused attention kernel, and 8196 is not a multiple of 8, which the GEMM-built attention
+    # needs: the one-wavefront kernels remain, whose LDS rows end below this length
+    (dict(dtype=B.LGA_BF16, d_model=1024, d_ff=4096, seq_len=8196), B.LGA_ERR_SHAPE),
     (dict(attention=2), B.LGA_ERR_ARG), (dict(offload_checkpoints=2), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=128, n_heads=4, d_ff=500), B.LGA_ERR_SHAPE),
     (dict(seq_len=0), B.LGA_ERR_SHAPE),
@@ -59,6 +61,23 @@ def test_bad_configurations_are_refused_on_the_host(kw, code):
     h = C.c_void_p()
     assert B.lib.lga_init_stack(C.byref(cfg(**kw)), None, C.byref(h)) == code
     assert not h.value
+
+
+def test_large_heads_get_a_workspace_for_the_gemm_built_attention():
+    # d_h = 256 (4 heads) against d_h = 128 (8 heads) at the same width: the arenas differ by the workspace - one
+    # sequence's score matrices, 12 s^2 bytes per head, for as many heads as fit 4 GiB - less the four extra heads'
+    # rows in the two softmax-statistics buffers (4 bytes per head, position and sequence of a group)
+    wide = dict(dtype=B.LGA_BF16, d_model=1024, d_ff=4096)
+    assert B.lib.lga_op_attention_gemm_workspace_bytes(1024, 4) == 12 * 1024 * 1024 * 4
+
+    def extra(heads_in_workspace, **kw):
+        c4, c8 = cfg(**wide, **kw), cfg(**wide, n_heads=8, **kw)
+        stats = 2 * 4 * (8 - 4) * c4.group * c4.micro_batch * c4.seq_len
+        return B.arena_bytes(c4) - B.arena_bytes(c8) + stats - 12 * c4.seq_len ** 2 * heads_in_workspace
+
+    assert 0 <= extra(4, seq_len=1024) < 4096
+    assert 0 <= extra(4, seq_len=8192) < 4096                                     # 3.2 GB: all four heads still fit
+    assert 0 <= extra(1, seq_len=16384, micro_batch=1, n_micro=1) < 4096          # 3.2 GB per head: one at a time
 
 
 def test_null_arguments():

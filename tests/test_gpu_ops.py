@@ -437,6 +437,57 @@ def test_attention_forward_ends_on_non_finite_scores(dt, bad):
     assert rel_err(got[:3, :dh], out_ref[:3, :dh]) < TOL_ATTN[dt][0]  # queries before the bad key (causal)
 
 
+GEMM_ATTN_CASES = [
+    # dtype, n_seq, s, heads, dh, causal, heads that fit the workspace
+    (BF16, 2, 200, 3, 216, True, 3), (BF16, 1, 328, 2, 320, False, 2), (BF16, 1, 264, 3, 168, True, 1),
+    (BF16, 1, 8, 1, 8, True, 1), (BF16, 1, 1024, 8, 176, True, 8), (BF16, 2, 136, 5, 64, False, 2),
+    (F16, 2, 200, 3, 216, True, 2), (F16, 1, 520, 2, 320, False, 2),
+]
+
+
+@pytest.mark.parametrize("case", GEMM_ATTN_CASES, ids=lambda c: "-".join(map(str, c)))
+def test_attention_built_from_batched_gemms(case):
+    """Head sizes beyond the fused kernels (216 and 320 are the X_108 and X_160 heads of table B.1): scores through a
+    workspace, batched GEMMs over the heads in all three operand layouts, row kernels for the softmax and for dS.
+    Workspaces that hold all heads, some (several passes, a ragged last one) or one; 1024 x 8 heads takes the
+    256 x 256-tile kernel for the score products, the others the 128 x 128 one."""
+    dt, n_seq, s, heads, dh, causal, fit = case
+    d = heads * dh
+    rng = np.random.default_rng(hash(case) % (2 ** 32))
+    qkv = rnd(rng, (n_seq * s, 3 * d), dt)
+    dout = rnd(rng, (n_seq * s, d), dt)
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh, causal)
+    qd, dod = to_dev(qkv, dt), to_dev(dout, dt)
+    out, dqkv = empty_dev((n_seq * s, d), dt), empty_dev((n_seq * s, 3 * d), dt)
+    lse = torch.empty(n_seq * heads * s, device="cuda")
+    delta = torch.empty(n_seq * heads * s, device="cuda")
+    nbytes = int(B.lib.lga_op_attention_gemm_workspace_bytes(s, fit))
+    assert nbytes == 12 * s * s * fit
+    ws = torch.full((nbytes // 4 + 64,), float("nan"), device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    B.check(B.lib.lga_op_attention_gemm_fwd(dt, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+                                            int(causal), base, nbytes, None))
+    B.check(B.lib.lga_op_attention_gemm_bwd(dt, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+                                            dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), base,
+                                            nbytes, None))
+    torch.cuda.synchronize()
+    tol_f, tol_b = TOL_ATTN[dt]
+    assert rel_err(to_host(out), out_ref) < tol_f
+    assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < 1e-3 * max(1.0, np.abs(lse_ref).max())
+    do64, o64 = dout.astype(np.float64).reshape(n_seq, s, heads, dh), out_ref.reshape(n_seq, s, heads, dh)
+    assert rel_err(delta.cpu().numpy().reshape(n_seq, heads, s), (do64 * o64).sum(-1).transpose(0, 2, 1)) < tol_f
+    got = to_host(dqkv)
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < tol_b, name
+    # refused on the host: sequence length or head size not a multiple of 8, workspace missing, unaligned or too small
+    for bad in (dict(s=s + 4), dict(dh=dh + 4), dict(ws=None), dict(ws=base + 16), dict(nbytes=12 * s * s - 1)):
+        a = dict(s=s, dh=dh, ws=base, nbytes=nbytes)
+        a.update(bad)
+        rc = B.lib.lga_op_attention_gemm_fwd(dt, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, a["s"], heads, a["dh"],
+                                             int(causal), a["ws"], a["nbytes"], None)
+        assert rc in (B.LGA_ERR_SHAPE, B.LGA_ERR_ARG), bad
+
+
 def test_attention_mfma_rejects_unsupported_head_size():
     t = torch.zeros(4096, device="cuda", dtype=torch.bfloat16)
     l = torch.zeros(64, device="cuda")

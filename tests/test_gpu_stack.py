@@ -103,19 +103,22 @@ def test_x_family_shapes_match_oracle(x_, layers, causal):
     print(f"X_{x_} ({layers} layers, causal={causal}) worst rel err {max(worst.values()):.3e}")
 
 
-@pytest.mark.parametrize("dh,causal", [(24, True), (152, True), (216, False)])
-def test_head_sizes_between_and_beyond_the_attention_kernels_own(dh, causal):
-    """bf16 mode with a head size outside {32, 64, 96, 128, 160}: up to 160 (T-NLG of table B.1 has d_h = 152) the
-    next larger MFMA kernel serves it with zero columns; beyond (X_108 has d_h = 216) the one-wavefront attention
-    kernels do; everything else is unchanged."""
-    heads = 2 if dh < 100 else 1
+@pytest.mark.parametrize("dh,heads,seq,causal,dtype", [(24, 2, 72, True, "bf16"), (152, 1, 72, True, "bf16"),
+                                                       (216, 1, 72, False, "bf16"), (216, 2, 76, True, "bf16"),
+                                                       (320, 2, 136, True, "bf16"), (176, 3, 264, False, "fp16")])
+def test_head_sizes_between_and_beyond_the_attention_kernels_own(dh, heads, seq, causal, dtype):
+    """16-bit modes with a head size outside {32, 64, 96, 128, 160}: up to 160 (T-NLG of table B.1 has d_h = 152) the
+    next larger fused kernel serves it with zero columns; beyond (X_108 has d_h = 216, X_160 has 320) the attention
+    built from batched GEMMs does when the sequence length is a multiple of 8, else (76) the one-wavefront kernels;
+    everything else is unchanged."""
     d = heads * dh
-    w = S.Workload(f"oddhead_dh{dh}", 1, d, heads, 4 * d, 72, 1, 2, "bf16")
+    w = S.Workload(f"oddhead_dh{dh}", 1 if heads == 1 else 2, d, heads, 4 * d, seq, 1 if seq % 8 == 0 else 2, 2, dtype)
     x, G, params = S.make_inputs(w, seed=37)
     adam = adam_struct()
     ref = O.step_microbatch_major(x, G, params, oracle_shape(w, causal=causal), oracle_adam(adam))
-    got = run_gpu_step(w, x, G, params, group=1, retain=1, adam=adam, attention=0 if causal else B.LGA_ATTN_FULL)
-    compare_with_oracle(w, got, ref, GATE["bf16"], adam)
+    got = run_gpu_step(w, x, G, params, group=2 if heads > 1 else 1, retain=1, adam=adam,
+                       attention=0 if causal else B.LGA_ATTN_FULL)
+    compare_with_oracle(w, got, ref, 2.5e-3 if dtype == "fp16" else GATE["bf16"], adam)
 
 
 def test_orders_and_group_sizes_agree_on_the_gpu():
