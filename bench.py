@@ -34,6 +34,10 @@ def parse():
     ap.add_argument("--x-family", type=int, default=0, metavar="X",
                     help="instead of --config: the paper's X_[x] model (table B.1), all x layers, micro-batches of one "
                          "sequence; --n-micro sets how many")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="with --x-family: run this many of the model's layers (0 = all x of them)")
+    ap.add_argument("--heads", type=int, default=0,
+                    help="override the configuration's number of heads (cfg4 with 80 heads is X_160's own 320-wide head)")
     ap.add_argument("--n-micro", type=int, default=0,
                     help="micro-batches per step: of the --x-family workload (default 32), or instead of the benchmark "
                          "configuration's own (for traffic-versus-n measurements; the workload name then says so)")
@@ -104,7 +108,10 @@ def main():
     import synth_inputs as S
     from paper_2106_02679_amd import binding as B
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = S.x_family(args.x_family, args.n_micro or 32) if args.x_family else S.CONFIGS[args.config]
+    w = S.x_family(args.x_family, args.n_micro or 32, n_layers=args.layers) if args.x_family else S.CONFIGS[args.config]
+    if args.heads and args.heads != w.n_heads:
+        w = S.Workload(f"{w.name}_h{args.heads}", w.n_layers, w.d_model, args.heads, w.d_ff, w.seq_len, w.micro_batch,
+                       w.n_micro, w.dtype)
     if args.n_micro and not args.x_family and args.n_micro != w.n_micro:
         w = S.Workload(f"{w.name}_n{args.n_micro}", w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch,
                        args.n_micro, w.dtype)

@@ -166,9 +166,12 @@ int lga_loss_scaler_update(lga_loss_scaler *scaler, int32_t overflowed);
  * (section 2.5: parameters are converted to 16 bits before use) and refreshed by each Adam step.
  * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in the 16-bit modes,
  * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes up to 160 have MFMA attention kernels in the 16-bit modes
- * (built for 32, 64, 96, 128, 160; sizes in between run in the next larger one); larger head sizes, and the fp32
- * mode, use a one-wavefront-per-position kernel that is meant for checking, not for speed, and limits seq_len
- * (2 seq_len + 2 d_h <= 15000).  LGA_ERR_OOM if the arena does not fit. */
+ * (built for 32, 64, 96, 128, 160; sizes in between run in the next larger one).  Larger head sizes (table B.1's
+ * X_[x] family has d_h = 2 x) run an attention built from batched GEMMs over the heads when seq_len is a multiple of 8
+ * (at most 32768); the arena then holds one sequence's score matrices, 12 seq_len^2 bytes per head for as many
+ * heads as fit 4 GiB.  Otherwise, and in the fp32 mode, a one-wavefront-per-position kernel is used that is meant
+ * for checking, not for speed, and limits seq_len (2 seq_len + 2 d_h <= 15000).  LGA_ERR_OOM if the arena does not
+ * fit. */
 int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **out);
 
 void lga_destroy_stack(lga_stack *stack);
