@@ -410,16 +410,16 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     float *lse = st->at<float>(st->plan.lse);
     const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads, c.attention == LGA_ATTN_CAUSAL};
 
-    // y[t, out] = x[t, in] W[in, out]: fp32 mode reads W as stored; bf16 mode reads the transposed copy
+    // y[t, out] = x[t, in] W[in, out]: fp32 mode reads W as stored; the 16-bit modes read the transposed copy
     // W^T[out, in], so both operands are k-contiguous.
-    constexpr bool kBf16 = !std::is_same<T, float>::value;
+    constexpr bool k16bit = !std::is_same<T, float>::value;
     const T *pwt = pw;
-    if constexpr (kBf16) pwt = st->w16t<T>(l);
+    if constexpr (k16bit) pwt = st->w16t<T>(l);
     auto fwd_gemm = [&](GemmParams<T> g, size_t w_off, int in, int out, Epilogue e) {
         g.M = t; g.N = out; g.K = in; g.lda = in; g.ldc = out;
         g.B = pwt + w_off;
-        g.ldb = kBf16 ? in : out;
-        gemm<T>(g, true, kBf16, e, s);
+        g.ldb = k16bit ? in : out;
+        gemm<T>(g, true, k16bit, e, s);
     };
 
     launch_layernorm_fwd<T>(x_in, pf + o.ln1_g, pf + o.ln1_b, h, st->at<float>(st->plan.mean1),
@@ -450,15 +450,15 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
 struct GradStep {
     float beta;       // vectors (biases, LayerNorm): 0 for the layer's first group, then 1
     float beta_mat;   // matrices: 0 for the first weight-gradient GEMM of the layer, then 1
-    int slot;         // bf16 mode: position of this group's tokens in the transposed operand buffers
-    bool flush;       // bf16 mode: run the matrix GEMMs now, over slots 0..slot
+    int slot;         // 16-bit modes: position of this group's tokens in the transposed operand buffers
+    bool flush;       // 16-bit modes: run the matrix GEMMs now, over slots 0..slot
 };
 
 // Backward of layer l on one group whose intermediates were just recomputed by layer_forward.
 // dy: [t, d] group slice of the running activation gradient, overwritten with dx.
 // gbuf: the layer's fp32 gradient buffer (canonical layout).
 //
-// bf16 mode merges the weight-gradient GEMMs of consecutive groups of a layer (possible because the
+// The 16-bit modes merge the weight-gradient GEMMs of consecutive groups of a layer (possible because the
 // layered order visits all micro-batches of a layer back to back): each group only appends its
 // transposed operands, and one GEMM then contracts over all their tokens.  The accumulation over
 // micro-batches that the fp32 buffer would do by read-modify-write happens inside the GEMM's
@@ -482,7 +482,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     float *partial = st->at<float>(st->plan.partial);
     const AttnShape ash{c.group * c.micro_batch, c.seq_len, c.n_heads, d / c.n_heads, c.attention == LGA_ATTN_CAUSAL};
 
-    // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over tokens.  bf16 mode first writes X^T [in][.]
+    // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over tokens.  The 16-bit modes first write X^T [in][.]
     // and dY^T [out][.] (two HBM-bound passes, ~1 % of the GEMM's time) so that the GEMM reads both
     // operands k-contiguous; `which` names the matrix's pair of transposed buffers.
     auto wgrad = [&](int which, const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off) {
@@ -828,7 +828,7 @@ int lga_traffic_model(const lga_config *cfg, int32_t order, uint64_t *param_byte
         *param_bytes = L * (24 * P + groups * per_group_param) + adam_copies * copies + restores * (4 * P + copies);
     // gradient buffer: the first pass over it writes (4 B), later ones read-modify-write (8 B); Adam reads
     // (4 B).  Vectors take one pass per group; matrices one per weight-gradient GEMM, which in the layered
-    // bf16 path covers wgrad_groups groups.
+    // 16-bit path covers wgrad_groups groups.
     uint64_t mat_passes = groups;
     if (order == LGA_ORDER_LAYERED && is16) {
         const uint64_t wb = make_plan(*cfg).wgrad_groups;
