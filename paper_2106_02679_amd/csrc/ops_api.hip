@@ -188,7 +188,7 @@ int lga_op_attention_fwd(int32_t dtype, int32_t kind, const void *qkv, void *out
     if (!qkv || !out || !lse) return err(LGA_ERR_ARG, "NULL argument");
     if (kind == 1 && (!dtype16(dtype) || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out)))
         return err(LGA_ERR_SHAPE, "MFMA attention needs a 16-bit dtype, 16-byte aligned tensors and d_h a multiple of 8 up to 160");
-    if ((size_t)(dh + s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
+    if (kind == 0 && (size_t)(dh + s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
     const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (dtype == LGA_FP32)
@@ -211,7 +211,7 @@ int lga_op_attention_bwd(int32_t dtype, int32_t kind, const void *qkv, const voi
     if (!qkv || !out || !lse || !dout || !dqkv || !delta) return err(LGA_ERR_ARG, "NULL argument");
     if (kind == 1 && (!dtype16(dtype) || !attn_bf16_supports(dh) || !a16(qkv) || !a16(out) || !a16(dout) || !a16(dqkv)))
         return err(LGA_ERR_SHAPE, "MFMA attention needs a 16-bit dtype, 16-byte aligned tensors and d_h a multiple of 8 up to 160");
-    if ((size_t)(2 * dh + 2 * s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
+    if (kind == 0 && (size_t)(2 * dh + 2 * s_len) * 4 > 60000) return err(LGA_ERR_SHAPE, "sequence too long for the one-wavefront kernel");
     const AttnShape sh{n_seq, s_len, heads, dh, causal != 0};
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (dtype == LGA_FP32)

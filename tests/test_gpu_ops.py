@@ -437,6 +437,43 @@ def test_attention_forward_ends_on_non_finite_scores(dt, bad):
     assert rel_err(got[:3, :dh], out_ref[:3, :dh]) < TOL_ATTN[dt][0]  # queries before the bad key (causal)
 
 
+@pytest.mark.parametrize("kind,dt,s,heads,dh,causal", [("fused", BF16, 16384, 1, 128, True), ("fused", BF16, 6000, 2, 64, False),
+                                                       ("gemm", BF16, 4096, 2, 216, True), ("fused", F16, 8192, 1, 160, True)])
+def test_attention_on_long_sequences(kind, dt, s, heads, dh, causal):
+    """Sequences up to eight times the benchmark's 2048: dozens of query blocks per (sequence, head), hundreds of key
+    tiles per block, the longest rows of the softmax sums."""
+    n_seq, d = 1, heads * dh
+    rng = np.random.default_rng(s + dh)
+    qkv = rnd(rng, (n_seq * s, 3 * d), dt)
+    dout = rnd(rng, (n_seq * s, d), dt)
+    out_ref, lse_ref, dqkv_ref = attention_reference(qkv, dout, n_seq, s, heads, dh, causal)
+    qd, dod = to_dev(qkv, dt), to_dev(dout, dt)
+    out, dqkv = empty_dev((n_seq * s, d), dt), empty_dev((n_seq * s, 3 * d), dt)
+    lse = torch.empty(n_seq * heads * s, device="cuda")
+    delta = torch.empty(n_seq * heads * s, device="cuda")
+    if kind == "fused":
+        B.check(B.lib.lga_op_attention_fwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+                                           int(causal), None))
+        B.check(B.lib.lga_op_attention_bwd(dt, 1, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+                                           dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), None))
+    else:
+        nbytes = int(B.lib.lga_op_attention_gemm_workspace_bytes(s, heads))
+        ws = torch.empty(nbytes // 4 + 64, device="cuda")
+        base = (ws.data_ptr() + 255) // 256 * 256
+        B.check(B.lib.lga_op_attention_gemm_fwd(dt, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), n_seq, s, heads, dh,
+                                                int(causal), base, nbytes, None))
+        B.check(B.lib.lga_op_attention_gemm_bwd(dt, qd.data_ptr(), out.data_ptr(), lse.data_ptr(), dod.data_ptr(),
+                                                dqkv.data_ptr(), delta.data_ptr(), n_seq, s, heads, dh, int(causal), base,
+                                                nbytes, None))
+    torch.cuda.synchronize()
+    tol_f, tol_b = TOL_ATTN[dt]
+    assert rel_err(to_host(out), out_ref) < tol_f
+    assert np.abs(lse.cpu().numpy().reshape(n_seq, heads, s) - lse_ref).max() < 1e-3 * max(1.0, np.abs(lse_ref).max())
+    got = to_host(dqkv)
+    for name, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert rel_err(got[:, sl], dqkv_ref[:, sl]) < tol_b, name
+
+
 GEMM_ATTN_CASES = [
     # dtype, n_seq, s, heads, dh, causal, heads that fit the workspace
     (BF16, 2, 200, 3, 216, True, 3), (BF16, 1, 328, 2, 320, False, 2), (BF16, 1, 264, 3, 168, True, 1),
