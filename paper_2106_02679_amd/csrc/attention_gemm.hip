@@ -11,7 +11,9 @@
 //              dV = P^T dO ; dQ = dS K ; dK = dS^T Q                                                        batched GEMMs
 //
 // Heads are operands of one launch (GemmParams::batch), sequences are looped over on the host.  With the causal
-// mask the full s x s products are computed and the masked half of P and dS is written as zeros.  The workspace holds
+// mask the row kernels write the masked half of P and dS as zeros and never read the masked half of S and dP, so the
+// products leave out what that makes superfluous (GemmParams::tri): score tiles above the diagonal, and the part of
+// every contraction over positions that meets only zeros.  The workspace holds
 // S, dP (fp32) and P, dS (16 bits) of as many heads as fit: 12 s^2 bytes per head.
 #include <algorithm>
 #include <type_traits>
@@ -180,6 +182,7 @@ void launch_attn_fwd_gemm(const E *qkv, E *out, float *lse, AttnShape sh, void *
             g.A = seq + (size_t)h0 * dh; g.lda = 3 * d; g.strideA = dh;
             g.B = seq + d + (size_t)h0 * dh; g.ldb = 3 * d; g.strideB = dh;
             g.outf = w.S; g.ldc = s; g.strideC = (long long)s * s;
+            g.tri = sh.causal ? 1 : 0;
             launch_gemm_mfma<E>(g, true, true, EPI_ACCUM_F32, st);
             {
                 const long long rows = (long long)hc * s;
@@ -193,6 +196,7 @@ void launch_attn_fwd_gemm(const E *qkv, E *out, float *lse, AttnShape sh, void *
             g.A = w.P; g.lda = s; g.strideA = (long long)s * s;
             g.B = seq + 2 * d + (size_t)h0 * dh; g.ldb = 3 * d; g.strideB = dh;
             g.out = out + (size_t)b * s * d + (size_t)h0 * dh; g.ldc = d; g.strideC = dh;
+            g.tri = sh.causal ? 2 : 0;                     // keys up to the query
             launch_gemm_mfma<E>(g, true, false, EPI_STORE, st);
         }
     }
@@ -218,11 +222,13 @@ void launch_attn_bwd_gemm(const E *qkv, const E *out, const float *lse, const E 
             g.A = q; g.lda = 3 * d; g.strideA = dh;
             g.B = k; g.ldb = 3 * d; g.strideB = dh;
             g.outf = w.S; g.ldc = s; g.strideC = ss;
+            g.tri = sh.causal ? 1 : 0;
             launch_gemm_mfma<E>(g, true, true, EPI_ACCUM_F32, st);
             g = batched<E>(hc, s, s, dh);
             g.A = dO; g.lda = d; g.strideA = dh;
             g.B = v; g.ldb = 3 * d; g.strideB = dh;
             g.outf = w.dP; g.ldc = s; g.strideC = ss;
+            g.tri = sh.causal ? 1 : 0;
             launch_gemm_mfma<E>(g, true, true, EPI_ACCUM_F32, st);
             {
                 const long long rows = (long long)hc * s;
@@ -237,18 +243,21 @@ void launch_attn_bwd_gemm(const E *qkv, const E *out, const float *lse, const E 
             g.A = w.P; g.lda = s; g.strideA = ss;
             g.B = dO; g.ldb = d; g.strideB = dh;
             g.out = dseq + 2 * d + (size_t)h0 * dh; g.ldc = 3 * d; g.strideC = dh;
+            g.tri = sh.causal ? 3 : 0;                     // queries from the key on
             launch_gemm_mfma<E>(g, false, false, EPI_STORE, st);
             // dQ_h = dS_h K_h
             g = batched<E>(hc, s, dh, s);
             g.A = w.dS; g.lda = s; g.strideA = ss;
             g.B = k; g.ldb = 3 * d; g.strideB = dh;
             g.out = dseq + (size_t)h0 * dh; g.ldc = 3 * d; g.strideC = dh;
+            g.tri = sh.causal ? 2 : 0;
             launch_gemm_mfma<E>(g, true, false, EPI_STORE, st);
             // dK_h = dS_h^T Q_h
             g = batched<E>(hc, s, dh, s);
             g.A = w.dS; g.lda = s; g.strideA = ss;
             g.B = q; g.ldb = 3 * d; g.strideB = dh;
             g.out = dseq + d + (size_t)h0 * dh; g.ldc = 3 * d; g.strideC = dh;
+            g.tri = sh.causal ? 3 : 0;
             launch_gemm_mfma<E>(g, false, false, EPI_STORE, st);
         }
     }

@@ -117,6 +117,11 @@ template <class T> struct GemmParams {
     // B + z strideB and writes every output (and reads aux) at + z strideC (elements).  Not combined with a split k range.
     int batch;
     long long strideA, strideB, strideC;
+    // Products with a causal mask (M = N = positions, or K = positions): what a tile may leave out because its
+    // operand or its consumer is zero there.  0: nothing.  1: tiles entirely above the diagonal (n > every m of the
+    // tile) are not computed and not written.  2: the contraction index stops at the tile's last row (k <= m).
+    // 3: it starts at the tile's first row (k >= m), rounded down to a whole k tile.
+    int tri;
 };
 
 }  // namespace lga

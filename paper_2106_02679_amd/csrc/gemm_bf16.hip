@@ -269,6 +269,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int til
     const int tm = first_m + (tile % group_size) % gsz;
     const int tn = (tile % group_size) / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
+    if (p.tri == 1 && n0 >= m0 + BM) return;             // whole workgroup: the tile lies above the diagonal
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -291,6 +292,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int til
     const E *b_ptr = B_KM ? p.B + (size_t)n0 * p.ldb : p.B + n0;
     const size_t a_step = A_KM ? (size_t)BK : (size_t)BK * p.lda;
     const size_t b_step = B_KM ? (size_t)BK : (size_t)BK * p.ldb;
+    if (p.tri == 2) p.K = min(p.K, m0 + BM);
+    if (p.tri == 3) {
+        const int skip = min(m0, p.K) / BK;              // whole k tiles before the tile's first row
+        a_ptr += skip * a_step;
+        b_ptr += skip * b_step;
+        p.K -= skip * BK;
+    }
     const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
     auto load_tile = [&](int t) {
         if (t < nk_full) {
@@ -510,6 +518,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     const int tm = first_m + (tile % group_size) % gsz;
     const int tn = (tile % group_size) / gsz;
     const int m0 = tm * BM, n0 = tn * BN;
+    if (p.tri == 1 && n0 >= m0 + BM) return;             // whole workgroup: the tile lies above the diagonal
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
