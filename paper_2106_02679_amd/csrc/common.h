@@ -122,6 +122,9 @@ template <class T> struct GemmParams {
     // tile) are not computed and not written.  2: the contraction index stops at the tile's last row (k <= m).
     // 3: it starts at the tile's first row (k >= m), rounded down to a whole k tile.
     int tri;
+    // set by the launcher for the 256 x 256-tile kernel when the tile grid is a whole number of 16 x 16 blocks: the 256
+    // workgroups in flight - 32 per XCD - work on one such block together, each XCD on an 8 x 4 part of it
+    int sblock;
 };
 
 }  // namespace lga

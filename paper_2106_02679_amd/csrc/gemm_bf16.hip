@@ -22,7 +22,8 @@
 // Common to both: the MFMA is issued with the B tile as its first operand so that each lane ends up with
 // 4 consecutive n of one row m (row-major stores of 8 bytes (bf16) or 16 bytes (fp32) per lane, epilogues
 // fused); workgroup ids are remapped so that each XCD (ids are dealt round-robin over the 8 XCDs) works on
-// a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse.
+// a contiguous range of tiles, walked in groups of 8 tile-rows for L2 reuse - or, in the direct-to-LDS kernel on
+// tile grids made of whole 16 x 16 blocks, so that all XCDs work on one such block at a time.
 #include <algorithm>
 #include <cstdio>
 #include <type_traits>
@@ -515,8 +516,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     const int gid = tile / group_size;
     const int first_m = gid * GROUP_M;
     const int gsz = min(tiles_m - first_m, GROUP_M);
-    const int tm = first_m + (tile % group_size) % gsz;
-    const int tn = (tile % group_size) / gsz;
+    int tm = first_m + (tile % group_size) % gsz;
+    int tn = (tile % group_size) / gsz;
+    if (p.sblock) {
+        // Round r of 256 consecutive workgroup ids is one 16 x 16 block of tiles (blocks walk along n first); XCD
+        // x = id mod 8 takes rows 8 (x / 4) .. + 7 and columns 4 (x mod 4) .. + 3 of it.  All 8 XCDs then read the
+        // same 16 + 16 operand panels at about the same time, so memory sees each of them once per k step instead of
+        // once per XCD or per pass over the other dimension; inside an XCD the footprint is the same 8 x 4 tiles.
+        const int pid = blockIdx.x, r = pid >> 8, x = pid & 7, local = (pid >> 3) & 31;
+        const int nsn = tiles_n >> 4;
+        tm = ((r / nsn) << 4) + ((x >> 2) << 3) + (local & 7);
+        tn = ((r % nsn) << 4) + ((x & 3) << 2) + (local >> 3);
+    }
     const int m0 = tm * BM, n0 = tn * BN;
     if (p.tri == 1 && n0 >= m0 + BM) return;             // whole workgroup: the tile lies above the diagonal
 
@@ -797,10 +808,20 @@ template <bool A_KM, bool B_KM, int EPI, class E> void launch_tiles(const GemmPa
             launch_one<128, 128, A_KM, B_KM, EPI, E>(p, s);
         return;
     }
-    if (big >= 128)
+    if (big >= 128) {
+        if constexpr (A_KM && B_KM) {
+            const int tm = (p.M + 255) / 256, tn = (p.N + 255) / 256;
+            if (tm % 16 == 0 && tn % 16 == 0) {                  // + 1 % on the weight-gradient shapes of d = 12288
+                GemmParams<E> q = p;
+                q.sblock = 1;
+                launch_one<256, 256, A_KM, B_KM, EPI, E>(q, s);
+                return;
+            }
+        }
         launch_one<256, 256, A_KM, B_KM, EPI, E>(p, s);
-    else
+    } else {
         launch_one<128, 128, A_KM, B_KM, EPI, E>(p, s);
+    }
 }
 
 }  // namespace

@@ -79,6 +79,9 @@ GEMM_CASES = [
     (BF16, 1, 1, B.LGA_EPI_MUL_DGELU, 4100, 8200, 72),
     (BF16, 1, 1, B.LGA_EPI_BIAS_RESID, 4100, 8200, 72),
     (BF16, 1, 1, B.LGA_EPI_BIAS, 2050, 16392, 200),
+    # tile grids that are whole 16 x 16 blocks of 256 x 256 tiles: the block-wise workgroup order
+    (BF16, 1, 1, B.LGA_EPI_STORE, 4096, 4096, 72), (BF16, 1, 1, B.LGA_EPI_ACCUM_F32, 4096, 8192, 200),
+    (BF16, 1, 1, B.LGA_EPI_BIAS_GELU, 8192, 4096, 136),
 ]
 
 
