@@ -191,8 +191,10 @@ __device__ __forceinline__ void epilogue4(const GemmParams<E> &p, int m, int n, 
 
 // The same for 8 consecutive n of one row, with 16-byte accesses (bf16 outputs only): n, ldc multiples of 8 and
 // 16-byte aligned tensors.
+// aux8: the 8 values of aux at (m, n .. n + 7) for the two epilogues that read it, loaded by the caller (ahead of time).
 template <int EPI, class E>
-__device__ __forceinline__ void epilogue8(const GemmParams<E> &p, int m, int n, const f32x4 &lo, const f32x4 &hi) {
+__device__ __forceinline__ void epilogue8(const GemmParams<E> &p, int m, int n, const f32x4 &lo, const f32x4 &hi,
+                                          const x8<E> &aux8) {
     static_assert(EPI != EPI_ACCUM_F32, "16-bit outputs only");
     const size_t idx = (size_t)m * p.ldc + n;
     float r[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -205,14 +207,12 @@ __device__ __forceinline__ void epilogue8(const GemmParams<E> &p, int m, int n, 
         }
     }
     if constexpr (EPI == EPI_BIAS_RESID) {
-        const x8<E> x = *reinterpret_cast<const x8<E> *>(p.aux + idx);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] += (float)x[i];
+        for (int i = 0; i < 8; ++i) r[i] += (float)aux8[i];
     }
     if constexpr (EPI == EPI_MUL_DGELU) {
-        const x8<E> u = *reinterpret_cast<const x8<E> *>(p.aux + idx);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) r[i] *= gelu_grad_f((float)u[i]);
+        for (int i = 0; i < 8; ++i) r[i] *= gelu_grad_f((float)aux8[i]);
     }
     if constexpr (EPI == EPI_BIAS_GELU) {
         x8<E> u;
@@ -695,6 +695,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         if (wide) {
             constexpr int SP = WN + 4;                                  // staging pitch in floats
             static_assert(4 * 32 * SP * 4 <= 5 * BM * BK * 2, "staging fits in the operand ring");
+            // The residual / pre-activation values of the whole wavefront tile are requested first - FM x 8 loads of
+            // 16 bytes per lane, into registers the main loop no longer needs - so that their latency is paid once,
+            // under the staging of the first strip, and not once per strip.
+            constexpr bool kReadsAux = EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU;
+            x8<E> aux8[kReadsAux ? FM : 1][kReadsAux ? 8 : 1];
+            if constexpr (kReadsAux) {
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int it = 0; it < 8; ++it) {
+                        const int m = m0 + wm * WM + i * 32 + it * 4 + (lane >> 4), n = n0 + wn * WN + 8 * (lane & 15);
+                        if (m < p.M && n < p.N) aux8[i][it] = *reinterpret_cast<const x8<E> *>(p.aux + (size_t)m * p.ldc + n);
+                    }
+            }
             __syncthreads();                                            // every wavefront has left the main loop
             float *stage = reinterpret_cast<float *>(smem_raw) + wave * (32 * SP);
 #pragma unroll
@@ -713,7 +727,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
                     const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + 8 * c8;
                     const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8);
                     const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8 + 4);
-                    if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi);
+                    if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi, aux8[kReadsAux ? i : 0][kReadsAux ? it : 0]);
                 }
                 asm volatile("" ::: "memory");
             }
