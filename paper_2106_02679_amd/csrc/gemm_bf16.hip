@@ -26,6 +26,7 @@
 // tile grids made of whole 16 x 16 blocks, so that all XCDs work on one such block at a time.
 #include <algorithm>
 #include <cstdio>
+#include <cstring>
 #include <type_traits>
 
 #include "kernels.h"
@@ -765,6 +766,10 @@ void launch_one(const GemmParams<E> &p, hipStream_t s) {
     else
         snprintf(name, sizeof(name), "gemm_%s_kernel<%d, %d, %s, %s, %d>", et, BM, BN, A_KM ? "true" : "false",
                  B_KM ? "true" : "false", EPI);
+    if (p.batch > 1) {                                       // the products of attention: listed apart from the layer's own
+        const size_t len = strlen(name);
+        snprintf(name + len, sizeof(name) - len, " (batched)");
+    }
     const double mn = (double)p.M * p.N;
     const double out_bytes = EPI == EPI_ACCUM_F32 ? (p.beta != 0.f ? 8.0 : 4.0) : (EPI == EPI_BIAS_GELU ? 4.0 : 2.0);
     const double aux_bytes = (EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU) ? 2.0 : 0.0;
