@@ -119,7 +119,8 @@ int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t
  * operands re-read from LDS as a 256 x 256 GEMM tile of 2 x 2 wavefronts must (eight 16-byte reads per 16 MFMAs);
  * 3: as 2, plus the direct-to-LDS loads that fill such a tile (64 KB per 64 MFMAs of each wavefront, from a 4 MB
  * window that stays in L2); 4: as 3, plus a workgroup barrier per k tile; 5: as 0 in IEEE half (v_mfma_f32_32x32x16_f16,
- * sign and all 10 mantissa bits random).
+ * sign and all 10 mantissa bits random); 6: as 0 plus the direct-to-LDS loads of 3 (nothing reads LDS); 7: as 0 plus the
+ * same bytes loaded into registers instead.
  * sink: device, >= 65536 floats + 4 MB (1 114 112 floats): the first 65536 are overwritten, modes 3 and 4 read the
  * rest (any finite contents).  Synchronous: returns after the kernel has run.  tflops: host. */
 int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream);

@@ -20,7 +20,10 @@ constexpr int kLdsChunks = 8192;        // 128 KB of operand data in LDS (mode 2
 
 // mode 0: random register operands; 1: constant register operands; 2: random operands re-read from LDS;
 // 3: as 2, plus direct-to-LDS loads at a GEMM tile's rate; 4: as 3, plus a barrier per k tile;
-// 5: random register operands in IEEE half, the f16 instruction
+// 5: random register operands in IEEE half, the f16 instruction;
+// 6: register operands (as 0) plus the direct-to-LDS loads of 3, nothing reads LDS; 7: register operands plus the same
+// bytes loaded into registers instead of LDS (taken apart: what of mode 3's loss is the way from L2 to the CU, what
+// is LDS)
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 constexpr int kDmaWindow = 4 << 20;       // bytes of source data the loads of modes 3 and 4 walk over (L2-resident)
 
@@ -77,6 +80,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
         off += 2048;
     };
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    u32x4 junk[4] = {};
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned *>(src), 0, kDmaWindow, 0x00020000);
     unsigned goff = (blockIdx.x * 65536u + wave * 16384u) & (kDmaWindow - 1);
     for (int it = 0; it < iters; it += 4) {
@@ -84,7 +88,13 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
         // runs; in modes >= 3 each wavefront also issues its 16 KB share of the tile's 64 KB of direct-to-LDS loads
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if constexpr (MODE == 3 || MODE == 4) {
+            if constexpr (MODE == 7) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    junk[j] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rs, (int)((goff + (q * 4 + j) * 1024 + lane * 16) & (kDmaWindow - 1)), 0, 0);
+            }
+            if constexpr (MODE == 3 || MODE == 4 || MODE == 6) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -109,7 +119,11 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
                 }
         }
         goff = (goff + 65536u * 7u) & (kDmaWindow - 1);
-        if constexpr (MODE == 3 || MODE == 4) __builtin_amdgcn_s_waitcnt(0x0070 | 15);     // at most one tile's loads in flight
+        if constexpr (MODE == 3 || MODE == 4 || MODE == 6) __builtin_amdgcn_s_waitcnt(0x0070 | 15);
+        if constexpr (MODE == 7) {                          // keep the loaded values alive without touching the MFMAs
+#pragma unroll
+            for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(junk[j]));
+        }     // at most one tile's loads in flight
         if constexpr (MODE == 4) {
             asm volatile("" ::: "memory");
             __builtin_amdgcn_s_barrier();
@@ -129,7 +143,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
 
 extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 5 || !sink || !tflops) return LGA_ERR_ARG;
+    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 7 || !sink || !tflops) return LGA_ERR_ARG;
     iters &= ~3;                                            // the loop does four groups of 16 MFMAs per turn
     // results go to the first 65536 floats of sink; modes 3 and 4 read the kDmaWindow bytes after them
     const unsigned *src = reinterpret_cast<const unsigned *>(sink + 65536);
@@ -151,6 +165,7 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<2>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<6>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
         attr_set = true;
     }
     switch (mode) {
@@ -159,7 +174,9 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         case 2: hipLaunchKernelGGL(mfma_rate_kernel<2>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
         case 3: hipLaunchKernelGGL(mfma_rate_kernel<3>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
         case 4: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
-        default: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 5: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 6: hipLaunchKernelGGL(mfma_rate_kernel<6>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
+        default: hipLaunchKernelGGL(mfma_rate_kernel<7>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
     }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);
