@@ -23,7 +23,9 @@ constexpr int kLdsChunks = 8192;        // 128 KB of operand data in LDS (mode 2
 // 5: random register operands in IEEE half, the f16 instruction;
 // 6: register operands (as 0) plus the direct-to-LDS loads of 3, nothing reads LDS; 7: register operands plus the same
 // bytes loaded into registers instead of LDS (taken apart: what of mode 3's loss is the way from L2 to the CU, what
-// is LDS)
+// is LDS); 8: register operands plus the same bytes loaded into registers and written to LDS with ds_write_b128 three
+// MFMA groups later (the classic staging, against 6); 9: as 0 with v_mfma_f32_16x16x32_bf16 (twice as many instructions
+// for the same flops, half the operand reuse per instruction)
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 constexpr int kDmaWindow = 4 << 20;       // bytes of source data the loads of modes 3 and 4 walk over (L2-resident)
 
@@ -81,6 +83,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
     };
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     u32x4 junk[4] = {};
+    u32x4 stage[4][4] = {};          // mode 8: four sets of four 16-byte loads in flight
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned *>(src), 0, kDmaWindow, 0x00020000);
     unsigned goff = (blockIdx.x * 65536u + wave * 16384u) & (kDmaWindow - 1);
     for (int it = 0; it < iters; it += 4) {
@@ -88,6 +91,18 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
         // runs; in modes >= 3 each wavefront also issues its 16 KB share of the tile's 64 KB of direct-to-LDS loads
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+            if constexpr (MODE == 8) {
+                // write the set that was requested three groups ago (its loads are the oldest 4 of the 16 in flight), then
+                // request into it again
+                __builtin_amdgcn_s_waitcnt(0x0070 | 12);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<u32x4 *>(smem + kLdsChunks * 8 + wave * 16384 + (q * 4 + j) * 1024 + lane * 16) = stage[q][j];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    stage[q][j] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rs, (int)((goff + (q * 4 + j) * 1024 + lane * 16) & (kDmaWindow - 1)), 0, 0);
+            }
             if constexpr (MODE == 7) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
@@ -111,7 +126,11 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
                 for (int j = 0; j < 4; ++j) {
                     constexpr bool second = MODE >= 2 && MODE <= 4;       // operand sets alternate when they come from LDS
                     const bf16x8 fa = (second && (q & 1)) ? a2[i] : a[i], fb = (second && (q & 1)) ? b2[j] : b[j];
-                    if constexpr (MODE == 5)
+                    if constexpr (MODE == 9) {
+                        f32x4 *a16 = reinterpret_cast<f32x4 *>(&acc[i * 4 + j]);
+                        a16[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fb, a16[0], 0, 0, 0);
+                        a16[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb, fa, a16[1], 0, 0, 0);
+                    } else if constexpr (MODE == 5)
                         acc[i * 4 + j] = mfma_32x32x16<f16>(__builtin_bit_cast(x8<f16>, fa), __builtin_bit_cast(x8<f16>, fb),
                                                             acc[i * 4 + j]);
                     else
@@ -143,7 +162,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
 
 extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 7 || !sink || !tflops) return LGA_ERR_ARG;
+    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 9 || !sink || !tflops) return LGA_ERR_ARG;
     iters &= ~3;                                            // the loop does four groups of 16 MFMAs per turn
     // results go to the first 65536 floats of sink; modes 3 and 4 read the kDmaWindow bytes after them
     const unsigned *src = reinterpret_cast<const unsigned *>(sink + 65536);
@@ -166,6 +185,7 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<6>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_rate_kernel<8>), hipFuncAttributeMaxDynamicSharedMemorySize, kSmem);
         attr_set = true;
     }
     switch (mode) {
@@ -176,7 +196,9 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         case 4: hipLaunchKernelGGL(mfma_rate_kernel<4>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
         case 5: hipLaunchKernelGGL(mfma_rate_kernel<5>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
         case 6: hipLaunchKernelGGL(mfma_rate_kernel<6>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
-        default: hipLaunchKernelGGL(mfma_rate_kernel<7>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 7: hipLaunchKernelGGL(mfma_rate_kernel<7>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 8: hipLaunchKernelGGL(mfma_rate_kernel<8>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
+        default: hipLaunchKernelGGL(mfma_rate_kernel<9>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
     }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);
