@@ -25,7 +25,8 @@ constexpr int kLdsChunks = 8192;        // 128 KB of operand data in LDS (mode 2
 // bytes loaded into registers instead of LDS (taken apart: what of mode 3's loss is the way from L2 to the CU, what
 // is LDS); 8: register operands plus the same bytes loaded into registers and written to LDS with ds_write_b128 three
 // MFMA groups later (the classic staging, against 6); 9: as 0 with v_mfma_f32_16x16x32_bf16 (twice as many instructions
-// for the same flops, half the operand reuse per instruction)
+// for the same flops, half the operand reuse per instruction); 10: as 7 with twice the bytes (128 KB per k tile and CU:
+// what a kernel would move if every wavefront fetched its own operands into registers, with no LDS and no barrier)
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 constexpr int kDmaWindow = 4 << 20;       // bytes of source data the loads of modes 3 and 4 walk over (L2-resident)
 
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
         off += 2048;
     };
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    u32x4 junk[4] = {};
+    u32x4 junk[4] = {}, junk2[4] = {};
     u32x4 stage[4][4] = {};          // mode 8: four sets of four 16-byte loads in flight
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned *>(src), 0, kDmaWindow, 0x00020000);
     unsigned goff = (blockIdx.x * 65536u + wave * 16384u) & (kDmaWindow - 1);
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
             if constexpr (MODE == 8) {
                 // write the set that was requested three groups ago (its loads are the oldest 4 of the 16 in flight), then
                 // request into it again
-                __builtin_amdgcn_s_waitcnt(0x0070 | 12);
+                __builtin_amdgcn_s_waitcnt(0x0F70 | 12);        // vmcnt only
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     *reinterpret_cast<u32x4 *>(smem + kLdsChunks * 8 + wave * 16384 + (q * 4 + j) * 1024 + lane * 16) = stage[q][j];
@@ -103,7 +104,13 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
                     stage[q][j] = __builtin_amdgcn_raw_buffer_load_b128(
                         rs, (int)((goff + (q * 4 + j) * 1024 + lane * 16) & (kDmaWindow - 1)), 0, 0);
             }
-            if constexpr (MODE == 7) {
+            if constexpr (MODE == 10) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    junk2[j] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rs, (int)((goff + 32768u + (q * 4 + j) * 1024 + lane * 16) & (kDmaWindow - 1)), 0, 0);
+            }
+            if constexpr (MODE == 7 || MODE == 10) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     junk[j] = __builtin_amdgcn_raw_buffer_load_b128(
@@ -139,9 +146,13 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
         }
         goff = (goff + 65536u * 7u) & (kDmaWindow - 1);
         if constexpr (MODE == 3 || MODE == 4 || MODE == 6) __builtin_amdgcn_s_waitcnt(0x0070 | 15);
-        if constexpr (MODE == 7) {                          // keep the loaded values alive without touching the MFMAs
+        if constexpr (MODE == 7 || MODE == 10) {            // keep the loaded values alive without touching the MFMAs
 #pragma unroll
             for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(junk[j]));
+        }
+        if constexpr (MODE == 10) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(junk2[j]));
         }     // at most one tile's loads in flight
         if constexpr (MODE == 4) {
             asm volatile("" ::: "memory");
@@ -162,7 +173,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
 
 extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 9 || !sink || !tflops) return LGA_ERR_ARG;
+    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 10 || !sink || !tflops) return LGA_ERR_ARG;
     iters &= ~3;                                            // the loop does four groups of 16 MFMAs per turn
     // results go to the first 65536 floats of sink; modes 3 and 4 read the kDmaWindow bytes after them
     const unsigned *src = reinterpret_cast<const unsigned *>(sink + 65536);
@@ -198,7 +209,8 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         case 6: hipLaunchKernelGGL(mfma_rate_kernel<6>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
         case 7: hipLaunchKernelGGL(mfma_rate_kernel<7>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
         case 8: hipLaunchKernelGGL(mfma_rate_kernel<8>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
-        default: hipLaunchKernelGGL(mfma_rate_kernel<9>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 9: hipLaunchKernelGGL(mfma_rate_kernel<9>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        default: hipLaunchKernelGGL(mfma_rate_kernel<10>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
     }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);

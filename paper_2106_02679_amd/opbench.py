@@ -120,8 +120,9 @@ def run_mfma(args):
     what = {1: "constant register operands", 0: "random register operands  ", 2: "random operands via LDS   ",
             3: "... + direct-to-LDS loads ", 4: "... + a barrier per k tile", 5: "random registers, IEEE half",
             6: "registers + direct-to-LDS loads", 7: "registers + loads to registers",
-            8: "registers + loads to registers + ds_write", 9: "random registers, 16x16x32 instruction"}
-    for mode in (1, 0, 5, 9, 2, 3, 4, 6, 7, 8):
+            8: "registers + loads to registers + ds_write", 9: "random registers, 16x16x32 instruction",
+            10: "registers + twice the loads to registers"}
+    for mode in (1, 0, 5, 9, 2, 3, 4, 6, 7, 10, 8):
         for iters in (400000, 4000000):
             tf = C.c_double()
             B.check(B.lib.lga_op_mfma_rate(iters, mode, sink.data_ptr(), C.byref(tf), None))
