@@ -121,7 +121,9 @@ int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t
  * window that stays in L2); 4: as 3, plus a workgroup barrier per k tile; 5: as 0 in IEEE half (v_mfma_f32_32x32x16_f16,
  * sign and all 10 mantissa bits random); 6: as 0 plus the direct-to-LDS loads of 3 (nothing reads LDS); 7: as 0 plus the
  * same bytes loaded into registers instead; 8: as 7, the registers then written to LDS with ds_write_b128;
- * 9: as 0 with v_mfma_f32_16x16x32_bf16 (same flops in twice as many instructions); 10: as 7 with twice the bytes.
+ * 9: as 0 with v_mfma_f32_16x16x32_bf16 (same flops in twice as many instructions); 10: as 7 with twice the bytes;
+ * 11: a register-direct inner loop in miniature: the 16x16x32 instruction on a 128 x 128 wavefront tile whose operands
+ * are loaded from (L2-resident) memory in the instruction's own layout, one k step ahead, no LDS and no barrier.
  * sink: device, >= 65536 floats + 4 MB (1 114 112 floats): the first 65536 are overwritten, modes 3 and 4 read the
  * rest (any finite contents).  Synchronous: returns after the kernel has run.  tflops: host. */
 int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream);

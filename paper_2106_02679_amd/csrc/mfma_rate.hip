@@ -168,12 +168,57 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, const un
     sink[blockIdx.x * 256 + threadIdx.x] = t;
 }
 
+// Mode 11: a register-direct GEMM inner loop in miniature.  v_mfma_f32_16x16x32_bf16 on a 128 x 128 wavefront tile
+// (8 x 8 blocks), both operands loaded straight from (L2-resident) memory into registers in the instruction's own
+// layout - lane = (row l % 16, 16-byte k chunk l / 16), so the four lanes of a row read 64 contiguous bytes and one
+// load instruction touches 16 rows - double-buffered one k step (32) ahead.  No LDS, no barrier; the four wavefronts
+// of a workgroup form a 2 x 2 arrangement that shares row blocks only through the caches.  Rows are 4 KB + 128 B apart
+// in a 2.1 MB window that every workgroup reads alike.
+__global__ __launch_bounds__(256, 1) void mfma_direct_kernel(float *sink, const unsigned *src, int iters) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int kRowBytes = 4096 + 128, kRowData = 4096;     // a pitch that is not a power of two
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned *>(src), 0, 4 << 20, 0x00020000);
+    // rows 0..255: the A panel (wm selects a half), rows 256..511: the B panel (wn selects a half)
+    const int offA = (wm * 128 + (lane & 15)) * kRowBytes + (lane >> 4) * 16;
+    const int offB = (256 + wn * 128 + (lane & 15)) * kRowBytes + (lane >> 4) * 16;
+    bf16x8 a[2][8], b[2][8];
+    f32x4 acc[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto fetch = [&](int buf, int kbyte) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[buf][i] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, offA + i * 16 * kRowBytes, kbyte, 0));
+            b[buf][i] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, offB + i * 16 * kRowBytes, kbyte, 0));
+        }
+    };
+    int kbyte = 0;
+    fetch(0, 0);
+    for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {                         // two k steps of 32 = the flops of 64 32x32x16 MFMAs
+            kbyte = (kbyte + 64) & (kRowData - 1);
+            fetch(h ^ 1, kbyte);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[h][j], a[h][i], acc[i * 8 + j], 0, 0, 0);
+        }
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) t += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    sink[blockIdx.x * 256 + threadIdx.x] = t;
+}
+
 }  // namespace
 }  // namespace lga
 
 extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream) {
     using namespace lga;
-    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 10 || !sink || !tflops) return LGA_ERR_ARG;
+    if (iters < 4 || iters > (1 << 24) || mode < 0 || mode > 11 || !sink || !tflops) return LGA_ERR_ARG;
     iters &= ~3;                                            // the loop does four groups of 16 MFMAs per turn
     // results go to the first 65536 floats of sink; modes 3 and 4 read the kDmaWindow bytes after them
     const unsigned *src = reinterpret_cast<const unsigned *>(sink + 65536);
@@ -210,7 +255,8 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
         case 7: hipLaunchKernelGGL(mfma_rate_kernel<7>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
         case 8: hipLaunchKernelGGL(mfma_rate_kernel<8>, dim3(cus), dim3(256), kSmem, s, sink, src, iters); break;
         case 9: hipLaunchKernelGGL(mfma_rate_kernel<9>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
-        default: hipLaunchKernelGGL(mfma_rate_kernel<10>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        case 10: hipLaunchKernelGGL(mfma_rate_kernel<10>, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
+        default: hipLaunchKernelGGL(mfma_direct_kernel, dim3(cus), dim3(256), 0, s, sink, src, iters); break;
     }
     (void)hipEventRecord(e1, s);
     hipError_t e = hipEventSynchronize(e1);
