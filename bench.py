@@ -8,6 +8,15 @@ the timed region.  Prints ONE JSON line:
   roofline           the dominant kernel's achieved rate against the MI355X peak, from HIP event
                      pairs the library records around every launch inside the timed region
   cpu_baseline       the fp64 numpy oracle timed on the host cores on a bounded sample
+  audit              what the timed steps left behind (output, weights, gradient: finite? how large?), every step's
+                     time, the dominant kernel's average per step, and the clock / power the board reported meanwhile
+
+The timed steps are kept statistically alike: every step sees the same batch, so with the configurations' learning
+rate of 1e-3 Adam would move every weight the same way step after step (its first steps are sign steps: 25 of them
+shift each weight by more than the initial standard deviation of 0.02) and the operands of the later steps would no
+longer be the workload's.  The benchmark therefore runs the same kernels with a learning rate of 1e-6 (`--lr`), which
+leaves the weights within 0.2 % of their initial values over 25 steps; the arithmetic per step is identical, and the
+audit reports the drift that did happen.
 """
 import argparse
 import json
@@ -54,8 +63,13 @@ def parse():
     ap.add_argument("--fp16", action="store_true",
                     help="run the 16-bit configuration in IEEE half instead of bfloat16, with the per-layer non-finite "
                          "test before each Adam step (not the headline)")
+    ap.add_argument("--lr", type=float, default=1e-6,
+                    help="Adam learning rate of the timed steps (see the module docstring; the parity tests use the "
+                         "configurations' 1e-3 for their single step)")
+    ap.add_argument("--no-audit", action="store_true", help="skip the read-back of output, weights and gradient")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=64)
+    ap.add_argument("--cpu-sample-seq", type=int, default=256, help="positions per sequence of the oracle's sample")
+    ap.add_argument("--cpu-sample-micro", type=int, default=2, help="micro-batches of the oracle's sample")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
     return ap.parse_args()
 
@@ -75,8 +89,9 @@ def measured_traffic(workload, kernel):
     return None
 
 
-def cpu_baseline(w, sample_tokens, causal=True):
-    """Time the oracle (as it stands) on a one-layer, one-micro-batch sample of the same layer shape."""
+def cpu_baseline(w, n_micro, seq_len, causal=True):
+    """Time the oracle (as it stands) on the workload's parity slice: one layer of the same shape (width, heads,
+    feed-forward width), `n_micro` micro-batches of `seq_len` positions, forward + backward + Adam."""
     import numpy as np
     import synth_inputs as S
     from oracle import lga_oracle as O
@@ -85,18 +100,106 @@ def cpu_baseline(w, sample_tokens, causal=True):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    s = min(w.seq_len, sample_tokens)
-    sw = S.Workload(w.name + "_cpu_sample", 1, w.d_model, w.n_heads, w.d_ff, s, 1, 1, w.dtype)
+    s = min(w.seq_len, seq_len)
+    n = min(w.n_micro, n_micro)
+    sw = S.Workload(w.name + "_cpu_sample", 1, w.d_model, w.n_heads, w.d_ff, s, w.micro_batch, n, w.dtype)
     x, G, params = S.make_inputs(sw, seed=0)
-    shape = O.StackShape(d_l=1, d_m=sw.d_model, d_a=sw.n_heads, d_I=sw.d_ff, d_s=s, b_mu=1, n_mu=1, causal=causal)
+    shape = O.StackShape(d_l=1, d_m=sw.d_model, d_a=sw.n_heads, d_I=sw.d_ff, d_s=s, b_mu=sw.micro_batch, n_mu=n, causal=causal)
     t0 = time.perf_counter()
     O.step_microbatch_major(x, G, params, shape, O.AdamHyper())
     dt = time.perf_counter() - t0
+    # what the oracle multiplies: 2 flop per token and matrix entry forward, twice that backward (it stores instead of
+    # recomputing); attention as full s x s products, 2 forward and 4 backward, 2 s^2 d flop each per sequence
+    d, f = sw.d_model, sw.d_ff
+    flops = 6.0 * sw.tokens * (4.0 * d * d + 2.0 * d * f) + 12.0 * n * sw.micro_batch * float(s) * s * d
     # the full workload does the same per-token work in each of its layers
-    return {"value": s / dt / w.n_layers, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"fp64 numpy oracle, 1 layer x 1 micro-batch x {s} tokens of the same layer shape "
-                      f"(d={w.d_model}, heads={w.n_heads}, d_ff={w.d_ff}), fwd+bwd+Adam in {dt:.2f} s; "
-                      f"tokens/s scaled by 1/{w.n_layers} layers"}
+    return {"value": sw.tokens / dt / w.n_layers, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "fp64_gflops": flops / dt / 1e9, "seconds": dt,
+            "sample": f"fp64 numpy oracle on the workload's parity slice: 1 layer of the same shape (d={w.d_model}, "
+                      f"heads={w.n_heads}, d_ff={w.d_ff}) x {n} micro-batches x {sw.micro_batch} x {s} positions = "
+                      f"{sw.tokens} tokens, fwd+bwd+Adam in {dt:.1f} s (its per-parameter work - gradient buffers and "
+                      f"Adam over {sw.params_per_layer / 1e9:.2f} G fp64 values - is included and does not shrink with "
+                      f"the sample); tokens/s scaled by 1/{w.n_layers} layers"}
+
+
+class BoardSampler:
+    """Clock and power of GPU 0 as rocm-smi reports them, sampled about once a second by a thread of its own while the
+    timed steps run (a child process per sample: host-side only, nothing is enqueued on the GPU)."""
+
+    def __init__(self, period=1.0):
+        import shutil
+        import threading
+        self.exe = shutil.which("rocm-smi") or ("/opt/rocm/bin/rocm-smi" if os.path.exists("/opt/rocm/bin/rocm-smi") else None)
+        self.period = period
+        self.samples = []           # (sclk MHz or None, W or None)
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True) if self.exe else None
+
+    def _once(self):
+        import re
+        import subprocess
+        try:
+            txt = subprocess.run([self.exe, "-d", "0", "--showclocks", "--showpower"], capture_output=True, text=True,
+                                 timeout=10).stdout
+        except Exception:
+            return
+        sclk = re.search(r"sclk clock level[^(]*\((\d+)Mhz\)", txt)
+        pw = re.search(r"Power[^:\n]*\(W\)\s*:\s*([0-9.]+)", txt)
+        self.samples.append((int(sclk.group(1)) if sclk else None, float(pw.group(1)) if pw else None))
+
+    def _run(self):
+        while not self._stop.is_set():
+            self._once()
+            self._stop.wait(self.period)
+
+    def start(self):
+        if self._thread:
+            self._thread.start()
+
+    def stop(self):
+        if not self._thread:
+            return None
+        self._stop.set()
+        self._thread.join(timeout=15)
+        clk = [c for c, _ in self.samples if c is not None]
+        pw = [p for _, p in self.samples if p is not None]
+        mean = lambda v: sum(v) / len(v) if v else None
+        return {"samples": len(self.samples), "sclk_mhz_mean": mean(clk), "sclk_mhz_min": min(clk) if clk else None,
+                "sclk_mhz_max": max(clk) if clk else None, "power_w_mean": mean(pw), "power_w_max": max(pw) if pw else None,
+                "source": "rocm-smi --showclocks --showpower, one sample per second during the timed steps"}
+
+
+def tensor_audit(torch, B, ptr, count, tdt):
+    """finite? / rms / largest magnitude of `count` elements of type tdt at device (or pinned host) address ptr."""
+    t = torch.empty(count, device="cuda", dtype=tdt)
+    B.copy_device(t.data_ptr(), ptr, t.numel() * t.element_size())
+    torch.cuda.synchronize()
+    finite = torch.isfinite(t)
+    n_bad = int(t.numel() - int(finite.sum()))
+    sq, mx = 0.0, 0.0
+    for part in t.split(1 << 28):           # float64 sums of squares, in pieces that keep the temporaries small
+        p = torch.nan_to_num(part.double(), nan=0.0, posinf=0.0, neginf=0.0)
+        sq += float((p * p).sum())
+        mx = max(mx, float(p.abs().max())) if p.numel() else mx
+    return {"all_finite": n_bad == 0, "nonfinite_count": n_bad, "rms": (sq / max(1, t.numel())) ** 0.5, "abs_max": mx}, t
+
+
+def profile_figures(workload, kernel):
+    """avg launch duration (us) of `kernel` in the committed rocprofv3 --kernel-trace --stats summary of this workload,
+    and the box-to-box spread that summary states, or (None, None)."""
+    path = os.path.join(ROOT, "profiles", f"train_step_{workload}_kernel_stats.txt")
+    avg = spread = None
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.rstrip("\n").split("\t")
+                if len(parts) == 3 and parts[0] == "rocprof_avg_us" and parts[1] == kernel:
+                    avg = float(parts[2])
+                if len(parts) == 2 and parts[0] == "box_to_box_spread":
+                    spread = float(parts[1])
+    except OSError:
+        pass
+    return avg, spread
 
 
 def main():
@@ -144,11 +247,18 @@ def main():
     dy = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)      # "scaled" by loss_scale = 1
     st = B.Stack(cfg)                     # weights filled on the device: N(0, 0.02^2), gains 1, biases 0
     torch.cuda.synchronize()
+    audit = None
+    if not args.no_audit:
+        # layer 0's weights as initialised, kept (if they fit) to report how far the timed steps moved them
+        ptr, n = st.params(0)
+        free, _ = torch.cuda.mem_get_info()
+        a0, w_start = tensor_audit(torch, B, ptr, n, torch.float32) if free > 3 * 4 * n + (8 << 30) else (None, None)
+        audit = {"adam_lr": args.lr, "weights_layer0_start": a0}
 
     marks = []      # per timed step: events at its start, between the sweeps, at its end
 
     def step(t, timed=False):
-        adam = B.lga_adam(1e-3, 0.9, 0.999, 1e-8, t, loss_scale, 1 if dt == B.LGA_FP16 else 0)
+        adam = B.lga_adam(args.lr, 0.9, 0.999, 1e-8, t, loss_scale, 1 if dt == B.LGA_FP16 else 0)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if timed else None
         if timed:
             ev[0].record()
@@ -169,16 +279,29 @@ def main():
     for _ in range(args.warmup):
         step(t); t += 1
     torch.cuda.synchronize()
-    st.profile_begin()
     restores0 = st.restore_count()
+    sampler = BoardSampler()
+    sampler.start()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
+    per_step_stats = []
     for _ in range(args.steps):
+        # the library's per-launch event pairs are collected step by step (lga_profile_end waits for the step to
+        # finish: one host round trip per step inside the timed region)
+        st.profile_begin()
         step(t, timed=True); t += 1
+        per_step_stats.append(st.profile_end())
     e1.record()
     torch.cuda.synchronize()
+    board = sampler.stop()
     ms_total = e0.elapsed_time(e1)
-    stats = st.profile_end()
+    merged = {}
+    for one in per_step_stats:
+        for k in one:
+            m = merged.setdefault(k["name"], dict(name=k["name"], launches=0, ms=0.0, flops=0.0, bytes=0.0))
+            for key in ("launches", "ms", "flops", "bytes"):
+                m[key] += k[key]
+    stats = sorted(merged.values(), key=lambda k: -k["ms"])
     restores = (st.restore_count() - restores0) / args.steps
     skipped = sum(st.nonfinite_layers()) if dt == B.LGA_FP16 else 0       # layers whose last update was left out
     ms_step = ms_total / args.steps
@@ -210,7 +333,7 @@ def main():
         # calibration, measured live: what the chip sustains with nothing but MFMAs on register operands with random
         # mantissas and signs (its power management holds the clock below nominal on such data)
         import ctypes as C
-        sink = torch.ones(65536 + (4 << 20) // 4, device="cuda")
+        sink = torch.ones(65536, device="cuda")
         tf = C.c_double()
         B.check(B.lib.lga_op_mfma_rate(800000, 0, sink.data_ptr(), C.byref(tf), None))
         roof["mfma_only_rate_random_operands"] = tf.value
@@ -221,6 +344,40 @@ def main():
     roof["launches"] = dom["launches"]
     roof["avg_launch_ms"] = per_launch_ms
     roof["share_of_step"] = dom["ms"] / ms_total
+    dom_per_step = [next((k["ms"] / k["launches"] for k in one if k["name"] == dom["name"]), None) for one in per_step_stats]
+    roof["avg_launch_ms_per_step"] = dom_per_step
+    # the committed rocprofv3 summary of this workload: its average for this kernel must agree with the live one
+    prof_us, spread = profile_figures(w.name, dom["name"]) if (group == default_group and causal) else (None, None)
+    if prof_us:
+        live = per_launch_ms * 1e3
+        roof["profile_avg_launch_us"] = prof_us
+        roof["profile_frac"] = roof["frac"] * live / prof_us
+        roof["live_over_profile"] = live / prof_us
+        roof["agrees_with_profile"] = abs(live / prof_us - 1.0) <= (spread or 0.05)
+        if not roof["agrees_with_profile"]:
+            roof["note"] = (f"this run's average launch of {dom['name']} ({live:.0f} us) differs from the committed profile's "
+                            f"({prof_us:.0f} us) by more than the stated box-to-box spread of {100 * (spread or 0.05):.0f} %: "
+                            "frac is this run's, profile_frac the profile's")
+    if audit is not None:
+        ptr, nbytes = st.checkpoint(w.n_layers)
+        audit["output_y"], _ = tensor_audit(torch, B, ptr, nbytes // (2 if is16 else 4), tdt)
+        ptr, n = st.params(0)
+        audit["weights_layer0_end"], w_end = tensor_audit(torch, B, ptr, n, torch.float32)
+        if w_start is not None:
+            num = den = 0.0
+            for a, b in zip(w_end.split(1 << 28), w_start.split(1 << 28)):
+                num += float((a.double() - b.double()).pow(2).sum())
+                den += float(b.double().pow(2).sum())
+            audit["weights_layer0_relative_change"] = (num / den) ** 0.5 if den > 0 else None
+        del w_end, w_start
+        try:
+            last = 0 if args.order == "layered" else w.n_layers - 1        # the layer whose gradient the buffer still holds
+            ptr, n = st.grads(last)
+            audit["gradient_last_layer_done"], _ = tensor_audit(torch, B, ptr, n, torch.float32)
+        except B.LgaError:
+            audit["gradient_last_layer_done"] = None
+        audit["all_finite"] = all(v["all_finite"] for k, v in audit.items() if isinstance(v, dict) and "all_finite" in v)
+        audit["board"] = board
 
     gemm_ms = sum(k["ms"] for k in stats if k["name"].startswith("gemm"))
     gemm_fl = sum(k["flops"] for k in stats if k["name"].startswith("gemm"))
@@ -235,8 +392,8 @@ def main():
                    "d_ff": w.d_ff, "seq_len": w.seq_len, "micro_batch": w.micro_batch, "n_micro": w.n_micro,
                    "group": group, "order": args.order, "attention": args.attention, "tokens_per_step": tokens,
                    "param_buffers": args.param_buffers or w.n_layers, "overlap": args.overlap,
-                   "offload_checkpoints": bool(args.offload)},
-        "ms_per_step_min": min(step_ms), "ms_per_step_max": max(step_ms),
+                   "offload_checkpoints": bool(args.offload), "adam_lr": args.lr},
+        "ms_per_step_min": min(step_ms), "ms_per_step_max": max(step_ms), "ms_per_step_list": step_ms,
         # layered order: forward sweep / backward sweep with recompute and the per-layer Adam steps (mean over the steps)
         "phase_ms": ({"forward": sum(fwd_ms) / len(fwd_ms), "backward_with_adam": ms_step - sum(fwd_ms) / len(fwd_ms),
                       "adam_kernels": sum(k["ms"] for k in stats if k["name"].startswith("adam")) / args.steps}
@@ -254,6 +411,7 @@ def main():
         "all_gemm_share_of_step": gemm_ms / ms_total,
         "model_param_bytes_per_step": param_bytes, "model_grad_bytes_per_step": grad_bytes,
         "roofline": roof,
+        "audit": audit,
     }
     if args.kernels:
         for k in stats:
@@ -264,7 +422,7 @@ def main():
     del x, dy
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_tokens, causal)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_micro, args.cpu_sample_seq, causal)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

@@ -114,18 +114,10 @@ int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t
 
 /* Calibration for the benchmark tools: the bf16 MFMA rate (TFLOP/s, executed) that the GPU sustains on register
  * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 16 v_mfma_f32_32x32x16_bf16 back to
- * back, no memory traffic.  mode 0: operand values around +-1 with random mantissas and signs (what the power
- * management allows on realistic data); 1: all operand values 1.0 (approaches the nominal peak); 2: as 0, with the
- * operands re-read from LDS as a 256 x 256 GEMM tile of 2 x 2 wavefronts must (eight 16-byte reads per 16 MFMAs);
- * 3: as 2, plus the direct-to-LDS loads that fill such a tile (64 KB per 64 MFMAs of each wavefront, from a 4 MB
- * window that stays in L2); 4: as 3, plus a workgroup barrier per k tile; 5: as 0 in IEEE half (v_mfma_f32_32x32x16_f16,
- * sign and all 10 mantissa bits random); 6: as 0 plus the direct-to-LDS loads of 3 (nothing reads LDS); 7: as 0 plus the
- * same bytes loaded into registers instead; 8: as 7, the registers then written to LDS with ds_write_b128;
- * 9: as 0 with v_mfma_f32_16x16x32_bf16 (same flops in twice as many instructions); 10: as 7 with twice the bytes;
- * 11: a register-direct inner loop in miniature: the 16x16x32 instruction on a 128 x 128 wavefront tile whose operands
- * are loaded from (L2-resident) memory in the instruction's own layout, one k step ahead, no LDS and no barrier.
- * sink: device, >= 65536 floats + 4 MB (1 114 112 floats): the first 65536 are overwritten, modes 3 and 4 read the
- * rest (any finite contents).  Synchronous: returns after the kernel has run.  tflops: host. */
+ * back, no memory traffic.  mode 0: operand values in [0.5, 1) with random mantissas and signs (what the power
+ * management allows on realistic data); 1: all operand values 1.0 (approaches the nominal peak).
+ * sink: device, >= 65536 floats, overwritten.  iters in 1 .. 2^24.  Synchronous: returns after the kernel has run.
+ * tflops: host. */
 int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream);
 
 #ifdef __cplusplus

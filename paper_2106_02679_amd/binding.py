@@ -136,6 +136,13 @@ def read_device(ptr: int, count: int, dtype="float32"):
     return out
 
 
+def copy_device(dst_ptr: int, src_ptr: int, nbytes: int) -> None:
+    """Blocking copy of nbytes between two addresses the runtime knows (device or pinned host)."""
+    rc = _hip.hipMemcpy(dst_ptr, src_ptr, nbytes, 4)                   # hipMemcpyDefault
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy failed with HIP error {rc}")
+
+
 def write_device(ptr: int, array) -> None:
     """Blocking copy of a contiguous numpy array to device address `ptr`."""
     import numpy as np
