@@ -13,6 +13,9 @@
  *  - Pointers marked "dev" are device (HBM) addresses, "host" are host addresses.
  *  - Work is enqueued on the HIP stream given in lga_config.stream (borrowed; NULL = the
  *    default stream) and the call returns without synchronising; the caller synchronises.
+ *  - That stream must not be in graph capture: lga_forward_layered, lga_backward_layered, lga_forward_layer,
+ *    lga_backward_layer, lga_step_mbmajor and lga_adam_step_layer ask it first and return LGA_ERR_STATE, with
+ *    nothing enqueued, while it is being captured (capture of whole sweeps is not a supported use).
  *  - The caller owns x, y, dy, dx.  The library owns weights, Adam moments, gradient
  *    buffer(s), the 16-bit parameter copies, the activation checkpoints and all scratch:
  *    one arena, sized from the configuration and allocated once in lga_init_stack
@@ -133,7 +136,13 @@ typedef struct lga_config {
  * pass the decision is per layer by necessity: layers above the one whose gradient overflowed have already been
  * updated, and every layer below it receives the non-finite activation gradient and is skipped too.  A caller that
  * wants all-or-nothing steps sets retain_grads, runs the backward pass unfused, asks lga_grads_nonfinite, and only
- * when that reports no layer calls lga_adam_step_layer for every layer. */
+ * when that reports no layer calls lga_adam_step_layer for every layer.
+ * Consequence for the step count: after a fused backward pass in which some layers were left out, the layers above
+ * them HAVE taken update number `step` (moments advanced, bias correction of `step` applied) and the others have
+ * not.  The library keeps no per-layer count.  A caller that backs the scale off and repeats the pass with the same
+ * `step` gives the already updated layers a second update under that same bias correction; one that wants every
+ * layer to see each step number exactly once reads lga_nonfinite_layers, keeps a count per layer, and drives the
+ * repeat through lga_backward_layer, which takes its own lga_adam per layer (or uses the unfused path above). */
 typedef struct lga_adam {
     float lr, beta1, beta2, eps;
     int32_t step;
@@ -165,7 +174,9 @@ int lga_loss_scaler_update(lga_loss_scaler *scaler, int32_t overflowed);
  * Adam moments start at zero.  The 16-bit parameter copy of every layer is produced here
  * (section 2.5: parameters are converted to 16 bits before use) and refreshed by each Adam step.
  * LGA_ERR_SHAPE if any size is < 1, d_model % n_heads != 0, n_micro % group != 0, or, in the 16-bit modes,
- * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0.  Head sizes up to 160 have MFMA attention kernels in the 16-bit modes
+ * d_h % 8 != 0, d_model % 8 != 0 or d_ff % 8 != 0, or if a leading dimension of a GEMM operand would exceed
+ * 2 097 151 elements (3 d_model, d_ff, group * micro_batch * seq_len + 64, and with an explicit wgrad_groups that
+ * many groups' tokens + 64; the automatic wgrad_groups stays within it).  Head sizes up to 160 have MFMA attention kernels in the 16-bit modes
  * (built for 32, 64, 96, 128, 160; sizes in between run in the next larger one).  Larger head sizes (table B.1's
  * X_[x] family has d_h = 2 x) run an attention built from batched GEMMs over the heads when seq_len is a multiple of 8
  * (at most 32768); the arena then holds one sequence's score matrices, 12 seq_len^2 bytes per head for as many

@@ -952,6 +952,41 @@ LGA_INSTANTIATE_TYPE(f16);
 #undef LGA_INSTANTIATE_TYPE
 #undef LGA_INSTANTIATE_KERNELS
 
+// Dynamic LDS of the three kernels, in bytes.
+// forward: three stages of a 64-key K tile and V tile
+template <int DH> constexpr int smem_fwd() {
+    return 3 * (TileDma<64, DH, pitch_rd<DH>()>::ELEMS + TileDma<64, DH, pitch_tr<DH>()>::ELEMS) * 2;
+}
+// dQ: two stages of a 64-key K tile and V tile
+template <int DH> constexpr int smem_dq() {
+    return 2 * (TileDma<64, DH, pitch_both<DH>()>::ELEMS + TileDma<64, DH, pitch_rd<DH>()>::ELEMS) * 2;
+}
+// dK/dV: three stages of a Q tile, a dO tile and the row statistics
+template <int DH> constexpr int smem_dkv() { return 3 * (2 * 64 * DH * 2 + 2 * 64 * 4); }
+template <int DH> constexpr int occ_dq() { return DH <= 128 ? 2 : 1; }     // workgroups per CU the dQ kernel's register budget is set for
+
+// All three kernels use more dynamic LDS than a launch may ask for by default: raise the limit of every
+// instantiation.  Called once, outside any launch path (see attn_prepare_kernels).
+template <int DH, class E> hipError_t raise_lds_limits() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_kernel<DH, E>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem_fwd<DH>());
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dq_kernel<DH, occ_dq<DH>(), E>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq<DH>());
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_kernel<DH, E>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_dkv<DH>());
+    return e;
+}
+template <class E> hipError_t raise_lds_limits_all() {
+    hipError_t e = raise_lds_limits<32, E>();
+    if (e == hipSuccess) e = raise_lds_limits<64, E>();
+    if (e == hipSuccess) e = raise_lds_limits<96, E>();
+    if (e == hipSuccess) e = raise_lds_limits<128, E>();
+    if (e == hipSuccess) e = raise_lds_limits<160, E>();
+    return e;
+}
+
 template <int DH, class E> void fwd_dh(const E *qkv, E *out, float *lse, AttnShape sh, hipStream_t s) {
     dim3 grid((unsigned)(sh.n_seq * sh.heads) * ((sh.s + 255) / 256));
     char name[64];
@@ -959,15 +994,7 @@ template <int DH, class E> void fwd_dh(const E *qkv, E *out, float *lse, AttnSha
     const double pairs = (double)sh.n_seq * sh.heads * sh.s * sh.s * (sh.causal ? 0.5 : 1.0);      // visible (query, key) pairs
     const double act = (double)sh.n_seq * sh.s * sh.heads * sh.dh * 2.0;      // bytes of one [tokens, d] bf16 tensor
     ProfScope scope(name, 4.0 * pairs * sh.dh, 4.0 * act, s);
-    // three stages of a 64-key K tile and V tile
-    constexpr int smem = 3 * (TileDma<64, DH, pitch_rd<DH>()>::ELEMS + TileDma<64, DH, pitch_tr<DH>()>::ELEMS) * 2;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_fwd_kernel<DH, E>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        attr_set = true;
-    }
-    hipLaunchKernelGGL((attn_fwd_kernel<DH, E>), grid, dim3(256), smem, s, qkv, out, lse, sh);
+    hipLaunchKernelGGL((attn_fwd_kernel<DH, E>), grid, dim3(256), smem_fwd<DH>(), s, qkv, out, lse, sh);
 }
 template <int DH, class E>
 void bwd_dh(const E *qkv, const float *lse, const float *delta, const E *dout, E *dqkv, AttnShape sh,
@@ -979,28 +1006,13 @@ void bwd_dh(const E *qkv, const float *lse, const float *delta, const E *dout, E
     {
         snprintf(name, sizeof(name), "attn_bwd_dq_kernel<%d>", DH);
         ProfScope scope(name, 6.0 * pairs * sh.dh, 5.0 * act, s);
-        constexpr int kOccDq = DH <= 128 ? 2 : 1;     // workgroups per CU the register budget is set for
-        // two stages of a 64-key K tile and V tile
-        constexpr int smem_dq = 2 * (TileDma<64, DH, pitch_both<DH>()>::ELEMS + TileDma<64, DH, pitch_rd<DH>()>::ELEMS) * 2;
-        static bool attr_set_dq = false;
-        if (!attr_set_dq) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dq_kernel<DH, kOccDq, E>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem_dq);
-            attr_set_dq = true;
-        }
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, kOccDq, E>), grid, dim3(256), smem_dq, s, qkv, lse, delta, dout, dqkv, sh);
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, occ_dq<DH>(), E>), grid, dim3(256), smem_dq<DH>(), s, qkv, lse, delta, dout,
+                           dqkv, sh);
     }
     {
         snprintf(name, sizeof(name), "attn_bwd_dkv_kernel<%d>", DH);
         ProfScope scope(name, 8.0 * pairs * sh.dh, 6.0 * act, s);
-        constexpr int smem = 3 * (2 * 64 * DH * 2 + 2 * 64 * 4);   // three stages of a Q tile, a dO tile and the row statistics
-        static bool attr_set = false;
-        if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkv_kernel<DH, E>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            attr_set = true;
-        }
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, E>), grid, dim3(256), smem, s, qkv, lse, delta, dout, dqkv, sh);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, E>), grid, dim3(256), smem_dkv<DH>(), s, qkv, lse, delta, dout, dqkv, sh);
     }
 }
 
@@ -1011,12 +1023,19 @@ void bwd_dh(const E *qkv, const float *lse, const float *delta, const E *dout, E
 bool attn_bf16_supports(int dh) { return dh >= 8 && dh <= 160 && dh % 8 == 0; }
 static int padded_dh(int dh) { return (dh + 31) / 32 * 32; }
 
+hipError_t attn_prepare_kernels() {
+    hipError_t e = raise_lds_limits_all<bf16>();
+    if (e == hipSuccess) e = raise_lds_limits_all<f16>();
+    return e;
+}
+
 template <class E> void launch_attn_fwd_mfma(const E *qkv, E *out, float *lse, AttnShape sh, hipStream_t s) {
     if (sh.n_seq == 0 || sh.s == 0) return;
     if (!attn_bf16_supports(sh.dh)) {
         launch_attn_fwd_simple<E>(qkv, out, lse, sh, s);
         return;
     }
+    (void)prepare_kernels();
     switch (padded_dh(sh.dh)) {
         case 32: fwd_dh<32, E>(qkv, out, lse, sh, s); break;
         case 64: fwd_dh<64, E>(qkv, out, lse, sh, s); break;
@@ -1034,6 +1053,7 @@ void launch_attn_bwd_mfma(const E *qkv, const E *out, const float *lse, const E 
         launch_attn_bwd_simple<E>(qkv, out, lse, dout, dqkv, delta, sh, s);
         return;
     }
+    (void)prepare_kernels();
     const size_t items = (size_t)sh.n_seq * sh.s * sh.heads;
     {
         ProfScope scope("attn_delta_kernel", 2.0 * items * sh.dh, 4.0 * items * sh.dh, s);

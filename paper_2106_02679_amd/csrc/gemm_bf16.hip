@@ -752,13 +752,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     }
 }
 
+// The kernel that serves a (tile size, layout, epilogue) combination and its dynamic LDS in bytes.
+template <int BM, int BN, bool A_KM, bool B_KM, int EPI, class E> struct KernelFor {
+    static constexpr bool kDma = A_KM && B_KM && BM == 256;
+    static constexpr size_t smem = kDma ? (size_t)5 * BM * BK * sizeof(E)            // the DMA kernel's operand ring
+                                        : (size_t)2 * (BM + BN) * BK * sizeof(E);    // two stages of both operands
+    static auto get() -> void (*)(GemmParams<E>, int, int) {
+        if constexpr (kDma) return gemm_bf16_dma_kernel<BM, BN, 2, 2, EPI, E>;
+        else return gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI, E>;
+    }
+    // up to 160 KB of dynamic LDS: more than a launch may ask for by default
+    static hipError_t raise_lds_limit() {
+        return hipFuncSetAttribute(reinterpret_cast<const void *>(get()), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    }
+};
+
 template <int BM, int BN, bool A_KM, bool B_KM, int EPI, class E>
 void launch_one(const GemmParams<E> &p, hipStream_t s) {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(E);
-    if constexpr (A_KM && B_KM && BM == 256) smem = (size_t)5 * BM * BK * sizeof(E);     // the DMA kernel's operand ring
-    void (*kern)(GemmParams<E>, int, int) = gemm_bf16_kernel<BM, BN, A_KM, B_KM, EPI, E>;
-    if constexpr (A_KM && B_KM && BM == 256) kern = gemm_bf16_dma_kernel<BM, BN, 2, 2, EPI, E>;
+    const size_t smem = KernelFor<BM, BN, A_KM, B_KM, EPI, E>::smem;
+    void (*kern)(GemmParams<E>, int, int) = KernelFor<BM, BN, A_KM, B_KM, EPI, E>::get();
     char name[96];
     const char *et = std::is_same<E, bf16>::value ? "bf16" : "f16";       // profile names: gemm_bf16_... or gemm_f16_...
     if (A_KM && B_KM && BM == 256)
@@ -861,35 +874,75 @@ int gemm_splitk_slices(int M, int N, int K) {
     return 1;
 }
 
+bool gemm_mfma_supports(bool a_kmajor, bool b_kmajor, Epilogue epi) {
+    if (a_kmajor && !b_kmajor) return epi == EPI_STORE || epi == EPI_BIAS || epi == EPI_BIAS_RESID || epi == EPI_BIAS_GELU;
+    if (a_kmajor && b_kmajor) return epi >= EPI_STORE && epi <= EPI_ACCUM_F32;
+    if (!a_kmajor && !b_kmajor) return epi == EPI_STORE || epi == EPI_ACCUM_F32;
+    return false;
+}
+
 template <class E>
-void launch_gemm_mfma(const GemmParams<E> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s) {
-    if (p.M == 0 || p.N == 0) return;
+bool launch_gemm_mfma(const GemmParams<E> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s) {
+    if (!gemm_mfma_supports(a_kmajor, b_kmajor, epi)) return false;
+    // the direct-to-LDS loads address an operand tile's 256 rows with 32-bit byte offsets inside a 1 GiB window
+    if (p.lda > kGemmMaxLd || p.ldb > kGemmMaxLd) return false;
+    if (p.M == 0 || p.N == 0) return true;
+    (void)prepare_kernels();
     // The three operand layouts the layer uses; every epilogue is tied to the family that needs it.
     if (a_kmajor && !b_kmajor) {          // forward
         switch (epi) {
-            case EPI_BIAS: launch_tiles<true, false, EPI_BIAS, E>(p, s); return;
-            case EPI_BIAS_RESID: launch_tiles<true, false, EPI_BIAS_RESID, E>(p, s); return;
-            case EPI_BIAS_GELU: launch_tiles<true, false, EPI_BIAS_GELU, E>(p, s); return;
-            case EPI_STORE: launch_tiles<true, false, EPI_STORE, E>(p, s); return;
-            default: break;
+            case EPI_BIAS: launch_tiles<true, false, EPI_BIAS, E>(p, s); break;
+            case EPI_BIAS_RESID: launch_tiles<true, false, EPI_BIAS_RESID, E>(p, s); break;
+            case EPI_BIAS_GELU: launch_tiles<true, false, EPI_BIAS_GELU, E>(p, s); break;
+            default: launch_tiles<true, false, EPI_STORE, E>(p, s); break;
         }
     } else if (a_kmajor && b_kmajor) {    // both operands k-contiguous: the layout the layer stack uses
         switch (epi) {
-            case EPI_STORE: launch_tiles<true, true, EPI_STORE, E>(p, s); return;
-            case EPI_BIAS: launch_tiles<true, true, EPI_BIAS, E>(p, s); return;
-            case EPI_BIAS_RESID: launch_tiles<true, true, EPI_BIAS_RESID, E>(p, s); return;
-            case EPI_BIAS_GELU: launch_tiles<true, true, EPI_BIAS_GELU, E>(p, s); return;
-            case EPI_MUL_DGELU: launch_tiles<true, true, EPI_MUL_DGELU, E>(p, s); return;
-            case EPI_ACCUM_F32: launch_tiles<true, true, EPI_ACCUM_F32, E>(p, s); return;
+            case EPI_STORE: launch_tiles<true, true, EPI_STORE, E>(p, s); break;
+            case EPI_BIAS: launch_tiles<true, true, EPI_BIAS, E>(p, s); break;
+            case EPI_BIAS_RESID: launch_tiles<true, true, EPI_BIAS_RESID, E>(p, s); break;
+            case EPI_BIAS_GELU: launch_tiles<true, true, EPI_BIAS_GELU, E>(p, s); break;
+            case EPI_MUL_DGELU: launch_tiles<true, true, EPI_MUL_DGELU, E>(p, s); break;
+            case EPI_ACCUM_F32: launch_tiles<true, true, EPI_ACCUM_F32, E>(p, s); break;
         }
-    } else if (!a_kmajor && !b_kmajor) {  // weight gradient
-        if (epi == EPI_ACCUM_F32) { launch_tiles<false, false, EPI_ACCUM_F32, E>(p, s); return; }
-        if (epi == EPI_STORE) { launch_tiles<false, false, EPI_STORE, E>(p, s); return; }
+    } else {                              // weight gradient from operands as stored
+        if (epi == EPI_ACCUM_F32) launch_tiles<false, false, EPI_ACCUM_F32, E>(p, s);
+        else launch_tiles<false, false, EPI_STORE, E>(p, s);
     }
-    // Unsupported combination: callers validate before launching, so reaching this is a bug.
-    abort();
+    return true;
 }
-template void launch_gemm_mfma<bf16>(const GemmParams<bf16> &, bool, bool, Epilogue, hipStream_t);
-template void launch_gemm_mfma<f16>(const GemmParams<f16> &, bool, bool, Epilogue, hipStream_t);
+template bool launch_gemm_mfma<bf16>(const GemmParams<bf16> &, bool, bool, Epilogue, hipStream_t);
+template bool launch_gemm_mfma<f16>(const GemmParams<f16> &, bool, bool, Epilogue, hipStream_t);
+
+namespace {
+template <bool A_KM, bool B_KM, int EPI, class E> hipError_t raise_pair() {
+    hipError_t e = KernelFor<256, 256, A_KM, B_KM, EPI, E>::raise_lds_limit();
+    if (e == hipSuccess) e = KernelFor<128, 128, A_KM, B_KM, EPI, E>::raise_lds_limit();
+    return e;
+}
+template <class E> hipError_t raise_all() {
+    hipError_t e = hipSuccess;
+    auto next = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    next(raise_pair<true, false, EPI_STORE, E>());
+    next(raise_pair<true, false, EPI_BIAS, E>());
+    next(raise_pair<true, false, EPI_BIAS_RESID, E>());
+    next(raise_pair<true, false, EPI_BIAS_GELU, E>());
+    next(raise_pair<true, true, EPI_STORE, E>());
+    next(raise_pair<true, true, EPI_BIAS, E>());
+    next(raise_pair<true, true, EPI_BIAS_RESID, E>());
+    next(raise_pair<true, true, EPI_BIAS_GELU, E>());
+    next(raise_pair<true, true, EPI_MUL_DGELU, E>());
+    next(raise_pair<true, true, EPI_ACCUM_F32, E>());
+    next(raise_pair<false, false, EPI_STORE, E>());
+    next(raise_pair<false, false, EPI_ACCUM_F32, E>());
+    return e;
+}
+}  // namespace
+
+hipError_t gemm_prepare_kernels() {
+    hipError_t e = raise_all<bf16>();
+    if (e == hipSuccess) e = raise_all<f16>();
+    return e;
+}
 
 }  // namespace lga

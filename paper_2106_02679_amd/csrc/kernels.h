@@ -7,6 +7,16 @@
 
 namespace lga {
 
+// ---- one-time set-up ----------------------------------------------------------------------
+// Kernels that use more dynamic LDS than a launch may ask for by default (the attention kernels, the large-tile
+// GEMM) have their limit raised here, once per process, before anything is launched: lga_init_stack calls it, and
+// so does every launcher of such a kernel (a flag test after the first call), so the op-level entry points need no
+// stack.  It must not run for the first time on a stream that is being captured into a graph - which is why the
+// stack-level entry points call it at init and refuse capturing streams.
+hipError_t prepare_kernels();
+hipError_t attn_prepare_kernels();      // attention_bf16.hip's part
+hipError_t gemm_prepare_kernels();      // gemm_bf16.hip's part
+
 // ---- element-wise / row kernels (rowops.hip) ---------------------------------------------
 // fp32 -> 16-bit copy of a parameter vector ("restore": parameters converted to 16 bits before use); E = bf16 or f16.
 template <class E> void launch_cast_f32_to_16(const float *src, E *dst, size_t n, hipStream_t s);
@@ -55,8 +65,12 @@ void launch_adam(float *w, float *m, float *v, const float *g, E *w16, size_t n,
 void launch_gemm_f32(const GemmParams<float> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
 // 16-bit MFMA kernel (E = bf16 or f16), fp32 accumulate.  Needs lda, ldb, ldc, N multiples of 8 and 16-byte aligned
 // bases.
+// Returns false, launching nothing, for a layout / epilogue pair that is not built (gemm_mfma_supports) or a leading
+// dimension beyond kGemmMaxLd.
+constexpr int kGemmMaxLd = ((1 << 30) - 256) / (2 * 256);      // 2 097 151 elements: row 255 of a tile stays inside the loads' 1 GiB window
+bool gemm_mfma_supports(bool a_kmajor, bool b_kmajor, Epilogue epi);
 template <class E>
-void launch_gemm_mfma(const GemmParams<E> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
+bool launch_gemm_mfma(const GemmParams<E> &p, bool a_kmajor, bool b_kmajor, Epilogue epi, hipStream_t s);
 // Into how many slices of the k range launch_gemm_mfma cuts an fp32-accumulating, k-contiguous GEMM whose output has
 // too few 256 x 256 tiles to occupy the chip (1 = not at all); it then needs slices * M * N floats of scratch.
 // k = 0 asks for the largest count any k would give (for sizing the scratch).

@@ -71,7 +71,11 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
         if (akm && !bkm) ok = e == EPI_STORE || e == EPI_BIAS || e == EPI_BIAS_RESID || e == EPI_BIAS_GELU;
         else if (akm && bkm) ok = true;
         else if (!akm && !bkm) ok = e == EPI_STORE || e == EPI_ACCUM_F32;
-        if (!ok) return err(LGA_ERR_SHAPE, "16-bit GEMM: this layout/epilogue pair is not built");
+        if (!ok || !gemm_mfma_supports(akm, bkm, e)) return err(LGA_ERR_SHAPE, "16-bit GEMM: this layout/epilogue pair is not built");
+        if (lda > kGemmMaxLd || ldb > kGemmMaxLd)
+            return err(LGA_ERR_SHAPE, "16-bit GEMM: lda and ldb must not exceed 2 097 151 elements (the kernels address a "
+                                      "tile's 256 rows with 32-bit byte offsets inside a 1 GiB window)");
+        bool launched = true;
         with16(dtype, [&](auto tag) {
             using E = decltype(tag);
             GemmParams<E> p{};
@@ -79,8 +83,9 @@ int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilo
             p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
             p.out = out16<E>(out); p.out2 = out16<E>(out2); p.outf = outf;
             p.bias = bias; p.aux = in16<E>(aux); p.beta = beta;
-            launch_gemm_mfma<E>(p, akm, bkm, e, s);
+            launched = launch_gemm_mfma<E>(p, akm, bkm, e, s);
         });
+        if (!launched) return err(LGA_ERR_SHAPE, "16-bit GEMM: the launcher refused these arguments");
     }
     return done("lga_op_gemm");
 }
@@ -99,6 +104,9 @@ int lga_op_gemm_splitk(int32_t dtype, int32_t M, int32_t N, int32_t K, const voi
     if (lda % 8 || ldb % 8 || ldc % 8 || N % 8 || K % 8)
         return err(LGA_ERR_SHAPE, "16-bit GEMM needs lda, ldb, ldc, N and K to be multiples of 8");
     if (!a16(A) || !a16(B) || !a16(outf) || !a16(scratch)) return err(LGA_ERR_SHAPE, "16-bit GEMM needs 16-byte aligned pointers");
+    if (lda > kGemmMaxLd || ldb > kGemmMaxLd)
+        return err(LGA_ERR_SHAPE, "16-bit GEMM: lda and ldb must not exceed 2 097 151 elements");
+    bool launched = true;
     with16(dtype, [&](auto tag) {
         using E = decltype(tag);
         GemmParams<E> p{};
@@ -106,8 +114,9 @@ int lga_op_gemm_splitk(int32_t dtype, int32_t M, int32_t N, int32_t K, const voi
         p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
         p.outf = outf; p.beta = beta;
         p.partial = scratch; p.partial_floats = scratch ? scratch_floats : 0;
-        launch_gemm_mfma<E>(p, true, true, EPI_ACCUM_F32, reinterpret_cast<hipStream_t>(stream));
+        launched = launch_gemm_mfma<E>(p, true, true, EPI_ACCUM_F32, reinterpret_cast<hipStream_t>(stream));
     });
+    if (!launched) return err(LGA_ERR_SHAPE, "16-bit GEMM: the launcher refused these arguments");
     return done("lga_op_gemm_splitk");
 }
 

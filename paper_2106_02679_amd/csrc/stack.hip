@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <type_traits>
@@ -33,6 +34,15 @@ int set_last_error(int code, const char *msg) { return fail(code, msg); }
 LaunchProfiler &profiler() {
     static LaunchProfiler p;
     return p;
+}
+hipError_t prepare_kernels() {
+    static std::once_flag once;
+    static hipError_t result = hipSuccess;
+    std::call_once(once, [] {
+        result = attn_prepare_kernels();
+        if (result == hipSuccess) result = gemm_prepare_kernels();
+    });
+    return result;
 }
 }  // namespace lga
 
@@ -108,6 +118,19 @@ int validate_config(const lga_config *c) {
         if (((long)c->group * c->micro_batch * c->seq_len) % 8 != 0)
             return fail(LGA_ERR_SHAPE, "the 16-bit modes need group * micro_batch * seq_len to be a multiple of 8");
     }
+    // the 16-bit GEMMs address the 256 rows of an operand tile with 32-bit byte offsets inside a 1 GiB window, which
+    // bounds every leading dimension: the widths, and the token count of one group (the weight-gradient GEMMs
+    // contract over at least one group's tokens, stored with that pitch plus 64)
+    if (c->dtype != LGA_FP32) {
+        const long widest = std::max<long>(3L * c->d_model, c->d_ff);
+        const long t_group = (long)c->group * c->micro_batch * c->seq_len;
+        if (widest > kGemmMaxLd || t_group + 64 > kGemmMaxLd)
+            return fail(LGA_ERR_SHAPE, "the 16-bit modes need 3 d_model, d_ff and group * micro_batch * seq_len + 64 to "
+                                       "stay within 2 097 151 (leading dimensions of the GEMM operands)");
+        if (c->wgrad_groups > 1 && (long)c->wgrad_groups * t_group + 64 > kGemmMaxLd)
+            return fail(LGA_ERR_SHAPE, "wgrad_groups * group * micro_batch * seq_len + 64 must stay within 2 097 151 "
+                                       "(row pitch of the merged weight-gradient GEMMs' operands); 0 chooses a count that does");
+    }
     // kernels index rows and columns with int and elements with size_t
     const double tokens_group = (double)c->group * c->micro_batch * c->seq_len;
     if (tokens_group > 1.0e9 || 3.0 * c->d_model > 2.0e9 || (double)c->n_heads * c->micro_batch * c->group * ((c->seq_len + 127) / 128) > 2.0e9)
@@ -170,8 +193,9 @@ Plan make_plan(const lga_config &c) {
     size_t wb = c.wgrad_groups ? (size_t)c.wgrad_groups : 1;
     if (is16 && c.wgrad_groups == 0) {
         // automatic: as many groups as keep these buffers within a quarter of everything else
+        // ... and keep their row pitch within what the GEMM's loads can address
         wb = groups;
-        while (wb > 1 && rows * (wb * t + 64) * 2 > off / 4) --wb;
+        while (wb > 1 && (rows * (wb * t + 64) * 2 > off / 4 || wb * t + 64 > (size_t)kGemmMaxLd)) --wb;
     }
     p.wgrad_groups = (int)wb;
     p.ldk = wb * t + 64;
@@ -266,9 +290,12 @@ struct lga_stack {
 
 namespace {
 
+// Set when a GEMM launcher refused its arguments (validate_config rules that out); finish() turns it into an error.
+bool g_gemm_refused = false;
+
 template <class T> void gemm(const GemmParams<T> &p, bool akm, bool bkm, Epilogue e, hipStream_t s) {
     if constexpr (std::is_same<T, float>::value) launch_gemm_f32(p, akm, bkm, e, s);
-    else launch_gemm_mfma<T>(p, akm, bkm, e, s);
+    else if (!launch_gemm_mfma<T>(p, akm, bkm, e, s)) g_gemm_refused = true;
 }
 
 // The weights the GEMMs read: fp32 masters in fp32 mode, the 16-bit copy in the 16-bit modes.
@@ -587,6 +614,23 @@ int check_adam(const lga_adam *a) {
 int finish(const char *what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(LGA_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+    if (g_gemm_refused) {
+        g_gemm_refused = false;
+        return fail(LGA_ERR_SHAPE, std::string(what) + ": a GEMM launch was refused (operand layout or leading dimension)");
+    }
+    return LGA_OK;
+}
+
+// The sweeps enqueue thousands of launches and copies, set function attributes on first use and (with a second
+// stream or offload) record and wait for events; none of that has been shown to work on a stream that is being
+// captured into a HIP graph, so such a stream is refused before anything is enqueued.
+int refuse_capture(const lga_stack *st, const char *what) {
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    const hipError_t e = hipStreamIsCapturing(st->stream, &status);
+    if (e != hipSuccess) (void)hipGetLastError();       // the legacy stream cannot even be asked while another stream captures
+    if (e != hipSuccess || status != hipStreamCaptureStatusNone)
+        return fail(LGA_ERR_STATE, std::string(what) + ": the stack's stream is being captured into a graph (or cannot be "
+                                   "used while another stream is): graph capture of the layer sweeps is not supported");
     return LGA_OK;
 }
 
@@ -859,6 +903,14 @@ int lga_init_stack(const lga_config *cfg, const float *host_params, lga_stack **
     if (!out) return fail(LGA_ERR_ARG, "out is NULL");
     *out = nullptr;
     if (int rc = validate_config(cfg)) return rc;
+    {
+        // dynamic-LDS limits of the large kernels, once per process and before any launch
+        const hipError_t pe = prepare_kernels();
+        if (pe != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(LGA_ERR_HIP, std::string("raising the kernels' dynamic LDS limit: ") + hipGetErrorString(pe));
+        }
+    }
     lga_stack *st = new (std::nothrow) lga_stack();
     if (!st) return fail(LGA_ERR_OOM, "host allocation failed");
     st->cfg = *cfg;
@@ -966,6 +1018,7 @@ void lga_destroy_stack(lga_stack *st) {
 
 int lga_forward_layered(lga_stack *st, const void *x, void *y) {
     if (!st || !x) return fail(LGA_ERR_ARG, "NULL argument");
+    if (int rc = refuse_capture(st, "lga_forward_layered")) return rc;
     int rc = LGA_DISPATCH(st, forward_layered_t, st, x, y);
     if (rc == LGA_OK) st->set_forward(true);
     return rc;
@@ -978,12 +1031,14 @@ int lga_backward_layered(lga_stack *st, const void *dy, void *dx, const lga_adam
         return fail(LGA_ERR_STATE, "unfused backward with a single gradient buffer would lose all but one layer's gradient");
     if (fused)
         if (int rc = check_adam(fused)) return rc;
+    if (int rc = refuse_capture(st, "lga_backward_layered")) return rc;
     return LGA_DISPATCH(st, backward_layered_t, st, dy, dx, fused);
 }
 
 int lga_forward_layer(lga_stack *st, int32_t layer, const void *x_in, void *x_out) {
     if (int rc = check_layer(st, layer)) return rc;
     if (!x_in) return fail(LGA_ERR_ARG, "x_in is NULL");
+    if (int rc = refuse_capture(st, "lga_forward_layer")) return rc;
     int rc = LGA_DISPATCH(st, forward_layer_t, st, layer, x_in, x_out);
     if (rc == LGA_OK) {
         st->input_valid[layer] = 1;
@@ -1000,6 +1055,7 @@ int lga_backward_layer(lga_stack *st, int32_t layer, const void *dy, void *dx, c
         return fail(LGA_ERR_STATE, "lga_backward_layer needs a preceding forward of this layer with its current weights");
     if (fused)
         if (int rc = check_adam(fused)) return rc;
+    if (int rc = refuse_capture(st, "lga_backward_layer")) return rc;
     return LGA_DISPATCH(st, backward_layer_t, st, layer, dy, dx, fused);
 }
 
@@ -1012,6 +1068,7 @@ int lga_step_mbmajor(lga_stack *st, const void *x, const void *dy, void *y, void
                                    "offload_checkpoints");
     if (adam)
         if (int rc = check_adam(adam)) return rc;
+    if (int rc = refuse_capture(st, "lga_step_mbmajor")) return rc;
     return LGA_DISPATCH(st, step_mbmajor_t, st, x, dy, y, dx, adam);
 }
 
@@ -1021,6 +1078,7 @@ int lga_adam_step_layer(lga_stack *st, int32_t layer, const lga_adam *adam) {
     if (int rc = check_adam(adam)) return rc;
     if (st->grad_owner[st->grad_slot(layer)] != layer)
         return fail(LGA_ERR_STATE, "no accumulated gradient is available for this layer");
+    if (int rc = refuse_capture(st, "lga_adam_step_layer")) return rc;
     adam_layer(st, layer, *adam);
     st->input_valid[layer] = 0;
     return finish("lga_adam_step_layer");

@@ -53,6 +53,11 @@ def test_parameter_count_follows_table_b1_closed_form():
     (dict(attention=2), B.LGA_ERR_ARG), (dict(offload_checkpoints=2), B.LGA_ERR_ARG),
     (dict(dtype=B.LGA_BF16, d_model=128, n_heads=4, d_ff=500), B.LGA_ERR_SHAPE),
     (dict(seq_len=0), B.LGA_ERR_SHAPE),
+    # leading dimensions of the 16-bit GEMM operands end at 2 097 151 elements: one group's tokens + 64 ...
+    (dict(dtype=B.LGA_BF16, d_model=64, n_heads=4, d_ff=256, seq_len=2097088, micro_batch=1, n_micro=1), B.LGA_ERR_SHAPE),
+    # ... and an explicit number of merged weight-gradient groups times that
+    (dict(dtype=B.LGA_BF16, d_model=64, n_heads=4, d_ff=256, seq_len=1048576, micro_batch=1, n_micro=4, wgrad_groups=2),
+     B.LGA_ERR_SHAPE),
 ])
 def test_bad_configurations_are_refused_on_the_host(kw, code):
     out = C.c_uint64()
@@ -61,6 +66,17 @@ def test_bad_configurations_are_refused_on_the_host(kw, code):
     h = C.c_void_p()
     assert B.lib.lga_init_stack(C.byref(cfg(**kw)), None, C.byref(h)) == code
     assert not h.value
+
+
+def test_automatic_merging_of_weight_gradient_gemms_respects_the_leading_dimension_limit():
+    # 4 groups of 1 048 576 tokens: two of them side by side would need a row pitch of 2 097 216 > 2 097 151, so the
+    # automatic choice must be 1 group per GEMM - the arena of the explicit setting
+    # (64 layers: their checkpoints make the arena large enough that the memory rule alone would merge all four)
+    long = dict(dtype=B.LGA_BF16, n_layers=64, d_model=64, n_heads=4, d_ff=256, seq_len=1048576, micro_batch=1, n_micro=4)
+    assert B.arena_bytes(cfg(**long, wgrad_groups=0)) == B.arena_bytes(cfg(**long, wgrad_groups=1))
+    # a quarter as long: all four groups fit one pitch, and the automatic choice merges them
+    shorter = dict(long, seq_len=262144)
+    assert B.arena_bytes(cfg(**shorter, wgrad_groups=0)) == B.arena_bytes(cfg(**shorter, wgrad_groups=4))
 
 
 def test_large_heads_get_a_workspace_for_the_gemm_built_attention():
@@ -245,4 +261,5 @@ def test_init_without_a_gpu_reports_a_hip_error_instead_of_crashing():
         pytest.skip("a GPU is present")
     h = C.c_void_p()
     assert B.lib.lga_init_stack(C.byref(cfg()), None, C.byref(h)) == B.LGA_ERR_HIP
-    assert "hipMalloc" in B.last_error()
+    # the first HIP call of lga_init_stack (raising the large kernels' dynamic LDS limit) is the one that fails
+    assert "dynamic LDS limit" in B.last_error() or "hipMalloc" in B.last_error()
