@@ -76,6 +76,20 @@ int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int3
                   float *scratch, void *stream);
 uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols);
 
+/* lga_op_colsum for callers that cannot allocate device memory or hand over a workspace: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as lga_op_colsum (same two
+ * kernels, bit-identical output) without `scratch`: the partial sums go to a 16 MiB array that is part of the library's
+ * device image (one copy per GPU, kept until the process ends).  The call allocates nothing - no device or host
+ * memory, no events (its launches are left out of lga_profile_begin/end) - and enqueues two kernels on `stream`.
+ * LGA_ERR_SHAPE if lga_op_colsum_scratch_floats(rows, cols) exceeds lga_op_colsum_static_max_floats() (4 194 304),
+ * i.e. if ceil(rows / 128) x 2 x cols floats of partial sums do not fit.
+ * All calls on one GPU share that one array: two calls whose kernels may overlap in time (different streams, or
+ * different host threads) race on it; calls on one stream are ordered and safe.  Nothing has to be cleared between
+ * calls: every partial sum the second kernel reads is written by the first kernel of the same call. */
+int lga_op_colsum_static(int32_t dtype, const void *a, int32_t rows, int32_t cols, int32_t ld, float beta, float *out,
+                         void *stream);
+uint64_t lga_op_colsum_static_max_floats(void);
+
 /* Softmax attention per (sequence, head), scores scaled by 1/sqrt(d_h) (section 5, "Model").
  * causal != 0: position i attends to positions j <= i (decoder); causal == 0: to the whole sequence (encoder).
  *  qkv  [n_seq*s, 3*heads*dh]: columns [Q | K | V], head h at columns h*dh inside each third

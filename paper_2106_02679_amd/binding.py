@@ -103,6 +103,8 @@ SIGNATURES = {
     "lga_op_transpose": (C.c_int, [_vp, _vp, _i32, _i32, C.c_int64, C.c_int64, _vp]),
     "lga_op_colsum": (C.c_int, [_i32, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "lga_op_colsum_scratch_floats": (_u64, [_i32, _i32]),
+    "lga_op_colsum_static": (C.c_int, [_i32, _vp, _i32, _i32, _i32, _f32, _vp, _vp]),
+    "lga_op_colsum_static_max_floats": (_u64, []),
     "lga_op_attention_fwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
     "lga_op_attention_bwd": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
     "lga_op_attention_gemm_workspace_bytes": (_u64, [_i32, _i32]),

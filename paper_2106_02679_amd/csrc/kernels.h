@@ -38,10 +38,11 @@ void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const f
 //   out0[c] = beta * out0[c] + sum_r a[r, c]
 //   out1[c] = beta * out1[c] + sum_r a[r, c] * (x[r, c] - mean[r]) * rstd[r]     (only if out1 != NULL)
 // a and x have leading dimension ld.  partial must hold colsum_partial_floats(rows, cols) floats.
+// timed = false keeps the launch out of the per-launch profile (no events are created for it).
 size_t colsum_partial_floats(int rows, int cols);
 template <class T>
 void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd, int rows, int cols, int ld,
-                   float beta, float *out0, float *out1, float *partial, hipStream_t s);
+                   float beta, float *out0, float *out1, float *partial, hipStream_t s, bool timed = true);
 
 // out[c][r] = in[r][c] for matrices of 16-bit elements of any format; R, C, ldi, ldo multiples of 8, 16-byte
 // aligned bases.

@@ -1,6 +1,7 @@
 // Kernel-level C ABI (include/lga_ops.h): one kernel per call on caller-owned device buffers.
 #include "../../include/lga_ops.h"
 
+#include <mutex>
 #include <string>
 
 #include "kernels.h"
@@ -35,9 +36,68 @@ template <class F> void with16(int32_t dt, F &&body) {
 template <class E> const E *in16(const void *p) { return static_cast<const E *>(p); }
 template <class E> E *out16(void *p) { return static_cast<E *>(p); }
 
+// ---- lga_op_colsum_static: the column sums with their partial results in memory that is part of the library's image
+// One copy of this array exists on every GPU the library's code object is loaded on, at its own address there, for as
+// long as the process lives.  In host code its name is only a handle for hipGetSymbolAddress; the address the kernels
+// get is looked up once per device and kept.
+constexpr size_t kStaticScratchFloats = (size_t)4 << 20;         // 16 MiB
+static __device__ __align__(256) float static_scratch[kStaticScratchFloats];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+float *g_static_ptr[kMaxDevices];                                // per device, null until first used there
+
+// Address of the current device's copy of static_scratch (looked up on the first call on that device).
+int static_scratch_ptr(float **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return err(LGA_ERR_HIP, (std::string("hipGetDevice: ") + hipGetErrorString(e)).c_str());
+    if (dev < 0 || dev >= kMaxDevices) return err(LGA_ERR_HIP, "device index out of the supported range");
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return err(LGA_ERR_HIP, (std::string("hipGetSymbolAddress(static_scratch): ") + hipGetErrorString(e)).c_str());
+        }
+        g_static_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_static_ptr[dev];
+    return LGA_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+uint64_t lga_op_colsum_static_max_floats(void) { return kStaticScratchFloats; }
+
+int lga_op_colsum_static(int32_t dtype, const void *a, int32_t rows, int32_t cols, int32_t ld, float beta, float *out,
+                         void *stream) {
+    if (!dtype_ok(dtype)) return err(LGA_ERR_ARG, "bad dtype");
+    if (rows < 0 || cols < 0 || ld < cols) return err(LGA_ERR_SHAPE, "bad shape");
+    if ((!a && rows > 0) || !out) return err(LGA_ERR_ARG, "NULL argument");
+    const size_t need = colsum_partial_floats(rows, cols);
+    if (need > kStaticScratchFloats)
+        return err(LGA_ERR_SHAPE, ("lga_op_colsum_static: rows x cols needs " + std::to_string(need) +
+                                   " floats of partial sums, the built-in scratch holds " +
+                                   std::to_string(kStaticScratchFloats) + " (use lga_op_colsum with a workspace)").c_str());
+    float *scratch = nullptr;
+    if (int rc = static_scratch_ptr(&scratch)) return rc;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // Every partial sum the second pass reads is written by the first pass of the same call, so nothing needs to be
+    // cleared between calls.  timed = false: no events are created for these launches.
+    if (dtype == LGA_FP32)
+        launch_colsum<float>(static_cast<const float *>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr,
+                             scratch, s, false);
+    else
+        with16(dtype, [&](auto tag) {
+            using E = decltype(tag);
+            launch_colsum<E>(in16<E>(a), nullptr, nullptr, nullptr, rows, cols, ld, beta, out, nullptr, scratch, s, false);
+        });
+    return done("lga_op_colsum_static");
+}
 
 int lga_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t epilogue, int32_t M, int32_t N, int32_t K,
                 const void *A, int32_t lda, const void *B, int32_t ldb, void *out, void *out2, float *outf,

@@ -25,7 +25,9 @@ LaunchProfiler &profiler();
 // RAII bracket around one launch.  flops / bytes are the algorithmic work of that launch.
 class ProfScope {
   public:
-    ProfScope(const char *name, double flops, double bytes, hipStream_t s) : stream_(s), active_(profiler().enabled) {
+    // timed = false: never bracket this launch (for callers that must not create events)
+    ProfScope(const char *name, double flops, double bytes, hipStream_t s, bool timed = true)
+        : stream_(s), active_(timed && profiler().enabled) {
         if (!active_) return;
         LaunchRecord r{name, flops, bytes, nullptr, nullptr};
         if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {

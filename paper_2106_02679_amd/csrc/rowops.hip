@@ -643,11 +643,11 @@ size_t colsum_partial_floats(int rows, int cols) {
 
 template <class T>
 void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd, int rows, int cols, int ld,
-                   float beta, float *out0, float *out1, float *partial, hipStream_t s) {
+                   float beta, float *out0, float *out1, float *partial, hipStream_t s, bool timed) {
     if (cols == 0) return;
     constexpr int VMAX = VecOf<T>::N;
     ProfScope scope(out1 ? "colsum_kernels(with xhat)" : "colsum_kernels", (out1 ? 4.0 : 1.0) * rows * cols,
-                    (out1 ? 2.0 : 1.0) * sizeof(T) * rows * (double)cols, s);
+                    (out1 ? 2.0 : 1.0) * sizeof(T) * rows * (double)cols, s, timed);
     const int chunks = rows > 0 ? (rows + kColsumRows - 1) / kColsumRows : 0;
     const bool vec = (cols % VMAX == 0) && (ld % VMAX == 0) && aligned16(a) && (x == nullptr || aligned16(x));
     if (chunks > 0) {
@@ -673,11 +673,11 @@ void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd,
                        out0, out1);
 }
 template void launch_colsum<float>(const float *, const float *, const float *, const float *, int, int, int, float,
-                                   float *, float *, float *, hipStream_t);
+                                   float *, float *, float *, hipStream_t, bool);
 template void launch_colsum<bf16>(const bf16 *, const bf16 *, const float *, const float *, int, int, int, float,
-                                  float *, float *, float *, hipStream_t);
+                                  float *, float *, float *, hipStream_t, bool);
 template void launch_colsum<f16>(const f16 *, const f16 *, const float *, const float *, int, int, int, float,
-                                  float *, float *, float *, hipStream_t);
+                                  float *, float *, float *, hipStream_t, bool);
 
 void launch_transpose16(const void *in, void *out, int R, int C, long ldi, long ldo, hipStream_t s) {
     if (R == 0 || C == 0) return;
