@@ -169,19 +169,34 @@ class BoardSampler:
                 "source": "rocm-smi --showclocks --showpower, one sample per second during the timed steps"}
 
 
-def tensor_audit(torch, B, ptr, count, tdt):
-    """finite? / rms / largest magnitude of `count` elements of type tdt at device (or pinned host) address ptr."""
-    t = torch.empty(count, device="cuda", dtype=tdt)
-    B.copy_device(t.data_ptr(), ptr, t.numel() * t.element_size())
-    torch.cuda.synchronize()
-    finite = torch.isfinite(t)
-    n_bad = int(t.numel() - int(finite.sum()))
-    sq, mx = 0.0, 0.0
-    for part in t.split(1 << 28):           # float64 sums of squares, in pieces that keep the temporaries small
-        p = torch.nan_to_num(part.double(), nan=0.0, posinf=0.0, neginf=0.0)
+AUDIT_CHUNK = 1 << 28          # elements per piece of a read-back (at most 1 GiB of fp32 on the device at a time)
+
+
+def tensor_audit(torch, B, ptr, count, tdt, keep=False, against=None):
+    """finite? / rms / largest magnitude of `count` elements of type tdt at device (or pinned host) address ptr, read
+    piece by piece.  keep: also return a device copy of the whole tensor; against: a tensor from an earlier call with
+    keep - the relative change ||now - then|| / ||then|| is added to the result."""
+    esz = torch.empty((), dtype=tdt).element_size()
+    whole = torch.empty(count, device="cuda", dtype=tdt) if keep else None
+    n_bad, sq, mx, num, den = 0, 0.0, 0.0, 0.0, 0.0
+    for off in range(0, count, AUDIT_CHUNK):
+        n = min(AUDIT_CHUNK, count - off)
+        t = whole[off:off + n] if keep else torch.empty(n, device="cuda", dtype=tdt)
+        B.copy_device(t.data_ptr(), ptr + off * esz, n * esz)
+        torch.cuda.synchronize()
+        n_bad += int(n - int(torch.isfinite(t).sum()))
+        p = torch.nan_to_num(t.double(), nan=0.0, posinf=0.0, neginf=0.0)
         sq += float((p * p).sum())
-        mx = max(mx, float(p.abs().max())) if p.numel() else mx
-    return {"all_finite": n_bad == 0, "nonfinite_count": n_bad, "rms": (sq / max(1, t.numel())) ** 0.5, "abs_max": mx}, t
+        mx = max(mx, float(p.abs().max()))
+        if against is not None:
+            q = against[off:off + n].double()
+            num += float((p - q).pow(2).sum())
+            den += float((q * q).sum())
+        del p, t
+    out = {"all_finite": n_bad == 0, "nonfinite_count": n_bad, "rms": (sq / max(1, count)) ** 0.5, "abs_max": mx}
+    if against is not None:
+        out["relative_change"] = (num / den) ** 0.5 if den > 0 else None
+    return out, whole
 
 
 def profile_figures(workload, kernel):
@@ -252,7 +267,7 @@ def main():
         # layer 0's weights as initialised, kept (if they fit) to report how far the timed steps moved them
         ptr, n = st.params(0)
         free, _ = torch.cuda.mem_get_info()
-        a0, w_start = tensor_audit(torch, B, ptr, n, torch.float32) if free > 3 * 4 * n + (8 << 30) else (None, None)
+        a0, w_start = tensor_audit(torch, B, ptr, n, torch.float32, keep=free > 4 * n + (24 << 30))
         audit = {"adam_lr": args.lr, "weights_layer0_start": a0}
 
     marks = []      # per timed step: events at its start, between the sweeps, at its end
@@ -291,6 +306,8 @@ def main():
         st.profile_begin()
         step(t, timed=True); t += 1
         per_step_stats.append(st.profile_end())
+        # one line per finished step on stderr: a run under a profiler or a watchdog shows that it is alive
+        print(f"[bench] step {len(per_step_stats)}/{args.steps} done", file=sys.stderr, flush=True)
     e1.record()
     torch.cuda.synchronize()
     board = sampler.stop()
@@ -362,14 +379,9 @@ def main():
         ptr, nbytes = st.checkpoint(w.n_layers)
         audit["output_y"], _ = tensor_audit(torch, B, ptr, nbytes // (2 if is16 else 4), tdt)
         ptr, n = st.params(0)
-        audit["weights_layer0_end"], w_end = tensor_audit(torch, B, ptr, n, torch.float32)
-        if w_start is not None:
-            num = den = 0.0
-            for a, b in zip(w_end.split(1 << 28), w_start.split(1 << 28)):
-                num += float((a.double() - b.double()).pow(2).sum())
-                den += float(b.double().pow(2).sum())
-            audit["weights_layer0_relative_change"] = (num / den) ** 0.5 if den > 0 else None
-        del w_end, w_start
+        audit["weights_layer0_end"], _ = tensor_audit(torch, B, ptr, n, torch.float32, against=w_start)
+        audit["weights_layer0_relative_change"] = audit["weights_layer0_end"].pop("relative_change", None)
+        del w_start
         try:
             last = 0 if args.order == "layered" else w.n_layers - 1        # the layer whose gradient the buffer still holds
             ptr, n = st.grads(last)
