@@ -601,6 +601,44 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
 #pragma unroll
         for (int f = 0; f < FM + FN; ++f) load_frag(ks, qa, f);
     };
+    // The same two operations for the unrolled main loop, where the ring slot is a compile-time constant.  A wavefront
+    // issues strictly in order and, being alone on its SIMD, has nobody to fill the matrix pipe while it issues
+    // anything else: measured, every instruction of the loop that is not an MFMA costs about four cycles of MFMA
+    // time (64 MFMAs of 32 cycles per k tile; 126 other instructions made a k tile take 2400 cycles instead of 2048).
+    // So the loop keeps nothing but the loads themselves:
+    //  - LDS operand reads take their address from one of 24 registers set up once - (lane address ^ swizzle term)
+    //    for the four values the term takes, in each of the three 64 KB ranges an immediate offset reaches - plus an
+    //    immediate offset: no address arithmetic per read;
+    //  - the direct-to-LDS loads use one buffer resource per operand for the whole tile and take the k position from
+    //    a scalar offset that advances once per k tile; the LDS destination is a constant.
+    int pa[4][3], pb[4][3];
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            pa[v][r] = (lane_a ^ ((2 * v) << 4)) + r * 65536;
+            pb[v][r] = (lane_b ^ ((2 * v) << 4)) + r * 65536;
+            // opaque to the compiler, which would otherwise fold the range into each read's offset and add it back
+            // with a VALU instruction per read
+            asm volatile("" : "+v"(pa[v][r]), "+v"(pb[v][r]));
+        }
+    auto load_frag_c = [&](int ks, int qa, int f) {          // qa: a constant at every call
+        const bool is_a = f < FM;
+        const int blk = is_a ? f : f - FM;
+        const int v = (((2 * ks) ^ (2 * blk)) & 7) >> 1;
+        const int off = (is_a ? qa : wrap(qa + 1)) * (kSlotElems * 2) + blk * 32 * BK * 2;      // below 160 KB
+        const unsigned char *src = smem_raw + (is_a ? pa[v][off >> 16] : pb[v][off >> 16]) + (off & 0xFFFF);
+        if (is_a) af[ks][blk] = *reinterpret_cast<const x8<E> *>(src);
+        else bf[ks][blk] = *reinterpret_cast<const x8<E> *>(src);
+    };
+    const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a_ptr), rsB = make_rsrc(b_ptr);
+    // DMA instruction i of a full k tile of A or B into (constant) ring slot q; koff: byte offset of the k tile in a row
+    auto dma_c = [&](bool is_a, int q, int koff, int i) {
+        // (two calls: the host pass of the compiler does not take a conditional expression of the resource type)
+        const int vo = is_a ? offA[i] : offB[i];
+        if (is_a) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr)(slot(q) + (i * NW + wave) * 8 * BK), 16, vo, koff, 0, 0);
+        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr)(slot(q) + (i * NW + wave) * 8 * BK), 16, vo, koff, 0, 0);
+    };
     // s_waitcnt immediates (vmcnt in bits 3:0, expcnt 6:4 left at its maximum, lgkmcnt 11:8 = 0): all LDS reads
     // returned and every load landed, or every load but the newest NIA landed.
     constexpr int kWaitVm0 = 0x0070;
@@ -630,8 +668,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     // barrier, together with the three others, finds the load queue full and stalls with its MFMAs behind it.
     static_assert(NIA % (2 * FM) == 0 && NIB % (2 * FM) == 0 && (FM + FN) % FM == 0, "work shares per MFMA group");
     constexpr int RPG = (FM + FN + FM - 2) / (FM - 1);      // LDS reads after each group but the last, which gets none
-    auto k_step = [&](int ks, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, int dfirst, int dpg,
+    // lean_c: the unrolled main loop's forms of the loads (constant slots; dkt is then the k tile's byte offset)
+    auto k_step = [&](auto lean_c, int ks, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, int dfirst, int dpg,
                       bool do_read, int rks, int rqa) {
+        constexpr bool LEAN = decltype(lean_c)::value;
 #pragma unroll
         for (int g = 0; g < FM; ++g) {
 #pragma unroll
@@ -639,11 +679,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
                 acc[g][j] = mfma_32x32x16<E>(bf[ks][j], af[ks][g], acc[g][j]);
             if (do_dma) {
 #pragma unroll
-                for (int u = 0; u < dpg; ++u) dma_one(dma_is_a, dq, dkt, dkrem, dfirst + g * dpg + u);
+                for (int u = 0; u < dpg; ++u) {
+                    if constexpr (LEAN) dma_c(dma_is_a, dq, dkt, dfirst + g * dpg + u);
+                    else dma_one(dma_is_a, dq, dkt, dkrem, dfirst + g * dpg + u);
+                }
             }
             if (do_read) {
 #pragma unroll
-                for (int f = g * RPG; f < (g + 1) * RPG && f < FM + FN; ++f) load_frag(rks, rqa, f);
+                for (int f = g * RPG; f < (g + 1) * RPG && f < FM + FN; ++f) {
+                    if constexpr (LEAN) load_frag_c(rks, rqa, f);
+                    else load_frag(rks, rqa, f);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -664,8 +710,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);      // A(kt+1), A(kt+2); B(kt+2) goes to qa
         constexpr int DA = NIA / (2 * FM), DB = NIB / (2 * FM);
 
-        k_step(0, more2, true, qa2, kt + 2, krem2, 0, DA, true, 2, qa);
-        k_step(1, more2, true, qa2, kt + 2, krem2, NIA / 2, DA, true, 3, qa);
+        k_step(std::false_type{}, 0, more2, true, qa2, kt + 2, krem2, 0, DA, true, 2, qa);
+        k_step(std::false_type{}, 1, more2, true, qa2, kt + 2, krem2, NIA / 2, DA, true, 3, qa);
         // A bare s_barrier: __syncthreads() would add a fence that waits for every load, A(kt+2)'s included.
         // The LDS reads above must have returned before other wavefronts may overwrite those slots.
         if (more2)
@@ -676,11 +722,38 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        k_step(2, more2, false, qa, kt + 2, krem2, 0, DB, more1, 0, qa1);
-        k_step(3, more2, false, qa, kt + 2, krem2, NIB / 2, DB, more1, 1, qa1);
+        k_step(std::false_type{}, 2, more2, false, qa, kt + 2, krem2, 0, DB, more1, 0, qa1);
+        k_step(std::false_type{}, 3, more2, false, qa, kt + 2, krem2, NIB / 2, DB, more1, 1, qa1);
+    };
+    // The same k tile for the unrolled main loop: ring slot qa is a constant, tiles kt+1 and kt+2 exist and are full;
+    // koff2 is the byte offset of k tile kt+2 within a row.
+    auto k_tile_c = [&](int qa, int koff2) {
+        const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);
+        constexpr int DA = NIA / (2 * FM), DB = NIB / (2 * FM);
+        k_step(std::true_type{}, 0, true, true, qa2, koff2, BK, 0, DA, true, 2, qa);
+        k_step(std::true_type{}, 1, true, true, qa2, koff2, BK, NIA / 2, DA, true, 3, qa);
+        __builtin_amdgcn_s_waitcnt(kWaitVmA);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        k_step(std::true_type{}, 2, true, false, qa, koff2, BK, 0, DB, true, 0, qa1);
+        k_step(std::true_type{}, 3, true, false, qa, koff2, BK, NIB / 2, DB, true, 1, qa1);
     };
     int kt = 0, qa = 0;
-    for (; kt + 2 < nk_full; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::true_type{});      // straight-line main loop
+    // Main loop, unrolled over one period of the ring (five k tiles; the slot of A(kt) is 0, 2, 4, 1, 3, 0, ...).
+    {
+        int koff2 = 2 * BK * (int)sizeof(E);
+        for (; kt + 6 < nk_full; kt += 5) {
+            k_tile_c(0, koff2);
+            k_tile_c(2, koff2 + 1 * BK * (int)sizeof(E));
+            k_tile_c(4, koff2 + 2 * BK * (int)sizeof(E));
+            k_tile_c(1, koff2 + 3 * BK * (int)sizeof(E));
+            k_tile_c(3, koff2 + 4 * BK * (int)sizeof(E));
+            koff2 += 5 * BK * (int)sizeof(E);
+        }
+    }
+    for (; kt + 2 < nk_full; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::true_type{});      // what is left of the full tiles
     for (; kt < nk; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::false_type{});              // the last tiles, with tests
 
     if constexpr (EPI != EPI_ACCUM_F32) {
@@ -751,6 +824,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         }
     }
 }
+
+// Explicit instantiations: the host compiler does not always emit the launch stub of a kernel template from its use
+// in the launchers below alone.
+#define LGA_INSTANTIATE_DMA(EPI)                                                                                 \
+    template __global__ void gemm_bf16_dma_kernel<256, 256, 2, 2, EPI, bf16>(GemmParams<bf16>, int, int);        \
+    template __global__ void gemm_bf16_dma_kernel<256, 256, 2, 2, EPI, f16>(GemmParams<f16>, int, int)
+LGA_INSTANTIATE_DMA(EPI_STORE);
+LGA_INSTANTIATE_DMA(EPI_BIAS);
+LGA_INSTANTIATE_DMA(EPI_BIAS_RESID);
+LGA_INSTANTIATE_DMA(EPI_BIAS_GELU);
+LGA_INSTANTIATE_DMA(EPI_MUL_DGELU);
+LGA_INSTANTIATE_DMA(EPI_ACCUM_F32);
+#undef LGA_INSTANTIATE_DMA
 
 // The kernel that serves a (tile size, layout, epilogue) combination and its dynamic LDS in bytes.
 template <int BM, int BN, bool A_KM, bool B_KM, int EPI, class E> struct KernelFor {
