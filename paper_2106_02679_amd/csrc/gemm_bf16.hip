@@ -548,16 +548,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     // Loop-invariant per-lane byte offsets of the DMA loads inside an operand tile (or the poison
     // offset for rows beyond the matrix, which the hardware answers with zeros).
     const int lda2 = p.lda * 2, ldb2 = p.ldb * 2;
+    // DMA instruction i of a wavefront fills tile rows [(wave NIA + i) 8, + 8): 1 KB of LDS, right behind that of
+    // instruction i - 1.  Four consecutive instructions share one LDS base (M0, a scalar write each time it changes)
+    // and tell their places apart by the instruction's immediate offset, 1024 (i % 4) - which the hardware adds to the
+    // memory address too, so the per-lane offsets have it subtracted.  (A row is at least 128 bytes long here - the
+    // launcher sends shorter leading dimensions to the other kernel - so the difference is never negative.)
+    auto dma_row = [&](int i) { return (wave * NIA + i) * 8 + (lane >> 3); };
+    static_assert(NIA == NIB && NIA % 4 == 0, "row mapping and M0 groups below");
     int offA[NIA], offB[NIB];
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
-        const int r = (i * NW + wave) * 8 + (lane >> 3);
-        offA[i] = (m0 + r < p.M) ? r * lda2 + (((lane & 7) ^ swz(r)) << 4) : kBufPoison;
+        const int r = dma_row(i);
+        offA[i] = (m0 + r < p.M) ? r * lda2 + (((lane & 7) ^ swz(r)) << 4) - (i & 3) * 1024 : kBufPoison;
     }
 #pragma unroll
     for (int i = 0; i < NIB; ++i) {
-        const int r = (i * NW + wave) * 8 + (lane >> 3);
-        offB[i] = (n0 + r < p.N) ? r * ldb2 + (((lane & 7) ^ swz(r)) << 4) : kBufPoison;
+        const int r = dma_row(i);
+        offB[i] = (n0 + r < p.N) ? r * ldb2 + (((lane & 7) ^ swz(r)) << 4) - (i & 3) * 1024 : kBufPoison;
     }
     const E *a_ptr = p.A + (size_t)m0 * p.lda;
     const E *b_ptr = p.B + (size_t)n0 * p.ldb;
@@ -570,11 +577,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
     // One DMA instruction: rows [(i NW + wave) 8, +8) of operand tile kt (A if is_a, else B) into ring slot q.
     // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
+    // One direct-to-LDS load: instruction i of a wavefront's share of an operand tile into ring slot q.  The LDS base
+    // is that of the instruction's group of four; the immediate offset (a literal, hence the switch over a value that
+    // is a constant wherever this is called) places it inside the group.
+    auto lds_dma = [&](const __amdgpu_buffer_rsrc_t &r, int q, int i, int voff, int soff) {
+        E *group = slot(q) + (wave * NIA + (i & ~3)) * 8 * BK;
+        switch (i & 3) {
+            case 0: __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)group, 16, voff, soff, 0, 0); break;
+            case 1: __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)group, 16, voff, soff, 1024, 0); break;
+            case 2: __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)group, 16, voff, soff, 2048, 0); break;
+            default: __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)group, 16, voff, soff, 3072, 0); break;
+        }
+    };
     auto dma_one = [&](bool is_a, int q, int kt, int krem, int i) {
         const __amdgpu_buffer_rsrc_t r = make_rsrc((is_a ? a_ptr : b_ptr) + (size_t)kt * BK);
         int off = is_a ? offA[i] : offB[i];
-        if (krem < BK) off |= ((((lane & 7) ^ swz((i * NW + wave) * 8 + (lane >> 3))) * 8 < krem) ? 0 : kBufPoison);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)(slot(q) + (i * NW + wave) * 8 * BK), 16, off, 0, 0, 0);
+        if (krem < BK) off |= ((((lane & 7) ^ swz(dma_row(i))) * 8 < krem) ? 0 : kBufPoison);
+        lds_dma(r, q, i, off, 0);
     };
     // MFMA operands of the four k steps of a tile, one register buffer each: a step's operands are read
     // from LDS two steps (32 MFMAs) ahead, which rides out the LDS latency spikes that the incoming DMA
@@ -636,8 +655,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     auto dma_c = [&](bool is_a, int q, int koff, int i) {
         // (two calls: the host pass of the compiler does not take a conditional expression of the resource type)
         const int vo = is_a ? offA[i] : offB[i];
-        if (is_a) __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr)(slot(q) + (i * NW + wave) * 8 * BK), 16, vo, koff, 0, 0);
-        else __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr)(slot(q) + (i * NW + wave) * 8 * BK), 16, vo, koff, 0, 0);
+        if (is_a) lds_dma(rsA, q, i, vo, koff);
+        else lds_dma(rsB, q, i, vo, koff);
     };
     // s_waitcnt immediates (vmcnt in bits 3:0, expcnt 6:4 left at its maximum, lgkmcnt 11:8 = 0): all LDS reads
     // returned and every load landed, or every load but the newest NIA landed.
@@ -920,13 +939,15 @@ template <bool A_KM, bool B_KM, int EPI, class E> void launch_tiles(const GemmPa
         // many small problems (the products of attention, one per head): enough work items either way, so take the
         // tile size that pads the output less, the large one on a tie
         const double pad256 = (double)big * 65536.0, pad128 = (double)((p.M + 127) / 128) * ((p.N + 127) / 128) * 16384.0;
-        if (big * p.batch >= 128 && pad256 <= 1.15 * pad128)
+        const bool short_rows = A_KM && B_KM && (p.lda < BK || p.ldb < BK);      // see below
+        if (big * p.batch >= 128 && pad256 <= 1.15 * pad128 && !short_rows)
             launch_one<256, 256, A_KM, B_KM, EPI, E>(p, s);
         else
             launch_one<128, 128, A_KM, B_KM, EPI, E>(p, s);
         return;
     }
-    if (big >= 128) {
+    // (the direct-to-LDS kernel wants rows of at least 128 bytes: see its per-lane load offsets)
+    if (big >= 128 && !(A_KM && B_KM && (p.lda < BK || p.ldb < BK))) {
         if constexpr (A_KM && B_KM) {
             const int tm = (p.M + 255) / 256, tn = (p.N + 255) / 256;
             if (tm % 16 == 0 && tn % 16 == 0) {                  // + 1 % on the weight-gradient shapes of d = 12288
