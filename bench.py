@@ -122,22 +122,65 @@ def cpu_baseline(w, n_micro, seq_len, causal=True):
                       f"the sample); tokens/s scaled by 1/{w.n_layers} layers"}
 
 
-class BoardSampler:
-    """Clock and power of GPU 0 as rocm-smi reports them, sampled about once a second by a thread of its own while the
-    timed steps run (a child process per sample: host-side only, nothing is enqueued on the GPU)."""
+def gpu0_pci_address(torch):
+    """'dddd:bb:dd.f' of cuda:0, or None where this torch does not report it."""
+    try:
+        p = torch.cuda.get_device_properties(0)
+        return f"{p.pci_domain_id:04x}:{p.pci_bus_id:02x}:{p.pci_device_id:02x}.0"
+    except Exception:
+        return None
 
-    def __init__(self, period=1.0):
+
+class BoardSampler:
+    """Clock and power of GPU 0, sampled about once a second by a thread of its own while the timed steps run (host-side
+    only, nothing is enqueued on the GPU).  Read from the driver's sysfs files of the device with GPU 0's PCI address;
+    where those cannot be read, from `rocm-smi` in a child process - but not under a profiler, whose preloaded library
+    would come up inside that child."""
+
+    def __init__(self, period=1.0, pci=None):
+        import glob
         import shutil
         import threading
-        self.exe = shutil.which("rocm-smi") or ("/opt/rocm/bin/rocm-smi" if os.path.exists("/opt/rocm/bin/rocm-smi") else None)
         self.period = period
         self.samples = []           # (sclk MHz or None, W or None)
+        self.sysfs = None
+        if pci:
+            for dev in glob.glob("/sys/class/drm/card*/device"):
+                if os.path.realpath(dev).lower().endswith(pci.lower()) and os.access(os.path.join(dev, "pp_dpm_sclk"), os.R_OK):
+                    self.sysfs = dev
+        under_profiler = any("rocprof" in os.environ.get(k, "").lower() for k in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES", "HSA_TOOLS_LIB"))
+        self.exe = None
+        if not self.sysfs and not under_profiler:
+            self.exe = shutil.which("rocm-smi") or ("/opt/rocm/bin/rocm-smi" if os.path.exists("/opt/rocm/bin/rocm-smi") else None)
         self._stop = threading.Event()
-        self._thread = threading.Thread(target=self._run, daemon=True) if self.exe else None
+        self._thread = threading.Thread(target=self._run, daemon=True) if (self.sysfs or self.exe) else None
+
+    def _once_sysfs(self):
+        import glob
+        import re
+        sclk = pw = None
+        try:
+            cur = [l for l in open(os.path.join(self.sysfs, "pp_dpm_sclk")).read().splitlines() if l.rstrip().endswith("*")]
+            m = re.search(r"(\d+)\s*mhz", cur[0].lower()) if cur else None
+            sclk = int(m.group(1)) if m else None
+        except OSError:
+            pass
+        for name in ("power1_average", "power1_input"):
+            for f in glob.glob(os.path.join(self.sysfs, "hwmon", "hwmon*", name)):
+                try:
+                    pw = int(open(f).read().strip()) / 1e6          # microwatts
+                except (OSError, ValueError):
+                    continue
+                break
+            if pw is not None:
+                break
+        self.samples.append((sclk, pw))
 
     def _once(self):
         import re
         import subprocess
+        if self.sysfs:
+            return self._once_sysfs()
         try:
             txt = subprocess.run([self.exe, "-d", "0", "--showclocks", "--showpower"], capture_output=True, text=True,
                                  timeout=10).stdout
@@ -166,7 +209,8 @@ class BoardSampler:
         mean = lambda v: sum(v) / len(v) if v else None
         return {"samples": len(self.samples), "sclk_mhz_mean": mean(clk), "sclk_mhz_min": min(clk) if clk else None,
                 "sclk_mhz_max": max(clk) if clk else None, "power_w_mean": mean(pw), "power_w_max": max(pw) if pw else None,
-                "source": "rocm-smi --showclocks --showpower, one sample per second during the timed steps"}
+                "source": (f"sysfs {self.sysfs}: pp_dpm_sclk, hwmon power" if self.sysfs else "rocm-smi --showclocks --showpower")
+                          + ", one sample per second during the timed steps"}
 
 
 AUDIT_CHUNK = 1 << 28          # elements per piece of a read-back (at most 1 GiB of fp32 on the device at a time)
@@ -290,12 +334,24 @@ def main():
             ev[2].record()
             marks.append(ev)
 
+    # The last warm-up step is bracketed launch by launch: it names the dominant kernel and gives the per-kernel table.
+    # The timed steps bracket that kernel alone (two event records per launch are a measurable share of a step of
+    # thousands of short launches), unless --kernels asks for the table over the timed steps themselves.
     t = 1
-    for _ in range(args.warmup):
+    warm_stats = None
+    for i in range(args.warmup):
+        if i == args.warmup - 1:
+            st.profile_begin()
         step(t); t += 1
+        if i == args.warmup - 1:
+            warm_stats = st.profile_end()
+        print(f"[bench] warm-up step {i + 1}/{args.warmup} enqueued", file=sys.stderr, flush=True)
     torch.cuda.synchronize()
+    only = None
+    if warm_stats and not args.kernels:
+        only = max(warm_stats, key=lambda k: k["ms"])["name"]
     restores0 = st.restore_count()
-    sampler = BoardSampler()
+    sampler = BoardSampler(pci=gpu0_pci_address(torch))
     sampler.start()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
@@ -303,7 +359,7 @@ def main():
     for _ in range(args.steps):
         # the library's per-launch event pairs are collected step by step (lga_profile_end waits for the step to
         # finish: one host round trip per step inside the timed region)
-        st.profile_begin()
+        st.profile_begin(only)
         step(t, timed=True); t += 1
         per_step_stats.append(st.profile_end())
         # one line per finished step on stderr: a run under a profiler or a watchdog shows that it is alive
@@ -319,6 +375,8 @@ def main():
             for key in ("launches", "ms", "flops", "bytes"):
                 m[key] += k[key]
     stats = sorted(merged.values(), key=lambda k: -k["ms"])
+    # per-kernel table: over the timed steps if every launch was bracketed there, else the last warm-up step's
+    table, table_steps = (stats, args.steps) if only is None else (warm_stats, 1)
     restores = (st.restore_count() - restores0) / args.steps
     skipped = sum(st.nonfinite_layers()) if dt == B.LGA_FP16 else 0       # layers whose last update was left out
     ms_step = ms_total / args.steps
@@ -391,8 +449,8 @@ def main():
         audit["all_finite"] = all(v["all_finite"] for k, v in audit.items() if isinstance(v, dict) and "all_finite" in v)
         audit["board"] = board
 
-    gemm_ms = sum(k["ms"] for k in stats if k["name"].startswith("gemm"))
-    gemm_fl = sum(k["flops"] for k in stats if k["name"].startswith("gemm"))
+    gemm_ms = sum(k["ms"] for k in table if k["name"].startswith("gemm")) / table_steps
+    gemm_fl = sum(k["flops"] for k in table if k["name"].startswith("gemm")) / table_steps
     out = {
         "metric": "tokens/sec fwd+bwd+Adam per GPT layer stack (1 GPU)",
         "value": tokens / (ms_step / 1e3),
@@ -408,7 +466,7 @@ def main():
         "ms_per_step_min": min(step_ms), "ms_per_step_max": max(step_ms), "ms_per_step_list": step_ms,
         # layered order: forward sweep / backward sweep with recompute and the per-layer Adam steps (mean over the steps)
         "phase_ms": ({"forward": sum(fwd_ms) / len(fwd_ms), "backward_with_adam": ms_step - sum(fwd_ms) / len(fwd_ms),
-                      "adam_kernels": sum(k["ms"] for k in stats if k["name"].startswith("adam")) / args.steps}
+                      "adam_kernels": sum(k["ms"] for k in table if k["name"].startswith("adam")) / table_steps}
                      if args.order == "layered" else None),
         "restores_per_step": restores,
         "skipped_layer_updates": skipped,
@@ -420,13 +478,14 @@ def main():
         "pct_peak_paper_flops": 100.0 * flops_paper / ms_step / 1e9 / peak,     # 8 p + 9 s^2 d accounting
         "pct_peak_model_flops": 100.0 * flops_model / ms_step / 1e9 / peak,     # 6 p + 7 s^2 d (no recompute)
         "all_gemm_tflops": gemm_fl / gemm_ms / 1e9 if gemm_ms > 0 else None,
-        "all_gemm_share_of_step": gemm_ms / ms_total,
+        "all_gemm_share_of_step": gemm_ms / ms_step,
+        "per_kernel_table_from": "timed steps" if only is None else "last warm-up step (timed steps bracket the dominant kernel only)",
         "model_param_bytes_per_step": param_bytes, "model_grad_bytes_per_step": grad_bytes,
         "roofline": roof,
         "audit": audit,
     }
     if args.kernels:
-        for k in stats:
+        for k in table:
             print(f"{k['name']:<48} n={k['launches']:<6} ms={k['ms']:<10.3f} "
                   f"TFLOP/s={k['flops'] / k['ms'] / 1e9 if k['ms'] else 0:<8.1f} GB/s={k['bytes'] / k['ms'] / 1e6 if k['ms'] else 0:<8.1f}",
                   file=sys.stderr)

@@ -298,13 +298,17 @@ int lga_params_per_layer(const lga_config *cfg, uint64_t *count);
  * synchronises the stack's stream and returns one record per kernel name, sorted by total time:
  * launches, summed event time in ms, and the summed algorithmic flops and HBM bytes of those
  * launches (each operand read once, each result written once).  out holds `capacity` records;
- * *count receives the number of distinct kernels (which may exceed capacity). */
+ * *count receives the number of distinct kernels (which may exceed capacity).
+ * lga_profile_begin_only brackets only the launches whose kernel name starts with `kernel_name` (host string, copied;
+ * NULL or empty: all of them) - two event records per launch are a measurable share of a step made of thousands of
+ * short launches, so a benchmark that needs one kernel's times asks for that kernel alone. */
 typedef struct lga_kernel_stat {
     char name[112];
     uint64_t launches;
     double ms, flops, bytes;
 } lga_kernel_stat;
 int lga_profile_begin(lga_stack *stack);
+int lga_profile_begin_only(lga_stack *stack, const char *kernel_name);
 int lga_profile_end(lga_stack *stack, lga_kernel_stat *out, int32_t capacity, int32_t *count);
 
 const char *lga_last_error(void);

@@ -91,6 +91,7 @@ SIGNATURES = {
     "lga_params_per_layer": (C.c_int, [_P(lga_config), _P(_u64)]),
     "lga_last_error": (C.c_char_p, []),
     "lga_profile_begin": (C.c_int, [_vp]),
+    "lga_profile_begin_only": (C.c_int, [_vp, C.c_char_p]),
     "lga_profile_end": (C.c_int, [_vp, _P(lga_kernel_stat), _i32, _P(_i32)]),
     "lga_op_gemm": (C.c_int, [_i32, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _vp, _vp, _i32,
                               _vp, _vp, _f32, _vp]),
@@ -274,8 +275,12 @@ class Stack:
         check(lib.lga_restore_count(self._h, C.byref(out)))
         return out.value
 
-    def profile_begin(self):
-        check(lib.lga_profile_begin(self._h))
+    def profile_begin(self, only: str | None = None):
+        """Bracket every launch with an event pair, or only those of the kernel whose name starts with `only`."""
+        if only:
+            check(lib.lga_profile_begin_only(self._h, only.encode()))
+        else:
+            check(lib.lga_profile_begin(self._h))
 
     def profile_end(self, capacity: int = 64):
         arr = (lga_kernel_stat * capacity)()

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstring>
 #include <string>
 #include <vector>
 
@@ -17,6 +18,7 @@ struct LaunchRecord {
 
 struct LaunchProfiler {
     bool enabled = false;
+    std::string only;       // not empty: bracket only the launches whose kernel name starts with this
     std::vector<LaunchRecord> records;
 };
 
@@ -28,6 +30,8 @@ class ProfScope {
     // timed = false: never bracket this launch (for callers that must not create events)
     ProfScope(const char *name, double flops, double bytes, hipStream_t s, bool timed = true)
         : stream_(s), active_(timed && profiler().enabled) {
+        if (active_ && !profiler().only.empty() && std::strncmp(name, profiler().only.c_str(), profiler().only.size()) != 0)
+            active_ = false;
         if (!active_) return;
         LaunchRecord r{name, flops, bytes, nullptr, nullptr};
         if (hipEventCreate(&r.start) != hipSuccess || hipEventCreate(&r.stop) != hipSuccess) {

@@ -1159,9 +1159,10 @@ int lga_loss_scaler_update(lga_loss_scaler *sc, int32_t overflowed) {
     return LGA_OK;
 }
 
-int lga_profile_begin(lga_stack *st) {
+static int profile_begin(lga_stack *st, const char *only) {
     if (!st) return fail(LGA_ERR_ARG, "stack is NULL");
     LaunchProfiler &p = profiler();
+    p.only = only ? only : "";
     for (auto &r : p.records) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -1170,6 +1171,9 @@ int lga_profile_begin(lga_stack *st) {
     p.enabled = true;
     return LGA_OK;
 }
+
+int lga_profile_begin(lga_stack *st) { return profile_begin(st, nullptr); }
+int lga_profile_begin_only(lga_stack *st, const char *kernel_name) { return profile_begin(st, kernel_name); }
 
 int lga_profile_end(lga_stack *st, lga_kernel_stat *out, int32_t capacity, int32_t *count) {
     if (!st || !count || (capacity > 0 && !out) || capacity < 0) return fail(LGA_ERR_ARG, "bad argument");
