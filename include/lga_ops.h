@@ -61,15 +61,28 @@ int lga_op_layernorm_fwd(int32_t dtype, const void *x, const float *g, const flo
 /* LayerNorm backward fused with the residual add:
  *   dx = resid + rstd * (g*dy - mean_row(g*dy) - xhat * mean_row(g*dy*xhat))
  *   dgamma = beta*dgamma + sum_rows dy*xhat ;  dbeta = beta*dbeta + sum_rows dy
- * scratch: lga_op_colsum_scratch_floats(rows, d) floats of device memory. */
+ * The two sums are taken inside the dx kernel from the operands it holds anyway (rows of up to 8192 16-bit or 4096
+ * fp32 values; wider rows: by the column-sum kernels, in a pass of their own), block by block into `scratch`, and
+ * added up in block order, so the result does not depend on scheduling.
+ * scratch: lga_op_layernorm_bwd_scratch_floats(rows, d) floats of device memory, 16-byte aligned. */
 int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const float *mean, const float *rstd,
                          const float *g, const void *resid, void *dx, float *dgamma, float *dbeta, float beta,
                          float *scratch, int32_t rows, int32_t d, void *stream);
+uint64_t lga_op_layernorm_bwd_scratch_floats(int32_t rows, int32_t d);
 
 /* out[c][r] = in[r][c] for matrices of 16-bit elements of either format (in: [R][ldi], out: [C][ldo]); R, C, ldi, ldo multiples of 8,
  * 16-byte aligned.  The stack keeps a transposed 16-bit copy of each weight matrix and transposes the
  * two operands of every weight-gradient GEMM so that all GEMM operands are k-contiguous. */
 int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo, void *stream);
+
+/* lga_op_transpose of a matrix of format `dtype` (LGA_BF16 or LGA_FP16) that also returns its column sums,
+ *   sums[c] = beta*sums[c] + sum_r in[r,c],
+ * added up tile by tile as the matrix passes through the transposing kernel: the output gradient of a linear map is
+ * transposed for the weight-gradient GEMM, and its column sums are the bias gradient (section 3: gradients accumulated
+ * per layer), so that gradient costs no pass over memory of its own.  Deterministic (two passes, fixed order).
+ * scratch: lga_op_colsum_scratch_floats(R, C) floats of device memory. */
+int lga_op_transpose_colsum(int32_t dtype, const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo,
+                            float beta, float *sums, float *scratch, void *stream);
 
 /* out[c] = beta*out[c] + sum_r a[r,c]  (bias gradients).  a: [rows][ld]. */
 int lga_op_colsum(int32_t dtype, const void *a, int32_t rows, int32_t cols, int32_t ld, float beta, float *out,

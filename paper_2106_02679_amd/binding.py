@@ -101,7 +101,9 @@ SIGNATURES = {
     "lga_op_layernorm_fwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "lga_op_layernorm_bwd": (C.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _i32, _i32,
                                        _vp]),
+    "lga_op_layernorm_bwd_scratch_floats": (_u64, [_i32, _i32]),
     "lga_op_transpose": (C.c_int, [_vp, _vp, _i32, _i32, C.c_int64, C.c_int64, _vp]),
+    "lga_op_transpose_colsum": (C.c_int, [_i32, _vp, _vp, _i32, _i32, C.c_int64, C.c_int64, _f32, _vp, _vp, _vp]),
     "lga_op_colsum": (C.c_int, [_i32, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp]),
     "lga_op_colsum_scratch_floats": (_u64, [_i32, _i32]),
     "lga_op_colsum_static": (C.c_int, [_i32, _vp, _i32, _i32, _i32, _f32, _vp, _vp]),

@@ -30,9 +30,15 @@ void launch_layernorm_fwd(const T *x, const float *g, const float *b, T *y, floa
                           int rows, int d, float eps, hipStream_t s);
 // LayerNorm backward w.r.t. the input, fused with the residual add:
 //   dx = resid + rstd * (g dy - mean_row(g dy) - xhat * mean_row(g dy xhat))
+// dbeta != NULL: also the gradients of the LayerNorm bias and gain,
+//   dbeta[c] = beta * dbeta[c] + sum_r dy[r, c],   dgamma[c] = beta * dgamma[c] + sum_r dy[r, c] xhat[r, c],
+// added up inside the same kernel where the width allows, by the column-sum kernels otherwise; partial then holds
+// layernorm_bwd_partial_floats(rows, d) floats.
+size_t layernorm_bwd_partial_floats(int rows, int d);
 template <class T>
 void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const float *rstd, const float *g,
-                             const T *resid, T *dx, int rows, int d, hipStream_t s);
+                             const T *resid, T *dx, int rows, int d, hipStream_t s, float beta = 0.f,
+                             float *dbeta = nullptr, float *dgamma = nullptr, float *partial = nullptr);
 
 // Column sums over rows, in two deterministic passes through `partial`:
 //   out0[c] = beta * out0[c] + sum_r a[r, c]
@@ -47,6 +53,11 @@ void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd,
 // out[c][r] = in[r][c] for matrices of 16-bit elements of any format; R, C, ldi, ldo multiples of 8, 16-byte
 // aligned bases.
 void launch_transpose16(const void *in, void *out, int R, int C, long ldi, long ldo, hipStream_t s);
+// The same for format E, and out0[c] = beta * out0[c] + sum_r in[r, c] from the tiles as they pass through the
+// transposing kernel (partial: colsum_partial_floats(R, C) floats).
+template <class E>
+void launch_transpose16_colsum(const E *in, E *out, int R, int C, long ldi, long ldo, float beta, float *out0,
+                               float *partial, hipStream_t s);
 
 // 1 into *flag if any of the n values is infinite or not a number (*flag is not cleared here).
 void launch_nonfinite_flag(const float *g, size_t n, int *flag, hipStream_t s);

@@ -205,18 +205,22 @@ int lga_op_layernorm_bwd(int32_t dtype, const void *dy, const void *x, const flo
         return err(LGA_ERR_ARG, "NULL argument");
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     if (dtype == LGA_FP32) {
-        launch_colsum<float>(static_cast<const float *>(dy), static_cast<const float *>(x), mean, rstd, rows, d, d, beta,
-                             dbeta, dgamma, scratch, s);
         launch_layernorm_bwd_dx<float>(static_cast<const float *>(dy), static_cast<const float *>(x), mean, rstd, g,
-                                       static_cast<const float *>(resid), static_cast<float *>(dx), rows, d, s);
+                                       static_cast<const float *>(resid), static_cast<float *>(dx), rows, d, s, beta, dbeta,
+                                       dgamma, scratch);
     } else {
         with16(dtype, [&](auto tag) {
             using E = decltype(tag);
-            launch_colsum<E>(in16<E>(dy), in16<E>(x), mean, rstd, rows, d, d, beta, dbeta, dgamma, scratch, s);
-            launch_layernorm_bwd_dx<E>(in16<E>(dy), in16<E>(x), mean, rstd, g, in16<E>(resid), out16<E>(dx), rows, d, s);
+            launch_layernorm_bwd_dx<E>(in16<E>(dy), in16<E>(x), mean, rstd, g, in16<E>(resid), out16<E>(dx), rows, d, s,
+                                       beta, dbeta, dgamma, scratch);
         });
     }
     return done("lga_op_layernorm_bwd");
+}
+
+uint64_t lga_op_layernorm_bwd_scratch_floats(int32_t rows, int32_t d) {
+    if (rows < 0 || d < 0) return 0;
+    return layernorm_bwd_partial_floats(rows, d);
 }
 
 int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo, void *stream) {
@@ -226,6 +230,21 @@ int lga_op_transpose(const void *in, void *out, int32_t R, int32_t C, int64_t ld
     if ((!in || !out) && R > 0 && C > 0) return err(LGA_ERR_ARG, "NULL argument");
     launch_transpose16(in, out, R, C, ldi, ldo, reinterpret_cast<hipStream_t>(stream));
     return done("lga_op_transpose");
+}
+
+int lga_op_transpose_colsum(int32_t dtype, const void *in, void *out, int32_t R, int32_t C, int64_t ldi, int64_t ldo,
+                            float beta, float *sums, float *scratch, void *stream) {
+    if (dtype != LGA_BF16 && dtype != LGA_FP16) return err(LGA_ERR_ARG, "a 16-bit dtype is needed");
+    if (R < 0 || C < 0 || ldi < C || ldo < R) return err(LGA_ERR_SHAPE, "bad shape");
+    if (R % 8 || C % 8 || ldi % 8 || ldo % 8 || !a16(in) || !a16(out))
+        return err(LGA_ERR_SHAPE, "transpose needs sizes and leading dimensions that are multiples of 8, 16-byte aligned");
+    if (((!in || !out) && R > 0 && C > 0) || !sums || !scratch) return err(LGA_ERR_ARG, "NULL argument");
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    with16(dtype, [&](auto tag) {
+        using E = decltype(tag);
+        launch_transpose16_colsum<E>(in16<E>(in), out16<E>(out), R, C, ldi, ldo, beta, sums, scratch, s);
+    });
+    return done("lga_op_transpose_colsum");
 }
 
 uint64_t lga_op_colsum_scratch_floats(int32_t rows, int32_t cols) {

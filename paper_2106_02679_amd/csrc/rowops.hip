@@ -279,12 +279,15 @@ __global__ __launch_bounds__(256) void layernorm_bwd_dx_kernel(const T *__restri
 // The same with a block walking over many rows: dy, x and the residual of a row are read once and kept in
 // registers, the gains too, the next row is requested before this row's block-wide sums, and the two sums share one
 // barrier (two scratch rows used in turn).  d <= TH * V * NP.
-template <class T, int V, int TH, int NP>
+// SUMS: every thread also adds up dy and dy * xhat of its columns over the rows its block walks, and the block writes
+// them to partial[blockIdx.x][0 / 1][c] - the first pass of the column sums that give the gradients of the LayerNorm
+// bias and gain (colsum_final_kernel adds the blocks' rows up in a fixed order), from operands that are in registers anyway.
+template <class T, int V, int TH, int NP, bool SUMS>
 __global__ __launch_bounds__(TH) void layernorm_bwd_dx_rows_kernel(const T *__restrict__ dy, const T *__restrict__ x,
                                                                    const float *__restrict__ mean,
                                                                    const float *__restrict__ rstd,
                                                                    const float *__restrict__ g, const T *resid, T *dx,
-                                                                   int rows, int d) {
+                                                                   int rows, int d, float *__restrict__ partial) {
     __shared__ float red[2][2][16];
     float gv[NP][V];
 #pragma unroll
@@ -315,6 +318,11 @@ __global__ __launch_bounds__(TH) void layernorm_bwd_dx_rows_kernel(const T *__re
         nmu = mean[row];
         nrs = rstd[row];
     };
+    float sb[SUMS ? NP : 1][V], sg[SUMS ? NP : 1][V];
+#pragma unroll
+    for (int p = 0; p < (SUMS ? NP : 1); ++p)
+#pragma unroll
+        for (int i = 0; i < V; ++i) sb[p][i] = sg[p][i] = 0.f;
     if (blockIdx.x < (unsigned)rows) request(blockIdx.x);
     int turn = 0;
     for (size_t row = blockIdx.x; row < (size_t)rows; row += gridDim.x, turn ^= 1) {
@@ -327,11 +335,16 @@ __global__ __launch_bounds__(TH) void layernorm_bwd_dx_rows_kernel(const T *__re
             if (c < d) {
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
-                    gd[p][i] = to_f32(na[p].v[i]) * gv[p][i];
+                    const float a = to_f32(na[p].v[i]);
+                    gd[p][i] = a * gv[p][i];
                     xh[p][i] = (to_f32(nx[p].v[i]) - mu) * rs;
                     r[p][i] = to_f32(nr[p].v[i]);
                     s1 += gd[p][i];
                     s2 += gd[p][i] * xh[p][i];
+                    if constexpr (SUMS) {
+                        sb[p][i] += a;
+                        sg[p][i] += a * xh[p][i];
+                    }
                 }
             }
         }
@@ -360,6 +373,21 @@ __global__ __launch_bounds__(TH) void layernorm_bwd_dx_rows_kernel(const T *__re
 #pragma unroll
                 for (int i = 0; i < V; ++i) o[i] = r[p][i] + rs * (gd[p][i] - t1 - xh[p][i] * t2);
                 store_pack<T, V>(dxr + c, o);
+            }
+        }
+    }
+    if constexpr (SUMS) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int c = (p * TH + threadIdx.x) * V;
+            if (c < d) {
+#pragma unroll
+                for (int q = 0; q < V / 4; ++q) {       // 16-byte pieces: partial is 16-byte aligned, c a multiple of 4
+                    const float b4[4] = {sb[p][4 * q], sb[p][4 * q + 1], sb[p][4 * q + 2], sb[p][4 * q + 3]};
+                    const float g4[4] = {sg[p][4 * q], sg[p][4 * q + 1], sg[p][4 * q + 2], sg[p][4 * q + 3]};
+                    store_pack<float, 4>(partial + ((size_t)blockIdx.x * 2 + 0) * d + c + 4 * q, b4);
+                    store_pack<float, 4>(partial + ((size_t)blockIdx.x * 2 + 1) * d + c + 4 * q, g4);
+                }
             }
         }
     }
@@ -418,16 +446,35 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict
     }
 }
 
-// Pass 2: block = 64 columns x 4 groups of row chunks (group q adds chunks q, q + 4, ...), combined through LDS in
-// group order, so the result does not depend on scheduling.
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partial, int chunks, int cols,
-                                                           float beta, float *out0, float *out1) {
-    __shared__ float red[2][4][64];
-    const int tx = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + tx;
+// Pass 2: block = 32 columns x 32 groups of row chunks (group q adds chunks q, q + 32, ... in that order), combined
+// through LDS in group order, so the result does not depend on scheduling.  Many groups and four loads in flight per
+// thread: with the partial rows of a kernel that writes one per block (up to 4096) a thread's chain of dependent adds
+// is what this pass takes, not its bytes.
+constexpr int kFinalCols = 32, kFinalGroups = 32;
+
+__global__ __launch_bounds__(kFinalCols * kFinalGroups) void colsum_final_kernel(const float *__restrict__ partial, int chunks,
+                                                                                 int cols, float beta, float *out0,
+                                                                                 float *out1) {
+    __shared__ float red[2][kFinalGroups][kFinalCols + 1];
+    const int tx = threadIdx.x % kFinalCols, q = threadIdx.x / kFinalCols;
+    const int c = blockIdx.x * kFinalCols + tx;
     float t0 = 0.f, t1 = 0.f;
     if (c < cols) {
-        for (int k = q; k < chunks; k += 4) {
+        int k = q;
+        for (; k + 3 * kFinalGroups < chunks; k += 4 * kFinalGroups) {
+            float a[4], b[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                a[j] = partial[((size_t)(k + j * kFinalGroups) * 2 + 0) * cols + c];
+                if (out1) b[j] = partial[((size_t)(k + j * kFinalGroups) * 2 + 1) * cols + c];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                t0 += a[j];
+                t1 += b[j];
+            }
+        }
+        for (; k < chunks; k += kFinalGroups) {
             t0 += partial[((size_t)k * 2 + 0) * cols + c];
             if (out1) t1 += partial[((size_t)k * 2 + 1) * cols + c];
         }
@@ -435,13 +482,12 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restri
     red[0][q][tx] = t0;
     red[1][q][tx] = t1;
     __syncthreads();
-    if (q == 0 && c < cols) {
-        t0 = (red[0][0][tx] + red[0][1][tx]) + (red[0][2][tx] + red[0][3][tx]);
-        out0[c] = (beta == 0.f ? 0.f : beta * out0[c]) + t0;
-        if (out1) {
-            t1 = (red[1][0][tx] + red[1][1][tx]) + (red[1][2][tx] + red[1][3][tx]);
-            out1[c] = (beta == 0.f ? 0.f : beta * out1[c]) + t1;
-        }
+    if (q < 2 && c < cols && (q == 0 || out1)) {
+        float t = 0.f;
+#pragma unroll
+        for (int j = 0; j < kFinalGroups; ++j) t += red[q][j][tx];
+        float *o = q == 0 ? out0 : out1;
+        o[c] = (beta == 0.f ? 0.f : beta * o[c]) + t;
     }
 }
 
@@ -503,8 +549,13 @@ __global__ __launch_bounds__(256) void adam_kernel(float *__restrict__ w, float 
 constexpr int kTrTile = 128;
 constexpr int kTrPitch = kTrTile + 8;     // elements; keeps 16-byte alignment and skews the banks
 
+// SUM: the block also adds up its 128 rows of every column it moves (as values of format E, in fp32) and writes them
+// to partial[blockIdx.y][0][c] - the first pass of the column sums (colsum_partial_kernel's layout, same 128-row
+// chunks), so that the bias gradient costs no pass of its own over a matrix that is being transposed anyway.
+template <class E, bool SUM>
 __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *__restrict__ in, uint16_t *__restrict__ out,
-                                                          int R, int C, long ldi, long ldo) {
+                                                          int R, int C, long ldi, long ldo, float *__restrict__ partial) {
+    static_assert(kTrTile == kColsumRows, "one transposed tile = one chunk of rows of the column sums");
     __shared__ __attribute__((aligned(16))) uint16_t tile[kTrTile * kTrPitch];     // [c][r]
     const int r0 = blockIdx.y * kTrTile, c0 = blockIdx.x * kTrTile;
     const int tid = threadIdx.x;
@@ -534,9 +585,21 @@ __global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t *__rest
     for (int j = 0; j < 8; ++j) {
         const int c = (tid >> 4) + 16 * j, rch = tid & 15;
         const int gc = c0 + c, gr = r0 + rch * 8;
-        if (gc < C && gr < R)
-            *reinterpret_cast<u32x4 *>(out + (size_t)gc * ldo + gr) =
-                *reinterpret_cast<const u32x4 *>(tile + c * kTrPitch + rch * 8);
+        const u32x4 piece = *reinterpret_cast<const u32x4 *>(tile + c * kTrPitch + rch * 8);
+        if (gc < C && gr < R) *reinterpret_cast<u32x4 *>(out + (size_t)gc * ldo + gr) = piece;
+        if constexpr (SUM) {
+            // rows beyond R were staged as zeros; the 16 lanes that hold column c's 128 rows are neighbours
+            float sum = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = piece[q];
+                const uint16_t lo = (uint16_t)(w & 0xFFFFu), hi = (uint16_t)(w >> 16);
+                sum += to_f32(__builtin_bit_cast(E, lo)) + to_f32(__builtin_bit_cast(E, hi));
+            }
+#pragma unroll
+            for (int m = 8; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 16);
+            if (rch == 0 && gc < C) partial[((size_t)blockIdx.y * 2 + 0) * C + gc] = sum;
+        }
     }
 }
 
@@ -606,35 +669,63 @@ template void launch_layernorm_fwd<bf16>(const bf16 *, const float *, const floa
 template void launch_layernorm_fwd<f16>(const f16 *, const float *, const float *, f16 *, float *, float *, int,
                                          int, float, hipStream_t);
 
+// blocks of the row-walking kernel for `rows` rows of length d (0: that kernel does not serve d)
+static int lnb_rows_blocks(int rows, int d, int V) {
+    if (d > 1024 * V * 2) return 0;
+    const int th = d <= 256 * V ? 256 : d <= 512 * V ? 512 : 1024;
+    return std::min(rows, 256 * (2048 / th));
+}
+
+size_t layernorm_bwd_partial_floats(int rows, int d) {
+    // fused sums: one pair of partial rows per block (only widths one pass of the block covers); else the column sums' own
+    const size_t fused = (size_t)std::max(lnb_rows_blocks(rows, d, 4), lnb_rows_blocks(rows, d, 8)) * 2 * (size_t)d;
+    return std::max(fused, colsum_partial_floats(rows, d));
+}
+
 template <class T>
 void launch_layernorm_bwd_dx(const T *dy, const T *x, const float *mean, const float *rstd, const float *g,
-                             const T *resid, T *dx, int rows, int d, hipStream_t s) {
-    if (rows == 0) return;
+                             const T *resid, T *dx, int rows, int d, hipStream_t s, float beta, float *dbeta,
+                             float *dgamma, float *partial) {
     constexpr int V = VecOf<T>::N;
-    ProfScope scope("layernorm_bwd_dx_kernel", 14.0 * rows * d, 4.0 * sizeof(T) * rows * (double)d, s);
+    const bool sums = dbeta != nullptr;
     const bool vec = d % V == 0 && aligned16(dy) && aligned16(x) && aligned16(resid) && aligned16(dx);
-    if (vec && aligned16(g) && d <= 1024 * V * 2) {
-#define LGA_LNB_ROWS(TH, NP) \
-        hipLaunchKernelGGL((layernorm_bwd_dx_rows_kernel<T, V, TH, NP>), dim3((unsigned)std::min(rows, 256 * (2048 / TH))), \
-                           dim3(TH), 0, s, dy, x, mean, rstd, g, resid, dx, rows, d)
-        if (d <= 256 * V) LGA_LNB_ROWS(256, 1);
-        else if (d <= 512 * V) LGA_LNB_ROWS(512, 1);
-        else if (d <= 1024 * V) LGA_LNB_ROWS(1024, 1);
-        else LGA_LNB_ROWS(1024, 2);
+    const bool rows_kernel = vec && aligned16(g) && d <= 1024 * V * 2;
+    // the sums ride along where a thread holds one piece of a row (d <= 1024 V): with two, their 4 V extra registers
+    // per thread do not fit beside the row
+    const bool fused = sums && rows_kernel && d <= 1024 * V && rows > 0 && aligned16(partial);
+    if (sums && !fused) launch_colsum<T>(dy, x, mean, rstd, rows, d, d, beta, dbeta, dgamma, partial, s);
+    if (rows == 0) return;
+    {
+        ProfScope scope(fused ? "layernorm_bwd_dx_kernel(with sums)" : "layernorm_bwd_dx_kernel", (fused ? 18.0 : 14.0) * rows * d,
+                        4.0 * sizeof(T) * rows * (double)d, s);
+        const int blocks = lnb_rows_blocks(rows, d, V);
+        if (rows_kernel) {
+#define LGA_LNB_ROWS(TH, NP, SUMS) \
+            hipLaunchKernelGGL((layernorm_bwd_dx_rows_kernel<T, V, TH, NP, SUMS>), dim3((unsigned)blocks), dim3(TH), 0, s, dy, x, \
+                               mean, rstd, g, resid, dx, rows, d, partial)
+            if (d <= 256 * V) { if (fused) LGA_LNB_ROWS(256, 1, true); else LGA_LNB_ROWS(256, 1, false); }
+            else if (d <= 512 * V) { if (fused) LGA_LNB_ROWS(512, 1, true); else LGA_LNB_ROWS(512, 1, false); }
+            else if (d <= 1024 * V) { if (fused) LGA_LNB_ROWS(1024, 1, true); else LGA_LNB_ROWS(1024, 1, false); }
+            else LGA_LNB_ROWS(1024, 2, false);
 #undef LGA_LNB_ROWS
-    } else if (vec)
-        hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
-                           dx, d);
-    else
-        hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, 1>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
-                           dx, d);
+        } else if (vec)
+            hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, V>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
+                               dx, d);
+        else
+            hipLaunchKernelGGL((layernorm_bwd_dx_kernel<T, 1>), dim3(rows), dim3(256), 0, s, dy, x, mean, rstd, g, resid,
+                               dx, d);
+        if (fused)
+            hipLaunchKernelGGL(colsum_final_kernel, dim3((d + kFinalCols - 1) / kFinalCols), dim3(kFinalCols * kFinalGroups), 0, s, partial, blocks, d, beta, dbeta,
+                               dgamma);
+    }
 }
 template void launch_layernorm_bwd_dx<float>(const float *, const float *, const float *, const float *,
-                                             const float *, const float *, float *, int, int, hipStream_t);
+                                             const float *, const float *, float *, int, int, hipStream_t, float,
+                                             float *, float *, float *);
 template void launch_layernorm_bwd_dx<bf16>(const bf16 *, const bf16 *, const float *, const float *, const float *,
-                                            const bf16 *, bf16 *, int, int, hipStream_t);
+                                            const bf16 *, bf16 *, int, int, hipStream_t, float, float *, float *, float *);
 template void launch_layernorm_bwd_dx<f16>(const f16 *, const f16 *, const float *, const float *, const float *,
-                                            const f16 *, f16 *, int, int, hipStream_t);
+                                            const f16 *, f16 *, int, int, hipStream_t, float, float *, float *, float *);
 
 size_t colsum_partial_floats(int rows, int cols) {
     const size_t chunks = ((size_t)rows + kColsumRows - 1) / kColsumRows;
@@ -669,7 +760,7 @@ void launch_colsum(const T *a, const T *x, const float *mean, const float *rstd,
                                    cols, ld, partial);
         }
     }
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 63) / 64), dim3(256), 0, s, partial, chunks, cols, beta,
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + kFinalCols - 1) / kFinalCols), dim3(kFinalCols * kFinalGroups), 0, s, partial, chunks, cols, beta,
                        out0, out1);
 }
 template void launch_colsum<float>(const float *, const float *, const float *, const float *, int, int, int, float,
@@ -683,9 +774,26 @@ void launch_transpose16(const void *in, void *out, int R, int C, long ldi, long 
     if (R == 0 || C == 0) return;
     ProfScope scope("transpose16_kernel", 0.0, 4.0 * R * (double)C, s);
     dim3 grid((C + kTrTile - 1) / kTrTile, (R + kTrTile - 1) / kTrTile);
-    hipLaunchKernelGGL(transpose16_kernel, grid, dim3(256), 0, s, static_cast<const uint16_t *>(in),
-                       static_cast<uint16_t *>(out), R, C, ldi, ldo);
+    hipLaunchKernelGGL((transpose16_kernel<bf16, false>), grid, dim3(256), 0, s, static_cast<const uint16_t *>(in),
+                       static_cast<uint16_t *>(out), R, C, ldi, ldo, (float *)nullptr);
 }
+
+template <class E>
+void launch_transpose16_colsum(const E *in, E *out, int R, int C, long ldi, long ldo, float beta, float *out0,
+                               float *partial, hipStream_t s) {
+    if (C == 0) return;
+    ProfScope scope("transpose16_kernel(with column sums)", 1.0 * R * C, 4.0 * R * (double)C, s);
+    const int chunks = (R + kTrTile - 1) / kTrTile;
+    if (R > 0) {
+        dim3 grid((C + kTrTile - 1) / kTrTile, chunks);
+        hipLaunchKernelGGL((transpose16_kernel<E, true>), grid, dim3(256), 0, s, reinterpret_cast<const uint16_t *>(in),
+                           reinterpret_cast<uint16_t *>(out), R, C, ldi, ldo, partial);
+    }
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((C + kFinalCols - 1) / kFinalCols), dim3(kFinalCols * kFinalGroups), 0, s, partial, chunks, C, beta, out0,
+                       (float *)nullptr);
+}
+template void launch_transpose16_colsum<bf16>(const bf16 *, bf16 *, int, int, long, long, float, float *, float *, hipStream_t);
+template void launch_transpose16_colsum<f16>(const f16 *, f16 *, int, int, long, long, float, float *, float *, hipStream_t);
 
 template <class E>
 void launch_adam(float *w, float *m, float *v, const float *g, E *w16, size_t n, float lr, float beta1, float beta2,

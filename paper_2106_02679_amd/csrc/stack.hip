@@ -220,7 +220,7 @@ Plan make_plan(const lga_config &c) {
     p.lse = take(stats * 4);
     p.delta = take(stats * 4);
     const size_t widest = std::max<size_t>(3 * d, f);
-    p.partial = take(colsum_partial_floats((int)t, (int)widest) * 4);
+    p.partial = take(std::max(colsum_partial_floats((int)t, (int)widest), layernorm_bwd_partial_floats((int)t, (int)c.d_model)) * 4);
     p.nonfinite = take(L * 4);          // one flag per layer, see lga_adam.skip_nonfinite
     // head sizes without a fused attention kernel: score matrices of as many heads of one sequence as fit 4 GiB
     p.attn_ws_bytes = 0;
@@ -524,7 +524,8 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
             const int ldk = (int)st->plan.ldk;
             T *xT = st->at<T>(st->plan.xT[which]), *dyT = st->at<T>(st->plan.dyT[which]);
             launch_transpose16(X, xT + (size_t)gs.slot * t, t, in, in, ldk, s);
-            launch_transpose16(dY, dyT + (size_t)gs.slot * t, t, out, out, ldk, s);
+            // the bias gradient is the column sum of dY: taken from the tiles as they are transposed
+            launch_transpose16_colsum<T>(dY, dyT + (size_t)gs.slot * t, t, out, out, ldk, beta, gbuf + b_off, partial, s);
             if (gs.flush) {
                 g.K = (gs.slot + 1) * t; g.beta = gs.beta_mat;
                 g.A = xT; g.lda = ldk; g.B = dyT; g.ldb = ldk;
@@ -532,7 +533,8 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
                 gemm<T>(g, true, true, EPI_ACCUM_F32, s);
             }
         }
-        launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, out, beta, gbuf + b_off, nullptr, partial, s);
+        if constexpr (std::is_same<T, float>::value)
+            launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, out, beta, gbuf + b_off, nullptr, partial, s);
     };
     auto dgrad = [&](const T *dY, int out, size_t w_off, int in, T *dX, Epilogue e, const T *aux) {
         GemmParams<T> g{};
@@ -548,8 +550,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     wgrad(1, h2, d, du, f, o.w_1, o.b_1);
     dgrad(du, f, o.w_1, d, dh2, EPI_STORE, nullptr);
     // h2 = LN2(x1); dx1 = dy + LN2'(dh2)
-    launch_colsum<T>(dh2, x1, mean2, rstd2, t, d, d, beta, gbuf + o.ln2_b, gbuf + o.ln2_g, partial, s);
-    launch_layernorm_bwd_dx<T>(dh2, x1, mean2, rstd2, pf + o.ln2_g, dy, dx1, t, d, s);
+    launch_layernorm_bwd_dx<T>(dh2, x1, mean2, rstd2, pf + o.ln2_g, dy, dx1, t, d, s, beta, gbuf + o.ln2_b, gbuf + o.ln2_g, partial);
     // x1 = x + a Wo + bo
     wgrad(2, a, d, dx1, d, o.w_o, o.b_o);
     dgrad(dx1, d, o.w_o, d, da, EPI_STORE, nullptr);
@@ -561,8 +562,7 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     wgrad(3, h, d, dqkv, 3 * d, o.w_qkv, o.b_qkv);
     dgrad(dqkv, 3 * d, o.w_qkv, d, dh, EPI_STORE, nullptr);
     // h = LN1(x); dx = dx1 + LN1'(dh)
-    launch_colsum<T>(dh, x_in, mean1, rstd1, t, d, d, beta, gbuf + o.ln1_b, gbuf + o.ln1_g, partial, s);
-    launch_layernorm_bwd_dx<T>(dh, x_in, mean1, rstd1, pf + o.ln1_g, dx1, dy, t, d, s);
+    launch_layernorm_bwd_dx<T>(dh, x_in, mean1, rstd1, pf + o.ln1_g, dx1, dy, t, d, s, beta, gbuf + o.ln1_b, gbuf + o.ln1_g, partial);
 }
 
 // async: on the second stream, after everything enqueued so far (overlap mode, fused Adam of the layered order)

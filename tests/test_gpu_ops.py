@@ -196,6 +196,40 @@ def test_transpose(R, C, pad):
     assert np.all(got[:, R:] == 0)
 
 
+@pytest.mark.parametrize("dt,R,C,pad", [(BF16, 8, 8, 0), (BF16, 136, 264, 8), (BF16, 1000, 128, 0), (F16, 128, 3000, 16),
+                                         (F16, 4104, 776, 8), (BF16, 0, 64, 0)])
+def test_transpose_that_also_returns_the_column_sums(dt, R, C, pad):
+    """The transposing pass of the weight-gradient operands hands back the bias gradient (section 3: one gradient per
+    layer, accumulated): the transposed matrix must be bit-exact, the sums those of the fp64 column sums, with beta 1
+    and beta 0, on ragged tiles (R, C not multiples of 128) and padded leading dimensions."""
+    rng = np.random.default_rng(R * C + 1)
+    a = rnd(rng, (max(R, 1), C + pad), dt)[:R]
+    ad = to_dev(a if R else np.zeros((1, C + pad), np.float32), dt)
+    out = empty_dev((C, R + pad + (8 if R == 0 else 0)), dt)
+    out.zero_()
+    old = rng.standard_normal(C).astype(np.float32)
+    sums = fvec(old)
+    scratch = torch.empty(max(1, int(B.lib.lga_op_colsum_scratch_floats(R, C))), device="cuda")
+    ldo = R + pad + (8 if R == 0 else 0)
+    B.check(B.lib.lga_op_transpose_colsum(dt, ad.data_ptr(), out.data_ptr(), R, C, C + pad, ldo, 1.0, sums.data_ptr(),
+                                          scratch.data_ptr(), None))
+    torch.cuda.synchronize()
+    got = to_host(out)
+    assert np.array_equal(got[:, :R], a[:, :C].T.astype(np.float64))
+    assert np.all(got[:, R:] == 0)
+    ref = a[:, :C].astype(np.float64).sum(0)
+    assert rel_err(sums.cpu().numpy(), old + ref) < 1e-5
+    B.check(B.lib.lga_op_transpose_colsum(dt, ad.data_ptr(), out.data_ptr(), R, C, C + pad, ldo, 0.0, sums.data_ptr(),
+                                          scratch.data_ptr(), None))
+    torch.cuda.synchronize()
+    if R:
+        assert rel_err(sums.cpu().numpy(), ref) < 1e-5
+    else:
+        assert np.all(sums.cpu().numpy() == 0)
+    assert B.lib.lga_op_transpose_colsum(F32, ad.data_ptr(), out.data_ptr(), R, C, C + pad, ldo, 0.0, sums.data_ptr(),
+                                         scratch.data_ptr(), None) == B.LGA_ERR_ARG
+
+
 def test_gemm_empty_and_rejected_arguments():
     t = torch.zeros(64, device="cuda")
     # M = 0: nothing to do, no launch
@@ -241,7 +275,7 @@ def test_layernorm_forward_and_backward(dt, rows, d):
                                        rs.data_ptr(), rows, d, eps, None))
     old_g = rng.standard_normal(d).astype(np.float32); old_b = rng.standard_normal(d).astype(np.float32)
     dgd, dbd = fvec(old_g), fvec(old_b)
-    scratch = torch.empty(int(B.lib.lga_op_colsum_scratch_floats(rows, d)), device="cuda")
+    scratch = torch.empty(int(B.lib.lga_op_layernorm_bwd_scratch_floats(rows, d)), device="cuda")
     B.check(B.lib.lga_op_layernorm_bwd(dt, dyd.data_ptr(), xd.data_ptr(), mean.data_ptr(), rs.data_ptr(), gd.data_ptr(),
                                        rd.data_ptr(), dx.data_ptr(), dgd.data_ptr(), dbd.data_ptr(), 1.0,
                                        scratch.data_ptr(), rows, d, None))
