@@ -29,7 +29,28 @@ template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return sta
 __device__ __forceinline__ float to_f32(f16 v) { return static_cast<float>(v); }
 template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return static_cast<f16>(v); }
 
-// ---- the 32 x 32 x 16 matrix instruction for either 16-bit element type, fp32 accumulate ----
+// ---- the 16 x 16 x 32 and 32 x 32 x 16 matrix instructions for either 16-bit element type, fp32 accumulate ----
+template <class E> __device__ __forceinline__ f32x4 mfma_16x16x32(x8<E> a, x8<E> b, f32x4 c);
+template <> __device__ __forceinline__ f32x4 mfma_16x16x32<bf16>(x8<bf16> a, x8<bf16> b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4 mfma_16x16x32<f16>(x8<f16> a, x8<f16> b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+// The same instruction accumulating in place, acc += a b, with acc held in accumulation registers: written as
+// assembly because the builtin leaves the choice of destination to the register allocator, which with all 256
+// accumulation registers taken by accumulators gives some products a destination other than their addend and then
+// moves accumulators around in the loop.  What the compiler no longer knows about this instruction, the caller
+// guarantees: an accumulator is not read by anything but this instruction until at least 32 wait states after its
+// last update, and its operands a, b are registers whose loads the compiler still tracks (s_waitcnt).
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+template <class E> __device__ __forceinline__ void mfma_16x16x32_acc(x8<E> a, x8<E> b, f32x4 &acc);
+template <> __device__ __forceinline__ void mfma_16x16x32_acc<bf16>(x8<bf16> a, x8<bf16> b, f32x4 &acc) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(__builtin_bit_cast(i32x4, a)), "v"(__builtin_bit_cast(i32x4, b)));
+}
+template <> __device__ __forceinline__ void mfma_16x16x32_acc<f16>(x8<f16> a, x8<f16> b, f32x4 &acc) {
+    asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(__builtin_bit_cast(i32x4, a)), "v"(__builtin_bit_cast(i32x4, b)));
+}
 template <class E> __device__ __forceinline__ f32x16 mfma_32x32x16(x8<E> a, x8<E> b, f32x16 c);
 template <> __device__ __forceinline__ f32x16 mfma_32x32x16<bf16>(x8<bf16> a, x8<bf16> b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);

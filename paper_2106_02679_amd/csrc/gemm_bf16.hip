@@ -10,7 +10,7 @@
 // are all run by the layer stack with BOTH operands k-contiguous (it keeps a transposed 16-bit copy of
 // every weight matrix and transposes the two operands of a weight-gradient GEMM beforehand).  That layout
 // is served by gemm_bf16_dma_kernel: 256 threads = 4 wavefronts (2x2) on a 256x256x64 tile,
-// v_mfma_f32_32x32x16_bf16, tiles moved global -> LDS without passing through registers.
+// v_mfma_f32_16x16x32_bf16, tiles moved global -> LDS without passing through registers.
 //
 // gemm_bf16_kernel is the register-staged predecessor and still serves the other operand layouts of
 // the op-level API and the small (128x128-tile) problems: both operands sit in LDS k-contiguous
@@ -469,16 +469,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int til
 // `buffer_load_dwordx4 ... lds` writes lane L's 16 bytes at (LDS base in M0) + 16 L, so one
 // wavefront instruction fills 8 consecutive 128-byte tile rows.  The XOR swizzle of the tile is
 // obtained on the global side: lane L, which lands in physical chunk L%8 of row r, fetches logical
-// chunk (L%8) ^ swz(r) of that row.  No staging registers, no LDS store instructions, no waits on
+// chunk (L%8) ^ swz16(r) of that row.  No staging registers, no LDS store instructions, no waits on
 // individual loads: the next k tile streams into the other LDS stage while this one is multiplied,
-// and one vmcnt(0) + barrier per tile publishes it.
+// and one vmcnt wait + barrier per tile publishes it.
+//
+// The matrix instruction is v_mfma_f32_16x16x32 (a wavefront's 128 x 128 tile = 8 x 8 blocks of 16 x 16, four
+// accumulator registers each), not the 32x32x16 one: same flops per cycle, same LDS and register operand bytes per k
+// tile, but a quarter of the accumulator registers read and written per instruction and per flop (a 16 x 16 block
+// stays in the pipe for 32 k instead of a 32 x 32 block for 16).  The chip is power-limited on this kernel, and at
+// the board's limit the clock it grants is what that difference in power per cycle buys: measured on the merged
+// weight-gradient shapes of d = 12288 at sustained load, 1.50 GHz with the 32x32x16 loop against 1.77 GHz with this
+// instruction at the same 1.35 kW.
+__device__ __forceinline__ int swz16(int row) { return (row >> 1) & 7; }      // 16 rows of one chunk column -> 8 chunk places x 2 row parities
+
 template <int BM, int BN, int WGM, int WGN, int EPI, class E>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParams<E> p, int tiles_m, int tiles_n) {
     constexpr int NW = WGM * WGN;                   // wavefronts per workgroup, WGM x WGN over the tile
     constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int FM = WM / 16, FN = WN / 16;       // 16 x 16 blocks of a wavefront's tile
     constexpr int NIA = BM / (8 * NW), NIB = BN / (8 * NW);     // DMA instructions per wavefront per operand tile
     static_assert(BM == BN, "the operand ring below uses one slot size for both operands");
+    static_assert(BK == 64, "two k steps of 32 per tile");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     E *lds = reinterpret_cast<E *>(smem_raw);
     // LDS is a ring of kSlots operand tiles of BM x BK.  Operand tiles enter it in the order A(0), B(0), A(1),
@@ -535,15 +546,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
-    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int l16 = lane & 15, lq = lane >> 4;           // lane = 16 lq + l16
 
-    f32x16 acc[FM][FN];
+    // A lane's part of a 16 x 16 block: column (m) l16, rows (n) 4 lq .. + 3 - the B tile is the instruction's first
+    // operand, so a lane ends with 4 consecutive n of one row m of C.
+    f32x4 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // Loop-invariant per-lane byte offsets of the DMA loads inside an operand tile (or the poison
     // offset for rows beyond the matrix, which the hardware answers with zeros).
@@ -559,24 +570,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
         const int r = dma_row(i);
-        offA[i] = (m0 + r < p.M) ? r * lda2 + (((lane & 7) ^ swz(r)) << 4) - (i & 3) * 1024 : kBufPoison;
+        offA[i] = (m0 + r < p.M) ? r * lda2 + (((lane & 7) ^ swz16(r)) << 4) - (i & 3) * 1024 : kBufPoison;
     }
 #pragma unroll
     for (int i = 0; i < NIB; ++i) {
         const int r = dma_row(i);
-        offB[i] = (n0 + r < p.N) ? r * ldb2 + (((lane & 7) ^ swz(r)) << 4) - (i & 3) * 1024 : kBufPoison;
+        offB[i] = (n0 + r < p.N) ? r * ldb2 + (((lane & 7) ^ swz16(r)) << 4) - (i & 3) * 1024 : kBufPoison;
     }
     const E *a_ptr = p.A + (size_t)m0 * p.lda;
     const E *b_ptr = p.B + (size_t)n0 * p.ldb;
     const int nk = (p.K + BK - 1) / BK, nk_full = p.K / BK;
 
     typedef __attribute__((address_space(3))) void *lds_ptr;
-    // DMA instructions [j0, j1) of one operand tile (k tile kt of A or of B) into ring slot q.  They are issued
-    // in slices so that they can be spread over the whole iteration: the CU's texture-address unit needs at
-    // least 16 cycles for each, and a wavefront whose load finds its queue full stalls, MFMAs included.
-    // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
-    // One DMA instruction: rows [(i NW + wave) 8, +8) of operand tile kt (A if is_a, else B) into ring slot q.
-    // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
     // One direct-to-LDS load: instruction i of a wavefront's share of an operand tile into ring slot q.  The LDS base
     // is that of the instruction's group of four; the immediate offset (a literal, hence the switch over a value that
     // is a constant wherever this is called) places it inside the group.
@@ -589,66 +594,66 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
             default: __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)group, 16, voff, soff, 3072, 0); break;
         }
     };
+    // krem < 64 (partial last tile): k chunks at or beyond krem read as zero.
     auto dma_one = [&](bool is_a, int q, int kt, int krem, int i) {
         const __amdgpu_buffer_rsrc_t r = make_rsrc((is_a ? a_ptr : b_ptr) + (size_t)kt * BK);
         int off = is_a ? offA[i] : offB[i];
-        if (krem < BK) off |= ((((lane & 7) ^ swz(dma_row(i))) * 8 < krem) ? 0 : kBufPoison);
+        if (krem < BK) off |= ((((lane & 7) ^ swz16(dma_row(i))) * 8 < krem) ? 0 : kBufPoison);
         lds_dma(r, q, i, off, 0);
     };
-    // MFMA operands of the four k steps of a tile, one register buffer each: a step's operands are read
-    // from LDS two steps (32 MFMAs) ahead, which rides out the LDS latency spikes that the incoming DMA
-    // traffic causes.  qa is the ring slot of the tile's A operand; its B operand is in the next slot.
-    x8<E> af[4][FM], bf[4][FN];
-    // LDS byte address of an operand chunk, kept to one register per operand: with 128-row wavefront tiles the
-    // swizzle term of row (tile row 0 + 32 i + lrow) is (lane part) ^ (2 i), so chunk 2 ks + lhalf of block i
-    // lies at (lane address) ^ (((2 ks) ^ (2 i)) << 4) plus a compile-time offset.
-    static_assert(WM % 128 == 0 && WN % 128 == 0, "swizzle split below assumes 128-row wavefront tiles");
-    const int lane_sw = lhalf ^ ((lrow >> 1) & 7) ^ (lrow >> 4);
-    const int lane_a = ((wm * WM + lrow) * BK + lane_sw * 8) * 2;
-    const int lane_b = ((wn * WN + lrow) * BK + lane_sw * 8) * 2;
-    // operand f of step ks (f < FM: A block f, else B block f - FM) of the tile whose A operand is in slot qa
-    auto load_frag = [&](int ks, int qa, int f) {
-        if (f < FM) {
-            const int va = lane_a + qa * (kSlotElems * 2);
-            af[ks][f] = *reinterpret_cast<const x8<E> *>(smem_raw + ((va ^ ((((2 * ks) ^ (2 * f)) & 7) << 4)) + f * 32 * BK * 2));
+    // MFMA operands of the two k steps (32 k each) of a tile, one register buffer each: while one step is multiplied
+    // from its buffer, the other buffer takes the next step's operands, so every LDS read is a whole step (64 MFMAs,
+    // about 1000 cycles) ahead of its use, which rides out the LDS latency spikes that the incoming DMA traffic causes.
+    x8<E> af[2][FM], bf[2][FN];
+    // LDS byte address of an operand chunk.  A lane reads row (block row 0 + l16), logical chunk 4 s + lq of k step
+    // s; the swizzle term of that row is l16 >> 1 whatever the block (blocks start at multiples of 16 rows), so the
+    // chunk lies at (lane address) ^ (s << 6) plus a compile-time offset for slot and block.
+    static_assert(WM % 16 == 0 && WN % 16 == 0, "whole 16 x 16 blocks");
+    const int lane_sw = lq ^ (l16 >> 1);
+    const int lane_a = ((wm * WM + l16) * BK + lane_sw * 8) * 2;
+    const int lane_b = ((wn * WN + l16) * BK + lane_sw * 8) * 2;
+    // operand f of step s (f < FN: B block f, else A block f - FN) of the tile whose A operand is in slot qa.  B first:
+    // a step starts with A block 0 against every B block.
+    auto load_frag = [&](int s, int qa, int f) {
+        if (f < FN) {
+            const int vb = (lane_b ^ (s << 6)) + wrap(qa + 1) * (kSlotElems * 2);
+            bf[s][f] = *reinterpret_cast<const x8<E> *>(smem_raw + vb + f * 16 * BK * 2);
         } else {
-            const int j = f - FM, vb = lane_b + wrap(qa + 1) * (kSlotElems * 2);
-            bf[ks][j] = *reinterpret_cast<const x8<E> *>(smem_raw + ((vb ^ ((((2 * ks) ^ (2 * j)) & 7) << 4)) + j * 32 * BK * 2));
+            const int g = f - FN, va = (lane_a ^ (s << 6)) + qa * (kSlotElems * 2);
+            af[s][g] = *reinterpret_cast<const x8<E> *>(smem_raw + va + g * 16 * BK * 2);
         }
     };
-    auto load_frags = [&](int ks, int qa) {
+    auto load_frags = [&](int s, int qa) {
 #pragma unroll
-        for (int f = 0; f < FM + FN; ++f) load_frag(ks, qa, f);
+        for (int f = 0; f < FM + FN; ++f) load_frag(s, qa, f);
     };
     // The same two operations for the unrolled main loop, where the ring slot is a compile-time constant.  A wavefront
     // issues strictly in order and, being alone on its SIMD, has nobody to fill the matrix pipe while it issues
-    // anything else: measured, every instruction of the loop that is not an MFMA costs about four cycles of MFMA
-    // time (64 MFMAs of 32 cycles per k tile; 126 other instructions made a k tile take 2400 cycles instead of 2048).
-    // So the loop keeps nothing but the loads themselves:
-    //  - LDS operand reads take their address from one of 24 registers set up once - (lane address ^ swizzle term)
-    //    for the four values the term takes, in each of the three 64 KB ranges an immediate offset reaches - plus an
-    //    immediate offset: no address arithmetic per read;
+    // anything else: measured (32x32x16 form of this loop), 126 other instructions per k tile made a k tile take 2400
+    // cycles where its MFMAs need 2048, 64 of them about 2230.  So the loop keeps nothing but the loads themselves:
+    //  - LDS operand reads take their address from one of 12 registers set up once - (lane address ^ step term) for
+    //    the two steps, in each of the three 64 KB ranges an immediate offset reaches - plus an immediate offset: no
+    //    address arithmetic per read;
     //  - the direct-to-LDS loads use one buffer resource per operand for the whole tile and take the k position from
     //    a scalar offset that advances once per k tile; the LDS destination is a constant.
-    int pa[4][3], pb[4][3];
+    int pa[2][3], pb[2][3];
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
+    for (int v = 0; v < 2; ++v)
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
-            pa[v][r] = (lane_a ^ ((2 * v) << 4)) + r * 65536;
-            pb[v][r] = (lane_b ^ ((2 * v) << 4)) + r * 65536;
+            pa[v][r] = (lane_a ^ (v << 6)) + r * 65536;
+            pb[v][r] = (lane_b ^ (v << 6)) + r * 65536;
             // opaque to the compiler, which would otherwise fold the range into each read's offset and add it back
             // with a VALU instruction per read
             asm volatile("" : "+v"(pa[v][r]), "+v"(pb[v][r]));
         }
-    auto load_frag_c = [&](int ks, int qa, int f) {          // qa: a constant at every call
-        const bool is_a = f < FM;
-        const int blk = is_a ? f : f - FM;
-        const int v = (((2 * ks) ^ (2 * blk)) & 7) >> 1;
-        const int off = (is_a ? qa : wrap(qa + 1)) * (kSlotElems * 2) + blk * 32 * BK * 2;      // below 160 KB
-        const unsigned char *src = smem_raw + (is_a ? pa[v][off >> 16] : pb[v][off >> 16]) + (off & 0xFFFF);
-        if (is_a) af[ks][blk] = *reinterpret_cast<const x8<E> *>(src);
-        else bf[ks][blk] = *reinterpret_cast<const x8<E> *>(src);
+    auto load_frag_c = [&](int s, int qa, int f) {           // qa: a constant at every call
+        const bool is_b = f < FN;
+        const int blk = is_b ? f : f - FN;
+        const int off = (is_b ? wrap(qa + 1) : qa) * (kSlotElems * 2) + blk * 16 * BK * 2;      // below 160 KB
+        const unsigned char *src = smem_raw + (is_b ? pb[s][off >> 16] : pa[s][off >> 16]) + (off & 0xFFFF);
+        if (is_b) bf[s][blk] = *reinterpret_cast<const x8<E> *>(src);
+        else af[s][blk] = *reinterpret_cast<const x8<E> *>(src);
     };
     const __amdgpu_buffer_rsrc_t rsA = make_rsrc(a_ptr), rsB = make_rsrc(b_ptr);
     // DMA instruction i of a full k tile of A or B into (constant) ring slot q; koff: byte offset of the k tile in a row
@@ -664,7 +669,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     static_assert(NIA < 16, "vmcnt immediate below uses the low four bits only");
     constexpr int kWaitVmA = 0x0070 | NIA;
 
-    // prologue: tile 0 published, tile 1 in flight, operands of steps 0 and 1 in registers
+    // prologue: tile 0 published, tile 1 in flight, operands of step 0 in registers
 #pragma unroll
     for (int i = 0; i < NIA; ++i) dma_one(true, 0, 0, p.K, i);
 #pragma unroll
@@ -678,59 +683,50 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         for (int i = 0; i < NIB; ++i) dma_one(false, 3, 1, p.K - BK, i);
     }
     load_frags(0, 0);
-    load_frags(1, 0);
 
-    // One k step = FM groups of FN MFMAs (one A block against all B blocks).  After each group the wavefront
-    // issues its share of the step's other work: DMA instructions [g DPG, (g+1) DPG) of operand tile `dkt`
-    // and two of the 8 LDS operand reads for step `rks`.  The order is pinned (sched_barrier) because the
-    // compiler otherwise clumps the loads, and a wavefront that issues several loads in a row right after the
-    // barrier, together with the three others, finds the load queue full and stalls with its MFMAs behind it.
-    static_assert(NIA % (2 * FM) == 0 && NIB % (2 * FM) == 0 && (FM + FN) % FM == 0, "work shares per MFMA group");
-    constexpr int RPG = (FM + FN + FM - 2) / (FM - 1);      // LDS reads after each group but the last, which gets none
+    // One k step = FM rows of FN MFMAs (one A block against all B blocks).  Each row also issues its share of the
+    // step's other work, never two memory instructions in a row: one direct-to-LDS load of operand tile `dkt` after its
+    // first MFMA, and two of the step's 16 LDS operand reads (for step `rs` of the tile in slot `rqa`) further on.
+    // The order is pinned (sched_barrier): left to itself the compiler clumps the loads, and a wavefront that issues
+    // several in a row right after the barrier, together with the three others, finds the load queue full and
+    // stalls with its MFMAs behind it.
+    static_assert(NIA == FM && NIB == FM && FM + FN == 2 * FM && FN >= 6, "one load and two reads per row of MFMAs");
     // lean_c: the unrolled main loop's forms of the loads (constant slots; dkt is then the k tile's byte offset)
-    auto k_step = [&](auto lean_c, int ks, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, int dfirst, int dpg,
-                      bool do_read, int rks, int rqa) {
+    auto k_step = [&](auto lean_c, int s, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, bool do_read, int rs,
+                      int rqa) __attribute__((always_inline)) {
         constexpr bool LEAN = decltype(lean_c)::value;
 #pragma unroll
         for (int g = 0; g < FM; ++g) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
-                acc[g][j] = mfma_32x32x16<E>(bf[ks][j], af[ks][g], acc[g][j]);
-            if (do_dma) {
-#pragma unroll
-                for (int u = 0; u < dpg; ++u) {
-                    if constexpr (LEAN) dma_c(dma_is_a, dq, dkt, dfirst + g * dpg + u);
-                    else dma_one(dma_is_a, dq, dkt, dkrem, dfirst + g * dpg + u);
+            for (int j = 0; j < FN; ++j) {
+                mfma_16x16x32_acc<E>(bf[s][j], af[s][g], acc[g][j]);
+                if (j == 0 && do_dma) {
+                    if constexpr (LEAN) dma_c(dma_is_a, dq, dkt, g);
+                    else dma_one(dma_is_a, dq, dkt, dkrem, g);
                 }
-            }
-            if (do_read) {
-#pragma unroll
-                for (int f = g * RPG; f < (g + 1) * RPG && f < FM + FN; ++f) {
-                    if constexpr (LEAN) load_frag_c(rks, rqa, f);
-                    else load_frag(rks, rqa, f);
+                if ((j == 2 || j == 5) && do_read) {
+                    const int f = 2 * g + (j == 5 ? 1 : 0);
+                    if constexpr (LEAN) load_frag_c(rs, rqa, f);
+                    else load_frag(rs, rqa, f);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     // One k tile whose A operand is in ring slot qa.  STRAIGHT: tiles kt+1 and kt+2 exist and are full, so
-    // nothing is tested.  Every step issues the same mix, so the load queue never sees a burst:
-    //   step 0: MFMAs | LDS reads of step 2's operands | first half of A(kt+2)'s loads, into the free slot
-    //   step 1: MFMAs | LDS reads of step 3's operands | second half of A(kt+2)'s loads
+    // nothing is tested.  Both steps issue the same mix, so the load queue never sees a burst:
+    //   step 0: MFMAs | LDS reads of step 1's operands | A(kt+2)'s loads, into the free slot
     //   wait for all loads but A(kt+2)'s + barrier: tile kt+1 is published, and nobody reads tile kt's slots
     //   any more
-    //   step 2: MFMAs | LDS reads of tile kt+1's step 0 | first half of B(kt+2)'s loads, into A(kt)'s slot
-    //   step 3: MFMAs | LDS reads of tile kt+1's step 1 | second half of B(kt+2)'s loads
-    auto k_tile = [&](int kt, int qa, auto straight_c) {
+    //   step 1: MFMAs | LDS reads of tile kt+1's step 0 | B(kt+2)'s loads, into A(kt)'s slot
+    auto k_tile = [&](int kt, int qa, auto straight_c) __attribute__((always_inline)) {
         constexpr bool STRAIGHT = decltype(straight_c)::value;
         const bool more1 = STRAIGHT || kt + 1 < nk, more2 = STRAIGHT || kt + 2 < nk;
         const int krem2 = STRAIGHT ? BK : p.K - (kt + 2) * BK;
         const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);      // A(kt+1), A(kt+2); B(kt+2) goes to qa
-        constexpr int DA = NIA / (2 * FM), DB = NIB / (2 * FM);
 
-        k_step(std::false_type{}, 0, more2, true, qa2, kt + 2, krem2, 0, DA, true, 2, qa);
-        k_step(std::false_type{}, 1, more2, true, qa2, kt + 2, krem2, NIA / 2, DA, true, 3, qa);
+        k_step(std::false_type{}, 0, more2, true, qa2, kt + 2, krem2, true, 1, qa);
         // A bare s_barrier: __syncthreads() would add a fence that waits for every load, A(kt+2)'s included.
         // The LDS reads above must have returned before other wavefronts may overwrite those slots.
         if (more2)
@@ -741,23 +737,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        k_step(std::false_type{}, 2, more2, false, qa, kt + 2, krem2, 0, DB, more1, 0, qa1);
-        k_step(std::false_type{}, 3, more2, false, qa, kt + 2, krem2, NIB / 2, DB, more1, 1, qa1);
+        k_step(std::false_type{}, 1, more2, false, qa, kt + 2, krem2, more1, 0, qa1);
     };
     // The same k tile for the unrolled main loop: ring slot qa is a constant, tiles kt+1 and kt+2 exist and are full;
     // koff2 is the byte offset of k tile kt+2 within a row.
-    auto k_tile_c = [&](int qa, int koff2) {
+    auto k_tile_c = [&](int qa, int koff2) __attribute__((always_inline)) {
         const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);
-        constexpr int DA = NIA / (2 * FM), DB = NIB / (2 * FM);
-        k_step(std::true_type{}, 0, true, true, qa2, koff2, BK, 0, DA, true, 2, qa);
-        k_step(std::true_type{}, 1, true, true, qa2, koff2, BK, NIA / 2, DA, true, 3, qa);
+        k_step(std::true_type{}, 0, true, true, qa2, koff2, BK, true, 1, qa);
         __builtin_amdgcn_s_waitcnt(kWaitVmA);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        k_step(std::true_type{}, 2, true, false, qa, koff2, BK, 0, DB, true, 0, qa1);
-        k_step(std::true_type{}, 3, true, false, qa, koff2, BK, NIB / 2, DB, true, 1, qa1);
+        k_step(std::true_type{}, 1, true, false, qa, koff2, BK, true, 0, qa1);
     };
     int kt = 0, qa = 0;
     // Main loop, unrolled over one period of the ring (five k tiles; the slot of A(kt) is 0, 2, 4, 1, 3, 0, ...).
@@ -774,50 +766,50 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     }
     for (; kt + 2 < nk_full; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::true_type{});      // what is left of the full tiles
     for (; kt < nk; ++kt, qa = wrap(qa + 2)) k_tile(kt, qa, std::false_type{});              // the last tiles, with tests
+    // the accumulators' last updates must have left the matrix pipe before anything else reads them (see
+    // mfma_16x16x32_acc): twice the longest wait the instruction set asks for after a matrix instruction
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
     if constexpr (EPI != EPI_ACCUM_F32) {
-        // bf16 outputs: a lane holds 4 consecutive n of 16 different (row, column group) places, so storing from
-        // the accumulators writes 16-byte runs per row and instruction - partial cache lines that reach memory in
-        // pieces (measured: up to 2.3 x the output bytes) and scattered reads of the residual / pre-activation.
-        // Instead each wavefront passes its results, 32 rows at a time, through a private piece of the (now idle)
-        // operand ring and stores whole rows: 16 lanes x 16 bytes = 256 contiguous bytes, 4 rows per instruction.
+        // bf16 outputs: a lane holds 4 consecutive n of 64 different (row, column group) places, so storing from
+        // the accumulators writes 8-byte runs per row and instruction - partial cache lines that reach memory in
+        // pieces (measured with the 32 x 32 blocks: up to 2.3 x the output bytes) and scattered reads of the residual /
+        // pre-activation.  Instead each wavefront passes its results, 16 rows at a time, through a private piece of
+        // the (now idle) operand ring and stores whole rows: 16 lanes x 16 bytes = 256 contiguous bytes, 4 rows per
+        // instruction.
         const auto al16 = [](const void *q) { return (reinterpret_cast<uintptr_t>(q) & 15) == 0; };
         const bool wide = ((p.N | p.ldc) & 7) == 0 && al16(p.out) && (EPI != EPI_BIAS_GELU || al16(p.out2)) &&
                           ((EPI != EPI_BIAS_RESID && EPI != EPI_MUL_DGELU) || al16(p.aux)) &&
                           ((EPI != EPI_BIAS && EPI != EPI_BIAS_RESID && EPI != EPI_BIAS_GELU) || al16(p.bias));
         if (wide) {
             constexpr int SP = WN + 4;                                  // staging pitch in floats
-            static_assert(4 * 32 * SP * 4 <= 5 * BM * BK * 2, "staging fits in the operand ring");
-            // The residual / pre-activation values of the whole wavefront tile are requested first - FM x 8 loads of
+            static_assert(NW * 16 * SP * 4 <= 5 * BM * BK * 2, "staging fits in the operand ring");
+            // The residual / pre-activation values of the whole wavefront tile are requested first - FM x 4 loads of
             // 16 bytes per lane, into registers the main loop no longer needs - so that their latency is paid once,
             // under the staging of the first strip, and not once per strip.
             constexpr bool kReadsAux = EPI == EPI_BIAS_RESID || EPI == EPI_MUL_DGELU;
-            x8<E> aux8[kReadsAux ? FM : 1][kReadsAux ? 8 : 1];
+            x8<E> aux8[kReadsAux ? FM : 1][kReadsAux ? 4 : 1];
             if constexpr (kReadsAux) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
-                    for (int it = 0; it < 8; ++it) {
-                        const int m = m0 + wm * WM + i * 32 + it * 4 + (lane >> 4), n = n0 + wn * WN + 8 * (lane & 15);
+                    for (int it = 0; it < 4; ++it) {
+                        const int m = m0 + wm * WM + i * 16 + it * 4 + lq, n = n0 + wn * WN + 8 * l16;
                         if (m < p.M && n < p.N) aux8[i][it] = *reinterpret_cast<const x8<E> *>(p.aux + (size_t)m * p.ldc + n);
                     }
             }
             __syncthreads();                                            // every wavefront has left the main loop
-            float *stage = reinterpret_cast<float *>(smem_raw) + wave * (32 * SP);
+            float *stage = reinterpret_cast<float *>(smem_raw) + wave * (16 * SP);
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                        *reinterpret_cast<f32x4 *>(stage + lrow * SP + j * 32 + 8 * q + 4 * lhalf) = v;
-                    }
+                    *reinterpret_cast<f32x4 *>(stage + l16 * SP + j * 16 + 4 * lq) = acc[i][j];
                 asm volatile("" ::: "memory");                          // LDS operations of one wavefront execute in order
 #pragma unroll
-                for (int it = 0; it < 8; ++it) {
-                    const int row = it * 4 + (lane >> 4), c8 = lane & 15;
-                    const int m = m0 + wm * WM + i * 32 + row, n = n0 + wn * WN + 8 * c8;
+                for (int it = 0; it < 4; ++it) {
+                    const int row = it * 4 + lq, c8 = l16;
+                    const int m = m0 + wm * WM + i * 16 + row, n = n0 + wn * WN + 8 * c8;
                     const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8);
                     const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8 + 4);
                     if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi, aux8[kReadsAux ? i : 0][kReadsAux ? it : 0]);
@@ -829,17 +821,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     }
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-        const int m = m0 + wm * WM + i * 32 + lrow;
+        const int m = m0 + wm * WM + i * 16 + l16;
         if (m >= p.M) continue;
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * lhalf;
-                if (n >= p.N) continue;
-                const float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                epilogue4<EPI, E>(p, m, n, v);
-            }
+            const int n = n0 + wn * WN + j * 16 + 4 * lq;
+            if (n >= p.N) continue;
+            const float v[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+            epilogue4<EPI, E>(p, m, n, v);
         }
     }
 }
