@@ -53,8 +53,11 @@ def run_gemm(args):
     for name, epi, M, N, K in gemm_shapes(w, args.group, args.wgrad_groups or groups):
         if args.only and args.only not in name:
             continue
-        A = torch.randn(M, K, device="cuda", dtype=bf)
-        Bm = (torch.randn(N, K, device="cuda", dtype=torch.float32) * (1.0 if epi == 5 else 0.02)).to(bf)
+        # the stack's transposed weight-gradient operands have a row pitch of K + 64 elements: a power of two as pitch
+        # sends the 256 rows of an operand tile to the same few memory channels (10 % slower at K = 65536)
+        ld = K + 64 if epi == 5 else K
+        A = torch.randn(M, ld, device="cuda", dtype=bf)
+        Bm = (torch.randn(N, ld, device="cuda", dtype=torch.float32) * (1.0 if epi == 5 else 0.02)).to(bf)
         out = torch.empty(M, N, device="cuda", dtype=bf) if epi != 5 else None
         out2 = torch.empty(M, N, device="cuda", dtype=bf) if epi == 3 else None
         outf = torch.zeros(M, N, device="cuda", dtype=torch.float32) if epi == 5 else None
@@ -67,10 +70,10 @@ def run_gemm(args):
 
         def call():
             if epi == 5:      # the weight-gradient GEMM as the stack runs it (k range split when the output is small)
-                B.check(B.lib.lga_op_gemm_splitk(B.LGA_BF16, M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, outf.data_ptr(), N, 0.0,
+                B.check(B.lib.lga_op_gemm_splitk(B.LGA_BF16, M, N, K, A.data_ptr(), ld, Bm.data_ptr(), ld, outf.data_ptr(), N, 0.0,
                                                  ptr(scratch), slices * M * N, None))
             else:
-                B.check(B.lib.lga_op_gemm(B.LGA_BF16, 1, 1, epi, M, N, K, A.data_ptr(), K, Bm.data_ptr(), K, ptr(out),
+                B.check(B.lib.lga_op_gemm(B.LGA_BF16, 1, 1, epi, M, N, K, A.data_ptr(), ld, Bm.data_ptr(), ld, ptr(out),
                                           ptr(out2), ptr(outf), N, bias.data_ptr(), ptr(aux), 0.0, None))
         ms = _time(call, args.iters)
         print(f"{name:<28} M={M:<6} N={N:<6} K={K:<6} {ms:9.3f} ms {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s"
