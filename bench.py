@@ -412,7 +412,7 @@ def main():
         import ctypes as C
         sink = torch.ones(65536, device="cuda")
         tf = C.c_double()
-        B.check(B.lib.lga_op_mfma_rate(800000, 0, sink.data_ptr(), C.byref(tf), None))
+        B.check(B.lib.lga_op_mfma_rate(1600000, 0, sink.data_ptr(), C.byref(tf), None))
         roof["mfma_only_rate_random_operands"] = tf.value
         roof["frac_of_mfma_only_rate"] = roof["achieved"] / tf.value
     roof["traffic"] = measured_traffic(w.name, dom["name"]) if (group == default_group and causal) else None

@@ -30,14 +30,7 @@ __device__ __forceinline__ float to_f32(f16 v) { return static_cast<float>(v); }
 template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return static_cast<f16>(v); }
 
 // ---- the 16 x 16 x 32 and 32 x 32 x 16 matrix instructions for either 16-bit element type, fp32 accumulate ----
-template <class E> __device__ __forceinline__ f32x4 mfma_16x16x32(x8<E> a, x8<E> b, f32x4 c);
-template <> __device__ __forceinline__ f32x4 mfma_16x16x32<bf16>(x8<bf16> a, x8<bf16> b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-template <> __device__ __forceinline__ f32x4 mfma_16x16x32<f16>(x8<f16> a, x8<f16> b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
-// The same instruction accumulating in place, acc += a b, with acc held in accumulation registers: written as
+// v_mfma_f32_16x16x32 accumulating in place, acc += a b, with acc held in accumulation registers: written as
 // assembly because the builtin leaves the choice of destination to the register allocator, which with all 256
 // accumulation registers taken by accumulators gives some products a destination other than their addend and then
 // moves accumulators around in the loop.  What the compiler no longer knows about this instruction, the caller

@@ -1,5 +1,5 @@
 // Calibration: the bf16 MFMA rate the chip sustains on register operands alone - no memory, no LDS, nothing but
-// v_mfma_f32_32x32x16_bf16 back to back on every SIMD.  With constant operands this reaches the nominal peak; with
+// v_mfma_f32_16x16x32_bf16 (the instruction of the GEMM kernel) back to back on every SIMD.  With constant operands this reaches the nominal peak; with
 // random mantissas and signs the chip's power management holds the clock lower, and that rate - not the nominal
 // one - is what a GEMM on real activations can approach.  Used by the benchmark tools only.
 #include "kernels.h"
@@ -28,22 +28,21 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float *sink, int iter
         a[i] = __builtin_bit_cast(bf16x8, va);
         b[i] = __builtin_bit_cast(bf16x8, vb);
     }
-    f32x16 acc[16];
+    f32x4 acc[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    for (int i = 0; i < 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i * 4 + j] = mfma_32x32x16<bf16>(a[i], b[j], acc[i * 4 + j]);
+            for (int j = 0; j < 4; ++j) mfma_16x16x32_acc<bf16>(a[i], b[j], acc[i * 4 + j]);
     }
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");      // see mfma_16x16x32_acc
     float t = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) t += acc[i][r];
+        for (int r = 0; r < 4; ++r) t += acc[i][r];
     sink[blockIdx.x * 256 + threadIdx.x] = t;
 }
 
@@ -74,7 +73,7 @@ extern "C" int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (e != hipSuccess || hipGetLastError() != hipSuccess) return LGA_ERR_HIP;
-    // per workgroup: 4 wavefronts x iters x 16 MFMAs of 32 x 32 x 16 x 2 flop
-    *tflops = (double)cus * 4.0 * iters * 16.0 * 32768.0 / (ms * 1e9);
+    // per workgroup: 4 wavefronts x iters x 16 MFMAs of 16 x 16 x 32 x 2 flop
+    *tflops = (double)cus * 4.0 * iters * 16.0 * 16384.0 / (ms * 1e9);
     return LGA_OK;
 }

@@ -76,8 +76,22 @@ def run_gemm(args):
                 B.check(B.lib.lga_op_gemm(B.LGA_BF16, 1, 1, epi, M, N, K, A.data_ptr(), ld, Bm.data_ptr(), ld, ptr(out),
                                           ptr(out2), ptr(outf), N, bias.data_ptr(), ptr(aux), 0.0, None))
         ms = _time(call, args.iters)
-        print(f"{name:<28} M={M:<6} N={N:<6} K={K:<6} {ms:9.3f} ms {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s"
-              + (f"  ({slices} k slices)" if slices > 1 else ""), flush=True)
+        line = (f"{name:<28} M={M:<6} N={N:<6} K={K:<6} {ms:9.3f} ms {2.0 * M * N * K / ms / 1e9:8.1f} TFLOP/s"
+                + (f"  ({slices} k slices)" if slices > 1 else ""))
+        if args.library:
+            # the plain product of the same operands into a 16-bit matrix (no epilogue; for the weight gradient the
+            # library writes half the output bytes), best of three alternating rounds for both
+            lib_out = torch.empty(M, N, device="cuda", dtype=bf)
+            lib_call = lambda: torch.matmul(A[:, :K], Bm[:, :K].t(), out=lib_out)
+            ours, theirs = [ms], []
+            for _ in range(3):
+                theirs.append(_time(lib_call, args.iters))
+                ours.append(_time(call, args.iters))
+            o, l = min(ours), min(theirs)
+            line = (f"{name:<28} M={M:<6} N={N:<6} K={K:<6} {2.0 * M * N * K / o / 1e9:8.1f} TFLOP/s   vendor library "
+                    f"{2.0 * M * N * K / l / 1e9:8.1f} TFLOP/s   ratio {l / o:.3f}")
+            del lib_out
+        print(line, flush=True)
         del A, Bm, out, out2, outf, aux, scratch
         torch.cuda.empty_cache()
 
@@ -125,7 +139,7 @@ def run_mfma(args):
         for iters in (400000, 4000000):
             tf = C.c_double()
             B.check(B.lib.lga_op_mfma_rate(iters, mode, sink.data_ptr(), C.byref(tf), None))
-            print(f"v_mfma_f32_32x32x16_bf16 only, {what[mode]}, {iters * 16} MFMAs per wavefront: {tf.value:8.1f} TFLOP/s",
+            print(f"v_mfma_f32_16x16x32_bf16 only, {what[mode]}, {iters * 16} MFMAs per wavefront: {tf.value:8.1f} TFLOP/s",
                   flush=True)
 
 
@@ -138,6 +152,9 @@ def main():
     ap.add_argument("--only", default=None)
     ap.add_argument("--iters", type=int, default=8)
     ap.add_argument("--full", action="store_true", help="attention without the causal mask (encoder)")
+    ap.add_argument("--library", action="store_true",
+                    help="gemm: also time torch.matmul (the vendor library) on the same operands, alternating with this "
+                         "library's kernel in the same process - context for the rates, never part of the product path")
     args = ap.parse_args()
     import torch
     assert torch.cuda.is_available(), "opbench needs a GPU"
