@@ -367,6 +367,49 @@ def test_a_capturing_stream_is_refused_before_anything_is_enqueued():
         st.close()
 
 
+def test_per_kernel_timing_of_all_launches_and_of_one_kernel_alone():
+    """The benchmark's roofline figures come from the library's event pairs: bracketing every launch must list every kernel
+    of a step with consistent launch counts and work, bracketing one kernel alone must list that kernel only, with the
+    same launch count and algorithmic work, and neither may change the results of the step."""
+    w = S.Workload("timing_bf16", 2, 256, 2, 1024, 128, 2, 4, "bf16")
+    x, G, params = S.make_inputs(w, seed=21)
+    dt = B.LGA_BF16
+    cfg = B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro, dt, group=2,
+                        retain_grads=1)
+    from gpu_helpers import to_dev, empty_dev, to_host
+    xd, Gd = to_dev(x, dt), to_dev(G, dt)
+    yd, dxd = empty_dev(x.shape, dt), empty_dev(x.shape, dt)
+    st = B.Stack(cfg, np.concatenate(params))
+    try:
+        def step():
+            st.forward_layered(xd.data_ptr(), yd.data_ptr())
+            st.backward_layered(Gd.data_ptr(), dxd.data_ptr(), None)
+        step()
+        torch.cuda.synchronize()
+        plain = to_host(dxd).copy()
+        st.profile_begin()
+        step()
+        everything = {k["name"]: k for k in st.profile_end()}
+        assert np.array_equal(to_host(dxd), plain)
+        gemms = [n for n in everything if n.startswith("gemm")]
+        assert gemms and any(n.startswith("attn_fwd") for n in everything) and any(n.startswith("layernorm_fwd") for n in everything)
+        for k in everything.values():
+            assert k["launches"] >= 1 and k["ms"] > 0 and k["bytes"] > 0
+        one = max(gemms, key=lambda n: everything[n]["ms"])
+        st.profile_begin(one)
+        step()
+        alone = st.profile_end()
+        assert np.array_equal(to_host(dxd), plain)
+        assert [k["name"] for k in alone] == [one]
+        assert alone[0]["launches"] == everything[one]["launches"]
+        assert alone[0]["flops"] == everything[one]["flops"] and alone[0]["bytes"] == everything[one]["bytes"]
+        st.profile_begin("no kernel has this name")
+        step()
+        assert st.profile_end() == []
+    finally:
+        st.close()
+
+
 def test_runs_are_bit_reproducible():
     w = S.Workload("repro_bf16", 1, 128, 2, 512, 160, 1, 2, "bf16")
     x, G, params = S.make_inputs(w, seed=9)
