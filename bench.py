@@ -31,10 +31,6 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
-# micro-batches per kernel launch: the narrow configurations gain from more tokens per launch (their GEMMs have few
-# tiles per round of 256 workgroups and short contractions), the wide ones do not (within 0.5 % for 2 ... 16)
-DEFAULT_GROUP = {0: 4, 1: 8, 2: 8, 3: 4, 4: 4}
-
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -285,7 +281,7 @@ def main():
     dt = {"fp32": B.LGA_FP32, "bf16": B.LGA_BF16, "fp16": B.LGA_FP16}[w.dtype]
     is16 = dt != B.LGA_FP32
     # default group: the benchmark configurations' own, else about 4096 tokens per launch
-    default_group = max(1, 4096 // (w.micro_batch * w.seq_len)) if args.x_family else DEFAULT_GROUP[args.config]
+    default_group = max(1, 4096 // (w.micro_batch * w.seq_len)) if args.x_family else S.BENCH_GROUP[args.config]
     group = args.group or default_group
     causal = args.attention == "causal"
     if args.order == "mbmajor":

@@ -1,7 +1,7 @@
 """GPU checks at the benchmark configurations' full sizes - cfg3, which bench.py times (4 layers, d = 12288,
 96 heads, d_ff = 49152, seq 2048, 32 micro-batches), once more in IEEE half, and the two smaller bf16 configurations
-cfg1 and cfg2 - in the launch configuration bench.py uses (layered order, group 4, single gradient buffer,
-fused Adam, device-filled weights).
+cfg1 and cfg2 - in the launch configuration bench.py uses (layered order, the benchmark's `group` of the configuration,
+single gradient buffer, fused Adam, device-filled weights).
 
 The fp64 oracle cannot run this size, so it checks sampled outputs it can compute one by one:
 attention is causal, hence the first P positions of a sequence at the first layer boundary depend
@@ -76,14 +76,14 @@ def test_full_size_sampled_prefix_parity_and_regrouping(config, dtype):
     gate = 2.5e-3 if dtype == "fp16" else 2e-2
     free, _ = torch.cuda.mem_get_info()
     need = B.arena_bytes(B.make_config(w.n_layers, w.d_model, w.n_heads, w.d_ff, w.seq_len, w.micro_batch, w.n_micro,
-                                       B.LGA_BF16, group=4)) + 6 * w.tokens * w.d_model * 2 + 4e9
+                                       B.LGA_BF16, group=S.BENCH_GROUP[config])) + 6 * w.tokens * w.d_model * 2 + 4e9
     if free < need:
         pytest.skip(f"needs about {need / 1e9:.0f} GB of free HBM")
     shape = (w.n_micro, w.micro_batch, w.seq_len, w.d_model)
     gen = torch.Generator(device="cuda").manual_seed(0)
     x = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)
     dy = torch.randn(shape, device="cuda", dtype=torch.float32, generator=gen).to(tdt)
-    a = _run(w, 4, x, dy, True)
+    a = _run(w, S.BENCH_GROUP[config], x, dy, True)
     # --- sampled outputs against the oracle
     p0 = O.unflatten_layer(a["params0"], w.d_model, w.d_ff)
     a["params0"] = None
@@ -99,7 +99,7 @@ def test_full_size_sampled_prefix_parity_and_regrouping(config, dtype):
     assert np.linalg.norm(a["g_bqkv"][d:2 * d]) < 5e-2 * np.linalg.norm(a["g_bqkv"][:d])
     # --- same step with another grouping (same kernels per token, different fp32 summation order) and with the
     # boundary activations offloaded to the host (1.6 GB per boundary, read back from there)
-    b = _run(w, 2, x, dy, False, offload=1)
+    b = _run(w, S.BENCH_GROUP[config] // 2, x, dy, False, offload=1)
     assert np.array_equal(a["y_head"], b["y_head"])
     for mu in a["samples"]:
         assert np.array_equal(a["samples"][mu], b["samples"][mu])
@@ -159,7 +159,7 @@ def test_full_size_weight_gradients_and_adam_against_the_oracle(config, capfd):
     w = S.Workload(base.name + "_one_layer", 1, base.d_model, base.n_heads, base.d_ff, base.seq_len, base.micro_batch,
                    base.n_micro, base.dtype)
     d, f, s, n = w.d_model, w.d_ff, w.seq_len, w.n_micro
-    cfg = B.make_config(1, d, w.n_heads, f, s, w.micro_batch, n, B.LGA_BF16, group=4, retain_grads=0)
+    cfg = B.make_config(1, d, w.n_heads, f, s, w.micro_batch, n, B.LGA_BF16, group=S.BENCH_GROUP[config], retain_grads=0)
     free, _ = torch.cuda.mem_get_info()
     need = B.arena_bytes(cfg) + 5 * w.tokens * d * 2 + 4e9
     if free < need:
@@ -249,7 +249,7 @@ def test_full_size_weight_gradients_and_adam_against_the_oracle(config, capfd):
 @pytest.mark.timeout(900)
 def test_cfg1_at_full_size_against_the_oracle(capfd):
     """GPT-2-small shape, all 12 layers, 8 micro-batches of 4 sequences of 1024 positions: the whole step of the
-    benchmark's launch configuration (layered order, group 4, fused per-layer Adam) against the oracle's plain
+    benchmark's launch configuration (layered order, all 8 micro-batches per launch, fused per-layer Adam) against the oracle's plain
     micro-batch-major step - every boundary, every gradient tensor, the updated weights and moments."""
     from gpu_helpers import run_gpu_step, oracle_shape, adam_struct, oracle_adam, compare_with_oracle
     w = S.CONFIGS[1]
@@ -258,7 +258,7 @@ def test_cfg1_at_full_size_against_the_oracle(capfd):
     _progress(capfd, f"{w.name}: oracle step over {w.tokens} tokens x {w.n_layers} layers")
     ref = O.step_microbatch_major(x, G, params, oracle_shape(w), oracle_adam(adam))
     _progress(capfd, "oracle done, GPU step")
-    got = run_gpu_step(w, x, G, params, group=4, retain=1, adam=adam)
+    got = run_gpu_step(w, x, G, params, group=S.BENCH_GROUP[1], retain=1, adam=adam)
     worst = compare_with_oracle(w, got, ref, 2e-2, adam)
     top = sorted(worst.items(), key=lambda kv: -kv[1])[:5]
     _progress(capfd, "worst relative errors: " + ", ".join(f"{k} {v:.2e}" for k, v in top))
