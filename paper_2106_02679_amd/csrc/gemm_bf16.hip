@@ -474,12 +474,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int til
 // and one vmcnt wait + barrier per tile publishes it.
 //
 // The matrix instruction is v_mfma_f32_16x16x32 (a wavefront's 128 x 128 tile = 8 x 8 blocks of 16 x 16, four
-// accumulator registers each), not the 32x32x16 one: same flops per cycle, same LDS and register operand bytes per k
-// tile, but a quarter of the accumulator registers read and written per instruction and per flop (a 16 x 16 block
-// stays in the pipe for 32 k instead of a 32 x 32 block for 16).  The chip is power-limited on this kernel, and at
-// the board's limit the clock it grants is what that difference in power per cycle buys: measured on the merged
-// weight-gradient shapes of d = 12288 at sustained load, 1.50 GHz with the 32x32x16 loop against 1.77 GHz with this
-// instruction at the same 1.35 kW.
+// accumulator registers each), not the 32x32x16 one: same flops per cycle and the same LDS operand bytes per k tile,
+// twice the 16-bit operand registers read per flop, but a quarter of the fp32 accumulator registers read and written
+// per instruction, half per flop (a 16 x 16 block stays in the pipe for 32 k, a 32 x 32 block for 16) - 0.5 instead of
+// 0.625 register bytes per multiply-add.  The chip is power-limited on this kernel, and at the board's limit the
+// clock it grants is what that difference in power per cycle buys: measured on a merged weight-gradient shape of
+// d = 12288 at sustained load and the same 1.35 kW, the 32x32x16 form of this loop ran at 1.50 GHz (1.37 PFLOP/s) and
+// this one runs at 1.65 GHz (1.56 PFLOP/s), both with the matrix pipe busy in 0.9 of the cycles.
 __device__ __forceinline__ int swz16(int row) { return (row >> 1) & 7; }      // 16 rows of one chunk column -> 8 chunk places x 2 row parities
 
 template <int BM, int BN, int WGM, int WGN, int EPI, class E>
