@@ -35,7 +35,9 @@ template <> __device__ __forceinline__ f16 from_f32<f16>(float v) { return stati
 // accumulation registers taken by accumulators gives some products a destination other than their addend and then
 // moves accumulators around in the loop.  What the compiler no longer knows about this instruction, the caller
 // guarantees: an accumulator is not read by anything but this instruction until at least 32 wait states after its
-// last update, and its operands a, b are registers whose loads the compiler still tracks (s_waitcnt).
+// last update, and its operands a, b are registers whose loads the compiler still tracks (s_waitcnt).  Two of these
+// in a row on one accumulator need one wait state between them (without it the sums come out wrong): the compiler's
+// hazard pass puts an s_nop there when they are two asm statements, as here - it does not look inside one.
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 template <class E> __device__ __forceinline__ void mfma_16x16x32_acc(x8<E> a, x8<E> b, f32x4 &acc);
 template <> __device__ __forceinline__ void mfma_16x16x32_acc<bf16>(x8<bf16> a, x8<bf16> b, f32x4 &acc) {

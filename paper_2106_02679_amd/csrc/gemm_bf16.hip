@@ -480,7 +480,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmParams<E> p, int til
 // 0.625 register bytes per multiply-add.  The chip is power-limited on this kernel, and at the board's limit the
 // clock it grants is what that difference in power per cycle buys: measured on a merged weight-gradient shape of
 // d = 12288 at sustained load and the same 1.35 kW, the 32x32x16 form of this loop ran at 1.50 GHz (1.37 PFLOP/s) and
-// this one runs at 1.65 GHz (1.56 PFLOP/s), both with the matrix pipe busy in 0.9 of the cycles.
+// this one runs at 1.65 GHz (1.56 PFLOP/s), both with the matrix pipe busy in 0.9 of the cycles.  For the same reason
+// the two products that a block receives per k tile are issued back to back (see `half` in the kernel): the second finds
+// the accumulator still in the pipe.
 __device__ __forceinline__ int swz16(int row) { return (row >> 1) & 7; }      // 16 rows of one chunk column -> 8 chunk places x 2 row parities
 
 template <int BM, int BN, int WGM, int WGN, int EPI, class E>
@@ -602,9 +604,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         if (krem < BK) off |= ((((lane & 7) ^ swz16(dma_row(i))) * 8 < krem) ? 0 : kBufPoison);
         lds_dma(r, q, i, off, 0);
     };
-    // MFMA operands of the two k steps (32 k each) of a tile, one register buffer each: while one step is multiplied
-    // from its buffer, the other buffer takes the next step's operands, so every LDS read is a whole step (64 MFMAs,
-    // about 1000 cycles) ahead of its use, which rides out the LDS latency spikes that the incoming DMA traffic causes.
+    // MFMA operands of a whole k tile: block f of k step s (32 k each) of A and of B, 128 registers.  A tile is
+    // multiplied in two halves of FM/2 A blocks against all FN B blocks, and the two products of a block - k step 0,
+    // k step 1 - are issued one right after the other (see `half` below), so both steps' operands of the blocks in
+    // work are in registers at once.  The registers are refilled as they fall free: the A blocks of the second half
+    // while the first is multiplied, the next tile's first A half while the second is, and the next tile's B
+    // blocks column by column behind the second half's walk over them.  Every LDS read is thus at least 18 block
+    // pairs (some 580 cycles) ahead of its use, which rides out the LDS latency spikes that the incoming DMA
+    // traffic causes.
     x8<E> af[2][FM], bf[2][FN];
     // LDS byte address of an operand chunk.  A lane reads row (block row 0 + l16), logical chunk 4 s + lq of k step
     // s; the swizzle term of that row is l16 >> 1 whatever the block (blocks start at multiples of 16 rows), so the
@@ -613,8 +620,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     const int lane_sw = lq ^ (l16 >> 1);
     const int lane_a = ((wm * WM + l16) * BK + lane_sw * 8) * 2;
     const int lane_b = ((wn * WN + l16) * BK + lane_sw * 8) * 2;
-    // operand f of step s (f < FN: B block f, else A block f - FN) of the tile whose A operand is in slot qa.  B first:
-    // a step starts with A block 0 against every B block.
+    // operand f of step s (f < FN: B block f, else A block f - FN) of the tile whose A operand is in slot qa
     auto load_frag = [&](int s, int qa, int f) {
         if (f < FN) {
             const int vb = (lane_b ^ (s << 6)) + wrap(qa + 1) * (kSlotElems * 2);
@@ -624,11 +630,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
             af[s][g] = *reinterpret_cast<const x8<E> *>(smem_raw + va + g * 16 * BK * 2);
         }
     };
-    auto load_frags = [&](int s, int qa) {
-#pragma unroll
-        for (int f = 0; f < FM + FN; ++f) load_frag(s, qa, f);
-    };
-    // The same two operations for the unrolled main loop, where the ring slot is a compile-time constant.  A wavefront
+    // The same operation for the unrolled main loop, where the ring slot is a compile-time constant.  A wavefront
     // issues strictly in order and, being alone on its SIMD, has nobody to fill the matrix pipe while it issues
     // anything else: measured (32x32x16 form of this loop), 126 other instructions per k tile made a k tile take 2400
     // cycles where its MFMAs need 2048, 64 of them about 2230.  So the loop keeps nothing but the loads themselves:
@@ -670,7 +672,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
     static_assert(NIA < 16, "vmcnt immediate below uses the low four bits only");
     constexpr int kWaitVmA = 0x0070 | NIA;
 
-    // prologue: tile 0 published, tile 1 in flight, operands of step 0 in registers
+    // prologue: tile 0 published, tile 1 in flight, tile 0's B blocks and first A half in registers
 #pragma unroll
     for (int i = 0; i < NIA; ++i) dma_one(true, 0, 0, p.K, i);
 #pragma unroll
@@ -683,51 +685,72 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
 #pragma unroll
         for (int i = 0; i < NIB; ++i) dma_one(false, 3, 1, p.K - BK, i);
     }
-    load_frags(0, 0);
+#pragma unroll
+    for (int f = 0; f < FN + FM / 2; ++f) {
+        load_frag(0, 0, f);
+        load_frag(1, 0, f);
+    }
 
-    // One k step = FM rows of FN MFMAs (one A block against all B blocks).  Each row also issues its share of the
-    // step's other work, never two memory instructions in a row: one direct-to-LDS load of operand tile `dkt` after its
-    // first MFMA, and two of the step's 16 LDS operand reads (for step `rs` of the tile in slot `rqa`) further on.
+    // Half h of a k tile: A blocks g = 4 h .. 4 h + 3 against all B blocks, column by column (j outer, g inner), and
+    // for each block its two products in a row on the same accumulator.  Measured on register operands, a second
+    // MFMA on the accumulator of the one just issued costs no cycles and less power than one on another accumulator
+    // - the board then grants the clock for it: at the same power, random operands, 2.43 PFLOP/s with strictly
+    // adjacent pairs against 2.21 with 64 different accumulators in turn - and in this kernel, on the merged
+    // weight-gradient shape of d = 12288 at sustained load, this order gave 1.53 PFLOP/s where the order "all blocks
+    // of k step 0, then all of k step 1" gave 1.47 on the same box.
+    // Each half also issues its share of the tile's other work, between the pairs and never more than two memory
+    // instructions at one place: its 8 direct-to-LDS loads of operand tile `dkt`, one after the first pair of every
+    // column; with rd_a, the 8 LDS reads of A blocks ga0 .. ga0 + 3 (both steps) of the tile in slot rqa, after the
+    // second and third pair of the first four columns; with rd_b, the two reads of B block j of that tile after the
+    // last pair of column j, which was the last use of those registers.
     // The order is pinned (sched_barrier): left to itself the compiler clumps the loads, and a wavefront that issues
     // several in a row right after the barrier, together with the three others, finds the load queue full and
     // stalls with its MFMAs behind it.
-    static_assert(NIA == FM && NIB == FM && FM + FN == 2 * FM && FN >= 6, "one load and two reads per row of MFMAs");
+    static_assert(NIA == 8 && NIB == 8 && FM == 8 && FN == 8, "one load per column of a half, four A blocks per half");
     // lean_c: the unrolled main loop's forms of the loads (constant slots; dkt is then the k tile's byte offset)
-    auto k_step = [&](auto lean_c, int s, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, bool do_read, int rs,
-                      int rqa) __attribute__((always_inline)) {
+    auto half = [&](auto lean_c, int h, bool do_dma, bool dma_is_a, int dq, int dkt, int dkrem, bool rd_a, int ga0, bool rd_b,
+                    int rqa) __attribute__((always_inline)) {
         constexpr bool LEAN = decltype(lean_c)::value;
 #pragma unroll
-        for (int g = 0; g < FM; ++g) {
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                mfma_16x16x32_acc<E>(bf[s][j], af[s][g], acc[g][j]);
-                if (j == 0 && do_dma) {
-                    if constexpr (LEAN) dma_c(dma_is_a, dq, dkt, g);
-                    else dma_one(dma_is_a, dq, dkt, dkrem, g);
-                }
-                if ((j == 2 || j == 5) && do_read) {
-                    const int f = 2 * g + (j == 5 ? 1 : 0);
-                    if constexpr (LEAN) load_frag_c(rs, rqa, f);
-                    else load_frag(rs, rqa, f);
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        for (int pr = 0; pr < 4 * FN; ++pr) {
+            const int j = pr >> 2, g = 4 * h + (pr & 3);
+            mfma_16x16x32_acc<E>(bf[0][j], af[0][g], acc[g][j]);
+            mfma_16x16x32_acc<E>(bf[1][j], af[1][g], acc[g][j]);
+            if ((pr & 3) == 0 && do_dma) {
+                if constexpr (LEAN) dma_c(dma_is_a, dq, dkt, j);
+                else dma_one(dma_is_a, dq, dkt, dkrem, j);
             }
+            if (rd_a && j < 4 && ((pr & 3) == 1 || (pr & 3) == 2)) {
+                const int ia = 2 * j + (pr & 3) - 1;                    // 0 .. 7: block ga0 + ia / 2, step ia % 2
+                if constexpr (LEAN) load_frag_c(ia & 1, rqa, FN + ga0 + (ia >> 1));
+                else load_frag(ia & 1, rqa, FN + ga0 + (ia >> 1));
+            }
+            if (rd_b && (pr & 3) == 3) {
+                if constexpr (LEAN) {
+                    load_frag_c(0, rqa, j);
+                    load_frag_c(1, rqa, j);
+                } else {
+                    load_frag(0, rqa, j);
+                    load_frag(1, rqa, j);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // One k tile whose A operand is in ring slot qa.  STRAIGHT: tiles kt+1 and kt+2 exist and are full, so
-    // nothing is tested.  Both steps issue the same mix, so the load queue never sees a burst:
-    //   step 0: MFMAs | LDS reads of step 1's operands | A(kt+2)'s loads, into the free slot
+    // One k tile whose A operand is in ring slot qa; its B blocks and first A half are in registers.  STRAIGHT:
+    // tiles kt+1 and kt+2 exist and are full, so nothing is tested.
+    //   half 0: MFMAs | LDS reads of this tile's second A half | A(kt+2)'s loads, into the free slot
     //   wait for all loads but A(kt+2)'s + barrier: tile kt+1 is published, and nobody reads tile kt's slots
     //   any more
-    //   step 1: MFMAs | LDS reads of tile kt+1's step 0 | B(kt+2)'s loads, into A(kt)'s slot
+    //   half 1: MFMAs | LDS reads of tile kt+1's first A half and B blocks | B(kt+2)'s loads, into A(kt)'s slot
     auto k_tile = [&](int kt, int qa, auto straight_c) __attribute__((always_inline)) {
         constexpr bool STRAIGHT = decltype(straight_c)::value;
         const bool more1 = STRAIGHT || kt + 1 < nk, more2 = STRAIGHT || kt + 2 < nk;
         const int krem2 = STRAIGHT ? BK : p.K - (kt + 2) * BK;
         const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);      // A(kt+1), A(kt+2); B(kt+2) goes to qa
 
-        k_step(std::false_type{}, 0, more2, true, qa2, kt + 2, krem2, true, 1, qa);
+        half(std::false_type{}, 0, more2, true, qa2, kt + 2, krem2, true, FM / 2, false, qa);
         // A bare s_barrier: __syncthreads() would add a fence that waits for every load, A(kt+2)'s included.
         // The LDS reads above must have returned before other wavefronts may overwrite those slots.
         if (more2)
@@ -738,19 +761,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        k_step(std::false_type{}, 1, more2, false, qa, kt + 2, krem2, more1, 0, qa1);
+        half(std::false_type{}, 1, more2, false, qa, kt + 2, krem2, more1, 0, more1, qa1);
     };
     // The same k tile for the unrolled main loop: ring slot qa is a constant, tiles kt+1 and kt+2 exist and are full;
     // koff2 is the byte offset of k tile kt+2 within a row.
     auto k_tile_c = [&](int qa, int koff2) __attribute__((always_inline)) {
         const int qa1 = wrap(qa + 2), qa2 = wrap(qa + 4);
-        k_step(std::true_type{}, 0, true, true, qa2, koff2, BK, true, 1, qa);
+        half(std::true_type{}, 0, true, true, qa2, koff2, BK, true, FM / 2, false, qa);
         __builtin_amdgcn_s_waitcnt(kWaitVmA);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
-        k_step(std::true_type{}, 1, true, false, qa, koff2, BK, true, 0, qa1);
+        half(std::true_type{}, 1, true, false, qa, koff2, BK, true, 0, true, qa1);
     };
     int kt = 0, qa = 0;
     // Main loop, unrolled over one period of the ring (five k tiles; the slot of A(kt) is 0, 2, 4, 1, 3, 0, ...).

@@ -263,3 +263,41 @@ def test_init_without_a_gpu_reports_a_hip_error_instead_of_crashing():
     assert B.lib.lga_init_stack(C.byref(cfg()), None, C.byref(h)) == B.LGA_ERR_HIP
     # the first HIP call of lga_init_stack (raising the large kernels' dynamic LDS limit) is the one that fails
     assert "dynamic LDS limit" in B.last_error() or "hipMalloc" in B.last_error()
+
+
+def test_generated_gemm_code_keeps_a_wait_state_between_two_mfmas_on_one_accumulator(tmp_path):
+    """The direct-to-LDS GEMM issues a block's two products of a k tile back to back on the same accumulator through
+    assembly statements the compiler does not model as matrix instructions; the hardware needs one wait state between
+    the two.  The compiler's hazard pass supplies it: this test reads the device assembly it generates and fails if a
+    toolchain ever stops doing so.  (Also: every accumulator update in the kernel is in place.)"""
+    import shutil
+    import subprocess
+    from paper_2106_02679_amd import build as bld
+    hipcc = bld._hipcc()
+    if shutil.which(hipcc) is None and not os.path.exists(hipcc):
+        pytest.skip("no hipcc")
+    asm = tmp_path / "gemm_bf16.s"
+    flags = [f for f in bld.FLAGS if f not in ("-fPIC", "-Wall", "-Wno-unused-function")]
+    res = subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", os.path.join(bld.CSRC, "gemm_bf16.hip"), "-o", str(asm)],
+                         capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    pat = re.compile(r"v_mfma_f32_16x16x32_\w+ (a\[\d+:\d+\]), v\[\d+:\d+\], v\[\d+:\d+\], (a\[\d+:\d+\])")
+    n = pairs = 0
+    last_dst, between = None, 0
+    for line in asm.read_text().splitlines():
+        t = line.strip()
+        if not t or t.startswith(";") or (t.startswith(".") and not t.endswith(":")):
+            continue
+        m = pat.match(t)
+        if m:
+            n += 1
+            assert m.group(1) == m.group(2), t                   # accumulates in place
+            if m.group(1) == last_dst:
+                pairs += 1
+                assert between >= 1, f"no wait state before: {t}"
+            last_dst, between = m.group(1), 0
+        elif t.endswith(":"):
+            last_dst = None                                       # a label: another path may arrive here
+        else:
+            between += 1
+    assert n >= 12 * 128 and pairs >= n // 4, (n, pairs)         # 12 kernel instances, at least the unrolled loop of each
