@@ -403,12 +403,12 @@ def main():
                 "peak": peak, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     if roof["bound"] == "mfma":
-        # calibration, measured live: what the chip sustains with nothing but MFMAs on register operands with random
-        # mantissas and signs (its power management holds the clock below nominal on such data)
+        # calibration, measured live: what the chip sustains with nothing but MFMAs (in the GEMM loop's issue order) on
+        # register operands with random mantissas and signs (its power management holds the clock below nominal on such data)
         import ctypes as C
         sink = torch.ones(65536, device="cuda")
         tf = C.c_double()
-        B.check(B.lib.lga_op_mfma_rate(1600000, 0, sink.data_ptr(), C.byref(tf), None))
+        B.check(B.lib.lga_op_mfma_rate(800000, 0, sink.data_ptr(), C.byref(tf), None))
         roof["mfma_only_rate_random_operands"] = tf.value
         roof["frac_of_mfma_only_rate"] = roof["achieved"] / tf.value
     roof["traffic"] = measured_traffic(w.name, dom["name"]) if (group == default_group and causal) else None

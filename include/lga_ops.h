@@ -140,10 +140,10 @@ int lga_op_adam(float *w, float *m, float *v, const float *g, void *w16, int32_t
                 const lga_adam *adam, int32_t *nonfinite, void *stream);
 
 /* Calibration for the benchmark tools: the bf16 MFMA rate (TFLOP/s, executed) that the GPU sustains on register
- * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 16 v_mfma_f32_16x16x32_bf16 (the GEMM kernel's instruction) back to
- * back, no memory traffic.  mode 0: operand values in [0.5, 1) with random mantissas and signs (what the power
+ * operands alone - one workgroup of four wavefronts per CU, each issuing iters x 32 v_mfma_f32_16x16x32_bf16 (the GEMM
+ * kernel's instruction, in that kernel's order: two products in a row on each of 16 accumulators), no memory traffic.  mode 0: operand values in [0.5, 1) with random mantissas and signs (what the power
  * management allows on realistic data); 1: all operand values 1.0 (approaches the nominal peak).
- * sink: device, >= 65536 floats, overwritten.  iters in 1 .. 2^24.  Synchronous: returns after the kernel has run.
+ * sink: device, >= 65536 floats, overwritten.  iters in 1 .. 2^23.  Synchronous: returns after the kernel has run.
  * tflops: host. */
 int lga_op_mfma_rate(int32_t iters, int32_t mode, float *sink, double *tflops, void *stream);
 

@@ -265,20 +265,22 @@ def test_init_without_a_gpu_reports_a_hip_error_instead_of_crashing():
     assert "dynamic LDS limit" in B.last_error() or "hipMalloc" in B.last_error()
 
 
-def test_generated_gemm_code_keeps_a_wait_state_between_two_mfmas_on_one_accumulator(tmp_path):
-    """The direct-to-LDS GEMM issues a block's two products of a k tile back to back on the same accumulator through
-    assembly statements the compiler does not model as matrix instructions; the hardware needs one wait state between
-    the two.  The compiler's hazard pass supplies it: this test reads the device assembly it generates and fails if a
-    toolchain ever stops doing so.  (Also: every accumulator update in the kernel is in place.)"""
+@pytest.mark.parametrize("source,min_mfmas", [("gemm_bf16.hip", 12 * 128), ("mfma_rate.hip", 64)])
+def test_generated_code_keeps_a_wait_state_between_two_mfmas_on_one_accumulator(tmp_path, source, min_mfmas):
+    """The direct-to-LDS GEMM (and the MFMA-only calibration, which copies its issue order) issues a block's two
+    products of a k tile back to back on the same accumulator through assembly statements the compiler does not model
+    as matrix instructions; the hardware needs one wait state between the two.  The compiler's hazard pass supplies it:
+    this test reads the device assembly it generates and fails if a toolchain ever stops doing so.  (Also: every
+    accumulator update of that instruction is in place.)"""
     import shutil
     import subprocess
     from paper_2106_02679_amd import build as bld
     hipcc = bld._hipcc()
     if shutil.which(hipcc) is None and not os.path.exists(hipcc):
         pytest.skip("no hipcc")
-    asm = tmp_path / "gemm_bf16.s"
+    asm = tmp_path / "device.s"
     flags = [f for f in bld.FLAGS if f not in ("-fPIC", "-Wall", "-Wno-unused-function")]
-    res = subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", os.path.join(bld.CSRC, "gemm_bf16.hip"), "-o", str(asm)],
+    res = subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", os.path.join(bld.CSRC, source), "-o", str(asm)],
                          capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
     pat = re.compile(r"v_mfma_f32_16x16x32_\w+ (a\[\d+:\d+\]), v\[\d+:\d+\], v\[\d+:\d+\], (a\[\d+:\d+\])")
@@ -300,4 +302,4 @@ def test_generated_gemm_code_keeps_a_wait_state_between_two_mfmas_on_one_accumul
             last_dst = None                                       # a label: another path may arrive here
         else:
             between += 1
-    assert n >= 12 * 128 and pairs >= n // 4, (n, pairs)         # 12 kernel instances, at least the unrolled loop of each
+    assert n >= min_mfmas and pairs >= n // 4, (n, pairs)        # at least the unrolled loop of every kernel instance
