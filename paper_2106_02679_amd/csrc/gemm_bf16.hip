@@ -192,15 +192,15 @@ __device__ __forceinline__ void epilogue4(const GemmParams<E> &p, int m, int n, 
 
 // The same for 8 consecutive n of one row, with 16-byte accesses (bf16 outputs only): n, ldc multiples of 8 and
 // 16-byte aligned tensors.
-// aux8: the 8 values of aux at (m, n .. n + 7) for the two epilogues that read it, loaded by the caller (ahead of time).
+// aux8: the 8 values of aux at (m, n .. n + 7) for the two epilogues that read it, and b0, b1: the bias of columns
+// n .. n + 7 for the three that add it, both loaded by the caller (ahead of time).
 template <int EPI, class E>
 __device__ __forceinline__ void epilogue8(const GemmParams<E> &p, int m, int n, const f32x4 &lo, const f32x4 &hi,
-                                          const x8<E> &aux8) {
+                                          const x8<E> &aux8, const f32x4 &b0, const f32x4 &b1) {
     static_assert(EPI != EPI_ACCUM_F32, "16-bit outputs only");
     const size_t idx = (size_t)m * p.ldc + n;
     float r[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
-        const f32x4 b0 = *reinterpret_cast<const f32x4 *>(p.bias + n), b1 = *reinterpret_cast<const f32x4 *>(p.bias + n + 4);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             r[i] += b0[i];
@@ -822,6 +822,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
                         if (m < p.M && n < p.N) aux8[i][it] = *reinterpret_cast<const x8<E> *>(p.aux + (size_t)m * p.ldc + n);
                     }
             }
+            // A lane stores the same 8 columns of every row: their bias values are read once, not once per store (read
+            // inside the loop below, each waits out its whole latency between the staging of two strips: 3 us per tile).
+            f32x4 bias_lo = {0.f, 0.f, 0.f, 0.f}, bias_hi = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
+                const int n = n0 + wn * WN + 8 * l16;
+                if (n < p.N) {
+                    bias_lo = *reinterpret_cast<const f32x4 *>(p.bias + n);
+                    bias_hi = *reinterpret_cast<const f32x4 *>(p.bias + n + 4);
+                }
+            }
             __syncthreads();                                            // every wavefront has left the main loop
             float *stage = reinterpret_cast<float *>(smem_raw) + wave * (16 * SP);
 #pragma unroll
@@ -836,7 +846,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
                     const int m = m0 + wm * WM + i * 16 + row, n = n0 + wn * WN + 8 * c8;
                     const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8);
                     const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8 + 4);
-                    if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi, aux8[kReadsAux ? i : 0][kReadsAux ? it : 0]);
+                    if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi, aux8[kReadsAux ? i : 0][kReadsAux ? it : 0], bias_lo, bias_hi);
                 }
                 asm volatile("" ::: "memory");
             }
