@@ -87,6 +87,25 @@ GEMM_CASES = [
 
 @pytest.mark.parametrize("case", with_half(GEMM_CASES), ids=lambda c: "-".join(map(str, c)))
 def test_gemm_against_oracle_matmul(case):
+    check_gemm(case)
+
+
+# The large-tile kernel's k loop: a ring of five operand slots, a main loop unrolled over five k tiles that needs
+# seven tiles ahead of it, a generic form for what is left, a tested form for the last two tiles and a prologue that
+# has tile 1 in flight only if it exists.  Every k tile count from 1 to 13 (all residues of the ring, with and without
+# the unrolled loop taking part), some with a ragged last tile, on the two workgroup orders.
+K_SWEEP = [(BF16, 1, 1, (B.LGA_EPI_STORE, B.LGA_EPI_ACCUM_F32)[n % 2], 2048, 4096, 64 * n) for n in range(1, 14)] + \
+          [(BF16, 1, 1, B.LGA_EPI_BIAS, 2048, 4096, K) for K in (328, 392, 456, 712, 776)] + \
+          [(BF16, 1, 1, B.LGA_EPI_STORE, 4096, 4096, K) for K in (320, 448, 584)] + \
+          [(F16, 1, 1, B.LGA_EPI_ACCUM_F32, 2048, 4096, K) for K in (384, 520)]
+
+
+@pytest.mark.parametrize("case", K_SWEEP, ids=lambda c: "-".join(map(str, c)))
+def test_large_tile_gemm_with_every_number_of_k_tiles(case):
+    check_gemm(case)
+
+
+def check_gemm(case):
     dt, akm, bkm, epi, M, N, K = case
     rng = np.random.default_rng(hash(case) % (2 ** 32))
     pad = 8      # leading dimensions larger than the logical width: exercises pitches
