@@ -303,3 +303,11 @@ def test_generated_code_keeps_a_wait_state_between_two_mfmas_on_one_accumulator(
         else:
             between += 1
     assert n >= min_mfmas and pairs >= n // 4, (n, pairs)        # at least the unrolled loop of every kernel instance
+
+
+def test_mfma_calibration_refuses_bad_arguments_before_touching_the_gpu():
+    tf = C.c_double()
+    sink = (C.c_float * 4)()
+    for iters, mode, s, t in ((0, 0, sink, C.byref(tf)), ((1 << 23) + 1, 0, sink, C.byref(tf)), (10, 2, sink, C.byref(tf)),
+                              (10, 0, None, C.byref(tf)), (10, 0, sink, None)):
+        assert B.lib.lga_op_mfma_rate(iters, mode, s, t, None) == B.LGA_ERR_ARG
