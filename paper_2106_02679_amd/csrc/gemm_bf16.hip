@@ -834,21 +834,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dma_kernel(GemmParam
             }
             __syncthreads();                                            // every wavefront has left the main loop
             float *stage = reinterpret_cast<float *>(smem_raw) + wave * (16 * SP);
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
+            auto stage_strip = [&](int i) {
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
                     *reinterpret_cast<f32x4 *>(stage + l16 * SP + j * 16 + 4 * lq) = acc[i][j];
-                asm volatile("" ::: "memory");                          // LDS operations of one wavefront execute in order
+            };
+            // LDS operations of one wavefront execute in order, so strip i + 1 may be written into the same piece of
+            // LDS as soon as the reads of strip i have been ISSUED: its writes then travel under the wait for those
+            // reads.  All eight reads of a strip are issued before any of them is used (left inside the bounds test
+            // of its row, each pair waited out the LDS latency on its own: 32 times per tile, 3 us of a tile's 5.5).
+            stage_strip(0);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                asm volatile("" ::: "memory");
+                f32x4 lo[4], hi[4];
 #pragma unroll
                 for (int it = 0; it < 4; ++it) {
-                    const int row = it * 4 + lq, c8 = l16;
-                    const int m = m0 + wm * WM + i * 16 + row, n = n0 + wn * WN + 8 * c8;
-                    const f32x4 lo = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8);
-                    const f32x4 hi = *reinterpret_cast<const f32x4 *>(stage + row * SP + 8 * c8 + 4);
-                    if (m < p.M && n < p.N) epilogue8<EPI, E>(p, m, n, lo, hi, aux8[kReadsAux ? i : 0][kReadsAux ? it : 0], bias_lo, bias_hi);
+                    lo[it] = *reinterpret_cast<const f32x4 *>(stage + (it * 4 + lq) * SP + 8 * l16);
+                    hi[it] = *reinterpret_cast<const f32x4 *>(stage + (it * 4 + lq) * SP + 8 * l16 + 4);
                 }
                 asm volatile("" ::: "memory");
+                if (i + 1 < FM) stage_strip(i + 1);
+                asm volatile("" : "+v"(lo[0]), "+v"(hi[0]), "+v"(lo[1]), "+v"(hi[1]), "+v"(lo[2]), "+v"(hi[2]), "+v"(lo[3]), "+v"(hi[3]));
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int m = m0 + wm * WM + i * 16 + it * 4 + lq, n = n0 + wn * WN + 8 * l16;
+                    if (m < p.M && n < p.N)
+                        epilogue8<EPI, E>(p, m, n, lo[it], hi[it], aux8[kReadsAux ? i : 0][kReadsAux ? it : 0], bias_lo, bias_hi);
+                }
             }
             return;
         }
