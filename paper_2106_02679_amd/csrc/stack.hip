@@ -122,7 +122,7 @@ int validate_config(const lga_config *c) {
     // bounds every leading dimension: the widths, and the token count of one group (the weight-gradient GEMMs
     // contract over at least one group's tokens, stored with that pitch plus 64)
     if (c->dtype != LGA_FP32) {
-        const long widest = std::max<long>(3L * c->d_model, c->d_ff);
+        const long widest = std::max<long>(3L * c->d_model, c->d_ff + 64L);      // (d_ff-wide rows may be stored with a pitch of d_ff + 64)
         const long t_group = (long)c->group * c->micro_batch * c->seq_len;
         if (widest > kGemmMaxLd || t_group + 64 > kGemmMaxLd)
             return fail(LGA_ERR_SHAPE, "the 16-bit modes need 3 d_model, d_ff and group * micro_batch * seq_len + 64 to "
@@ -144,6 +144,7 @@ struct Plan {
     size_t xT[4], dyT[4];      // transposed operands of the four weight-gradient GEMMs (16-bit modes)
     int wgrad_groups;          // groups whose tokens one weight-gradient GEMM contracts over
     size_t ldk;                // row pitch (elements) of the transposed operands
+    size_t ldf;                // row pitch (elements) of the d_ff-wide activations u, gl, du
     size_t h, qkv, a, x1, h2, u, gl, du, dh2, dx1, da, dqkv, dh;
     size_t mean1, rstd1, mean2, rstd2, lse, delta, partial;
     size_t splitk, splitk_floats;   // partial results of weight-gradient GEMMs whose k range is split (narrow layers)
@@ -176,9 +177,14 @@ Plan make_plan(const lga_config &c) {
     p.a = take(t * d * esz);
     p.x1 = take(t * d * esz);
     p.h2 = take(t * d * esz);
-    p.u = take(t * f * esz);
-    p.gl = take(t * f * esz);
-    p.du = take(t * f * esz);
+    // Rows of d_ff elements whose byte length is a multiple of 32 KB (d_ff = 49152: 96 KB) get a pitch 64 elements
+    // longer: with the bare pitch the 256 rows of a GEMM operand tile start in few memory channels, and the two GEMMs
+    // that contract over d_ff lose 7 % (1.50 against 1.61 PFLOP/s; 1 % of the step).  Measured without effect on rows
+    // of 16 KB (d_ff = 8192), 6 KB and 200 KB, and on the d_model- and 3 d_model-wide rows of all configurations.
+    p.ldf = (is16 && (f * esz) % 32768 == 0) ? f + 64 : f;
+    p.u = take(t * p.ldf * esz);
+    p.gl = take(t * p.ldf * esz);
+    p.du = take(t * p.ldf * esz);
     p.dh2 = take(t * d * esz);
     p.dx1 = take(t * d * esz);
     p.da = take(t * d * esz);
@@ -442,8 +448,9 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
     constexpr bool k16bit = !std::is_same<T, float>::value;
     const T *pwt = pw;
     if constexpr (k16bit) pwt = st->w16t<T>(l);
-    auto fwd_gemm = [&](GemmParams<T> g, size_t w_off, int in, int out, Epilogue e) {
-        g.M = t; g.N = out; g.K = in; g.lda = in; g.ldc = out;
+    const int ldf = (int)st->plan.ldf;                       // pitch of u and gl
+    auto fwd_gemm = [&](GemmParams<T> g, size_t w_off, int in, int out, Epilogue e, int lda = 0, int ldc = 0) {
+        g.M = t; g.N = out; g.K = in; g.lda = lda ? lda : in; g.ldc = ldc ? ldc : out;
         g.B = pwt + w_off;
         g.ldb = k16bit ? in : out;
         gemm<T>(g, true, k16bit, e, s);
@@ -465,11 +472,11 @@ template <class T> void layer_forward(lga_stack *st, int l, const T *x_in, T *y_
                             st->at<float>(st->plan.rstd2), t, d, c.ln_eps, s);
     g = GemmParams<T>{};
     g.A = h2; g.out = gl; g.out2 = u; g.bias = pf + o.b_1;
-    fwd_gemm(g, o.w_1, d, f, EPI_BIAS_GELU);
+    fwd_gemm(g, o.w_1, d, f, EPI_BIAS_GELU, 0, ldf);
     if (y_out) {
         g = GemmParams<T>{};
         g.A = gl; g.out = y_out; g.bias = pf + o.b_2; g.aux = x1;
-        fwd_gemm(g, o.w_2, f, d, EPI_BIAS_RESID);
+        fwd_gemm(g, o.w_2, f, d, EPI_BIAS_RESID, ldf, 0);
     }
 }
 
@@ -512,20 +519,24 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
     // gW[in, out] (+)= X[t, in]^T dY[t, out], contracted over tokens.  The 16-bit modes first write X^T [in][.]
     // and dY^T [out][.] (two HBM-bound passes, ~1 % of the GEMM's time) so that the GEMM reads both
     // operands k-contiguous; `which` names the matrix's pair of transposed buffers.
-    auto wgrad = [&](int which, const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off) {
+    const int ldf = (int)st->plan.ldf;                       // pitch of u, gl and du
+    // ldx, ldy: row pitches of X and dY where they differ from the widths
+    auto wgrad = [&](int which, const T *X, int in, const T *dY, int out, size_t w_off, size_t b_off, int ldx = 0, int ldy = 0) {
+        if (!ldx) ldx = in;
+        if (!ldy) ldy = out;
         GemmParams<T> g{};
         g.M = in; g.N = out;
         g.outf = gbuf + w_off; g.ldc = out;
         if constexpr (std::is_same<T, float>::value) {
             g.K = t; g.beta = beta;
-            g.A = X; g.lda = in; g.B = dY; g.ldb = out;
+            g.A = X; g.lda = ldx; g.B = dY; g.ldb = ldy;
             gemm<T>(g, false, false, EPI_ACCUM_F32, s);
         } else {
             const int ldk = (int)st->plan.ldk;
             T *xT = st->at<T>(st->plan.xT[which]), *dyT = st->at<T>(st->plan.dyT[which]);
-            launch_transpose16(X, xT + (size_t)gs.slot * t, t, in, in, ldk, s);
+            launch_transpose16(X, xT + (size_t)gs.slot * t, t, in, ldx, ldk, s);
             // the bias gradient is the column sum of dY: taken from the tiles as they are transposed
-            launch_transpose16_colsum<T>(dY, dyT + (size_t)gs.slot * t, t, out, out, ldk, beta, gbuf + b_off, partial, s);
+            launch_transpose16_colsum<T>(dY, dyT + (size_t)gs.slot * t, t, out, ldy, ldk, beta, gbuf + b_off, partial, s);
             if (gs.flush) {
                 g.K = (gs.slot + 1) * t; g.beta = gs.beta_mat;
                 g.A = xT; g.lda = ldk; g.B = dyT; g.ldb = ldk;
@@ -534,21 +545,22 @@ template <class T> void layer_backward(lga_stack *st, int l, const T *x_in, T *d
             }
         }
         if constexpr (std::is_same<T, float>::value)
-            launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, out, beta, gbuf + b_off, nullptr, partial, s);
+            launch_colsum<T>(dY, nullptr, nullptr, nullptr, t, out, ldy, beta, gbuf + b_off, nullptr, partial, s);
     };
-    auto dgrad = [&](const T *dY, int out, size_t w_off, int in, T *dX, Epilogue e, const T *aux) {
+    // lda: row pitch of dY, ldc: of dX and aux, where they differ from the widths
+    auto dgrad = [&](const T *dY, int out, size_t w_off, int in, T *dX, Epilogue e, const T *aux, int lda = 0, int ldc = 0) {
         GemmParams<T> g{};
-        g.A = dY; g.lda = out; g.B = pw + w_off; g.ldb = out; g.M = t; g.N = in; g.K = out;
-        g.out = dX; g.ldc = in; g.aux = aux;
+        g.A = dY; g.lda = lda ? lda : out; g.B = pw + w_off; g.ldb = out; g.M = t; g.N = in; g.K = out;
+        g.out = dX; g.ldc = ldc ? ldc : in; g.aux = aux;
         gemm<T>(g, true, true, e, s);
     };
 
     // y = x1 + gelu(u) W2 + b2
-    wgrad(0, gl, f, dy, d, o.w_2, o.b_2);
-    dgrad(dy, d, o.w_2, f, du, EPI_MUL_DGELU, u);            // du = (dy W2^T) * gelu'(u)
+    wgrad(0, gl, f, dy, d, o.w_2, o.b_2, ldf, 0);
+    dgrad(dy, d, o.w_2, f, du, EPI_MUL_DGELU, u, 0, ldf);    // du = (dy W2^T) * gelu'(u)
     // u = h2 W1 + b1
-    wgrad(1, h2, d, du, f, o.w_1, o.b_1);
-    dgrad(du, f, o.w_1, d, dh2, EPI_STORE, nullptr);
+    wgrad(1, h2, d, du, f, o.w_1, o.b_1, 0, ldf);
+    dgrad(du, f, o.w_1, d, dh2, EPI_STORE, nullptr, ldf, 0);
     // h2 = LN2(x1); dx1 = dy + LN2'(dh2)
     launch_layernorm_bwd_dx<T>(dh2, x1, mean2, rstd2, pf + o.ln2_g, dy, dx1, t, d, s, beta, gbuf + o.ln2_b, gbuf + o.ln2_g, partial);
     // x1 = x + a Wo + bo

@@ -467,6 +467,10 @@ SLICES = [
     # cfg4's head size (160) and d_ff = 4 d at one eighth of its width: the full width needs > 250 GB of
     # host memory for the fp64 oracle
     ("cfg4_narrow", S.Workload("cfg4_narrow_slice", 1, 3200, 20, 12800, 256, 1, 2, "bf16"), 2),
+    # d_ff-wide rows of a multiple of 32 KB are stored with a pitch of d_ff + 64 (like cfg3's): a narrow model with
+    # such rows, two layers, in both 16-bit types
+    ("padded_ff_pitch", S.Workload("padded_ff_bf16", 2, 256, 4, 16384, 64, 1, 4, "bf16"), 2),
+    ("padded_ff_pitch_fp16", S.Workload("padded_ff_fp16", 2, 256, 4, 16384, 64, 1, 4, "fp16"), 2),
 ]
 
 
